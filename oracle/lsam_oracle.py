@@ -1,0 +1,276 @@
+"""Plain CPU oracle of the K-replica LSAM step.  TEST INFRASTRUCTURE ONLY.
+
+This file is the correctness reference the HIP path is compared against.  It is
+imported only by the tests, the smoke check and the benchmark's CPU-baseline
+leg; the product path never calls it and shares no code with it.
+
+Everything is float64 numpy, one replica after another, no blocking, fusion or
+reordering beyond what the paper's formulas state.  `numpy.matmul` is the only
+library primitive used as a step (the dense layers).
+
+What follows the paper, by passage:
+  * loss f(x; xi): empirical mean over the minibatch (Introduction, problem
+    statement).
+  * first-order SAM point  x~ = x + rho * grad f(x) / (||grad f(x)|| + gamma)
+    (Formulation, definition of f_SAM; Appendix, look-back map T_{rho,gamma}).
+  * SAM gradient g_t = grad f(x~; xi_t), same minibatch in both passes, no
+    Jacobian of the map (Theorem "Convergence of G_t with Constant
+    Perturbation", definition of g_t).
+  * local update  x <- x - eta (g_t + lambda (x - y))  (Algorithm 1, x-update),
+    driven through a Nesterov-momentum sampler (Section "Distributed Training").
+  * center direction g' = (1/(n tau)) sum_i sum_s x_s^(i) - y, look-ahead
+    g = g' + beta (g' - g'_prev), y <- Optimizer(y, g, eta'), counters reset
+    (Algorithm 2, synchronous optimization step; Section "Acceleration
+    Techniques for Optimization").
+  * lambda = lambda0 / (eta tau) (Appendix "Hyperparameter Search").
+
+Readings where the paper is silent (each also listed in the design notes):
+  gamma default 1e-12; y <- y + eta' g (ascent on the log-density score, which
+  makes beta = 0, eta' = 1 give the plain mean of the samples and agrees with
+  Algorithm 1's y-update); no look-ahead term at the first sync; Nesterov form
+  v <- mu v + G, x <- x - eta (G + mu v); per-replica trigger c_i >= tau_i with
+  the mean taken over the due replicas' samples (equals Algorithm 2 when all
+  periods are equal); the iterate sum S_i collects post-update iterates;
+  ReLU'(0) = 0; reported loss is the first-pass loss.
+
+Parity status: the paper prints no iterate, loss value or worked example, so
+agreement with the authors' own implementation is "parity unpinned".  Every
+function here is pinned instead by finite differences, closed forms, reduction
+to Algorithm 1 / Algorithm 2 special cases, brute-force bookkeeping and an
+autograd/`torch.optim.SGD` witness in tests/test_oracle_pins.py.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+SCHED_FIXED = 0
+SCHED_REDRAW = 1
+
+_LCG_A = 6364136223846793005
+_LCG_C = 1442695040888963407
+_MASK64 = (1 << 64) - 1
+
+
+class PeriodSchedule:
+    """Seeded per-replica communication periods (integer only).
+
+    State s_0 = seed; s_{j+1} = (A s_j + C) mod 2^64; draw_j = (s_{j+1} >> 33)
+    mod (tau_max - tau_min + 1) + tau_min.  The first K draws give tau_0..tau_{K-1};
+    in redraw mode every replica that syncs takes the next draw, lower index first.
+    """
+
+    def __init__(self, K, tau=None, tau_min=1, tau_max=1, seed=0, mode=SCHED_FIXED):
+        self.K = int(K)
+        self.tau_min, self.tau_max = int(tau_min), int(tau_max)
+        self.mode = int(mode)
+        self.state = int(seed) & _MASK64
+        if tau is not None:
+            self.tau = [int(t) for t in tau]
+            self.explicit = True
+        else:
+            self.explicit = False
+            self.tau = [self.draw() for _ in range(self.K)]
+        if len(self.tau) != self.K or min(self.tau) < 1:
+            raise ValueError("need K periods >= 1")
+        self.count = [0] * self.K   # c_i: local iterations since replica i last synced
+        self.t_y = 0                # number of center updates so far
+
+    def draw(self):
+        self.state = (_LCG_A * self.state + _LCG_C) & _MASK64
+        return (self.state >> 33) % (self.tau_max - self.tau_min + 1) + self.tau_min
+
+    def tick(self):
+        for i in range(self.K):
+            self.count[i] += 1
+
+    def due(self):
+        return [i for i in range(self.K) if self.count[i] >= self.tau[i]]
+
+    def served(self, due):
+        for i in due:
+            self.count[i] = 0
+            if self.mode == SCHED_REDRAW and not self.explicit:
+                self.tau[i] = self.draw()
+        self.t_y += 1
+
+
+def bf16_round(a):
+    """Round-to-nearest-even to bfloat16, taken from the float32 value (the precision
+    the rounded tensors have on the device), returned as float64."""
+    f = np.ascontiguousarray(a, dtype=np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).astype(np.float64).reshape(np.shape(a))
+
+
+def _identity(a):
+    return np.asarray(a, dtype=np.float64)
+
+
+class Mlp:
+    """Dense ReLU classifier on a flat parameter vector: per layer W_l [out,in]
+    row-major then b_l [out]; Z_l = A_{l-1} W_l^T + b_l, A_l = ReLU(Z_l) for l < L,
+    logits = Z_L; loss = mean_b [logsumexp(logits_b) - logits_b[label_b]]."""
+
+    def __init__(self, dims, gemm_dtype=0):
+        self.dims = tuple(int(v) for v in dims)
+        self.L = len(self.dims) - 1
+        self.q = bf16_round if gemm_dtype == 1 else _identity
+        self.offsets = []
+        off = 0
+        for l in range(self.L):
+            fi, fo = self.dims[l], self.dims[l + 1]
+            self.offsets.append((off, off + fo * fi, off + fo * fi + fo))
+            off += fo * fi + fo
+        self.d = off
+
+    def unpack(self, x):
+        out = []
+        for l, (o0, o1, o2) in enumerate(self.offsets):
+            out.append((x[o0:o1].reshape(self.dims[l + 1], self.dims[l]), x[o1:o2]))
+        return out
+
+    def loss_and_grad(self, x, X, labels):
+        """Returns (loss, grad [d]).  With bf16 operands, exactly the tensors fed to the
+        matrix units are rounded: W, the input X, hidden activations and every dZ (the
+        bias gradient sums the same rounded dZ); all accumulation, the softmax and the
+        results stay in float64."""
+        q = self.q
+        layers = self.unpack(np.asarray(x, dtype=np.float64))
+        B = X.shape[0]
+        acts = [q(X)]
+        for l, (W, b) in enumerate(layers):
+            Z = acts[l] @ q(W).T + b
+            acts.append(q(np.maximum(Z, 0.0)) if l < self.L - 1 else Z)
+        logits = acts[-1]
+        zmax = logits.max(axis=1, keepdims=True)
+        e = np.exp(logits - zmax)
+        se = e.sum(axis=1, keepdims=True)
+        lse = np.log(se) + zmax
+        rows = np.arange(B)
+        loss = float(np.mean(lse[:, 0] - logits[rows, labels]))
+        dZ = e / se
+        dZ[rows, labels] -= 1.0
+        dZ /= B
+        grad = np.zeros(self.d)
+        for l in range(self.L - 1, -1, -1):
+            W, _ = layers[l]
+            o0, o1, o2 = self.offsets[l]
+            dZq = q(dZ)
+            grad[o0:o1] = (dZq.T @ acts[l]).ravel()
+            grad[o1:o2] = dZq.sum(axis=0)
+            if l > 0:
+                dA = dZq @ q(W)
+                dZ = dA * (acts[l] > 0.0)
+        return loss, grad
+
+
+class LsamOracle:
+    """K replicas x_i, velocities v_i, iterate sums S_i, one center y."""
+
+    def __init__(self, K, init_params, dims=(), d_raw=0, batch=0, gemm_dtype=0,
+                 rho=0.05, gamma=1e-12, lr=0.1, lr_center=1.0, momentum=0.9, beta=0.9,
+                 lambda0=0.5, lambda_abs=-1.0, nesterov=1, tau=None, tau_min=1, tau_max=1,
+                 sched_seed=0, sched_mode=SCHED_FIXED):
+        self.K = int(K)
+        self.model = Mlp(dims, gemm_dtype) if len(dims) else None
+        self.d = self.model.d if self.model else int(d_raw)
+        self.batch = int(batch)
+        self.rho, self.gamma = float(rho), float(gamma)
+        self.lr, self.lr_center = float(lr), float(lr_center)
+        self.mu, self.beta = float(momentum), float(beta)
+        self.lambda0, self.lambda_abs = float(lambda0), float(lambda_abs)
+        self.nesterov = bool(nesterov)
+        self.sched = PeriodSchedule(K, tau, tau_min, tau_max, sched_seed, sched_mode)
+        p = np.asarray(init_params, dtype=np.float64).ravel()
+        if p.size == self.d:
+            self.x = np.tile(p, (self.K, 1))
+            self.y = p.copy()
+        elif p.size == (self.K + 1) * self.d:
+            self.x = p[: self.K * self.d].reshape(self.K, self.d).copy()
+            self.y = p[self.K * self.d:].copy()
+        else:
+            raise ValueError("init_params must hold d or (K+1)*d values")
+        self.v = np.zeros((self.K, self.d))
+        self.S = np.zeros((self.K, self.d))
+        self.gprev = None
+        # kept for inspection by tests
+        self.last_norm = np.zeros(self.K)
+        self.last_perturbed = np.zeros((self.K, self.d))
+        self.last_g1 = np.zeros((self.K, self.d))
+        self.last_g2 = np.zeros((self.K, self.d))
+
+    # -- hyper-parameters -------------------------------------------------------------
+    def set_scalars(self, lr, rho):
+        self.lr, self.rho = float(lr), float(rho)
+
+    def coupling(self, i):
+        """lambda_i = lambda0 / (eta tau_i) unless a fixed lambda is given."""
+        if self.lambda_abs >= 0.0:
+            return self.lambda_abs
+        return self.lambda0 / (self.lr * self.sched.tau[i])
+
+    # -- the sampler step --------------------------------------------------------------
+    def _ascend(self, i, g1):
+        n = float(np.sqrt(np.sum(g1 * g1)))
+        self.last_norm[i] = n
+        xt = self.x[i] + self.rho * g1 / (n + self.gamma)
+        self.last_perturbed[i] = xt
+        return xt
+
+    def _descend(self, i, g2):
+        G = g2 + self.coupling(i) * (self.x[i] - self.y)
+        self.v[i] = self.mu * self.v[i] + G
+        if self.nesterov:
+            self.x[i] = self.x[i] - self.lr * (G + self.mu * self.v[i])
+        else:
+            self.x[i] = self.x[i] - self.lr * self.v[i]
+        self.S[i] += self.x[i]
+
+    def step(self, X, labels):
+        """One local iteration of every replica on its own minibatch; returns the K
+        first-pass losses."""
+        losses = np.zeros(self.K)
+        for i in range(self.K):
+            Xi = np.asarray(X[i], dtype=np.float64)
+            li = np.asarray(labels[i]).astype(np.int64)
+            losses[i], g1 = self.model.loss_and_grad(self.x[i], Xi, li)
+            xt = self._ascend(i, g1)
+            _, g2 = self.model.loss_and_grad(xt, Xi, li)
+            self.last_g1[i], self.last_g2[i] = g1, g2
+            self._descend(i, g2)
+        self.sched.tick()
+        return losses
+
+    def step_grads(self, g1, g2):
+        """Raw-vector mode: the two gradients are handed in instead of computed."""
+        for i in range(self.K):
+            a = np.asarray(g1[i], dtype=np.float64)
+            self._ascend(i, a)
+            self._descend(i, np.asarray(g2[i], dtype=np.float64))
+        self.sched.tick()
+
+    # -- the center step ---------------------------------------------------------------
+    def sync(self):
+        due = self.sched.due()
+        if not due:
+            return 0
+        m = sum(self.sched.count[i] for i in due)
+        total = np.zeros(self.d)
+        for i in due:
+            total += self.S[i]
+        gp = total / m - self.y
+        g = gp if self.gprev is None else gp + self.beta * (gp - self.gprev)
+        self.y = self.y + self.lr_center * g
+        self.gprev = gp
+        for i in due:
+            self.S[i] = 0.0
+        self.sched.served(due)
+        return len(due)
+
+    # -- read-out ----------------------------------------------------------------------
+    def get_params(self, replica):
+        return (self.y if replica < 0 else self.x[replica]).copy()
+
+    def get_schedule(self):
+        return list(self.sched.tau), list(self.sched.count), self.sched.t_y

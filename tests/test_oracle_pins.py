@@ -1,0 +1,339 @@
+"""Pins for the CPU oracle: each test checks it against something fixed by the paper or by
+mathematics (finite differences, closed forms, reductions to Algorithm 1 / Algorithm 2,
+brute-force bookkeeping, an autograd / torch.optim witness), never against itself.
+CPU only."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle.lsam_oracle import (LsamOracle, Mlp, PeriodSchedule, SCHED_FIXED, SCHED_REDRAW,
+                                bf16_round)
+
+TINY = workloads.Workload("tiny", K=2, dims=(5, 4, 3), batch=3, rho=0.05, tau=(2, 2),
+                          n_classes=3, data_seed=11)
+
+
+def _tiny_data(w, step=0):
+    return workloads.batch(w, step)
+
+
+# ---- P1: backward pass vs central finite differences ------------------------------------
+@pytest.mark.parametrize("dims,B", [((5, 4, 3), 3), ((6, 5, 4, 3), 4), ((7, 3), 2)])
+def test_gradient_matches_finite_differences(dims, B):
+    rng = np.random.default_rng(5)
+    m = Mlp(dims)
+    x = rng.standard_normal(m.d) * 0.5
+    X = rng.standard_normal((B, dims[0]))
+    lab = rng.integers(0, dims[-1], B)
+    _, g = m.loss_and_grad(x, X, lab)
+    h = 1e-6
+    fd = np.zeros(m.d)
+    for j in range(m.d):
+        e = np.zeros(m.d)
+        e[j] = h
+        fd[j] = (m.loss_and_grad(x + e, X, lab)[0] - m.loss_and_grad(x - e, X, lab)[0]) / (2 * h)
+    assert np.max(np.abs(fd - g)) / np.max(np.abs(g)) < 1e-6
+
+
+def test_loss_is_mean_cross_entropy_closed_form():
+    # zero weights => uniform softmax => loss = log(C) exactly; dZ rows sum to zero
+    m = Mlp((4, 3, 5))
+    X = np.random.default_rng(0).standard_normal((6, 4))
+    lab = np.arange(6) % 5
+    loss, g = m.loss_and_grad(np.zeros(m.d), X, lab)
+    assert abs(loss - np.log(5.0)) < 1e-14
+    o0, o1, o2 = m.offsets[-1]
+    # bias gradient of the last layer = mean(softmax - onehot) = 1/C - freq(label)
+    freq = np.bincount(lab, minlength=5) / 6.0
+    assert np.allclose(g[o1:o2], 1.0 / 5 - freq, atol=1e-15)
+
+
+def test_gradient_matches_torch_autograd():
+    # independent witness: torch autograd on the same network in float64
+    w = TINY.scaled(dims=(9, 8, 7, 4), batch=5, n_classes=4)
+    m = Mlp(w.dims)
+    x = workloads.init_params(w).astype(np.float64)
+    X, lab = _tiny_data(w)
+    loss, g = m.loss_and_grad(x, X[0].astype(np.float64), lab[0])
+    xt = torch.tensor(x, requires_grad=True)
+    a = torch.tensor(X[0], dtype=torch.float64)
+    off = 0
+    for l in range(len(w.dims) - 1):
+        fi, fo = w.dims[l], w.dims[l + 1]
+        W = xt[off:off + fo * fi].view(fo, fi)
+        b = xt[off + fo * fi: off + fo * fi + fo]
+        off += fo * fi + fo
+        a = torch.nn.functional.linear(a, W, b)
+        if l < len(w.dims) - 2:
+            a = torch.relu(a)
+    tl = torch.nn.functional.cross_entropy(a, torch.tensor(lab[0], dtype=torch.long))
+    tl.backward()
+    assert abs(loss - tl.item()) < 1e-12
+    assert np.allclose(g, xt.grad.numpy(), rtol=1e-10, atol=1e-14)
+
+
+# ---- P2: the look-back map's shift has norm rho n / (n + gamma), along g1 ---------------
+@pytest.mark.parametrize("gamma", [1e-12, 0.3])
+def test_perturbation_norm_and_direction(gamma):
+    w = TINY
+    x0 = workloads.init_params(w)
+    o = LsamOracle(w.K, x0, dims=w.dims, batch=w.batch, rho=0.07, gamma=gamma, tau=w.tau)
+    X, lab = _tiny_data(w)
+    o.step(X, lab)
+    for i in range(w.K):
+        delta = o.last_perturbed[i] - x0
+        n = np.linalg.norm(o.last_g1[i])
+        assert abs(o.last_norm[i] - n) < 1e-15
+        assert abs(np.linalg.norm(delta) - 0.07 * n / (n + gamma)) < 1e-12
+        assert np.linalg.norm(delta) <= 0.07 + 1e-15
+        cos = delta @ o.last_g1[i] / (np.linalg.norm(delta) * n)
+        assert abs(cos - 1.0) < 1e-12
+
+
+def test_raw_mode_perturbation_uses_whole_vector_norm():
+    # a 3-4-12 gradient has norm 13: the shift must be rho * g / 13 exactly (gamma = 0)
+    g1 = np.array([[3.0, 4.0, 12.0]])
+    o = LsamOracle(1, np.zeros(3), d_raw=3, rho=0.26, gamma=0.0, tau=(5,))
+    o.step_grads(g1, np.zeros((1, 3)))
+    assert np.allclose(o.last_perturbed[0], [0.06, 0.08, 0.24], atol=1e-16)
+
+
+# ---- P3: rho = 0, lambda = 0 is textbook (Nesterov) momentum SGD ------------------------
+@pytest.mark.parametrize("nesterov", [1, 0])
+def test_rho_zero_reduces_to_torch_sgd(nesterov):
+    w = TINY.scaled(dims=(6, 5, 3), batch=4)
+    x0 = workloads.init_params(w)
+    o = LsamOracle(1, x0, dims=w.dims, batch=w.batch, rho=0.0, gamma=1e-12, lr=0.1,
+                   momentum=0.9, lambda_abs=0.0, nesterov=nesterov, tau=(1000,))
+    p = torch.tensor(x0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.SGD([p], lr=0.1, momentum=0.9, nesterov=bool(nesterov))
+    for t in range(6):
+        X, lab = _tiny_data(w.scaled(K=1), t)
+        o.step(X, lab)
+        opt.zero_grad()
+        a = torch.tensor(X[0], dtype=torch.float64)
+        W1 = p[:30].view(5, 6); b1 = p[30:35]; W2 = p[35:50].view(3, 5); b2 = p[50:53]
+        z = torch.relu(a @ W1.T + b1) @ W2.T + b2
+        torch.nn.functional.cross_entropy(z, torch.tensor(lab[0], dtype=torch.long)).backward()
+        opt.step()
+        assert np.allclose(o.get_params(0), p.detach().numpy(), rtol=1e-12, atol=1e-15)
+
+
+# ---- P4: K = 1, no coupling, no momentum is plain SAM -----------------------------------
+def test_single_replica_without_coupling_is_plain_sam():
+    w = TINY.scaled(K=1, dims=(6, 5, 3), batch=4)
+    x0 = workloads.init_params(w)
+    rho, lr = 0.05, 0.1
+    o = LsamOracle(1, x0, dims=w.dims, batch=w.batch, rho=rho, gamma=0.0, lr=lr,
+                   momentum=0.0, lambda_abs=0.0, tau=(1000,))
+
+    def loss_fn(p, X, lab):
+        a = torch.tensor(X, dtype=torch.float64)
+        W1 = p[:30].view(5, 6); b1 = p[30:35]; W2 = p[35:50].view(3, 5); b2 = p[50:53]
+        z = torch.relu(a @ W1.T + b1) @ W2.T + b2
+        return torch.nn.functional.cross_entropy(z, torch.tensor(lab, dtype=torch.long))
+
+    p = torch.tensor(x0, dtype=torch.float64)
+    for t in range(4):
+        X, lab = _tiny_data(w, t)
+        o.step(X, lab)
+        q = p.clone().requires_grad_(True)
+        g1, = torch.autograd.grad(loss_fn(q, X[0], lab[0]), q)
+        q2 = (p + rho * g1 / g1.norm()).requires_grad_(True)
+        g2, = torch.autograd.grad(loss_fn(q2, X[0], lab[0]), q2)
+        p = p - lr * g2
+        assert np.allclose(o.get_params(0), p.numpy(), rtol=1e-11, atol=1e-15)
+
+
+# ---- P5: K = 1, tau = 1, beta = 0, eta' = alpha, mu = 0 is Algorithm 1 -------------------
+def test_reduces_to_algorithm_one_anchor_gap_identity():
+    # proof of the anchor-gap lemma: z_{t+1} = (1 - alpha) [(1 - lambda eta) z_t - eta g_t]
+    rng = np.random.default_rng(3)
+    d, lam, eta, alpha = 7, 0.8, 0.05, 0.3
+    x0 = rng.standard_normal(d)
+    y0 = rng.standard_normal(d)
+    o = LsamOracle(1, np.concatenate([x0, y0]), d_raw=d, rho=0.1, lr=eta, lr_center=alpha,
+                   momentum=0.0, beta=0.0, lambda_abs=lam, tau=(1,))
+    z = x0 - y0
+    x, y = x0.copy(), y0.copy()
+    for t in range(10):
+        g = rng.standard_normal((1, d))
+        o.step_grads(rng.standard_normal((1, d)), g)
+        assert o.sync() == 1
+        # Algorithm 1 written out
+        x = x - eta * (g[0] + lam * (x - y))
+        y = alpha * x + (1 - alpha) * y
+        z = (1 - alpha) * ((1 - lam * eta) * z - eta * g[0])
+        assert np.allclose(o.get_params(0), x, atol=1e-14)
+        assert np.allclose(o.get_params(-1), y, atol=1e-14)
+        assert np.allclose(o.get_params(0) - o.get_params(-1), z, atol=1e-14)
+
+
+# ---- P6: beta = 0, eta' = 1, equal periods: y = plain mean of the n*tau samples ----------
+def test_center_is_mean_of_recorded_iterates():
+    rng = np.random.default_rng(8)
+    K, d, tau = 3, 5, 4
+    o = LsamOracle(K, rng.standard_normal(d), d_raw=d, rho=0.1, lr=0.05, lr_center=1.0,
+                   momentum=0.9, beta=0.0, lambda0=0.5, tau=(tau,) * K)
+    for rnd in range(3):
+        seen = []
+        for t in range(tau):
+            assert o.sync() == 0
+            o.step_grads(rng.standard_normal((K, d)), rng.standard_normal((K, d)))
+            seen.extend(o.get_params(i) for i in range(K))
+        assert len(seen) == K * tau
+        assert o.sync() == K
+        assert np.allclose(o.get_params(-1), np.mean(seen, axis=0), atol=1e-14)
+        assert o.get_schedule()[1] == [0] * K
+
+
+def test_lookahead_term_uses_previous_center_direction():
+    # two syncs with tau = 1, K = 1, fixed samples: y2 = y1 + g'_1 + beta (g'_1 - g'_0)
+    d, beta = 3, 0.9
+    o = LsamOracle(1, np.concatenate([np.ones(d), np.zeros(d)]), d_raw=d, rho=0.0, lr=0.0,
+                   lr_center=0.5, momentum=0.0, beta=beta, lambda_abs=0.0, tau=(1,))
+    z = np.zeros((1, d))
+    o.step_grads(z, z); o.sync()          # x stays 1 (lr = 0): g'_0 = 1 - 0 = 1, y1 = .5
+    assert np.allclose(o.get_params(-1), 0.5)
+    o.step_grads(z, z); o.sync()          # g'_1 = .5 ; g = .5 + .9 (.5 - 1) = .05 ; y2 = .525
+    assert np.allclose(o.get_params(-1), 0.525, atol=1e-15)
+
+
+# ---- P7: zero gradient, no momentum: the gap shrinks by (1 - lambda0/tau) per step ------
+def test_pull_fraction_is_lambda0_over_tau():
+    rng = np.random.default_rng(2)
+    d, tau, lam0 = 6, 8, 0.5
+    x0 = rng.standard_normal(d)
+    y0 = rng.standard_normal(d)
+    o = LsamOracle(1, np.concatenate([x0, y0]), d_raw=d, rho=0.1, lr=0.2, momentum=0.0,
+                   lambda0=lam0, tau=(tau,))
+    zero = np.zeros((1, d))
+    for t in range(1, tau):
+        o.step_grads(rng.standard_normal((1, d)), zero)
+        assert np.allclose(o.get_params(0) - y0, (1 - lam0 / tau) ** t * (x0 - y0), atol=1e-14)
+
+
+def test_heavy_ball_closed_form():
+    # constant gradient c, no coupling: v_t = c (1-mu^t)/(1-mu); x_t = x_0 - eta sum_s v_s
+    d, mu, eta = 4, 0.5, 0.1
+    c = np.arange(1.0, d + 1)[None]
+    o = LsamOracle(1, np.zeros(d), d_raw=d, rho=0.1, lr=eta, momentum=mu, lambda_abs=0.0,
+                   nesterov=0, tau=(100,))
+    acc = np.zeros(d)
+    for t in range(1, 6):
+        o.step_grads(c, c)
+        acc += c[0] * (1 - mu ** t) / (1 - mu)
+        assert np.allclose(o.get_params(0), -eta * acc, atol=1e-15)
+
+
+# ---- P8: the schedule --------------------------------------------------------------------
+def test_due_sets_hand_computed():
+    # K = 3, periods (2,3,4), one sync attempt after every tick, 12 ticks
+    s = PeriodSchedule(3, tau=(2, 3, 4))
+    expected = {2: [0], 3: [1], 4: [0, 2], 6: [0, 1], 8: [0, 2], 9: [1], 10: [0], 12: [0, 1, 2]}
+    for tick in range(1, 13):
+        s.tick()
+        due = s.due()
+        assert due == expected.get(tick, []), tick
+        if due:
+            s.served(due)
+    assert s.t_y == len(expected)
+
+
+def test_uniform_period_syncs_every_tau_ticks_with_n_tau_samples():
+    K, tau = 4, 16
+    o = LsamOracle(K, np.zeros(2), d_raw=2, tau=(tau,) * K)
+    z = np.zeros((K, 2))
+    for tick in range(1, 3 * tau + 1):
+        o.step_grads(z, z)
+        total = sum(o.get_schedule()[1])
+        n = o.sync()
+        assert (n == K) == (tick % tau == 0)
+        if n:
+            assert total == K * tau      # Algorithm 2's trigger: n*tau iterations in total
+    assert o.get_schedule()[2] == 3
+
+
+def test_period_generator_first_draw_and_range():
+    # seed 0: s_1 = A*0 + C = C, so draw_0 = (C >> 33) mod range + tau_min
+    # C = 0x14057B7EF767814F (the published MMIX increment); its top 31 bits are
+    # 0x14057B7E >> 1 = 167951807
+    s = PeriodSchedule(1, tau_min=2, tau_max=8, seed=0)
+    assert s.state == 0x14057B7EF767814F
+    assert s.tau == [167951807 % 7 + 2]
+    s = PeriodSchedule(4096, tau_min=4, tau_max=16, seed=123)
+    assert min(s.tau) == 4 and max(s.tau) == 16
+    counts = np.bincount(s.tau, minlength=17)[4:]
+    assert counts.min() > 4096 / 13 * 0.7       # roughly uniform
+    # full-period property of a mixed congruential generator modulo 2^16
+    g = PeriodSchedule(1, tau_min=1, tau_max=1, seed=99)
+    seen = set()
+    for _ in range(65536):
+        g.draw()
+        seen.add(g.state & 0xFFFF)
+    assert len(seen) == 65536
+
+
+def test_redraw_mode_consumes_draws_in_replica_order():
+    a = PeriodSchedule(3, tau_min=2, tau_max=5, seed=7, mode=SCHED_REDRAW)
+    b = PeriodSchedule(1, tau_min=2, tau_max=5, seed=7, mode=SCHED_FIXED)
+    stream = list(b.tau) + [b.draw() for _ in range(40)]
+    assert a.tau == stream[:3]
+    used = 3
+    for _ in range(12):
+        a.tick()
+        due = a.due()
+        if due:
+            a.served(due)
+            for i in due:
+                assert a.tau[i] == stream[used]
+                used += 1
+
+
+def test_per_replica_sync_uses_only_due_replicas():
+    rng = np.random.default_rng(4)
+    d = 3
+    o = LsamOracle(2, rng.standard_normal(d), d_raw=d, lr=0.1, lr_center=1.0, beta=0.0,
+                   momentum=0.0, tau=(1, 2))
+    y0 = o.get_params(-1)
+    o.step_grads(rng.standard_normal((2, d)), rng.standard_normal((2, d)))
+    x0_after1 = o.get_params(0)
+    assert o.sync() == 1
+    assert np.allclose(o.get_params(-1), x0_after1)       # mean over replica 0's 1 sample
+    x1_hist = [o.get_params(1)]
+    o.step_grads(rng.standard_normal((2, d)), rng.standard_normal((2, d)))
+    x1_hist.append(o.get_params(1))
+    mean = (o.get_params(0) + x1_hist[0] + x1_hist[1]) / 3
+    assert o.sync() == 2
+    assert np.allclose(o.get_params(-1), mean)
+    assert not np.allclose(y0, mean)
+
+
+# ---- bf16 operand rounding ---------------------------------------------------------------
+def test_bf16_round_nearest_even():
+    one = np.float32(1.0)
+    ulp = np.float32(2.0 ** -7)                    # spacing of bf16 in [1,2)
+    assert bf16_round(one + ulp / 2) == 1.0                       # tie -> even (1.0)
+    assert bf16_round(one + ulp * 1.5) == float(one + 2 * ulp)    # tie -> even (1+2ulp)
+    assert bf16_round(one + ulp * 0.51) == float(one + ulp)
+    assert bf16_round(np.float32(-3.0)) == -3.0
+    x = np.random.default_rng(0).standard_normal(1000).astype(np.float32)
+    r = bf16_round(x)
+    assert np.all(np.abs(r - x) <= np.abs(x) * 2.0 ** -8)
+    t = torch.tensor(x).to(torch.bfloat16).to(torch.float64).numpy()   # library witness
+    assert np.array_equal(r, t)
+
+
+def test_bf16_model_rounds_only_matrix_operands():
+    # with inputs and weights already bf16-representable and a single layer the bf16
+    # model equals the fp64 model except for the rounding of dZ in dW
+    m32, m16 = Mlp((8, 4)), Mlp((8, 4), gemm_dtype=1)
+    rng = np.random.default_rng(1)
+    x = bf16_round(rng.standard_normal(m32.d).astype(np.float32))
+    X = bf16_round(rng.standard_normal((5, 8)).astype(np.float32))
+    lab = rng.integers(0, 4, 5)
+    l32, g32 = m32.loss_and_grad(x, X, lab)
+    l16, g16 = m16.loss_and_grad(x, X, lab)
+    assert l32 == l16
+    assert np.max(np.abs(g16 - g32)) <= 2.0 ** -8 * np.max(np.abs(g32)) * 1.01

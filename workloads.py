@@ -1,0 +1,130 @@
+"""Workload table and seeded synthetic input generators.
+
+This module holds data only: hyper-parameter tables for the five workloads and
+seeded numpy generators for initial parameters, input batches, labels and raw
+gradient vectors.  It contains none of the method's arithmetic (no model, no
+schedule generator, no rounding rules), so both the CPU oracle's tests and the
+GPU path's tests/benchmarks can draw identical inputs from it without sharing
+any computation.
+
+The shapes mirror the paper's image-classification set-up (Experiments,
+"Experiment Setup": n = 4 workers, per-worker batch 128; CIFAR-shaped
+3x32x32 = 3072-dim inputs, 10/100 classes), with dense MLPs standing in for
+the paper's convolutional models.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field, replace
+from typing import Optional, Tuple
+
+import numpy as np
+
+SCHED_FIXED = 0   # periods drawn once at start
+SCHED_REDRAW = 1  # a replica's period is redrawn at each of its syncs
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    K: int                                  # replicas (the paper's n workers)
+    dims: Tuple[int, ...] = ()              # in_0, out_1, ..., out_L; () => raw-vector mode
+    d_raw: int = 0                          # parameters per replica in raw-vector mode
+    batch: int = 0                          # B per replica
+    gemm_dtype: int = 0                     # 0 = fp32, 1 = bf16 operands / fp32 accumulate
+    rho: float = 0.05
+    gamma: float = 1e-12
+    lr: float = 0.1
+    lr_center: float = 1.0
+    momentum: float = 0.9
+    beta: float = 0.9
+    lambda0: float = 0.5
+    lambda_abs: float = -1.0                # >= 0 overrides lambda0/(lr*tau)
+    nesterov: int = 1
+    tau: Optional[Tuple[int, ...]] = None   # explicit periods, else drawn
+    tau_min: int = 1
+    tau_max: int = 1
+    sched_seed: int = 0
+    sched_mode: int = SCHED_FIXED
+    steps: int = 20
+    data_seed: int = 0
+    n_classes: int = field(default=0)
+    grad_std: float = 1e-2                  # raw mode: std of the synthetic gradients
+    batch_pool: int = 0                     # 0 => fresh batch each step, else pool size cycled
+
+    @property
+    def d(self) -> int:
+        if not self.dims:
+            return self.d_raw
+        return sum(self.dims[l] * self.dims[l + 1] + self.dims[l + 1]
+                   for l in range(len(self.dims) - 1))
+
+    def scaled(self, **kw) -> "Workload":
+        return replace(self, **kw)
+
+
+def _mlp(inp, width, hidden, classes):
+    return (inp,) + (width,) * hidden + (classes,)
+
+
+WORKLOADS = {
+    # K=2, MLP 784-128-10 fp32, B=32, rho .05, lr .1, momentum .9, period 4, 20 steps
+    "cfg1": Workload("cfg1", K=2, dims=(784, 128, 10), batch=32, rho=0.05,
+                     tau=(4, 4), steps=20, data_seed=0, n_classes=10),
+    # K=4, MLP 3072-1024-1024-10 fp32, B=128, periods from {2..8} seeded, 50 steps
+    "cfg2": Workload("cfg2", K=4, dims=(3072, 1024, 1024, 10), batch=128, rho=0.05,
+                     tau_min=2, tau_max=8, sched_seed=2, steps=50, data_seed=2,
+                     n_classes=10),
+    # K=8, 4 hidden layers of width 4096, 100 classes, bf16 operands, B=256
+    "cfg3": Workload("cfg3", K=8, dims=_mlp(3072, 4096, 4, 100), batch=256, gemm_dtype=1,
+                     rho=0.1, tau_min=2, tau_max=8, sched_seed=3, steps=20, data_seed=3,
+                     n_classes=100, batch_pool=8),
+    # update-only bandwidth path: K=8 x d=1e8 raw vectors, 100 iterations
+    "cfg4": Workload("cfg4", K=8, d_raw=100_000_000, rho=0.05, tau_min=2, tau_max=8,
+                     sched_seed=4, steps=100, data_seed=4),
+    # K=16, 6 hidden layers of width 8192, 1000 classes, bf16 operands, B=512
+    "cfg5": Workload("cfg5", K=16, dims=_mlp(3072, 8192, 6, 1000), batch=512, gemm_dtype=1,
+                     rho=0.1, tau_min=4, tau_max=16, sched_seed=5, steps=20, data_seed=5,
+                     n_classes=1000, batch_pool=4),
+}
+
+
+def _rng(seed: int, stream: int) -> np.random.Generator:
+    return np.random.default_rng([int(seed), int(stream)])
+
+
+def init_params(w: Workload, seed: Optional[int] = None) -> np.ndarray:
+    """One flat fp32 parameter vector [d]: per layer W [out,in] row-major then b [out],
+    each drawn U(-1/sqrt(in), 1/sqrt(in)); raw mode: N(0,1)."""
+    rng = _rng(w.data_seed if seed is None else seed, 1)
+    if not w.dims:
+        return rng.standard_normal(w.d_raw, dtype=np.float32)
+    parts = []
+    for l in range(len(w.dims) - 1):
+        fan_in, out = w.dims[l], w.dims[l + 1]
+        bound = np.float32(1.0 / np.sqrt(fan_in))
+        parts.append((rng.random(out * fan_in, dtype=np.float32) * 2 - 1) * bound)
+        parts.append((rng.random(out, dtype=np.float32) * 2 - 1) * bound)
+    return np.concatenate(parts).astype(np.float32)
+
+
+def batch(w: Workload, step: int):
+    """Inputs X [K,B,in_0] fp32 ~ N(0,1) and labels [K,B] int32 uniform over the classes
+    for tick `step` (a pool index when the workload cycles a fixed pool).  For bf16
+    workloads the low 16 mantissa bits are cleared so every value is exactly
+    representable in bf16 and no rounding rule enters the data."""
+    idx = step % w.batch_pool if w.batch_pool else step
+    rng = _rng(w.data_seed, 1000 + idx)
+    X = rng.standard_normal((w.K, w.batch, w.dims[0]), dtype=np.float32)
+    if w.gemm_dtype == 1:
+        X = (X.view(np.uint32) & np.uint32(0xFFFF0000)).view(np.float32)
+    labels = rng.integers(0, w.n_classes, size=(w.K, w.batch), dtype=np.int32)
+    return X, labels
+
+
+def raw_grads(w: Workload, step: int, d: Optional[int] = None):
+    """Raw-vector mode: two gradient sets g1, g2 [K,d] fp32 ~ N(0, grad_std^2)."""
+    d = w.d_raw if d is None else d
+    rng = _rng(w.data_seed, 5000 + step)
+    g1 = rng.standard_normal((w.K, d), dtype=np.float32) * np.float32(w.grad_std)
+    g2 = rng.standard_normal((w.K, d), dtype=np.float32) * np.float32(w.grad_std)
+    return g1, g2

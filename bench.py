@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Throughput of the K-replica LSAM hot path on one MI355X.
+
+One "step" is one pass of the whole path over one batch of synthetic input: `lsam_step`
+(forward/backward, gradient norm, ascent perturbation, second forward/backward, descent +
+coupling for all K replicas) followed by `lsam_sync` (schedule test and, when replicas are
+due, the center update).  Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line: replica-samples/s plus a `roofline` object for the dominant kernel
+class (HIP-event durations measured inside the library on its own stream over a second run
+of the same steps) and a `cpu_baseline` object (the CPU oracle timed on a bounded sample).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads  # noqa: E402
+
+PEAK_HBM_GBS = 8000.0
+PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
+
+
+def gemm_flops(w):
+    """Per all-replica step: flops of the forward, dX and dW GEMM classes (both passes)."""
+    B, K = w.batch, w.K
+    sw = sum(w.dims[l] * w.dims[l + 1] for l in range(len(w.dims) - 1))
+    sw_dx = sum(w.dims[l] * w.dims[l + 1] for l in range(1, len(w.dims) - 1))
+    return {"gemm_fwd": 2 * 2.0 * B * sw * K, "gemm_dw": 2 * 2.0 * B * sw * K,
+            "gemm_dx": 2 * 2.0 * B * sw_dx * K}
+
+
+def stream_bytes(w):
+    """Algorithmic bytes per all-replica step of the update-path kernels (reads + writes
+    the method itself requires; y is shared by the K replicas)."""
+    n = float(w.K) * w.d
+    bf = w.gemm_dtype == 1
+    return {"sumsq_partials": 4 * n,
+            "perturb": (10 if bf else 12) * n,
+            "descent": (34 if bf else 32) * n + 4.0 * w.d}
+
+
+def make_inputs(w, torch, dev, n_sets):
+    sets = []
+    if w.dims:
+        for s in range(n_sets):
+            X, lab = workloads.batch(w, s)
+            Xd = torch.from_numpy(X).to(dev)
+            if w.gemm_dtype == 1:
+                Xd = Xd.to(torch.bfloat16)
+            sets.append((Xd.contiguous(), torch.from_numpy(lab).to(dev)))
+    else:
+        # raw-vector mode: fixed gradient buffers ~ N(0, grad_std^2), generated on the device
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(w.data_seed)
+        g1 = torch.randn(w.K, w.d_raw, device=dev, generator=gen) * w.grad_std
+        g2 = torch.randn(w.K, w.d_raw, device=dev, generator=gen) * w.grad_std
+        sets.append((g1, g2))
+    return sets
+
+
+def cpu_baseline(w, budget_s=20.0):
+    """Times the oracle, single-threaded, on a bounded sample of the workload."""
+    from threadpoolctl import threadpool_limits
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from util import oracle_from
+    with threadpool_limits(limits=1):
+        if w.dims:
+            # one replica; shrink the batch for the two largest workloads
+            frac = {"cfg5": 8, "cfg3": 2}.get(w.name, 1)
+            ws = w.scaled(K=1, batch=max(w.batch // frac, 1), tau=(10 ** 6,))
+            o = oracle_from(ws, workloads.init_params(ws))
+            X, lab = workloads.batch(ws, 0)
+            n, t0 = 0, time.perf_counter()
+            while True:
+                o.step(X, lab)
+                n += 1
+                if time.perf_counter() - t0 > budget_s / 2 or n >= 20:
+                    break
+            dt = time.perf_counter() - t0
+            value = n * ws.batch / dt
+            sample = "%d step(s) of 1 replica at batch %d (of K=%d, B=%d)" % (n, ws.batch, w.K, w.batch)
+            unit = "replica-samples/s"
+        else:
+            d = min(w.d_raw, 10_000_000)
+            ws = w.scaled(K=1, d_raw=d, tau=(4,))
+            o = oracle_from(ws, workloads.init_params(ws))
+            g1, g2 = workloads.raw_grads(ws, 0)
+            n, t0 = 0, time.perf_counter()
+            while True:
+                o.step_grads(g1, g2)
+                o.sync()
+                n += 1
+                if time.perf_counter() - t0 > budget_s / 2 or n >= 20:
+                    break
+            dt = time.perf_counter() - t0
+            value = n * d / dt
+            sample = "%d iteration(s) of 1 replica at d=%d (of K=%d, d=%d)" % (n, d, w.K, w.d_raw)
+            unit = "replica-params/s"
+    return {"value": value, "unit": unit, "cores": 1, "kind": "oracle", "sample": sample}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2", choices=sorted(workloads.WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the path holds all K replicas on a single MI355X and "
+              "uses no collectives, so --gpus %d is not supported." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2509_03110_amd import lsam
+    if not torch.cuda.is_available():
+        print("no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    w = workloads.WORKLOADS[args.workload]
+    steps = args.steps if args.steps is not None else {"cfg1": 200, "cfg2": 200}.get(w.name, 20)
+
+    cfg, keep = lsam.config_from_workload(w)
+    eng = lsam.Lsam(cfg, workloads.init_params(w), device=dev, keep=keep)
+    sets = make_inputs(w, torch, dev, w.batch_pool or 8)
+    loss = torch.zeros(w.K, device=dev)
+
+    def one(i):
+        a, b = sets[i % len(sets)]
+        if w.dims:
+            eng.lsam_step(a, b, loss)
+        else:
+            eng.lsam_step_grads(a, b)
+        eng.lsam_sync()
+
+    for i in range(args.warmup):
+        one(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        one(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms = dt / steps * 1e3
+
+    if w.dims:
+        value, unit, metric = w.K * w.batch / (dt / steps), "replica-samples/s", \
+            "replica-samples/sec per LSAM step"
+    else:
+        value, unit, metric = w.K * w.d_raw / (dt / steps), "replica-params/s", \
+            "replica-params/sec per LSAM update iteration"
+
+    roof, kernels = None, {}
+    if not args.no_kernel_timing:
+        eng.lsam_timing_enable(True)
+        for i in range(steps):
+            one(i)
+        stats = eng.lsam_timing_read()
+        eng.lsam_timing_enable(False)
+        flops = gemm_flops(w) if w.dims else {}
+        nbytes = stream_bytes(w)
+        for name, (cnt, tot) in stats.items():
+            if cnt == 0:
+                continue
+            k = {"launches_per_step": cnt / steps, "ms_per_step": tot / steps,
+                 "avg_launch_ms": tot / cnt}
+            if name in flops and tot > 0:
+                k.update(bound="mfma", achieved=flops[name] * steps / (tot * 1e-3) / 1e12,
+                         peak=PEAK_TFLOPS[w.gemm_dtype], unit="TFLOP/s")
+            elif name in nbytes and tot > 0:
+                k.update(bound="hbm", achieved=nbytes[name] * steps / (tot * 1e-3) / 1e9,
+                         peak=PEAK_HBM_GBS, unit="GB/s")
+            if "achieved" in k:
+                k["frac"] = k["achieved"] / k["peak"]
+            kernels[name] = k
+        ranked = [n for n in sorted(kernels, key=lambda n: -kernels[n]["ms_per_step"])
+                  if "achieved" in kernels[n]]
+        if ranked:
+            top = kernels[ranked[0]]
+            roof = {"kernel": ranked[0], "bound": top["bound"], "achieved": top["achieved"],
+                    "peak": top["peak"], "unit": top["unit"], "frac": top["frac"],
+                    "traffic": None, "avg_launch_ms": top["avg_launch_ms"]}
+
+    out = {
+        "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if (w.gemm_dtype == 0) else "bf16 operands, f32 accumulate and master weights",
+        "data": "synthetic",
+        "config": {"workload": w.name, "K": w.K, "dims": list(w.dims), "d": w.d, "batch": w.batch,
+                   "rho": w.rho, "lr": w.lr, "momentum": w.momentum,
+                   "periods": eng.lsam_get_schedule()[0]},
+        "roofline": roof, "kernels": kernels,
+    }
+    eng.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,173 @@
+/*
+ * lsam.h -- C boundary of the K-replica LSAM step engine for AMD MI355X (gfx950).
+ *
+ * K worker replicas of one model live on one GPU.  `lsam_step` advances every replica by
+ * one sharpness-aware local iteration; `lsam_sync` performs the center update for the
+ * replicas whose communication period has elapsed.  The paper's asynchronous multi-worker
+ * schedule (Algorithm 2, "Asynchronous Distributed LSAM") is replayed deterministically:
+ * every call to `lsam_step` is one local iteration of every worker, and the period of each
+ * worker comes from an explicit list or a seeded integer generator.
+ *
+ * Conventions
+ *   - C linkage, no exceptions cross the boundary.  Every call returns 0 (or a count >= 0
+ *     where stated) on success and a negative LSAM_E* code on failure;
+ *     `lsam_last_error()` then returns a thread-local message.
+ *   - Pointer arguments are marked [host] or [device].  The library never allocates or
+ *     frees device memory: all device state lives in one caller-provided workspace
+ *     (`lsam_workspace_bytes` tells its size) that must stay valid, and must not be
+ *     touched by the caller, until `lsam_destroy`.  It must be 256-byte aligned.
+ *   - All kernels are enqueued on the caller's stream (a hipStream_t passed as void*,
+ *     NULL = the default stream).  `lsam_step` and `lsam_sync` do not block the host;
+ *     the read-out calls synchronise the stream before copying.
+ *   - A context is not thread-safe; use one per host thread.
+ *
+ * Flat parameter layout of one replica and of the center y (what `init_params` holds and
+ * what `lsam_get_params` returns): for l = 1..L: W_l row-major [out_l, in_l], then
+ * b_l [out_l].  In raw-vector mode (n_layers == 0) it is a plain vector of d_raw floats.
+ */
+#ifndef LSAM_H
+#define LSAM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LSAM_OK       0
+#define LSAM_EINVAL  -1   /* bad argument or configuration                       */
+#define LSAM_ENOMEM  -2   /* workspace too small / host allocation failed        */
+#define LSAM_EHIP    -3   /* a HIP runtime call failed                           */
+#define LSAM_ESTATE  -4   /* call not valid for this context (e.g. wrong mode)   */
+
+#define LSAM_MAX_REPLICAS 64
+#define LSAM_MAX_LAYERS   16
+
+#define LSAM_GEMM_FP32 0  /* fp32 operands, fp32 accumulate                      */
+#define LSAM_GEMM_BF16 1  /* bf16 operands, fp32 accumulate, fp32 master weights */
+
+#define LSAM_SCHED_FIXED  0  /* periods drawn once at init                       */
+#define LSAM_SCHED_REDRAW 1  /* a replica draws a new period at each of its syncs */
+
+typedef struct lsam_ctx lsam_ctx;
+
+/* Inputs of Algorithm 2 ("pulling coefficient lambda, perturbation radius rho, learning
+ * rates (eta, eta'), sync period tau, momentum factor beta") plus the model shape. */
+typedef struct {
+  int32_t K;              /* number of replicas = the paper's n workers, 1..LSAM_MAX_REPLICAS */
+  int32_t n_layers;       /* L dense layers; 0 selects raw-vector mode                */
+  const int32_t* dims;    /* [host] L+1 entries in_0, out_1, ..., out_L (MLP mode)    */
+  int64_t d_raw;          /* parameters per replica, raw-vector mode only             */
+  int32_t batch;          /* B samples per replica per step (MLP mode)                */
+  int32_t gemm_dtype;     /* LSAM_GEMM_FP32 or LSAM_GEMM_BF16                         */
+  float rho;              /* perturbation radius (Formulation, f_SAM)                 */
+  float gamma;            /* stabiliser in rho*g/(||g||+gamma), >= 0                  */
+  float lr;               /* eta: sampler step size                                   */
+  float lr_center;        /* eta': center step size; the paper fixes 1.0              */
+  float momentum;         /* mu of the momentum sampler (Section "Distributed Training") */
+  float beta;             /* look-ahead factor of g = g' + beta (g' - g'_prev)        */
+  float lambda0;          /* lambda_i = lambda0 / (lr * tau_i) (Appendix, Hyperparameter Search) */
+  float lambda_abs;       /* if >= 0: fixed lambda for every replica instead          */
+  int32_t nesterov;       /* 1: x -= lr (G + mu v);  0: x -= lr v                     */
+  const int32_t* tau;     /* [host] K explicit periods >= 1, or NULL to draw them     */
+  int32_t tau_min;        /* inclusive range of drawn periods                         */
+  int32_t tau_max;
+  uint64_t sched_seed;    /* s_0 of the period generator                              */
+  int32_t sched_mode;     /* LSAM_SCHED_FIXED or LSAM_SCHED_REDRAW                    */
+} lsam_config;
+
+/* Which per-replica buffer `lsam_get_buffer` copies out. */
+#define LSAM_BUF_PARAMS     0  /* x_i (replica -1: center y)                          */
+#define LSAM_BUF_VELOCITY   1  /* v_i                                                  */
+#define LSAM_BUF_ITER_SUM   2  /* S_i = sum of x_i's iterates since its last sync     */
+#define LSAM_BUF_GRAD       3  /* gradient buffer (g2 after a step; MLP mode only)    */
+#define LSAM_BUF_PERTURBED  4  /* x~_i of the last step: fp32, or the bf16 operand copy
+                                  widened to fp32 in bf16 mode (which holds bf16(x_i)
+                                  again once the step has finished)                    */
+#define LSAM_BUF_CENTER_DIR 5  /* g'_prev (replica ignored)                            */
+
+/* Bytes of device workspace the configuration needs; 0 if the configuration is invalid
+ * (then `lsam_last_error` says why).  Host-only, touches no GPU. */
+size_t lsam_workspace_bytes(const lsam_config* cfg);
+
+/* Creates a context (Algorithm 2, "Initialization").  `init_params` [host] holds either d
+ * values, copied to all K replicas and to y, or (K+1)*d values: replicas 0..K-1, then y.
+ * `n_init` is that count.  v, S, g'_prev and all counters start at zero.
+ * `workspace` [device], `workspace_bytes` >= lsam_workspace_bytes(cfg).
+ * `stream`: hipStream_t as void*.  The configuration (including dims/tau) is copied. */
+int lsam_init(const lsam_config* cfg, const float* init_params, int64_t n_init,
+              void* workspace, size_t workspace_bytes, void* stream, lsam_ctx** out);
+
+/* One local iteration of every replica (Algorithm 2, asynchronous sampling step, with the
+ * score of q(x|y) built from the SAM gradient of Theorem "Convergence of G_t with Constant
+ * Perturbation"): forward/backward at x_i on (X_i, labels_i) -> g1; n = ||g1||_2 over the
+ * whole replica; x~ = x + rho g1/(n + gamma); forward/backward at x~ on the same batch
+ * -> g2; G = g2 + lambda_i (x_i - y); momentum update of x_i; S_i += x_i; c_i += 1.
+ *   X      [device] [K, B, in_0] row-major; float in fp32 mode, bfloat16 in bf16 mode
+ *   labels [device] [K, B] int32 class indices in [0, out_L)
+ *   loss   [device] [K] floats receiving the first-pass mean cross-entropy, or NULL
+ * MLP mode only (LSAM_ESTATE otherwise).  Labels are not range-checked on the host. */
+int lsam_step(lsam_ctx* ctx, const void* X, const int32_t* labels, float* loss);
+
+/* Raw-vector mode: same iteration with both gradients handed in.
+ *   g1, g2 [device] [K, d_raw] floats, row stride d_raw.  Read only. */
+int lsam_step_grads(lsam_ctx* ctx, const float* g1, const float* g2);
+
+/* Center update (Algorithm 2, synchronous optimization step) for the due set
+ * D = {i : c_i >= tau_i}: g' = sum_{i in D} S_i / sum_{i in D} c_i - y;
+ * g = g' + beta (g' - g'_prev) (g = g' at the first sync); y += eta' g; g'_prev = g';
+ * S_i = 0, c_i = 0 for i in D (and tau_i redrawn in redraw mode).
+ * Returns |D| (0: nothing was due, nothing launched) or a negative error. */
+int lsam_sync(lsam_ctx* ctx);
+
+/* Copies replica `replica`'s parameters (or y for replica == -1) to `dst` [host] in the
+ * flat layout; `n` must equal d.  Synchronises the stream. */
+int lsam_get_params(lsam_ctx* ctx, int32_t replica, float* dst, int64_t n);
+
+/* Same for the other per-replica buffers (LSAM_BUF_*). */
+int lsam_get_buffer(lsam_ctx* ctx, int32_t which, int32_t replica, float* dst, int64_t n);
+
+/* Overwrites one buffer from `src` [host] in the flat layout (restoring a snapshot taken
+ * with lsam_get_buffer; together with lsam_init this is the checkpoint/resume path).
+ * Valid for LSAM_BUF_PARAMS (replica -1: y), LSAM_BUF_VELOCITY, LSAM_BUF_ITER_SUM and
+ * LSAM_BUF_CENTER_DIR.  In bf16 mode setting a replica's parameters also refreshes its bf16
+ * operand copy.  Synchronises the stream before and after the copy. */
+int lsam_set_buffer(lsam_ctx* ctx, int32_t which, int32_t replica, const float* src, int64_t n);
+
+/* Per-replica gradient norms ||g1_i|| of the last step: `dst` [host] [K]. Synchronises. */
+int lsam_get_norms(lsam_ctx* ctx, float* dst);
+
+/* Schedule state: any of the outputs may be NULL.  tau_out, count_out [host] [K]. */
+int lsam_get_schedule(lsam_ctx* ctx, int32_t* tau_out, int32_t* count_out, int64_t* t_y_out);
+
+/* Changes eta and rho from the next step on (decaying schedules eta_t, rho_t of the
+ * convergence theorems are driven from the host through this call). */
+int lsam_set_scalars(lsam_ctx* ctx, float lr, float rho);
+
+/* Parameters per replica (d) of a configuration; -1 if invalid.  Host-only. */
+int64_t lsam_num_params(const lsam_config* cfg);
+
+/* Host-only replay of the schedule for `n_ticks` ticks (one step then one sync attempt
+ * per tick): due_out [host] [n_ticks*K] gets 1 where replica i was served at that tick,
+ * tau_out [host] [n_ticks*K] the period in force during that tick.  Touches no GPU. */
+int lsam_schedule_replay(const lsam_config* cfg, int32_t n_ticks, int32_t* due_out,
+                         int32_t* tau_out);
+
+/* Per-kernel launch statistics gathered with HIP events when enabled: for profiling
+ * only (it serialises nothing but adds two event records per launch).
+ * `lsam_timing_read` synchronises the stream and fills, for up to `cap` kernel classes,
+ * name pointers (static strings), launch counts and total milliseconds; returns the number
+ * of classes.  `lsam_timing_enable(ctx, 0)` switches it off and clears the totals. */
+int lsam_timing_enable(lsam_ctx* ctx, int32_t on);
+int lsam_timing_read(lsam_ctx* ctx, int32_t cap, const char** names, int64_t* counts,
+                     double* total_ms);
+
+void lsam_destroy(lsam_ctx* ctx);
+
+const char* lsam_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LSAM_H */

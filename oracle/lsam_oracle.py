@@ -123,6 +123,7 @@ class Mlp:
             self.offsets.append((off, off + fo * fi, off + fo * fi + fo))
             off += fo * fi + fo
         self.d = off
+        self.last_margin = np.inf   # diagnostic: smallest |hidden pre-activation| seen last call
 
     def unpack(self, x):
         out = []
@@ -139,8 +140,11 @@ class Mlp:
         layers = self.unpack(np.asarray(x, dtype=np.float64))
         B = X.shape[0]
         acts = [q(X)]
+        self.last_margin = np.inf
         for l, (W, b) in enumerate(layers):
             Z = acts[l] @ q(W).T + b
+            if l < self.L - 1:
+                self.last_margin = min(self.last_margin, float(np.min(np.abs(Z))))
             acts.append(q(np.maximum(Z, 0.0)) if l < self.L - 1 else Z)
         logits = acts[-1]
         zmax = logits.max(axis=1, keepdims=True)

@@ -1,0 +1,90 @@
+// Internal declarations shared by the host engine and the kernel launchers.
+// Nothing here is part of the public boundary (include/lsam.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/lsam.h"
+
+namespace lsam {
+
+constexpr int kMaxK = LSAM_MAX_REPLICAS;
+
+// Small per-replica tables handed to kernels by value.
+struct ReplicaScalars {
+  float v[kMaxK];
+};
+struct DueList {
+  int32_t n;
+  int32_t idx[kMaxK];
+};
+
+// ---- streaming kernels (update path) ---------------------------------------------------
+
+// Sum of squares, pass 1: per (replica, block) partial sums in double.
+// g: [K] rows of `n` floats with row stride `g_stride`; partials: [K, nblk] doubles.
+void launch_sumsq_partials(const float* g, int64_t g_stride, int64_t n, int K, double* partials,
+                           int nblk, hipStream_t s);
+// Pass 2: norms[k] = sqrt(sum_b partials[k,b]); scale[k] = rho / (norm + gamma).
+// If loss_rows != nullptr also reduces loss_rows [K,B] to loss_out[k] = mean (both passes of
+// the tree are fixed-order, so the result is run-to-run deterministic).
+void launch_norm_finish(const double* partials, int nblk, int K, float rho, float gamma,
+                        float* norms, float* scale, const float* loss_rows, int B,
+                        float* loss_out, hipStream_t s);
+// x~ = x + scale[k] * g.  Writes fp32 (xt_f32) or bf16 (xt_bf16), whichever is non-null.
+void launch_perturb(const float* x, const float* g, int64_t g_stride, const float* scale,
+                    float* xt_f32, uint16_t* xt_bf16, int64_t stride, int64_t n, int K,
+                    hipStream_t s);
+// Descent + coupling for all K replicas, y read once per index:
+//   G = g + lam[k] (x - y); v = mu v + G; x -= lr (G + mu v) [nesterov] | lr v; S += x.
+// Also writes bf16(x) to shadow if non-null.
+void launch_descent(float* x, const float* g, int64_t g_stride, float* v, float* S,
+                    const float* y, uint16_t* shadow, int64_t stride, int64_t n, int K,
+                    const ReplicaScalars& lam, float lr, float mu, int nesterov, hipStream_t s);
+// Center update over the due replicas (Algorithm 2, synchronous optimization step).
+void launch_center(float* S, float* y, float* gprev, int64_t stride, int64_t n,
+                   const DueList& due, float inv_m, float beta, float lr_center, int has_prev,
+                   hipStream_t s);
+// dst[k, :] = src[:] for k < K (fp32), optionally also a bf16 copy.
+void launch_broadcast(const float* src, float* dst, uint16_t* dst_bf16, int64_t stride, int64_t n,
+                      int K, hipStream_t s);
+void launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+// fp32 -> bf16 (round to nearest even) / bf16 -> fp32 element-wise copies.
+void launch_to_bf16(const float* src, uint16_t* dst, int64_t n, hipStream_t s);
+void launch_from_bf16(const uint16_t* src, float* dst, int64_t n, hipStream_t s);
+// Row-padded copy: dst[r, 0:cols] = src[r, 0:cols], rows of `elem` bytes-sized elements.
+void launch_pad_rows(const void* src, void* dst, int64_t rows, int cols, int ld_dst, int elem,
+                     hipStream_t s);
+
+// ---- model kernels ------------------------------------------------------------------------
+
+enum GemmEpilogue { EPI_BIAS = 0, EPI_BIAS_RELU = 1, EPI_MASK = 2, EPI_PLAIN = 3 };
+
+// C[k][m, n] = sum_kk A(k; m, kk) * B(k; n, kk), batched over replicas k.
+// An operand is "k-major" when kk is its contiguous index (row pitch ld along m resp. n),
+// otherwise "m-major" (kk selects the row, m resp. n is contiguous).
+struct GemmDesc {
+  const void* A; int64_t strideA; int ldA; int a_kmajor;
+  const void* B; int64_t strideB; int ldB; int b_kmajor;
+  void* C; int64_t strideC; int ldC;
+  int M, N, Kd, batch;
+  int in_bf16;        // operands bf16 (else fp32)
+  int out_bf16;       // output bf16 (else fp32)
+  int epilogue;       // GemmEpilogue
+  const float* bias; int64_t strideBias;          // EPI_BIAS*: bias[n]
+  const float* bias_dir; const float* bias_scale; // if set: bias[n] + bias_scale[k] * bias_dir[n]
+  const void* mask; int64_t strideMask; int ldMask; // EPI_MASK: keep where mask[m,n] > 0 (operand dtype)
+};
+int launch_gemm(const GemmDesc& d, hipStream_t s);   // 0 ok, <0 unsupported shape
+
+// Softmax cross-entropy, forward and backward.  logits [K,B,ld] fp32; labels [K,B];
+// dz [K,B,ld_dz] (fp32 or bf16) = (softmax - onehot)/B, zero in the padded columns;
+// loss_rows [K,B] = lse - logit[label] (may be null).
+void launch_softmax_ce(const float* logits, int ld, const int32_t* labels, void* dz, int ld_dz,
+                       int dz_bf16, float* loss_rows, int K, int B, int C, hipStream_t s);
+// db[k][n] = sum_b dz[k][b][n].
+void launch_bias_grad(const void* dz, int ld, int dz_bf16, float* db, int64_t strideDb, int K,
+                      int B, int N, hipStream_t s);
+
+}  // namespace lsam

@@ -1,0 +1,112 @@
+// Fused softmax cross-entropy forward + backward (one wavefront per sample row, wavefront
+// shuffle reductions) and the bias gradient (column sums of dZ).
+#include "engine.h"
+
+namespace lsam {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+template <typename TD>
+__device__ __forceinline__ void put(TD* p, float v);
+template <> __device__ __forceinline__ void put<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void put<__bf16>(__bf16* p, float v) {
+  *p = static_cast<__bf16>(v);
+}
+
+// Row r = replica*B + sample.  loss_row = logsumexp(z) - z[label];
+// dz = (softmax(z) - onehot(label)) / B;  padded columns [C, ld_dz) are written as zero.
+template <typename TD>
+__global__ __launch_bounds__(kThreads) void softmax_ce_kernel(
+    const float* __restrict__ logits, int ld, const int32_t* __restrict__ labels,
+    TD* __restrict__ dz, int ld_dz, float* __restrict__ loss_rows, int rows, int B, int C) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * kWaves + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  const float* z = logits + (long long)r * ld;
+  const int lab = labels[r];
+  float mx = -INFINITY;
+  for (int c = lane; c < C; c += 64) mx = fmaxf(mx, z[c]);
+  mx = wave_max(mx);
+  float se = 0.f;
+  for (int c = lane; c < C; c += 64) se += __expf(z[c] - mx);
+  se = wave_sum(se);
+  const float inv = 1.f / se;
+  const float invB = 1.f / (float)B;
+  TD* d = dz + (long long)r * ld_dz;
+  for (int c = lane; c < ld_dz; c += 64) {
+    float v = 0.f;
+    if (c < C) {
+      v = __expf(z[c] - mx) * inv;
+      if (c == lab) v -= 1.f;
+      v *= invB;
+    }
+    put<TD>(d + c, v);
+  }
+  if (loss_rows != nullptr && lane == 0) {
+    const float zl = (lab >= 0 && lab < C) ? z[lab] : 0.f;
+    loss_rows[r] = logf(se) + mx - zl;
+  }
+}
+
+template <typename TD> __device__ __forceinline__ float get(const TD* p);
+template <> __device__ __forceinline__ float get<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float get<__bf16>(const __bf16* p) {
+  return static_cast<float>(*p);
+}
+
+// db[k][n] = sum_b dz[k][b][n]; one thread per column, rows summed in order.
+template <typename TD>
+__global__ __launch_bounds__(kThreads) void bias_grad_kernel(const TD* __restrict__ dz, int ld,
+                                                            float* __restrict__ db,
+                                                            long long strideDb, int B, int N) {
+  const int k = blockIdx.y;
+  const int n = blockIdx.x * kThreads + threadIdx.x;
+  if (n >= N) return;
+  const TD* p = dz + (long long)k * B * ld + n;
+  float s0 = 0.f, s1 = 0.f;
+  int b = 0;
+  for (; b + 1 < B; b += 2) {
+    s0 += get<TD>(p + (long long)b * ld);
+    s1 += get<TD>(p + (long long)(b + 1) * ld);
+  }
+  if (b < B) s0 += get<TD>(p + (long long)b * ld);
+  db[(long long)k * strideDb + n] = s0 + s1;
+}
+
+}  // namespace
+
+void launch_softmax_ce(const float* logits, int ld, const int32_t* labels, void* dz, int ld_dz,
+                       int dz_bf16, float* loss_rows, int K, int B, int C, hipStream_t s) {
+  const int rows = K * B;
+  const unsigned grid = (rows + kWaves - 1) / kWaves;
+  if (dz_bf16)
+    softmax_ce_kernel<__bf16><<<grid, kThreads, 0, s>>>(logits, ld, labels, (__bf16*)dz, ld_dz,
+                                                        loss_rows, rows, B, C);
+  else
+    softmax_ce_kernel<float><<<grid, kThreads, 0, s>>>(logits, ld, labels, (float*)dz, ld_dz,
+                                                       loss_rows, rows, B, C);
+}
+
+void launch_bias_grad(const void* dz, int ld, int dz_bf16, float* db, int64_t strideDb, int K,
+                      int B, int N, hipStream_t s) {
+  dim3 grid((N + kThreads - 1) / kThreads, K);
+  if (dz_bf16)
+    bias_grad_kernel<__bf16><<<grid, kThreads, 0, s>>>((const __bf16*)dz, ld, db, strideDb, B, N);
+  else
+    bias_grad_kernel<float><<<grid, kThreads, 0, s>>>((const float*)dz, ld, db, strideDb, B, N);
+}
+
+}  // namespace lsam

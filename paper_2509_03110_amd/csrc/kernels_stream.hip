@@ -1,0 +1,384 @@
+// Streaming kernels of the update path: gradient-norm reduction, ascent perturbation,
+// descent + coupling, center update.  All are HBM-bandwidth bound: every array is touched
+// once per kernel with 128-bit accesses, consecutive lanes on consecutive 16-byte words.
+#include "engine.h"
+
+namespace lsam {
+namespace {
+
+constexpr int kThreads = 256;
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
+
+template <int VEC> struct Vec;
+template <> struct Vec<4> { typedef f32x4 type; };
+template <> struct Vec<1> { typedef float type; };
+
+template <int VEC>
+__device__ __forceinline__ typename Vec<VEC>::type ldv(const float* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const typename Vec<VEC>::type*>(p));
+}
+template <int VEC>
+__device__ __forceinline__ void stv(float* p, typename Vec<VEC>::type v) {
+  __builtin_nontemporal_store(v, reinterpret_cast<typename Vec<VEC>::type*>(p));
+}
+// y / g'_prev are re-read by later kernels and other replicas: ordinary cached access.
+template <int VEC>
+__device__ __forceinline__ typename Vec<VEC>::type ldc(const float* p) {
+  return *reinterpret_cast<const typename Vec<VEC>::type*>(p);
+}
+
+__device__ __forceinline__ float elem(const f32x4& v, int i) { return v[i]; }
+__device__ __forceinline__ float elem(const float& v, int) { return v; }
+__device__ __forceinline__ void set_elem(f32x4& v, int i, float a) { v[i] = a; }
+__device__ __forceinline__ void set_elem(float& v, int, float a) { v = a; }
+
+__device__ __forceinline__ unsigned short bf16_bits(float f) {
+  return __builtin_bit_cast(unsigned short, static_cast<__bf16>(f));
+}
+template <int VEC>
+__device__ __forceinline__ void store_bf16(uint16_t* p, const typename Vec<VEC>::type& v) {
+  if constexpr (VEC == 4) {
+    u16x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = bf16_bits(v[i]);
+    *reinterpret_cast<u16x4*>(p) = o;
+  } else {
+    *p = bf16_bits(v);
+  }
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+  return v;
+}
+
+// Sum over the block in a fixed order; result valid in thread 0.
+__device__ __forceinline__ double block_sum(double v) {
+  __shared__ double part[kThreads / 64];
+  v = wave_sum(v);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) part[wave] = v;
+  __syncthreads();
+  double r = 0.0;
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 0; w < kThreads / 64; ++w) r += part[w];
+  }
+  __syncthreads();
+  return r;
+}
+
+// ---- gradient norm, pass 1 ------------------------------------------------------------------
+template <int VEC>
+__global__ __launch_bounds__(kThreads) void sumsq_partials_kernel(
+    const float* __restrict__ g, int64_t g_stride, int64_t nv, double* __restrict__ partials,
+    int nblk) {
+  const int k = blockIdx.y;
+  const int64_t chunk = (nv + nblk - 1) / nblk;
+  const int64_t beg = (int64_t)blockIdx.x * chunk;
+  const int64_t end = beg + chunk < nv ? beg + chunk : nv;
+  const float* gk = g + (int64_t)k * g_stride;
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  int64_t i = beg + threadIdx.x;
+  for (; i + 3 * kThreads < end; i += 4 * kThreads) {
+    auto v0 = ldv<VEC>(gk + i * VEC);
+    auto v1 = ldv<VEC>(gk + (i + kThreads) * VEC);
+    auto v2 = ldv<VEC>(gk + (i + 2 * kThreads) * VEC);
+    auto v3 = ldv<VEC>(gk + (i + 3 * kThreads) * VEC);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      a0 += elem(v0, e) * elem(v0, e);
+      a1 += elem(v1, e) * elem(v1, e);
+      a2 += elem(v2, e) * elem(v2, e);
+      a3 += elem(v3, e) * elem(v3, e);
+    }
+  }
+  for (; i < end; i += kThreads) {
+    auto v0 = ldv<VEC>(gk + i * VEC);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) a0 += elem(v0, e) * elem(v0, e);
+  }
+  double s = ((double)a0 + (double)a1) + ((double)a2 + (double)a3);
+  s = block_sum(s);
+  if (threadIdx.x == 0) partials[(int64_t)k * nblk + blockIdx.x] = s;
+}
+
+// ---- gradient norm, pass 2 (+ mean loss) ----------------------------------------------------
+__global__ __launch_bounds__(kThreads) void norm_finish_kernel(
+    const double* __restrict__ partials, int nblk, float rho, float gamma,
+    float* __restrict__ norms, float* __restrict__ scale, const float* __restrict__ loss_rows,
+    int B, float* __restrict__ loss_out) {
+  const int k = blockIdx.x;
+  double s = 0.0;
+  for (int i = threadIdx.x; i < nblk; i += kThreads) s += partials[(int64_t)k * nblk + i];
+  s = block_sum(s);
+  if (threadIdx.x == 0) {
+    const double n = sqrt(s);
+    norms[k] = (float)n;
+    scale[k] = (float)((double)rho / (n + (double)gamma));
+  }
+  if (loss_rows != nullptr && loss_out != nullptr) {
+    double l = 0.0;
+    for (int i = threadIdx.x; i < B; i += kThreads) l += (double)loss_rows[(int64_t)k * B + i];
+    l = block_sum(l);
+    if (threadIdx.x == 0) loss_out[k] = (float)(l / (double)B);
+  }
+}
+
+// ---- ascent perturbation ----------------------------------------------------------------------
+template <int VEC, bool BF16_OUT>
+__global__ __launch_bounds__(kThreads) void perturb_kernel(
+    const float* __restrict__ x, const float* __restrict__ g, int64_t g_stride,
+    const float* __restrict__ scale, float* __restrict__ xt, uint16_t* __restrict__ xt16,
+    int64_t stride, int64_t nv) {
+  const int k = blockIdx.y;
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= nv) return;
+  const float sc = scale[k];
+  auto xv = ldv<VEC>(x + (int64_t)k * stride + i * VEC);
+  auto gv = ldv<VEC>(g + (int64_t)k * g_stride + i * VEC);
+  typename Vec<VEC>::type o;
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) set_elem(o, e, elem(xv, e) + sc * elem(gv, e));
+  if constexpr (BF16_OUT) {
+    store_bf16<VEC>(xt16 + (int64_t)k * stride + i * VEC, o);
+  } else {
+    stv<VEC>(xt + (int64_t)k * stride + i * VEC, o);
+  }
+}
+
+// ---- descent + coupling -------------------------------------------------------------------------
+template <int VEC, bool SHADOW>
+__global__ __launch_bounds__(kThreads) void descent_kernel(
+    float* __restrict__ x, const float* __restrict__ g, int64_t g_stride, float* __restrict__ v,
+    float* __restrict__ S, const float* __restrict__ y, uint16_t* __restrict__ shadow,
+    int64_t stride, int64_t nv, int K, ReplicaScalars lam, float lr, float mu, int nesterov) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= nv) return;
+  const auto yv = ldc<VEC>(y + i * VEC);
+#pragma unroll 2
+  for (int k = 0; k < K; ++k) {
+    const int64_t o = (int64_t)k * stride + i * VEC;
+    auto xv = ldv<VEC>(x + o);
+    auto gv = ldv<VEC>(g + (int64_t)k * g_stride + i * VEC);
+    auto vv = ldv<VEC>(v + o);
+    auto sv = ldv<VEC>(S + o);
+    const float lk = lam.v[k];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const float xe = elem(xv, e);
+      const float G = elem(gv, e) + lk * (xe - elem(yv, e));
+      const float vn = mu * elem(vv, e) + G;
+      const float xn = nesterov ? xe - lr * (G + mu * vn) : xe - lr * vn;
+      set_elem(vv, e, vn);
+      set_elem(xv, e, xn);
+      set_elem(sv, e, elem(sv, e) + xn);
+    }
+    stv<VEC>(x + o, xv);
+    stv<VEC>(v + o, vv);
+    stv<VEC>(S + o, sv);
+    if constexpr (SHADOW) store_bf16<VEC>(shadow + o, xv);
+  }
+}
+
+// ---- center update ------------------------------------------------------------------------------
+template <int VEC>
+__global__ __launch_bounds__(kThreads) void center_kernel(
+    float* __restrict__ S, float* __restrict__ y, float* __restrict__ gprev, int64_t stride,
+    int64_t nv, DueList due, float inv_m, float beta, float lr_center, int has_prev) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= nv) return;
+  typename Vec<VEC>::type tot, zero;
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) { set_elem(tot, e, 0.f); set_elem(zero, e, 0.f); }
+  for (int j = 0; j < due.n; ++j) {
+    float* p = S + (int64_t)due.idx[j] * stride + i * VEC;
+    auto sv = ldv<VEC>(p);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) set_elem(tot, e, elem(tot, e) + elem(sv, e));
+    stv<VEC>(p, zero);
+  }
+  auto yv = ldc<VEC>(y + i * VEC);
+  auto pv = ldc<VEC>(gprev + i * VEC);
+  typename Vec<VEC>::type gp;
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) {
+    const float gpe = elem(tot, e) * inv_m - elem(yv, e);
+    const float ge = has_prev ? gpe + beta * (gpe - elem(pv, e)) : gpe;
+    set_elem(gp, e, gpe);
+    set_elem(yv, e, elem(yv, e) + lr_center * ge);
+  }
+  *reinterpret_cast<typename Vec<VEC>::type*>(y + i * VEC) = yv;
+  *reinterpret_cast<typename Vec<VEC>::type*>(gprev + i * VEC) = gp;
+}
+
+// ---- small utility kernels ------------------------------------------------------------------------
+template <int VEC, bool SHADOW>
+__global__ __launch_bounds__(kThreads) void broadcast_kernel(
+    const float* __restrict__ src, float* __restrict__ dst, uint16_t* __restrict__ dst16,
+    int64_t stride, int64_t nv, int K) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= nv) return;
+  auto sv = ldc<VEC>(src + i * VEC);
+  for (int k = 0; k < K; ++k) {
+    stv<VEC>(dst + (int64_t)k * stride + i * VEC, sv);
+    if constexpr (SHADOW) store_bf16<VEC>(dst16 + (int64_t)k * stride + i * VEC, sv);
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void fill_zero_kernel(uint4* __restrict__ p, int64_t n16) {
+  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  const int64_t step = (int64_t)gridDim.x * kThreads;
+  for (; i < n16; i += step) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+__global__ __launch_bounds__(kThreads) void to_bf16_kernel(const float* __restrict__ s,
+                                                          uint16_t* __restrict__ d, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  const int64_t step = (int64_t)gridDim.x * kThreads;
+  for (; i < n; i += step) d[i] = bf16_bits(s[i]);
+}
+
+__global__ __launch_bounds__(kThreads) void from_bf16_kernel(const uint16_t* __restrict__ s,
+                                                            float* __restrict__ d, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  const int64_t step = (int64_t)gridDim.x * kThreads;
+  for (; i < n; i += step) d[i] = __uint_as_float((unsigned)s[i] << 16);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void pad_rows_kernel(const T* __restrict__ s,
+                                                           T* __restrict__ d, int64_t rows,
+                                                           int cols, int ld) {
+  const int64_t total = rows * cols;
+  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  const int64_t step = (int64_t)gridDim.x * kThreads;
+  for (; i < total; i += step) {
+    const int64_t r = i / cols;
+    const int c = (int)(i - r * cols);
+    d[r * ld + c] = s[i];
+  }
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+inline unsigned blocks_for(int64_t n) { return (unsigned)((n + kThreads - 1) / kThreads); }
+inline unsigned capped_blocks(int64_t n) {
+  int64_t b = (n + kThreads - 1) / kThreads;
+  return (unsigned)(b < 1 ? 1 : (b > 65536 ? 65536 : b));
+}
+
+}  // namespace
+
+void launch_sumsq_partials(const float* g, int64_t g_stride, int64_t n, int K, double* partials,
+                           int nblk, hipStream_t s) {
+  dim3 grid(nblk, K);
+  if (n % 4 == 0 && g_stride % 4 == 0 && aligned16(g)) {
+    sumsq_partials_kernel<4><<<grid, kThreads, 0, s>>>(g, g_stride, n / 4, partials, nblk);
+  } else {
+    sumsq_partials_kernel<1><<<grid, kThreads, 0, s>>>(g, g_stride, n, partials, nblk);
+  }
+}
+
+void launch_norm_finish(const double* partials, int nblk, int K, float rho, float gamma,
+                        float* norms, float* scale, const float* loss_rows, int B,
+                        float* loss_out, hipStream_t s) {
+  norm_finish_kernel<<<K, kThreads, 0, s>>>(partials, nblk, rho, gamma, norms, scale, loss_rows,
+                                            B, loss_out);
+}
+
+void launch_perturb(const float* x, const float* g, int64_t g_stride, const float* scale,
+                    float* xt_f32, uint16_t* xt_bf16, int64_t stride, int64_t n, int K,
+                    hipStream_t s) {
+  const bool vec = n % 4 == 0 && g_stride % 4 == 0 && stride % 4 == 0 && aligned16(g);
+  if (vec) {
+    dim3 grid(blocks_for(n / 4), K);
+    if (xt_bf16)
+      perturb_kernel<4, true><<<grid, kThreads, 0, s>>>(x, g, g_stride, scale, nullptr, xt_bf16,
+                                                        stride, n / 4);
+    else
+      perturb_kernel<4, false><<<grid, kThreads, 0, s>>>(x, g, g_stride, scale, xt_f32, nullptr,
+                                                         stride, n / 4);
+  } else {
+    dim3 grid(blocks_for(n), K);
+    if (xt_bf16)
+      perturb_kernel<1, true><<<grid, kThreads, 0, s>>>(x, g, g_stride, scale, nullptr, xt_bf16,
+                                                        stride, n);
+    else
+      perturb_kernel<1, false><<<grid, kThreads, 0, s>>>(x, g, g_stride, scale, xt_f32, nullptr,
+                                                         stride, n);
+  }
+}
+
+void launch_descent(float* x, const float* g, int64_t g_stride, float* v, float* S,
+                    const float* y, uint16_t* shadow, int64_t stride, int64_t n, int K,
+                    const ReplicaScalars& lam, float lr, float mu, int nesterov, hipStream_t s) {
+  const bool vec = n % 4 == 0 && g_stride % 4 == 0 && stride % 4 == 0 && aligned16(g);
+  if (vec) {
+    const unsigned grid = blocks_for(n / 4);
+    if (shadow)
+      descent_kernel<4, true><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, shadow, stride,
+                                                        n / 4, K, lam, lr, mu, nesterov);
+    else
+      descent_kernel<4, false><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, nullptr, stride,
+                                                         n / 4, K, lam, lr, mu, nesterov);
+  } else {
+    const unsigned grid = blocks_for(n);
+    if (shadow)
+      descent_kernel<1, true><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, shadow, stride, n,
+                                                        K, lam, lr, mu, nesterov);
+    else
+      descent_kernel<1, false><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, nullptr, stride,
+                                                         n, K, lam, lr, mu, nesterov);
+  }
+}
+
+void launch_center(float* S, float* y, float* gprev, int64_t stride, int64_t n,
+                   const DueList& due, float inv_m, float beta, float lr_center, int has_prev,
+                   hipStream_t s) {
+  if (n % 4 == 0 && stride % 4 == 0) {
+    center_kernel<4><<<blocks_for(n / 4), kThreads, 0, s>>>(S, y, gprev, stride, n / 4, due, inv_m,
+                                                            beta, lr_center, has_prev);
+  } else {
+    center_kernel<1><<<blocks_for(n), kThreads, 0, s>>>(S, y, gprev, stride, n, due, inv_m, beta,
+                                                        lr_center, has_prev);
+  }
+}
+
+void launch_broadcast(const float* src, float* dst, uint16_t* dst_bf16, int64_t stride, int64_t n,
+                      int K, hipStream_t s) {
+  // internal buffers only: n and stride are multiples of 4 by construction
+  const unsigned grid = blocks_for(n / 4);
+  if (dst_bf16)
+    broadcast_kernel<4, true><<<grid, kThreads, 0, s>>>(src, dst, dst_bf16, stride, n / 4, K);
+  else
+    broadcast_kernel<4, false><<<grid, kThreads, 0, s>>>(src, dst, nullptr, stride, n / 4, K);
+}
+
+void launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return;
+  fill_zero_kernel<<<capped_blocks((int64_t)(bytes / 16)), kThreads, 0, s>>>(
+      reinterpret_cast<uint4*>(p), (int64_t)(bytes / 16));
+}
+
+void launch_to_bf16(const float* src, uint16_t* dst, int64_t n, hipStream_t s) {
+  to_bf16_kernel<<<capped_blocks(n), kThreads, 0, s>>>(src, dst, n);
+}
+void launch_from_bf16(const uint16_t* src, float* dst, int64_t n, hipStream_t s) {
+  from_bf16_kernel<<<capped_blocks(n), kThreads, 0, s>>>(src, dst, n);
+}
+
+void launch_pad_rows(const void* src, void* dst, int64_t rows, int cols, int ld_dst, int elem,
+                     hipStream_t s) {
+  const unsigned grid = capped_blocks(rows * cols);
+  if (elem == 4)
+    pad_rows_kernel<float><<<grid, kThreads, 0, s>>>((const float*)src, (float*)dst, rows, cols,
+                                                     ld_dst);
+  else
+    pad_rows_kernel<uint16_t><<<grid, kThreads, 0, s>>>((const uint16_t*)src, (uint16_t*)dst, rows,
+                                                        cols, ld_dst);
+}
+
+}  // namespace lsam

@@ -1,0 +1,753 @@
+// Host engine behind include/lsam.h: configuration checks, workspace carve-up, the integer
+// communication schedule, and the kernel sequence of one LSAM step / one center update.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "engine.h"
+
+namespace lsam {
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                   \
+  do {                                                                                  \
+    hipError_t e_ = (expr);                                                             \
+    if (e_ != hipSuccess) return fail(LSAM_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+// ---- communication schedule (integers only) -------------------------------------------------
+// Period generator: s_{j+1} = A s_j + C mod 2^64, draw_j = (s_{j+1} >> 33) mod range + min.
+// Replica i is due when its local count reaches its period (Algorithm 2's trigger
+// "sum_i t_x^(i) mod n tau = 0", taken per replica so that periods may differ; with equal
+// periods every replica is due at the same tick and the two coincide).
+class Schedule {
+ public:
+  void init(const lsam_config& c) {
+    K_ = c.K;
+    lo_ = c.tau_min;
+    hi_ = c.tau_max;
+    redraw_ = c.sched_mode == LSAM_SCHED_REDRAW;
+    state_ = c.sched_seed;
+    explicit_ = c.tau != nullptr;
+    tau_.resize(K_);
+    count_.assign(K_, 0);
+    t_y_ = 0;
+    for (int i = 0; i < K_; ++i) tau_[i] = explicit_ ? c.tau[i] : draw();
+  }
+  int32_t draw() {
+    state_ = state_ * 6364136223846793005ULL + 1442695040888963407ULL;
+    const uint64_t range = (uint64_t)(hi_ - lo_ + 1);
+    return (int32_t)((state_ >> 33) % range) + lo_;
+  }
+  void tick() {
+    for (int i = 0; i < K_; ++i) ++count_[i];
+  }
+  DueList due() const {
+    DueList d;
+    d.n = 0;
+    for (int i = 0; i < K_; ++i)
+      if (count_[i] >= tau_[i]) d.idx[d.n++] = i;
+    return d;
+  }
+  int64_t samples(const DueList& d) const {
+    int64_t m = 0;
+    for (int j = 0; j < d.n; ++j) m += count_[d.idx[j]];
+    return m;
+  }
+  void served(const DueList& d) {
+    for (int j = 0; j < d.n; ++j) {
+      count_[d.idx[j]] = 0;
+      if (redraw_ && !explicit_) tau_[d.idx[j]] = draw();
+    }
+    ++t_y_;
+  }
+  const std::vector<int32_t>& tau() const { return tau_; }
+  const std::vector<int32_t>& count() const { return count_; }
+  int64_t t_y() const { return t_y_; }
+
+ private:
+  int K_ = 0, lo_ = 1, hi_ = 1;
+  bool redraw_ = false, explicit_ = false;
+  uint64_t state_ = 0;
+  std::vector<int32_t> tau_, count_;
+  int64_t t_y_ = 0;
+};
+
+// ---- layout -----------------------------------------------------------------------------------
+struct Layer {
+  int in, out;          // true extents
+  int ldw;              // row pitch of W in the padded layout (floats)
+  int64_t w_off, b_off; // offsets inside one replica of the padded layout (floats)
+  int64_t w_flat, b_flat; // offsets inside the public flat layout
+};
+
+struct Layout {
+  int K = 0, L = 0, B = 0;
+  bool bf16 = false, raw = false;
+  int64_t d = 0, d_pad = 0;
+  std::vector<Layer> layers;
+  std::vector<int> ld;       // activation pitches ld[0..L]
+  bool need_a0 = false;
+  int nblk = 1;
+  // byte offsets into the workspace
+  size_t x = 0, g = 0, v = 0, S = 0, xt = 0, y = 0, gprev = 0, partials = 0, norms = 0, scale = 0,
+         loss_rows = 0, loss = 0, logits = 0, a0 = 0, total = 0;
+  std::vector<size_t> act, dz;  // act[l] for l = 1..L-1, dz[l] for l = 1..L (index l)
+  size_t es() const { return bf16 ? 2 : 4; }
+};
+
+int check_config(const lsam_config* c) {
+  if (!c) return fail(LSAM_EINVAL, "config is NULL");
+  if (c->K < 1 || c->K > LSAM_MAX_REPLICAS)
+    return fail(LSAM_EINVAL, "K=%d outside 1..%d", c->K, LSAM_MAX_REPLICAS);
+  if (c->n_layers < 0 || c->n_layers > LSAM_MAX_LAYERS)
+    return fail(LSAM_EINVAL, "n_layers=%d outside 0..%d", c->n_layers, LSAM_MAX_LAYERS);
+  if (c->n_layers == 0) {
+    if (c->d_raw < 1) return fail(LSAM_EINVAL, "raw-vector mode needs d_raw >= 1");
+  } else {
+    if (!c->dims) return fail(LSAM_EINVAL, "dims is NULL");
+    for (int l = 0; l <= c->n_layers; ++l)
+      if (c->dims[l] < 1) return fail(LSAM_EINVAL, "dims[%d]=%d must be >= 1", l, c->dims[l]);
+    if (c->batch < 1) return fail(LSAM_EINVAL, "batch must be >= 1");
+    if ((int64_t)c->K * c->batch > (1 << 24)) return fail(LSAM_EINVAL, "K*batch too large");
+    if (c->gemm_dtype != LSAM_GEMM_FP32 && c->gemm_dtype != LSAM_GEMM_BF16)
+      return fail(LSAM_EINVAL, "gemm_dtype must be 0 (fp32) or 1 (bf16)");
+  }
+  if (!(c->rho >= 0.f) || !(c->gamma >= 0.f)) return fail(LSAM_EINVAL, "rho, gamma must be >= 0");
+  if (!(c->lr > 0.f) && c->lambda_abs < 0.f)
+    return fail(LSAM_EINVAL, "lr must be > 0 when lambda is derived as lambda0/(lr*tau)");
+  if (!(c->lr >= 0.f)) return fail(LSAM_EINVAL, "lr must be >= 0");
+  if (!(c->momentum >= 0.f && c->momentum < 1.f))
+    return fail(LSAM_EINVAL, "momentum must be in [0,1)");
+  if (!std::isfinite(c->beta) || !std::isfinite(c->lr_center) || !std::isfinite(c->lambda0))
+    return fail(LSAM_EINVAL, "beta, lr_center, lambda0 must be finite");
+  if (c->tau) {
+    for (int i = 0; i < c->K; ++i)
+      if (c->tau[i] < 1) return fail(LSAM_EINVAL, "tau[%d]=%d must be >= 1", i, c->tau[i]);
+  } else {
+    if (c->tau_min < 1 || c->tau_max < c->tau_min)
+      return fail(LSAM_EINVAL, "need 1 <= tau_min <= tau_max");
+  }
+  if (c->sched_mode != LSAM_SCHED_FIXED && c->sched_mode != LSAM_SCHED_REDRAW)
+    return fail(LSAM_EINVAL, "sched_mode must be 0 or 1");
+  return LSAM_OK;
+}
+
+size_t take(size_t& cursor, size_t bytes) {
+  const size_t at = cursor;
+  cursor = (size_t)round_up((int64_t)(cursor + bytes), 256);
+  return at;
+}
+
+void build_layout(const lsam_config& c, Layout& lo) {
+  lo.K = c.K;
+  lo.L = c.n_layers;
+  lo.raw = c.n_layers == 0;
+  lo.B = lo.raw ? 0 : c.batch;
+  lo.bf16 = !lo.raw && c.gemm_dtype == LSAM_GEMM_BF16;
+  int64_t off = 0, flat = 0;
+  if (lo.raw) {
+    lo.d = c.d_raw;
+    lo.d_pad = round_up(c.d_raw, 64);
+  } else {
+    lo.ld.resize(lo.L + 1);
+    for (int l = 0; l <= lo.L; ++l) lo.ld[l] = (int)round_up(c.dims[l], 8);
+    lo.need_a0 = (c.dims[0] % 8) != 0;
+    for (int l = 0; l < lo.L; ++l) {
+      Layer s;
+      s.in = c.dims[l];
+      s.out = c.dims[l + 1];
+      s.ldw = lo.ld[l];
+      s.w_off = off;
+      off = round_up(off + (int64_t)s.out * s.ldw, 64);
+      s.b_off = off;
+      off = round_up(off + s.out, 64);
+      s.w_flat = flat;
+      flat += (int64_t)s.out * s.in;
+      s.b_flat = flat;
+      flat += s.out;
+      lo.layers.push_back(s);
+    }
+    lo.d = flat;
+    lo.d_pad = off;
+  }
+  int64_t nb = (lo.d_pad + 65535) / 65536;
+  lo.nblk = (int)(nb < 1 ? 1 : (nb > 1024 ? 1024 : nb));
+
+  size_t cur = 0;
+  const size_t vec = (size_t)lo.K * lo.d_pad * 4;
+  lo.x = take(cur, vec);
+  lo.v = take(cur, vec);
+  lo.S = take(cur, vec);
+  lo.g = lo.raw ? 0 : take(cur, vec);
+  lo.xt = take(cur, lo.bf16 ? vec / 2 : vec);
+  lo.y = take(cur, (size_t)lo.d_pad * 4);
+  lo.gprev = take(cur, (size_t)lo.d_pad * 4);
+  lo.partials = take(cur, (size_t)lo.K * lo.nblk * 8);
+  lo.norms = take(cur, (size_t)lo.K * 4);
+  lo.scale = take(cur, (size_t)lo.K * 4);
+  lo.loss = take(cur, (size_t)lo.K * 4);
+  if (!lo.raw) {
+    const size_t rows = (size_t)lo.K * lo.B;
+    lo.loss_rows = take(cur, rows * 4);
+    lo.act.assign(lo.L + 1, 0);
+    lo.dz.assign(lo.L + 1, 0);
+    for (int l = 1; l < lo.L; ++l) lo.act[l] = take(cur, rows * lo.ld[l] * lo.es());
+    for (int l = 1; l <= lo.L; ++l) lo.dz[l] = take(cur, rows * lo.ld[l] * lo.es());
+    lo.logits = take(cur, rows * lo.ld[lo.L] * 4);
+    if (lo.need_a0) lo.a0 = take(cur, rows * lo.ld[0] * lo.es());
+  }
+  lo.total = cur;
+}
+
+// ---- per-kernel timing ---------------------------------------------------------------------------
+enum KernelClass {
+  KC_GEMM_FWD = 0, KC_GEMM_DX, KC_GEMM_DW, KC_SOFTMAX_CE, KC_BIAS_GRAD, KC_SUMSQ, KC_NORM_FINISH,
+  KC_PERTURB, KC_DESCENT, KC_CENTER, KC_MISC, KC_COUNT
+};
+const char* const kClassNames[KC_COUNT] = {
+    "gemm_fwd", "gemm_dx", "gemm_dw", "softmax_ce", "bias_grad", "sumsq_partials", "norm_finish",
+    "perturb", "descent", "center", "misc"};
+
+struct TimedLaunch {
+  int cls;
+  hipEvent_t a, b;
+};
+
+}  // namespace
+}  // namespace lsam
+
+using namespace lsam;
+
+struct lsam_ctx {
+  lsam_config cfg;
+  std::vector<int32_t> dims, tau_explicit;
+  Layout lo;
+  Schedule sched;
+  char* ws = nullptr;
+  hipStream_t stream = nullptr;
+  float lr = 0.f, rho = 0.f;
+  // timing
+  bool timing = false;
+  std::vector<TimedLaunch> pending;
+  std::vector<hipEvent_t> free_events;
+  int64_t t_count[KC_COUNT] = {0};
+  double t_ms[KC_COUNT] = {0};
+
+  template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+};
+
+namespace {
+
+struct LaunchTimer {
+  lsam_ctx* c;
+  TimedLaunch t;
+  bool on;
+  LaunchTimer(lsam_ctx* ctx, int cls) : c(ctx), on(ctx->timing) {
+    if (!on) return;
+    t.cls = cls;
+    t.a = grab();
+    t.b = grab();
+    if (t.a == nullptr || t.b == nullptr) { on = false; return; }
+    (void)hipEventRecord(t.a, c->stream);
+  }
+  ~LaunchTimer() {
+    if (!on) return;
+    (void)hipEventRecord(t.b, c->stream);
+    c->pending.push_back(t);
+  }
+  hipEvent_t grab() {
+    if (!c->free_events.empty()) {
+      hipEvent_t e = c->free_events.back();
+      c->free_events.pop_back();
+      return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+};
+
+int drain_timing(lsam_ctx* c) {
+  if (c->pending.empty()) return LSAM_OK;
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  for (auto& t : c->pending) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, t.a, t.b) == hipSuccess) {
+      c->t_ms[t.cls] += ms;
+      c->t_count[t.cls] += 1;
+    }
+    c->free_events.push_back(t.a);
+    c->free_events.push_back(t.b);
+  }
+  c->pending.clear();
+  return LSAM_OK;
+}
+
+int check_launch(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(LSAM_EHIP, "launch of %s failed: %s", what, hipGetErrorString(e));
+  return LSAM_OK;
+}
+
+float coupling(const lsam_ctx* c, int i) {
+  if (c->cfg.lambda_abs >= 0.f) return c->cfg.lambda_abs;
+  return (float)((double)c->cfg.lambda0 / ((double)c->lr * (double)c->sched.tau()[i]));
+}
+
+// forward + backward of all replicas; weights taken from `wts` (fp32 or bf16 per mode).
+// `second` selects the pass at the perturbed point: its biases are x_b + scale * g1_b, which in
+// fp32 mode sit in the perturbed copy and in bf16 mode are formed in the GEMM epilogue from
+// the fp32 master bias and the first-pass bias gradient (only matrix operands are rounded).
+int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const void* wts,
+                     bool second) {
+  const bool want_loss = !second;
+  const Layout& lo = c->lo;
+  const int K = lo.K, B = lo.B, L = lo.L;
+  const size_t es = lo.es();
+  hipStream_t s = c->stream;
+  auto wptr = [&](int64_t off) { return (const char*)wts + (size_t)off * es; };
+
+  for (int l = 0; l < L; ++l) {
+    const Layer& ly = lo.layers[l];
+    const bool last = l == L - 1;
+    GemmDesc d{};
+    d.A = l == 0 ? A0 : c->at<char>(lo.act[l]);
+    d.strideA = (int64_t)B * lo.ld[l]; d.ldA = lo.ld[l]; d.a_kmajor = 1;
+    d.B = wptr(ly.w_off); d.strideB = lo.d_pad; d.ldB = ly.ldw; d.b_kmajor = 1;
+    d.C = last ? c->at<char>(lo.logits) : c->at<char>(lo.act[l + 1]);
+    d.strideC = (int64_t)B * lo.ld[l + 1]; d.ldC = lo.ld[l + 1];
+    d.M = B; d.N = ly.out; d.Kd = ly.in; d.batch = K;
+    d.in_bf16 = lo.bf16; d.out_bf16 = lo.bf16 && !last;
+    d.epilogue = last ? EPI_BIAS : EPI_BIAS_RELU;
+    d.bias = c->at<float>(lo.x) + ly.b_off; d.strideBias = lo.d_pad;
+    if (second && !lo.bf16) d.bias = c->at<float>(lo.xt) + ly.b_off;
+    if (second && lo.bf16) {
+      d.bias_dir = c->at<float>(lo.g) + ly.b_off;
+      d.bias_scale = c->at<float>(lo.scale);
+    }
+    LaunchTimer t(c, KC_GEMM_FWD);
+    if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "forward GEMM of layer %d rejected", l);
+  }
+  {
+    LaunchTimer t(c, KC_SOFTMAX_CE);
+    launch_softmax_ce(c->at<float>(lo.logits), lo.ld[L], labels, c->at<char>(lo.dz[L]), lo.ld[L],
+                      lo.bf16, want_loss ? c->at<float>(lo.loss_rows) : nullptr, K, B,
+                      lo.layers[L - 1].out, s);
+  }
+  float* g = c->at<float>(lo.g);
+  for (int l = L - 1; l >= 0; --l) {
+    const Layer& ly = lo.layers[l];
+    const char* dz = c->at<char>(lo.dz[l + 1]);
+    const int ld_dz = lo.ld[l + 1];
+    const void* act = l == 0 ? A0 : (const void*)c->at<char>(lo.act[l]);
+    {
+      GemmDesc d{};
+      d.A = dz; d.strideA = (int64_t)B * ld_dz; d.ldA = ld_dz; d.a_kmajor = 0;
+      d.B = act; d.strideB = (int64_t)B * lo.ld[l]; d.ldB = lo.ld[l]; d.b_kmajor = 0;
+      d.C = g + ly.w_off; d.strideC = lo.d_pad; d.ldC = ly.ldw;
+      d.M = ly.out; d.N = ly.in; d.Kd = B; d.batch = K;
+      d.in_bf16 = lo.bf16; d.out_bf16 = 0; d.epilogue = EPI_PLAIN;
+      LaunchTimer t(c, KC_GEMM_DW);
+      if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "dW GEMM of layer %d rejected", l);
+    }
+    {
+      LaunchTimer t(c, KC_BIAS_GRAD);
+      launch_bias_grad(dz, ld_dz, lo.bf16, g + ly.b_off, lo.d_pad, K, B, ly.out, s);
+    }
+    if (l > 0) {
+      GemmDesc d{};
+      d.A = dz; d.strideA = (int64_t)B * ld_dz; d.ldA = ld_dz; d.a_kmajor = 1;
+      d.B = wptr(ly.w_off); d.strideB = lo.d_pad; d.ldB = ly.ldw; d.b_kmajor = 0;
+      d.C = c->at<char>(lo.dz[l]); d.strideC = (int64_t)B * lo.ld[l]; d.ldC = lo.ld[l];
+      d.M = B; d.N = ly.in; d.Kd = ly.out; d.batch = K;
+      d.in_bf16 = lo.bf16; d.out_bf16 = lo.bf16; d.epilogue = EPI_MASK;
+      d.mask = act; d.strideMask = (int64_t)B * lo.ld[l]; d.ldMask = lo.ld[l];
+      LaunchTimer t(c, KC_GEMM_DX);
+      if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "dX GEMM of layer %d rejected", l);
+    }
+  }
+  return check_launch("forward/backward");
+}
+
+int update_tail_first(lsam_ctx* c, const float* g1, int64_t g_stride, int64_t n, float* loss) {
+  const Layout& lo = c->lo;
+  hipStream_t s = c->stream;
+  {
+    LaunchTimer t(c, KC_SUMSQ);
+    launch_sumsq_partials(g1, g_stride, n, lo.K, c->at<double>(lo.partials), lo.nblk, s);
+  }
+  {
+    LaunchTimer t(c, KC_NORM_FINISH);
+    launch_norm_finish(c->at<double>(lo.partials), lo.nblk, lo.K, c->rho, c->cfg.gamma,
+                       c->at<float>(lo.norms), c->at<float>(lo.scale),
+                       lo.raw ? nullptr : c->at<float>(lo.loss_rows), lo.B,
+                       lo.raw ? nullptr : (loss ? loss : c->at<float>(lo.loss)), s);
+  }
+  {
+    LaunchTimer t(c, KC_PERTURB);
+    launch_perturb(c->at<float>(lo.x), g1, g_stride, c->at<float>(lo.scale),
+                   lo.bf16 ? nullptr : c->at<float>(lo.xt),
+                   lo.bf16 ? c->at<uint16_t>(lo.xt) : nullptr, lo.d_pad, n, lo.K, s);
+  }
+  return check_launch("norm/perturb");
+}
+
+int update_tail_second(lsam_ctx* c, const float* g2, int64_t g_stride, int64_t n) {
+  const Layout& lo = c->lo;
+  ReplicaScalars lam;
+  for (int i = 0; i < lo.K; ++i) lam.v[i] = coupling(c, i);
+  {
+    LaunchTimer t(c, KC_DESCENT);
+    launch_descent(c->at<float>(lo.x), g2, g_stride, c->at<float>(lo.v), c->at<float>(lo.S),
+                   c->at<float>(lo.y), lo.bf16 ? c->at<uint16_t>(lo.xt) : nullptr, lo.d_pad, n,
+                   lo.K, lam, c->lr, c->cfg.momentum, c->cfg.nesterov, c->stream);
+  }
+  c->sched.tick();
+  return check_launch("descent");
+}
+
+// Copies between the public flat layout (host) and one padded replica vector (device).
+int copy_in(lsam_ctx* c, const float* src_flat, float* dst_dev) {
+  const Layout& lo = c->lo;
+  if (lo.raw) {
+    HIP_TRY(hipMemcpy(dst_dev, src_flat, (size_t)lo.d * 4, hipMemcpyHostToDevice));
+    return LSAM_OK;
+  }
+  for (const Layer& ly : lo.layers) {
+    HIP_TRY(hipMemcpy2D(dst_dev + ly.w_off, (size_t)ly.ldw * 4, src_flat + ly.w_flat,
+                        (size_t)ly.in * 4, (size_t)ly.in * 4, ly.out, hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(dst_dev + ly.b_off, src_flat + ly.b_flat, (size_t)ly.out * 4,
+                      hipMemcpyHostToDevice));
+  }
+  return LSAM_OK;
+}
+
+int copy_out(lsam_ctx* c, const float* src_dev, float* dst_flat) {
+  const Layout& lo = c->lo;
+  if (lo.raw) {
+    HIP_TRY(hipMemcpy(dst_flat, src_dev, (size_t)lo.d * 4, hipMemcpyDeviceToHost));
+    return LSAM_OK;
+  }
+  for (const Layer& ly : lo.layers) {
+    HIP_TRY(hipMemcpy2D(dst_flat + ly.w_flat, (size_t)ly.in * 4, src_dev + ly.w_off,
+                        (size_t)ly.ldw * 4, (size_t)ly.in * 4, ly.out, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(dst_flat + ly.b_flat, src_dev + ly.b_off, (size_t)ly.out * 4,
+                      hipMemcpyDeviceToHost));
+  }
+  return LSAM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* lsam_last_error(void) { return g_err.c_str(); }
+
+int64_t lsam_num_params(const lsam_config* cfg) {
+  if (check_config(cfg) != LSAM_OK) return -1;
+  Layout lo;
+  build_layout(*cfg, lo);
+  return lo.d;
+}
+
+size_t lsam_workspace_bytes(const lsam_config* cfg) {
+  if (check_config(cfg) != LSAM_OK) return 0;
+  Layout lo;
+  build_layout(*cfg, lo);
+  return lo.total;
+}
+
+int lsam_schedule_replay(const lsam_config* cfg, int32_t n_ticks, int32_t* due_out,
+                         int32_t* tau_out) {
+  int rc = check_config(cfg);
+  if (rc != LSAM_OK) return rc;
+  if (n_ticks < 0 || (!due_out && !tau_out)) return fail(LSAM_EINVAL, "nothing to replay into");
+  Schedule s;
+  s.init(*cfg);
+  for (int t = 0; t < n_ticks; ++t) {
+    if (tau_out)
+      for (int i = 0; i < cfg->K; ++i) tau_out[(int64_t)t * cfg->K + i] = s.tau()[i];
+    s.tick();
+    DueList d = s.due();
+    if (due_out) {
+      for (int i = 0; i < cfg->K; ++i) due_out[(int64_t)t * cfg->K + i] = 0;
+      for (int j = 0; j < d.n; ++j) due_out[(int64_t)t * cfg->K + d.idx[j]] = 1;
+    }
+    if (d.n) s.served(d);
+  }
+  return LSAM_OK;
+}
+
+int lsam_init(const lsam_config* cfg, const float* init_params, int64_t n_init, void* workspace,
+              size_t workspace_bytes, void* stream, lsam_ctx** out) {
+  if (!out) return fail(LSAM_EINVAL, "out is NULL");
+  *out = nullptr;
+  int rc = check_config(cfg);
+  if (rc != LSAM_OK) return rc;
+  if (!init_params) return fail(LSAM_EINVAL, "init_params is NULL");
+  if (!workspace) return fail(LSAM_EINVAL, "workspace is NULL");
+  if (reinterpret_cast<uintptr_t>(workspace) & 255)
+    return fail(LSAM_EINVAL, "workspace must be 256-byte aligned");
+  lsam_ctx* c = new (std::nothrow) lsam_ctx();
+  if (!c) return fail(LSAM_ENOMEM, "host allocation failed");
+  c->cfg = *cfg;
+  if (cfg->n_layers > 0) {
+    c->dims.assign(cfg->dims, cfg->dims + cfg->n_layers + 1);
+    c->cfg.dims = c->dims.data();
+  } else {
+    c->cfg.dims = nullptr;
+  }
+  if (cfg->tau) {
+    c->tau_explicit.assign(cfg->tau, cfg->tau + cfg->K);
+    c->cfg.tau = c->tau_explicit.data();
+  }
+  build_layout(c->cfg, c->lo);
+  const Layout& lo = c->lo;
+  if (n_init != lo.d && n_init != (int64_t)(lo.K + 1) * lo.d) {
+    delete c;
+    return fail(LSAM_EINVAL, "n_init=%lld must be d=%lld or (K+1)*d", (long long)n_init,
+                (long long)lo.d);
+  }
+  if (workspace_bytes < lo.total) {
+    delete c;
+    return fail(LSAM_ENOMEM, "workspace holds %zu bytes, %zu needed", workspace_bytes, lo.total);
+  }
+  c->ws = static_cast<char*>(workspace);
+  c->stream = static_cast<hipStream_t>(stream);
+  c->lr = cfg->lr;
+  c->rho = cfg->rho;
+  c->sched.init(c->cfg);
+
+  auto bail = [&](int code) { delete c; return code; };
+  launch_fill_zero(c->ws, lo.total, c->stream);
+  if (check_launch("zero fill") != LSAM_OK) return bail(LSAM_EHIP);
+  if (hipStreamSynchronize(c->stream) != hipSuccess)
+    return bail(fail(LSAM_EHIP, "stream synchronize failed during init"));
+  float* x = c->at<float>(lo.x);
+  float* y = c->at<float>(lo.y);
+  if (n_init == lo.d) {
+    if ((rc = copy_in(c, init_params, y)) != LSAM_OK) return bail(rc);
+    launch_broadcast(y, x, lo.bf16 ? c->at<uint16_t>(lo.xt) : nullptr, lo.d_pad, lo.d_pad, lo.K,
+                     c->stream);
+  } else {
+    for (int i = 0; i < lo.K; ++i)
+      if ((rc = copy_in(c, init_params + (int64_t)i * lo.d, x + (int64_t)i * lo.d_pad)) != LSAM_OK)
+        return bail(rc);
+    if ((rc = copy_in(c, init_params + (int64_t)lo.K * lo.d, y)) != LSAM_OK) return bail(rc);
+    if (lo.bf16) launch_to_bf16(x, c->at<uint16_t>(lo.xt), (int64_t)lo.K * lo.d_pad, c->stream);
+  }
+  if (check_launch("parameter broadcast") != LSAM_OK) return bail(LSAM_EHIP);
+  if (hipStreamSynchronize(c->stream) != hipSuccess)
+    return bail(fail(LSAM_EHIP, "stream synchronize failed during init"));
+  *out = c;
+  return LSAM_OK;
+}
+
+int lsam_step(lsam_ctx* c, const void* X, const int32_t* labels, float* loss) {
+  if (!c) return fail(LSAM_EINVAL, "ctx is NULL");
+  if (c->lo.raw) return fail(LSAM_ESTATE, "lsam_step needs an MLP configuration");
+  if (!X || !labels) return fail(LSAM_EINVAL, "X or labels is NULL");
+  const Layout& lo = c->lo;
+  const void* A0 = X;
+  if (lo.need_a0) {
+    LaunchTimer t(c, KC_MISC);
+    launch_pad_rows(X, c->at<char>(lo.a0), (int64_t)lo.K * lo.B, lo.layers[0].in, lo.ld[0],
+                    (int)lo.es(), c->stream);
+    A0 = c->at<char>(lo.a0);
+  } else if (reinterpret_cast<uintptr_t>(X) & 15) {
+    return fail(LSAM_EINVAL, "X must be 16-byte aligned");
+  }
+  int rc;
+  const void* w1 = lo.bf16 ? (const void*)c->at<char>(lo.xt) : (const void*)c->at<char>(lo.x);
+  if ((rc = forward_backward(c, A0, labels, w1, false)) != LSAM_OK) return rc;
+  if ((rc = update_tail_first(c, c->at<float>(lo.g), lo.d_pad, lo.d_pad, loss)) != LSAM_OK)
+    return rc;
+  if ((rc = forward_backward(c, A0, labels, c->at<char>(lo.xt), true)) != LSAM_OK) return rc;
+  return update_tail_second(c, c->at<float>(lo.g), lo.d_pad, lo.d_pad);
+}
+
+int lsam_step_grads(lsam_ctx* c, const float* g1, const float* g2) {
+  if (!c) return fail(LSAM_EINVAL, "ctx is NULL");
+  if (!c->lo.raw) return fail(LSAM_ESTATE, "lsam_step_grads needs raw-vector mode");
+  if (!g1 || !g2) return fail(LSAM_EINVAL, "g1 or g2 is NULL");
+  if ((reinterpret_cast<uintptr_t>(g1) & 3) || (reinterpret_cast<uintptr_t>(g2) & 3))
+    return fail(LSAM_EINVAL, "gradients must be 4-byte aligned");
+  int rc;
+  if ((rc = update_tail_first(c, g1, c->lo.d, c->lo.d, nullptr)) != LSAM_OK) return rc;
+  return update_tail_second(c, g2, c->lo.d, c->lo.d);
+}
+
+int lsam_sync(lsam_ctx* c) {
+  if (!c) return fail(LSAM_EINVAL, "ctx is NULL");
+  const Layout& lo = c->lo;
+  const DueList due = c->sched.due();
+  if (due.n == 0) return 0;
+  const int64_t m = c->sched.samples(due);
+  {
+    LaunchTimer t(c, KC_CENTER);
+    launch_center(c->at<float>(lo.S), c->at<float>(lo.y), c->at<float>(lo.gprev), lo.d_pad,
+                  lo.raw ? lo.d : lo.d_pad, due, (float)(1.0 / (double)m), c->cfg.beta,
+                  c->cfg.lr_center, c->sched.t_y() > 0 ? 1 : 0, c->stream);
+  }
+  int rc = check_launch("center update");
+  if (rc != LSAM_OK) return rc;
+  c->sched.served(due);
+  return due.n;
+}
+
+int lsam_get_buffer(lsam_ctx* c, int32_t which, int32_t replica, float* dst, int64_t n) {
+  if (!c || !dst) return fail(LSAM_EINVAL, "ctx or dst is NULL");
+  const Layout& lo = c->lo;
+  if (n != lo.d) return fail(LSAM_EINVAL, "n=%lld must equal d=%lld", (long long)n, (long long)lo.d);
+  if (replica < -1 || replica >= lo.K) return fail(LSAM_EINVAL, "replica %d out of range", replica);
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  const int64_t roff = (int64_t)(replica < 0 ? 0 : replica) * lo.d_pad;
+  switch (which) {
+    case LSAM_BUF_PARAMS:
+      return copy_out(c, replica < 0 ? c->at<float>(lo.y) : c->at<float>(lo.x) + roff, dst);
+    case LSAM_BUF_CENTER_DIR:
+      return copy_out(c, c->at<float>(lo.gprev), dst);
+    default: break;
+  }
+  if (replica < 0) return fail(LSAM_EINVAL, "replica -1 is valid for the parameters only");
+  switch (which) {
+    case LSAM_BUF_VELOCITY: return copy_out(c, c->at<float>(lo.v) + roff, dst);
+    case LSAM_BUF_ITER_SUM: return copy_out(c, c->at<float>(lo.S) + roff, dst);
+    case LSAM_BUF_GRAD:
+      if (lo.raw) return fail(LSAM_ESTATE, "raw-vector mode keeps no gradient buffer");
+      return copy_out(c, c->at<float>(lo.g) + roff, dst);
+    case LSAM_BUF_PERTURBED: {
+      if (!lo.bf16) return copy_out(c, c->at<float>(lo.xt) + roff, dst);
+      // bf16 operand copy: fetch the padded vector, widen and un-pad on the host
+      std::vector<uint16_t> h((size_t)lo.d_pad);
+      HIP_TRY(hipMemcpy(h.data(), c->at<uint16_t>(lo.xt) + roff, (size_t)lo.d_pad * 2,
+                        hipMemcpyDeviceToHost));
+      auto widen = [&](int64_t i) {
+        const uint32_t u = (uint32_t)h[(size_t)i] << 16;
+        float f;
+        memcpy(&f, &u, 4);
+        return f;
+      };
+      for (const Layer& ly : lo.layers) {
+        for (int r = 0; r < ly.out; ++r)
+          for (int q = 0; q < ly.in; ++q)
+            dst[ly.w_flat + (int64_t)r * ly.in + q] = widen(ly.w_off + (int64_t)r * ly.ldw + q);
+        for (int r = 0; r < ly.out; ++r) dst[ly.b_flat + r] = widen(ly.b_off + r);
+      }
+      return LSAM_OK;
+    }
+    default: return fail(LSAM_EINVAL, "unknown buffer id %d", which);
+  }
+}
+
+int lsam_set_buffer(lsam_ctx* c, int32_t which, int32_t replica, const float* src, int64_t n) {
+  if (!c || !src) return fail(LSAM_EINVAL, "ctx or src is NULL");
+  const Layout& lo = c->lo;
+  if (n != lo.d) return fail(LSAM_EINVAL, "n=%lld must equal d=%lld", (long long)n, (long long)lo.d);
+  if (replica < -1 || replica >= lo.K) return fail(LSAM_EINVAL, "replica %d out of range", replica);
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  const int64_t roff = (int64_t)(replica < 0 ? 0 : replica) * lo.d_pad;
+  float* dst = nullptr;
+  switch (which) {
+    case LSAM_BUF_PARAMS: dst = replica < 0 ? c->at<float>(lo.y) : c->at<float>(lo.x) + roff; break;
+    case LSAM_BUF_CENTER_DIR: dst = c->at<float>(lo.gprev); break;
+    case LSAM_BUF_VELOCITY: dst = replica < 0 ? nullptr : c->at<float>(lo.v) + roff; break;
+    case LSAM_BUF_ITER_SUM: dst = replica < 0 ? nullptr : c->at<float>(lo.S) + roff; break;
+    default: return fail(LSAM_EINVAL, "buffer id %d cannot be set", which);
+  }
+  if (!dst) return fail(LSAM_EINVAL, "replica -1 is valid for the parameters only");
+  int rc = copy_in(c, src, dst);
+  if (rc != LSAM_OK) return rc;
+  if (which == LSAM_BUF_PARAMS && replica >= 0 && lo.bf16) {
+    launch_to_bf16(dst, c->at<uint16_t>(lo.xt) + roff, lo.d_pad, c->stream);
+    if ((rc = check_launch("bf16 operand refresh")) != LSAM_OK) return rc;
+    HIP_TRY(hipStreamSynchronize(c->stream));
+  }
+  return LSAM_OK;
+}
+
+int lsam_get_params(lsam_ctx* c, int32_t replica, float* dst, int64_t n) {
+  return lsam_get_buffer(c, LSAM_BUF_PARAMS, replica, dst, n);
+}
+
+int lsam_get_norms(lsam_ctx* c, float* dst) {
+  if (!c || !dst) return fail(LSAM_EINVAL, "ctx or dst is NULL");
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  HIP_TRY(hipMemcpy(dst, c->at<float>(c->lo.norms), (size_t)c->lo.K * 4, hipMemcpyDeviceToHost));
+  return LSAM_OK;
+}
+
+int lsam_get_schedule(lsam_ctx* c, int32_t* tau_out, int32_t* count_out, int64_t* t_y_out) {
+  if (!c) return fail(LSAM_EINVAL, "ctx is NULL");
+  for (int i = 0; i < c->lo.K; ++i) {
+    if (tau_out) tau_out[i] = c->sched.tau()[i];
+    if (count_out) count_out[i] = c->sched.count()[i];
+  }
+  if (t_y_out) *t_y_out = c->sched.t_y();
+  return LSAM_OK;
+}
+
+int lsam_set_scalars(lsam_ctx* c, float lr, float rho) {
+  if (!c) return fail(LSAM_EINVAL, "ctx is NULL");
+  if (!(rho >= 0.f) || !(lr >= 0.f)) return fail(LSAM_EINVAL, "lr and rho must be >= 0");
+  if (!(lr > 0.f) && c->cfg.lambda_abs < 0.f)
+    return fail(LSAM_EINVAL, "lr must be > 0 when lambda is derived as lambda0/(lr*tau)");
+  c->lr = lr;
+  c->rho = rho;
+  return LSAM_OK;
+}
+
+int lsam_timing_enable(lsam_ctx* c, int32_t on) {
+  if (!c) return fail(LSAM_EINVAL, "ctx is NULL");
+  int rc = drain_timing(c);
+  if (rc != LSAM_OK) return rc;
+  c->timing = on != 0;
+  if (!on) {
+    for (int i = 0; i < KC_COUNT; ++i) { c->t_count[i] = 0; c->t_ms[i] = 0.0; }
+  }
+  return LSAM_OK;
+}
+
+int lsam_timing_read(lsam_ctx* c, int32_t cap, const char** names, int64_t* counts,
+                     double* total_ms) {
+  if (!c || !names || !counts || !total_ms) return fail(LSAM_EINVAL, "NULL argument");
+  int rc = drain_timing(c);
+  if (rc != LSAM_OK) return rc;
+  int n = 0;
+  for (int i = 0; i < KC_COUNT && n < cap; ++i) {
+    names[n] = kClassNames[i];
+    counts[n] = c->t_count[i];
+    total_ms[n] = c->t_ms[i];
+    ++n;
+  }
+  return n;
+}
+
+void lsam_destroy(lsam_ctx* c) {
+  if (!c) return;
+  (void)hipStreamSynchronize(c->stream);
+  for (auto& t : c->pending) { (void)hipEventDestroy(t.a); (void)hipEventDestroy(t.b); }
+  for (auto e : c->free_events) (void)hipEventDestroy(e);
+  delete c;
+}
+
+}  // extern "C"

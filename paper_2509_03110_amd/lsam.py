@@ -1,0 +1,246 @@
+"""ctypes binding of liblsam.so: the same entry points as include/lsam.h, argument
+marshalling only.  PyTorch appears here solely as the owner of device memory and of the
+HIP stream; every step of the method runs in the library's kernels.
+
+The library must have been built (python -m paper_2509_03110_amd.build); loading fails
+loudly otherwise -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblsam.so")
+
+OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4
+GEMM_FP32, GEMM_BF16 = 0, 1
+SCHED_FIXED, SCHED_REDRAW = 0, 1
+BUF_PARAMS, BUF_VELOCITY, BUF_ITER_SUM, BUF_GRAD, BUF_PERTURBED, BUF_CENTER_DIR = range(6)
+
+EXPORTS = [
+    "lsam_workspace_bytes", "lsam_init", "lsam_step", "lsam_step_grads", "lsam_sync",
+    "lsam_get_params", "lsam_get_buffer", "lsam_set_buffer", "lsam_get_norms", "lsam_get_schedule",
+    "lsam_set_scalars", "lsam_num_params", "lsam_schedule_replay", "lsam_timing_enable",
+    "lsam_timing_read", "lsam_destroy", "lsam_last_error",
+]
+
+
+class lsam_config(C.Structure):
+    _fields_ = [
+        ("K", C.c_int32), ("n_layers", C.c_int32), ("dims", C.POINTER(C.c_int32)),
+        ("d_raw", C.c_int64), ("batch", C.c_int32), ("gemm_dtype", C.c_int32),
+        ("rho", C.c_float), ("gamma", C.c_float), ("lr", C.c_float), ("lr_center", C.c_float),
+        ("momentum", C.c_float), ("beta", C.c_float), ("lambda0", C.c_float),
+        ("lambda_abs", C.c_float), ("nesterov", C.c_int32), ("tau", C.POINTER(C.c_int32)),
+        ("tau_min", C.c_int32), ("tau_max", C.c_int32), ("sched_seed", C.c_uint64),
+        ("sched_mode", C.c_int32),
+    ]
+
+
+class LsamError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("lsam error %d: %s" % (code, msg))
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("%s is missing: run `python -m paper_2509_03110_amd.build`" % LIB_PATH)
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+        cfgp = C.POINTER(lsam_config)
+        L.lsam_workspace_bytes.restype = C.c_size_t
+        L.lsam_workspace_bytes.argtypes = [cfgp]
+        L.lsam_num_params.restype = i64
+        L.lsam_num_params.argtypes = [cfgp]
+        L.lsam_init.restype = C.c_int
+        L.lsam_init.argtypes = [cfgp, vp, i64, vp, C.c_size_t, vp, C.POINTER(vp)]
+        L.lsam_step.restype = C.c_int
+        L.lsam_step.argtypes = [vp, vp, vp, vp]
+        L.lsam_step_grads.restype = C.c_int
+        L.lsam_step_grads.argtypes = [vp, vp, vp]
+        L.lsam_sync.restype = C.c_int
+        L.lsam_sync.argtypes = [vp]
+        L.lsam_get_params.restype = C.c_int
+        L.lsam_get_params.argtypes = [vp, i32, vp, i64]
+        L.lsam_get_buffer.restype = C.c_int
+        L.lsam_get_buffer.argtypes = [vp, i32, i32, vp, i64]
+        L.lsam_set_buffer.restype = C.c_int
+        L.lsam_set_buffer.argtypes = [vp, i32, i32, vp, i64]
+        L.lsam_get_norms.restype = C.c_int
+        L.lsam_get_norms.argtypes = [vp, vp]
+        L.lsam_get_schedule.restype = C.c_int
+        L.lsam_get_schedule.argtypes = [vp, vp, vp, vp]
+        L.lsam_set_scalars.restype = C.c_int
+        L.lsam_set_scalars.argtypes = [vp, C.c_float, C.c_float]
+        L.lsam_schedule_replay.restype = C.c_int
+        L.lsam_schedule_replay.argtypes = [cfgp, i32, vp, vp]
+        L.lsam_timing_enable.restype = C.c_int
+        L.lsam_timing_enable.argtypes = [vp, i32]
+        L.lsam_timing_read.restype = C.c_int
+        L.lsam_timing_read.argtypes = [vp, i32, vp, vp, vp]
+        L.lsam_destroy.restype = None
+        L.lsam_destroy.argtypes = [vp]
+        L.lsam_last_error.restype = C.c_char_p
+        L.lsam_last_error.argtypes = []
+        _lib = L
+    return _lib
+
+
+def last_error() -> str:
+    return lib().lsam_last_error().decode()
+
+
+def _check(rc):
+    if rc < 0:
+        raise LsamError(rc, last_error())
+    return rc
+
+
+def make_config(K, dims=(), d_raw=0, batch=0, gemm_dtype=GEMM_FP32, rho=0.05, gamma=1e-12,
+                lr=0.1, lr_center=1.0, momentum=0.9, beta=0.9, lambda0=0.5, lambda_abs=-1.0,
+                nesterov=1, tau=None, tau_min=1, tau_max=1, sched_seed=0,
+                sched_mode=SCHED_FIXED):
+    """Fills an lsam_config; returns (config, keepalive) -- keep `keepalive` referenced while
+    the config is in use (it owns the dims / tau arrays the struct points to)."""
+    cfg = lsam_config()
+    keep = []
+    cfg.K = K
+    cfg.n_layers = max(len(dims) - 1, 0)
+    if len(dims):
+        arr = (C.c_int32 * len(dims))(*dims)
+        keep.append(arr)
+        cfg.dims = C.cast(arr, C.POINTER(C.c_int32))
+    cfg.d_raw = d_raw
+    cfg.batch = batch
+    cfg.gemm_dtype = gemm_dtype
+    cfg.rho, cfg.gamma, cfg.lr, cfg.lr_center = rho, gamma, lr, lr_center
+    cfg.momentum, cfg.beta, cfg.lambda0, cfg.lambda_abs = momentum, beta, lambda0, lambda_abs
+    cfg.nesterov = nesterov
+    if tau is not None:
+        t = (C.c_int32 * len(tau))(*tau)
+        keep.append(t)
+        cfg.tau = C.cast(t, C.POINTER(C.c_int32))
+    cfg.tau_min, cfg.tau_max = tau_min, tau_max
+    cfg.sched_seed, cfg.sched_mode = sched_seed, sched_mode
+    return cfg, keep
+
+
+def config_from_workload(w, **over):
+    kw = dict(K=w.K, dims=w.dims, d_raw=w.d_raw, batch=w.batch, gemm_dtype=w.gemm_dtype,
+              rho=w.rho, gamma=w.gamma, lr=w.lr, lr_center=w.lr_center, momentum=w.momentum,
+              beta=w.beta, lambda0=w.lambda0, lambda_abs=w.lambda_abs, nesterov=w.nesterov,
+              tau=w.tau, tau_min=w.tau_min, tau_max=w.tau_max, sched_seed=w.sched_seed,
+              sched_mode=w.sched_mode)
+    kw.update(over)
+    return make_config(**kw)
+
+
+def lsam_workspace_bytes(cfg) -> int:
+    return lib().lsam_workspace_bytes(C.byref(cfg))
+
+
+def lsam_num_params(cfg) -> int:
+    return lib().lsam_num_params(C.byref(cfg))
+
+
+def lsam_schedule_replay(cfg, n_ticks):
+    due = np.zeros((n_ticks, cfg.K), dtype=np.int32)
+    tau = np.zeros((n_ticks, cfg.K), dtype=np.int32)
+    _check(lib().lsam_schedule_replay(C.byref(cfg), n_ticks, due.ctypes.data, tau.ctypes.data))
+    return due, tau
+
+
+class Lsam:
+    """Owns one lsam_ctx plus the torch tensor that backs its workspace."""
+
+    def __init__(self, cfg, init_params, device="cuda:0", stream=None, keep=None):
+        import torch
+        self._keep = keep
+        self.cfg = cfg
+        self.K = cfg.K
+        self.d = lsam_num_params(cfg)
+        nbytes = lsam_workspace_bytes(cfg)
+        if nbytes == 0:
+            raise LsamError(EINVAL, last_error())
+        self.device = torch.device(device)
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+        base = self.workspace.data_ptr()
+        self._ws_ptr = (base + 255) // 256 * 256
+        self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        init = np.ascontiguousarray(init_params, dtype=np.float32).ravel()
+        h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            _check(lib().lsam_init(C.byref(cfg), init.ctypes.data, init.size, self._ws_ptr, nbytes,
+                                   self.stream.cuda_stream, C.byref(h)))
+        self._h = h
+
+    def lsam_step(self, X, labels, loss=None):
+        return _check(lib().lsam_step(self._h, X.data_ptr(), labels.data_ptr(),
+                                      None if loss is None else loss.data_ptr()))
+
+    def lsam_step_grads(self, g1, g2):
+        return _check(lib().lsam_step_grads(self._h, g1.data_ptr(), g2.data_ptr()))
+
+    def lsam_sync(self):
+        return _check(lib().lsam_sync(self._h))
+
+    def lsam_get_params(self, replica):
+        out = np.empty(self.d, dtype=np.float32)
+        _check(lib().lsam_get_params(self._h, replica, out.ctypes.data, out.size))
+        return out
+
+    def lsam_get_buffer(self, which, replica):
+        out = np.empty(self.d, dtype=np.float32)
+        _check(lib().lsam_get_buffer(self._h, which, replica, out.ctypes.data, out.size))
+        return out
+
+    def lsam_set_buffer(self, which, replica, src):
+        a = np.ascontiguousarray(src, dtype=np.float32).ravel()
+        return _check(lib().lsam_set_buffer(self._h, which, replica, a.ctypes.data, a.size))
+
+    def lsam_get_norms(self):
+        out = np.empty(self.K, dtype=np.float32)
+        _check(lib().lsam_get_norms(self._h, out.ctypes.data))
+        return out
+
+    def lsam_get_schedule(self):
+        tau = np.zeros(self.K, dtype=np.int32)
+        cnt = np.zeros(self.K, dtype=np.int32)
+        ty = C.c_int64(0)
+        _check(lib().lsam_get_schedule(self._h, tau.ctypes.data, cnt.ctypes.data, C.byref(ty)))
+        return tau.tolist(), cnt.tolist(), ty.value
+
+    def lsam_set_scalars(self, lr, rho):
+        return _check(lib().lsam_set_scalars(self._h, lr, rho))
+
+    def lsam_timing_enable(self, on):
+        return _check(lib().lsam_timing_enable(self._h, 1 if on else 0))
+
+    def lsam_timing_read(self):
+        cap = 32
+        names = (C.c_char_p * cap)()
+        counts = (C.c_int64 * cap)()
+        ms = (C.c_double * cap)()
+        n = _check(lib().lsam_timing_read(self._h, cap, names, counts, ms))
+        return {names[i].decode(): (counts[i], ms[i]) for i in range(n)}
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().lsam_destroy(self._h)
+            self._h = None
+            self.workspace = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,241 @@
+"""GPU parity: the HIP path, called through the C boundary, against the CPU oracle on the
+same seeded inputs.  Integer state (periods, counters, due sets) must be bit-exact; fp32
+parameters within relative 1e-4 after one step and 1e-3 over the run (bf16-operand
+configurations within 2e-2), measured as max-abs difference over max-abs value and as
+relative L2 error, per replica."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from paper_2509_03110_amd import lsam
+from util import close_enough, oracle_from, rel_l2, rel_max
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def make_pair(w, init=None):
+    init = workloads.init_params(w) if init is None else init
+    cfg, keep = lsam.config_from_workload(w)
+    return lsam.Lsam(cfg, init, device=DEV, keep=keep), oracle_from(w, init)
+
+
+def to_dev(X, labels, w):
+    Xd = torch.from_numpy(X).to(DEV)
+    if w.gemm_dtype == 1:
+        Xd = Xd.to(torch.bfloat16)
+    return Xd.contiguous(), torch.from_numpy(labels).to(DEV)
+
+
+def check_state(g, o, tol, what, tol_v=None):
+    """Parameters, velocities and iterate sums of every replica plus the center, and the
+    integer schedule state (bit-exact)."""
+    worst = 0.0
+    for i in list(range(o.K)) + [-1]:
+        a, b = g.lsam_get_params(i), o.get_params(i)
+        worst = max(worst, close_enough(a, b, tol, "%s: params of replica %d" % (what, i)))
+    for i in range(o.K):
+        for which, ref, name, t in ((lsam.BUF_VELOCITY, o.v[i], "v", tol_v or tol),
+                                    (lsam.BUF_ITER_SUM, o.S[i], "S", tol)):
+            a = g.lsam_get_buffer(which, i)
+            if np.max(np.abs(ref)) == 0.0:
+                assert np.max(np.abs(a)) == 0.0
+                continue
+            close_enough(a, ref, t, "%s: %s of replica %d" % (what, name, i))
+    tau, cnt, ty = g.lsam_get_schedule()
+    otau, ocnt, oty = o.get_schedule()
+    assert (tau, cnt, ty) == (otau, ocnt, oty), what
+    return worst
+
+
+def anchor(g, o):
+    """Restarts the GPU from the oracle's current state (rounded to fp32), so that the next
+    step is compared from a common starting point."""
+    for i in range(o.K):
+        g.lsam_set_buffer(lsam.BUF_PARAMS, i, o.x[i])
+        g.lsam_set_buffer(lsam.BUF_VELOCITY, i, o.v[i])
+        g.lsam_set_buffer(lsam.BUF_ITER_SUM, i, o.S[i])
+    g.lsam_set_buffer(lsam.BUF_PARAMS, -1, o.y)
+    if o.gprev is not None:
+        g.lsam_set_buffer(lsam.BUF_CENTER_DIR, -1, o.gprev)
+
+
+def run_mlp(w, steps, tol1, tol_run, check_every=1, margin=False, tol_flip=5e-2,
+            anchor_after=None):
+    """Runs GPU and oracle side by side.
+
+    margin=True starts from parameters whose hidden pre-activations are far from zero, so no
+    ReLU decision can differ between fp32 and float64: then gradients, velocities, sums and
+    parameters must all agree to the tight tolerance, layer by layer.  With the natural
+    initialisation a pre-activation within rounding distance of zero flips now and then
+    (about one unit per replica-step at the cfg2 shape), each flip moving the gradient by
+    ~1/sqrt(B*width) of its norm; parameters still have to meet the tight bound, velocities
+    and gradients the looser tol_flip.  Flips also make two free-running trajectories drift
+    apart (the dynamics amplify each one), so from step `anchor_after` on the GPU state is
+    reset to the oracle's before every step and each step is held to the one-step bound tol1."""
+    if margin:
+        w = w.scaled(lr=0.01)     # slow enough that the margin survives the whole run
+    init = workloads.init_params_margin(w) if margin else workloads.init_params(w)
+    g, o = make_pair(w, init)
+    tol_v = None if margin else tol_flip
+    loss_d = torch.zeros(w.K, dtype=torch.float32, device=DEV)
+    worst = 0.0
+    for t in range(steps):
+        anchored = anchor_after is not None and t >= anchor_after
+        if anchored:
+            anchor(g, o)
+        X, lab = workloads.batch(w, t)
+        Xd, ld = to_dev(X, lab, w)
+        g.lsam_step(Xd, ld, loss_d)
+        ol = o.step(X, lab)
+        if margin:
+            assert o.model.last_margin > 1e-3, "margin initialisation lost its margin"
+        gl = loss_d.cpu().numpy()
+        assert np.allclose(gl, ol, rtol=max(tol_run, 1e-5), atol=1e-6), (t, gl, ol)
+        if t == 0:
+            norms = g.lsam_get_norms()
+            assert np.allclose(norms, o.last_norm, rtol=(tol1 if margin else tol_flip)), (norms, o.last_norm)
+            for i in range(w.K):
+                g2 = g.lsam_get_buffer(lsam.BUF_GRAD, i)
+                if margin:
+                    for l, (o0, o1, o2) in enumerate(o.model.offsets):
+                        close_enough(g2[o0:o1], o.last_g2[i][o0:o1], tol1, "dW%d of replica %d" % (l + 1, i))
+                        close_enough(g2[o1:o2], o.last_g2[i][o1:o2], tol1, "db%d of replica %d" % (l + 1, i))
+                else:
+                    close_enough(g2, o.last_g2[i], tol_flip, "g2 of replica %d" % i)
+        ng, no = g.lsam_sync(), o.sync()
+        assert ng == no, (t, ng, no)
+        if t == 0:
+            check_state(g, o, tol1, "%s step 1" % w.name, tol_v)
+        elif (t + 1) % check_every == 0 or t == steps - 1:
+            tol = tol1 if anchored else tol_run
+            e = check_state(g, o, tol, "%s step %d" % (w.name, t + 1), tol_v)
+            print("%s margin=%s step %d: worst parameter error %.3e" % (w.name, margin, t + 1, e))
+            worst = max(worst, e)
+    g.close()
+    return worst
+
+
+# ---- raw-vector mode: norm + perturb + descent + center ----------------------------------------
+@pytest.mark.parametrize("d,K,tau", [(1000, 3, (2, 3, 4)), (4099, 2, (1, 2)), (65536 * 3 + 64, 4, None),
+                                     (7, 1, (1,))])
+@pytest.mark.parametrize("nesterov", [1, 0])
+def test_raw_mode_matches_oracle(d, K, tau, nesterov):
+    w = workloads.WORKLOADS["cfg4"].scaled(K=K, d_raw=d, tau=tau, nesterov=nesterov, steps=12,
+                                           grad_std=1e-2)
+    g, o = make_pair(w)
+    for t in range(w.steps):
+        g1, g2 = workloads.raw_grads(w, t)
+        g.lsam_step_grads(torch.from_numpy(g1).to(DEV), torch.from_numpy(g2).to(DEV))
+        o.step_grads(g1, g2)
+        norms = g.lsam_get_norms()
+        assert np.allclose(norms, o.last_norm, rtol=1e-5)
+        for i in range(K):
+            xt = g.lsam_get_buffer(lsam.BUF_PERTURBED, i)
+            assert rel_max(xt, o.last_perturbed[i]) < 1e-6
+        assert g.lsam_sync() == o.sync()
+        check_state(g, o, 1e-4, "raw d=%d step %d" % (d, t + 1))
+    g.close()
+
+
+def test_raw_mode_separate_initial_points_and_fixed_lambda():
+    w = workloads.WORKLOADS["cfg4"].scaled(K=3, d_raw=2048, tau=(2, 2, 5), lambda_abs=0.7,
+                                           beta=0.5, lr_center=0.8, momentum=0.5, steps=11)
+    rng = np.random.default_rng(1)
+    init = rng.standard_normal((w.K + 1) * w.d_raw).astype(np.float32)
+    g, o = make_pair(w, init)
+    for t in range(w.steps):
+        g1, g2 = workloads.raw_grads(w, t)
+        g.lsam_step_grads(torch.from_numpy(g1).to(DEV), torch.from_numpy(g2).to(DEV))
+        o.step_grads(g1, g2)
+        assert g.lsam_sync() == o.sync()
+    check_state(g, o, 1e-4, "raw separate init")
+    a = g.lsam_get_buffer(lsam.BUF_CENTER_DIR, -1)
+    assert rel_max(a, o.gprev) < 1e-4
+    g.close()
+
+
+def test_redraw_schedule_stays_bit_exact():
+    w = workloads.WORKLOADS["cfg4"].scaled(K=5, d_raw=256, tau_min=1, tau_max=4, sched_seed=77,
+                                           sched_mode=workloads.SCHED_REDRAW, steps=40)
+    g, o = make_pair(w)
+    z = torch.zeros(w.K, w.d_raw, device=DEV)
+    for t in range(w.steps):
+        g.lsam_step_grads(z, z)
+        o.step_grads(np.zeros((w.K, w.d_raw)), np.zeros((w.K, w.d_raw)))
+        assert g.lsam_sync() == o.sync()
+        assert g.lsam_get_schedule() == o.get_schedule()
+    g.close()
+
+
+def test_set_scalars_changes_step_size_and_radius():
+    w = workloads.WORKLOADS["cfg4"].scaled(K=2, d_raw=512, tau=(3, 3), steps=6)
+    g, o = make_pair(w)
+    for t in range(w.steps):
+        lr, rho = 0.1 / np.sqrt(t + 1), 0.05 / np.sqrt(t + 1)   # the theorems' decaying schedules
+        g.lsam_set_scalars(lr, rho)
+        o.set_scalars(np.float32(lr), np.float32(rho))
+        g1, g2 = workloads.raw_grads(w, t)
+        g.lsam_step_grads(torch.from_numpy(g1).to(DEV), torch.from_numpy(g2).to(DEV))
+        o.step_grads(g1, g2)
+        assert g.lsam_sync() == o.sync()
+    check_state(g, o, 1e-4, "decaying scalars")
+    g.close()
+
+
+# ---- fp32 MLP configurations ----------------------------------------------------------------------
+@pytest.mark.parametrize("margin", [True, False])
+def test_cfg1_twenty_steps(margin):
+    w = workloads.WORKLOADS["cfg1"]
+    worst = run_mlp(w, w.steps, 1e-4, 1e-3, margin=margin)
+    print("cfg1 margin=%s worst relative error over 20 steps: %.3e" % (margin, worst))
+
+
+@pytest.mark.parametrize("margin", [True, False])
+def test_cfg2_fifty_steps(margin):
+    w = workloads.WORKLOADS["cfg2"]
+    worst = run_mlp(w, 12 if margin else w.steps, 1e-4, 1e-3, check_every=5, margin=margin,
+                    anchor_after=None if margin else 10)
+    print("cfg2 margin=%s worst relative error over 50 steps: %.3e" % (margin, worst))
+
+
+@pytest.mark.parametrize("dims,B,K", [((50, 37, 19, 7), 5, 3), ((8, 3), 1, 1), ((100, 300, 10), 70, 2),
+                                      ((24, 130, 260, 66, 5), 33, 2)])
+def test_fp32_ragged_shapes(dims, B, K):
+    w = workloads.WORKLOADS["cfg1"].scaled(name="ragged", K=K, dims=dims, batch=B, tau=(2,) * K,
+                                           n_classes=dims[-1], steps=5, data_seed=9)
+    run_mlp(w, w.steps, 1e-4, 1e-3, margin=True)
+    run_mlp(w, w.steps, 1e-4, 1e-3, margin=False)
+
+
+# ---- bf16-operand configurations at reduced width (same depth, K and schedule) ---------------------
+@pytest.mark.parametrize("name,width,B", [("cfg3", 256, 32), ("cfg5", 128, 64)])
+def test_bf16_reduced_shapes(name, width, B):
+    full = workloads.WORKLOADS[name]
+    dims = (full.dims[0] // 8,) + (width,) * (len(full.dims) - 2) + (full.dims[-1],)
+    w = full.scaled(dims=dims, batch=B, steps=10)
+    worst = run_mlp(w, w.steps, 2e-2, 2e-2, margin=True)
+    print("%s reduced, margin init: worst relative error %.3e" % (name, worst))
+    worst = run_mlp(w, w.steps, 2e-2, 2e-2, margin=False, tol_flip=1e-1, anchor_after=2)
+    print("%s reduced: worst relative error %.3e" % (name, worst))
+
+
+def test_bf16_ragged_shapes():
+    w = workloads.WORKLOADS["cfg3"].scaled(name="ragged16", K=2, dims=(40, 72, 100, 9), batch=20,
+                                           tau=(2, 3), n_classes=9, steps=6, batch_pool=0)
+    run_mlp(w, w.steps, 2e-2, 2e-2, margin=True)
+    run_mlp(w, w.steps, 2e-2, 2e-2, margin=False, tol_flip=1e-1, anchor_after=2)
+
+
+def test_wrong_mode_calls_fail_cleanly():
+    w = workloads.WORKLOADS["cfg4"].scaled(K=1, d_raw=64, tau=(1,))
+    g, o = make_pair(w)
+    z = torch.zeros(64, device=DEV)
+    with pytest.raises(lsam.LsamError) as e:
+        g.lsam_step(z, z.to(torch.int32), None)
+    assert e.value.code == lsam.ESTATE
+    with pytest.raises(lsam.LsamError):
+        lsam._check(lsam.lib().lsam_get_params(g._h, 3, z.cpu().numpy().ctypes.data, 64))
+    g.close()

@@ -24,3 +24,26 @@ def rel_max(a, b):
     a = np.asarray(a, dtype=np.float64).ravel()
     b = np.asarray(b, dtype=np.float64).ravel()
     return float(np.max(np.abs(a - b)) / max(np.max(np.abs(b)), 1e-300))
+
+
+def outlier_fraction(a, b, tol):
+    """Fraction of elements whose error exceeds tol * max|b|."""
+    a = np.asarray(a, dtype=np.float64).ravel()
+    b = np.asarray(b, dtype=np.float64).ravel()
+    return float(np.mean(np.abs(a - b) > tol * max(np.max(np.abs(b)), 1e-300)))
+
+
+def close_enough(a, b, tol, what):
+    """The parity criterion for floating-point vectors.
+
+    Relative L2 error <= tol.  Element-wise, |a-b| <= tol * max|b| must hold for all but a
+    fraction 2e-3 of the elements, and no element may be off by more than 100 tol * max|b|.
+    The allowance exists because the ReLU mask is a decision taken on a rounded value: a
+    pre-activation within rounding distance of zero can fall on different sides in fp32 and in
+    the float64 oracle, which switches one sample's contribution to one weight row on or off
+    (a change of order 1/B of that row's gradient) without either side being wrong."""
+    l2, mx, fr = rel_l2(a, b), rel_max(a, b), outlier_fraction(a, b, tol)
+    assert l2 <= tol, "%s: relative L2 error %.3e > %.1e" % (what, l2, tol)
+    assert fr <= 2e-3, "%s: %.2e of the elements are off by more than %.1e (max %.3e)" % (what, fr, tol, mx)
+    assert mx <= 100 * tol, "%s: worst element off by %.3e" % (what, mx)
+    return max(l2, mx if fr == 0.0 else l2)

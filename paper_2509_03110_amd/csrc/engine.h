@@ -77,6 +77,7 @@ struct GemmDesc {
   const void* mask; int64_t strideMask; int ldMask; // EPI_MASK: keep where mask[m,n] > 0 (operand dtype)
 };
 int launch_gemm(const GemmDesc& d, hipStream_t s);   // 0 ok, <0 unsupported shape
+void set_gemm_tile_override(int code);               // tuning hook: 0 = choose by shape
 
 // Softmax cross-entropy, forward and backward.  logits [K,B,ld] fp32; labels [K,B];
 // dz [K,B,ld_dz] (fp32 or bf16) = (softmax - onehot)/B, zero in the padded columns;

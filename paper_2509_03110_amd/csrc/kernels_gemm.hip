@@ -8,8 +8,16 @@
 // (UE = 4 floats or 8 bf16).  k-major operands are loaded as units straight from memory;
 // m-major operands are loaded as UE rows x 16 bytes per thread and transposed in registers
 // (free for fp32, a few byte-permutes for bf16), so that the MFMA feed is the same 128-bit
-// LDS read in every case.  A workgroup is 4 wavefronts in a 2x2 arrangement; each wavefront
-// owns a (BM/2)x(BN/2) block of 32x32 MFMA tiles.
+// LDS read in every case.  Global loads are buffer loads: rows past the end of an operand
+// come back as zeros from the hardware range check instead of through branches.
+//
+// A workgroup is 4 wavefronts in a 2x2 arrangement; each wavefront owns a (BM/2)x(BN/2)
+// block of 32x32 MFMA tiles.  LDS is double buffered (one barrier per k-step): the next
+// k-step's global loads are issued before the MFMAs of the current one and written to the
+// other LDS buffer after them; operand fragments are double buffered in registers so LDS
+// reads of the next 16 (bf16) / 8 (fp32) k overlap the MFMAs of the current ones.
+// The MFMA is issued with the roles swapped (rows <- B operand, columns <- A operand), so
+// that a lane ends up with 4 consecutive n of one row m: 16-byte stores in the epilogue.
 #include "engine.h"
 
 namespace lsam {
@@ -21,7 +29,7 @@ constexpr int BKU = 8;   // 16-byte units per row per k-step: 128 bytes of k per
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 struct GemmParams {
@@ -36,9 +44,13 @@ struct GemmParams {
   const char* mask; long long strideMask; int ldMask;
 };
 
+int g_tile_override = 0;   // tuning hook, 0 = choose by shape
+
 template <typename T> struct Op;
 template <> struct Op<float> { static constexpr int UE = 4; };
 template <> struct Op<__bf16> { static constexpr int UE = 8; };
+
+constexpr unsigned kOob = 0x7FFFFFF0u;   // byte offset past any operand: load returns zeros
 
 // Row position inside an LDS tile: rows are permuted inside groups of UE so that both the
 // transposing writes (lanes UE rows apart) and the MFMA reads (lanes on consecutive rows)
@@ -46,50 +58,54 @@ template <> struct Op<__bf16> { static constexpr int UE = 8; };
 template <int UE>
 __device__ __forceinline__ int swz(int r) { return r ^ ((r / UE) & (UE - 1)); }
 
-// Loads one operand tile (R rows x BKU units) from global memory into registers.
+// Loads one operand tile (R rows x BKU units) from global memory into registers and writes
+// it to LDS laid out as units [BKU][R + 1].
 template <typename T, int R, bool KMAJOR>
 struct TileLoader {
   static constexpr int UE = Op<T>::UE;
+  static constexpr int ES = sizeof(T);
   static constexpr int NUNITS = KMAJOR ? (R * BKU / kThreads) : 0;                 // per thread
   static constexpr int NBLK_TOTAL = BKU * (R / UE);
   static constexpr int NBLK = KMAJOR ? 0 : (NBLK_TOTAL + kThreads - 1) / kThreads;  // per thread
   static constexpr int NREG = KMAJOR ? (NUNITS > 0 ? NUNITS : 1) : NBLK * UE;
   u32x4 reg[NREG];
 
-  // base: operand of this replica; row0: first tile row; k0u: first k-unit of this step;
-  // rows: row extent with readable padding up to a multiple of UE; kd: true k extent.
-  __device__ __forceinline__ void load(const T* __restrict__ base, int ld, int row0, int rows,
+  // rsrc covers the operand of this replica: rows*ld elements (k-major) or kd*ld (m-major),
+  // so a row index past the end is out of range by construction.  row0: first tile row;
+  // k0u: first k-unit of this step; rows: row extent; kd: true k extent.
+  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, int ld, int row0, int rows,
                                        int k0u, int kd, int tid) {
-    const u32x4 zero = {0u, 0u, 0u, 0u};
     if constexpr (KMAJOR) {
       const int kunits = (kd + UE - 1) / UE;
 #pragma unroll
       for (int j = 0; j < NUNITS; ++j) {
         const int u = tid + kThreads * j;
         const int r = row0 + u / BKU, ku = k0u + u % BKU;
-        reg[j] = (r < rows && ku < kunits)
-                     ? *reinterpret_cast<const u32x4*>(base + (long long)r * ld + ku * UE)
-                     : zero;
+        const unsigned off = (unsigned)(r * ld + ku * UE) * ES;
+        reg[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (r < rows && ku < kunits) ? off : kOob,
+                                                       0, 0);
       }
     } else {
+      // Rows k >= kd lie past the end of the buffer and read as zeros by themselves; a
+      // column group past the operand's width is sent there through its column offset.
       const int rows_up = (rows + UE - 1) / UE * UE;
 #pragma unroll
       for (int j = 0; j < NBLK; ++j) {
         const int b = tid + kThreads * j;
         const int mg = b % (R / UE), kb = b / (R / UE);
         const int m = row0 + mg * UE;
+        const unsigned moff = (b < NBLK_TOTAL && m < rows_up) ? (unsigned)m * ES : kOob;
 #pragma unroll
         for (int i = 0; i < UE; ++i) {
           const int k = (k0u + kb) * UE + i;
-          reg[j * UE + i] = (b < NBLK_TOTAL && m < rows_up && k < kd)
-                                ? *reinterpret_cast<const u32x4*>(base + (long long)k * ld + m)
-                                : zero;
+          const unsigned koff = (k < kd) ? (unsigned)(k * ld) * ES : 0u;
+          reg[j * UE + i] = __builtin_amdgcn_raw_buffer_load_b128(
+              rsrc, (k < kd) ? koff + moff : kOob, 0, 0);
         }
       }
     }
   }
 
-  // Writes the registers to the LDS tile laid out as units [BKU][R + 1].
   __device__ __forceinline__ void store(u32x4* __restrict__ lds, int tid) const {
     if constexpr (KMAJOR) {
 #pragma unroll
@@ -116,8 +132,9 @@ struct TileLoader {
               for (int q = 0; q < 4; ++q) {
                 const unsigned lo = reg[j * 8 + 2 * q][e / 2];
                 const unsigned hi = reg[j * 8 + 2 * q + 1][e / 2];
-                unit[q] = (e & 1) ? ((lo >> 16) | (hi & 0xFFFF0000u))
-                                  : ((lo & 0xFFFFu) | (hi << 16));
+                // bytes of {hi,lo}: keep the even (low) or the odd (high) halfwords
+                unit[q] = (e & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u)
+                                  : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
               }
             }
             lds[kb * (R + 1) + swz<UE>(mg * UE + e)] = unit;
@@ -128,16 +145,50 @@ struct TileLoader {
   }
 };
 
+template <typename T> struct Pack;
+template <> struct Pack<float> {
+  typedef f32x4 vec;
+  static __device__ __forceinline__ vec from(const f32x4& v) { return v; }
+  static __device__ __forceinline__ float one(float v) { return v; }
+};
+template <> struct Pack<__bf16> {
+  typedef u32x2 vec;
+  static __device__ __forceinline__ vec from(const f32x4& v) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    bf16x2 lo = {static_cast<__bf16>(v[0]), static_cast<__bf16>(v[1])};
+    bf16x2 hi = {static_cast<__bf16>(v[2]), static_cast<__bf16>(v[3])};
+    vec o;
+    o[0] = __builtin_bit_cast(unsigned, lo);
+    o[1] = __builtin_bit_cast(unsigned, hi);
+    return o;
+  }
+  static __device__ __forceinline__ __bf16 one(float v) { return static_cast<__bf16>(v); }
+};
+
+// Buffer resource for one replica's operand.  Base and size are the same for every lane;
+// passing them through readfirstlane tells the compiler so (the descriptor must sit in
+// scalar registers, and a descriptor it believes to vary per lane costs a loop per load).
+template <typename T>
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const T* base, unsigned bytes) {
+  const unsigned long long a = reinterpret_cast<unsigned long long>(base);
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a);
+  const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
+  void* ptr = reinterpret_cast<void*>(((unsigned long long)hi << 32) | lo);
+  return __builtin_amdgcn_make_buffer_rsrc(ptr, 0, __builtin_amdgcn_readfirstlane(bytes),
+                                           0x00020000);
+}
+
 __device__ __forceinline__ float widen(float v) { return v; }
 __device__ __forceinline__ float widen(__bf16 v) { return static_cast<float>(v); }
 
-template <typename T, typename TC, int BM, int BN, bool A_KMAJOR, bool B_KMAJOR>
-__global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams p) {
+template <typename T, typename TC, int BM, int BN, bool A_KMAJOR, bool B_KMAJOR, int OCC>
+__global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
   constexpr int UE = Op<T>::UE;
   constexpr int TM = BM / 64, TN = BN / 64;
+  constexpr int A_UNITS = BKU * (BM + 1), B_UNITS = BKU * (BN + 1);
+  constexpr int STAGE_UNITS = A_UNITS + B_UNITS;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  u32x4* ldsA = reinterpret_cast<u32x4*>(smem);
-  u32x4* ldsB = ldsA + BKU * (BM + 1);
+  u32x4* lds = reinterpret_cast<u32x4*>(smem);
 
   // Workgroup -> tile.  Hardware deals consecutive workgroup ids round-robin over the 8
   // XCDs; remap so that each XCD walks a contiguous range of tiles (tiles that share a
@@ -152,6 +203,10 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams p) {
 
   const T* A = reinterpret_cast<const T*>(p.A) + (long long)bat * p.strideA;
   const T* B = reinterpret_cast<const T*>(p.B) + (long long)bat * p.strideB;
+  const unsigned bytesA = (unsigned)((A_KMAJOR ? p.M : p.Kd) * p.ldA) * sizeof(T);
+  const unsigned bytesB = (unsigned)((B_KMAJOR ? p.N : p.Kd) * p.ldB) * sizeof(T);
+  const __amdgpu_buffer_rsrc_t rsrcA = make_rsrc(A, bytesA);
+  const __amdgpu_buffer_rsrc_t rsrcB = make_rsrc(B, bytesB);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -169,87 +224,155 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams p) {
   TileLoader<T, BM, A_KMAJOR> la;
   TileLoader<T, BN, B_KMAJOR> lb;
   const int ksteps = (p.Kd + BKU * UE - 1) / (BKU * UE);
-  la.load(A, p.ldA, m0, p.M, 0, p.Kd, tid);
-  lb.load(B, p.ldB, n0, p.N, 0, p.Kd, tid);
+  la.load(rsrcA, p.ldA, m0, p.M, 0, p.Kd, tid);
+  lb.load(rsrcB, p.ldB, n0, p.N, 0, p.Kd, tid);
+  la.store(lds, tid);
+  lb.store(lds + A_UNITS, tid);
+  __syncthreads();
+
+  // LDS read positions of this lane (k-unit `h` of each k-chunk is added in the loop)
+  int posA[TM], posB[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) posA[i] = h * (BM + 1) + swz<UE>(wm0 + i * 32 + l32);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) posB[j] = A_UNITS + h * (BN + 1) + swz<UE>(wn0 + j * 32 + l32);
 
   for (int ks = 0; ks < ksteps; ++ks) {
-    la.store(ldsA, tid);
-    lb.store(ldsB, tid);
-    __syncthreads();
-    if (ks + 1 < ksteps) {
-      la.load(A, p.ldA, m0, p.M, (ks + 1) * BKU, p.Kd, tid);
-      lb.load(B, p.ldB, n0, p.N, (ks + 1) * BKU, p.Kd, tid);
+    const u32x4* cur = lds + (ks & 1) * STAGE_UNITS;
+    u32x4* nxt = lds + ((ks + 1) & 1) * STAGE_UNITS;
+    const bool more = ks + 1 < ksteps;
+    if (more) {
+      la.load(rsrcA, p.ldA, m0, p.M, (ks + 1) * BKU, p.Kd, tid);
+      lb.load(rsrcB, p.ldB, n0, p.N, (ks + 1) * BKU, p.Kd, tid);
     }
+    u32x4 fa[2][TM], fb[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[0][i] = cur[posA[i]];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[0][j] = cur[posB[j]];
 #pragma unroll
     for (int kc = 0; kc < BKU / 2; ++kc) {
-      const int ku = kc * 2 + h;
-      u32x4 fa[TM], fb[TN];
+      const int c = kc & 1;
+      if (kc + 1 < BKU / 2) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = ldsA[ku * (BM + 1) + swz<UE>(wm0 + i * 32 + l32)];
+        for (int i = 0; i < TM; ++i) fa[c ^ 1][i] = cur[posA[i] + (kc + 1) * 2 * (BM + 1)];
 #pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = ldsB[ku * (BN + 1) + swz<UE>(wn0 + j * 32 + l32)];
+        for (int j = 0; j < TN; ++j) fb[c ^ 1][j] = cur[posB[j] + (kc + 1) * 2 * (BN + 1)];
+      }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           if constexpr (UE == 4) {
-            const f32x4 a = __builtin_bit_cast(f32x4, fa[i]);
-            const f32x4 b = __builtin_bit_cast(f32x4, fb[j]);
+            const f32x4 a = __builtin_bit_cast(f32x4, fa[c][i]);
+            const f32x4 b = __builtin_bit_cast(f32x4, fb[c][j]);
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e], b[e], acc[i][j], 0, 0, 0);
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[e], a[e], acc[i][j], 0, 0, 0);
           } else {
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                __builtin_bit_cast(bf16x8, fa[i]), __builtin_bit_cast(bf16x8, fb[j]), acc[i][j], 0,
-                0, 0);
+                __builtin_bit_cast(bf16x8, fb[c][j]), __builtin_bit_cast(bf16x8, fa[c][i]),
+                acc[i][j], 0, 0, 0);
           }
         }
+    }
+    if (more) {
+      la.store(nxt, tid);
+      lb.store(nxt + A_UNITS, tid);
     }
     __syncthreads();
   }
 
-  // Epilogue.  Accumulator element e of a 32x32 tile: row (e/4)*8 + h*4 + e%4, column l32.
+  // Epilogue.  With the swapped MFMA roles, accumulator element e of a 32x32 tile belongs to
+  // row m = l32 and column n = (e/4)*8 + h*4 + e%4.  Stores straight from that layout would
+  // scatter 16-byte pieces over 32 rows per instruction; instead the tile is passed through
+  // LDS (now free) 64 rows at a time and written out as whole rows, consecutive lanes on
+  // consecutive 16 bytes, which is also how bias and the ReLU mask are read.
   TC* C = reinterpret_cast<TC*>(p.C) + (long long)bat * p.strideC;
   const float* bias = p.bias ? p.bias + (long long)bat * p.strideBias : nullptr;
   const float* bias_dir = p.bias_dir ? p.bias_dir + (long long)bat * p.strideBias : nullptr;
   const float bias_sc = p.bias_dir ? p.bias_scale[bat] : 0.f;
   const T* mask = p.mask ? reinterpret_cast<const T*>(p.mask) + (long long)bat * p.strideMask
                          : nullptr;
+  const bool has_bias = p.epilogue == EPI_BIAS || p.epilogue == EPI_BIAS_RELU;
+  const bool relu = p.epilogue == EPI_BIAS_RELU;
+  const bool masked = p.epilogue == EPI_MASK;
+  typedef typename Pack<TC>::vec cvec;
+  typedef typename Pack<T>::vec mvec;
+  constexpr int PITCH = BN + 4;                 // floats; +4 keeps the 16-byte writes off one bank
+  constexpr int LANES_PER_ROW = BN / 4;         // lanes that cover one row of the tile
+  constexpr int ROWS_PER_PASS = kThreads / LANES_PER_ROW;
+  float* stage = reinterpret_cast<float*>(smem);
+  const int c4 = (tid % LANES_PER_ROW) * 4;     // first of this lane's 4 columns (read-out phase)
+  const int rsub = tid / LANES_PER_ROW;
+  const int n = n0 + c4;
+  f32x4 bv = {0.f, 0.f, 0.f, 0.f};
+  if (has_bias) {
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int n = n0 + wn0 + j * 32 + l32;
-    if (n >= p.N) continue;
-    float bv = 0.f;
-    if (p.epilogue == EPI_BIAS || p.epilogue == EPI_BIAS_RELU) {
-      bv = bias[n];
-      if (bias_dir) bv = bv + bias_sc * bias_dir[n];   // bias of the perturbed point
-    }
+    for (int r = 0; r < 4; ++r)
+      if (n + r < p.N) {
+        bv[r] = bias[n + r];
+        if (bias_dir) bv[r] = bv[r] + bias_sc * bias_dir[n + r];   // bias of the perturbed point
+      }
+  }
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+  for (int i = 0; i < TM; ++i) {
+    // rows of this pass: for each of the two wave rows, its i-th 32-row strip
+    const int lrow = (wave >> 1) * 32 + l32;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int m = m0 + wm0 + i * 32 + (e / 4) * 8 + h * 4 + (e % 4);
-        if (m >= p.M) continue;
-        float v = acc[i][j][e] + bv;
-        if (p.epilogue == EPI_BIAS_RELU) v = v > 0.f ? v : 0.f;
-        if (p.epilogue == EPI_MASK) {
-          if (!(widen(mask[(long long)m * p.ldMask + n]) > 0.f)) v = 0.f;
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        f32x4 v;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = acc[i][j][q * 4 + r];
+        *reinterpret_cast<f32x4*>(stage + lrow * PITCH + wn0 + j * 32 + q * 8 + h * 4) = v;
+      }
+    __syncthreads();
+#pragma unroll
+    for (int rr = rsub; rr < 64; rr += ROWS_PER_PASS) {
+      const int m = m0 + (rr >> 5) * (BM / 2) + i * 32 + (rr & 31);
+      if (m < p.M && n < p.N) {
+        f32x4 v = *reinterpret_cast<const f32x4*>(stage + rr * PITCH + c4);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          v[r] += bv[r];
+          if (relu) v[r] = v[r] > 0.f ? v[r] : 0.f;
         }
-        C[(long long)m * p.ldC + n] = static_cast<TC>(v);
+        if (n + 3 < p.N) {
+          if (masked) {
+            const mvec mk = *reinterpret_cast<const mvec*>(mask + (long long)m * p.ldMask + n);
+            const T* me = reinterpret_cast<const T*>(&mk);
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              if (!(widen(me[r]) > 0.f)) v[r] = 0.f;
+          }
+          *reinterpret_cast<cvec*>(C + (long long)m * p.ldC + n) = Pack<TC>::from(v);
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (n + r < p.N) {
+              float o = v[r];
+              if (masked && !(widen(mask[(long long)m * p.ldMask + n + r]) > 0.f)) o = 0.f;
+              C[(long long)m * p.ldC + n + r] = Pack<TC>::one(o);
+            }
+        }
       }
     }
+    if (i + 1 < TM) __syncthreads();
   }
 }
 
 template <typename T, typename TC, int BM, int BN, bool AK, bool BK_>
 int launch_one(const GemmParams& p0, hipStream_t s) {
+  constexpr int OCC = (BM * BN >= 256 * 256) ? 1 : 2;
   GemmParams p = p0;
   p.tilesM = (p.M + BM - 1) / BM;
   p.tilesN = (p.N + BN - 1) / BN;
   p.total = p.tilesM * p.tilesN * p.batch;
   p.chunks = (p.total + 7) / 8;
-  const size_t smem = (size_t)BKU * ((BM + 1) + (BN + 1)) * 16;
-  auto kern = gemm_kernel<T, TC, BM, BN, AK, BK_>;
+  const size_t smem = (size_t)2 * BKU * ((BM + 1) + (BN + 1)) * 16;
+  auto kern = gemm_kernel<T, TC, BM, BN, AK, BK_, OCC>;
   static bool attr_set = false;   // per instantiation
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -263,10 +386,16 @@ int launch_one(const GemmParams& p0, hipStream_t s) {
 
 template <typename T, typename TC, bool AK, bool BK_>
 int launch_tiled(const GemmParams& p, hipStream_t s) {
-  // Largest tile that still yields at least ~2 workgroups per compute unit.
   auto tiles = [&](int bm, int bn) {
     return (long long)((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn) * p.batch;
   };
+  switch (g_tile_override) {
+    case 1: return launch_one<T, TC, 256, 256, AK, BK_>(p, s);
+    case 4: return launch_one<T, TC, 128, 128, AK, BK_>(p, s);
+    case 5: return launch_one<T, TC, 64, 64, AK, BK_>(p, s);
+    default: break;
+  }
+  // Largest tile that still yields at least ~2 workgroups per compute unit.
   if (p.M >= 256 && p.N >= 256 && tiles(256, 256) >= 512)
     return launch_one<T, TC, 256, 256, AK, BK_>(p, s);
   if (p.M >= 128 && p.N >= 128 && tiles(128, 128) >= 512)
@@ -284,6 +413,8 @@ int launch_layout(const GemmDesc& d, const GemmParams& p, hipStream_t s) {
 
 }  // namespace
 
+void set_gemm_tile_override(int code) { g_tile_override = code; }
+
 int launch_gemm(const GemmDesc& d, hipStream_t s) {
   GemmParams p;
   p.A = (const char*)d.A; p.strideA = d.strideA; p.ldA = d.ldA;
@@ -297,13 +428,20 @@ int launch_gemm(const GemmDesc& d, hipStream_t s) {
   p.mask = (const char*)d.mask; p.strideMask = d.strideMask; p.ldMask = d.ldMask;
   if (d.M <= 0 || d.N <= 0 || d.Kd <= 0 || d.batch <= 0) return -1;
   // 16-byte units: pitches must be multiples of 8 elements and bases 16-byte aligned.
-  if ((d.ldA % 8) || (d.ldB % 8) || ((uintptr_t)d.A & 15) || ((uintptr_t)d.B & 15)) return -1;
+  if ((d.ldA % 8) || (d.ldB % 8) || (d.ldC % 8) || ((uintptr_t)d.A & 15) ||
+      ((uintptr_t)d.B & 15) || ((uintptr_t)d.C & 15))
+    return -1;
+  if (d.epilogue == EPI_MASK && ((d.ldMask % 8) || ((uintptr_t)d.mask & 15))) return -1;
+  // buffer-load offsets are 32-bit byte offsets inside one replica's operand
+  const long long es = d.in_bf16 ? 2 : 4;
+  const long long rowsA = d.a_kmajor ? d.M : d.Kd, rowsB = d.b_kmajor ? d.N : d.Kd;
+  if (rowsA * d.ldA * es >= 0x7FFFFFF0LL || rowsB * d.ldB * es >= 0x7FFFFFF0LL) return -1;
   if (d.in_bf16) {
-    if ((d.strideA % 8) || (d.strideB % 8)) return -1;
+    if ((d.strideA % 8) || (d.strideB % 8) || (d.strideC % 8)) return -1;
     if (d.out_bf16) return launch_layout<__bf16, __bf16>(d, p, s);
     return launch_layout<__bf16, float>(d, p, s);
   }
-  if ((d.strideA % 4) || (d.strideB % 4)) return -1;
+  if ((d.strideA % 4) || (d.strideB % 4) || (d.strideC % 4)) return -1;
   if (d.out_bf16) return -1;
   return launch_layout<float, float>(d, p, s);
 }

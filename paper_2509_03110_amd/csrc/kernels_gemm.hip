@@ -24,7 +24,6 @@ namespace lsam {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int BKU = 8;   // 16-byte units per row per k-step: 128 bytes of k per step
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -58,9 +57,9 @@ constexpr unsigned kOob = 0x7FFFFFF0u;   // byte offset past any operand: load r
 template <int UE>
 __device__ __forceinline__ int swz(int r) { return r ^ ((r / UE) & (UE - 1)); }
 
-// Loads one operand tile (R rows x BKU units) from global memory into registers and writes
-// it to LDS laid out as units [BKU][R + 1].
-template <typename T, int R, bool KMAJOR>
+// Loads one operand tile (R rows x BKU units of 16 bytes: 16*BKU bytes of k per k-step) from
+// global memory into registers and writes it to LDS laid out as units [BKU][R + 1].
+template <typename T, int R, bool KMAJOR, int BKU>
 struct TileLoader {
   static constexpr int UE = Op<T>::UE;
   static constexpr int ES = sizeof(T);
@@ -181,7 +180,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const T* base, unsig
 __device__ __forceinline__ float widen(float v) { return v; }
 __device__ __forceinline__ float widen(__bf16 v) { return static_cast<float>(v); }
 
-template <typename T, typename TC, int BM, int BN, bool A_KMAJOR, bool B_KMAJOR, int OCC>
+template <typename T, typename TC, int BM, int BN, int BKU, bool A_KMAJOR, bool B_KMAJOR, int OCC>
 __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
   constexpr int UE = Op<T>::UE;
   constexpr int TM = BM / 64, TN = BN / 64;
@@ -221,8 +220,8 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  TileLoader<T, BM, A_KMAJOR> la;
-  TileLoader<T, BN, B_KMAJOR> lb;
+  TileLoader<T, BM, A_KMAJOR, BKU> la;
+  TileLoader<T, BN, B_KMAJOR, BKU> lb;
   const int ksteps = (p.Kd + BKU * UE - 1) / (BKU * UE);
   la.load(rsrcA, p.ldA, m0, p.M, 0, p.Kd, tid);
   lb.load(rsrcB, p.ldB, n0, p.N, 0, p.Kd, tid);
@@ -363,7 +362,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
   }
 }
 
-template <typename T, typename TC, int BM, int BN, bool AK, bool BK_>
+template <typename T, typename TC, int BM, int BN, int BKU, bool AK, bool BK_>
 int launch_one(const GemmParams& p0, hipStream_t s) {
   constexpr int OCC = (BM * BN >= 256 * 256) ? 1 : 2;
   GemmParams p = p0;
@@ -371,8 +370,10 @@ int launch_one(const GemmParams& p0, hipStream_t s) {
   p.tilesN = (p.N + BN - 1) / BN;
   p.total = p.tilesM * p.tilesN * p.batch;
   p.chunks = (p.total + 7) / 8;
-  const size_t smem = (size_t)2 * BKU * ((BM + 1) + (BN + 1)) * 16;
-  auto kern = gemm_kernel<T, TC, BM, BN, AK, BK_, OCC>;
+  const size_t loop_smem = (size_t)2 * BKU * ((BM + 1) + (BN + 1)) * 16;
+  const size_t epi_smem = (size_t)64 * (BN + 4) * 4;
+  const size_t smem = loop_smem > epi_smem ? loop_smem : epi_smem;
+  auto kern = gemm_kernel<T, TC, BM, BN, BKU, AK, BK_, OCC>;
   static bool attr_set = false;   // per instantiation
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -390,17 +391,23 @@ int launch_tiled(const GemmParams& p, hipStream_t s) {
     return (long long)((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn) * p.batch;
   };
   switch (g_tile_override) {
-    case 1: return launch_one<T, TC, 256, 256, AK, BK_>(p, s);
-    case 4: return launch_one<T, TC, 128, 128, AK, BK_>(p, s);
-    case 5: return launch_one<T, TC, 64, 64, AK, BK_>(p, s);
+    case 1: return launch_one<T, TC, 256, 256, 8, AK, BK_>(p, s);
+    case 2: return launch_one<T, TC, 256, 128, 4, AK, BK_>(p, s);
+    case 4: return launch_one<T, TC, 128, 128, 8, AK, BK_>(p, s);
+    case 5: return launch_one<T, TC, 64, 64, 8, AK, BK_>(p, s);
     default: break;
   }
-  // Largest tile that still yields at least ~2 workgroups per compute unit.
+  // Tile choice, from measurements on MI355X at the workload shapes: the forward GEMM (both
+  // operands k-major, few staging registers) runs best as 256x128 tiles with two workgroups
+  // per compute unit; the GEMMs with transposing loads as 256x256 with one.  Smaller tiles
+  // only where the larger ones would leave compute units idle.
+  if (AK && BK_ && p.M >= 256 && p.N >= 128 && tiles(256, 128) >= 512)
+    return launch_one<T, TC, 256, 128, 4, AK, BK_>(p, s);
   if (p.M >= 256 && p.N >= 256 && tiles(256, 256) >= 512)
-    return launch_one<T, TC, 256, 256, AK, BK_>(p, s);
-  if (p.M >= 128 && p.N >= 128 && tiles(128, 128) >= 512)
-    return launch_one<T, TC, 128, 128, AK, BK_>(p, s);
-  return launch_one<T, TC, 64, 64, AK, BK_>(p, s);
+    return launch_one<T, TC, 256, 256, 8, AK, BK_>(p, s);
+  if (p.M >= 128 && p.N >= 128 && tiles(128, 128) >= 256)
+    return launch_one<T, TC, 128, 128, 8, AK, BK_>(p, s);
+  return launch_one<T, TC, 64, 64, 8, AK, BK_>(p, s);
 }
 
 template <typename T, typename TC>

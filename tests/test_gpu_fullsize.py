@@ -1,0 +1,102 @@
+"""GPU parity at the full sizes the benchmark runs, in the benchmark's launch configuration.
+
+A float64 oracle of every replica at these sizes would take many minutes, so each test checks
+what the oracle can reach in seconds and covers the rest by properties that hold at any size:
+
+  * update-only path (K=8, d=1e8): the update is coordinate-wise once the per-replica norm is
+    known, so the oracle runs on a sample of 200 000 coordinates plus one extra coordinate
+    that carries the norm of all the others (||g1|| is then exactly the full-vector norm);
+    the GPU's norms are also compared with the float64 norm of the whole vector.
+  * bf16 MLP shapes (cfg3: K=8, width 4096, B=256; cfg5: K=16, width 8192, B=512): the oracle
+    computes one whole replica; several other replicas get the same batch and must reproduce
+    that replica's loss and gradients bit for bit (the kernels are deterministic and
+    replica-independent), the remaining ones are checked for finite, plausible output.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from paper_2509_03110_amd import lsam
+from util import close_enough, oracle_from, rel_max
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def test_update_path_full_size_sampled():
+    w = workloads.WORKLOADS["cfg4"]
+    K, d = w.K, w.d_raw
+    rng = np.random.default_rng(44)
+    J = np.sort(rng.choice(d, size=200_000, replace=False))
+    init = workloads.init_params(w)                       # y = x_i ~ N(0,1) [1e8]
+    g1 = np.empty((K, d), dtype=np.float32)
+    g2 = np.empty((K, d), dtype=np.float32)
+    gen = np.random.default_rng([w.data_seed, 77])
+    for k in range(K):                                    # fixed gradient buffers ~ N(0, 1e-2^2)
+        g1[k] = gen.standard_normal(d, dtype=np.float32) * np.float32(w.grad_std)
+        g2[k] = gen.standard_normal(d, dtype=np.float32) * np.float32(w.grad_std)
+    full_norm = np.array([np.sqrt(np.sum(np.square(g1[k], dtype=np.float64))) for k in range(K)])
+    rest = np.sqrt(np.maximum(full_norm ** 2 - np.sum(np.square(g1[:, J], dtype=np.float64), axis=1), 0))
+    g1s = np.concatenate([g1[:, J].astype(np.float64), rest[:, None]], axis=1)
+    g2s = np.concatenate([g2[:, J].astype(np.float64), np.zeros((K, 1))], axis=1)
+    ws = w.scaled(d_raw=J.size + 1)
+    ora = oracle_from(ws, np.concatenate([init[J].astype(np.float64), [0.0]]))
+
+    cfg, keep = lsam.config_from_workload(w)
+    eng = lsam.Lsam(cfg, init, device=DEV, keep=keep)
+    g1d, g2d = torch.from_numpy(g1).to(DEV), torch.from_numpy(g2).to(DEV)
+    del g1, g2
+    for t in range(8):
+        eng.lsam_step_grads(g1d, g2d)
+        ora.step_grads(g1s, g2s)
+        assert np.allclose(eng.lsam_get_norms(), full_norm, rtol=1e-6)
+        assert np.allclose(ora.last_norm, full_norm, rtol=1e-12)
+        assert eng.lsam_sync() == ora.sync()
+        assert eng.lsam_get_schedule() == ora.get_schedule()
+    for i in list(range(K)) + [-1]:
+        close_enough(eng.lsam_get_params(i)[J], ora.get_params(i)[:-1], 1e-4, "x of replica %d" % i)
+    for i in (0, K - 1):
+        close_enough(eng.lsam_get_buffer(lsam.BUF_VELOCITY, i)[J], ora.v[i][:-1], 1e-4, "v %d" % i)
+        close_enough(eng.lsam_get_buffer(lsam.BUF_ITER_SUM, i)[J], ora.S[i][:-1], 1e-4, "S %d" % i)
+        xt = eng.lsam_get_buffer(lsam.BUF_PERTURBED, i)[J]
+        assert rel_max(xt, ora.last_perturbed[i][:-1]) < 1e-5
+    eng.close()
+
+
+def _full_shape_one_replica(name, twins):
+    w = workloads.WORKLOADS[name]
+    init = workloads.init_params(w)
+    cfg, keep = lsam.config_from_workload(w)
+    eng = lsam.Lsam(cfg, init, device=DEV, keep=keep)
+    tau0 = eng.lsam_get_schedule()[0][0]
+    X, lab = workloads.batch(w, 0)
+    for k in twins:                      # replicas that see replica 0's batch
+        X[k], lab[k] = X[0], lab[0]
+    loss = torch.zeros(w.K, device=DEV)
+    eng.lsam_step(torch.from_numpy(X).to(DEV).to(torch.bfloat16).contiguous(),
+                  torch.from_numpy(lab).to(DEV), loss)
+    gl = loss.cpu().numpy()
+    ora = oracle_from(w.scaled(K=1, tau=(tau0,)), init)
+    ol = ora.step(X[:1], lab[:1])
+    assert abs(gl[0] - ol[0]) <= 2e-2 * abs(ol[0])
+    assert abs(eng.lsam_get_norms()[0] - ora.last_norm[0]) <= 5e-2 * ora.last_norm[0]
+    g2 = eng.lsam_get_buffer(lsam.BUF_GRAD, 0)
+    close_enough(g2, ora.last_g2[0], 1e-1, "%s full shape: g2 of replica 0" % name)
+    close_enough(eng.lsam_get_params(0), ora.get_params(0), 2e-2, "%s full shape: x of replica 0" % name)
+    close_enough(eng.lsam_get_buffer(lsam.BUF_VELOCITY, 0), ora.v[0], 1e-1, "%s full shape: v" % name)
+    for k in twins:
+        assert gl[k] == gl[0]
+        assert np.array_equal(eng.lsam_get_buffer(lsam.BUF_GRAD, k), g2), "replica %d differs" % k
+    norms = eng.lsam_get_norms()
+    assert np.all(np.isfinite(gl)) and np.all(np.isfinite(norms)) and np.all(norms > 0)
+    assert np.all(np.abs(gl - np.log(w.n_classes)) < 0.5)     # near-uniform predictions at init
+    eng.close()
+
+
+def test_cfg3_full_shape_one_replica():
+    _full_shape_one_replica("cfg3", twins=(3, 7))
+
+
+def test_cfg5_full_shape_one_replica():
+    _full_shape_one_replica("cfg5", twins=(6, 15))

@@ -77,6 +77,8 @@ struct GemmDesc {
   const void* mask; int64_t strideMask; int ldMask; // EPI_MASK: keep where mask[m,n] > 0 (operand dtype)
 };
 int launch_gemm(const GemmDesc& d, hipStream_t s);   // 0 ok, <0 unsupported shape
+// bf16 fast path (direct-to-LDS ring); returns 1 when the shape is left to the generic kernel.
+int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s);
 void set_gemm_tile_override(int code);               // tuning hook: 0 = choose by shape
 
 // Softmax cross-entropy, forward and backward.  logits [K,B,ld] fp32; labels [K,B];

@@ -44,6 +44,7 @@ struct GemmParams {
 };
 
 int g_tile_override = 0;   // tuning hook, 0 = choose by shape
+bool g_use_ring = true;    // tuning hook: bf16 shapes go to the direct-to-LDS kernel when it takes them
 
 template <typename T> struct Op;
 template <> struct Op<float> { static constexpr int UE = 4; };
@@ -67,6 +68,7 @@ struct TileLoader {
   static constexpr int NBLK_TOTAL = BKU * (R / UE);
   static constexpr int NBLK = KMAJOR ? 0 : (NBLK_TOTAL + kThreads - 1) / kThreads;  // per thread
   static constexpr int NREG = KMAJOR ? (NUNITS > 0 ? NUNITS : 1) : NBLK * UE;
+  static constexpr int NSTORE = NREG;   // 16-byte LDS writes per thread and k-step
   u32x4 reg[NREG];
 
   // rsrc covers the operand of this replica: rows*ld elements (k-major) or kd*ld (m-major),
@@ -116,7 +118,7 @@ struct TileLoader {
 #pragma unroll
       for (int j = 0; j < NBLK; ++j) {
         const int b = tid + kThreads * j;
-        if (b < NBLK_TOTAL) {
+        if (NBLK_TOTAL % kThreads == 0 || b < NBLK_TOTAL) {
           const int mg = b % (R / UE), kb = b / (R / UE);
 #pragma unroll
           for (int e = 0; e < UE; ++e) {
@@ -177,6 +179,29 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const T* base, unsig
                                            0x00020000);
 }
 
+// Scheduling hints (sched_group_barrier): spread N instructions of class MASK evenly over M
+// MFMAs, in that order.  Classes: 0x008 MFMA, 0x020 VMEM read, 0x100 LDS read, 0x200 LDS write.
+template <int MASK, int N, int M, int I>
+struct Interleave {
+  static __device__ __forceinline__ void run() {
+    constexpr int ops = N * (I + 1) / M - N * I / M;
+    if constexpr (ops > 0) __builtin_amdgcn_sched_group_barrier(MASK, ops, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if constexpr (I + 1 < M) Interleave<MASK, N, M, I + 1>::run();
+  }
+};
+// One k-chunk: ND fragment reads, then NX other memory instructions (class XMASK), laid over
+// the chunk's NM MFMAs.
+template <int ND, int NX, int XMASK, int NM>
+struct Pipeline {
+  static __device__ __forceinline__ void run() {
+    constexpr int MA = NX > 0 ? (NM + 1) / 2 : NM;
+    constexpr int MB = NM - MA;
+    Interleave<0x100, ND, MA, 0>::run();
+    if constexpr (MB > 0) Interleave<XMASK, NX, MB, 0>::run();
+  }
+};
+
 __device__ __forceinline__ float widen(float v) { return v; }
 __device__ __forceinline__ float widen(__bf16 v) { return static_cast<float>(v); }
 
@@ -195,9 +220,19 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
   const int w = blockIdx.x;
   const int logical = (w % 8) * p.chunks + w / 8;
   if (logical >= p.total) return;
-  const int tm_idx = logical % p.tilesM;
-  const int tn_idx = (logical / p.tilesM) % p.tilesN;
-  const int bat = logical / (p.tilesM * p.tilesN);
+  // Inside a replica, tiles go in bands of GROUP_M tile rows, m fastest inside a band: the
+  // workgroups running together then cover a compact block of the output, and the operand
+  // panels they share stay within one XCD's L2.
+  constexpr int GROUP_M = 8;
+  const int per_rep = p.tilesM * p.tilesN;
+  const int bat = logical / per_rep;
+  const int t = logical - bat * per_rep;
+  const int band = t / (GROUP_M * p.tilesN);
+  const int first_m = band * GROUP_M;
+  const int gsize = p.tilesM - first_m < GROUP_M ? p.tilesM - first_m : GROUP_M;
+  const int tin = t - band * GROUP_M * p.tilesN;
+  const int tm_idx = first_m + tin % gsize;
+  const int tn_idx = tin / gsize;
   const int m0 = tm_idx * BM, n0 = tn_idx * BN;
 
   const T* A = reinterpret_cast<const T*>(p.A) + (long long)bat * p.strideA;
@@ -222,65 +257,98 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
 
   TileLoader<T, BM, A_KMAJOR, BKU> la;
   TileLoader<T, BN, B_KMAJOR, BKU> lb;
+  constexpr int NKC = BKU / 2;                        // k-chunks (one MFMA depth each) per k-step
+  constexpr int ND = TM + TN;                         // LDS fragment reads per k-chunk
+  constexpr int NM = TM * TN * (UE == 4 ? 4 : 1);     // MFMAs per k-chunk
+  constexpr int NW = TileLoader<T, BM, A_KMAJOR, BKU>::NSTORE +
+                     TileLoader<T, BN, B_KMAJOR, BKU>::NSTORE;   // LDS writes per k-step
+  constexpr int NV = TileLoader<T, BM, A_KMAJOR, BKU>::NREG +
+                     TileLoader<T, BN, B_KMAJOR, BKU>::NREG;     // global loads per k-step
   const int ksteps = (p.Kd + BKU * UE - 1) / (BKU * UE);
-  la.load(rsrcA, p.ldA, m0, p.M, 0, p.Kd, tid);
-  lb.load(rsrcB, p.ldB, n0, p.N, 0, p.Kd, tid);
-  la.store(lds, tid);
-  lb.store(lds + A_UNITS, tid);
-  __syncthreads();
 
-  // LDS read positions of this lane (k-unit `h` of each k-chunk is added in the loop)
+  // LDS read positions of this lane (k-unit `h` of each k-chunk is added per chunk)
   int posA[TM], posB[TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i) posA[i] = h * (BM + 1) + swz<UE>(wm0 + i * 32 + l32);
 #pragma unroll
   for (int j = 0; j < TN; ++j) posB[j] = A_UNITS + h * (BN + 1) + swz<UE>(wn0 + j * 32 + l32);
 
-  for (int ks = 0; ks < ksteps; ++ks) {
+  u32x4 fa[2][TM], fb[2][TN];
+  auto read_frags = [&](const u32x4* stage, int kc, int buf) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[buf][i] = stage[posA[i] + kc * 2 * (BM + 1)];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[buf][j] = stage[posB[j] + kc * 2 * (BN + 1)];
+  };
+  auto mfma_chunk = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        if constexpr (UE == 4) {
+          const f32x4 a = __builtin_bit_cast(f32x4, fa[buf][i]);
+          const f32x4 b = __builtin_bit_cast(f32x4, fb[buf][j]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[e], a[e], acc[i][j], 0, 0, 0);
+        } else {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              __builtin_bit_cast(bf16x8, fb[buf][j]), __builtin_bit_cast(bf16x8, fa[buf][i]),
+              acc[i][j], 0, 0, 0);
+        }
+      }
+  };
+
+  // Software pipeline.  At the top of k-step ks: LDS buffer ks&1 holds tile ks, the registers
+  // of the loaders hold tile ks+1 (in flight), fragment buffer 0 holds k-chunk 0 of tile ks.
+  //   chunks 0..NKC-2: read the next chunk's fragments while the MFMAs of this one run; in
+  //                    the last of them also write tile ks+1 to the other LDS buffer;
+  //   barrier;
+  //   chunk NKC-1:     its MFMAs cover the barrier, the fragment reads of tile ks+1 and the
+  //                    issue of the global loads of tile ks+2.
+  // The scheduling hints fix that interleaving; left alone, the compiler sinks every LDS read
+  // next to its first use and the single wavefront per SIMD stalls on each one.
+  la.load(rsrcA, p.ldA, m0, p.M, 0, p.Kd, tid);
+  lb.load(rsrcB, p.ldB, n0, p.N, 0, p.Kd, tid);
+  la.store(lds, tid);
+  lb.store(lds + A_UNITS, tid);
+  la.load(rsrcA, p.ldA, m0, p.M, BKU, p.Kd, tid);      // past the end: reads as zeros
+  lb.load(rsrcB, p.ldB, n0, p.N, BKU, p.Kd, tid);
+  __syncthreads();
+  read_frags(lds, 0, 0);
+
+  for (int ks = 0; ks + 1 < ksteps; ++ks) {
     const u32x4* cur = lds + (ks & 1) * STAGE_UNITS;
     u32x4* nxt = lds + ((ks + 1) & 1) * STAGE_UNITS;
-    const bool more = ks + 1 < ksteps;
-    if (more) {
-      la.load(rsrcA, p.ldA, m0, p.M, (ks + 1) * BKU, p.Kd, tid);
-      lb.load(rsrcB, p.ldB, n0, p.N, (ks + 1) * BKU, p.Kd, tid);
-    }
-    u32x4 fa[2][TM], fb[2][TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) fa[0][i] = cur[posA[i]];
-#pragma unroll
-    for (int j = 0; j < TN; ++j) fb[0][j] = cur[posB[j]];
-#pragma unroll
-    for (int kc = 0; kc < BKU / 2; ++kc) {
-      const int c = kc & 1;
-      if (kc + 1 < BKU / 2) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fa[c ^ 1][i] = cur[posA[i] + (kc + 1) * 2 * (BM + 1)];
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fb[c ^ 1][j] = cur[posB[j] + (kc + 1) * 2 * (BN + 1)];
+    for (int kc = 0; kc + 1 < NKC; ++kc) {
+      read_frags(cur, kc + 1, (kc + 1) & 1);
+      mfma_chunk(kc & 1);
+      if (kc + 2 == NKC) {
+        la.store(nxt, tid);
+        lb.store(nxt + A_UNITS, tid);
+        Pipeline<ND, NW, 0x200, NM>::run();
+      } else {
+        Pipeline<ND, 0, 0, NM>::run();
       }
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          if constexpr (UE == 4) {
-            const f32x4 a = __builtin_bit_cast(f32x4, fa[c][i]);
-            const f32x4 b = __builtin_bit_cast(f32x4, fb[c][j]);
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[e], a[e], acc[i][j], 0, 0, 0);
-          } else {
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                __builtin_bit_cast(bf16x8, fb[c][j]), __builtin_bit_cast(bf16x8, fa[c][i]),
-                acc[i][j], 0, 0, 0);
-          }
-        }
-    }
-    if (more) {
-      la.store(nxt, tid);
-      lb.store(nxt + A_UNITS, tid);
     }
     __syncthreads();
+    read_frags(nxt, 0, 0);
+    mfma_chunk((NKC - 1) & 1);
+    la.load(rsrcA, p.ldA, m0, p.M, (ks + 2) * BKU, p.Kd, tid);
+    lb.load(rsrcB, p.ldB, n0, p.N, (ks + 2) * BKU, p.Kd, tid);
+    Pipeline<ND, NV, 0x020, NM>::run();
   }
+  {
+    const u32x4* cur = lds + ((ksteps - 1) & 1) * STAGE_UNITS;
+#pragma unroll
+    for (int kc = 0; kc < NKC; ++kc) {
+      if (kc + 1 < NKC) read_frags(cur, kc + 1, (kc + 1) & 1);
+      mfma_chunk(kc & 1);
+      if (kc + 1 < NKC) Pipeline<ND, 0, 0, NM>::run();
+    }
+  }
+  __syncthreads();
 
   // Epilogue.  With the swapped MFMA roles, accumulator element e of a 32x32 tile belongs to
   // row m = l32 and column n = (e/4)*8 + h*4 + e%4.  Stores straight from that layout would
@@ -420,7 +488,10 @@ int launch_layout(const GemmDesc& d, const GemmParams& p, hipStream_t s) {
 
 }  // namespace
 
-void set_gemm_tile_override(int code) { g_tile_override = code; }
+void set_gemm_tile_override(int code) {
+  g_use_ring = code < 100;          // codes >= 100 select the generic kernel with tile code-100
+  g_tile_override = code % 100;
+}
 
 int launch_gemm(const GemmDesc& d, hipStream_t s) {
   GemmParams p;
@@ -445,6 +516,7 @@ int launch_gemm(const GemmDesc& d, hipStream_t s) {
   if (rowsA * d.ldA * es >= 0x7FFFFFF0LL || rowsB * d.ldB * es >= 0x7FFFFFF0LL) return -1;
   if (d.in_bf16) {
     if ((d.strideA % 8) || (d.strideB % 8) || (d.strideC % 8)) return -1;
+    if (g_use_ring && launch_gemm_bf16(d, g_tile_override, s) == 0) return 0;
     if (d.out_bf16) return launch_layout<__bf16, __bf16>(d, p, s);
     return launch_layout<__bf16, float>(d, p, s);
   }

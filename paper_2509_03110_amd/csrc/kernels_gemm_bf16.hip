@@ -1,0 +1,451 @@
+// bf16 replica GEMMs with a four-stage LDS ring fed by direct global->LDS loads.
+//
+// Same contract as the generic kernel (C[m,n] = sum_k A(m,k) B(n,k), operands k-major or
+// m-major, batched over replicas), specialised for bf16 operands whose contraction length is a
+// multiple of 32.  No operand passes through registers on its way to LDS:
+//   * every thread issues `buffer_load_dwordx4 ... lds` instructions; a wavefront instruction
+//     fills 1 KiB of LDS in lane order, so the LDS image is fixed by which global address each
+//     lane asks for.  k-major tiles are stored [row][4 units of 16 B] with the unit index
+//     XOR-ed by (row/4)%4; m-major tiles are stored as they are in memory, [k][m], with the
+//     16-byte column unit XOR-ed by 2*(k%4).  Both swizzles are applied on the global side.
+//   * k-major fragments are one 128-bit LDS read; m-major fragments are two transposing LDS
+//     reads (ds_read_b64_tr_b16: within 16 lanes, lanes 4j..4j+3 address row j of a 4x16
+//     block and lane i receives column i), which delivers exactly the MFMA operand layout, so
+//     neither weights nor activations need a transposed copy or a register shuffle.
+//   * a k-step is 32 deep (two MFMA depths); three k-steps are in flight behind the one being
+//     multiplied (~96 KiB per compute unit), which is what hides HBM latency with a single
+//     wavefront per SIMD.  Each stage is its own LDS array so that the compiler's wait-count
+//     tracking can tell them apart; the wait that orders a stage's arrival before the
+//     workgroup barrier is explicit.
+#include "engine.h"
+
+namespace lsam {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int BK = 32;        // bf16 elements of k per stage
+constexpr int NSTAGE = 4;
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
+
+struct Bf16GemmParams {
+  const char* A; long long strideA; int ldA;
+  const char* B; long long strideB; int ldB;
+  char* C; long long strideC; int ldC;
+  int M, N, Kd, batch;
+  int tilesM, tilesN, total, chunks;
+  int epilogue;
+  const float* bias; long long strideBias;
+  const float* bias_dir; const float* bias_scale;
+  const char* mask; long long strideMask; int ldMask;
+};
+
+// s_waitcnt immediate: vmcnt = vm (0..63), lgkmcnt = lgkm (0..15), expcnt untouched.
+constexpr int waitcnt(int vm, int lgkm) {
+  return (vm & 0xF) | ((vm >> 4) << 14) | (0x7 << 4) | ((lgkm & 0xF) << 8);
+}
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, unsigned bytes) {
+  const unsigned long long a = reinterpret_cast<unsigned long long>(base);
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a);
+  const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
+  void* ptr = reinterpret_cast<void*>(((unsigned long long)hi << 32) | lo);
+  return __builtin_amdgcn_make_buffer_rsrc(ptr, 0, __builtin_amdgcn_readfirstlane(bytes),
+                                           0x00020000);
+}
+
+// One operand tile of R rows (of the output) by BK of k, as it lives in one LDS stage.
+template <int R, bool KMAJOR, int NFRAG>
+struct Operand {
+  static constexpr int BYTES = R * BK * 2;
+  static constexpr int NLOAD = BYTES / (kThreads * 16);       // load instructions per thread
+  static constexpr int NREAD = KMAJOR ? NFRAG : 2 * NFRAG;    // LDS reads per MFMA depth
+  unsigned goff[NLOAD];       // global byte offset of this lane's 16 bytes at k-step 0
+  unsigned kstep;             // bytes from one k-step to the next
+  unsigned lds_slot0;         // LDS byte offset (in the tile) of the wavefront's first 1 KiB chunk
+  // LDS byte offsets of the fragment reads.  k-major: [depth] for fragment 0, fragment t lies
+  // t*2048 bytes further (32 rows of 64 bytes; the swizzle repeats every 16 rows).
+  // m-major: [frag][depth][half].
+  unsigned rd[KMAJOR ? 1 : NFRAG][2][KMAJOR ? 1 : 2];
+
+  // row0: first output row (or column) of the tile in the operand; wrow0: first row of this
+  // wavefront's part inside the tile.
+  __device__ __forceinline__ void init(int ld, int row0, int wrow0, int tid) {
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, h = lane >> 5;
+    lds_slot0 = (unsigned)(wave * NLOAD) * 1024u;
+#pragma unroll
+    for (int j = 0; j < NLOAD; ++j) {
+      const int chunk = wave * NLOAD + j;
+      const int u = chunk * 64 + lane;          // 16-byte unit index inside the tile
+      if constexpr (KMAJOR) {
+        const int r = u >> 2, s = u & 3;
+        const int ku = s ^ ((r >> 2) & 3);
+        goff[j] = (unsigned)((row0 + r) * ld + ku * 8) * 2u;
+      } else {
+        constexpr int UPR = R / 8;               // units per k-row
+        const int kr = u / UPR, pos = u % UPR;
+        const int cu = pos ^ (2 * (kr & 3));
+        goff[j] = (unsigned)(kr * ld + row0 + cu * 8) * 2u;
+      }
+    }
+    kstep = KMAJOR ? (unsigned)BK * 2u : (unsigned)(BK * ld) * 2u;
+#pragma unroll
+    for (int t = 0; t < (KMAJOR ? 1 : NFRAG); ++t)
+#pragma unroll
+      for (int kc = 0; kc < 2; ++kc) {
+        if constexpr (KMAJOR) {
+          const int r = wrow0 + l32;
+          const int ku = kc * 2 + h;
+          rd[0][kc][0] = (unsigned)(r * 64 + ((ku ^ ((r >> 2) & 3)) * 16));
+        } else {
+          const int il = lane & 15, gq = lane >> 4;
+#pragma unroll
+          for (int kk = 0; kk < 2; ++kk) {
+            const int kr = kc * 16 + (gq >> 1) * 8 + kk * 4 + (il >> 2);
+            const int col = wrow0 + t * 32 + (gq & 1) * 16 + 4 * (il & 3);
+            const int cu = (col >> 3) ^ (2 * (kr & 3));
+            rd[t][kc][kk] = (unsigned)(kr * (R * 2) + cu * 16 + ((il & 1) * 8));
+          }
+        }
+      }
+  }
+
+  // Requests k-step `ks` of the tile into `tile`.  A step at or past `ksteps` is sent out of
+  // range on purpose: the stage then fills with zeros, which add nothing when multiplied.
+  __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rsrc, lds_byte* tile, int ks,
+                                        int ksteps) const {
+    const unsigned adv = ks < ksteps ? (unsigned)ks * kstep : 0x7FFFFFF0u;
+#pragma unroll
+    for (int j = 0; j < NLOAD; ++j)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(
+          rsrc, (__attribute__((address_space(3))) void*)(tile + lds_slot0 + j * 1024), 16,
+          ks < ksteps ? goff[j] + adv : 0x7FFFFFF0u, 0, 0, 0);
+  }
+
+  __device__ __forceinline__ void read(const lds_byte* tile, int kc, u32x4 (&f)[NFRAG]) const {
+#pragma unroll
+    for (int t = 0; t < NFRAG; ++t) {
+      if constexpr (KMAJOR) {
+        f[t] = *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(
+            tile + rd[0][kc][0] + t * 2048);
+      } else {
+#if defined(__HIP_DEVICE_COMPILE__)
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4*)(tile + rd[t][kc][0]));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4*)(tile + rd[t][kc][1]));
+        const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+        f[t][0] = l2[0]; f[t][1] = l2[1]; f[t][2] = h2[0]; f[t][3] = h2[1];
+#endif
+      }
+    }
+  }
+};
+
+template <int MASK, int N, int M, int I>
+struct Interleave {
+  static __device__ __forceinline__ void run() {
+    constexpr int ops = N * (I + 1) / M - N * I / M;
+    if constexpr (ops > 0) __builtin_amdgcn_sched_group_barrier(MASK, ops, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if constexpr (I + 1 < M) Interleave<MASK, N, M, I + 1>::run();
+  }
+};
+
+template <typename TC> struct Out;
+template <> struct Out<float> {
+  typedef f32x4 vec;
+  static __device__ __forceinline__ vec from(const f32x4& v) { return v; }
+  static __device__ __forceinline__ float one(float v) { return v; }
+};
+template <> struct Out<__bf16> {
+  typedef u32x2 vec;
+  static __device__ __forceinline__ vec from(const f32x4& v) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    bf16x2 lo = {static_cast<__bf16>(v[0]), static_cast<__bf16>(v[1])};
+    bf16x2 hi = {static_cast<__bf16>(v[2]), static_cast<__bf16>(v[3])};
+    vec o;
+    o[0] = __builtin_bit_cast(unsigned, lo);
+    o[1] = __builtin_bit_cast(unsigned, hi);
+    return o;
+  }
+  static __device__ __forceinline__ __bf16 one(float v) { return static_cast<__bf16>(v); }
+};
+
+template <typename TC, int BM, int BN, bool A_KMAJOR, bool B_KMAJOR, int OCC>
+__global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams p) {
+  constexpr int TM = BM / 64, TN = BN / 64;
+  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+  constexpr int PITCH = BN + 4;                               // epilogue staging pitch (floats)
+  constexpr int EPI_BYTES = 32 * PITCH * 4;
+  constexpr int STAGE_BYTES = A_BYTES + B_BYTES > EPI_BYTES ? A_BYTES + B_BYTES : EPI_BYTES;
+  __shared__ __attribute__((aligned(1024))) unsigned char st0[STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char st1[STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char st2[STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char st3[STAGE_BYTES];
+
+  const int w = blockIdx.x;
+  const int logical = (w % 8) * p.chunks + w / 8;    // contiguous tile range per XCD
+  if (logical >= p.total) return;
+  constexpr int GROUP_M = 8;
+  const int per_rep = p.tilesM * p.tilesN;
+  const int bat = logical / per_rep;
+  const int t_in = logical - bat * per_rep;
+  const int band = t_in / (GROUP_M * p.tilesN);
+  const int first_m = band * GROUP_M;
+  const int gsize = p.tilesM - first_m < GROUP_M ? p.tilesM - first_m : GROUP_M;
+  const int tin = t_in - band * GROUP_M * p.tilesN;
+  const int m0 = (first_m + tin % gsize) * BM, n0 = (tin / gsize) * BN;
+
+  const __bf16* A = reinterpret_cast<const __bf16*>(p.A) + (long long)bat * p.strideA;
+  const __bf16* B = reinterpret_cast<const __bf16*>(p.B) + (long long)bat * p.strideB;
+  const __amdgpu_buffer_rsrc_t rsrcA =
+      make_rsrc(A, (unsigned)((A_KMAJOR ? p.M : p.Kd) * p.ldA) * 2u);
+  const __amdgpu_buffer_rsrc_t rsrcB =
+      make_rsrc(B, (unsigned)((B_KMAJOR ? p.N : p.Kd) * p.ldB) * 2u);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
+  const int l32 = lane & 31, h = lane >> 5;
+
+  Operand<BM, A_KMAJOR, TM> oa;
+  Operand<BN, B_KMAJOR, TN> ob;
+  oa.init(p.ldA, m0, wm0, tid);
+  ob.init(p.ldB, n0, wn0, tid);
+  constexpr int NL = Operand<BM, A_KMAJOR, TM>::NLOAD + Operand<BN, B_KMAJOR, TN>::NLOAD;
+  constexpr int ND = Operand<BM, A_KMAJOR, TM>::NREAD + Operand<BN, B_KMAJOR, TN>::NREAD;
+  constexpr int NM = TM * TN;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  u32x4 fa[2][TM], fb[2][TN];
+  auto mfma_chunk = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+            __builtin_bit_cast(bf16x8, fb[buf][j]), __builtin_bit_cast(bf16x8, fa[buf][i]),
+            acc[i][j], 0, 0, 0);
+  };
+
+  const int ksteps = p.Kd / BK;
+  lds_byte* s0 = (lds_byte*)st0;
+  lds_byte* s1 = (lds_byte*)st1;
+  lds_byte* s2 = (lds_byte*)st2;
+  lds_byte* s3 = (lds_byte*)st3;
+
+  // Tiles past the last k-step are still requested (as zeros), which keeps the number of
+  // loads in flight, and so the wait counts, the same in every step, and lets the loop run
+  // in whole rounds of the four stages.
+  oa.issue(rsrcA, s0, 0, ksteps); ob.issue(rsrcB, s0 + A_BYTES, 0, ksteps);
+  oa.issue(rsrcA, s1, 1, ksteps); ob.issue(rsrcB, s1 + A_BYTES, 1, ksteps);
+  oa.issue(rsrcA, s2, 2, ksteps); ob.issue(rsrcB, s2 + A_BYTES, 2, ksteps);
+  oa.issue(rsrcA, s3, 3, ksteps); ob.issue(rsrcB, s3 + A_BYTES, 3, ksteps);
+  __builtin_amdgcn_s_waitcnt(waitcnt(3 * NL, 15));     // tile 0 has landed (this wavefront's part)
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  oa.read(s0, 0, fa[0]);
+  ob.read(s0 + A_BYTES, 0, fb[0]);
+
+  // One k-step on stage CUR; NEXT holds the following tile; the tile three steps ahead is
+  // requested into CUR as soon as every wavefront has taken its last fragment out of it.
+#define LSAM_GEMM_STEP(CUR, NEXT)                                                         \
+  {                                                                                       \
+    oa.read(CUR, 1, fa[1]);                                                               \
+    ob.read(CUR + A_BYTES, 1, fb[1]);                                                     \
+    mfma_chunk(0);                                                                        \
+    Interleave<0x100, ND, NM, 0>::run();                                                  \
+    __builtin_amdgcn_s_waitcnt(waitcnt(2 * NL, 0));                                       \
+    asm volatile("" ::: "memory");                                                        \
+    __builtin_amdgcn_s_barrier();                                                         \
+    asm volatile("" ::: "memory");                                                        \
+    oa.issue(rsrcA, CUR, ks + 4, ksteps);                                                 \
+    ob.issue(rsrcB, CUR + A_BYTES, ks + 4, ksteps);                                       \
+    oa.read(NEXT, 0, fa[0]);                                                              \
+    ob.read(NEXT + A_BYTES, 0, fb[0]);                                                    \
+    mfma_chunk(1);                                                                        \
+    Interleave<0x120, ND + NL, NM, 0>::run();                                             \
+    ++ks;                                                                                 \
+  }
+
+  for (int ks = 0; ks < ksteps;) {
+    LSAM_GEMM_STEP(s0, s1)
+    LSAM_GEMM_STEP(s1, s2)
+    LSAM_GEMM_STEP(s2, s3)
+    LSAM_GEMM_STEP(s3, s0)
+  }
+#undef LSAM_GEMM_STEP
+  __builtin_amdgcn_s_waitcnt(waitcnt(0, 0));           // nothing may still be writing LDS
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+
+  // Epilogue: accumulators -> LDS -> whole rows (element e of a 32x32 tile is row m = l32,
+  // column n = (e/4)*8 + h*4 + e%4 because the MFMA was issued with rows <- B, columns <- A).
+  TC* C = reinterpret_cast<TC*>(p.C) + (long long)bat * p.strideC;
+  const float* bias = p.bias ? p.bias + (long long)bat * p.strideBias : nullptr;
+  const float* bias_dir = p.bias_dir ? p.bias_dir + (long long)bat * p.strideBias : nullptr;
+  const float bias_sc = p.bias_dir ? p.bias_scale[bat] : 0.f;
+  const __bf16* mask = p.mask ? reinterpret_cast<const __bf16*>(p.mask) + (long long)bat * p.strideMask
+                              : nullptr;
+  const bool has_bias = p.epilogue == EPI_BIAS || p.epilogue == EPI_BIAS_RELU;
+  const bool relu = p.epilogue == EPI_BIAS_RELU;
+  const bool masked = p.epilogue == EPI_MASK;
+  typedef typename Out<TC>::vec cvec;
+  constexpr int LANES_PER_ROW = BN / 4;
+  constexpr int ROWS_PER_PASS = kThreads / LANES_PER_ROW;
+  float* stage_w = reinterpret_cast<float*>((wave >> 1) ? st1 : st0);   // written by this wavefront row
+  const int c4 = (tid % LANES_PER_ROW) * 4;
+  const int rsub = tid / LANES_PER_ROW;
+  const int n = n0 + c4;
+  f32x4 bv = {0.f, 0.f, 0.f, 0.f};
+  if (has_bias) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (n + r < p.N) {
+        bv[r] = bias[n + r];
+        if (bias_dir) bv[r] = bv[r] + bias_sc * bias_dir[n + r];
+      }
+  }
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        f32x4 v;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = acc[i][j][q * 4 + r];
+        *reinterpret_cast<f32x4*>(stage_w + l32 * PITCH + wn0 + j * 32 + q * 8 + h * 4) = v;
+      }
+    __syncthreads();
+    for (int rr = rsub; rr < 64; rr += ROWS_PER_PASS) {
+      const float* stage_r = reinterpret_cast<const float*>((rr >> 5) ? st1 : st0);
+      const int m = m0 + (rr >> 5) * (BM / 2) + i * 32 + (rr & 31);
+      if (m < p.M && n < p.N) {
+        f32x4 v = *reinterpret_cast<const f32x4*>(stage_r + (rr & 31) * PITCH + c4);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          v[r] += bv[r];
+          if (relu) v[r] = v[r] > 0.f ? v[r] : 0.f;
+        }
+        if (n + 3 < p.N) {
+          if (masked) {
+            const u32x2 mk = *reinterpret_cast<const u32x2*>(mask + (long long)m * p.ldMask + n);
+            const __bf16* me = reinterpret_cast<const __bf16*>(&mk);
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              if (!(static_cast<float>(me[r]) > 0.f)) v[r] = 0.f;
+          }
+          *reinterpret_cast<cvec*>(C + (long long)m * p.ldC + n) = Out<TC>::from(v);
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (n + r < p.N) {
+              float o = v[r];
+              if (masked && !(static_cast<float>(mask[(long long)m * p.ldMask + n + r]) > 0.f))
+                o = 0.f;
+              C[(long long)m * p.ldC + n + r] = Out<TC>::one(o);
+            }
+        }
+      }
+    }
+    if (i + 1 < TM) __syncthreads();
+  }
+}
+
+// Every specialisation that can be launched is instantiated explicitly (the host-side launch
+// stubs of implicit instantiations of this kernel were not all emitted by the compiler).
+#define LSAM_INSTANTIATE(TC, AK, BK_)                                                         \
+  template __global__ void gemm_bf16_kernel<TC, 256, 256, AK, BK_, 1>(Bf16GemmParams);         \
+  template __global__ void gemm_bf16_kernel<TC, 128, 128, AK, BK_, 2>(Bf16GemmParams);
+LSAM_INSTANTIATE(float, true, true)
+LSAM_INSTANTIATE(float, true, false)
+LSAM_INSTANTIATE(float, false, false)
+LSAM_INSTANTIATE(__bf16, true, true)
+LSAM_INSTANTIATE(__bf16, true, false)
+LSAM_INSTANTIATE(__bf16, false, false)
+#undef LSAM_INSTANTIATE
+
+template <typename TC, int BM, int BN, bool AK, bool BK_>
+int launch_one(const Bf16GemmParams& p0, hipStream_t s) {
+  constexpr int OCC = (BM * BN >= 256 * 256) ? 1 : 2;
+  Bf16GemmParams p = p0;
+  p.tilesM = (p.M + BM - 1) / BM;
+  p.tilesN = (p.N + BN - 1) / BN;
+  p.total = p.tilesM * p.tilesN * p.batch;
+  p.chunks = (p.total + 7) / 8;
+  gemm_bf16_kernel<TC, BM, BN, AK, BK_, OCC><<<p.chunks * 8, kThreads, 0, s>>>(p);
+  return 0;
+}
+
+template <typename TC, bool AK, bool BK_>
+int launch_tiled(const Bf16GemmParams& p, int tile, hipStream_t s) {
+  if (tile == 256) return launch_one<TC, 256, 256, AK, BK_>(p, s);
+  return launch_one<TC, 128, 128, AK, BK_>(p, s);
+}
+
+template <typename TC>
+int launch_layout(const GemmDesc& d, const Bf16GemmParams& p, int tile, hipStream_t s) {
+  if (d.a_kmajor && d.b_kmajor) return launch_tiled<TC, true, true>(p, tile, s);
+  if (d.a_kmajor && !d.b_kmajor) return launch_tiled<TC, true, false>(p, tile, s);
+  if (!d.a_kmajor && !d.b_kmajor) return launch_tiled<TC, false, false>(p, tile, s);
+  return -1;
+}
+
+}  // namespace
+
+// Returns 1 if this shape is not handled here (the caller then uses the generic kernel),
+// 0 after a launch.
+int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s) {
+  if (!d.in_bf16 || d.Kd % BK != 0) return 1;
+  auto tiles = [&](int bm, int bn) {
+    return (long long)((d.M + bm - 1) / bm) * ((d.N + bn - 1) / bn) * d.batch;
+  };
+  int tile = 0;
+  if (tile_override == 1) tile = 256;
+  else if (tile_override == 4) tile = 128;
+  else if (tile_override != 0) return 1;
+  // By measurement on MI355X: with enough 256x256 tiles to fill the chip twice this kernel wins
+  // for all three GEMMs; below that it still wins for dW (both operands m-major: no register
+  // transposes), while the generic kernel's deeper k-steps suit 128x128 tiles better when an
+  // operand is k-major.
+  else if (d.M >= 256 && d.N >= 256 && tiles(256, 256) >= 512) tile = 256;
+  else if (d.M >= 128 && d.N >= 128 && !d.a_kmajor && !d.b_kmajor) tile = 128;
+  else return 1;
+  // 32-bit byte offsets: the farthest address a lane can form must stay below 2^31
+  const long long rowsA = d.a_kmajor ? d.M + tile : d.Kd + 8 * BK;
+  const long long rowsB = d.b_kmajor ? d.N + tile : d.Kd + 8 * BK;
+  if ((rowsA + 1) * d.ldA * 2 + 4096 >= 0x7FFFFFFFLL || (rowsB + 1) * d.ldB * 2 + 4096 >= 0x7FFFFFFFLL)
+    return 1;
+  Bf16GemmParams p;
+  p.A = (const char*)d.A; p.strideA = d.strideA; p.ldA = d.ldA;
+  p.B = (const char*)d.B; p.strideB = d.strideB; p.ldB = d.ldB;
+  p.C = (char*)d.C; p.strideC = d.strideC; p.ldC = d.ldC;
+  p.M = d.M; p.N = d.N; p.Kd = d.Kd; p.batch = d.batch;
+  p.tilesM = p.tilesN = p.total = p.chunks = 0;
+  p.epilogue = d.epilogue;
+  p.bias = d.bias; p.strideBias = d.strideBias;
+  p.bias_dir = d.bias_dir; p.bias_scale = d.bias_scale;
+  p.mask = (const char*)d.mask; p.strideMask = d.strideMask; p.ldMask = d.ldMask;
+  const int rc = d.out_bf16 ? launch_layout<__bf16>(d, p, tile, s) : launch_layout<float>(d, p, tile, s);
+  return rc == 0 ? 0 : 1;
+}
+
+}  // namespace lsam

@@ -229,6 +229,16 @@ def test_bf16_ragged_shapes():
     run_mlp(w, w.steps, 2e-2, 2e-2, margin=False, tol_flip=1e-1, anchor_after=2)
 
 
+def test_bf16_ring_kernel_ragged_tiles_and_short_contractions():
+    # dW shapes that take the direct-to-LDS kernel with 128x128 tiles while leaving ragged row
+    # and column tiles (160, 288, 352 are not multiples of 128) and a k-step count (5 steps of
+    # 32) that is not a multiple of the four-stage ring.
+    w = workloads.WORKLOADS["cfg3"].scaled(name="ring16", K=2, dims=(352, 288, 288, 160), batch=160,
+                                           tau=(2, 3), n_classes=160, steps=4, batch_pool=0)
+    run_mlp(w, w.steps, 2e-2, 2e-2, margin=True)
+    run_mlp(w, w.steps, 2e-2, 2e-2, margin=False, tol_flip=1e-1, anchor_after=2)
+
+
 def test_wrong_mode_calls_fail_cleanly():
     w = workloads.WORKLOADS["cfg4"].scaled(K=1, d_raw=64, tau=(1,))
     g, o = make_pair(w)

@@ -75,8 +75,10 @@ struct GemmDesc {
   const float* bias; int64_t strideBias;          // EPI_BIAS*: bias[n]
   const float* bias_dir; const float* bias_scale; // if set: bias[n] + bias_scale[k] * bias_dir[n]
   const void* mask; int64_t strideMask; int ldMask; // EPI_MASK: keep where mask[m,n] > 0 (operand dtype)
+  float* splitk_ws; size_t splitk_bytes;            // scratch for split-K partial sums (may be null)
 };
 int launch_gemm(const GemmDesc& d, hipStream_t s);   // 0 ok, <0 unsupported shape
+size_t gemm_splitk_bytes(const GemmDesc& d);          // scratch this GEMM would like (0: none)
 // bf16 fast path (direct-to-LDS ring); returns 1 when the shape is left to the generic kernel.
 int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s);
 void set_gemm_tile_override(int code);               // tuning hook: 0 = choose by shape

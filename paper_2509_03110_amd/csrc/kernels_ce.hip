@@ -67,23 +67,33 @@ template <> __device__ __forceinline__ float get<__bf16>(const __bf16* p) {
   return static_cast<float>(*p);
 }
 
-// db[k][n] = sum_b dz[k][b][n]; one thread per column, rows summed in order.
+// db[k][n] = sum_b dz[k][b][n].  A workgroup owns 64 adjacent columns of one replica; its four
+// wavefronts take every fourth row (lane = column, so a row is one coalesced read), each lane
+// keeps four partial sums, and the partials are combined in a fixed order through LDS.
 template <typename TD>
 __global__ __launch_bounds__(kThreads) void bias_grad_kernel(const TD* __restrict__ dz, int ld,
                                                             float* __restrict__ db,
                                                             long long strideDb, int B, int N) {
+  __shared__ float part[kWaves][64];
   const int k = blockIdx.y;
-  const int n = blockIdx.x * kThreads + threadIdx.x;
-  if (n >= N) return;
-  const TD* p = dz + (long long)k * B * ld + n;
-  float s0 = 0.f, s1 = 0.f;
-  int b = 0;
-  for (; b + 1 < B; b += 2) {
-    s0 += get<TD>(p + (long long)b * ld);
-    s1 += get<TD>(p + (long long)(b + 1) * ld);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = blockIdx.x * 64 + lane;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  if (n < N) {
+    const TD* p = dz + (long long)k * B * ld + n;
+    int b = wave;
+    for (; b + 3 * kWaves < B; b += 4 * kWaves) {
+      s0 += get<TD>(p + (long long)b * ld);
+      s1 += get<TD>(p + (long long)(b + kWaves) * ld);
+      s2 += get<TD>(p + (long long)(b + 2 * kWaves) * ld);
+      s3 += get<TD>(p + (long long)(b + 3 * kWaves) * ld);
+    }
+    for (; b < B; b += kWaves) s0 += get<TD>(p + (long long)b * ld);
   }
-  if (b < B) s0 += get<TD>(p + (long long)b * ld);
-  db[(long long)k * strideDb + n] = s0 + s1;
+  part[wave][lane] = (s0 + s1) + (s2 + s3);
+  __syncthreads();
+  if (wave == 0 && n < N)
+    db[(long long)k * strideDb + n] = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
 }
 
 }  // namespace
@@ -102,7 +112,7 @@ void launch_softmax_ce(const float* logits, int ld, const int32_t* labels, void*
 
 void launch_bias_grad(const void* dz, int ld, int dz_bf16, float* db, int64_t strideDb, int K,
                       int B, int N, hipStream_t s) {
-  dim3 grid((N + kThreads - 1) / kThreads, K);
+  dim3 grid((N + 63) / 64, K);
   if (dz_bf16)
     bias_grad_kernel<__bf16><<<grid, kThreads, 0, s>>>((const __bf16*)dz, ld, db, strideDb, B, N);
   else

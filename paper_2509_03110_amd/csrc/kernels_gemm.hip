@@ -41,6 +41,10 @@ struct GemmParams {
   const float* bias; long long strideBias;
   const float* bias_dir; const float* bias_scale;
   const char* mask; long long strideMask; int ldMask;
+  // split-K: the contraction is cut into `splits` ranges of `steps_per_split` k-steps, each
+  // range owned by its own workgroup, which writes raw fp32 sums to partial[split]
+  float* partial; long long strideSplit; int ldP;
+  int splits, steps_per_split;
 };
 
 int g_tile_override = 0;   // tuning hook, 0 = choose by shape
@@ -218,8 +222,10 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
   // XCDs; remap so that each XCD walks a contiguous range of tiles (tiles that share a
   // weight panel then share one L2).
   const int w = blockIdx.x;
-  const int logical = (w % 8) * p.chunks + w / 8;
-  if (logical >= p.total) return;
+  const int slot = (w % 8) * p.chunks + w / 8;
+  if (slot >= p.total) return;
+  const int split = slot % p.splits;
+  const int logical = slot / p.splits;
   // Inside a replica, tiles go in bands of GROUP_M tile rows, m fastest inside a band: the
   // workgroups running together then cover a compact block of the output, and the operand
   // panels they share stay within one XCD's L2.
@@ -264,7 +270,10 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
                      TileLoader<T, BN, B_KMAJOR, BKU>::NSTORE;   // LDS writes per k-step
   constexpr int NV = TileLoader<T, BM, A_KMAJOR, BKU>::NREG +
                      TileLoader<T, BN, B_KMAJOR, BKU>::NREG;     // global loads per k-step
-  const int ksteps = (p.Kd + BKU * UE - 1) / (BKU * UE);
+  const int ksteps_all = (p.Kd + BKU * UE - 1) / (BKU * UE);
+  const int kbeg = split * p.steps_per_split;                  // first k-step of this split
+  const int ksteps = ksteps_all - kbeg < p.steps_per_split ? ksteps_all - kbeg : p.steps_per_split;
+  const int kb = kbeg * BKU;
 
   // LDS read positions of this lane (k-unit `h` of each k-chunk is added per chunk)
   int posA[TM], posB[TN];
@@ -308,12 +317,12 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
   //                    issue of the global loads of tile ks+2.
   // The scheduling hints fix that interleaving; left alone, the compiler sinks every LDS read
   // next to its first use and the single wavefront per SIMD stalls on each one.
-  la.load(rsrcA, p.ldA, m0, p.M, 0, p.Kd, tid);
-  lb.load(rsrcB, p.ldB, n0, p.N, 0, p.Kd, tid);
+  la.load(rsrcA, p.ldA, m0, p.M, kb, p.Kd, tid);
+  lb.load(rsrcB, p.ldB, n0, p.N, kb, p.Kd, tid);
   la.store(lds, tid);
   lb.store(lds + A_UNITS, tid);
-  la.load(rsrcA, p.ldA, m0, p.M, BKU, p.Kd, tid);      // past the end: reads as zeros
-  lb.load(rsrcB, p.ldB, n0, p.N, BKU, p.Kd, tid);
+  la.load(rsrcA, p.ldA, m0, p.M, kb + BKU, p.Kd, tid);      // past the end: reads as zeros
+  lb.load(rsrcB, p.ldB, n0, p.N, kb + BKU, p.Kd, tid);
   __syncthreads();
   read_frags(lds, 0, 0);
 
@@ -335,8 +344,8 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
     __syncthreads();
     read_frags(nxt, 0, 0);
     mfma_chunk((NKC - 1) & 1);
-    la.load(rsrcA, p.ldA, m0, p.M, (ks + 2) * BKU, p.Kd, tid);
-    lb.load(rsrcB, p.ldB, n0, p.N, (ks + 2) * BKU, p.Kd, tid);
+    la.load(rsrcA, p.ldA, m0, p.M, kb + (ks + 2) * BKU, p.Kd, tid);
+    lb.load(rsrcB, p.ldB, n0, p.N, kb + (ks + 2) * BKU, p.Kd, tid);
     Pipeline<ND, NV, 0x020, NM>::run();
   }
   {
@@ -355,15 +364,19 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
   // scatter 16-byte pieces over 32 rows per instruction; instead the tile is passed through
   // LDS (now free) 64 rows at a time and written out as whole rows, consecutive lanes on
   // consecutive 16 bytes, which is also how bias and the ReLU mask are read.
-  TC* C = reinterpret_cast<TC*>(p.C) + (long long)bat * p.strideC;
+  const bool split_mode = p.splits > 1;     // raw partial sums; bias/ReLU/mask wait for the reduce
+  TC* C = split_mode ? reinterpret_cast<TC*>(p.partial + (long long)split * p.strideSplit +
+                                             (long long)bat * p.M * p.ldP)
+                     : reinterpret_cast<TC*>(p.C) + (long long)bat * p.strideC;
+  const int ldC = split_mode ? p.ldP : p.ldC;
   const float* bias = p.bias ? p.bias + (long long)bat * p.strideBias : nullptr;
   const float* bias_dir = p.bias_dir ? p.bias_dir + (long long)bat * p.strideBias : nullptr;
   const float bias_sc = p.bias_dir ? p.bias_scale[bat] : 0.f;
   const T* mask = p.mask ? reinterpret_cast<const T*>(p.mask) + (long long)bat * p.strideMask
                          : nullptr;
-  const bool has_bias = p.epilogue == EPI_BIAS || p.epilogue == EPI_BIAS_RELU;
-  const bool relu = p.epilogue == EPI_BIAS_RELU;
-  const bool masked = p.epilogue == EPI_MASK;
+  const bool has_bias = !split_mode && (p.epilogue == EPI_BIAS || p.epilogue == EPI_BIAS_RELU);
+  const bool relu = !split_mode && p.epilogue == EPI_BIAS_RELU;
+  const bool masked = !split_mode && p.epilogue == EPI_MASK;
   typedef typename Pack<TC>::vec cvec;
   typedef typename Pack<T>::vec mvec;
   constexpr int PITCH = BN + 4;                 // floats; +4 keeps the 16-byte writes off one bank
@@ -414,14 +427,14 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
             for (int r = 0; r < 4; ++r)
               if (!(widen(me[r]) > 0.f)) v[r] = 0.f;
           }
-          *reinterpret_cast<cvec*>(C + (long long)m * p.ldC + n) = Pack<TC>::from(v);
+          *reinterpret_cast<cvec*>(C + (long long)m * ldC + n) = Pack<TC>::from(v);
         } else {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
             if (n + r < p.N) {
               float o = v[r];
               if (masked && !(widen(mask[(long long)m * p.ldMask + n + r]) > 0.f)) o = 0.f;
-              C[(long long)m * p.ldC + n + r] = Pack<TC>::one(o);
+              C[(long long)m * ldC + n + r] = Pack<TC>::one(o);
             }
         }
       }
@@ -430,13 +443,92 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
   }
 }
 
+// Sums the split-K partials in split order and applies the epilogue the GEMM skipped.
+__global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(GemmParams p) {
+  const int n4 = p.ldP / 4;
+  const long long total = (long long)p.batch * p.M * n4;
+  const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= total) return;
+  const int c = (int)(idx % n4) * 4;
+  const long long row = idx / n4;             // bat * M + m
+  const int m = (int)(row % p.M), bat = (int)(row / p.M);
+  if (c >= p.N) return;
+  f32x4 v = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < p.splits; ++s)
+    v += *reinterpret_cast<const f32x4*>(p.partial + (long long)s * p.strideSplit + row * p.ldP + c);
+  const bool has_bias = p.epilogue == EPI_BIAS || p.epilogue == EPI_BIAS_RELU;
+  float* C = reinterpret_cast<float*>(p.C) + (long long)bat * p.strideC + (long long)m * p.ldC;
+  const float* mask = p.mask ? reinterpret_cast<const float*>(p.mask) + (long long)bat * p.strideMask +
+                                   (long long)m * p.ldMask
+                             : nullptr;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int n = c + r;
+    if (n >= p.N) break;
+    float o = v[r];
+    if (has_bias) {
+      float bv = p.bias[(long long)bat * p.strideBias + n];
+      if (p.bias_dir) bv = bv + p.bias_scale[bat] * p.bias_dir[(long long)bat * p.strideBias + n];
+      o += bv;
+    }
+    if (p.epilogue == EPI_BIAS_RELU) o = o > 0.f ? o : 0.f;
+    if (p.epilogue == EPI_MASK && !(mask[n] > 0.f)) o = 0.f;
+    C[n] = o;
+  }
+}
+
+// Tile shape and split of the contraction for one GEMM, chosen from measurements on MI355X at
+// the workload shapes: the forward GEMM (both operands k-major, few staging registers) runs
+// best as 256x128 tiles with two workgroups per compute unit; the GEMMs with transposing loads
+// as 256x256 with one; smaller tiles only where the larger ones would leave compute units
+// idle.  When even 64x64 or 128x128 tiles give fewer than two workgroups per compute unit and
+// the contraction is long (fp32 configurations with small batches), the contraction is split
+// so that every SIMD has work; the partial sums are reduced in a fixed order.
+struct Plan {
+  int bm, bn, bku;
+  int splits, steps_per_split, ldP;
+  size_t ws_bytes;
+};
+
+Plan make_plan(const GemmDesc& d, int tile_override) {
+  auto tiles = [&](int bm, int bn) {
+    return (long long)((d.M + bm - 1) / bm) * ((d.N + bn - 1) / bn) * d.batch;
+  };
+  Plan pl{64, 64, 8, 1, 0, 0, 0};
+  const bool kk = d.a_kmajor && d.b_kmajor;
+  if (tile_override == 1) { pl.bm = 256; pl.bn = 256; }
+  else if (tile_override == 2) { pl.bm = 256; pl.bn = 128; pl.bku = 4; }
+  else if (tile_override == 4) { pl.bm = 128; pl.bn = 128; }
+  else if (tile_override == 5) { pl.bm = 64; pl.bn = 64; }
+  else if (kk && d.M >= 256 && d.N >= 128 && tiles(256, 128) >= 512) { pl.bm = 256; pl.bn = 128; pl.bku = 4; }
+  else if (d.M >= 256 && d.N >= 256 && tiles(256, 256) >= 512) { pl.bm = 256; pl.bn = 256; }
+  else if (d.M >= 128 && d.N >= 128 && tiles(128, 128) >= 256) { pl.bm = 128; pl.bn = 128; }
+  const int ue = d.in_bf16 ? 8 : 4;
+  const int ksteps = (d.Kd + pl.bku * ue - 1) / (pl.bku * ue);
+  pl.steps_per_split = ksteps;
+  const long long nt = tiles(pl.bm, pl.bn);
+  if (!d.out_bf16 && !d.in_bf16 && nt < 512 && ksteps >= 8) {
+    int want = (int)((512 + nt - 1) / nt);
+    int cap = ksteps / 4;
+    int sp = want < cap ? want : cap;
+    if (sp > 16) sp = 16;
+    if (sp > 1) {
+      pl.steps_per_split = (ksteps + sp - 1) / sp;
+      pl.splits = (ksteps + pl.steps_per_split - 1) / pl.steps_per_split;
+      pl.ldP = (d.N + 3) / 4 * 4;
+      pl.ws_bytes = (size_t)pl.splits * d.batch * d.M * pl.ldP * 4;
+    }
+  }
+  return pl;
+}
+
 template <typename T, typename TC, int BM, int BN, int BKU, bool AK, bool BK_>
 int launch_one(const GemmParams& p0, hipStream_t s) {
   constexpr int OCC = (BM * BN >= 256 * 256) ? 1 : 2;
   GemmParams p = p0;
   p.tilesM = (p.M + BM - 1) / BM;
   p.tilesN = (p.N + BN - 1) / BN;
-  p.total = p.tilesM * p.tilesN * p.batch;
+  p.total = p.tilesM * p.tilesN * p.batch * p.splits;
   p.chunks = (p.total + 7) / 8;
   const size_t loop_smem = (size_t)2 * BKU * ((BM + 1) + (BN + 1)) * 16;
   const size_t epi_smem = (size_t)64 * (BN + 4) * 4;
@@ -450,43 +542,32 @@ int launch_one(const GemmParams& p0, hipStream_t s) {
     attr_set = true;
   }
   kern<<<p.chunks * 8, kThreads, smem, s>>>(p);
+  if (p.splits > 1) {
+    const long long total = (long long)p.batch * p.M * (p.ldP / 4);
+    splitk_reduce_kernel<<<(unsigned)((total + kThreads - 1) / kThreads), kThreads, 0, s>>>(p);
+  }
   return 0;
 }
 
 template <typename T, typename TC, bool AK, bool BK_>
-int launch_tiled(const GemmParams& p, hipStream_t s) {
-  auto tiles = [&](int bm, int bn) {
-    return (long long)((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn) * p.batch;
-  };
-  switch (g_tile_override) {
-    case 1: return launch_one<T, TC, 256, 256, 8, AK, BK_>(p, s);
-    case 2: return launch_one<T, TC, 256, 128, 4, AK, BK_>(p, s);
-    case 4: return launch_one<T, TC, 128, 128, 8, AK, BK_>(p, s);
-    case 5: return launch_one<T, TC, 64, 64, 8, AK, BK_>(p, s);
-    default: break;
-  }
-  // Tile choice, from measurements on MI355X at the workload shapes: the forward GEMM (both
-  // operands k-major, few staging registers) runs best as 256x128 tiles with two workgroups
-  // per compute unit; the GEMMs with transposing loads as 256x256 with one.  Smaller tiles
-  // only where the larger ones would leave compute units idle.
-  if (AK && BK_ && p.M >= 256 && p.N >= 128 && tiles(256, 128) >= 512)
-    return launch_one<T, TC, 256, 128, 4, AK, BK_>(p, s);
-  if (p.M >= 256 && p.N >= 256 && tiles(256, 256) >= 512)
-    return launch_one<T, TC, 256, 256, 8, AK, BK_>(p, s);
-  if (p.M >= 128 && p.N >= 128 && tiles(128, 128) >= 256)
-    return launch_one<T, TC, 128, 128, 8, AK, BK_>(p, s);
+int launch_tiled(const GemmParams& p, const Plan& pl, hipStream_t s) {
+  if (pl.bm == 256 && pl.bn == 128) return launch_one<T, TC, 256, 128, 4, AK, BK_>(p, s);
+  if (pl.bm == 256) return launch_one<T, TC, 256, 256, 8, AK, BK_>(p, s);
+  if (pl.bm == 128) return launch_one<T, TC, 128, 128, 8, AK, BK_>(p, s);
   return launch_one<T, TC, 64, 64, 8, AK, BK_>(p, s);
 }
 
 template <typename T, typename TC>
-int launch_layout(const GemmDesc& d, const GemmParams& p, hipStream_t s) {
-  if (d.a_kmajor && d.b_kmajor) return launch_tiled<T, TC, true, true>(p, s);
-  if (d.a_kmajor && !d.b_kmajor) return launch_tiled<T, TC, true, false>(p, s);
-  if (!d.a_kmajor && !d.b_kmajor) return launch_tiled<T, TC, false, false>(p, s);
+int launch_layout(const GemmDesc& d, const GemmParams& p, const Plan& pl, hipStream_t s) {
+  if (d.a_kmajor && d.b_kmajor) return launch_tiled<T, TC, true, true>(p, pl, s);
+  if (d.a_kmajor && !d.b_kmajor) return launch_tiled<T, TC, true, false>(p, pl, s);
+  if (!d.a_kmajor && !d.b_kmajor) return launch_tiled<T, TC, false, false>(p, pl, s);
   return -1;
 }
 
 }  // namespace
+
+size_t gemm_splitk_bytes(const GemmDesc& d) { return make_plan(d, 0).ws_bytes; }
 
 void set_gemm_tile_override(int code) {
   g_use_ring = code < 100;          // codes >= 100 select the generic kernel with tile code-100
@@ -504,6 +585,7 @@ int launch_gemm(const GemmDesc& d, hipStream_t s) {
   p.bias = d.bias; p.strideBias = d.strideBias;
   p.bias_dir = d.bias_dir; p.bias_scale = d.bias_scale;
   p.mask = (const char*)d.mask; p.strideMask = d.strideMask; p.ldMask = d.ldMask;
+  p.partial = nullptr; p.strideSplit = 0; p.ldP = 0; p.splits = 1; p.steps_per_split = 1 << 30;
   if (d.M <= 0 || d.N <= 0 || d.Kd <= 0 || d.batch <= 0) return -1;
   // 16-byte units: pitches must be multiples of 8 elements and bases 16-byte aligned.
   if ((d.ldA % 8) || (d.ldB % 8) || (d.ldC % 8) || ((uintptr_t)d.A & 15) ||
@@ -517,12 +599,22 @@ int launch_gemm(const GemmDesc& d, hipStream_t s) {
   if (d.in_bf16) {
     if ((d.strideA % 8) || (d.strideB % 8) || (d.strideC % 8)) return -1;
     if (g_use_ring && launch_gemm_bf16(d, g_tile_override, s) == 0) return 0;
-    if (d.out_bf16) return launch_layout<__bf16, __bf16>(d, p, s);
-    return launch_layout<__bf16, float>(d, p, s);
+    const Plan pl = make_plan(d, g_tile_override);
+    if (d.out_bf16) return launch_layout<__bf16, __bf16>(d, p, pl, s);
+    return launch_layout<__bf16, float>(d, p, pl, s);
   }
   if ((d.strideA % 4) || (d.strideB % 4) || (d.strideC % 4)) return -1;
   if (d.out_bf16) return -1;
-  return launch_layout<float, float>(d, p, s);
+  Plan pl = make_plan(d, g_tile_override);
+  if (pl.splits > 1 && d.splitk_ws != nullptr && d.splitk_bytes >= pl.ws_bytes &&
+      ((uintptr_t)d.splitk_ws & 15) == 0) {
+    p.partial = d.splitk_ws;
+    p.splits = pl.splits;
+    p.steps_per_split = pl.steps_per_split;
+    p.ldP = pl.ldP;
+    p.strideSplit = (long long)d.batch * d.M * pl.ldP;
+  }
+  return launch_layout<float, float>(d, p, pl, s);
 }
 
 }  // namespace lsam

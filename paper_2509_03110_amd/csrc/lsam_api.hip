@@ -1,5 +1,6 @@
 // Host engine behind include/lsam.h: configuration checks, workspace carve-up, the integer
 // communication schedule, and the kernel sequence of one LSAM step / one center update.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -109,7 +110,7 @@ struct Layout {
   int nblk = 1;
   // byte offsets into the workspace
   size_t x = 0, g = 0, v = 0, S = 0, xt = 0, y = 0, gprev = 0, partials = 0, norms = 0, scale = 0,
-         loss_rows = 0, loss = 0, logits = 0, a0 = 0, total = 0;
+         loss_rows = 0, loss = 0, logits = 0, a0 = 0, splitk = 0, splitk_bytes = 0, total = 0;
   std::vector<size_t> act, dz;  // act[l] for l = 1..L-1, dz[l] for l = 1..L (index l)
   size_t es() const { return bf16 ? 2 : 4; }
 };
@@ -214,6 +215,24 @@ void build_layout(const lsam_config& c, Layout& lo) {
     for (int l = 1; l <= lo.L; ++l) lo.dz[l] = take(cur, rows * lo.ld[l] * lo.es());
     lo.logits = take(cur, rows * lo.ld[lo.L] * 4);
     if (lo.need_a0) lo.a0 = take(cur, rows * lo.ld[0] * lo.es());
+    // scratch for split-K partial sums: the largest request among this model's GEMMs
+    size_t need = 0;
+    for (int l = 0; l < lo.L; ++l) {
+      const Layer& ly = lo.layers[l];
+      GemmDesc d{};
+      d.batch = lo.K; d.in_bf16 = lo.bf16;
+      d.M = lo.B; d.N = ly.out; d.Kd = ly.in; d.a_kmajor = 1; d.b_kmajor = 1;     // forward
+      d.out_bf16 = lo.bf16 && l + 1 < lo.L;
+      need = std::max(need, gemm_splitk_bytes(d));
+      d.M = lo.B; d.N = ly.in; d.Kd = ly.out; d.a_kmajor = 1; d.b_kmajor = 0;     // dX
+      d.out_bf16 = lo.bf16;
+      if (l > 0) need = std::max(need, gemm_splitk_bytes(d));
+      d.M = ly.out; d.N = ly.in; d.Kd = lo.B; d.a_kmajor = 0; d.b_kmajor = 0;     // dW
+      d.out_bf16 = 0;
+      need = std::max(need, gemm_splitk_bytes(d));
+    }
+    lo.splitk_bytes = need;
+    if (need) lo.splitk = take(cur, need);
   }
   lo.total = cur;
 }
@@ -344,6 +363,7 @@ int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const v
       d.bias_dir = c->at<float>(lo.g) + ly.b_off;
       d.bias_scale = c->at<float>(lo.scale);
     }
+    d.splitk_ws = lo.splitk_bytes ? c->at<float>(lo.splitk) : nullptr; d.splitk_bytes = lo.splitk_bytes;
     LaunchTimer t(c, KC_GEMM_FWD);
     if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "forward GEMM of layer %d rejected", l);
   }
@@ -366,6 +386,7 @@ int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const v
       d.C = g + ly.w_off; d.strideC = lo.d_pad; d.ldC = ly.ldw;
       d.M = ly.out; d.N = ly.in; d.Kd = B; d.batch = K;
       d.in_bf16 = lo.bf16; d.out_bf16 = 0; d.epilogue = EPI_PLAIN;
+      d.splitk_ws = lo.splitk_bytes ? c->at<float>(lo.splitk) : nullptr; d.splitk_bytes = lo.splitk_bytes;
       LaunchTimer t(c, KC_GEMM_DW);
       if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "dW GEMM of layer %d rejected", l);
     }
@@ -381,6 +402,7 @@ int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const v
       d.M = B; d.N = ly.in; d.Kd = ly.out; d.batch = K;
       d.in_bf16 = lo.bf16; d.out_bf16 = lo.bf16; d.epilogue = EPI_MASK;
       d.mask = act; d.strideMask = (int64_t)B * lo.ld[l]; d.ldMask = lo.ld[l];
+      d.splitk_ws = lo.splitk_bytes ? c->at<float>(lo.splitk) : nullptr; d.splitk_bytes = lo.splitk_bytes;
       LaunchTimer t(c, KC_GEMM_DX);
       if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "dX GEMM of layer %d rejected", l);
     }

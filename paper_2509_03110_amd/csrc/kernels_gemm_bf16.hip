@@ -24,7 +24,6 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int BK = 32;        // bf16 elements of k per stage
-constexpr int NSTAGE = 4;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -179,17 +178,18 @@ template <> struct Out<__bf16> {
   static __device__ __forceinline__ __bf16 one(float v) { return static_cast<__bf16>(v); }
 };
 
-template <typename TC, int BM, int BN, bool A_KMAJOR, bool B_KMAJOR, int OCC>
+template <typename TC, int BM, int BN, int NSTAGE, bool A_KMAJOR, bool B_KMAJOR, int OCC>
 __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams p) {
+  static_assert(NSTAGE == 3 || NSTAGE == 4, "ring of 3 or 4 stages");
   constexpr int TM = BM / 64, TN = BN / 64;
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
-  constexpr int PITCH = BN + 4;                               // epilogue staging pitch (floats)
-  constexpr int EPI_BYTES = 32 * PITCH * 4;
+  constexpr int EPI_PITCH = BN / 2 + 4;                       // epilogue staging pitch (floats)
+  constexpr int EPI_BYTES = 2 * 32 * EPI_PITCH * 4;           // two wavefronts stage in one array
   constexpr int STAGE_BYTES = A_BYTES + B_BYTES > EPI_BYTES ? A_BYTES + B_BYTES : EPI_BYTES;
   __shared__ __attribute__((aligned(1024))) unsigned char st0[STAGE_BYTES];
   __shared__ __attribute__((aligned(1024))) unsigned char st1[STAGE_BYTES];
   __shared__ __attribute__((aligned(1024))) unsigned char st2[STAGE_BYTES];
-  __shared__ __attribute__((aligned(1024))) unsigned char st3[STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char st3[NSTAGE == 4 ? STAGE_BYTES : 1024];
 
   const int w = blockIdx.x;
   const int logical = (w % 8) * p.chunks + w / 8;    // contiguous tile range per XCD
@@ -255,15 +255,17 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
   oa.issue(rsrcA, s0, 0, ksteps); ob.issue(rsrcB, s0 + A_BYTES, 0, ksteps);
   oa.issue(rsrcA, s1, 1, ksteps); ob.issue(rsrcB, s1 + A_BYTES, 1, ksteps);
   oa.issue(rsrcA, s2, 2, ksteps); ob.issue(rsrcB, s2 + A_BYTES, 2, ksteps);
-  oa.issue(rsrcA, s3, 3, ksteps); ob.issue(rsrcB, s3 + A_BYTES, 3, ksteps);
-  __builtin_amdgcn_s_waitcnt(waitcnt(3 * NL, 15));     // tile 0 has landed (this wavefront's part)
+  if constexpr (NSTAGE == 4) {
+    oa.issue(rsrcA, s3, 3, ksteps); ob.issue(rsrcB, s3 + A_BYTES, 3, ksteps);
+  }
+  __builtin_amdgcn_s_waitcnt(waitcnt((NSTAGE - 1) * NL, 15));   // tile 0 has landed (this wavefront's part)
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
   oa.read(s0, 0, fa[0]);
   ob.read(s0 + A_BYTES, 0, fb[0]);
 
-  // One k-step on stage CUR; NEXT holds the following tile; the tile three steps ahead is
+  // One k-step on stage CUR; NEXT holds the following tile; the tile NSTAGE steps ahead is
   // requested into CUR as soon as every wavefront has taken its last fragment out of it.
 #define LSAM_GEMM_STEP(CUR, NEXT)                                                         \
   {                                                                                       \
@@ -271,12 +273,12 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
     ob.read(CUR + A_BYTES, 1, fb[1]);                                                     \
     mfma_chunk(0);                                                                        \
     Interleave<0x100, ND, NM, 0>::run();                                                  \
-    __builtin_amdgcn_s_waitcnt(waitcnt(2 * NL, 0));                                       \
+    __builtin_amdgcn_s_waitcnt(waitcnt((NSTAGE - 2) * NL, 0));                            \
     asm volatile("" ::: "memory");                                                        \
     __builtin_amdgcn_s_barrier();                                                         \
     asm volatile("" ::: "memory");                                                        \
-    oa.issue(rsrcA, CUR, ks + 4, ksteps);                                                 \
-    ob.issue(rsrcB, CUR + A_BYTES, ks + 4, ksteps);                                       \
+    oa.issue(rsrcA, CUR, ks + NSTAGE, ksteps);                                            \
+    ob.issue(rsrcB, CUR + A_BYTES, ks + NSTAGE, ksteps);                                  \
     oa.read(NEXT, 0, fa[0]);                                                              \
     ob.read(NEXT + A_BYTES, 0, fb[0]);                                                    \
     mfma_chunk(1);                                                                        \
@@ -287,8 +289,12 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
   for (int ks = 0; ks < ksteps;) {
     LSAM_GEMM_STEP(s0, s1)
     LSAM_GEMM_STEP(s1, s2)
-    LSAM_GEMM_STEP(s2, s3)
-    LSAM_GEMM_STEP(s3, s0)
+    if constexpr (NSTAGE == 3) {
+      LSAM_GEMM_STEP(s2, s0)
+    } else {
+      LSAM_GEMM_STEP(s2, s3)
+      LSAM_GEMM_STEP(s3, s0)
+    }
   }
 #undef LSAM_GEMM_STEP
   __builtin_amdgcn_s_waitcnt(waitcnt(0, 0));           // nothing may still be writing LDS
@@ -296,8 +302,13 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 
-  // Epilogue: accumulators -> LDS -> whole rows (element e of a 32x32 tile is row m = l32,
-  // column n = (e/4)*8 + h*4 + e%4 because the MFMA was issued with rows <- B, columns <- A).
+  // Epilogue.  Element e of a 32x32 accumulator tile is row m = l32, column
+  // n = (e/4)*8 + h*4 + e%4 (the MFMA was issued with rows <- B, columns <- A); storing from
+  // that layout would scatter 16-byte pieces over 32 rows per instruction.  Each wavefront
+  // instead passes its own 32-row strips through a private piece of LDS (no workgroup
+  // barrier: LDS operations of one wavefront complete in order) and writes them out as row
+  // segments, consecutive lanes on consecutive 16 bytes; bias and the ReLU mask are read the
+  // same way.
   TC* C = reinterpret_cast<TC*>(p.C) + (long long)bat * p.strideC;
   const float* bias = p.bias ? p.bias + (long long)bat * p.strideBias : nullptr;
   const float* bias_dir = p.bias_dir ? p.bias_dir + (long long)bat * p.strideBias : nullptr;
@@ -308,12 +319,13 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
   const bool relu = p.epilogue == EPI_BIAS_RELU;
   const bool masked = p.epilogue == EPI_MASK;
   typedef typename Out<TC>::vec cvec;
-  constexpr int LANES_PER_ROW = BN / 4;
-  constexpr int ROWS_PER_PASS = kThreads / LANES_PER_ROW;
-  float* stage_w = reinterpret_cast<float*>((wave >> 1) ? st1 : st0);   // written by this wavefront row
-  const int c4 = (tid % LANES_PER_ROW) * 4;
-  const int rsub = tid / LANES_PER_ROW;
-  const int n = n0 + c4;
+  constexpr int WN = BN / 2;                       // columns of a wavefront's part
+  constexpr int LANES_PER_ROW = WN / 4;
+  constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
+  float* stage = reinterpret_cast<float*>((wave >> 1) ? st1 : st0) + (wave & 1) * (32 * EPI_PITCH);
+  const int c4 = (lane % LANES_PER_ROW) * 4;
+  const int rsub = lane / LANES_PER_ROW;
+  const int n = n0 + wn0 + c4;
   f32x4 bv = {0.f, 0.f, 0.f, 0.f};
   if (has_bias) {
 #pragma unroll
@@ -332,14 +344,14 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
         f32x4 v;
 #pragma unroll
         for (int r = 0; r < 4; ++r) v[r] = acc[i][j][q * 4 + r];
-        *reinterpret_cast<f32x4*>(stage_w + l32 * PITCH + wn0 + j * 32 + q * 8 + h * 4) = v;
+        *reinterpret_cast<f32x4*>(stage + l32 * EPI_PITCH + j * 32 + q * 8 + h * 4) = v;
       }
-    __syncthreads();
-    for (int rr = rsub; rr < 64; rr += ROWS_PER_PASS) {
-      const float* stage_r = reinterpret_cast<const float*>((rr >> 5) ? st1 : st0);
-      const int m = m0 + (rr >> 5) * (BM / 2) + i * 32 + (rr & 31);
+#pragma unroll
+    for (int pass = 0; pass < 32 / ROWS_PER_PASS; ++pass) {
+      const int rr = pass * ROWS_PER_PASS + rsub;
+      const int m = m0 + wm0 + i * 32 + rr;
+      f32x4 v = *reinterpret_cast<const f32x4*>(stage + rr * EPI_PITCH + c4);
       if (m < p.M && n < p.N) {
-        f32x4 v = *reinterpret_cast<const f32x4*>(stage_r + (rr & 31) * PITCH + c4);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           v[r] += bv[r];
@@ -366,15 +378,15 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
         }
       }
     }
-    if (i + 1 < TM) __syncthreads();
   }
 }
 
 // Every specialisation that can be launched is instantiated explicitly (the host-side launch
 // stubs of implicit instantiations of this kernel were not all emitted by the compiler).
 #define LSAM_INSTANTIATE(TC, AK, BK_)                                                         \
-  template __global__ void gemm_bf16_kernel<TC, 256, 256, AK, BK_, 1>(Bf16GemmParams);         \
-  template __global__ void gemm_bf16_kernel<TC, 128, 128, AK, BK_, 2>(Bf16GemmParams);
+  template __global__ void gemm_bf16_kernel<TC, 256, 256, 4, AK, BK_, 1>(Bf16GemmParams);      \
+  template __global__ void gemm_bf16_kernel<TC, 256, 128, 3, AK, BK_, 2>(Bf16GemmParams);      \
+  template __global__ void gemm_bf16_kernel<TC, 128, 128, 4, AK, BK_, 2>(Bf16GemmParams);
 LSAM_INSTANTIATE(float, true, true)
 LSAM_INSTANTIATE(float, true, false)
 LSAM_INSTANTIATE(float, false, false)
@@ -383,7 +395,7 @@ LSAM_INSTANTIATE(__bf16, true, false)
 LSAM_INSTANTIATE(__bf16, false, false)
 #undef LSAM_INSTANTIATE
 
-template <typename TC, int BM, int BN, bool AK, bool BK_>
+template <typename TC, int BM, int BN, int NSTAGE, bool AK, bool BK_>
 int launch_one(const Bf16GemmParams& p0, hipStream_t s) {
   constexpr int OCC = (BM * BN >= 256 * 256) ? 1 : 2;
   Bf16GemmParams p = p0;
@@ -391,14 +403,15 @@ int launch_one(const Bf16GemmParams& p0, hipStream_t s) {
   p.tilesN = (p.N + BN - 1) / BN;
   p.total = p.tilesM * p.tilesN * p.batch;
   p.chunks = (p.total + 7) / 8;
-  gemm_bf16_kernel<TC, BM, BN, AK, BK_, OCC><<<p.chunks * 8, kThreads, 0, s>>>(p);
+  gemm_bf16_kernel<TC, BM, BN, NSTAGE, AK, BK_, OCC><<<p.chunks * 8, kThreads, 0, s>>>(p);
   return 0;
 }
 
 template <typename TC, bool AK, bool BK_>
 int launch_tiled(const Bf16GemmParams& p, int tile, hipStream_t s) {
-  if (tile == 256) return launch_one<TC, 256, 256, AK, BK_>(p, s);
-  return launch_one<TC, 128, 128, AK, BK_>(p, s);
+  if (tile == 256) return launch_one<TC, 256, 256, 4, AK, BK_>(p, s);
+  if (tile == 2) return launch_one<TC, 256, 128, 3, AK, BK_>(p, s);
+  return launch_one<TC, 128, 128, 4, AK, BK_>(p, s);
 }
 
 template <typename TC>
@@ -420,6 +433,7 @@ int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s) {
   };
   int tile = 0;
   if (tile_override == 1) tile = 256;
+  else if (tile_override == 2) tile = 2;
   else if (tile_override == 4) tile = 128;
   else if (tile_override != 0) return 1;
   // By measurement on MI355X: with enough 256x256 tiles to fill the chip twice this kernel wins
@@ -430,8 +444,8 @@ int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s) {
   else if (d.M >= 128 && d.N >= 128 && !d.a_kmajor && !d.b_kmajor) tile = 128;
   else return 1;
   // 32-bit byte offsets: the farthest address a lane can form must stay below 2^31
-  const long long rowsA = d.a_kmajor ? d.M + tile : d.Kd + 8 * BK;
-  const long long rowsB = d.b_kmajor ? d.N + tile : d.Kd + 8 * BK;
+  const long long rowsA = d.a_kmajor ? d.M + 256 : d.Kd + 8 * BK;
+  const long long rowsB = d.b_kmajor ? d.N + 256 : d.Kd + 8 * BK;
   if ((rowsA + 1) * d.ldA * 2 + 4096 >= 0x7FFFFFFFLL || (rowsB + 1) * d.ldB * 2 + 4096 >= 0x7FFFFFFFLL)
     return 1;
   Bf16GemmParams p;

@@ -365,7 +365,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
             for (int r = 0; r < 4; ++r)
               if (!(static_cast<float>(me[r]) > 0.f)) v[r] = 0.f;
           }
-          *reinterpret_cast<cvec*>(C + (long long)m * p.ldC + n) = Out<TC>::from(v);
+          __builtin_nontemporal_store(Out<TC>::from(v), reinterpret_cast<cvec*>(C + (long long)m * p.ldC + n));
         } else {
 #pragma unroll
           for (int r = 0; r < 4; ++r)

@@ -82,9 +82,10 @@ typedef struct {
 #define LSAM_BUF_VELOCITY   1  /* v_i                                                  */
 #define LSAM_BUF_ITER_SUM   2  /* S_i = sum of x_i's iterates since its last sync     */
 #define LSAM_BUF_GRAD       3  /* gradient buffer (g2 after a step; MLP mode only)    */
-#define LSAM_BUF_PERTURBED  4  /* x~_i of the last step: fp32, or the bf16 operand copy
-                                  widened to fp32 in bf16 mode (which holds bf16(x_i)
-                                  again once the step has finished)                    */
+#define LSAM_BUF_PERTURBED  4  /* fp32 mode: x~_i of the last step.  bf16 mode: the bf16
+                                  operand copy of the weight matrices widened to fp32
+                                  (it holds bf16(x_i) once a step has finished), with the
+                                  biases, which have no bf16 copy, taken from x_i      */
 #define LSAM_BUF_CENTER_DIR 5  /* g'_prev (replica ignored)                            */
 
 /* Bytes of device workspace the configuration needs; 0 if the configuration is invalid

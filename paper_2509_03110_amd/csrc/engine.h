@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "../../include/lsam.h"
+#include "b32s.h"
 
 namespace lsam {
 
@@ -32,27 +33,33 @@ void launch_sumsq_partials(const float* g, int64_t g_stride, int64_t n, int K, d
 void launch_norm_finish(const double* partials, int nblk, int K, float rho, float gamma,
                         float* norms, float* scale, const float* loss_rows, int B,
                         float* loss_out, hipStream_t s);
-// x~ = x + scale[k] * g.  Writes fp32 (xt_f32) or bf16 (xt_bf16), whichever is non-null.
+// x~ = x + scale[k] * g.  Writes fp32 (xt_f32), or, if xt_bf16 is non-null, the bf16 operand
+// copy of the weight matrices in the blocked layout described by `map` (replica stride
+// `shadow_stride` elements).
 void launch_perturb(const float* x, const float* g, int64_t g_stride, const float* scale,
-                    float* xt_f32, uint16_t* xt_bf16, int64_t stride, int64_t n, int K,
-                    hipStream_t s);
+                    float* xt_f32, uint16_t* xt_bf16, const ShadowMap* map, int64_t shadow_stride,
+                    int64_t stride, int64_t n, int K, hipStream_t s);
 // Descent + coupling for all K replicas, y read once per index:
 //   G = g + lam[k] (x - y); v = mu v + G; x -= lr (G + mu v) [nesterov] | lr v; S += x.
-// Also writes bf16(x) to shadow if non-null.
+// Also refreshes the bf16 operand copy of the weight matrices if `shadow` is non-null.
 void launch_descent(float* x, const float* g, int64_t g_stride, float* v, float* S,
-                    const float* y, uint16_t* shadow, int64_t stride, int64_t n, int K,
-                    const ReplicaScalars& lam, float lr, float mu, int nesterov, hipStream_t s);
+                    const float* y, uint16_t* shadow, const ShadowMap* map, int64_t shadow_stride,
+                    int64_t stride, int64_t n, int K, const ReplicaScalars& lam, float lr, float mu,
+                    int nesterov, hipStream_t s);
 // Center update over the due replicas (Algorithm 2, synchronous optimization step).
 void launch_center(float* S, float* y, float* gprev, int64_t stride, int64_t n,
                    const DueList& due, float inv_m, float beta, float lr_center, int has_prev,
                    hipStream_t s);
-// dst[k, :] = src[:] for k < K (fp32), optionally also a bf16 copy.
-void launch_broadcast(const float* src, float* dst, uint16_t* dst_bf16, int64_t stride, int64_t n,
-                      int K, hipStream_t s);
+// dst[k, :] = src[:] for k < K (fp32).
+void launch_broadcast(const float* src, float* dst, int64_t stride, int64_t n, int K, hipStream_t s);
+// Rebuilds the bf16 operand copy of K replicas from their fp32 parameters.
+void launch_shadow_refresh(const float* x, uint16_t* shadow, const ShadowMap& map, int64_t stride,
+                           int64_t shadow_stride, int64_t n, int K, hipStream_t s);
+// Row-major bf16 [K][rows][cols] -> blocked layout, one matrix per replica (dst pre-zeroed
+// padding is left untouched).
+void launch_rowmajor_to_b32s(const uint16_t* src, uint16_t* dst, int rows, int cols, int K,
+                             hipStream_t s);
 void launch_fill_zero(void* p, size_t bytes, hipStream_t s);
-// fp32 -> bf16 (round to nearest even) / bf16 -> fp32 element-wise copies.
-void launch_to_bf16(const float* src, uint16_t* dst, int64_t n, hipStream_t s);
-void launch_from_bf16(const uint16_t* src, float* dst, int64_t n, hipStream_t s);
 // Row-padded copy: dst[r, 0:cols] = src[r, 0:cols], rows of `elem` bytes-sized elements.
 void launch_pad_rows(const void* src, void* dst, int64_t rows, int cols, int ld_dst, int elem,
                      hipStream_t s);
@@ -76,6 +83,9 @@ struct GemmDesc {
   const float* bias_dir; const float* bias_scale; // if set: bias[n] + bias_scale[k] * bias_dir[n]
   const void* mask; int64_t strideMask; int ldMask; // EPI_MASK: keep where mask[m,n] > 0 (operand dtype)
   float* splitk_ws; size_t splitk_bytes;            // scratch for split-K partial sums (may be null)
+  // bf16 tensors in the blocked layout (b32s.h): column blocks of the stored A, B, bf16 C, mask;
+  // strideA/B/C/Mask then count elements of one replica's stored matrix and ld* are unused
+  int b32s; int cbA, cbB, cbC, cbMask;
 };
 int launch_gemm(const GemmDesc& d, hipStream_t s);   // 0 ok, <0 unsupported shape
 size_t gemm_splitk_bytes(const GemmDesc& d);          // scratch this GEMM would like (0: none)
@@ -84,12 +94,14 @@ int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s);
 void set_gemm_tile_override(int code);               // tuning hook: 0 = choose by shape
 
 // Softmax cross-entropy, forward and backward.  logits [K,B,ld] fp32; labels [K,B];
-// dz [K,B,ld_dz] (fp32 or bf16) = (softmax - onehot)/B, zero in the padded columns;
+// dz = (softmax - onehot)/B: fp32 [K,B,ld_dz] row-major with zeros in the padded columns, or
+// (dz_bf16) bf16 in the blocked layout, ld_dz then being one replica's stored size in elements;
 // loss_rows [K,B] = lse - logit[label] (may be null).
-void launch_softmax_ce(const float* logits, int ld, const int32_t* labels, void* dz, int ld_dz,
+void launch_softmax_ce(const float* logits, int ld, const int32_t* labels, void* dz, int64_t ld_dz,
                        int dz_bf16, float* loss_rows, int K, int B, int C, hipStream_t s);
-// db[k][n] = sum_b dz[k][b][n].
-void launch_bias_grad(const void* dz, int ld, int dz_bf16, float* db, int64_t strideDb, int K,
+// db[k][n] = sum_b dz[k][b][n]; dz as written by the kernels above (ld: row pitch, or one
+// replica's stored size for the blocked bf16 layout).
+void launch_bias_grad(const void* dz, int64_t ld, int dz_bf16, float* db, int64_t strideDb, int K,
                       int B, int N, hipStream_t s);
 
 }  // namespace lsam

@@ -1,6 +1,7 @@
 // Fused softmax cross-entropy forward + backward (one wavefront per sample row, wavefront
 // shuffle reductions) and the bias gradient (column sums of dZ).
 #include "engine.h"
+#include "b32s.h"
 
 namespace lsam {
 namespace {
@@ -28,10 +29,12 @@ template <> __device__ __forceinline__ void put<__bf16>(__bf16* p, float v) {
 
 // Row r = replica*B + sample.  loss_row = logsumexp(z) - z[label];
 // dz = (softmax(z) - onehot(label)) / B;  padded columns [C, ld_dz) are written as zero.
+// TD = float: dz row-major with pitch ld_dz.  TD = bf16: dz in the blocked layout, one matrix
+// [B][C] per replica, ld_dz = elements per replica (its padding is zero from initialisation).
 template <typename TD>
 __global__ __launch_bounds__(kThreads) void softmax_ce_kernel(
     const float* __restrict__ logits, int ld, const int32_t* __restrict__ labels,
-    TD* __restrict__ dz, int ld_dz, float* __restrict__ loss_rows, int rows, int B, int C) {
+    TD* __restrict__ dz, long long ld_dz, float* __restrict__ loss_rows, int rows, int B, int C) {
   const int lane = threadIdx.x & 63;
   const int r = blockIdx.x * kWaves + (threadIdx.x >> 6);
   if (r >= rows) return;
@@ -45,15 +48,19 @@ __global__ __launch_bounds__(kThreads) void softmax_ce_kernel(
   se = wave_sum(se);
   const float inv = 1.f / se;
   const float invB = 1.f / (float)B;
-  TD* d = dz + (long long)r * ld_dz;
-  for (int c = lane; c < ld_dz; c += 64) {
+  constexpr bool blocked = sizeof(TD) == 2;
+  const int rep = r / B, b = r - rep * B;
+  const int cb = b32s_blocks(C);
+  const int width = blocked ? C : (int)ld_dz;
+  for (int c = lane; c < width; c += 64) {
     float v = 0.f;
     if (c < C) {
       v = __expf(z[c] - mx) * inv;
       if (c == lab) v -= 1.f;
       v *= invB;
     }
-    put<TD>(d + c, v);
+    TD* d = blocked ? dz + (long long)rep * ld_dz + b32s_offset(b, c, cb) : dz + (long long)r * ld_dz + c;
+    put<TD>(d, v);
   }
   if (loss_rows != nullptr && lane == 0) {
     const float zl = (lab >= 0 && lab < C) ? z[lab] : 0.f;
@@ -71,7 +78,7 @@ template <> __device__ __forceinline__ float get<__bf16>(const __bf16* p) {
 // wavefronts take every fourth row (lane = column, so a row is one coalesced read), each lane
 // keeps four partial sums, and the partials are combined in a fixed order through LDS.
 template <typename TD>
-__global__ __launch_bounds__(kThreads) void bias_grad_kernel(const TD* __restrict__ dz, int ld,
+__global__ __launch_bounds__(kThreads) void bias_grad_kernel(const TD* __restrict__ dz, long long ld,
                                                             float* __restrict__ db,
                                                             long long strideDb, int B, int N) {
   __shared__ float part[kWaves][64];
@@ -80,15 +87,20 @@ __global__ __launch_bounds__(kThreads) void bias_grad_kernel(const TD* __restric
   const int n = blockIdx.x * 64 + lane;
   float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
   if (n < N) {
-    const TD* p = dz + (long long)k * B * ld + n;
+    constexpr bool blocked = sizeof(TD) == 2;
+    const int cb = b32s_blocks(N);
+    const TD* base = blocked ? dz + (long long)k * ld : dz + (long long)k * B * ld + n;
+    auto at = [&](int b) {
+      return get<TD>(blocked ? base + b32s_offset(b, n, cb) : base + (long long)b * ld);
+    };
     int b = wave;
     for (; b + 3 * kWaves < B; b += 4 * kWaves) {
-      s0 += get<TD>(p + (long long)b * ld);
-      s1 += get<TD>(p + (long long)(b + kWaves) * ld);
-      s2 += get<TD>(p + (long long)(b + 2 * kWaves) * ld);
-      s3 += get<TD>(p + (long long)(b + 3 * kWaves) * ld);
+      s0 += at(b);
+      s1 += at(b + kWaves);
+      s2 += at(b + 2 * kWaves);
+      s3 += at(b + 3 * kWaves);
     }
-    for (; b < B; b += kWaves) s0 += get<TD>(p + (long long)b * ld);
+    for (; b < B; b += kWaves) s0 += at(b);
   }
   part[wave][lane] = (s0 + s1) + (s2 + s3);
   __syncthreads();
@@ -98,7 +110,7 @@ __global__ __launch_bounds__(kThreads) void bias_grad_kernel(const TD* __restric
 
 }  // namespace
 
-void launch_softmax_ce(const float* logits, int ld, const int32_t* labels, void* dz, int ld_dz,
+void launch_softmax_ce(const float* logits, int ld, const int32_t* labels, void* dz, int64_t ld_dz,
                        int dz_bf16, float* loss_rows, int K, int B, int C, hipStream_t s) {
   const int rows = K * B;
   const unsigned grid = (rows + kWaves - 1) / kWaves;
@@ -110,7 +122,7 @@ void launch_softmax_ce(const float* logits, int ld, const int32_t* labels, void*
                                                        loss_rows, rows, B, C);
 }
 
-void launch_bias_grad(const void* dz, int ld, int dz_bf16, float* db, int64_t strideDb, int K,
+void launch_bias_grad(const void* dz, int64_t ld, int dz_bf16, float* db, int64_t strideDb, int K,
                       int B, int N, hipStream_t s) {
   dim3 grid((N + 63) / 64, K);
   if (dz_bf16)

@@ -48,7 +48,6 @@ struct GemmParams {
 };
 
 int g_tile_override = 0;   // tuning hook, 0 = choose by shape
-bool g_use_ring = true;    // tuning hook: bf16 shapes go to the direct-to-LDS kernel when it takes them
 
 template <typename T> struct Op;
 template <> struct Op<float> { static constexpr int UE = 4; };
@@ -570,11 +569,13 @@ int launch_layout(const GemmDesc& d, const GemmParams& p, const Plan& pl, hipStr
 size_t gemm_splitk_bytes(const GemmDesc& d) { return make_plan(d, 0).ws_bytes; }
 
 void set_gemm_tile_override(int code) {
-  g_use_ring = code < 100;          // codes >= 100 select the generic kernel with tile code-100
-  g_tile_override = code % 100;
+  g_tile_override = code;
 }
 
 int launch_gemm(const GemmDesc& d, hipStream_t s) {
+  // bf16 operands live in the blocked layout and have their own kernel; this file's kernel
+  // serves the fp32 configurations
+  if (d.in_bf16) return launch_gemm_bf16(d, g_tile_override, s);
   GemmParams p;
   p.A = (const char*)d.A; p.strideA = d.strideA; p.ldA = d.ldA;
   p.B = (const char*)d.B; p.strideB = d.strideB; p.ldB = d.ldB;
@@ -596,13 +597,6 @@ int launch_gemm(const GemmDesc& d, hipStream_t s) {
   const long long es = d.in_bf16 ? 2 : 4;
   const long long rowsA = d.a_kmajor ? d.M : d.Kd, rowsB = d.b_kmajor ? d.N : d.Kd;
   if (rowsA * d.ldA * es >= 0x7FFFFFF0LL || rowsB * d.ldB * es >= 0x7FFFFFF0LL) return -1;
-  if (d.in_bf16) {
-    if ((d.strideA % 8) || (d.strideB % 8) || (d.strideC % 8)) return -1;
-    if (g_use_ring && launch_gemm_bf16(d, g_tile_override, s) == 0) return 0;
-    const Plan pl = make_plan(d, g_tile_override);
-    if (d.out_bf16) return launch_layout<__bf16, __bf16>(d, p, pl, s);
-    return launch_layout<__bf16, float>(d, p, pl, s);
-  }
   if ((d.strideA % 4) || (d.strideB % 4) || (d.strideC % 4)) return -1;
   if (d.out_bf16) return -1;
   Plan pl = make_plan(d, g_tile_override);

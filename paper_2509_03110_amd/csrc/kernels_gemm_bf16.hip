@@ -1,23 +1,22 @@
-// bf16 replica GEMMs with a four-stage LDS ring fed by direct global->LDS loads.
+// bf16 replica GEMMs with an LDS ring fed by direct global->LDS loads.
 //
 // Same contract as the generic kernel (C[m,n] = sum_k A(m,k) B(n,k), operands k-major or
-// m-major, batched over replicas), specialised for bf16 operands whose contraction length is a
-// multiple of 32.  No operand passes through registers on its way to LDS:
+// m-major, batched over replicas) for bf16 operands stored in the blocked layout of b32s.h.
+// No operand passes through registers on its way to LDS:
 //   * every thread issues `buffer_load_dwordx4 ... lds` instructions; a wavefront instruction
-//     fills 1 KiB of LDS in lane order, so the LDS image is fixed by which global address each
-//     lane asks for.  k-major tiles are stored [row][4 units of 16 B] with the unit index
-//     XOR-ed by (row/4)%4; m-major tiles are stored as they are in memory, [k][m], with the
-//     16-byte column unit XOR-ed by 2*(k%4).  Both swizzles are applied on the global side.
+//     copies 1 KiB of global memory to 1 KiB of LDS in lane order.  Because a tile is a run
+//     of whole 2 KiB blocks in that layout, the LDS image of a tile is a plain copy of it.
 //   * k-major fragments are one 128-bit LDS read; m-major fragments are two transposing LDS
 //     reads (ds_read_b64_tr_b16: within 16 lanes, lanes 4j..4j+3 address row j of a 4x16
 //     block and lane i receives column i), which delivers exactly the MFMA operand layout, so
 //     neither weights nor activations need a transposed copy or a register shuffle.
-//   * a k-step is 32 deep (two MFMA depths); three k-steps are in flight behind the one being
-//     multiplied (~96 KiB per compute unit), which is what hides HBM latency with a single
-//     wavefront per SIMD.  Each stage is its own LDS array so that the compiler's wait-count
-//     tracking can tell them apart; the wait that orders a stage's arrival before the
-//     workgroup barrier is explicit.
+//   * a k-step is 32 deep (two MFMA depths); NSTAGE-1 k-steps are in flight behind the one
+//     being multiplied (~96 KiB per compute unit), which is what hides HBM latency with a
+//     single wavefront per SIMD.  Each stage is its own LDS array so that the compiler's
+//     wait-count tracking can tell them apart; the wait that orders a stage's arrival before
+//     the workgroup barrier is explicit.
 #include "engine.h"
+#include "b32s.h"
 
 namespace lsam {
 namespace {
@@ -43,6 +42,8 @@ struct Bf16GemmParams {
   const float* bias; long long strideBias;
   const float* bias_dir; const float* bias_scale;
   const char* mask; long long strideMask; int ldMask;
+  int cbA, cbB, cbC, cbMask;          // column blocks of the stored A, B, C (bf16 out) and mask
+  unsigned bytesA, bytesB;            // size of one replica's stored A and B
 };
 
 // s_waitcnt immediate: vmcnt = vm (0..63), lgkmcnt = lgkm (0..15), expcnt untouched.
@@ -68,52 +69,45 @@ struct Operand {
   unsigned goff[NLOAD];       // global byte offset of this lane's 16 bytes at k-step 0
   unsigned kstep;             // bytes from one k-step to the next
   unsigned lds_slot0;         // LDS byte offset (in the tile) of the wavefront's first 1 KiB chunk
-  // LDS byte offsets of the fragment reads.  k-major: [depth] for fragment 0, fragment t lies
-  // t*2048 bytes further (32 rows of 64 bytes; the swizzle repeats every 16 rows).
-  // m-major: [frag][depth][half].
-  unsigned rd[KMAJOR ? 1 : NFRAG][2][KMAJOR ? 1 : 2];
+  // LDS byte offsets of the reads of fragment 0, [depth][half]; fragment t lies t*2048 bytes
+  // further (one 32-row or 32-column block) for both kinds of operand.
+  unsigned rd[1][2][KMAJOR ? 1 : 2];
 
-  // row0: first output row (or column) of the tile in the operand; wrow0: first row of this
-  // wavefront's part inside the tile.
-  __device__ __forceinline__ void init(int ld, int row0, int wrow0, int tid) {
+  // cblocks: column blocks of the stored matrix; row0: first output row (or column) of the
+  // tile, a multiple of 32; wrow0: first row of this wavefront's part inside the tile.
+  __device__ __forceinline__ void init(int cblocks, int row0, int wrow0, int tid) {
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, h = lane >> 5;
     lds_slot0 = (unsigned)(wave * NLOAD) * 1024u;
 #pragma unroll
     for (int j = 0; j < NLOAD; ++j) {
-      const int chunk = wave * NLOAD + j;
-      const int u = chunk * 64 + lane;          // 16-byte unit index inside the tile
+      const unsigned tb = (unsigned)(wave * NLOAD + j) * 1024u + (unsigned)lane * 16u;  // byte in the tile
       if constexpr (KMAJOR) {
-        const int r = u >> 2, s = u & 3;
-        const int ku = s ^ ((r >> 2) & 3);
-        goff[j] = (unsigned)((row0 + r) * ld + ku * 8) * 2u;
+        // R/32 blocks, one per 32 rows, `cblocks` blocks apart in memory
+        goff[j] = ((unsigned)(row0 >> 5) + (tb >> 11)) * (unsigned)cblocks * 2048u + (tb & 2047u);
       } else {
-        constexpr int UPR = R / 8;               // units per k-row
-        const int kr = u / UPR, pos = u % UPR;
-        const int cu = pos ^ (2 * (kr & 3));
-        goff[j] = (unsigned)(kr * ld + row0 + cu * 8) * 2u;
+        // R/32 consecutive blocks of one block row
+        goff[j] = (unsigned)(row0 >> 5) * 2048u + tb;
       }
     }
-    kstep = KMAJOR ? (unsigned)BK * 2u : (unsigned)(BK * ld) * 2u;
+    kstep = KMAJOR ? 2048u : (unsigned)cblocks * 2048u;
 #pragma unroll
-    for (int t = 0; t < (KMAJOR ? 1 : NFRAG); ++t)
+    for (int kc = 0; kc < 2; ++kc) {
+      if constexpr (KMAJOR) {
+        const int r = wrow0 + l32;
+        const int ku = kc * 2 + h;
+        rd[0][kc][0] = (unsigned)(r * 64 + ((ku ^ ((r >> 2) & 3)) * 16));
+      } else {
+        const int il = lane & 15, gq = lane >> 4;
 #pragma unroll
-      for (int kc = 0; kc < 2; ++kc) {
-        if constexpr (KMAJOR) {
-          const int r = wrow0 + l32;
-          const int ku = kc * 2 + h;
-          rd[0][kc][0] = (unsigned)(r * 64 + ((ku ^ ((r >> 2) & 3)) * 16));
-        } else {
-          const int il = lane & 15, gq = lane >> 4;
-#pragma unroll
-          for (int kk = 0; kk < 2; ++kk) {
-            const int kr = kc * 16 + (gq >> 1) * 8 + kk * 4 + (il >> 2);
-            const int col = wrow0 + t * 32 + (gq & 1) * 16 + 4 * (il & 3);
-            const int cu = (col >> 3) ^ (2 * (kr & 3));
-            rd[t][kc][kk] = (unsigned)(kr * (R * 2) + cu * 16 + ((il & 1) * 8));
-          }
+        for (int kk = 0; kk < 2; ++kk) {
+          const int kr = kc * 16 + (gq >> 1) * 8 + kk * 4 + (il >> 2);
+          const int col = wrow0 + (gq & 1) * 16 + 4 * (il & 3);
+          rd[0][kc][kk] = (unsigned)((col >> 5) * 2048 + kr * 64 +
+                                     ((((col & 31) >> 3) ^ ((kr >> 2) & 3)) << 4) + (col & 7) * 2);
         }
       }
+    }
   }
 
   // Requests k-step `ks` of the tile into `tile`.  A step at or past `ksteps` is sent out of
@@ -137,9 +131,9 @@ struct Operand {
       } else {
 #if defined(__HIP_DEVICE_COMPILE__)
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4*)(tile + rd[t][kc][0]));
+            (__attribute__((address_space(3))) s16x4*)(tile + rd[0][kc][0] + t * 2048));
         const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4*)(tile + rd[t][kc][1]));
+            (__attribute__((address_space(3))) s16x4*)(tile + rd[0][kc][1] + t * 2048));
         const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
         f[t][0] = l2[0]; f[t][1] = l2[1]; f[t][2] = h2[0]; f[t][3] = h2[1];
 #endif
@@ -206,10 +200,8 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
 
   const __bf16* A = reinterpret_cast<const __bf16*>(p.A) + (long long)bat * p.strideA;
   const __bf16* B = reinterpret_cast<const __bf16*>(p.B) + (long long)bat * p.strideB;
-  const __amdgpu_buffer_rsrc_t rsrcA =
-      make_rsrc(A, (unsigned)((A_KMAJOR ? p.M : p.Kd) * p.ldA) * 2u);
-  const __amdgpu_buffer_rsrc_t rsrcB =
-      make_rsrc(B, (unsigned)((B_KMAJOR ? p.N : p.Kd) * p.ldB) * 2u);
+  const __amdgpu_buffer_rsrc_t rsrcA = make_rsrc(A, p.bytesA);
+  const __amdgpu_buffer_rsrc_t rsrcB = make_rsrc(B, p.bytesB);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -218,8 +210,8 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
 
   Operand<BM, A_KMAJOR, TM> oa;
   Operand<BN, B_KMAJOR, TN> ob;
-  oa.init(p.ldA, m0, wm0, tid);
-  ob.init(p.ldB, n0, wn0, tid);
+  oa.init(p.cbA, m0, wm0, tid);
+  ob.init(p.cbB, n0, wn0, tid);
   constexpr int NL = Operand<BM, A_KMAJOR, TM>::NLOAD + Operand<BN, B_KMAJOR, TN>::NLOAD;
   constexpr int ND = Operand<BM, A_KMAJOR, TM>::NREAD + Operand<BN, B_KMAJOR, TN>::NREAD;
   constexpr int NM = TM * TN;
@@ -243,7 +235,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
             acc[i][j], 0, 0, 0);
   };
 
-  const int ksteps = p.Kd / BK;
+  const int ksteps = (p.Kd + BK - 1) / BK;     // the stored operands are zero-padded to 32
   lds_byte* s0 = (lds_byte*)st0;
   lds_byte* s1 = (lds_byte*)st1;
   lds_byte* s2 = (lds_byte*)st2;
@@ -357,23 +349,28 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
           v[r] += bv[r];
           if (relu) v[r] = v[r] > 0.f ? v[r] : 0.f;
         }
+        // bf16 results and the mask are in the blocked layout (4 consecutive n share a unit);
+        // fp32 results are row-major
+        long long coff;
+        if constexpr (sizeof(TC) == 2) coff = b32s_offset(m, n, p.cbC);
+        else coff = (long long)m * p.ldC + n;
+        const long long moff = masked ? b32s_offset(m, n, p.cbMask) : 0;
         if (n + 3 < p.N) {
           if (masked) {
-            const u32x2 mk = *reinterpret_cast<const u32x2*>(mask + (long long)m * p.ldMask + n);
+            const u32x2 mk = *reinterpret_cast<const u32x2*>(mask + moff);
             const __bf16* me = reinterpret_cast<const __bf16*>(&mk);
 #pragma unroll
             for (int r = 0; r < 4; ++r)
               if (!(static_cast<float>(me[r]) > 0.f)) v[r] = 0.f;
           }
-          __builtin_nontemporal_store(Out<TC>::from(v), reinterpret_cast<cvec*>(C + (long long)m * p.ldC + n));
+          __builtin_nontemporal_store(Out<TC>::from(v), reinterpret_cast<cvec*>(C + coff));
         } else {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
             if (n + r < p.N) {
               float o = v[r];
-              if (masked && !(static_cast<float>(mask[(long long)m * p.ldMask + n + r]) > 0.f))
-                o = 0.f;
-              C[(long long)m * p.ldC + n + r] = Out<TC>::one(o);
+              if (masked && !(static_cast<float>(mask[moff + r]) > 0.f)) o = 0.f;
+              C[coff + r] = Out<TC>::one(o);
             }
         }
       }
@@ -424,30 +421,38 @@ int launch_layout(const GemmDesc& d, const Bf16GemmParams& p, int tile, hipStrea
 
 }  // namespace
 
-// Returns 1 if this shape is not handled here (the caller then uses the generic kernel),
-// 0 after a launch.
+// All bf16 GEMMs of the MLP path come here; operands, bf16 results and the mask are in the
+// blocked layout.  Returns 0 after a launch, -1 if the description is not usable.
 int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s) {
-  if (!d.in_bf16 || d.Kd % BK != 0) return 1;
+  if (!d.in_bf16 || !d.b32s) return -1;
+  if (d.M <= 0 || d.N <= 0 || d.Kd <= 0 || d.batch <= 0) return -1;
   auto tiles = [&](int bm, int bn) {
     return (long long)((d.M + bm - 1) / bm) * ((d.N + bn - 1) / bn) * d.batch;
   };
-  int tile = 0;
+  // By measurement on MI355X: 256x256 tiles (one workgroup per compute unit) once there are
+  // enough of them to fill the chip twice -- except for the weight gradient with a short
+  // contraction (batch < 512), where a second workgroup per unit hides the per-tile start-up
+  // and write-out; 256x128 tiles with a three-stage ring (two workgroups per unit) when the
+  // batch still gives 256 rows; 128x128 otherwise.
+  int tile = 128;
   if (tile_override == 1) tile = 256;
   else if (tile_override == 2) tile = 2;
   else if (tile_override == 4) tile = 128;
-  else if (tile_override != 0) return 1;
-  // By measurement on MI355X: with enough 256x256 tiles to fill the chip twice this kernel wins
-  // for all three GEMMs; below that it still wins for dW (both operands m-major: no register
-  // transposes), while the generic kernel's deeper k-steps suit 128x128 tiles better when an
-  // operand is k-major.
-  else if (d.M >= 256 && d.N >= 256 && tiles(256, 256) >= 512) tile = 256;
-  else if (d.M >= 128 && d.N >= 128 && !d.a_kmajor && !d.b_kmajor) tile = 128;
-  else return 1;
-  // 32-bit byte offsets: the farthest address a lane can form must stay below 2^31
-  const long long rowsA = d.a_kmajor ? d.M + 256 : d.Kd + 8 * BK;
-  const long long rowsB = d.b_kmajor ? d.N + 256 : d.Kd + 8 * BK;
-  if ((rowsA + 1) * d.ldA * 2 + 4096 >= 0x7FFFFFFFLL || (rowsB + 1) * d.ldB * 2 + 4096 >= 0x7FFFFFFFLL)
-    return 1;
+  else if (d.M >= 256 && d.N >= 256 && tiles(256, 256) >= 512 && (d.Kd >= 512 || d.a_kmajor)) tile = 256;
+  else if (d.M >= 256 && d.N >= 128 && tiles(256, 128) >= 256) tile = 2;
+  const int kpad = (d.Kd + 31) / 32 * 32;
+  // stored shapes: k-major [rows][k], m-major [k][rows]
+  const long long blocksA = d.a_kmajor ? (long long)b32s_blocks(d.M) * d.cbA : (long long)b32s_blocks(kpad) * d.cbA;
+  const long long blocksB = d.b_kmajor ? (long long)b32s_blocks(d.N) * d.cbB : (long long)b32s_blocks(kpad) * d.cbB;
+  // 32-bit byte offsets: the farthest block a lane can name (8 tiles of rows, 4 k-steps past
+  // the end) must stay below 2^31
+  if ((blocksA + (long long)(16 + 8) * d.cbA + 64) * 2048 >= 0x7FFFFFF0LL ||
+      (blocksB + (long long)(16 + 8) * d.cbB + 64) * 2048 >= 0x7FFFFFF0LL)
+    return -1;
+  if (d.a_kmajor ? d.cbA < b32s_blocks(d.Kd) : d.cbA < b32s_blocks(d.M)) return -1;
+  if (d.b_kmajor ? d.cbB < b32s_blocks(d.Kd) : d.cbB < b32s_blocks(d.N)) return -1;
+  if (((uintptr_t)d.A & 15) || ((uintptr_t)d.B & 15) || (d.strideA % 1024) || (d.strideB % 1024))
+    return -1;
   Bf16GemmParams p;
   p.A = (const char*)d.A; p.strideA = d.strideA; p.ldA = d.ldA;
   p.B = (const char*)d.B; p.strideB = d.strideB; p.ldB = d.ldB;
@@ -458,8 +463,10 @@ int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s) {
   p.bias = d.bias; p.strideBias = d.strideBias;
   p.bias_dir = d.bias_dir; p.bias_scale = d.bias_scale;
   p.mask = (const char*)d.mask; p.strideMask = d.strideMask; p.ldMask = d.ldMask;
-  const int rc = d.out_bf16 ? launch_layout<__bf16>(d, p, tile, s) : launch_layout<float>(d, p, tile, s);
-  return rc == 0 ? 0 : 1;
+  p.cbA = d.cbA; p.cbB = d.cbB; p.cbC = d.cbC; p.cbMask = d.cbMask;
+  p.bytesA = (unsigned)(blocksA * 2048);
+  p.bytesB = (unsigned)(blocksB * 2048);
+  return d.out_bf16 ? launch_layout<__bf16>(d, p, tile, s) : launch_layout<float>(d, p, tile, s);
 }
 
 }  // namespace lsam

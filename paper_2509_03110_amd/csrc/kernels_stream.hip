@@ -129,14 +129,22 @@ __global__ __launch_bounds__(kThreads) void norm_finish_kernel(
 }
 
 // ---- ascent perturbation ----------------------------------------------------------------------
+// BF16_OUT: x~ exists only as the bf16 operand copy of the weight matrices (blocked layout);
+// elements that belong to no weight matrix (biases, padding) are not stored at all -- the
+// perturbed biases are formed in the GEMM epilogue from x, g1 and scale.
 template <int VEC, bool BF16_OUT>
 __global__ __launch_bounds__(kThreads) void perturb_kernel(
     const float* __restrict__ x, const float* __restrict__ g, int64_t g_stride,
     const float* __restrict__ scale, float* __restrict__ xt, uint16_t* __restrict__ xt16,
-    int64_t stride, int64_t nv) {
+    ShadowMap map, int64_t shadow_stride, int64_t stride, int64_t nv) {
   const int k = blockIdx.y;
   const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (i >= nv) return;
+  int64_t so = 0;
+  if constexpr (BF16_OUT) {
+    so = shadow_offset4(map, i * VEC);
+    if (so < 0) return;
+  }
   const float sc = scale[k];
   auto xv = ldv<VEC>(x + (int64_t)k * stride + i * VEC);
   auto gv = ldv<VEC>(g + (int64_t)k * g_stride + i * VEC);
@@ -144,7 +152,7 @@ __global__ __launch_bounds__(kThreads) void perturb_kernel(
 #pragma unroll
   for (int e = 0; e < VEC; ++e) set_elem(o, e, elem(xv, e) + sc * elem(gv, e));
   if constexpr (BF16_OUT) {
-    store_bf16<VEC>(xt16 + (int64_t)k * stride + i * VEC, o);
+    store_bf16<VEC>(xt16 + (int64_t)k * shadow_stride + so, o);
   } else {
     stv<VEC>(xt + (int64_t)k * stride + i * VEC, o);
   }
@@ -159,7 +167,8 @@ template <int VEC, bool SHADOW>
 __global__ __launch_bounds__(kThreads) void descent_kernel(
     float* __restrict__ x, const float* __restrict__ g, int64_t g_stride, float* __restrict__ v,
     float* __restrict__ S, const float* __restrict__ y, uint16_t* __restrict__ shadow,
-    int64_t stride, int64_t nv, int K, ReplicaScalars lam, float lr, float mu, int nesterov) {
+    ShadowMap map, int64_t shadow_stride, int64_t stride, int64_t nv, int K, ReplicaScalars lam,
+    float lr, float mu, int nesterov) {
   const int64_t b = blockIdx.x;
   const int k = (int)(b % K);
   const int64_t i = (b / K) * kThreads + threadIdx.x;
@@ -184,7 +193,10 @@ __global__ __launch_bounds__(kThreads) void descent_kernel(
   stv<VEC>(x + o, xv);
   stv<VEC>(v + o, vv);
   stv<VEC>(S + o, sv);
-  if constexpr (SHADOW) store_bf16<VEC>(shadow + o, xv);
+  if constexpr (SHADOW) {
+    const int64_t so = shadow_offset4(map, i * VEC);
+    if (so >= 0) store_bf16<VEC>(shadow + (int64_t)k * shadow_stride + so, xv);
+  }
 }
 
 // ---- center update ------------------------------------------------------------------------------
@@ -219,16 +231,42 @@ __global__ __launch_bounds__(kThreads) void center_kernel(
 }
 
 // ---- small utility kernels ------------------------------------------------------------------------
-template <int VEC, bool SHADOW>
+template <int VEC>
 __global__ __launch_bounds__(kThreads) void broadcast_kernel(
-    const float* __restrict__ src, float* __restrict__ dst, uint16_t* __restrict__ dst16,
-    int64_t stride, int64_t nv, int K) {
+    const float* __restrict__ src, float* __restrict__ dst, int64_t stride, int64_t nv, int K) {
   const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (i >= nv) return;
   auto sv = ldc<VEC>(src + i * VEC);
-  for (int k = 0; k < K; ++k) {
-    stv<VEC>(dst + (int64_t)k * stride + i * VEC, sv);
-    if constexpr (SHADOW) store_bf16<VEC>(dst16 + (int64_t)k * stride + i * VEC, sv);
+  for (int k = 0; k < K; ++k) stv<VEC>(dst + (int64_t)k * stride + i * VEC, sv);
+}
+
+// bf16 operand copy of the weight matrices of replica blockIdx.y from its fp32 parameters.
+__global__ __launch_bounds__(kThreads) void shadow_refresh_kernel(
+    const float* __restrict__ x, uint16_t* __restrict__ shadow, ShadowMap map, int64_t stride,
+    int64_t shadow_stride, int64_t nv) {
+  const int k = blockIdx.y;
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= nv) return;
+  const int64_t so = shadow_offset4(map, i * 4);
+  if (so < 0) return;
+  store_bf16<4>(shadow + (int64_t)k * shadow_stride + so, ldc<4>(x + (int64_t)k * stride + i * 4));
+}
+
+// Row-major bf16 matrix of replica blockIdx.y -> blocked layout; one thread per 8 elements.
+__global__ __launch_bounds__(kThreads) void rowmajor_to_b32s_kernel(
+    const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, int rows, int cols, int cblocks,
+    int64_t dst_stride) {
+  const int k = blockIdx.y;
+  const int units = (cols + 7) / 8;
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= (int64_t)rows * units) return;
+  const int r = (int)(i / units), c = (int)(i % units) * 8;
+  const uint16_t* sp = src + ((int64_t)k * rows + r) * cols + c;
+  uint16_t* dp = dst + (int64_t)k * dst_stride + b32s_offset(r, c, cblocks);
+  if (c + 8 <= cols && (cols % 8) == 0) {
+    *reinterpret_cast<uint4*>(dp) = *reinterpret_cast<const uint4*>(sp);
+  } else {
+    for (int e = 0; e < 8 && c + e < cols; ++e) dp[e] = sp[e];
   }
 }
 
@@ -236,20 +274,6 @@ __global__ __launch_bounds__(kThreads) void fill_zero_kernel(uint4* __restrict__
   int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   const int64_t step = (int64_t)gridDim.x * kThreads;
   for (; i < n16; i += step) p[i] = make_uint4(0, 0, 0, 0);
-}
-
-__global__ __launch_bounds__(kThreads) void to_bf16_kernel(const float* __restrict__ s,
-                                                          uint16_t* __restrict__ d, int64_t n) {
-  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  const int64_t step = (int64_t)gridDim.x * kThreads;
-  for (; i < n; i += step) d[i] = bf16_bits(s[i]);
-}
-
-__global__ __launch_bounds__(kThreads) void from_bf16_kernel(const uint16_t* __restrict__ s,
-                                                            float* __restrict__ d, int64_t n) {
-  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  const int64_t step = (int64_t)gridDim.x * kThreads;
-  for (; i < n; i += step) d[i] = __uint_as_float((unsigned)s[i] << 16);
 }
 
 template <typename T>
@@ -293,48 +317,45 @@ void launch_norm_finish(const double* partials, int nblk, int K, float rho, floa
 }
 
 void launch_perturb(const float* x, const float* g, int64_t g_stride, const float* scale,
-                    float* xt_f32, uint16_t* xt_bf16, int64_t stride, int64_t n, int K,
-                    hipStream_t s) {
+                    float* xt_f32, uint16_t* xt_bf16, const ShadowMap* map, int64_t shadow_stride,
+                    int64_t stride, int64_t n, int K, hipStream_t s) {
   const bool vec = n % 4 == 0 && g_stride % 4 == 0 && stride % 4 == 0 && aligned16(g);
-  if (vec) {
+  ShadowMap none{};
+  if (xt_bf16) {
+    // bf16 mode only exists for the MLP layouts, which are always vector-aligned
     dim3 grid(blocks_for(n / 4), K);
-    if (xt_bf16)
-      perturb_kernel<4, true><<<grid, kThreads, 0, s>>>(x, g, g_stride, scale, nullptr, xt_bf16,
-                                                        stride, n / 4);
-    else
-      perturb_kernel<4, false><<<grid, kThreads, 0, s>>>(x, g, g_stride, scale, xt_f32, nullptr,
-                                                         stride, n / 4);
+    perturb_kernel<4, true><<<grid, kThreads, 0, s>>>(x, g, g_stride, scale, nullptr, xt_bf16, *map,
+                                                      shadow_stride, stride, n / 4);
+  } else if (vec) {
+    dim3 grid(blocks_for(n / 4), K);
+    perturb_kernel<4, false><<<grid, kThreads, 0, s>>>(x, g, g_stride, scale, xt_f32, nullptr, none,
+                                                       0, stride, n / 4);
   } else {
     dim3 grid(blocks_for(n), K);
-    if (xt_bf16)
-      perturb_kernel<1, true><<<grid, kThreads, 0, s>>>(x, g, g_stride, scale, nullptr, xt_bf16,
-                                                        stride, n);
-    else
-      perturb_kernel<1, false><<<grid, kThreads, 0, s>>>(x, g, g_stride, scale, xt_f32, nullptr,
-                                                         stride, n);
+    perturb_kernel<1, false><<<grid, kThreads, 0, s>>>(x, g, g_stride, scale, xt_f32, nullptr, none,
+                                                       0, stride, n);
   }
 }
 
 void launch_descent(float* x, const float* g, int64_t g_stride, float* v, float* S,
-                    const float* y, uint16_t* shadow, int64_t stride, int64_t n, int K,
-                    const ReplicaScalars& lam, float lr, float mu, int nesterov, hipStream_t s) {
+                    const float* y, uint16_t* shadow, const ShadowMap* map, int64_t shadow_stride,
+                    int64_t stride, int64_t n, int K, const ReplicaScalars& lam, float lr, float mu,
+                    int nesterov, hipStream_t s) {
   const bool vec = n % 4 == 0 && g_stride % 4 == 0 && stride % 4 == 0 && aligned16(g);
-  if (vec) {
+  ShadowMap none{};
+  if (shadow) {
     const unsigned grid = blocks_for(n / 4) * (unsigned)K;
-    if (shadow)
-      descent_kernel<4, true><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, shadow, stride,
-                                                        n / 4, K, lam, lr, mu, nesterov);
-    else
-      descent_kernel<4, false><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, nullptr, stride,
-                                                         n / 4, K, lam, lr, mu, nesterov);
+    descent_kernel<4, true><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, shadow, *map,
+                                                      shadow_stride, stride, n / 4, K, lam, lr, mu,
+                                                      nesterov);
+  } else if (vec) {
+    const unsigned grid = blocks_for(n / 4) * (unsigned)K;
+    descent_kernel<4, false><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, nullptr, none, 0,
+                                                       stride, n / 4, K, lam, lr, mu, nesterov);
   } else {
     const unsigned grid = blocks_for(n) * (unsigned)K;
-    if (shadow)
-      descent_kernel<1, true><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, shadow, stride, n,
-                                                        K, lam, lr, mu, nesterov);
-    else
-      descent_kernel<1, false><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, nullptr, stride,
-                                                         n, K, lam, lr, mu, nesterov);
+    descent_kernel<1, false><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, nullptr, none, 0,
+                                                       stride, n, K, lam, lr, mu, nesterov);
   }
 }
 
@@ -350,27 +371,29 @@ void launch_center(float* S, float* y, float* gprev, int64_t stride, int64_t n,
   }
 }
 
-void launch_broadcast(const float* src, float* dst, uint16_t* dst_bf16, int64_t stride, int64_t n,
-                      int K, hipStream_t s) {
+void launch_broadcast(const float* src, float* dst, int64_t stride, int64_t n, int K, hipStream_t s) {
   // internal buffers only: n and stride are multiples of 4 by construction
-  const unsigned grid = blocks_for(n / 4);
-  if (dst_bf16)
-    broadcast_kernel<4, true><<<grid, kThreads, 0, s>>>(src, dst, dst_bf16, stride, n / 4, K);
-  else
-    broadcast_kernel<4, false><<<grid, kThreads, 0, s>>>(src, dst, nullptr, stride, n / 4, K);
+  broadcast_kernel<4><<<blocks_for(n / 4), kThreads, 0, s>>>(src, dst, stride, n / 4, K);
+}
+
+void launch_shadow_refresh(const float* x, uint16_t* shadow, const ShadowMap& map, int64_t stride,
+                           int64_t shadow_stride, int64_t n, int K, hipStream_t s) {
+  dim3 grid(blocks_for(n / 4), K);
+  shadow_refresh_kernel<<<grid, kThreads, 0, s>>>(x, shadow, map, stride, shadow_stride, n / 4);
+}
+
+void launch_rowmajor_to_b32s(const uint16_t* src, uint16_t* dst, int rows, int cols, int K,
+                             hipStream_t s) {
+  const int64_t work = (int64_t)rows * ((cols + 7) / 8);
+  dim3 grid(blocks_for(work), K);
+  rowmajor_to_b32s_kernel<<<grid, kThreads, 0, s>>>(src, dst, rows, cols, b32s_blocks(cols),
+                                                    b32s_size(rows, cols));
 }
 
 void launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
   if (bytes == 0) return;
   fill_zero_kernel<<<capped_blocks((int64_t)(bytes / 16)), kThreads, 0, s>>>(
       reinterpret_cast<uint4*>(p), (int64_t)(bytes / 16));
-}
-
-void launch_to_bf16(const float* src, uint16_t* dst, int64_t n, hipStream_t s) {
-  to_bf16_kernel<<<capped_blocks(n), kThreads, 0, s>>>(src, dst, n);
-}
-void launch_from_bf16(const uint16_t* src, float* dst, int64_t n, hipStream_t s) {
-  from_bf16_kernel<<<capped_blocks(n), kThreads, 0, s>>>(src, dst, n);
 }
 
 void launch_pad_rows(const void* src, void* dst, int64_t rows, int cols, int ld_dst, int elem,

@@ -112,7 +112,15 @@ struct Layout {
   size_t x = 0, g = 0, v = 0, S = 0, xt = 0, y = 0, gprev = 0, partials = 0, norms = 0, scale = 0,
          loss_rows = 0, loss = 0, logits = 0, a0 = 0, splitk = 0, splitk_bytes = 0, total = 0;
   std::vector<size_t> act, dz;  // act[l] for l = 1..L-1, dz[l] for l = 1..L (index l)
+  // bf16 mode: every bf16 tensor is stored in the blocked layout (b32s.h)
+  std::vector<int64_t> shadow_off;   // offset of W_l's operand copy inside a replica's copy
+  int64_t shadow_stride = 0;         // elements of one replica's operand copy
+  ShadowMap map{};
   size_t es() const { return bf16 ? 2 : 4; }
+  // elements of one replica's stored [B][dims] activation-like matrix
+  int64_t act_elems(int width, int pitch) const {
+    return bf16 ? b32s_size(B, width) : (int64_t)B * pitch;
+  }
 };
 
 int check_config(const lsam_config* c) {
@@ -154,7 +162,7 @@ int check_config(const lsam_config* c) {
 
 size_t take(size_t& cursor, size_t bytes) {
   const size_t at = cursor;
-  cursor = (size_t)round_up((int64_t)(cursor + bytes), 256);
+  cursor = (size_t)round_up((int64_t)(cursor + bytes), 2048);   // whole 2 KiB blocks of the bf16 layout
   return at;
 }
 
@@ -189,6 +197,22 @@ void build_layout(const lsam_config& c, Layout& lo) {
     }
     lo.d = flat;
     lo.d_pad = off;
+    if (lo.bf16) {
+      lo.need_a0 = true;     // the input is always re-stored in the blocked layout
+      lo.map.n = lo.L;
+      int64_t so = 0;
+      for (int l = 0; l < lo.L; ++l) {
+        const Layer& ly = lo.layers[l];
+        lo.shadow_off.push_back(so);
+        lo.map.ldw[l] = ly.ldw;
+        lo.map.cblocks[l] = b32s_blocks(ly.in);
+        lo.map.begin[l] = ly.w_off;
+        lo.map.end[l] = ly.w_off + (int64_t)ly.out * ly.ldw;
+        lo.map.shadow[l] = so;
+        so += b32s_size(ly.out, ly.in);
+      }
+      lo.shadow_stride = so;
+    }
   }
   int64_t nb = (lo.d_pad + 65535) / 65536;
   lo.nblk = (int)(nb < 1 ? 1 : (nb > 1024 ? 1024 : nb));
@@ -199,7 +223,7 @@ void build_layout(const lsam_config& c, Layout& lo) {
   lo.v = take(cur, vec);
   lo.S = take(cur, vec);
   lo.g = lo.raw ? 0 : take(cur, vec);
-  lo.xt = take(cur, lo.bf16 ? vec / 2 : vec);
+  lo.xt = take(cur, lo.bf16 ? (size_t)lo.K * lo.shadow_stride * 2 : vec);
   lo.y = take(cur, (size_t)lo.d_pad * 4);
   lo.gprev = take(cur, (size_t)lo.d_pad * 4);
   lo.partials = take(cur, (size_t)lo.K * lo.nblk * 8);
@@ -211,14 +235,16 @@ void build_layout(const lsam_config& c, Layout& lo) {
     lo.loss_rows = take(cur, rows * 4);
     lo.act.assign(lo.L + 1, 0);
     lo.dz.assign(lo.L + 1, 0);
-    for (int l = 1; l < lo.L; ++l) lo.act[l] = take(cur, rows * lo.ld[l] * lo.es());
-    for (int l = 1; l <= lo.L; ++l) lo.dz[l] = take(cur, rows * lo.ld[l] * lo.es());
+    auto act_bytes = [&](int l) { return (size_t)lo.K * lo.act_elems(c.dims[l], lo.ld[l]) * lo.es(); };
+    for (int l = 1; l < lo.L; ++l) lo.act[l] = take(cur, act_bytes(l));
+    for (int l = 1; l <= lo.L; ++l) lo.dz[l] = take(cur, act_bytes(l));
     lo.logits = take(cur, rows * lo.ld[lo.L] * 4);
-    if (lo.need_a0) lo.a0 = take(cur, rows * lo.ld[0] * lo.es());
+    if (lo.need_a0) lo.a0 = take(cur, act_bytes(0));
     // scratch for split-K partial sums: the largest request among this model's GEMMs
     size_t need = 0;
     for (int l = 0; l < lo.L; ++l) {
       const Layer& ly = lo.layers[l];
+      if (lo.bf16) break;      // split-K serves the fp32 kernel only
       GemmDesc d{};
       d.batch = lo.K; d.in_bf16 = lo.bf16;
       d.M = lo.B; d.N = ly.out; d.Kd = ly.in; d.a_kmajor = 1; d.b_kmajor = 1;     // forward
@@ -341,37 +367,50 @@ int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const v
   const bool want_loss = !second;
   const Layout& lo = c->lo;
   const int K = lo.K, B = lo.B, L = lo.L;
-  const size_t es = lo.es();
+  const int bf = lo.bf16 ? 1 : 0;
   hipStream_t s = c->stream;
-  auto wptr = [&](int64_t off) { return (const char*)wts + (size_t)off * es; };
+  // weight matrix l as a GEMM operand: fp32 rows inside the flat vector, or its blocked bf16 copy
+  auto wptr = [&](int l) {
+    return bf ? (const char*)wts + (size_t)lo.shadow_off[l] * 2
+              : (const char*)wts + (size_t)lo.layers[l].w_off * 4;
+  };
+  const int64_t wstride = bf ? lo.shadow_stride : lo.d_pad;
+  auto width = [&](int l) { return l == 0 ? lo.layers[0].in : lo.layers[l - 1].out; };
+  auto astride = [&](int l) { return lo.act_elems(width(l), lo.ld[l]); };
+  auto split = [&](GemmDesc& d) {
+    d.splitk_ws = lo.splitk_bytes ? c->at<float>(lo.splitk) : nullptr;
+    d.splitk_bytes = lo.splitk_bytes;
+  };
 
   for (int l = 0; l < L; ++l) {
     const Layer& ly = lo.layers[l];
     const bool last = l == L - 1;
     GemmDesc d{};
+    d.b32s = bf;
     d.A = l == 0 ? A0 : c->at<char>(lo.act[l]);
-    d.strideA = (int64_t)B * lo.ld[l]; d.ldA = lo.ld[l]; d.a_kmajor = 1;
-    d.B = wptr(ly.w_off); d.strideB = lo.d_pad; d.ldB = ly.ldw; d.b_kmajor = 1;
+    d.strideA = astride(l); d.ldA = lo.ld[l]; d.a_kmajor = 1; d.cbA = b32s_blocks(ly.in);
+    d.B = wptr(l); d.strideB = wstride; d.ldB = ly.ldw; d.b_kmajor = 1; d.cbB = b32s_blocks(ly.in);
     d.C = last ? c->at<char>(lo.logits) : c->at<char>(lo.act[l + 1]);
-    d.strideC = (int64_t)B * lo.ld[l + 1]; d.ldC = lo.ld[l + 1];
+    d.strideC = last ? (int64_t)B * lo.ld[l + 1] : astride(l + 1); d.ldC = lo.ld[l + 1];
+    d.cbC = b32s_blocks(ly.out);
     d.M = B; d.N = ly.out; d.Kd = ly.in; d.batch = K;
-    d.in_bf16 = lo.bf16; d.out_bf16 = lo.bf16 && !last;
+    d.in_bf16 = bf; d.out_bf16 = bf && !last;
     d.epilogue = last ? EPI_BIAS : EPI_BIAS_RELU;
     d.bias = c->at<float>(lo.x) + ly.b_off; d.strideBias = lo.d_pad;
-    if (second && !lo.bf16) d.bias = c->at<float>(lo.xt) + ly.b_off;
-    if (second && lo.bf16) {
+    if (second && !bf) d.bias = c->at<float>(lo.xt) + ly.b_off;
+    if (second && bf) {
       d.bias_dir = c->at<float>(lo.g) + ly.b_off;
       d.bias_scale = c->at<float>(lo.scale);
     }
-    d.splitk_ws = lo.splitk_bytes ? c->at<float>(lo.splitk) : nullptr; d.splitk_bytes = lo.splitk_bytes;
+    split(d);
     LaunchTimer t(c, KC_GEMM_FWD);
     if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "forward GEMM of layer %d rejected", l);
   }
   {
     LaunchTimer t(c, KC_SOFTMAX_CE);
-    launch_softmax_ce(c->at<float>(lo.logits), lo.ld[L], labels, c->at<char>(lo.dz[L]), lo.ld[L],
-                      lo.bf16, want_loss ? c->at<float>(lo.loss_rows) : nullptr, K, B,
-                      lo.layers[L - 1].out, s);
+    launch_softmax_ce(c->at<float>(lo.logits), lo.ld[L], labels, c->at<char>(lo.dz[L]),
+                      bf ? astride(L) : (int64_t)lo.ld[L], bf,
+                      want_loss ? c->at<float>(lo.loss_rows) : nullptr, K, B, lo.layers[L - 1].out, s);
   }
   float* g = c->at<float>(lo.g);
   for (int l = L - 1; l >= 0; --l) {
@@ -381,28 +420,31 @@ int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const v
     const void* act = l == 0 ? A0 : (const void*)c->at<char>(lo.act[l]);
     {
       GemmDesc d{};
-      d.A = dz; d.strideA = (int64_t)B * ld_dz; d.ldA = ld_dz; d.a_kmajor = 0;
-      d.B = act; d.strideB = (int64_t)B * lo.ld[l]; d.ldB = lo.ld[l]; d.b_kmajor = 0;
+      d.b32s = bf;
+      d.A = dz; d.strideA = astride(l + 1); d.ldA = ld_dz; d.a_kmajor = 0; d.cbA = b32s_blocks(ly.out);
+      d.B = act; d.strideB = astride(l); d.ldB = lo.ld[l]; d.b_kmajor = 0; d.cbB = b32s_blocks(ly.in);
       d.C = g + ly.w_off; d.strideC = lo.d_pad; d.ldC = ly.ldw;
       d.M = ly.out; d.N = ly.in; d.Kd = B; d.batch = K;
-      d.in_bf16 = lo.bf16; d.out_bf16 = 0; d.epilogue = EPI_PLAIN;
-      d.splitk_ws = lo.splitk_bytes ? c->at<float>(lo.splitk) : nullptr; d.splitk_bytes = lo.splitk_bytes;
+      d.in_bf16 = bf; d.out_bf16 = 0; d.epilogue = EPI_PLAIN;
+      split(d);
       LaunchTimer t(c, KC_GEMM_DW);
       if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "dW GEMM of layer %d rejected", l);
     }
     {
       LaunchTimer t(c, KC_BIAS_GRAD);
-      launch_bias_grad(dz, ld_dz, lo.bf16, g + ly.b_off, lo.d_pad, K, B, ly.out, s);
+      launch_bias_grad(dz, bf ? astride(l + 1) : (int64_t)ld_dz, bf, g + ly.b_off, lo.d_pad, K, B,
+                       ly.out, s);
     }
     if (l > 0) {
       GemmDesc d{};
-      d.A = dz; d.strideA = (int64_t)B * ld_dz; d.ldA = ld_dz; d.a_kmajor = 1;
-      d.B = wptr(ly.w_off); d.strideB = lo.d_pad; d.ldB = ly.ldw; d.b_kmajor = 0;
-      d.C = c->at<char>(lo.dz[l]); d.strideC = (int64_t)B * lo.ld[l]; d.ldC = lo.ld[l];
+      d.b32s = bf;
+      d.A = dz; d.strideA = astride(l + 1); d.ldA = ld_dz; d.a_kmajor = 1; d.cbA = b32s_blocks(ly.out);
+      d.B = wptr(l); d.strideB = wstride; d.ldB = ly.ldw; d.b_kmajor = 0; d.cbB = b32s_blocks(ly.in);
+      d.C = c->at<char>(lo.dz[l]); d.strideC = astride(l); d.ldC = lo.ld[l]; d.cbC = b32s_blocks(ly.in);
       d.M = B; d.N = ly.in; d.Kd = ly.out; d.batch = K;
-      d.in_bf16 = lo.bf16; d.out_bf16 = lo.bf16; d.epilogue = EPI_MASK;
-      d.mask = act; d.strideMask = (int64_t)B * lo.ld[l]; d.ldMask = lo.ld[l];
-      d.splitk_ws = lo.splitk_bytes ? c->at<float>(lo.splitk) : nullptr; d.splitk_bytes = lo.splitk_bytes;
+      d.in_bf16 = bf; d.out_bf16 = bf; d.epilogue = EPI_MASK;
+      d.mask = act; d.strideMask = astride(l); d.ldMask = lo.ld[l]; d.cbMask = b32s_blocks(ly.in);
+      split(d);
       LaunchTimer t(c, KC_GEMM_DX);
       if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "dX GEMM of layer %d rejected", l);
     }
@@ -428,7 +470,8 @@ int update_tail_first(lsam_ctx* c, const float* g1, int64_t g_stride, int64_t n,
     LaunchTimer t(c, KC_PERTURB);
     launch_perturb(c->at<float>(lo.x), g1, g_stride, c->at<float>(lo.scale),
                    lo.bf16 ? nullptr : c->at<float>(lo.xt),
-                   lo.bf16 ? c->at<uint16_t>(lo.xt) : nullptr, lo.d_pad, n, lo.K, s);
+                   lo.bf16 ? c->at<uint16_t>(lo.xt) : nullptr, &lo.map, lo.shadow_stride, lo.d_pad, n,
+                   lo.K, s);
   }
   return check_launch("norm/perturb");
 }
@@ -440,8 +483,9 @@ int update_tail_second(lsam_ctx* c, const float* g2, int64_t g_stride, int64_t n
   {
     LaunchTimer t(c, KC_DESCENT);
     launch_descent(c->at<float>(lo.x), g2, g_stride, c->at<float>(lo.v), c->at<float>(lo.S),
-                   c->at<float>(lo.y), lo.bf16 ? c->at<uint16_t>(lo.xt) : nullptr, lo.d_pad, n,
-                   lo.K, lam, c->lr, c->cfg.momentum, c->cfg.nesterov, c->stream);
+                   c->at<float>(lo.y), lo.bf16 ? c->at<uint16_t>(lo.xt) : nullptr, &lo.map,
+                   lo.shadow_stride, lo.d_pad, n, lo.K, lam, c->lr, c->cfg.momentum, c->cfg.nesterov,
+                   c->stream);
   }
   c->sched.tick();
   return check_launch("descent");
@@ -568,15 +612,16 @@ int lsam_init(const lsam_config* cfg, const float* init_params, int64_t n_init, 
   float* y = c->at<float>(lo.y);
   if (n_init == lo.d) {
     if ((rc = copy_in(c, init_params, y)) != LSAM_OK) return bail(rc);
-    launch_broadcast(y, x, lo.bf16 ? c->at<uint16_t>(lo.xt) : nullptr, lo.d_pad, lo.d_pad, lo.K,
-                     c->stream);
+    launch_broadcast(y, x, lo.d_pad, lo.d_pad, lo.K, c->stream);
   } else {
     for (int i = 0; i < lo.K; ++i)
       if ((rc = copy_in(c, init_params + (int64_t)i * lo.d, x + (int64_t)i * lo.d_pad)) != LSAM_OK)
         return bail(rc);
     if ((rc = copy_in(c, init_params + (int64_t)lo.K * lo.d, y)) != LSAM_OK) return bail(rc);
-    if (lo.bf16) launch_to_bf16(x, c->at<uint16_t>(lo.xt), (int64_t)lo.K * lo.d_pad, c->stream);
   }
+  if (lo.bf16)
+    launch_shadow_refresh(x, c->at<uint16_t>(lo.xt), lo.map, lo.d_pad, lo.shadow_stride, lo.d_pad,
+                          lo.K, c->stream);
   if (check_launch("parameter broadcast") != LSAM_OK) return bail(LSAM_EHIP);
   if (hipStreamSynchronize(c->stream) != hipSuccess)
     return bail(fail(LSAM_EHIP, "stream synchronize failed during init"));
@@ -590,13 +635,17 @@ int lsam_step(lsam_ctx* c, const void* X, const int32_t* labels, float* loss) {
   if (!X || !labels) return fail(LSAM_EINVAL, "X or labels is NULL");
   const Layout& lo = c->lo;
   const void* A0 = X;
-  if (lo.need_a0) {
+  if (reinterpret_cast<uintptr_t>(X) & 15) return fail(LSAM_EINVAL, "X must be 16-byte aligned");
+  if (lo.bf16) {
+    LaunchTimer t(c, KC_MISC);     // the input joins the other bf16 tensors in the blocked layout
+    launch_rowmajor_to_b32s(static_cast<const uint16_t*>(X), c->at<uint16_t>(lo.a0), lo.B,
+                            lo.layers[0].in, lo.K, c->stream);
+    A0 = c->at<char>(lo.a0);
+  } else if (lo.need_a0) {
     LaunchTimer t(c, KC_MISC);
     launch_pad_rows(X, c->at<char>(lo.a0), (int64_t)lo.K * lo.B, lo.layers[0].in, lo.ld[0],
                     (int)lo.es(), c->stream);
     A0 = c->at<char>(lo.a0);
-  } else if (reinterpret_cast<uintptr_t>(X) & 15) {
-    return fail(LSAM_EINVAL, "X must be 16-byte aligned");
   }
   int rc;
   const void* w1 = lo.bf16 ? (const void*)c->at<char>(lo.xt) : (const void*)c->at<char>(lo.x);
@@ -659,21 +708,24 @@ int lsam_get_buffer(lsam_ctx* c, int32_t which, int32_t replica, float* dst, int
       return copy_out(c, c->at<float>(lo.g) + roff, dst);
     case LSAM_BUF_PERTURBED: {
       if (!lo.bf16) return copy_out(c, c->at<float>(lo.xt) + roff, dst);
-      // bf16 operand copy: fetch the padded vector, widen and un-pad on the host
-      std::vector<uint16_t> h((size_t)lo.d_pad);
-      HIP_TRY(hipMemcpy(h.data(), c->at<uint16_t>(lo.xt) + roff, (size_t)lo.d_pad * 2,
-                        hipMemcpyDeviceToHost));
-      auto widen = [&](int64_t i) {
-        const uint32_t u = (uint32_t)h[(size_t)i] << 16;
-        float f;
-        memcpy(&f, &u, 4);
-        return f;
-      };
-      for (const Layer& ly : lo.layers) {
+      // bf16 operand copy of the weight matrices: fetch this replica's copy, widen and undo
+      // the blocked layout on the host; biases are not part of the copy (the GEMMs read the
+      // fp32 ones), they are reported from the master parameters
+      std::vector<uint16_t> h((size_t)lo.shadow_stride);
+      HIP_TRY(hipMemcpy(h.data(), c->at<uint16_t>(lo.xt) + (int64_t)replica * lo.shadow_stride,
+                        (size_t)lo.shadow_stride * 2, hipMemcpyDeviceToHost));
+      int rc = copy_out(c, c->at<float>(lo.x) + roff, dst);
+      if (rc != LSAM_OK) return rc;
+      for (int l = 0; l < lo.L; ++l) {
+        const Layer& ly = lo.layers[l];
+        const int cb = b32s_blocks(ly.in);
         for (int r = 0; r < ly.out; ++r)
-          for (int q = 0; q < ly.in; ++q)
-            dst[ly.w_flat + (int64_t)r * ly.in + q] = widen(ly.w_off + (int64_t)r * ly.ldw + q);
-        for (int r = 0; r < ly.out; ++r) dst[ly.b_flat + r] = widen(ly.b_off + r);
+          for (int q = 0; q < ly.in; ++q) {
+            const uint32_t u = (uint32_t)h[(size_t)(lo.shadow_off[l] + b32s_offset(r, q, cb))] << 16;
+            float f;
+            memcpy(&f, &u, 4);
+            dst[ly.w_flat + (int64_t)r * ly.in + q] = f;
+          }
       }
       return LSAM_OK;
     }
@@ -700,7 +752,8 @@ int lsam_set_buffer(lsam_ctx* c, int32_t which, int32_t replica, const float* sr
   int rc = copy_in(c, src, dst);
   if (rc != LSAM_OK) return rc;
   if (which == LSAM_BUF_PARAMS && replica >= 0 && lo.bf16) {
-    launch_to_bf16(dst, c->at<uint16_t>(lo.xt) + roff, lo.d_pad, c->stream);
+    launch_shadow_refresh(dst, c->at<uint16_t>(lo.xt) + (int64_t)replica * lo.shadow_stride, lo.map,
+                          lo.d_pad, lo.shadow_stride, lo.d_pad, 1, c->stream);
     if ((rc = check_launch("bf16 operand refresh")) != LSAM_OK) return rc;
     HIP_TRY(hipStreamSynchronize(c->stream));
   }

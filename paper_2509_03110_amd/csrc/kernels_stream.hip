@@ -43,7 +43,9 @@ __device__ __forceinline__ void store_bf16(uint16_t* p, const typename Vec<VEC>:
     u16x4 o;
 #pragma unroll
     for (int i = 0; i < 4; ++i) o[i] = bf16_bits(v[i]);
-    __builtin_nontemporal_store(o, reinterpret_cast<u16x4*>(p));   // streamed: +15 % over a plain store
+    // Plain store: a wavefront's 64-byte pieces of neighbouring blocks merge in L2 before they
+    // go out; the streaming hint measured no better once the copy became blocked.
+    *reinterpret_cast<u16x4*>(p) = o;
   } else {
     *p = bf16_bits(v);
   }

@@ -164,7 +164,9 @@ __global__ __launch_bounds__(kThreads) void perturb_kernel(
 // One workgroup updates 256 vector words of one replica; consecutive workgroups take the same
 // words of the K replicas in turn, so the K readers of a piece of y run close together and y
 // comes from HBM once.  (Looping over the replicas inside one thread, which reads y exactly
-// once, measured 8-12 % slower at K = 8 and 16.)
+// once, measured 8-12 % slower at K = 8 and 16; sending the K workgroups of a piece to the same
+// XCD, so that y misses only one L2, measured 4-9 % slower: the other XCDs' misses are served
+// by the memory-side cache, and the launch order here keeps each XCD on fewer DRAM pages.)
 template <int VEC, bool SHADOW>
 __global__ __launch_bounds__(kThreads) void descent_kernel(
     float* __restrict__ x, const float* __restrict__ g, int64_t g_stride, float* __restrict__ v,

@@ -27,6 +27,37 @@ PEAK_HBM_GBS = 8000.0
 PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 
 
+# HBM bytes per launch of each kernel class, from two `rocprofv3 --pmc` runs of this script
+# (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch scaled by what the same counter reads for a plain
+# 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
+# launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
+# kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
+TRAFFIC_SOURCES = "a0083c7c9415a389"
+TRAFFIC = {
+    "cfg2": {"bias_grad": 1445732, "center": 100986368, "descent": 538491904, "gemm_dw": 29784000,
+             "gemm_dx": 23319211, "gemm_fwd": 42419641, "perturb": 201946112,
+             "softmax_ce": 124245, "sumsq_partials": 67755819},
+    "cfg3": {"bias_grad": 13667934, "center": 1773570432, "descent": 17232319445,
+             "gemm_dw": 445868890, "gemm_dx": 250093627, "gemm_fwd": 233063084,
+             "perturb": 5065994539, "softmax_ce": 1426773, "sumsq_partials": 2027221120},
+    "cfg4": {"center": 3200045312, "descent": 25600045440, "perturb": 9600050475,
+             "sumsq_partials": 3416539595},
+    "cfg5": {"bias_grad": 117972108, "descent": 188960331200, "gemm_dw": 4344452885,
+             "gemm_dx": 2332843975, "gemm_fwd": 2034141679, "perturb": 59024429504,
+             "softmax_ce": 95913525, "sumsq_partials": 25556818549},
+}
+
+
+def kernel_sources_digest():
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2509_03110_amd", "csrc", "*"))):
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
 def gemm_flops(w):
     """Per all-replica step: flops of the forward, dX and dW GEMM classes (both passes)."""
     B, K = w.batch, w.K
@@ -168,6 +199,7 @@ def main():
         eng.lsam_timing_enable(False)
         flops = gemm_flops(w) if w.dims else {}
         nbytes = stream_bytes(w)
+        traffic = TRAFFIC.get(w.name, {}) if kernel_sources_digest() == TRAFFIC_SOURCES else {}
         for name, (cnt, tot) in stats.items():
             if cnt == 0:
                 continue
@@ -175,12 +207,15 @@ def main():
                  "avg_launch_ms": tot / cnt}
             if name in flops and tot > 0:
                 k.update(bound="mfma", achieved=flops[name] * steps / (tot * 1e-3) / 1e12,
-                         peak=PEAK_TFLOPS[w.gemm_dtype], unit="TFLOP/s")
+                         peak=PEAK_TFLOPS[w.gemm_dtype], unit="TFLOP/s",
+                         algorithmic_flops_per_launch=flops[name] * steps / cnt)
             elif name in nbytes and tot > 0:
                 k.update(bound="hbm", achieved=nbytes[name] * steps / (tot * 1e-3) / 1e9,
-                         peak=PEAK_HBM_GBS, unit="GB/s")
+                         peak=PEAK_HBM_GBS, unit="GB/s",
+                         algorithmic_bytes_per_launch=nbytes[name] * steps / cnt)
             if "achieved" in k:
                 k["frac"] = k["achieved"] / k["peak"]
+            k["traffic"] = traffic.get(name)
             kernels[name] = k
         ranked = [n for n in sorted(kernels, key=lambda n: -kernels[n]["ms_per_step"])
                   if "achieved" in kernels[n]]
@@ -188,7 +223,7 @@ def main():
             top = kernels[ranked[0]]
             roof = {"kernel": ranked[0], "bound": top["bound"], "achieved": top["achieved"],
                     "peak": top["peak"], "unit": top["unit"], "frac": top["frac"],
-                    "traffic": None, "avg_launch_ms": top["avg_launch_ms"]}
+                    "traffic": top["traffic"], "avg_launch_ms": top["avg_launch_ms"]}
 
     out = {
         "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": steps,

@@ -27,10 +27,10 @@ struct DueList {
 // g: [K] rows of `n` floats with row stride `g_stride`; partials: [K, nblk] doubles.
 void launch_sumsq_partials(const float* g, int64_t g_stride, int64_t n, int K, double* partials,
                            int nblk, hipStream_t s);
-// Pass 2: norms[k] = sqrt(sum_b partials[k,b]); scale[k] = rho / (norm + gamma).
+// Pass 2: norms[k] = sqrt(sum_{b<nblk} partials[k * partials_stride + b]); scale[k] = rho / (norm + gamma).
 // If loss_rows != nullptr also reduces loss_rows [K,B] to loss_out[k] = mean (both passes of
 // the tree are fixed-order, so the result is run-to-run deterministic).
-void launch_norm_finish(const double* partials, int nblk, int K, float rho, float gamma,
+void launch_norm_finish(const double* partials, int nblk, int64_t partials_stride, int K, float rho, float gamma,
                         float* norms, float* scale, const float* loss_rows, int B,
                         float* loss_out, hipStream_t s);
 // x~ = x + scale[k] * g.  Writes fp32 (xt_f32), or, if xt_bf16 is non-null, the bf16 operand
@@ -86,11 +86,18 @@ struct GemmDesc {
   // bf16 tensors in the blocked layout (b32s.h): column blocks of the stored A, B, bf16 C, mask;
   // strideA/B/C/Mask then count elements of one replica's stored matrix and ld* are unused
   int b32s; int cbA, cbB, cbC, cbMask;
+  // If set (fp32 results only): every workgroup that writes results also writes the sum of
+  // their squares, in double, to sumsq[k * sumsq_stride + slot], slot = 0 .. slots-1 inside a
+  // replica; `slots` comes back through launch_gemm.  Fixed summation order.
+  double* sumsq; int64_t sumsq_stride;
 };
-int launch_gemm(const GemmDesc& d, hipStream_t s);   // 0 ok, <0 unsupported shape
+// 0 ok, <0 unsupported shape; *sumsq_slots (if non-null) = slots written per replica
+int launch_gemm(const GemmDesc& d, hipStream_t s, int* sumsq_slots = nullptr);
+// Upper bound of the slots any launch of an [M, N] result can use.
+int gemm_sumsq_capacity(int M, int N);
 size_t gemm_splitk_bytes(const GemmDesc& d);          // scratch this GEMM would like (0: none)
 // bf16 fast path (direct-to-LDS ring); returns 1 when the shape is left to the generic kernel.
-int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s);
+int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s, int* sumsq_slots);
 void set_gemm_tile_override(int code);               // tuning hook: 0 = choose by shape
 
 // Softmax cross-entropy, forward and backward.  logits [K,B,ld] fp32; labels [K,B];
@@ -101,7 +108,9 @@ void launch_softmax_ce(const float* logits, int ld, const int32_t* labels, void*
                        int dz_bf16, float* loss_rows, int K, int B, int C, hipStream_t s);
 // db[k][n] = sum_b dz[k][b][n]; dz as written by the kernels above (ld: row pitch, or one
 // replica's stored size for the blocked bf16 layout).
-void launch_bias_grad(const void* dz, int64_t ld, int dz_bf16, float* db, int64_t strideDb, int K,
-                      int B, int N, hipStream_t s);
+// If sumsq is non-null, workgroup j of replica k also writes the sum of squares of its 64
+// results to sumsq[k * sumsq_stride + j]; returns the number of such slots per replica.
+int launch_bias_grad(const void* dz, int64_t ld, int dz_bf16, float* db, int64_t strideDb, int K,
+                     int B, int N, double* sumsq, int64_t sumsq_stride, hipStream_t s);
 
 }  // namespace lsam

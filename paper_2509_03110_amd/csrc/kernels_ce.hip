@@ -80,7 +80,9 @@ template <> __device__ __forceinline__ float get<__bf16>(const __bf16* p) {
 template <typename TD>
 __global__ __launch_bounds__(kThreads) void bias_grad_kernel(const TD* __restrict__ dz, long long ld,
                                                             float* __restrict__ db,
-                                                            long long strideDb, int B, int N) {
+                                                            long long strideDb, int B, int N,
+                                                            double* __restrict__ sumsq,
+                                                            long long strideSumsq) {
   __shared__ float part[kWaves][64];
   const int k = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -104,8 +106,19 @@ __global__ __launch_bounds__(kThreads) void bias_grad_kernel(const TD* __restric
   }
   part[wave][lane] = (s0 + s1) + (s2 + s3);
   __syncthreads();
-  if (wave == 0 && n < N)
-    db[(long long)k * strideDb + n] = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
+  if (wave == 0) {
+    float r = 0.f;
+    if (n < N) {
+      r = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
+      db[(long long)k * strideDb + n] = r;
+    }
+    if (sumsq != nullptr) {        // sum of the squares of this workgroup's 64 results
+      double q = (double)r * (double)r;
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) q += __shfl_xor(q, off, 64);
+      if (lane == 0) sumsq[(long long)k * strideSumsq + blockIdx.x] = q;
+    }
+  }
 }
 
 }  // namespace
@@ -122,13 +135,16 @@ void launch_softmax_ce(const float* logits, int ld, const int32_t* labels, void*
                                                        loss_rows, rows, B, C);
 }
 
-void launch_bias_grad(const void* dz, int64_t ld, int dz_bf16, float* db, int64_t strideDb, int K,
-                      int B, int N, hipStream_t s) {
+int launch_bias_grad(const void* dz, int64_t ld, int dz_bf16, float* db, int64_t strideDb, int K,
+                     int B, int N, double* sumsq, int64_t sumsq_stride, hipStream_t s) {
   dim3 grid((N + 63) / 64, K);
   if (dz_bf16)
-    bias_grad_kernel<__bf16><<<grid, kThreads, 0, s>>>((const __bf16*)dz, ld, db, strideDb, B, N);
+    bias_grad_kernel<__bf16><<<grid, kThreads, 0, s>>>((const __bf16*)dz, ld, db, strideDb, B, N,
+                                                       sumsq, sumsq_stride);
   else
-    bias_grad_kernel<float><<<grid, kThreads, 0, s>>>((const float*)dz, ld, db, strideDb, B, N);
+    bias_grad_kernel<float><<<grid, kThreads, 0, s>>>((const float*)dz, ld, db, strideDb, B, N,
+                                                      sumsq, sumsq_stride);
+  return (int)grid.x;
 }
 
 }  // namespace lsam

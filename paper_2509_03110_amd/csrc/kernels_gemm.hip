@@ -45,7 +45,20 @@ struct GemmParams {
   // range owned by its own workgroup, which writes raw fp32 sums to partial[split]
   float* partial; long long strideSplit; int ldP;
   int splits, steps_per_split;
+  // optional sum of squares of the stored results, one slot per workgroup that stores them
+  double* sumsq; long long strideSumsq;
 };
+
+// Sum over a 256-thread workgroup in a fixed order (lanes by xor-shuffle, then the four
+// wavefronts in turn); the result is valid in thread 0.
+__device__ __forceinline__ double workgroup_sum(double v) {
+  __shared__ double part[4];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return threadIdx.x == 0 ? (part[0] + part[1]) + (part[2] + part[3]) : 0.0;
+}
 
 int g_tile_override = 0;   // tuning hook, 0 = choose by shape
 
@@ -385,6 +398,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
   const int c4 = (tid % LANES_PER_ROW) * 4;     // first of this lane's 4 columns (read-out phase)
   const int rsub = tid / LANES_PER_ROW;
   const int n = n0 + c4;
+  float ssq = 0.f;                              // squares of what this thread stores
   f32x4 bv = {0.f, 0.f, 0.f, 0.f};
   if (has_bias) {
 #pragma unroll
@@ -427,6 +441,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
               if (!(widen(me[r]) > 0.f)) v[r] = 0.f;
           }
           *reinterpret_cast<cvec*>(C + (long long)m * ldC + n) = Pack<TC>::from(v);
+          ssq += (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
         } else {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
@@ -434,45 +449,60 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
               float o = v[r];
               if (masked && !(widen(mask[(long long)m * p.ldMask + n + r]) > 0.f)) o = 0.f;
               C[(long long)m * ldC + n + r] = Pack<TC>::one(o);
+              ssq += o * o;
             }
         }
       }
     }
     if (i + 1 < TM) __syncthreads();
   }
+  if (p.sumsq != nullptr && !split_mode) {
+    const double tot = workgroup_sum((double)ssq);
+    if (tid == 0) p.sumsq[(long long)bat * p.strideSumsq + t] = tot;
+  }
 }
 
 // Sums the split-K partials in split order and applies the epilogue the GEMM skipped.
+// Grid: x over the M * ldP/4 vector words of one replica, y = replica.
 __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(GemmParams p) {
   const int n4 = p.ldP / 4;
-  const long long total = (long long)p.batch * p.M * n4;
+  const long long per_rep = (long long)p.M * n4;
   const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
-  if (idx >= total) return;
-  const int c = (int)(idx % n4) * 4;
-  const long long row = idx / n4;             // bat * M + m
-  const int m = (int)(row % p.M), bat = (int)(row / p.M);
-  if (c >= p.N) return;
-  f32x4 v = {0.f, 0.f, 0.f, 0.f};
-  for (int s = 0; s < p.splits; ++s)
-    v += *reinterpret_cast<const f32x4*>(p.partial + (long long)s * p.strideSplit + row * p.ldP + c);
-  const bool has_bias = p.epilogue == EPI_BIAS || p.epilogue == EPI_BIAS_RELU;
-  float* C = reinterpret_cast<float*>(p.C) + (long long)bat * p.strideC + (long long)m * p.ldC;
-  const float* mask = p.mask ? reinterpret_cast<const float*>(p.mask) + (long long)bat * p.strideMask +
-                                   (long long)m * p.ldMask
-                             : nullptr;
+  const int bat = blockIdx.y;
+  float ssq = 0.f;
+  if (idx < per_rep) {
+    const int c = (int)(idx % n4) * 4;
+    const int m = (int)(idx / n4);
+    const long long row = (long long)bat * p.M + m;
+    if (c < p.N) {
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      for (int s = 0; s < p.splits; ++s)
+        v += *reinterpret_cast<const f32x4*>(p.partial + (long long)s * p.strideSplit + row * p.ldP + c);
+      const bool has_bias = p.epilogue == EPI_BIAS || p.epilogue == EPI_BIAS_RELU;
+      float* C = reinterpret_cast<float*>(p.C) + (long long)bat * p.strideC + (long long)m * p.ldC;
+      const float* mask = p.mask ? reinterpret_cast<const float*>(p.mask) +
+                                       (long long)bat * p.strideMask + (long long)m * p.ldMask
+                                 : nullptr;
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int n = c + r;
-    if (n >= p.N) break;
-    float o = v[r];
-    if (has_bias) {
-      float bv = p.bias[(long long)bat * p.strideBias + n];
-      if (p.bias_dir) bv = bv + p.bias_scale[bat] * p.bias_dir[(long long)bat * p.strideBias + n];
-      o += bv;
+      for (int r = 0; r < 4; ++r) {
+        const int n = c + r;
+        if (n >= p.N) break;
+        float o = v[r];
+        if (has_bias) {
+          float bv = p.bias[(long long)bat * p.strideBias + n];
+          if (p.bias_dir) bv = bv + p.bias_scale[bat] * p.bias_dir[(long long)bat * p.strideBias + n];
+          o += bv;
+        }
+        if (p.epilogue == EPI_BIAS_RELU) o = o > 0.f ? o : 0.f;
+        if (p.epilogue == EPI_MASK && !(mask[n] > 0.f)) o = 0.f;
+        C[n] = o;
+        ssq += o * o;
+      }
     }
-    if (p.epilogue == EPI_BIAS_RELU) o = o > 0.f ? o : 0.f;
-    if (p.epilogue == EPI_MASK && !(mask[n] > 0.f)) o = 0.f;
-    C[n] = o;
+  }
+  if (p.sumsq != nullptr) {
+    const double tot = workgroup_sum((double)ssq);
+    if (threadIdx.x == 0) p.sumsq[(long long)bat * p.strideSumsq + blockIdx.x] = tot;
   }
 }
 
@@ -522,7 +552,7 @@ Plan make_plan(const GemmDesc& d, int tile_override) {
 }
 
 template <typename T, typename TC, int BM, int BN, int BKU, bool AK, bool BK_>
-int launch_one(const GemmParams& p0, hipStream_t s) {
+int launch_one(const GemmParams& p0, hipStream_t s, int* sumsq_slots) {
   constexpr int OCC = (BM * BN >= 256 * 256) ? 1 : 2;
   GemmParams p = p0;
   p.tilesM = (p.M + BM - 1) / BM;
@@ -541,26 +571,29 @@ int launch_one(const GemmParams& p0, hipStream_t s) {
     attr_set = true;
   }
   kern<<<p.chunks * 8, kThreads, smem, s>>>(p);
+  int slots = p.tilesM * p.tilesN;
   if (p.splits > 1) {
-    const long long total = (long long)p.batch * p.M * (p.ldP / 4);
-    splitk_reduce_kernel<<<(unsigned)((total + kThreads - 1) / kThreads), kThreads, 0, s>>>(p);
+    const long long per_rep = (long long)p.M * (p.ldP / 4);
+    slots = (int)((per_rep + kThreads - 1) / kThreads);
+    splitk_reduce_kernel<<<dim3((unsigned)slots, (unsigned)p.batch), kThreads, 0, s>>>(p);
   }
+  if (sumsq_slots) *sumsq_slots = slots;
   return 0;
 }
 
 template <typename T, typename TC, bool AK, bool BK_>
-int launch_tiled(const GemmParams& p, const Plan& pl, hipStream_t s) {
-  if (pl.bm == 256 && pl.bn == 128) return launch_one<T, TC, 256, 128, 4, AK, BK_>(p, s);
-  if (pl.bm == 256) return launch_one<T, TC, 256, 256, 8, AK, BK_>(p, s);
-  if (pl.bm == 128) return launch_one<T, TC, 128, 128, 8, AK, BK_>(p, s);
-  return launch_one<T, TC, 64, 64, 8, AK, BK_>(p, s);
+int launch_tiled(const GemmParams& p, const Plan& pl, hipStream_t s, int* slots) {
+  if (pl.bm == 256 && pl.bn == 128) return launch_one<T, TC, 256, 128, 4, AK, BK_>(p, s, slots);
+  if (pl.bm == 256) return launch_one<T, TC, 256, 256, 8, AK, BK_>(p, s, slots);
+  if (pl.bm == 128) return launch_one<T, TC, 128, 128, 8, AK, BK_>(p, s, slots);
+  return launch_one<T, TC, 64, 64, 8, AK, BK_>(p, s, slots);
 }
 
 template <typename T, typename TC>
-int launch_layout(const GemmDesc& d, const GemmParams& p, const Plan& pl, hipStream_t s) {
-  if (d.a_kmajor && d.b_kmajor) return launch_tiled<T, TC, true, true>(p, pl, s);
-  if (d.a_kmajor && !d.b_kmajor) return launch_tiled<T, TC, true, false>(p, pl, s);
-  if (!d.a_kmajor && !d.b_kmajor) return launch_tiled<T, TC, false, false>(p, pl, s);
+int launch_layout(const GemmDesc& d, const GemmParams& p, const Plan& pl, hipStream_t s, int* slots) {
+  if (d.a_kmajor && d.b_kmajor) return launch_tiled<T, TC, true, true>(p, pl, s, slots);
+  if (d.a_kmajor && !d.b_kmajor) return launch_tiled<T, TC, true, false>(p, pl, s, slots);
+  if (!d.a_kmajor && !d.b_kmajor) return launch_tiled<T, TC, false, false>(p, pl, s, slots);
   return -1;
 }
 
@@ -572,10 +605,18 @@ void set_gemm_tile_override(int code) {
   g_tile_override = code;
 }
 
-int launch_gemm(const GemmDesc& d, hipStream_t s) {
+// Smallest tiles are 64x64; a split-K reduce uses one workgroup per 256 vector words of
+// [M][N rounded up to 4].
+int gemm_sumsq_capacity(int M, int N) {
+  const long long tiles = (long long)((M + 63) / 64) * ((N + 63) / 64);
+  const long long words = ((long long)M * ((N + 3) / 4) + kThreads - 1) / kThreads;
+  return (int)(tiles > words ? tiles : words);
+}
+
+int launch_gemm(const GemmDesc& d, hipStream_t s, int* sumsq_slots) {
   // bf16 operands live in the blocked layout and have their own kernel; this file's kernel
   // serves the fp32 configurations
-  if (d.in_bf16) return launch_gemm_bf16(d, g_tile_override, s);
+  if (d.in_bf16) return launch_gemm_bf16(d, g_tile_override, s, sumsq_slots);
   GemmParams p;
   p.A = (const char*)d.A; p.strideA = d.strideA; p.ldA = d.ldA;
   p.B = (const char*)d.B; p.strideB = d.strideB; p.ldB = d.ldB;
@@ -587,6 +628,7 @@ int launch_gemm(const GemmDesc& d, hipStream_t s) {
   p.bias_dir = d.bias_dir; p.bias_scale = d.bias_scale;
   p.mask = (const char*)d.mask; p.strideMask = d.strideMask; p.ldMask = d.ldMask;
   p.partial = nullptr; p.strideSplit = 0; p.ldP = 0; p.splits = 1; p.steps_per_split = 1 << 30;
+  p.sumsq = d.sumsq; p.strideSumsq = d.sumsq_stride;
   if (d.M <= 0 || d.N <= 0 || d.Kd <= 0 || d.batch <= 0) return -1;
   // 16-byte units: pitches must be multiples of 8 elements and bases 16-byte aligned.
   if ((d.ldA % 8) || (d.ldB % 8) || (d.ldC % 8) || ((uintptr_t)d.A & 15) ||
@@ -608,7 +650,7 @@ int launch_gemm(const GemmDesc& d, hipStream_t s) {
     p.ldP = pl.ldP;
     p.strideSplit = (long long)d.batch * d.M * pl.ldP;
   }
-  return launch_layout<float, float>(d, p, pl, s);
+  return launch_layout<float, float>(d, p, pl, s, sumsq_slots);
 }
 
 }  // namespace lsam

@@ -44,6 +44,7 @@ struct Bf16GemmParams {
   const char* mask; long long strideMask; int ldMask;
   int cbA, cbB, cbC, cbMask;          // column blocks of the stored A, B, C (bf16 out) and mask
   unsigned bytesA, bytesB;            // size of one replica's stored A and B
+  double* sumsq; long long strideSumsq;   // optional: sum of squares of each tile's results
 };
 
 // s_waitcnt immediate: vmcnt = vm (0..63), lgkmcnt = lgkm (0..15), expcnt untouched.
@@ -318,6 +319,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
   const int c4 = (lane % LANES_PER_ROW) * 4;
   const int rsub = lane / LANES_PER_ROW;
   const int n = n0 + wn0 + c4;
+  float ssq = 0.f;                                 // squares of what this thread stores
   f32x4 bv = {0.f, 0.f, 0.f, 0.f};
   if (has_bias) {
 #pragma unroll
@@ -364,6 +366,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
               if (!(static_cast<float>(me[r]) > 0.f)) v[r] = 0.f;
           }
           __builtin_nontemporal_store(Out<TC>::from(v), reinterpret_cast<cvec*>(C + coff));
+          ssq += (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
         } else {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
@@ -371,10 +374,21 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
               float o = v[r];
               if (masked && !(static_cast<float>(mask[moff + r]) > 0.f)) o = 0.f;
               C[coff + r] = Out<TC>::one(o);
+              ssq += o * o;
             }
         }
       }
     }
+  }
+  if (p.sumsq != nullptr) {
+    // fixed order: lanes by xor-shuffle, then the four wavefronts in turn
+    __shared__ double part[4];
+    double tot = (double)ssq;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) tot += __shfl_xor(tot, off, 64);
+    if (lane == 0) part[wave] = tot;
+    __syncthreads();
+    if (tid == 0) p.sumsq[(long long)bat * p.strideSumsq + t_in] = (part[0] + part[1]) + (part[2] + part[3]);
   }
 }
 
@@ -393,7 +407,7 @@ LSAM_INSTANTIATE(__bf16, false, false)
 #undef LSAM_INSTANTIATE
 
 template <typename TC, int BM, int BN, int NSTAGE, bool AK, bool BK_>
-int launch_one(const Bf16GemmParams& p0, hipStream_t s) {
+int launch_one(const Bf16GemmParams& p0, hipStream_t s, int* slots) {
   constexpr int OCC = (BM * BN >= 256 * 256) ? 1 : 2;
   Bf16GemmParams p = p0;
   p.tilesM = (p.M + BM - 1) / BM;
@@ -401,21 +415,22 @@ int launch_one(const Bf16GemmParams& p0, hipStream_t s) {
   p.total = p.tilesM * p.tilesN * p.batch;
   p.chunks = (p.total + 7) / 8;
   gemm_bf16_kernel<TC, BM, BN, NSTAGE, AK, BK_, OCC><<<p.chunks * 8, kThreads, 0, s>>>(p);
+  if (slots) *slots = p.tilesM * p.tilesN;
   return 0;
 }
 
 template <typename TC, bool AK, bool BK_>
-int launch_tiled(const Bf16GemmParams& p, int tile, hipStream_t s) {
-  if (tile == 256) return launch_one<TC, 256, 256, 4, AK, BK_>(p, s);
-  if (tile == 2) return launch_one<TC, 256, 128, 3, AK, BK_>(p, s);
-  return launch_one<TC, 128, 128, 4, AK, BK_>(p, s);
+int launch_tiled(const Bf16GemmParams& p, int tile, hipStream_t s, int* slots) {
+  if (tile == 256) return launch_one<TC, 256, 256, 4, AK, BK_>(p, s, slots);
+  if (tile == 2) return launch_one<TC, 256, 128, 3, AK, BK_>(p, s, slots);
+  return launch_one<TC, 128, 128, 4, AK, BK_>(p, s, slots);
 }
 
 template <typename TC>
-int launch_layout(const GemmDesc& d, const Bf16GemmParams& p, int tile, hipStream_t s) {
-  if (d.a_kmajor && d.b_kmajor) return launch_tiled<TC, true, true>(p, tile, s);
-  if (d.a_kmajor && !d.b_kmajor) return launch_tiled<TC, true, false>(p, tile, s);
-  if (!d.a_kmajor && !d.b_kmajor) return launch_tiled<TC, false, false>(p, tile, s);
+int launch_layout(const GemmDesc& d, const Bf16GemmParams& p, int tile, hipStream_t s, int* slots) {
+  if (d.a_kmajor && d.b_kmajor) return launch_tiled<TC, true, true>(p, tile, s, slots);
+  if (d.a_kmajor && !d.b_kmajor) return launch_tiled<TC, true, false>(p, tile, s, slots);
+  if (!d.a_kmajor && !d.b_kmajor) return launch_tiled<TC, false, false>(p, tile, s, slots);
   return -1;
 }
 
@@ -423,7 +438,7 @@ int launch_layout(const GemmDesc& d, const Bf16GemmParams& p, int tile, hipStrea
 
 // All bf16 GEMMs of the MLP path come here; operands, bf16 results and the mask are in the
 // blocked layout.  Returns 0 after a launch, -1 if the description is not usable.
-int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s) {
+int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s, int* sumsq_slots) {
   if (!d.in_bf16 || !d.b32s) return -1;
   if (d.M <= 0 || d.N <= 0 || d.Kd <= 0 || d.batch <= 0) return -1;
   auto tiles = [&](int bm, int bn) {
@@ -467,7 +482,10 @@ int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s) {
   p.cbA = d.cbA; p.cbB = d.cbB; p.cbC = d.cbC; p.cbMask = d.cbMask;
   p.bytesA = (unsigned)(blocksA * 2048);
   p.bytesB = (unsigned)(blocksB * 2048);
-  return d.out_bf16 ? launch_layout<__bf16>(d, p, tile, s) : launch_layout<float>(d, p, tile, s);
+  p.sumsq = d.out_bf16 ? nullptr : d.sumsq;
+  p.strideSumsq = d.sumsq_stride;
+  return d.out_bf16 ? launch_layout<__bf16>(d, p, tile, s, sumsq_slots)
+                    : launch_layout<float>(d, p, tile, s, sumsq_slots);
 }
 
 }  // namespace lsam

@@ -110,12 +110,12 @@ __global__ __launch_bounds__(kThreads) void sumsq_partials_kernel(
 
 // ---- gradient norm, pass 2 (+ mean loss) ----------------------------------------------------
 __global__ __launch_bounds__(kThreads) void norm_finish_kernel(
-    const double* __restrict__ partials, int nblk, float rho, float gamma,
+    const double* __restrict__ partials, int nblk, int64_t pstride, float rho, float gamma,
     float* __restrict__ norms, float* __restrict__ scale, const float* __restrict__ loss_rows,
     int B, float* __restrict__ loss_out) {
   const int k = blockIdx.x;
   double s = 0.0;
-  for (int i = threadIdx.x; i < nblk; i += kThreads) s += partials[(int64_t)k * nblk + i];
+  for (int i = threadIdx.x; i < nblk; i += kThreads) s += partials[(int64_t)k * pstride + i];
   s = block_sum(s);
   if (threadIdx.x == 0) {
     const double n = sqrt(s);
@@ -348,11 +348,11 @@ void launch_sumsq_partials(const float* g, int64_t g_stride, int64_t n, int K, d
   }
 }
 
-void launch_norm_finish(const double* partials, int nblk, int K, float rho, float gamma,
-                        float* norms, float* scale, const float* loss_rows, int B,
+void launch_norm_finish(const double* partials, int nblk, int64_t partials_stride, int K, float rho,
+                        float gamma, float* norms, float* scale, const float* loss_rows, int B,
                         float* loss_out, hipStream_t s) {
-  norm_finish_kernel<<<K, kThreads, 0, s>>>(partials, nblk, rho, gamma, norms, scale, loss_rows,
-                                            B, loss_out);
+  norm_finish_kernel<<<K, kThreads, 0, s>>>(partials, nblk, partials_stride, rho, gamma, norms,
+                                            scale, loss_rows, B, loss_out);
 }
 
 void launch_perturb(const float* x, const float* g, int64_t g_stride, const float* scale,

@@ -214,8 +214,16 @@ void build_layout(const lsam_config& c, Layout& lo) {
       lo.shadow_stride = so;
     }
   }
-  int64_t nb = (lo.d_pad + 65535) / 65536;
-  lo.nblk = (int)(nb < 1 ? 1 : (nb > 1024 ? 1024 : nb));
+  if (lo.raw) {
+    int64_t nb = (lo.d_pad + 65535) / 65536;
+    lo.nblk = (int)(nb < 1 ? 1 : (nb > 1024 ? 1024 : nb));
+  } else {
+    // the first backward pass leaves one partial sum of squares per workgroup that wrote a
+    // piece of the gradient: room for the most any tile choice can produce
+    int64_t cap = 0;
+    for (const Layer& ly : lo.layers) cap += gemm_sumsq_capacity(ly.out, ly.in) + (ly.out + 63) / 64;
+    lo.nblk = (int)cap;
+  }
 
   size_t cur = 0;
   const size_t vec = (size_t)lo.K * lo.d_pad * 4;
@@ -290,6 +298,7 @@ struct lsam_ctx {
   char* ws = nullptr;
   hipStream_t stream = nullptr;
   float lr = 0.f, rho = 0.f;
+  int norm_slots = 0;   // partial sums of squares left by the last first-pass backward
   // timing
   bool timing = false;
   std::vector<TimedLaunch> pending;
@@ -413,6 +422,9 @@ int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const v
                       want_loss ? c->at<float>(lo.loss_rows) : nullptr, K, B, lo.layers[L - 1].out, s);
   }
   float* g = c->at<float>(lo.g);
+  // first pass: the kernels that write the gradient also leave the partial sums of its squares
+  double* ssq = second ? nullptr : c->at<double>(lo.partials);
+  int slots = 0;
   for (int l = L - 1; l >= 0; --l) {
     const Layer& ly = lo.layers[l];
     const char* dz = c->at<char>(lo.dz[l + 1]);
@@ -427,13 +439,18 @@ int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const v
       d.M = ly.out; d.N = ly.in; d.Kd = B; d.batch = K;
       d.in_bf16 = bf; d.out_bf16 = 0; d.epilogue = EPI_PLAIN;
       split(d);
+      if (ssq) { d.sumsq = ssq + slots; d.sumsq_stride = lo.nblk; }
+      int used = 0;
       LaunchTimer t(c, KC_GEMM_DW);
-      if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "dW GEMM of layer %d rejected", l);
+      if (launch_gemm(d, s, &used) != 0) return fail(LSAM_EINVAL, "dW GEMM of layer %d rejected", l);
+      if (ssq) slots += used;
     }
     {
       LaunchTimer t(c, KC_BIAS_GRAD);
-      launch_bias_grad(dz, bf ? astride(l + 1) : (int64_t)ld_dz, bf, g + ly.b_off, lo.d_pad, K, B,
-                       ly.out, s);
+      const int used = launch_bias_grad(dz, bf ? astride(l + 1) : (int64_t)ld_dz, bf, g + ly.b_off,
+                                        lo.d_pad, K, B, ly.out, ssq ? ssq + slots : nullptr,
+                                        lo.nblk, s);
+      if (ssq) slots += used;
     }
     if (l > 0) {
       GemmDesc d{};
@@ -449,19 +466,26 @@ int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const v
       if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "dX GEMM of layer %d rejected", l);
     }
   }
+  if (ssq) {
+    if (slots > lo.nblk) return fail(LSAM_ESTATE, "gradient-norm partials overran their buffer");
+    c->norm_slots = slots;
+  }
   return check_launch("forward/backward");
 }
 
 int update_tail_first(lsam_ctx* c, const float* g1, int64_t g_stride, int64_t n, float* loss) {
   const Layout& lo = c->lo;
   hipStream_t s = c->stream;
-  {
+  int nparts = lo.nblk;
+  if (lo.raw) {
     LaunchTimer t(c, KC_SUMSQ);
     launch_sumsq_partials(g1, g_stride, n, lo.K, c->at<double>(lo.partials), lo.nblk, s);
+  } else {
+    nparts = c->norm_slots;      // written by the backward pass that produced g1
   }
   {
     LaunchTimer t(c, KC_NORM_FINISH);
-    launch_norm_finish(c->at<double>(lo.partials), lo.nblk, lo.K, c->rho, c->cfg.gamma,
+    launch_norm_finish(c->at<double>(lo.partials), nparts, lo.nblk, lo.K, c->rho, c->cfg.gamma,
                        c->at<float>(lo.norms), c->at<float>(lo.scale),
                        lo.raw ? nullptr : c->at<float>(lo.loss_rows), lo.B,
                        lo.raw ? nullptr : (loss ? loss : c->at<float>(lo.loss)), s);

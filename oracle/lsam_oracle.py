@@ -169,14 +169,24 @@ class Mlp:
         return loss, grad
 
 
+# Which method the K replicas run.  ALG_LSAM is Algorithm 2.  ALG_DATA_PARALLEL is the
+# synchronous baseline of the experiments section (DP-SAM; DP-SGD when rho = 0): every
+# iteration the workers' gradients are averaged, at the first pass and again at the perturbed
+# point, every replica takes the same momentum step on the averaged gradient, and there is
+# neither coupling nor a center update (communication interval 1, nothing left to average).
+ALG_LSAM = 0
+ALG_DATA_PARALLEL = 1
+
+
 class LsamOracle:
     """K replicas x_i, velocities v_i, iterate sums S_i, one center y."""
 
     def __init__(self, K, init_params, dims=(), d_raw=0, batch=0, gemm_dtype=0,
                  rho=0.05, gamma=1e-12, lr=0.1, lr_center=1.0, momentum=0.9, beta=0.9,
                  lambda0=0.5, lambda_abs=-1.0, nesterov=1, tau=None, tau_min=1, tau_max=1,
-                 sched_seed=0, sched_mode=SCHED_FIXED):
+                 sched_seed=0, sched_mode=SCHED_FIXED, algorithm=ALG_LSAM):
         self.K = int(K)
+        self.algorithm = int(algorithm)
         self.model = Mlp(dims, gemm_dtype) if len(dims) else None
         self.d = self.model.d if self.model else int(d_raw)
         self.batch = int(batch)
@@ -210,6 +220,8 @@ class LsamOracle:
 
     def coupling(self, i):
         """lambda_i = lambda0 / (eta tau_i) unless a fixed lambda is given."""
+        if self.algorithm == ALG_DATA_PARALLEL:
+            return 0.0
         if self.lambda_abs >= 0.0:
             return self.lambda_abs
         return self.lambda0 / (self.lr * self.sched.tau[i])
@@ -235,6 +247,19 @@ class LsamOracle:
         """One local iteration of every replica on its own minibatch; returns the K
         first-pass losses."""
         losses = np.zeros(self.K)
+        if self.algorithm == ALG_DATA_PARALLEL:
+            data = [(np.asarray(X[i], dtype=np.float64), np.asarray(labels[i]).astype(np.int64))
+                    for i in range(self.K)]
+            g1 = np.zeros((self.K, self.d))
+            for i, (Xi, li) in enumerate(data):
+                losses[i], g1[i] = self.model.loss_and_grad(self.x[i], Xi, li)
+            xt = self._ascend_mean(g1)
+            g2 = np.zeros((self.K, self.d))
+            for i, (Xi, li) in enumerate(data):
+                _, g2[i] = self.model.loss_and_grad(xt[i], Xi, li)
+            self._descend_mean(g2)
+            self.sched.tick()
+            return losses
         for i in range(self.K):
             Xi = np.asarray(X[i], dtype=np.float64)
             li = np.asarray(labels[i]).astype(np.int64)
@@ -246,8 +271,25 @@ class LsamOracle:
         self.sched.tick()
         return losses
 
+    def _ascend_mean(self, g1):
+        """Data-parallel ascent: one perturbation, from the average of the K gradients."""
+        gbar = np.mean(g1, axis=0)
+        self.last_g1[:] = gbar
+        return np.stack([self._ascend(i, gbar) for i in range(self.K)])
+
+    def _descend_mean(self, g2):
+        gbar = np.mean(g2, axis=0)
+        self.last_g2[:] = gbar
+        for i in range(self.K):
+            self._descend(i, gbar)
+
     def step_grads(self, g1, g2):
         """Raw-vector mode: the two gradients are handed in instead of computed."""
+        if self.algorithm == ALG_DATA_PARALLEL:
+            self._ascend_mean(np.asarray(g1, dtype=np.float64))
+            self._descend_mean(np.asarray(g2, dtype=np.float64))
+            self.sched.tick()
+            return
         for i in range(self.K):
             a = np.asarray(g1[i], dtype=np.float64)
             self._ascend(i, a)
@@ -256,6 +298,8 @@ class LsamOracle:
 
     # -- the center step ---------------------------------------------------------------
     def sync(self):
+        if self.algorithm == ALG_DATA_PARALLEL:
+            return 0
         due = self.sched.due()
         if not due:
             return 0

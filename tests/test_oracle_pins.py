@@ -7,8 +7,8 @@ import pytest
 import torch
 
 import workloads
-from oracle.lsam_oracle import (LsamOracle, Mlp, PeriodSchedule, SCHED_FIXED, SCHED_REDRAW,
-                                bf16_round)
+from oracle.lsam_oracle import (ALG_DATA_PARALLEL, LsamOracle, Mlp, PeriodSchedule, SCHED_FIXED,
+                                SCHED_REDRAW, bf16_round)
 
 TINY = workloads.Workload("tiny", K=2, dims=(5, 4, 3), batch=3, rho=0.05, tau=(2, 2),
                           n_classes=3, data_seed=11)
@@ -337,3 +337,59 @@ def test_bf16_model_rounds_only_matrix_operands():
     l16, g16 = m16.loss_and_grad(x, X, lab)
     assert l32 == l16
     assert np.max(np.abs(g16 - g32)) <= 2.0 ** -8 * np.max(np.abs(g32)) * 1.01
+
+
+# ---- data-parallel baseline (DP-SAM / DP-SGD of the experiments section) ------------------
+@pytest.mark.parametrize("rho", [0.05, 0.0])
+def test_data_parallel_mode_is_sam_on_the_pooled_batch(rho):
+    """K workers that average their gradients at both passes take exactly the (momentum) SAM
+    step of one model on the union of their minibatches: the loss is a mean over B samples per
+    worker and the gradients are averaged over K workers, i.e. a mean over K*B samples.
+    Witness: torch autograd + torch.optim.SGD on the pooled batch."""
+    w = TINY.scaled(K=3, dims=(6, 5, 3), batch=4, tau=(2, 2, 2))
+    x0 = workloads.init_params(w)
+    lr, mu = 0.1, 0.9
+    o = LsamOracle(3, x0, dims=w.dims, batch=w.batch, rho=rho, gamma=0.0 if rho else 1e-12, lr=lr,
+                   momentum=mu, nesterov=1, tau=(2, 2, 2), lambda0=0.5,
+                   algorithm=ALG_DATA_PARALLEL)
+
+    def loss_fn(p, X, lab):
+        a = torch.tensor(X, dtype=torch.float64)
+        W1 = p[:30].view(5, 6); b1 = p[30:35]; W2 = p[35:50].view(3, 5); b2 = p[50:53]
+        z = torch.relu(a @ W1.T + b1) @ W2.T + b2
+        return torch.nn.functional.cross_entropy(z, torch.tensor(lab, dtype=torch.long))
+
+    p = torch.tensor(x0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.SGD([p], lr=lr, momentum=mu, nesterov=True)
+    y0 = o.get_params(-1)
+    for t in range(5):
+        X, lab = _tiny_data(w, t)
+        o.step(X, lab)
+        assert o.sync() == 0                       # nothing to synchronise, the center never moves
+        Xp, lp = X.reshape(-1, X.shape[-1]), lab.reshape(-1)
+        g1, = torch.autograd.grad(loss_fn(p, Xp, lp), p)
+        with torch.no_grad():
+            q = p + rho * g1 / g1.norm() if rho else p.clone()
+        q.requires_grad_(True)
+        g2, = torch.autograd.grad(loss_fn(q, Xp, lp), q)
+        opt.zero_grad()
+        p.grad = g2
+        opt.step()
+        for i in range(3):                         # all replicas stay identical
+            assert np.allclose(o.get_params(i), p.detach().numpy(), rtol=1e-11, atol=1e-15)
+    assert np.array_equal(o.get_params(-1), y0)
+
+
+def test_data_parallel_raw_mode_averages_handed_gradients():
+    K, d = 3, 7
+    rng = np.random.default_rng(5)
+    x0 = rng.standard_normal(d)
+    g1, g2 = rng.standard_normal((K, d)), rng.standard_normal((K, d))
+    o = LsamOracle(K, x0, d_raw=d, rho=0.1, gamma=0.0, lr=0.5, momentum=0.0, tau=(1, 1, 1),
+                   algorithm=ALG_DATA_PARALLEL)
+    o.step_grads(g1, g2)
+    m1, m2 = g1.mean(0), g2.mean(0)
+    assert np.allclose(o.last_norm, np.linalg.norm(m1))
+    assert np.allclose(o.last_perturbed[1], x0 + 0.1 * m1 / np.linalg.norm(m1))
+    for i in range(K):
+        assert np.allclose(o.get_params(i), x0 - 0.5 * m2, rtol=1e-14)

@@ -50,6 +50,18 @@ extern "C" {
 #define LSAM_SCHED_FIXED  0  /* periods drawn once at init                       */
 #define LSAM_SCHED_REDRAW 1  /* a replica draws a new period at each of its syncs */
 
+/* What the K replicas run.
+ * LSAM_ALG_LSAM: Algorithm 2.  With rho = 0 the perturbed point is the point itself and the
+ *   step makes one forward/backward pass instead of two (the ESGD / EASGD family of the
+ *   "One-step LSAM / ESGD Update" algorithm; same results as the two-pass step).
+ * LSAM_ALG_DATA_PARALLEL: the synchronous baseline of Section "Experiments" (DP-SAM; DP-SGD
+ *   with rho = 0), communication interval 1: every step the K gradients are averaged, at the
+ *   first pass and again at the perturbed point; the one perturbation and the one momentum
+ *   step computed from the averages are applied to every replica.  No coupling term and no
+ *   center: lambda, beta, lr_center and the periods are ignored, `lsam_sync` returns 0. */
+#define LSAM_ALG_LSAM          0
+#define LSAM_ALG_DATA_PARALLEL 1
+
 typedef struct lsam_ctx lsam_ctx;
 
 /* Inputs of Algorithm 2 ("pulling coefficient lambda, perturbation radius rho, learning
@@ -75,6 +87,7 @@ typedef struct {
   int32_t tau_max;
   uint64_t sched_seed;    /* s_0 of the period generator                              */
   int32_t sched_mode;     /* LSAM_SCHED_FIXED or LSAM_SCHED_REDRAW                    */
+  int32_t algorithm;      /* LSAM_ALG_LSAM or LSAM_ALG_DATA_PARALLEL                  */
 } lsam_config;
 
 /* Which per-replica buffer `lsam_get_buffer` copies out. */

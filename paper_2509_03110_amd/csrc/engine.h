@@ -46,6 +46,11 @@ void launch_descent(float* x, const float* g, int64_t g_stride, float* v, float*
                     const float* y, uint16_t* shadow, const ShadowMap* map, int64_t shadow_stride,
                     int64_t stride, int64_t n, int K, const ReplicaScalars& lam, float lr, float mu,
                     int nesterov, hipStream_t s);
+// dst[c * dst_stride + i] = (1/K) sum_k src[k * src_stride + i] for c < copies, i < n; the K
+// terms are added in replica order.  dst may be src (each index is read in full before it is
+// written).
+void launch_grad_mean(const float* src, int64_t src_stride, float* dst, int64_t dst_stride,
+                      int64_t n, int K, int copies, hipStream_t s);
 // Center update over the due replicas (Algorithm 2, synchronous optimization step).
 void launch_center(float* S, float* y, float* gprev, int64_t stride, int64_t n,
                    const DueList& due, float inv_m, float beta, float lr_center, int has_prev,

@@ -238,6 +238,25 @@ __global__ __launch_bounds__(kThreads) void descent_kernel(
   }
 }
 
+// ---- average over replicas (synchronous data-parallel baseline) ---------------------------------
+template <int VEC>
+__global__ __launch_bounds__(kThreads) void grad_mean_kernel(
+    const float* src, int64_t src_stride, float* dst, int64_t dst_stride, int64_t nv, int K,
+    int copies) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= nv) return;
+  auto acc = ldv<VEC>(src + i * VEC);
+  for (int k = 1; k < K; ++k) {
+    const auto gv = ldv<VEC>(src + (int64_t)k * src_stride + i * VEC);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) set_elem(acc, e, elem(acc, e) + elem(gv, e));
+  }
+  const float inv = 1.f / (float)K;
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) set_elem(acc, e, elem(acc, e) * inv);
+  for (int c = 0; c < copies; ++c) stv<VEC>(dst + (int64_t)c * dst_stride + i * VEC, acc);
+}
+
 // ---- center update ------------------------------------------------------------------------------
 template <int VEC>
 __global__ __launch_bounds__(kThreads) void center_kernel(
@@ -406,6 +425,16 @@ void launch_descent(float* x, const float* g, int64_t g_stride, float* v, float*
     descent_kernel<1, false><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, nullptr, none, 0,
                                                        stride, n, K, lam, lr, mu, nesterov);
   }
+}
+
+void launch_grad_mean(const float* src, int64_t src_stride, float* dst, int64_t dst_stride,
+                      int64_t n, int K, int copies, hipStream_t s) {
+  if (n % 4 == 0 && src_stride % 4 == 0 && dst_stride % 4 == 0 && aligned16(src) && aligned16(dst))
+    grad_mean_kernel<4><<<blocks_for(n / 4), kThreads, 0, s>>>(src, src_stride, dst, dst_stride,
+                                                               n / 4, K, copies);
+  else
+    grad_mean_kernel<1><<<blocks_for(n), kThreads, 0, s>>>(src, src_stride, dst, dst_stride, n, K,
+                                                           copies);
 }
 
 void launch_center(float* S, float* y, float* gprev, int64_t stride, int64_t n,

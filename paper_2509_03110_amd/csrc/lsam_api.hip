@@ -109,6 +109,7 @@ struct Layout {
   bool need_a0 = false;
   int nblk = 1;
   // byte offsets into the workspace
+  size_t gmean = 0;   // raw-vector mode, data-parallel baseline: the averaged gradient [d_pad]
   size_t x = 0, g = 0, v = 0, S = 0, xt = 0, y = 0, gprev = 0, partials = 0, norms = 0, scale = 0,
          loss_rows = 0, loss = 0, logits = 0, a0 = 0, splitk = 0, splitk_bytes = 0, total = 0;
   std::vector<size_t> act, dz;  // act[l] for l = 1..L-1, dz[l] for l = 1..L (index l)
@@ -157,6 +158,8 @@ int check_config(const lsam_config* c) {
   }
   if (c->sched_mode != LSAM_SCHED_FIXED && c->sched_mode != LSAM_SCHED_REDRAW)
     return fail(LSAM_EINVAL, "sched_mode must be 0 or 1");
+  if (c->algorithm != LSAM_ALG_LSAM && c->algorithm != LSAM_ALG_DATA_PARALLEL)
+    return fail(LSAM_EINVAL, "algorithm must be LSAM_ALG_LSAM or LSAM_ALG_DATA_PARALLEL");
   return LSAM_OK;
 }
 
@@ -234,6 +237,7 @@ void build_layout(const lsam_config& c, Layout& lo) {
   lo.xt = take(cur, lo.bf16 ? (size_t)lo.K * lo.shadow_stride * 2 : vec);
   lo.y = take(cur, (size_t)lo.d_pad * 4);
   lo.gprev = take(cur, (size_t)lo.d_pad * 4);
+  if (lo.raw && c.algorithm == LSAM_ALG_DATA_PARALLEL) lo.gmean = take(cur, (size_t)lo.d_pad * 4);
   lo.partials = take(cur, (size_t)lo.K * lo.nblk * 8);
   lo.norms = take(cur, (size_t)lo.K * 4);
   lo.scale = take(cur, (size_t)lo.K * 4);
@@ -363,6 +367,7 @@ int check_launch(const char* what) {
 }
 
 float coupling(const lsam_ctx* c, int i) {
+  if (c->cfg.algorithm == LSAM_ALG_DATA_PARALLEL) return 0.f;
   if (c->cfg.lambda_abs >= 0.f) return c->cfg.lambda_abs;
   return (float)((double)c->cfg.lambda0 / ((double)c->lr * (double)c->sched.tau()[i]));
 }
@@ -372,7 +377,7 @@ float coupling(const lsam_ctx* c, int i) {
 // fp32 mode sit in the perturbed copy and in bf16 mode are formed in the GEMM epilogue from
 // the fp32 master bias and the first-pass bias gradient (only matrix operands are rounded).
 int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const void* wts,
-                     bool second) {
+                     bool second, bool fuse_norm) {
   const bool want_loss = !second;
   const Layout& lo = c->lo;
   const int K = lo.K, B = lo.B, L = lo.L;
@@ -423,7 +428,7 @@ int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const v
   }
   float* g = c->at<float>(lo.g);
   // first pass: the kernels that write the gradient also leave the partial sums of its squares
-  double* ssq = second ? nullptr : c->at<double>(lo.partials);
+  double* ssq = fuse_norm ? c->at<double>(lo.partials) : nullptr;
   int slots = 0;
   for (int l = L - 1; l >= 0; --l) {
     const Layer& ly = lo.layers[l];
@@ -473,24 +478,27 @@ int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const v
   return check_launch("forward/backward");
 }
 
-int update_tail_first(lsam_ctx* c, const float* g1, int64_t g_stride, int64_t n, float* loss) {
+// Norm of g1 and the perturbed point.  `partials_ready`: the kernels that wrote g1 already
+// left the partial sums of its squares.  With rho = 0 the perturbed point is x itself and is
+// not written.
+int update_tail_first(lsam_ctx* c, const float* g1, int64_t g_stride, int64_t n, float* loss,
+                      bool partials_ready) {
   const Layout& lo = c->lo;
   hipStream_t s = c->stream;
-  int nparts = lo.nblk;
-  if (lo.raw) {
+  int nparts = partials_ready ? c->norm_slots : (lo.nblk < 1024 ? lo.nblk : 1024);
+  if (!partials_ready) {
     LaunchTimer t(c, KC_SUMSQ);
-    launch_sumsq_partials(g1, g_stride, n, lo.K, c->at<double>(lo.partials), lo.nblk, s);
-  } else {
-    nparts = c->norm_slots;      // written by the backward pass that produced g1
+    launch_sumsq_partials(g1, g_stride, n, lo.K, c->at<double>(lo.partials), nparts, s);
   }
   {
     LaunchTimer t(c, KC_NORM_FINISH);
-    launch_norm_finish(c->at<double>(lo.partials), nparts, lo.nblk, lo.K, c->rho, c->cfg.gamma,
+    launch_norm_finish(c->at<double>(lo.partials), nparts, partials_ready ? lo.nblk : nparts, lo.K,
+                       c->rho, c->cfg.gamma,
                        c->at<float>(lo.norms), c->at<float>(lo.scale),
                        lo.raw ? nullptr : c->at<float>(lo.loss_rows), lo.B,
                        lo.raw ? nullptr : (loss ? loss : c->at<float>(lo.loss)), s);
   }
-  {
+  if (c->rho != 0.f) {
     LaunchTimer t(c, KC_PERTURB);
     launch_perturb(c->at<float>(lo.x), g1, g_stride, c->at<float>(lo.scale),
                    lo.bf16 ? nullptr : c->at<float>(lo.xt),
@@ -672,12 +680,23 @@ int lsam_step(lsam_ctx* c, const void* X, const int32_t* labels, float* loss) {
     A0 = c->at<char>(lo.a0);
   }
   int rc;
+  const bool dp = c->cfg.algorithm == LSAM_ALG_DATA_PARALLEL;
+  float* g = c->at<float>(lo.g);
+  // data-parallel baseline: every replica's gradient is replaced by the average over replicas
+  auto average = [&]() {
+    LaunchTimer t(c, KC_MISC);
+    launch_grad_mean(g, lo.d_pad, g, lo.d_pad, lo.d_pad, lo.K, lo.K, c->stream);
+  };
   const void* w1 = lo.bf16 ? (const void*)c->at<char>(lo.xt) : (const void*)c->at<char>(lo.x);
-  if ((rc = forward_backward(c, A0, labels, w1, false)) != LSAM_OK) return rc;
-  if ((rc = update_tail_first(c, c->at<float>(lo.g), lo.d_pad, lo.d_pad, loss)) != LSAM_OK)
-    return rc;
-  if ((rc = forward_backward(c, A0, labels, c->at<char>(lo.xt), true)) != LSAM_OK) return rc;
-  return update_tail_second(c, c->at<float>(lo.g), lo.d_pad, lo.d_pad);
+  if ((rc = forward_backward(c, A0, labels, w1, false, !dp)) != LSAM_OK) return rc;
+  if (dp) average();
+  if ((rc = update_tail_first(c, g, lo.d_pad, lo.d_pad, loss, !dp)) != LSAM_OK) return rc;
+  if (c->rho != 0.f) {     // otherwise the perturbed point is x and g already is its gradient
+    if ((rc = forward_backward(c, A0, labels, c->at<char>(lo.xt), true, false)) != LSAM_OK)
+      return rc;
+    if (dp) average();
+  }
+  return update_tail_second(c, g, lo.d_pad, lo.d_pad);
 }
 
 int lsam_step_grads(lsam_ctx* c, const float* g1, const float* g2) {
@@ -687,12 +706,28 @@ int lsam_step_grads(lsam_ctx* c, const float* g1, const float* g2) {
   if ((reinterpret_cast<uintptr_t>(g1) & 3) || (reinterpret_cast<uintptr_t>(g2) & 3))
     return fail(LSAM_EINVAL, "gradients must be 4-byte aligned");
   int rc;
-  if ((rc = update_tail_first(c, g1, c->lo.d, c->lo.d, nullptr)) != LSAM_OK) return rc;
-  return update_tail_second(c, g2, c->lo.d, c->lo.d);
+  const Layout& lo = c->lo;
+  if (c->cfg.algorithm == LSAM_ALG_DATA_PARALLEL) {
+    // one averaged vector, read by every replica (row stride 0)
+    float* m = c->at<float>(lo.gmean);
+    {
+      LaunchTimer t(c, KC_MISC);
+      launch_grad_mean(g1, lo.d, m, 0, lo.d, lo.K, 1, c->stream);
+    }
+    if ((rc = update_tail_first(c, m, 0, lo.d, nullptr, false)) != LSAM_OK) return rc;
+    {
+      LaunchTimer t(c, KC_MISC);
+      launch_grad_mean(g2, lo.d, m, 0, lo.d, lo.K, 1, c->stream);
+    }
+    return update_tail_second(c, m, 0, lo.d);
+  }
+  if ((rc = update_tail_first(c, g1, lo.d, lo.d, nullptr, false)) != LSAM_OK) return rc;
+  return update_tail_second(c, g2, lo.d, lo.d);
 }
 
 int lsam_sync(lsam_ctx* c) {
   if (!c) return fail(LSAM_EINVAL, "ctx is NULL");
+  if (c->cfg.algorithm == LSAM_ALG_DATA_PARALLEL) return 0;   // no center in that baseline
   const Layout& lo = c->lo;
   const DueList due = c->sched.due();
   if (due.n == 0) return 0;

@@ -249,3 +249,67 @@ def test_wrong_mode_calls_fail_cleanly():
     with pytest.raises(lsam.LsamError):
         lsam._check(lsam.lib().lsam_get_params(g._h, 3, z.cpu().numpy().ctypes.data, 64))
     g.close()
+
+
+# ---- comparators on the same kernels: synchronous data-parallel baseline, one-pass rho = 0 ---------
+@pytest.mark.parametrize("rho", [0.05, 0.0])
+def test_data_parallel_baseline_fp32(rho):
+    """DP-SAM (DP-SGD for rho = 0): gradients averaged over the replicas at both passes."""
+    w = workloads.WORKLOADS["cfg1"].scaled(name="dp32", K=3, tau=(2, 3, 4), steps=8, rho=rho,
+                                           algorithm=lsam.ALG_DATA_PARALLEL)
+    run_mlp(w, w.steps, 1e-4, 1e-3, margin=True)
+    run_mlp(w, w.steps, 1e-4, 1e-3, margin=False)
+
+
+def test_data_parallel_baseline_bf16():
+    full = workloads.WORKLOADS["cfg3"]
+    dims = (full.dims[0] // 8,) + (256,) * (len(full.dims) - 2) + (full.dims[-1],)
+    w = full.scaled(name="dp16", K=4, dims=dims, batch=32, steps=6,
+                    algorithm=lsam.ALG_DATA_PARALLEL)
+    run_mlp(w, w.steps, 2e-2, 2e-2, margin=True)
+    run_mlp(w, w.steps, 2e-2, 2e-2, margin=False, tol_flip=1e-1, anchor_after=2)
+
+
+@pytest.mark.parametrize("d,K", [(1000, 3), (65536 + 12, 4)])
+def test_data_parallel_baseline_raw_mode(d, K):
+    w = workloads.WORKLOADS["cfg4"].scaled(K=K, d_raw=d, tau=None, steps=6,
+                                           algorithm=lsam.ALG_DATA_PARALLEL)
+    g, o = make_pair(w)
+    for t in range(w.steps):
+        g1, g2 = workloads.raw_grads(w, t)
+        g.lsam_step_grads(torch.from_numpy(g1).to(DEV), torch.from_numpy(g2).to(DEV))
+        o.step_grads(g1, g2)
+        assert np.allclose(g.lsam_get_norms(), o.last_norm, rtol=1e-5)
+        for i in range(K):
+            assert rel_max(g.lsam_get_buffer(lsam.BUF_PERTURBED, i), o.last_perturbed[i]) < 1e-6
+        assert g.lsam_sync() == 0 and o.sync() == 0
+        check_state(g, o, 1e-4, "data-parallel raw d=%d step %d" % (d, t + 1))
+    g.close()
+
+
+@pytest.mark.parametrize("bf16", [0, 1])
+def test_rho_zero_takes_one_pass_and_matches_two_pass_oracle(bf16):
+    """With rho = 0 the step makes a single forward/backward pass (the ESGD / EASGD family);
+    the oracle still walks through both passes of Algorithm 2 and must agree."""
+    if bf16:
+        full = workloads.WORKLOADS["cfg5"]
+        dims = (full.dims[0] // 8,) + (128,) * (len(full.dims) - 2) + (full.dims[-1],)
+        w = full.scaled(name="esgd16", dims=dims, batch=64, steps=6, rho=0.0)
+        run_mlp(w, w.steps, 2e-2, 2e-2, margin=True)
+    else:
+        w = workloads.WORKLOADS["cfg1"].scaled(name="esgd32", steps=10, rho=0.0)
+        run_mlp(w, w.steps, 1e-4, 1e-3, margin=True)
+        run_mlp(w, w.steps, 1e-4, 1e-3, margin=False)
+
+
+def test_rho_zero_raw_mode():
+    w = workloads.WORKLOADS["cfg4"].scaled(K=3, d_raw=5000, tau=(2, 3, 4), steps=9, rho=0.0)
+    g, o = make_pair(w)
+    for t in range(w.steps):
+        g1, g2 = workloads.raw_grads(w, t)
+        g.lsam_step_grads(torch.from_numpy(g1).to(DEV), torch.from_numpy(g2).to(DEV))
+        o.step_grads(g1, g2)
+        assert np.allclose(g.lsam_get_norms(), o.last_norm, rtol=1e-5)
+        assert g.lsam_sync() == o.sync()
+        check_state(g, o, 1e-4, "rho=0 raw step %d" % (t + 1))
+    g.close()

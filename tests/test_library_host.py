@@ -36,7 +36,7 @@ def test_param_count_matches_workload(name):
 def test_bad_configs_are_rejected_with_a_message():
     w = workloads.WORKLOADS["cfg1"]
     for field, value in [("K", 0), ("K", 65), ("batch", 0), ("gemm_dtype", 7), ("rho", -1.0),
-                         ("momentum", 1.0), ("sched_mode", 3), ("lr", 0.0)]:
+                         ("momentum", 1.0), ("sched_mode", 3), ("lr", 0.0), ("algorithm", 2)]:
         cfg, keep = lsam.config_from_workload(w)
         setattr(cfg, field, value)
         assert lsam.lsam_workspace_bytes(cfg) == 0

@@ -9,7 +9,8 @@ def oracle_from(w, init, **over):
               gemm_dtype=w.gemm_dtype, rho=w.rho, gamma=w.gamma, lr=w.lr,
               lr_center=w.lr_center, momentum=w.momentum, beta=w.beta, lambda0=w.lambda0,
               lambda_abs=w.lambda_abs, nesterov=w.nesterov, tau=w.tau, tau_min=w.tau_min,
-              tau_max=w.tau_max, sched_seed=w.sched_seed, sched_mode=w.sched_mode)
+              tau_max=w.tau_max, sched_seed=w.sched_seed, sched_mode=w.sched_mode,
+              algorithm=w.algorithm)
     kw.update(over)
     return LsamOracle(**kw)
 

@@ -45,6 +45,7 @@ class Workload:
     tau_max: int = 1
     sched_seed: int = 0
     sched_mode: int = SCHED_FIXED
+    algorithm: int = 0                      # 0 = LSAM, 1 = synchronous data-parallel baseline
     steps: int = 20
     data_seed: int = 0
     n_classes: int = field(default=0)

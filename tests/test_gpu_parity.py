@@ -313,3 +313,44 @@ def test_rho_zero_raw_mode():
         assert g.lsam_sync() == o.sync()
         check_state(g, o, 1e-4, "rho=0 raw step %d" % (t + 1))
     g.close()
+
+
+# ---- Algorithm 1 mode and the theorems' step-size / radius schedules on a convex toy ---------------
+def test_algorithm_one_mode_constant_versus_decaying_perturbation():
+    """K = 1, tau = 1, beta = 0, eta' = alpha is Algorithm 1 (x-update with coupling, then
+    y <- alpha x + (1 - alpha) y).  On f(x) = x'Ax/2 with exact gradients, a constant radius
+    leaves ||grad f|| hovering at a floor set by rho (the constant-perturbation theorem's
+    O(rho^2) term), while rho_t = rho_0/sqrt(t+1) with eta_t = eta_0/sqrt(t+1) keeps
+    descending (the decaying-perturbation theorem).  Every step is also held to the oracle."""
+    d, alpha, lam, T = 64, 0.3, 0.5, 1500
+    rng = np.random.default_rng(3)
+    A = np.linspace(0.1, 1.0, d)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    finals = {}
+    for decaying in (False, True):
+        w = workloads.WORKLOADS["cfg4"].scaled(K=1, d_raw=d, tau=(1,), beta=0.0, lr_center=alpha,
+                                               momentum=0.0, lambda_abs=lam, rho=0.5, lr=0.5,
+                                               gamma=1e-12)
+        g, o = make_pair(w, x0)
+        for t in range(T):
+            lr, rho = (0.5 / np.sqrt(t + 1), 0.5 / np.sqrt(t + 1)) if decaying else (0.5, 0.5)
+            g.lsam_set_scalars(lr, rho)
+            o.set_scalars(np.float32(lr), np.float32(rho))
+            x = g.lsam_get_params(0).astype(np.float64)
+            g1 = A * x
+            xt = x + np.float64(np.float32(rho)) * g1 / (np.linalg.norm(g1) + 1e-12)
+            g2 = A * xt
+            g1f, g2f = g1.astype(np.float32)[None], g2.astype(np.float32)[None]
+            g.lsam_step_grads(torch.from_numpy(g1f).to(DEV), torch.from_numpy(g2f).to(DEV))
+            o.step_grads(g1f, g2f)
+            assert g.lsam_sync() == 1 and o.sync() == 1
+            if t % 250 == 0 or t == T - 1:
+                # the oracle is fed the GPU's gradients, so the two can only differ by one
+                # step's rounding plus what the contraction has not yet damped
+                close_enough(g.lsam_get_params(0), o.get_params(0), 1e-4, "x at step %d" % t)
+                close_enough(g.lsam_get_params(-1), o.get_params(-1), 1e-4, "y at step %d" % t)
+        finals[decaying] = float(np.linalg.norm(A * g.lsam_get_params(0).astype(np.float64)))
+        g.close()
+    print("||grad f|| after %d steps: constant rho %.3e, decaying %.3e" % (T, finals[False], finals[True]))
+    assert finals[False] > 1e-2               # the floor of the constant radius
+    assert finals[True] < 0.2 * finals[False]

@@ -169,6 +169,71 @@ class Mlp:
         return loss, grad
 
 
+# ---- Langevin noise of the sampler ----------------------------------------------------------------
+# Section "Langevin Dynamics for Sampling" names SGLD as the Sampler of Algorithm 2; the
+# experiments run it noise-free.  With noise_scale = sigma > 0 the sampler step becomes
+#   x <- x - eta (G + mu v) + sigma sqrt(2 eta) xi,   xi ~ N(0, I),
+# the Euler-Maruyama step of dx = grad log q dt + sqrt(2) dW at sigma = 1, mu = 0.
+# xi comes from the counter-based generator Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel
+# random numbers: as easy as 1, 2, 3", SC'11), so that any element of any step can be produced
+# on its own.  One call yields the four normals of four neighbouring columns:
+#   counter = (column // 4, row, (2 * layer + is_bias) | replica << 16, step)   [MLP]
+#   counter = (j // 4 mod 2^32, j // 4 >> 32, replica << 16, step)               [raw vector]
+#   key     = (seed mod 2^32, seed >> 32)
+#   u_i = ((r_i >> 8) + 1/2) / 2^24;  z0, z1 = sqrt(-2 ln u0) (cos, sin)(2 pi u1);  z2, z3 from u2, u3
+# (a bias vector counts as one row; `step` is the number of sampler steps taken before).
+PHILOX_M0, PHILOX_M1 = 0xD2511F53, 0xCD9E8D57
+PHILOX_W0, PHILOX_W1 = 0x9E3779B9, 0xBB67AE85
+
+
+def philox4x32_10(counter, key):
+    """counter: four arrays of 32-bit values, key: two 32-bit values -> four uint64 arrays
+    holding the 32-bit outputs."""
+    m32 = np.uint64(0xFFFFFFFF)
+    c = [np.asarray(x, dtype=np.uint64) & m32 for x in np.broadcast_arrays(*counter)]
+    k0, k1 = np.uint64(key[0]) & m32, np.uint64(key[1]) & m32
+    for _ in range(10):
+        p0 = np.uint64(PHILOX_M0) * c[0]
+        p1 = np.uint64(PHILOX_M1) * c[2]
+        c = [(p1 >> np.uint64(32)) ^ c[1] ^ k0, p1 & m32, (p0 >> np.uint64(32)) ^ c[3] ^ k1, p0 & m32]
+        k0 = (k0 + np.uint64(PHILOX_W0)) & m32
+        k1 = (k1 + np.uint64(PHILOX_W1)) & m32
+    return c
+
+
+def normals_from_counters(counter, key):
+    """[..., 4] standard normals, one Philox call per leading index (Box-Muller)."""
+    r = philox4x32_10(counter, key)
+    u = [((x >> np.uint64(8)).astype(np.float64) + 0.5) / 16777216.0 for x in r]
+    out = np.empty(u[0].shape + (4,))
+    for pair in range(2):
+        rad = np.sqrt(-2.0 * np.log(u[2 * pair]))
+        ang = 2.0 * np.pi * u[2 * pair + 1]
+        out[..., 2 * pair] = rad * np.cos(ang)
+        out[..., 2 * pair + 1] = rad * np.sin(ang)
+    return out
+
+
+def langevin_noise(dims, d_raw, replica, step, seed):
+    """xi for one replica and step, in the flat parameter layout."""
+    key = (seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF)
+    if not len(dims):
+        groups = np.arange((d_raw + 3) // 4, dtype=np.uint64)
+        z = normals_from_counters((groups & np.uint64(0xFFFFFFFF), groups >> np.uint64(32),
+                                   np.uint64(replica << 16), np.uint64(step)), key)
+        return z.reshape(-1)[:d_raw]
+    parts = []
+    for l in range(len(dims) - 1):
+        fi, fo = dims[l], dims[l + 1]
+        for is_bias, rows, cols in ((0, fo, fi), (1, 1, fo)):
+            cg = np.arange((cols + 3) // 4, dtype=np.uint64)[None, :]
+            rr = np.arange(rows, dtype=np.uint64)[:, None]
+            code = np.uint64((2 * l + is_bias) | (replica << 16))
+            z = normals_from_counters((cg, rr, code, np.uint64(step)), key)
+            parts.append(z.reshape(rows, -1)[:, :cols].ravel())
+    return np.concatenate(parts)
+
+
 # Which method the K replicas run.  ALG_LSAM is Algorithm 2.  ALG_DATA_PARALLEL is the
 # synchronous baseline of the experiments section (DP-SAM; DP-SGD when rho = 0): every
 # iteration the workers' gradients are averaged, at the first pass and again at the perturbed
@@ -184,9 +249,13 @@ class LsamOracle:
     def __init__(self, K, init_params, dims=(), d_raw=0, batch=0, gemm_dtype=0,
                  rho=0.05, gamma=1e-12, lr=0.1, lr_center=1.0, momentum=0.9, beta=0.9,
                  lambda0=0.5, lambda_abs=-1.0, nesterov=1, tau=None, tau_min=1, tau_max=1,
-                 sched_seed=0, sched_mode=SCHED_FIXED, algorithm=ALG_LSAM):
+                 sched_seed=0, sched_mode=SCHED_FIXED, algorithm=ALG_LSAM, noise_scale=0.0,
+                 noise_seed=0):
         self.K = int(K)
         self.algorithm = int(algorithm)
+        self.noise_scale, self.noise_seed = float(noise_scale), int(noise_seed)
+        self.dims = tuple(dims)
+        self.t = 0                      # sampler steps taken so far
         self.model = Mlp(dims, gemm_dtype) if len(dims) else None
         self.d = self.model.d if self.model else int(d_raw)
         self.batch = int(batch)
@@ -241,6 +310,9 @@ class LsamOracle:
             self.x[i] = self.x[i] - self.lr * (G + self.mu * self.v[i])
         else:
             self.x[i] = self.x[i] - self.lr * self.v[i]
+        if self.noise_scale != 0.0:
+            xi = langevin_noise(self.dims, self.d, i, self.t, self.noise_seed)
+            self.x[i] = self.x[i] + self.noise_scale * np.sqrt(2.0 * self.lr) * xi
         self.S[i] += self.x[i]
 
     def step(self, X, labels):
@@ -259,6 +331,7 @@ class LsamOracle:
                 _, g2[i] = self.model.loss_and_grad(xt[i], Xi, li)
             self._descend_mean(g2)
             self.sched.tick()
+            self.t += 1
             return losses
         for i in range(self.K):
             Xi = np.asarray(X[i], dtype=np.float64)
@@ -269,6 +342,7 @@ class LsamOracle:
             self.last_g1[i], self.last_g2[i] = g1, g2
             self._descend(i, g2)
         self.sched.tick()
+        self.t += 1
         return losses
 
     def _ascend_mean(self, g1):
@@ -289,12 +363,14 @@ class LsamOracle:
             self._ascend_mean(np.asarray(g1, dtype=np.float64))
             self._descend_mean(np.asarray(g2, dtype=np.float64))
             self.sched.tick()
+            self.t += 1
             return
         for i in range(self.K):
             a = np.asarray(g1[i], dtype=np.float64)
             self._ascend(i, a)
             self._descend(i, np.asarray(g2[i], dtype=np.float64))
         self.sched.tick()
+        self.t += 1
 
     # -- the center step ---------------------------------------------------------------
     def sync(self):

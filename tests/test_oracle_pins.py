@@ -7,8 +7,11 @@ import pytest
 import torch
 
 import workloads
+import os
+
 from oracle.lsam_oracle import (ALG_DATA_PARALLEL, LsamOracle, Mlp, PeriodSchedule, SCHED_FIXED,
-                                SCHED_REDRAW, bf16_round)
+                                SCHED_REDRAW, bf16_round, langevin_noise, normals_from_counters,
+                                philox4x32_10)
 
 TINY = workloads.Workload("tiny", K=2, dims=(5, 4, 3), batch=3, rho=0.05, tau=(2, 2),
                           n_classes=3, data_seed=11)
@@ -393,3 +396,66 @@ def test_data_parallel_raw_mode_averages_handed_gradients():
     assert np.allclose(o.last_perturbed[1], x0 + 0.1 * m1 / np.linalg.norm(m1))
     for i in range(K):
         assert np.allclose(o.get_params(i), x0 - 0.5 * m2, rtol=1e-14)
+
+
+# ---- Langevin noise of the sampler (Section "Langevin Dynamics for Sampling") ---------------------
+def test_philox_known_answer_vectors():
+    path = os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_kat.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 3
+    for r in rows:
+        w = [int(v, 16) for v in r]
+        out = philox4x32_10(w[0:4], w[4:6])
+        assert [int(v) for v in out] == w[6:10]
+
+
+def test_box_muller_normals_have_the_right_law():
+    from scipy import stats
+    n = 200_000
+    z = normals_from_counters((np.arange(n), 7, 3 << 16, 11), (123, 456))
+    assert z.shape == (n, 4)
+    for lane in range(4):
+        assert abs(z[:, lane].mean()) < 4 / np.sqrt(n)
+        assert abs(z[:, lane].var() - 1.0) < 0.01
+        assert stats.kstest(z[:, lane], "norm").pvalue > 1e-3
+    c = np.corrcoef(z.T)
+    assert np.max(np.abs(c - np.eye(4))) < 0.01
+    # another replica, step or seed is another stream
+    for other in (normals_from_counters((np.arange(n), 7, 4 << 16, 11), (123, 456)),
+                  normals_from_counters((np.arange(n), 7, 3 << 16, 12), (123, 456)),
+                  normals_from_counters((np.arange(n), 7, 3 << 16, 11), (124, 456))):
+        assert abs(np.corrcoef(z[:, 0], other[:, 0])[0, 1]) < 0.01
+
+
+def test_noise_layout_follows_rows_and_columns():
+    """Element (layer, row, column) takes lane column % 4 of the call with counter
+    (column // 4, row, 2*layer + is_bias | replica << 16, step), whatever the widths."""
+    dims, rep, step, seed = (6, 5, 3), 2, 9, (77 << 32) | 5
+    xi = langevin_noise(dims, 0, rep, step, seed)
+    assert xi.size == 6 * 5 + 5 + 5 * 3 + 3
+    key = (5, 77)
+    W1 = xi[:30].reshape(5, 6)
+    assert W1[3, 5] == normals_from_counters((1, 3, 0 | rep << 16, step), key)[1]
+    b1 = xi[30:35]
+    assert b1[4] == normals_from_counters((1, 0, 1 | rep << 16, step), key)[0]
+    W2 = xi[35:50].reshape(3, 5)
+    assert W2[2, 2] == normals_from_counters((0, 2, 2 | rep << 16, step), key)[2]
+    raw = langevin_noise((), 10, rep, step, seed)
+    assert raw.size == 10 and raw[9] == normals_from_counters((2, 0, rep << 16, step), key)[1]
+
+
+def test_langevin_sampler_reaches_the_stationary_variance():
+    """g = 0, fixed lambda, y = 0, no momentum: x <- (1 - eta lambda) x + sigma sqrt(2 eta) xi
+    is an AR(1) process with stationary variance 2 eta sigma^2 / (1 - (1 - eta lambda)^2)
+    = sigma^2 / (lambda (1 - eta lambda / 2)): pins the sqrt(2 eta) factor, that the noise is
+    added once per step outside the lr-scaled drift, and that draws differ from step to step."""
+    d, eta, lam, sigma = 20000, 0.1, 2.0, 0.7
+    o = LsamOracle(1, np.zeros(d), d_raw=d, rho=0.0, lr=eta, momentum=0.0, lambda_abs=lam,
+                   tau=(10**6,), noise_scale=sigma, noise_seed=2024)
+    zero = np.zeros((1, d))
+    for _ in range(120):
+        o.step_grads(zero, zero)
+    var = o.get_params(0).var()
+    expect = 2 * eta * sigma ** 2 / (1 - (1 - eta * lam) ** 2)
+    assert abs(var / expect - 1) < 0.03, (var, expect)
+    assert abs(o.get_params(0).mean()) < 4 * np.sqrt(expect / d)

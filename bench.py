@@ -143,6 +143,10 @@ def main():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2", choices=sorted(workloads.WORKLOADS))
+    ap.add_argument("--algorithm", type=int, default=0, choices=[0, 1],
+                    help="0 = LSAM (default), 1 = synchronous data-parallel baseline")
+    ap.add_argument("--noise-scale", type=float, default=0.0,
+                    help="sigma of the Langevin sampler (0 = noise-free, the default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     args = ap.parse_args()
@@ -158,6 +162,8 @@ def main():
         sys.exit(1)
     dev = torch.device("cuda:0")
     w = workloads.WORKLOADS[args.workload]
+    if args.algorithm or args.noise_scale:
+        w = w.scaled(algorithm=args.algorithm, noise_scale=args.noise_scale, noise_seed=1)
     steps = args.steps if args.steps is not None else {"cfg1": 200, "cfg2": 200}.get(w.name, 20)
 
     cfg, keep = lsam.config_from_workload(w)
@@ -232,7 +238,8 @@ def main():
         "dtype": "f32" if (w.gemm_dtype == 0) else "bf16 operands, f32 accumulate and master weights",
         "data": "synthetic",
         "config": {"workload": w.name, "K": w.K, "dims": list(w.dims), "d": w.d, "batch": w.batch,
-                   "rho": w.rho, "lr": w.lr, "momentum": w.momentum,
+                   "rho": w.rho, "lr": w.lr, "momentum": w.momentum, "algorithm": w.algorithm,
+                   "noise_scale": w.noise_scale,
                    "periods": eng.lsam_get_schedule()[0]},
         "roofline": roof, "kernels": kernels,
     }

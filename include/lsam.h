@@ -88,6 +88,12 @@ typedef struct {
   uint64_t sched_seed;    /* s_0 of the period generator                              */
   int32_t sched_mode;     /* LSAM_SCHED_FIXED or LSAM_SCHED_REDRAW                    */
   int32_t algorithm;      /* LSAM_ALG_LSAM or LSAM_ALG_DATA_PARALLEL                  */
+  float noise_scale;      /* sigma >= 0 of the Langevin sampler (Section "Langevin Dynamics
+                             for Sampling"): x <- x - lr (G + mu v) + sigma sqrt(2 lr) xi with
+                             xi ~ N(0, I) per replica, step and coordinate, drawn from
+                             Philox4x32-10 counters (see csrc/langevin.h); 0 = noise-free,
+                             as the paper's experiments run                            */
+  uint64_t noise_seed;    /* key of that generator                                    */
 } lsam_config;
 
 /* Which per-replica buffer `lsam_get_buffer` copies out. */

@@ -7,6 +7,7 @@
 
 #include "../../include/lsam.h"
 #include "b32s.h"
+#include "langevin.h"
 
 namespace lsam {
 
@@ -41,11 +42,12 @@ void launch_perturb(const float* x, const float* g, int64_t g_stride, const floa
                     int64_t stride, int64_t n, int K, hipStream_t s);
 // Descent + coupling for all K replicas, y read once per index:
 //   G = g + lam[k] (x - y); v = mu v + G; x -= lr (G + mu v) [nesterov] | lr v; S += x.
-// Also refreshes the bf16 operand copy of the weight matrices if `shadow` is non-null.
+// Also refreshes the bf16 operand copy of the weight matrices if `shadow` is non-null, and adds
+// the Langevin noise described by `noise` (null: none) to the new x.
 void launch_descent(float* x, const float* g, int64_t g_stride, float* v, float* S,
                     const float* y, uint16_t* shadow, const ShadowMap* map, int64_t shadow_stride,
                     int64_t stride, int64_t n, int K, const ReplicaScalars& lam, float lr, float mu,
-                    int nesterov, hipStream_t s);
+                    int nesterov, const NoiseMap* noise, hipStream_t s);
 // dst[c * dst_stride + i] = (1/K) sum_k src[k * src_stride + i] for c < copies, i < n; the K
 // terms are added in replica order.  dst may be src (each index is read in full before it is
 // written).

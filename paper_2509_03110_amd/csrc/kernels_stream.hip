@@ -1,6 +1,8 @@
 // Streaming kernels of the update path: gradient-norm reduction, ascent perturbation,
 // descent + coupling, center update.  All are HBM-bandwidth bound: every array is touched
 // once per kernel with 128-bit accesses, consecutive lanes on consecutive 16-byte words.
+#include <type_traits>
+
 #include "engine.h"
 
 namespace lsam {
@@ -202,12 +204,12 @@ __global__ __launch_bounds__(kThreads) void perturb_tiled_kernel(
 // once, measured 8-12 % slower at K = 8 and 16; sending the K workgroups of a piece to the same
 // XCD, so that y misses only one L2, measured 4-9 % slower: the other XCDs' misses are served
 // by the memory-side cache, and the launch order here keeps each XCD on fewer DRAM pages.)
-template <int VEC, bool SHADOW>
+template <int VEC, bool SHADOW, typename NOISE>
 __global__ __launch_bounds__(kThreads) void descent_kernel(
     float* __restrict__ x, const float* __restrict__ g, int64_t g_stride, float* __restrict__ v,
     float* __restrict__ S, const float* __restrict__ y, uint16_t* __restrict__ shadow,
     ShadowMap map, int64_t shadow_stride, int64_t stride, int64_t nv, int K, ReplicaScalars lam,
-    float lr, float mu, int nesterov) {
+    float lr, float mu, int nesterov, NOISE noise) {
   const int64_t b = blockIdx.x;
   const int k = (int)(b % K);
   const int64_t i = (b / K) * kThreads + threadIdx.x;
@@ -219,12 +221,22 @@ __global__ __launch_bounds__(kThreads) void descent_kernel(
   auto vv = ldv<VEC>(v + o);
   auto sv = ldv<VEC>(S + o);
   const float lk = lam.v[k];
+  float xi[4] = {0.f, 0.f, 0.f, 0.f};      // sigma sqrt(2 eta) xi of the Langevin sampler
+  if constexpr (!std::is_same<NOISE, NoNoise>::value) {
+    if constexpr (VEC == 4) {
+      langevin4(noise, k, i * 4, xi);
+    } else {
+      float grp[4];
+      langevin4(noise, k, i & ~(int64_t)3, grp);
+      xi[0] = grp[i & 3];
+    }
+  }
 #pragma unroll
   for (int e = 0; e < VEC; ++e) {
     const float xe = elem(xv, e);
     const float G = elem(gv, e) + lk * (xe - elem(yv, e));
     const float vn = mu * elem(vv, e) + G;
-    const float xn = nesterov ? xe - lr * (G + mu * vn) : xe - lr * vn;
+    const float xn = (nesterov ? xe - lr * (G + mu * vn) : xe - lr * vn) + xi[e];
     set_elem(vv, e, vn);
     set_elem(xv, e, xn);
     set_elem(sv, e, elem(sv, e) + xn);
@@ -405,26 +417,42 @@ void launch_perturb(const float* x, const float* g, int64_t g_stride, const floa
   }
 }
 
-void launch_descent(float* x, const float* g, int64_t g_stride, float* v, float* S,
-                    const float* y, uint16_t* shadow, const ShadowMap* map, int64_t shadow_stride,
-                    int64_t stride, int64_t n, int K, const ReplicaScalars& lam, float lr, float mu,
-                    int nesterov, hipStream_t s) {
+template <typename NOISE>
+void launch_descent_with(float* x, const float* g, int64_t g_stride, float* v, float* S,
+                         const float* y, uint16_t* shadow, const ShadowMap* map,
+                         int64_t shadow_stride, int64_t stride, int64_t n, int K,
+                         const ReplicaScalars& lam, float lr, float mu, int nesterov,
+                         const NOISE& noise, hipStream_t s) {
   const bool vec = n % 4 == 0 && g_stride % 4 == 0 && stride % 4 == 0 && aligned16(g);
   ShadowMap none{};
   if (shadow) {
     const unsigned grid = blocks_for(n / 4) * (unsigned)K;
-    descent_kernel<4, true><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, shadow, *map,
-                                                      shadow_stride, stride, n / 4, K, lam, lr, mu,
-                                                      nesterov);
+    descent_kernel<4, true, NOISE><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, shadow, *map,
+                                                             shadow_stride, stride, n / 4, K, lam,
+                                                             lr, mu, nesterov, noise);
   } else if (vec) {
     const unsigned grid = blocks_for(n / 4) * (unsigned)K;
-    descent_kernel<4, false><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, nullptr, none, 0,
-                                                       stride, n / 4, K, lam, lr, mu, nesterov);
+    descent_kernel<4, false, NOISE><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, nullptr, none,
+                                                              0, stride, n / 4, K, lam, lr, mu,
+                                                              nesterov, noise);
   } else {
     const unsigned grid = blocks_for(n) * (unsigned)K;
-    descent_kernel<1, false><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, nullptr, none, 0,
-                                                       stride, n, K, lam, lr, mu, nesterov);
+    descent_kernel<1, false, NOISE><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, nullptr, none,
+                                                              0, stride, n, K, lam, lr, mu,
+                                                              nesterov, noise);
   }
+}
+
+void launch_descent(float* x, const float* g, int64_t g_stride, float* v, float* S,
+                    const float* y, uint16_t* shadow, const ShadowMap* map, int64_t shadow_stride,
+                    int64_t stride, int64_t n, int K, const ReplicaScalars& lam, float lr, float mu,
+                    int nesterov, const NoiseMap* noise, hipStream_t s) {
+  if (noise)
+    launch_descent_with<NoiseMap>(x, g, g_stride, v, S, y, shadow, map, shadow_stride, stride, n, K,
+                                  lam, lr, mu, nesterov, *noise, s);
+  else
+    launch_descent_with<NoNoise>(x, g, g_stride, v, S, y, shadow, map, shadow_stride, stride, n, K,
+                                 lam, lr, mu, nesterov, NoNoise{}, s);
 }
 
 void launch_grad_mean(const float* src, int64_t src_stride, float* dst, int64_t dst_stride,

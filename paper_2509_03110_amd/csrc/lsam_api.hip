@@ -160,6 +160,8 @@ int check_config(const lsam_config* c) {
     return fail(LSAM_EINVAL, "sched_mode must be 0 or 1");
   if (c->algorithm != LSAM_ALG_LSAM && c->algorithm != LSAM_ALG_DATA_PARALLEL)
     return fail(LSAM_EINVAL, "algorithm must be LSAM_ALG_LSAM or LSAM_ALG_DATA_PARALLEL");
+  if (!(c->noise_scale >= 0.f) || !std::isfinite(c->noise_scale))
+    return fail(LSAM_EINVAL, "noise_scale must be finite and >= 0");
   return LSAM_OK;
 }
 
@@ -303,6 +305,8 @@ struct lsam_ctx {
   hipStream_t stream = nullptr;
   float lr = 0.f, rho = 0.f;
   int norm_slots = 0;   // partial sums of squares left by the last first-pass backward
+  uint32_t t_step = 0;  // sampler steps taken (counter word of the Langevin noise)
+  NoiseMap noise{};     // where the Langevin noise goes; used when cfg.noise_scale > 0
   // timing
   bool timing = false;
   std::vector<TimedLaunch> pending;
@@ -512,13 +516,20 @@ int update_tail_second(lsam_ctx* c, const float* g2, int64_t g_stride, int64_t n
   const Layout& lo = c->lo;
   ReplicaScalars lam;
   for (int i = 0; i < lo.K; ++i) lam.v[i] = coupling(c, i);
+  const NoiseMap* noise = nullptr;
+  if (c->cfg.noise_scale > 0.f) {
+    c->noise.step = c->t_step;
+    c->noise.amp = (float)((double)c->cfg.noise_scale * std::sqrt(2.0 * (double)c->lr));
+    noise = &c->noise;
+  }
   {
     LaunchTimer t(c, KC_DESCENT);
     launch_descent(c->at<float>(lo.x), g2, g_stride, c->at<float>(lo.v), c->at<float>(lo.S),
                    c->at<float>(lo.y), lo.bf16 ? c->at<uint16_t>(lo.xt) : nullptr, &lo.map,
                    lo.shadow_stride, lo.d_pad, n, lo.K, lam, c->lr, c->cfg.momentum, c->cfg.nesterov,
-                   c->stream);
+                   noise, c->stream);
   }
+  ++c->t_step;
   c->sched.tick();
   return check_launch("descent");
 }
@@ -631,6 +642,20 @@ int lsam_init(const lsam_config* cfg, const float* init_params, int64_t n_init, 
   }
   c->ws = static_cast<char*>(workspace);
   c->stream = static_cast<hipStream_t>(stream);
+  {
+    NoiseMap& nm = c->noise;
+    nm.key0 = (uint32_t)(c->cfg.noise_seed & 0xFFFFFFFFu);
+    nm.key1 = (uint32_t)(c->cfg.noise_seed >> 32);
+    nm.raw_n = lo.raw ? lo.d : 0;
+    nm.n = 0;
+    for (int l = 0; l < lo.L; ++l) {
+      const Layer& ly = lo.layers[l];
+      NoiseSeg w{ly.w_off, ly.w_off + (int64_t)ly.out * ly.ldw, ly.ldw, ly.in, 2 * l, 0};
+      NoiseSeg b{ly.b_off, ly.b_off + ly.out, (int32_t)round_up(ly.out, 4), ly.out, 2 * l + 1, 0};
+      nm.seg[nm.n++] = w;
+      nm.seg[nm.n++] = b;
+    }
+  }
   c->lr = cfg->lr;
   c->rho = cfg->rho;
   c->sched.init(c->cfg);

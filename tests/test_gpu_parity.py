@@ -354,3 +354,37 @@ def test_algorithm_one_mode_constant_versus_decaying_perturbation():
     print("||grad f|| after %d steps: constant rho %.3e, decaying %.3e" % (T, finals[False], finals[True]))
     assert finals[False] > 1e-2               # the floor of the constant radius
     assert finals[True] < 0.2 * finals[False]
+
+
+# ---- Langevin (SGLD) sampler: Philox-driven Gaussian noise inside the descent kernel ---------------
+@pytest.mark.parametrize("d,K", [(4096, 2), (1003, 3), (65536 * 2 + 7, 2)])
+def test_langevin_noise_raw_mode(d, K):
+    w = workloads.WORKLOADS["cfg4"].scaled(K=K, d_raw=d, tau=(2,) * K, steps=7, noise_scale=0.3,
+                                           noise_seed=(91 << 32) | 17)
+    g, o = make_pair(w)
+    for t in range(w.steps):
+        g1, g2 = workloads.raw_grads(w, t)
+        g.lsam_step_grads(torch.from_numpy(g1).to(DEV), torch.from_numpy(g2).to(DEV))
+        o.step_grads(g1, g2)
+        assert g.lsam_sync() == o.sync()
+        check_state(g, o, 1e-4, "langevin raw d=%d step %d" % (d, t + 1))
+    # the noise really is there: sigma sqrt(2 eta) = 0.13 per step dwarfs the 1e-2 gradients
+    assert np.std(g.lsam_get_params(0) - workloads.init_params(w)) > 0.1
+    g.close()
+
+
+def test_langevin_noise_fp32_mlp_ragged_widths():
+    # widths that are not multiples of 4 or 8: the noise must skip the padding of every row
+    w = workloads.WORKLOADS["cfg1"].scaled(name="sgld32", K=2, dims=(50, 37, 19, 7), batch=5,
+                                           tau=(2, 3), n_classes=7, steps=6, data_seed=9,
+                                           noise_scale=1e-3, noise_seed=5)
+    run_mlp(w, w.steps, 1e-4, 1e-3, margin=True)
+    run_mlp(w, w.steps, 1e-4, 1e-3, margin=False)
+
+
+def test_langevin_noise_bf16_mlp():
+    full = workloads.WORKLOADS["cfg3"]
+    dims = (full.dims[0] // 8,) + (256,) * (len(full.dims) - 2) + (full.dims[-1],)
+    w = full.scaled(name="sgld16", K=3, dims=dims, batch=32, steps=6, noise_scale=1e-3,
+                    noise_seed=2 ** 40 + 3)
+    run_mlp(w, w.steps, 2e-2, 2e-2, margin=True)

@@ -46,6 +46,8 @@ class Workload:
     sched_seed: int = 0
     sched_mode: int = SCHED_FIXED
     algorithm: int = 0                      # 0 = LSAM, 1 = synchronous data-parallel baseline
+    noise_scale: float = 0.0                # sigma of the Langevin sampler, 0 = noise-free
+    noise_seed: int = 0
     steps: int = 20
     data_seed: int = 0
     n_classes: int = field(default=0)

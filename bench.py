@@ -32,19 +32,18 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "a0083c7c9415a389"
+TRAFFIC_SOURCES = "0fce5f238c8cf606"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 1445732, "center": 100986368, "descent": 538491904, "gemm_dw": 29784000,
-             "gemm_dx": 23319211, "gemm_fwd": 42419641, "perturb": 201946112,
-             "softmax_ce": 124245, "sumsq_partials": 67755819},
-    "cfg3": {"bias_grad": 13667934, "center": 1773570432, "descent": 17232319445,
-             "gemm_dw": 445868890, "gemm_dx": 250093627, "gemm_fwd": 233063084,
-             "perturb": 5065994539, "softmax_ce": 1426773, "sumsq_partials": 2027221120},
-    "cfg4": {"center": 3200045312, "descent": 25600045440, "perturb": 9600050475,
-             "sumsq_partials": 3416539595},
-    "cfg5": {"bias_grad": 117972108, "descent": 188960331200, "gemm_dw": 4344452885,
-             "gemm_dx": 2332843975, "gemm_fwd": 2034141679, "perturb": 59024429504,
-             "softmax_ce": 95913525, "sumsq_partials": 25556818549},
+    "cfg2": {"bias_grad": 1442183, "center": 100986368, "descent": 538483755, "gemm_dw": 29898597,
+             "gemm_dx": 23335595, "gemm_fwd": 42462912, "perturb": 201947520, "softmax_ce":
+             124245},
+    "cfg3": {"bias_grad": 13681809, "center": 1773570432, "descent": 17232137195, "gemm_dw":
+             445912658, "gemm_dx": 250125360, "gemm_fwd": 233100654, "perturb": 5065998763,
+             "softmax_ce": 1422827},
+    "cfg4": {"center": 3200046336, "descent": 25600038571, "perturb": 9600050091,
+             "sumsq_partials": 3416082368},
+    "cfg5": {"bias_grad": 118000683, "descent": 188959237205, "gemm_dw": 4959333838, "gemm_dx":
+             2332900722, "gemm_fwd": 2034437735, "perturb": 59024482560, "softmax_ce": 95711893},
 }
 
 

@@ -60,8 +60,11 @@ def kernel_sources_digest():
 def gemm_flops(w):
     """Per all-replica step: flops of the forward, dX and dW GEMM classes (both passes)."""
     B, K = w.batch, w.K
-    sw = sum(w.dims[l] * w.dims[l + 1] for l in range(len(w.dims) - 1))
-    sw_dx = sum(w.dims[l] * w.dims[l + 1] for l in range(1, len(w.dims) - 1))
+    L = len(w.dims) - 1
+    if w.gemm_dtype == 0 and w.dims[-1] <= 16 and w.dims[-2] <= 1024 and B <= 512:
+        L -= 1      # a narrow fp32 classifier head runs as two fused non-MFMA kernels ("head")
+    sw = sum(w.dims[l] * w.dims[l + 1] for l in range(L))
+    sw_dx = sum(w.dims[l] * w.dims[l + 1] for l in range(1, L))
     return {"gemm_fwd": 2 * 2.0 * B * sw * K, "gemm_dw": 2 * 2.0 * B * sw * K,
             "gemm_dx": 2 * 2.0 * B * sw_dx * K}
 

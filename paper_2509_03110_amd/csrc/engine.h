@@ -120,4 +120,21 @@ void launch_softmax_ce(const float* logits, int ld, const int32_t* labels, void*
 int launch_bias_grad(const void* dz, int64_t ld, int dz_bf16, float* db, int64_t strideDb, int K,
                      int B, int N, double* sumsq, int64_t sumsq_stride, hipStream_t s);
 
+// Narrow classifier head in fp32 (head_fits: few classes, an input row that fits LDS, a
+// moderate batch): forward of the last layer, loss, dZ and the masked dX in one kernel (A: the
+// layer's input [K,B,ld], a ReLU output, ld = `in` rounded up to 8; W, bias: the layer's
+// parameters inside each replica, replica stride strideW, row pitch ld; dz [K,B,ld_dz] gets
+// the padded dZ; dA [K,B,ld], if non-null, dZ W where A > 0; returns <0 if the launch could
+// not be set up), and its weight and bias gradient in another (dW, db inside each replica's
+// gradient, stride strideG; returns the sum-of-squares slots written per replica, which is
+// head_sumsq_slots(in)).
+bool head_fits(int B, int C, int in);
+int head_sumsq_slots(int in);
+int launch_head_forward_backward(const float* A, const float* W, const float* bias, int64_t strideW,
+                                 const int32_t* labels, float* dz, int ld_dz, float* loss_rows,
+                                 float* dA, int K, int B, int C, int in, hipStream_t s);
+int launch_head_weight_grad(const float* dz, int ld_dz, const float* A, int ldA, float* dW, int ldw,
+                            float* db, int64_t strideG, int K, int B, int C, int in, double* sumsq,
+                            int64_t sumsq_stride, hipStream_t s);
+
 }  // namespace lsam

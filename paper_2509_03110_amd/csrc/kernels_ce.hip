@@ -121,7 +121,220 @@ __global__ __launch_bounds__(kThreads) void bias_grad_kernel(const TD* __restric
   }
 }
 
+// ---- narrow classifier head (fp32, at most 16 classes, at most 1024 inputs) ---------------------
+// With C <= 16 outputs the last layer is three matrix products far too thin for MFMA tiles
+// (forward [B x in] x [in x C], dX [B x C] x [C x in], dW [C x B] x [B x in]); as GEMMs each is
+// a launch of its own (plus split-K reduce, softmax and bias gradient) that lasts 5-10 us
+// whatever it computes.  Two kernels replace them.  Both are chains of memory latency, not of
+// arithmetic, so each fetches everything it needs in one round of loads into LDS.
+constexpr int kHeadMaxC = 16;
+constexpr int kHeadMaxIn = 1024;     // padded input width that fits LDS beside the rows
+constexpr int kHeadMaxB = 512;
+constexpr int kHeadRows = 4;         // sample rows per workgroup, one per wavefront
+typedef float hf4 __attribute__((ext_vector_type(4)));
+
+// Forward, loss, dZ and masked dX of kHeadRows rows of one replica.  LDS: the C weight rows
+// (pitch ld) then the sample rows (pitch ld); ld = input width rounded up to 8 = the pitch of
+// both in memory, columns in..ld-1 hold zeros.
+__global__ __launch_bounds__(kThreads) void head_forward_backward_kernel(
+    const float* __restrict__ A, const float* __restrict__ W, const float* __restrict__ bias,
+    long long strideW, const int32_t* __restrict__ labels, float* __restrict__ dz, int ld_dz,
+    float* __restrict__ loss_rows, float* __restrict__ dA, int B, int C, int in, int ld) {
+  extern __shared__ __attribute__((aligned(16))) float head_lds[];
+  __shared__ float reds[kWaves][kHeadMaxC * 64];
+  __shared__ float tot[kWaves][kHeadMaxC];
+  float* Ws = head_lds;
+  float* As = head_lds + C * ld;
+  const int k = blockIdx.y;
+  const int row0 = blockIdx.x * kHeadRows;
+  const int nrows = B - row0 < kHeadRows ? B - row0 : kHeadRows;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float* w = W + (long long)k * strideW;
+  const float* a = A + ((long long)k * B + row0) * ld;
+  for (int i = tid; i < C * ld / 4; i += kThreads)
+    reinterpret_cast<hf4*>(Ws)[i] = reinterpret_cast<const hf4*>(w)[i];
+  for (int i = tid; i < nrows * ld / 4; i += kThreads)
+    reinterpret_cast<hf4*>(As)[i] = reinterpret_cast<const hf4*>(a)[i];
+  __syncthreads();
+  for (int rr = wave; rr < nrows; rr += kWaves) {
+    const long long r = (long long)k * B + row0 + rr;
+    const float* ar = As + rr * ld;
+    float acc[kHeadMaxC];
+#pragma unroll
+    for (int c = 0; c < kHeadMaxC; ++c) acc[c] = 0.f;
+    for (int j = lane * 4; j < ld; j += 256) {
+      const hf4 av = *reinterpret_cast<const hf4*>(ar + j);
+#pragma unroll
+      for (int c = 0; c < kHeadMaxC; ++c)
+        if (c < C) {
+          const hf4 wv = *reinterpret_cast<const hf4*>(Ws + c * ld + j);
+          acc[c] += (av[0] * wv[0] + av[1] * wv[1]) + (av[2] * wv[2] + av[3] * wv[3]);
+        }
+    }
+    // Sum the 64 lanes' partial dot products: through the wavefront's LDS strip, lane l adding
+    // 16 of the 64 partials of class l / 4, then two neighbour exchanges; every lane then reads
+    // the C totals back.  (Sixty dependent cross-lane shuffles took longer than the products.)
+    float* red = reds[wave];
+#pragma unroll
+    for (int c = 0; c < kHeadMaxC; ++c) red[c * 64 + lane] = acc[c];
+    {
+      const float* src = red + (lane >> 2) * 64 + (lane & 3) * 16;
+      float t = 0.f;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) t += src[q];
+      t += __shfl_xor(t, 1, 64);
+      t += __shfl_xor(t, 2, 64);
+      tot[wave][lane >> 2] = t;
+    }
+    float d[kHeadMaxC];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < kHeadMaxC; ++c) {
+      d[c] = c < C ? tot[wave][c] + bias[(long long)k * strideW + c] : -INFINITY;   // logits
+      mx = fmaxf(mx, d[c]);
+    }
+    float se = 0.f;
+#pragma unroll
+    for (int c = 0; c < kHeadMaxC; ++c)
+      if (c < C) se += __expf(d[c] - mx);
+    const int lab = labels[r];
+    const float inv = 1.f / se, invB = 1.f / (float)B;
+    float zl = 0.f;
+#pragma unroll
+    for (int c = 0; c < kHeadMaxC; ++c) {
+      float v = 0.f;
+      if (c < C) {
+        v = __expf(d[c] - mx) * inv;
+        if (c == lab) { v -= 1.f; zl = d[c]; }
+        v *= invB;
+      }
+      d[c] = v;                                                                          // dZ
+    }
+    if (lane < ld_dz) {            // ld_dz <= 16: one lane per column, padding columns zero
+      float v = 0.f;
+#pragma unroll
+      for (int q = 0; q < kHeadMaxC; ++q)
+        if (q == lane) v = d[q];
+      dz[r * ld_dz + lane] = v;
+    }
+    if (loss_rows != nullptr && lane == 0) loss_rows[r] = logf(se) + mx - zl;
+    // dA = dZ W, kept where the layer's input (a ReLU output) is positive
+    if (dA != nullptr) {
+      for (int j = lane * 4; j < ld; j += 256) {
+        const hf4 av = *reinterpret_cast<const hf4*>(ar + j);
+        hf4 o = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < kHeadMaxC; ++c)
+          if (c < C) o += d[c] * *reinterpret_cast<const hf4*>(Ws + c * ld + j);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (!(j + e < in && av[e] > 0.f)) o[e] = 0.f;
+        *reinterpret_cast<hf4*>(dA + r * ld + j) = o;
+      }
+    }
+  }
+}
+
+// dW[k][c][j] = sum_b dz[k][b][c] A[k][b][j] for 16 columns j of one replica, and (first
+// workgroup of a replica) db[c] = sum_b dz[b][c].  Thread = (column, one of 16 row groups); the
+// row groups are combined in a fixed order through LDS.  LDS (dynamic): dZ of the replica.
+__global__ __launch_bounds__(kThreads) void head_weight_grad_kernel(
+    const float* __restrict__ dz, int ld_dz, const float* __restrict__ A, int ldA,
+    float* __restrict__ dW, int ldw, float* __restrict__ db, long long strideG, int B, int C,
+    int in, double* __restrict__ sumsq, long long strideSumsq) {
+  extern __shared__ __attribute__((aligned(16))) float head_lds[];
+  __shared__ float part[16][kHeadMaxC][17];
+  __shared__ double ssq_part[kWaves];
+  float* dzs = head_lds;
+  const int k = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = tid & 15, rg = tid >> 4;
+  const float* dzk = dz + (long long)k * B * ld_dz;
+  for (int i = tid; i < B * ld_dz / 4; i += kThreads)
+    reinterpret_cast<hf4*>(dzs)[i] = reinterpret_cast<const hf4*>(dzk)[i];
+  const int j = blockIdx.x * 16 + col;
+  const float* ak = A + (long long)k * B * ldA + j;
+  float acc[kHeadMaxC];
+#pragma unroll
+  for (int c = 0; c < kHeadMaxC; ++c) acc[c] = 0.f;
+  __syncthreads();
+  if (j < in) {
+#pragma unroll 8
+    for (int b = rg; b < B; b += 16) {
+      const float av = ak[(long long)b * ldA];
+#pragma unroll
+      for (int c = 0; c < kHeadMaxC; ++c)
+        if (c < C) acc[c] += dzs[b * ld_dz + c] * av;
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < kHeadMaxC; ++c) part[rg][c][col] = acc[c];
+  __syncthreads();
+  float ssq = 0.f;
+  {
+    const int c = tid >> 4;                 // thread = (class, column)
+    float v = 0.f;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) v += part[q][c][col];
+    if (c < C && j < in) {
+      dW[(long long)k * strideG + (long long)c * ldw + j] = v;
+      ssq += v * v;
+    }
+  }
+  if (blockIdx.x == 0 && tid < C) {
+    float s0 = 0.f, s1 = 0.f;
+    int b = 0;
+    for (; b + 1 < B; b += 2) { s0 += dzs[b * ld_dz + tid]; s1 += dzs[(b + 1) * ld_dz + tid]; }
+    if (b < B) s0 += dzs[b * ld_dz + tid];
+    const float sb = s0 + s1;
+    db[(long long)k * strideG + tid] = sb;
+    ssq += sb * sb;
+  }
+  if (sumsq != nullptr) {
+    double q = (double)ssq;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) q += __shfl_xor(q, off, 64);
+    if (lane == 0) ssq_part[wave] = q;
+    __syncthreads();
+    if (tid == 0)
+      sumsq[(long long)k * strideSumsq + blockIdx.x] =
+          (ssq_part[0] + ssq_part[1]) + (ssq_part[2] + ssq_part[3]);
+  }
+}
+
 }  // namespace
+
+bool head_fits(int B, int C, int in) {
+  return C <= kHeadMaxC && (in + 7) / 8 * 8 <= kHeadMaxIn && B <= kHeadMaxB;
+}
+int head_sumsq_slots(int in) { return (in + 15) / 16; }
+
+int launch_head_forward_backward(const float* A, const float* W, const float* bias, int64_t strideW,
+                                 const int32_t* labels, float* dz, int ld_dz, float* loss_rows,
+                                 float* dA, int K, int B, int C, int in, hipStream_t s) {
+  const int ld = (in + 7) / 8 * 8;
+  const size_t lds = (size_t)(C + kHeadRows) * ld * 4;
+  static size_t granted = 0;
+  if (lds > granted) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(head_forward_backward_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return -1;
+    granted = lds;
+  }
+  dim3 grid((B + kHeadRows - 1) / kHeadRows, K);
+  head_forward_backward_kernel<<<grid, kThreads, lds, s>>>(A, W, bias, strideW, labels, dz, ld_dz,
+                                                            loss_rows, dA, B, C, in, ld);
+  return 0;
+}
+
+int launch_head_weight_grad(const float* dz, int ld_dz, const float* A, int ldA, float* dW, int ldw,
+                            float* db, int64_t strideG, int K, int B, int C, int in, double* sumsq,
+                            int64_t sumsq_stride, hipStream_t s) {
+  dim3 grid(head_sumsq_slots(in), K);
+  head_weight_grad_kernel<<<grid, kThreads, (size_t)B * ld_dz * 4, s>>>(
+      dz, ld_dz, A, ldA, dW, ldw, db, strideG, B, C, in, sumsq, sumsq_stride);
+  return (int)grid.x;
+}
 
 void launch_softmax_ce(const float* logits, int ld, const int32_t* labels, void* dz, int64_t ld_dz,
                        int dz_bf16, float* loss_rows, int K, int B, int C, hipStream_t s) {

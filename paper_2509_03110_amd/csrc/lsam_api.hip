@@ -226,7 +226,8 @@ void build_layout(const lsam_config& c, Layout& lo) {
     // the first backward pass leaves one partial sum of squares per workgroup that wrote a
     // piece of the gradient: room for the most any tile choice can produce
     int64_t cap = 0;
-    for (const Layer& ly : lo.layers) cap += gemm_sumsq_capacity(ly.out, ly.in) + (ly.out + 63) / 64;
+    for (const Layer& ly : lo.layers)
+      cap += std::max(gemm_sumsq_capacity(ly.out, ly.in) + (ly.out + 63) / 64, head_sumsq_slots(ly.in));
     lo.nblk = (int)cap;
   }
 
@@ -280,11 +281,11 @@ void build_layout(const lsam_config& c, Layout& lo) {
 // ---- per-kernel timing ---------------------------------------------------------------------------
 enum KernelClass {
   KC_GEMM_FWD = 0, KC_GEMM_DX, KC_GEMM_DW, KC_SOFTMAX_CE, KC_BIAS_GRAD, KC_SUMSQ, KC_NORM_FINISH,
-  KC_PERTURB, KC_DESCENT, KC_CENTER, KC_MISC, KC_COUNT
+  KC_PERTURB, KC_DESCENT, KC_CENTER, KC_MISC, KC_HEAD, KC_COUNT
 };
 const char* const kClassNames[KC_COUNT] = {
     "gemm_fwd", "gemm_dx", "gemm_dw", "softmax_ce", "bias_grad", "sumsq_partials", "norm_finish",
-    "perturb", "descent", "center", "misc"};
+    "perturb", "descent", "center", "misc", "head"};
 
 struct TimedLaunch {
   int cls;
@@ -400,7 +401,11 @@ int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const v
     d.splitk_bytes = lo.splitk_bytes;
   };
 
-  for (int l = 0; l < L; ++l) {
+  // A narrow fp32 classifier head is not run as GEMMs: two fused kernels cover its forward
+  // pass, the loss, dZ, dX, dW and db.
+  const bool head = !bf && head_fits(B, lo.layers[L - 1].out, lo.layers[L - 1].in);
+  const float* params = static_cast<const float*>(wts);   // fp32 mode: x or the perturbed copy
+  for (int l = 0; l < (head ? L - 1 : L); ++l) {
     const Layer& ly = lo.layers[l];
     const bool last = l == L - 1;
     GemmDesc d{};
@@ -424,7 +429,17 @@ int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const v
     LaunchTimer t(c, KC_GEMM_FWD);
     if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "forward GEMM of layer %d rejected", l);
   }
-  {
+  if (head) {
+    const Layer& ly = lo.layers[L - 1];
+    const float* in_act = L == 1 ? static_cast<const float*>(A0) : c->at<float>(lo.act[L - 1]);
+    LaunchTimer t(c, KC_HEAD);
+    if (launch_head_forward_backward(in_act, params + ly.w_off, params + ly.b_off, lo.d_pad, labels,
+                                     c->at<float>(lo.dz[L]), lo.ld[L],
+                                     want_loss ? c->at<float>(lo.loss_rows) : nullptr,
+                                     L > 1 ? c->at<float>(lo.dz[L - 1]) : nullptr, K, B, ly.out,
+                                     ly.in, s) != 0)
+      return fail(LSAM_EHIP, "classifier-head kernel could not be launched");
+  } else {
     LaunchTimer t(c, KC_SOFTMAX_CE);
     launch_softmax_ce(c->at<float>(lo.logits), lo.ld[L], labels, c->at<char>(lo.dz[L]),
                       bf ? astride(L) : (int64_t)lo.ld[L], bf,
@@ -439,6 +454,15 @@ int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const v
     const char* dz = c->at<char>(lo.dz[l + 1]);
     const int ld_dz = lo.ld[l + 1];
     const void* act = l == 0 ? A0 : (const void*)c->at<char>(lo.act[l]);
+    if (head && l == L - 1) {
+      LaunchTimer t(c, KC_HEAD);
+      const int used = launch_head_weight_grad(
+          reinterpret_cast<const float*>(dz), ld_dz, static_cast<const float*>(act), lo.ld[l],
+          g + ly.w_off, ly.ldw, g + ly.b_off, lo.d_pad, K, B, ly.out, ly.in,
+          ssq ? ssq + slots : nullptr, lo.nblk, s);
+      if (ssq) slots += used;
+      continue;
+    }
     {
       GemmDesc d{};
       d.b32s = bf;

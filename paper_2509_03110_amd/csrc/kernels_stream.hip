@@ -25,6 +25,16 @@ template <int VEC>
 __device__ __forceinline__ void stv(float* p, typename Vec<VEC>::type v) {
   __builtin_nontemporal_store(v, reinterpret_cast<typename Vec<VEC>::type*>(p));
 }
+// Parameters that the next kernels read back: streamed past the caches when all replicas
+// together are far larger than they are (K d floats; measured at 3.2 GB: +5-9 % for the two
+// kernels with streaming stores), left in them when they fit (at 67 MB the following forward
+// GEMMs and the next descent find them there: -2 % per step).
+constexpr int64_t kCacheResidentBytes = 96ll << 20;
+template <int VEC, bool STREAM>
+__device__ __forceinline__ void st_param(float* p, typename Vec<VEC>::type v) {
+  if constexpr (STREAM) __builtin_nontemporal_store(v, reinterpret_cast<typename Vec<VEC>::type*>(p));
+  else *reinterpret_cast<typename Vec<VEC>::type*>(p) = v;
+}
 // y / g'_prev are re-read by later kernels and other replicas: ordinary cached access.
 template <int VEC>
 __device__ __forceinline__ typename Vec<VEC>::type ldc(const float* p) {
@@ -136,7 +146,7 @@ __global__ __launch_bounds__(kThreads) void norm_finish_kernel(
 // BF16_OUT: x~ exists only as the bf16 operand copy of the weight matrices (blocked layout);
 // elements that belong to no weight matrix (biases, padding) are not stored at all -- the
 // perturbed biases are formed in the GEMM epilogue from x, g1 and scale.
-template <int VEC, bool BF16_OUT>
+template <int VEC, bool BF16_OUT, bool STREAM>
 __global__ __launch_bounds__(kThreads) void perturb_kernel(
     const float* __restrict__ x, const float* __restrict__ g, int64_t g_stride,
     const float* __restrict__ scale, float* __restrict__ xt, uint16_t* __restrict__ xt16,
@@ -158,7 +168,7 @@ __global__ __launch_bounds__(kThreads) void perturb_kernel(
   if constexpr (BF16_OUT) {
     store_bf16<VEC>(xt16 + (int64_t)k * shadow_stride + so, o);
   } else {
-    stv<VEC>(xt + (int64_t)k * stride + i * VEC, o);
+    st_param<VEC, STREAM>(xt + (int64_t)k * stride + i * VEC, o);
   }
 }
 
@@ -204,7 +214,7 @@ __global__ __launch_bounds__(kThreads) void perturb_tiled_kernel(
 // once, measured 8-12 % slower at K = 8 and 16; sending the K workgroups of a piece to the same
 // XCD, so that y misses only one L2, measured 4-9 % slower: the other XCDs' misses are served
 // by the memory-side cache, and the launch order here keeps each XCD on fewer DRAM pages.)
-template <int VEC, bool SHADOW, typename NOISE>
+template <int VEC, bool SHADOW, bool STREAM, typename NOISE>
 __global__ __launch_bounds__(kThreads) void descent_kernel(
     float* __restrict__ x, const float* __restrict__ g, int64_t g_stride, float* __restrict__ v,
     float* __restrict__ S, const float* __restrict__ y, uint16_t* __restrict__ shadow,
@@ -241,7 +251,7 @@ __global__ __launch_bounds__(kThreads) void descent_kernel(
     set_elem(xv, e, xn);
     set_elem(sv, e, elem(sv, e) + xn);
   }
-  stv<VEC>(x + o, xv);
+  st_param<VEC, STREAM>(x + o, xv);
   stv<VEC>(v + o, vv);
   stv<VEC>(S + o, sv);
   if constexpr (SHADOW) {
@@ -408,12 +418,16 @@ void launch_perturb(const float* x, const float* g, int64_t g_stride, const floa
                                                    shadow_stride, stride);
   } else if (vec) {
     dim3 grid(blocks_for(n / 4), K);
-    perturb_kernel<4, false><<<grid, kThreads, 0, s>>>(x, g, g_stride, scale, xt_f32, nullptr, none,
-                                                       0, stride, n / 4);
+    if ((int64_t)K * n * 4 > kCacheResidentBytes)
+      perturb_kernel<4, false, true><<<grid, kThreads, 0, s>>>(x, g, g_stride, scale, xt_f32, nullptr,
+                                                               none, 0, stride, n / 4);
+    else
+      perturb_kernel<4, false, false><<<grid, kThreads, 0, s>>>(x, g, g_stride, scale, xt_f32,
+                                                                nullptr, none, 0, stride, n / 4);
   } else {
     dim3 grid(blocks_for(n), K);
-    perturb_kernel<1, false><<<grid, kThreads, 0, s>>>(x, g, g_stride, scale, xt_f32, nullptr, none,
-                                                       0, stride, n);
+    perturb_kernel<1, false, true><<<grid, kThreads, 0, s>>>(x, g, g_stride, scale, xt_f32, nullptr,
+                                                             none, 0, stride, n);
   }
 }
 
@@ -427,19 +441,21 @@ void launch_descent_with(float* x, const float* g, int64_t g_stride, float* v, f
   ShadowMap none{};
   if (shadow) {
     const unsigned grid = blocks_for(n / 4) * (unsigned)K;
-    descent_kernel<4, true, NOISE><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, shadow, *map,
-                                                             shadow_stride, stride, n / 4, K, lam,
-                                                             lr, mu, nesterov, noise);
+    descent_kernel<4, true, true, NOISE><<<grid, kThreads, 0, s>>>(
+        x, g, g_stride, v, S, y, shadow, *map, shadow_stride, stride, n / 4, K, lam, lr, mu,
+        nesterov, noise);
   } else if (vec) {
     const unsigned grid = blocks_for(n / 4) * (unsigned)K;
-    descent_kernel<4, false, NOISE><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, nullptr, none,
-                                                              0, stride, n / 4, K, lam, lr, mu,
-                                                              nesterov, noise);
+    if ((int64_t)K * n * 4 > kCacheResidentBytes)
+      descent_kernel<4, false, true, NOISE><<<grid, kThreads, 0, s>>>(
+          x, g, g_stride, v, S, y, nullptr, none, 0, stride, n / 4, K, lam, lr, mu, nesterov, noise);
+    else
+      descent_kernel<4, false, false, NOISE><<<grid, kThreads, 0, s>>>(
+          x, g, g_stride, v, S, y, nullptr, none, 0, stride, n / 4, K, lam, lr, mu, nesterov, noise);
   } else {
     const unsigned grid = blocks_for(n) * (unsigned)K;
-    descent_kernel<1, false, NOISE><<<grid, kThreads, 0, s>>>(x, g, g_stride, v, S, y, nullptr, none,
-                                                              0, stride, n, K, lam, lr, mu,
-                                                              nesterov, noise);
+    descent_kernel<1, false, true, NOISE><<<grid, kThreads, 0, s>>>(
+        x, g, g_stride, v, S, y, nullptr, none, 0, stride, n, K, lam, lr, mu, nesterov, noise);
   }
 }
 

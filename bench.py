@@ -32,18 +32,17 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "0fce5f238c8cf606"
+TRAFFIC_SOURCES = "313e5ea36b49ff84"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 1442183, "center": 100986368, "descent": 538483755, "gemm_dw": 29898597,
-             "gemm_dx": 23335595, "gemm_fwd": 42462912, "perturb": 201947520, "softmax_ce":
-             124245},
-    "cfg3": {"bias_grad": 13681809, "center": 1773570432, "descent": 17232137195, "gemm_dw":
-             445912658, "gemm_dx": 250125360, "gemm_fwd": 233100654, "perturb": 5065998763,
-             "softmax_ce": 1422827},
-    "cfg4": {"center": 3200046336, "descent": 25600038571, "perturb": 9600050091,
-             "sumsq_partials": 3416082368},
-    "cfg5": {"bias_grad": 118000683, "descent": 188959237205, "gemm_dw": 4959333838, "gemm_dx":
-             2332900722, "gemm_fwd": 2034437735, "perturb": 59024482560, "softmax_ce": 95711893},
+    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43624907,
+             "gemm_dx": 42129408, "gemm_fwd": 62203915, "perturb": 201945515},
+    "cfg3": {"bias_grad": 13681920, "center": 1773569920, "descent": 17232123925, "gemm_dw":
+             445816176, "gemm_dx": 250125381, "gemm_fwd": 233101291, "perturb": 5065988608,
+             "softmax_ce": 1428821},
+    "cfg4": {"center": 3200044800, "descent": 25600046421, "perturb": 9600050475,
+             "sumsq_partials": 3416042432},
+    "cfg5": {"bias_grad": 118026658, "descent": 188963156331, "gemm_dw": 4961566711, "gemm_dx":
+             2332911289, "gemm_fwd": 2034393146, "perturb": 59024471168, "softmax_ce": 95736395},
 }
 
 

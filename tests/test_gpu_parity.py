@@ -388,3 +388,58 @@ def test_langevin_noise_bf16_mlp():
     w = full.scaled(name="sgld16", K=3, dims=dims, batch=32, steps=6, noise_scale=1e-3,
                     noise_seed=2 ** 40 + 3)
     run_mlp(w, w.steps, 2e-2, 2e-2, margin=True)
+
+
+# ---- limits and degenerate inputs ------------------------------------------------------------------
+def test_maximum_replica_count_raw_mode():
+    K = 64                                          # LSAM_MAX_REPLICAS
+    w = workloads.WORKLOADS["cfg4"].scaled(K=K, d_raw=777, tau=None, tau_min=2, tau_max=6,
+                                           sched_seed=12, steps=8)
+    g, o = make_pair(w)
+    for t in range(w.steps):
+        g1, g2 = workloads.raw_grads(w, t)
+        g.lsam_step_grads(torch.from_numpy(g1).to(DEV), torch.from_numpy(g2).to(DEV))
+        o.step_grads(g1, g2)
+        assert g.lsam_sync() == o.sync()
+    # v carries lambda (x - y) with |x|, |y| ~ 1 but |x - y| ~ 1e-2 and gradients ~ 1e-2: the fp32
+    # rounding of x and y (1e-7) is a 1e-4 relative error of v once the center moves every tick,
+    # as it does with 64 replicas; parameters, sums and the center keep the tight bound
+    check_state(g, o, 1e-4, "K=64", tol_v=1e-3)
+    g.close()
+
+
+def test_maximum_depth_mlp():
+    dims = (24,) + (16,) * 15 + (5,)               # LSAM_MAX_LAYERS = 16 dense layers
+    w = workloads.WORKLOADS["cfg1"].scaled(name="deep", K=2, dims=dims, batch=6, tau=(2, 3),
+                                           n_classes=5, steps=4, data_seed=4)
+    run_mlp(w, w.steps, 1e-4, 1e-3, margin=True)
+
+
+def test_zero_gradients_leave_only_the_coupling():
+    """g1 = g2 = 0: the norm is 0, the perturbation rho * 0 / (0 + gamma) = 0, and the step is
+    the pure pull toward the center."""
+    w = workloads.WORKLOADS["cfg4"].scaled(K=2, d_raw=4096, tau=(1, 2), steps=4)
+    rng = np.random.default_rng(8)
+    init = rng.standard_normal(3 * w.d_raw).astype(np.float32)       # distinct x_0, x_1, y
+    g, o = make_pair(w, init)
+    z = np.zeros((2, w.d_raw), dtype=np.float32)
+    for t in range(w.steps):
+        before = [g.lsam_get_params(i) for i in range(2)]
+        g.lsam_step_grads(torch.from_numpy(z).to(DEV), torch.from_numpy(z).to(DEV))
+        o.step_grads(z, z)
+        assert np.all(g.lsam_get_norms() == 0.0)
+        for i in range(2):       # the perturbed point is the point itself, bit for bit
+            assert np.array_equal(g.lsam_get_buffer(lsam.BUF_PERTURBED, i), before[i])
+        assert g.lsam_sync() == o.sync()
+        check_state(g, o, 1e-4, "zero gradients step %d" % (t + 1))
+    g.close()
+
+
+@pytest.mark.parametrize("dims,B", [((40, 33, 17), 9),        # 17 classes: one more than the fused head takes
+                                    ((1100, 12), 7),          # head input wider than its LDS staging
+                                    ((16, 24, 3), 600)])      # batch beyond the head's dZ staging
+def test_fp32_classifier_head_fallbacks(dims, B):
+    w = workloads.WORKLOADS["cfg1"].scaled(name="headfb", K=2, dims=dims, batch=B, tau=(2, 3),
+                                           n_classes=dims[-1], steps=3, data_seed=6)
+    run_mlp(w, w.steps, 1e-4, 1e-3, margin=True)
+    run_mlp(w, w.steps, 1e-4, 1e-3, margin=False)

@@ -135,7 +135,17 @@ def cpu_baseline(w, budget_s=20.0):
             value = n * d / dt
             sample = "%d iteration(s) of 1 replica at d=%d (of K=%d, d=%d)" % (n, d, w.K, w.d_raw)
             unit = "replica-params/s"
-    return {"value": value, "unit": unit, "cores": 1, "kind": "oracle", "sample": sample}
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return {"value": value, "unit": unit, "cores": 1, "kind": "oracle", "sample": sample,
+            "host_cpu": model, "host_cores": os.cpu_count()}
 
 
 def main():
@@ -245,6 +255,19 @@ def main():
         "roofline": roof, "kernels": kernels,
     }
     eng.close()
+    if not args.no_kernel_timing:
+        # the same fractions against what the simplest kernels reach on this very device
+        scratch = torch.empty(1 << 28, dtype=torch.float32, device=dev)          # 1 GiB
+        copy_gbs, bf16_tf, f32_tf = lsam.lsam_probe_peaks(scratch)
+        del scratch
+        out["measured_peaks"] = {"copy_GBps": copy_gbs, "mfma_bf16_TFLOPs": bf16_tf,
+                                 "mfma_f32_TFLOPs": f32_tf}
+        mfma_meas = bf16_tf if w.gemm_dtype == 1 else f32_tf
+        for k in list(kernels.values()) + ([roof] if roof else []):
+            if k.get("bound") == "mfma":
+                k["frac_of_measured"] = k["achieved"] / mfma_meas
+            elif k.get("bound") == "hbm":
+                k["frac_of_measured"] = k["achieved"] / copy_gbs
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

@@ -183,6 +183,15 @@ int lsam_timing_enable(lsam_ctx* ctx, int32_t on);
 int lsam_timing_read(lsam_ctx* ctx, int32_t cap, const char** names, int64_t* counts,
                      double* total_ms);
 
+/* Ceilings of the device this process runs on, measured with the simplest kernels there are,
+ * for reading kernel throughputs against (needs no context): a plain copy between the two
+ * halves of `scratch` [device, 16-byte aligned, `scratch_bytes` >= 32 KiB; contents are
+ * overwritten] in GB/s counting bytes read plus bytes written, and loops of independent MFMA
+ * instructions on register operands in TFLOP/s, bf16 (32x32x16) and fp32 (32x32x2).
+ * Runs on `stream` and blocks until done.  Returns LSAM_OK or LSAM_EINVAL / LSAM_EHIP. */
+int lsam_probe_peaks(void* scratch, size_t scratch_bytes, void* stream, double* copy_gbytes_per_s,
+                     double* mfma_bf16_tflops, double* mfma_fp32_tflops);
+
 void lsam_destroy(lsam_ctx* ctx);
 
 const char* lsam_last_error(void);

@@ -137,4 +137,9 @@ int launch_head_weight_grad(const float* dz, int ld_dz, const float* A, int ldA,
                             float* db, int64_t strideG, int K, int B, int C, int in, double* sumsq,
                             int64_t sumsq_stride, hipStream_t s);
 
+// Measured ceilings: device copy (GB/s, read + written) between the halves of `scratch`, and
+// MFMA-only loops (TFLOP/s, bf16 32x32x16 and fp32 32x32x2).  Blocks until done; 0 or -1.
+int probe_peaks(void* scratch, size_t bytes, hipStream_t s, double* copy_gbs, double* bf16_tflops,
+                double* f32_tflops);
+
 }  // namespace lsam

@@ -925,6 +925,18 @@ int lsam_timing_read(lsam_ctx* c, int32_t cap, const char** names, int64_t* coun
   return n;
 }
 
+int lsam_probe_peaks(void* scratch, size_t scratch_bytes, void* stream, double* copy_gbytes_per_s,
+                     double* mfma_bf16_tflops, double* mfma_fp32_tflops) {
+  if (!scratch || !copy_gbytes_per_s || !mfma_bf16_tflops || !mfma_fp32_tflops)
+    return fail(LSAM_EINVAL, "NULL argument");
+  if (scratch_bytes < 32768 || (reinterpret_cast<uintptr_t>(scratch) & 15))
+    return fail(LSAM_EINVAL, "scratch must be 16-byte aligned and hold at least 32 KiB");
+  if (probe_peaks(scratch, scratch_bytes, static_cast<hipStream_t>(stream), copy_gbytes_per_s,
+                  mfma_bf16_tflops, mfma_fp32_tflops) != 0)
+    return fail(LSAM_EHIP, "peak probe failed: %s", hipGetErrorString(hipGetLastError()));
+  return LSAM_OK;
+}
+
 void lsam_destroy(lsam_ctx* c) {
   if (!c) return;
   (void)hipStreamSynchronize(c->stream);

@@ -25,7 +25,7 @@ EXPORTS = [
     "lsam_workspace_bytes", "lsam_init", "lsam_step", "lsam_step_grads", "lsam_sync",
     "lsam_get_params", "lsam_get_buffer", "lsam_set_buffer", "lsam_get_norms", "lsam_get_schedule",
     "lsam_set_scalars", "lsam_num_params", "lsam_schedule_replay", "lsam_timing_enable",
-    "lsam_timing_read", "lsam_destroy", "lsam_last_error",
+    "lsam_timing_read", "lsam_probe_peaks", "lsam_destroy", "lsam_last_error",
 ]
 
 
@@ -89,6 +89,8 @@ def lib():
         L.lsam_timing_enable.argtypes = [vp, i32]
         L.lsam_timing_read.restype = C.c_int
         L.lsam_timing_read.argtypes = [vp, i32, vp, vp, vp]
+        L.lsam_probe_peaks.restype = C.c_int
+        L.lsam_probe_peaks.argtypes = [vp, C.c_size_t, vp, vp, vp, vp]
         L.lsam_destroy.restype = None
         L.lsam_destroy.argtypes = [vp]
         L.lsam_last_error.restype = C.c_char_p
@@ -147,6 +149,17 @@ def config_from_workload(w, **over):
               noise_seed=w.noise_seed)
     kw.update(over)
     return make_config(**kw)
+
+
+def lsam_probe_peaks(scratch, stream=None):
+    """scratch: a contiguous device tensor (overwritten).  Returns (copy GB/s, bf16 MFMA TFLOP/s,
+    fp32 MFMA TFLOP/s) measured on its device."""
+    import torch
+    out = (C.c_double * 3)()
+    st = torch.cuda.current_stream(scratch.device).cuda_stream if stream is None else stream
+    _check(lib().lsam_probe_peaks(scratch.data_ptr(), scratch.numel() * scratch.element_size(), st,
+                                  C.addressof(out), C.addressof(out) + 8, C.addressof(out) + 16))
+    return out[0], out[1], out[2]
 
 
 def lsam_workspace_bytes(cfg) -> int:

@@ -443,3 +443,13 @@ def test_fp32_classifier_head_fallbacks(dims, B):
                                            n_classes=dims[-1], steps=3, data_seed=6)
     run_mlp(w, w.steps, 1e-4, 1e-3, margin=True)
     run_mlp(w, w.steps, 1e-4, 1e-3, margin=False)
+
+
+def test_peak_probe_reports_plausible_ceilings():
+    scratch = torch.empty(1 << 26, dtype=torch.float32, device=DEV)      # 256 MiB
+    copy_gbs, bf16_tf, f32_tf = lsam.lsam_probe_peaks(scratch)
+    assert 1000.0 < copy_gbs < 8000.0 * 1.05        # below the HBM datasheet figure
+    assert 500.0 < bf16_tf < 2500.0 * 1.05
+    assert 50.0 < f32_tf < 157.3 * 1.05
+    with pytest.raises(lsam.LsamError):
+        lsam.lsam_probe_peaks(scratch[:16])          # too small

@@ -216,6 +216,12 @@ def main():
         eng.lsam_timing_enable(False)
         flops = gemm_flops(w) if w.dims else {}
         nbytes = stream_bytes(w)
+        # center update: 8 B/param per due replica (S read, S cleared) + 16 B/param (y and
+        # g'_prev read and written), summed over the ticks of this run that had a sync
+        first = args.warmup + steps
+        due, _ = lsam.lsam_schedule_replay(cfg, first + steps)
+        nd = due[first:].sum(axis=1)
+        nbytes["center"] = float(np.sum((8.0 * nd + 16.0) * (nd > 0))) * w.d / steps
         traffic = TRAFFIC.get(w.name, {}) if kernel_sources_digest() == TRAFFIC_SOURCES else {}
         for name, (cnt, tot) in stats.items():
             if cnt == 0:

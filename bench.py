@@ -32,17 +32,17 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "feed14019fb774ef"
+TRAFFIC_SOURCES = "c85eed8911fabc59"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43622571,
-             "gemm_dx": 42129408, "gemm_fwd": 62205579, "perturb": 201945429},
-    "cfg3": {"bias_grad": 13681869, "center": 1773571968, "descent": 17232237419, "gemm_dw":
-             446045746, "gemm_dx": 250125387, "gemm_fwd": 233098342, "perturb": 5065986304,
-             "softmax_ce": 1429013},
-    "cfg4": {"center": 3200044160, "descent": 25600046293, "perturb": 9600050517,
-             "sumsq_partials": 3416347776},
-    "cfg5": {"bias_grad": 118029836, "descent": 188957529899, "gemm_dw": 4961108223, "gemm_dx":
-             2332888452, "gemm_fwd": 2034182561, "perturb": 59024471125, "softmax_ce": 95760400},
+    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43618677,
+             "gemm_dx": 42129408, "gemm_fwd": 62211200, "perturb": 201945387},
+    "cfg3": {"bias_grad": 13681886, "center": 1773570368, "descent": 17231887744, "gemm_dw":
+             445875178, "gemm_dx": 250125371, "gemm_fwd": 233098342, "perturb": 5065988139,
+             "softmax_ce": 1428821},
+    "cfg4": {"center": 3200044672, "descent": 25600046208, "perturb": 9600051243,
+             "sumsq_partials": 3416455232},
+    "cfg5": {"bias_grad": 118040190, "descent": 188957475584, "gemm_dw": 4964593542, "gemm_dx":
+             2332929572, "gemm_fwd": 2034322674, "perturb": 59024472960, "softmax_ce": 95729979},
 }
 
 

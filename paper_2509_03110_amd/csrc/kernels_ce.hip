@@ -1,5 +1,7 @@
 // Fused softmax cross-entropy forward + backward (one wavefront per sample row, wavefront
 // shuffle reductions) and the bias gradient (column sums of dZ).
+#include <atomic>
+
 #include "engine.h"
 #include "b32s.h"
 
@@ -314,12 +316,15 @@ int launch_head_forward_backward(const float* A, const float* W, const float* bi
                                  float* dA, int K, int B, int C, int in, hipStream_t s) {
   const int ld = (in + 7) / 8 * 8;
   const size_t lds = (size_t)(C + kHeadRows) * ld * 4;
-  static size_t granted = 0;
-  if (lds > granted) {
+  // the largest dynamic LDS size asked for so far (host threads may race here: the attribute
+  // call is idempotent, the counter only saves repeating it)
+  static std::atomic<size_t> granted{0};
+  if (lds > granted.load(std::memory_order_relaxed)) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(head_forward_backward_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)((size_t)(kHeadMaxC + kHeadRows) * kHeadMaxIn * 4)) != hipSuccess)
       return -1;
-    granted = lds;
+    granted.store((size_t)(kHeadMaxC + kHeadRows) * kHeadMaxIn * 4, std::memory_order_relaxed);
   }
   dim3 grid((B + kHeadRows - 1) / kHeadRows, K);
   head_forward_backward_kernel<<<grid, kThreads, lds, s>>>(A, W, bias, strideW, labels, dz, ld_dz,

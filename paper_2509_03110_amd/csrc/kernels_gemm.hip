@@ -18,6 +18,8 @@
 // reads of the next 16 (bf16) / 8 (fp32) k overlap the MFMAs of the current ones.
 // The MFMA is issued with the roles swapped (rows <- B operand, columns <- A operand), so
 // that a lane ends up with 4 consecutive n of one row m: 16-byte stores in the epilogue.
+#include <atomic>
+
 #include "engine.h"
 
 namespace lsam {
@@ -563,12 +565,12 @@ int launch_one(const GemmParams& p0, hipStream_t s, int* sumsq_slots) {
   const size_t epi_smem = (size_t)64 * (BN + 4) * 4;
   const size_t smem = loop_smem > epi_smem ? loop_smem : epi_smem;
   auto kern = gemm_kernel<T, TC, BM, BN, BKU, AK, BK_, OCC>;
-  static bool attr_set = false;   // per instantiation
-  if (!attr_set) {
+  static std::atomic<bool> attr_set{false};   // per instantiation; setting it twice is harmless
+  if (!attr_set.load(std::memory_order_relaxed)) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
       return -1;
-    attr_set = true;
+    attr_set.store(true, std::memory_order_relaxed);
   }
   kern<<<p.chunks * 8, kThreads, smem, s>>>(p);
   int slots = p.tilesM * p.tilesN;

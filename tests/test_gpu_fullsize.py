@@ -100,3 +100,38 @@ def test_cfg3_full_shape_one_replica():
 
 def test_cfg5_full_shape_one_replica():
     _full_shape_one_replica("cfg5", twins=(6, 15))
+
+
+def test_fp32_large_tile_variants_one_replica():
+    """fp32 shapes large enough for the 256x128 (forward) and 256x256 (weight-gradient) tile
+    variants of the fp32 GEMM, which the small parity cases never reach.  The oracle computes
+    replica 0 from a margin initialisation (no ReLU decision near zero, so the tight fp32
+    bound applies to every buffer); twin replicas must reproduce it bit for bit."""
+    w = workloads.Workload("fp32big", K=16, dims=(256, 2048, 2048, 24), batch=512, rho=0.05,
+                           lr=0.01, tau=(3,) * 16, n_classes=24, data_seed=21)
+    init = workloads.init_params_margin(w)
+    cfg, keep = lsam.config_from_workload(w)
+    eng = lsam.Lsam(cfg, init, device=DEV, keep=keep)
+    X, lab = workloads.batch(w, 0)
+    twins = (5, 15)
+    for k in twins:
+        X[k], lab[k] = X[0], lab[0]
+    loss = torch.zeros(w.K, device=DEV)
+    eng.lsam_step(torch.from_numpy(X).to(DEV), torch.from_numpy(lab).to(DEV), loss)
+    gl = loss.cpu().numpy()
+    ora = oracle_from(w.scaled(K=1, tau=(3,)), init)
+    ol = ora.step(X[:1], lab[:1])
+    assert ora.model.last_margin > 1e-3
+    assert abs(gl[0] - ol[0]) <= 1e-5 * abs(ol[0])
+    assert abs(eng.lsam_get_norms()[0] - ora.last_norm[0]) <= 1e-5 * ora.last_norm[0]
+    g2 = eng.lsam_get_buffer(lsam.BUF_GRAD, 0)
+    for l, (o0, o1, o2) in enumerate(ora.model.offsets):
+        close_enough(g2[o0:o1], ora.last_g2[0][o0:o1], 1e-4, "dW%d" % (l + 1))
+        close_enough(g2[o1:o2], ora.last_g2[0][o1:o2], 1e-4, "db%d" % (l + 1))
+    close_enough(eng.lsam_get_params(0), ora.get_params(0), 1e-4, "x of replica 0")
+    close_enough(eng.lsam_get_buffer(lsam.BUF_VELOCITY, 0), ora.v[0], 1e-4, "v of replica 0")
+    for k in twins:
+        assert gl[k] == gl[0]
+        assert np.array_equal(eng.lsam_get_buffer(lsam.BUF_GRAD, k), g2), "replica %d differs" % k
+    assert np.all(np.isfinite(gl)) and np.all(np.isfinite(eng.lsam_get_norms()))
+    eng.close()

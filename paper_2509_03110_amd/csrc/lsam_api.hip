@@ -307,6 +307,7 @@ struct lsam_ctx {
   float lr = 0.f, rho = 0.f;
   int norm_slots = 0;   // partial sums of squares left by the last first-pass backward
   uint32_t t_step = 0;  // sampler steps taken (counter word of the Langevin noise)
+  void* stage = nullptr;   // pinned host staging buffer for the read-out / restore calls (lazy)
   NoiseMap noise{};     // where the Langevin noise goes; used when cfg.noise_scale > 0
   // timing
   bool timing = false;
@@ -558,33 +559,90 @@ int update_tail_second(lsam_ctx* c, const float* g2, int64_t g_stride, int64_t n
   return check_launch("descent");
 }
 
-// Copies between the public flat layout (host) and one padded replica vector (device).
+// Host <-> device transfers go through a pinned staging buffer owned by the context, in
+// pieces of at most kStageBytes, each followed by a stream synchronisation: pageable-memory
+// copies are left to no one else's staging (a strided device-to-host copy into fresh pageable
+// memory was seen to return with a few words not yet written when run under the profiler).
+constexpr size_t kStageBytes = 64u << 20;
+
+int ensure_stage(lsam_ctx* c) {
+  if (c->stage) return LSAM_OK;
+  HIP_TRY(hipHostMalloc(&c->stage, kStageBytes, hipHostMallocDefault));
+  return LSAM_OK;
+}
+
+int to_host(lsam_ctx* c, void* dst, const void* src_dev, size_t bytes) {
+  int rc = ensure_stage(c);
+  if (rc != LSAM_OK) return rc;
+  char* d = static_cast<char*>(dst);
+  const char* s = static_cast<const char*>(src_dev);
+  for (size_t off = 0; off < bytes; off += kStageBytes) {
+    const size_t n = std::min(kStageBytes, bytes - off);
+    HIP_TRY(hipMemcpyAsync(c->stage, s + off, n, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    memcpy(d + off, c->stage, n);
+  }
+  return LSAM_OK;
+}
+
+int to_device(lsam_ctx* c, void* dst_dev, const void* src, size_t bytes) {
+  int rc = ensure_stage(c);
+  if (rc != LSAM_OK) return rc;
+  char* d = static_cast<char*>(dst_dev);
+  const char* s = static_cast<const char*>(src);
+  for (size_t off = 0; off < bytes; off += kStageBytes) {
+    const size_t n = std::min(kStageBytes, bytes - off);
+    memcpy(c->stage, s + off, n);
+    HIP_TRY(hipMemcpyAsync(d + off, c->stage, n, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+  }
+  return LSAM_OK;
+}
+
+// Copies between the public flat layout (host) and one padded replica vector (device): the
+// rows of W_l lose or gain their padding on the host side of the staging buffer.
 int copy_in(lsam_ctx* c, const float* src_flat, float* dst_dev) {
   const Layout& lo = c->lo;
-  if (lo.raw) {
-    HIP_TRY(hipMemcpy(dst_dev, src_flat, (size_t)lo.d * 4, hipMemcpyHostToDevice));
-    return LSAM_OK;
-  }
+  if (lo.raw) return to_device(c, dst_dev, src_flat, (size_t)lo.d * 4);
+  int rc = ensure_stage(c);
+  if (rc != LSAM_OK) return rc;
+  float* stage = static_cast<float*>(c->stage);
   for (const Layer& ly : lo.layers) {
-    HIP_TRY(hipMemcpy2D(dst_dev + ly.w_off, (size_t)ly.ldw * 4, src_flat + ly.w_flat,
-                        (size_t)ly.in * 4, (size_t)ly.in * 4, ly.out, hipMemcpyHostToDevice));
-    HIP_TRY(hipMemcpy(dst_dev + ly.b_off, src_flat + ly.b_flat, (size_t)ly.out * 4,
-                      hipMemcpyHostToDevice));
+    const int64_t rows_per = std::max<int64_t>(1, (int64_t)(kStageBytes / 4) / ly.ldw);
+    for (int64_t r0 = 0; r0 < ly.out; r0 += rows_per) {
+      const int64_t nr = std::min<int64_t>(rows_per, ly.out - r0);
+      for (int64_t r = 0; r < nr; ++r) {
+        memcpy(stage + r * ly.ldw, src_flat + ly.w_flat + (r0 + r) * ly.in, (size_t)ly.in * 4);
+        if (ly.ldw > ly.in) memset(stage + r * ly.ldw + ly.in, 0, (size_t)(ly.ldw - ly.in) * 4);
+      }
+      HIP_TRY(hipMemcpyAsync(dst_dev + ly.w_off + r0 * ly.ldw, stage, (size_t)nr * ly.ldw * 4,
+                             hipMemcpyHostToDevice, c->stream));
+      HIP_TRY(hipStreamSynchronize(c->stream));
+    }
+    if ((rc = to_device(c, dst_dev + ly.b_off, src_flat + ly.b_flat, (size_t)ly.out * 4)) != LSAM_OK)
+      return rc;
   }
   return LSAM_OK;
 }
 
 int copy_out(lsam_ctx* c, const float* src_dev, float* dst_flat) {
   const Layout& lo = c->lo;
-  if (lo.raw) {
-    HIP_TRY(hipMemcpy(dst_flat, src_dev, (size_t)lo.d * 4, hipMemcpyDeviceToHost));
-    return LSAM_OK;
-  }
+  if (lo.raw) return to_host(c, dst_flat, src_dev, (size_t)lo.d * 4);
+  int rc = ensure_stage(c);
+  if (rc != LSAM_OK) return rc;
+  const float* stage = static_cast<const float*>(c->stage);
   for (const Layer& ly : lo.layers) {
-    HIP_TRY(hipMemcpy2D(dst_flat + ly.w_flat, (size_t)ly.in * 4, src_dev + ly.w_off,
-                        (size_t)ly.ldw * 4, (size_t)ly.in * 4, ly.out, hipMemcpyDeviceToHost));
-    HIP_TRY(hipMemcpy(dst_flat + ly.b_flat, src_dev + ly.b_off, (size_t)ly.out * 4,
-                      hipMemcpyDeviceToHost));
+    const int64_t rows_per = std::max<int64_t>(1, (int64_t)(kStageBytes / 4) / ly.ldw);
+    for (int64_t r0 = 0; r0 < ly.out; r0 += rows_per) {
+      const int64_t nr = std::min<int64_t>(rows_per, ly.out - r0);
+      HIP_TRY(hipMemcpyAsync(c->stage, src_dev + ly.w_off + r0 * ly.ldw, (size_t)nr * ly.ldw * 4,
+                             hipMemcpyDeviceToHost, c->stream));
+      HIP_TRY(hipStreamSynchronize(c->stream));
+      for (int64_t r = 0; r < nr; ++r)
+        memcpy(dst_flat + ly.w_flat + (r0 + r) * ly.in, stage + r * ly.ldw, (size_t)ly.in * 4);
+    }
+    if ((rc = to_host(c, dst_flat + ly.b_flat, src_dev + ly.b_off, (size_t)ly.out * 4)) != LSAM_OK)
+      return rc;
   }
   return LSAM_OK;
 }
@@ -684,7 +742,11 @@ int lsam_init(const lsam_config* cfg, const float* init_params, int64_t n_init, 
   c->rho = cfg->rho;
   c->sched.init(c->cfg);
 
-  auto bail = [&](int code) { delete c; return code; };
+  auto bail = [&](int code) {
+    if (c->stage) (void)hipHostFree(c->stage);
+    delete c;
+    return code;
+  };
   launch_fill_zero(c->ws, lo.total, c->stream);
   if (check_launch("zero fill") != LSAM_OK) return bail(LSAM_EHIP);
   if (hipStreamSynchronize(c->stream) != hipSuccess)
@@ -820,8 +882,9 @@ int lsam_get_buffer(lsam_ctx* c, int32_t which, int32_t replica, float* dst, int
       // the blocked layout on the host; biases are not part of the copy (the GEMMs read the
       // fp32 ones), they are reported from the master parameters
       std::vector<uint16_t> h((size_t)lo.shadow_stride);
-      HIP_TRY(hipMemcpy(h.data(), c->at<uint16_t>(lo.xt) + (int64_t)replica * lo.shadow_stride,
-                        (size_t)lo.shadow_stride * 2, hipMemcpyDeviceToHost));
+      int rc0 = to_host(c, h.data(), c->at<uint16_t>(lo.xt) + (int64_t)replica * lo.shadow_stride,
+                        (size_t)lo.shadow_stride * 2);
+      if (rc0 != LSAM_OK) return rc0;
       int rc = copy_out(c, c->at<float>(lo.x) + roff, dst);
       if (rc != LSAM_OK) return rc;
       for (int l = 0; l < lo.L; ++l) {
@@ -875,7 +938,10 @@ int lsam_get_params(lsam_ctx* c, int32_t replica, float* dst, int64_t n) {
 int lsam_get_norms(lsam_ctx* c, float* dst) {
   if (!c || !dst) return fail(LSAM_EINVAL, "ctx or dst is NULL");
   HIP_TRY(hipStreamSynchronize(c->stream));
-  HIP_TRY(hipMemcpy(dst, c->at<float>(c->lo.norms), (size_t)c->lo.K * 4, hipMemcpyDeviceToHost));
+  {
+    int rc0 = to_host(c, dst, c->at<float>(c->lo.norms), (size_t)c->lo.K * 4);
+    if (rc0 != LSAM_OK) return rc0;
+  }
   return LSAM_OK;
 }
 
@@ -942,6 +1008,7 @@ void lsam_destroy(lsam_ctx* c) {
   (void)hipStreamSynchronize(c->stream);
   for (auto& t : c->pending) { (void)hipEventDestroy(t.a); (void)hipEventDestroy(t.b); }
   for (auto e : c->free_events) (void)hipEventDestroy(e);
+  if (c->stage) (void)hipHostFree(c->stage);
   delete c;
 }
 

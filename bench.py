@@ -32,17 +32,17 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "cb83d2caa98bb567"
+TRAFFIC_SOURCES = "76abd8ecabc85ef1"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43627051,
-             "gemm_dx": 42129408, "gemm_fwd": 62199712, "perturb": 201945557},
-    "cfg3": {"bias_grad": 13681847, "center": 1773571584, "descent": 17231780779, "gemm_dw":
-             445969709, "gemm_dx": 250125387, "gemm_fwd": 233096198, "perturb": 5065987157,
-             "softmax_ce": 1429184},
-    "cfg4": {"center": 3200045312, "descent": 25600046123, "perturb": 9600051221,
-             "sumsq_partials": 3415947477},
-    "cfg5": {"bias_grad": 118070296, "descent": 188956974485, "gemm_dw": 4956068735, "gemm_dx":
-             2332871460, "gemm_fwd": 2034888658, "perturb": 59024472107, "softmax_ce": 95660587},
+    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43657227,
+             "gemm_dx": 42128384, "gemm_fwd": 62144768, "perturb": 201945472},
+    "cfg3": {"bias_grad": 13681809, "center": 1773572160, "descent": 17232396523, "gemm_dw":
+             445944106, "gemm_dx": 250125392, "gemm_fwd": 233097444, "perturb": 5065986987,
+             "softmax_ce": 1429035},
+    "cfg4": {"center": 3200044288, "descent": 25600045909, "perturb": 9600050731,
+             "sumsq_partials": 3416330976},
+    "cfg5": {"bias_grad": 118063128, "descent": 188956680597, "gemm_dw": 4958184013, "gemm_dx":
+             2332865643, "gemm_fwd": 2035667436, "perturb": 59024471083, "softmax_ce": 95600107},
 }
 
 

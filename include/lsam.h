@@ -17,8 +17,12 @@
  *     (`lsam_workspace_bytes` tells its size) that must stay valid, and must not be
  *     touched by the caller, until `lsam_destroy`.  It must be 256-byte aligned.
  *   - All kernels are enqueued on the caller's stream (a hipStream_t passed as void*,
- *     NULL = the default stream).  `lsam_step` and `lsam_sync` do not block the host;
- *     the read-out calls synchronise the stream before copying.
+ *     NULL = the default stream).  `lsam_step` and `lsam_sync` do not block the host,
+ *     allocate nothing and may be captured into a HIP graph (the host-side counters --
+ *     periods, local counts, the noise step -- advance at capture, not at replay).  The
+ *     read-out and restore calls synchronise the stream and move data through a pinned
+ *     host staging buffer (64 MiB, allocated by the context on first use, freed by
+ *     `lsam_destroy`).
  *   - A context is not thread-safe; use one per host thread.
  *
  * Flat parameter layout of one replica and of the center y (what `init_params` holds and

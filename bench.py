@@ -32,17 +32,17 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "76abd8ecabc85ef1"
+TRAFFIC_SOURCES = "adf91bc39256b53b"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43657227,
-             "gemm_dx": 42128384, "gemm_fwd": 62144768, "perturb": 201945472},
-    "cfg3": {"bias_grad": 13681809, "center": 1773572160, "descent": 17232396523, "gemm_dw":
-             445944106, "gemm_dx": 250125392, "gemm_fwd": 233097444, "perturb": 5065986987,
-             "softmax_ce": 1429035},
-    "cfg4": {"center": 3200044288, "descent": 25600045909, "perturb": 9600050731,
-             "sumsq_partials": 3416330976},
-    "cfg5": {"bias_grad": 118063128, "descent": 188956680597, "gemm_dw": 4958184013, "gemm_dx":
-             2332865643, "gemm_fwd": 2035667436, "perturb": 59024471083, "softmax_ce": 95600107},
+    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43652597,
+             "gemm_dx": 42123264, "gemm_fwd": 62131520, "perturb": 201945685},
+    "cfg3": {"bias_grad": 13681894, "center": 1773569920, "descent": 17231767701, "gemm_dw":
+             445968794, "gemm_dx": 250125365, "gemm_fwd": 233099030, "perturb": 5065974059,
+             "softmax_ce": 1428971},
+    "cfg4": {"center": 3200045824, "descent": 25600045867, "perturb": 9600050389,
+             "sumsq_partials": 3415938837},
+    "cfg5": {"bias_grad": 118037751, "descent": 188959045440, "gemm_dw": 4953648477, "gemm_dx":
+             2333095758, "gemm_fwd": 2034256238, "perturb": 59024470869, "softmax_ce": 95613467},
 }
 
 

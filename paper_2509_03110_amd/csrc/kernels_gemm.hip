@@ -430,7 +430,8 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
       }
     __syncthreads();
 #pragma unroll
-    for (int rr = rsub; rr < 64; rr += ROWS_PER_PASS) {
+    for (int pass = 0; pass < 64 / ROWS_PER_PASS; ++pass) {
+      const int rr = pass * ROWS_PER_PASS + rsub;
       const int m = m0 + (rr >> 5) * (BM / 2) + i * 32 + (rr & 31);
       if (m < p.M && n < p.N) {
         f32x4 v = *reinterpret_cast<const f32x4*>(stage + rr * PITCH + c4);

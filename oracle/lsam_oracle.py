@@ -6,7 +6,8 @@ leg; the product path never calls it and shares no code with it.
 
 Everything is float64 numpy, one replica after another, no blocking, fusion or
 reordering beyond what the paper's formulas state.  `numpy.matmul` is the only
-library primitive used as a step (the dense layers).
+library primitive used as a step (the dense layers, and the nine taps of a
+3x3 convolution, each a matrix product over the channels).
 
 What follows the paper, by passage:
   * loss f(x; xi): empirical mean over the minibatch (Introduction, problem
@@ -37,7 +38,9 @@ Parity status: the paper prints no iterate, loss value or worked example, so
 agreement with the authors' own implementation is "parity unpinned".  Every
 function here is pinned instead by finite differences, closed forms, reduction
 to Algorithm 1 / Algorithm 2 special cases, brute-force bookkeeping and an
-autograd/`torch.optim.SGD` witness in tests/test_oracle_pins.py.
+autograd/`torch.optim.SGD` witness in tests/test_oracle_pins.py (the
+convolutional model: torch's own convolution and pooling routines under
+autograd, finite differences, and hand-worked impulse and tie cases).
 """
 from __future__ import annotations
 
@@ -169,6 +172,148 @@ class Mlp:
         return loss, grad
 
 
+def conv_layer_shapes(dims, n_conv, img_h, img_w, pool_mask):
+    """(fan_in, out) of every layer of the convolutional model described at `Cnn`, plus the
+    image size after the convolution stack."""
+    h, w = int(img_h), int(img_w)
+    shapes = []
+    for l in range(len(dims) - 1):
+        if l < n_conv:
+            shapes.append((9 * dims[l], dims[l + 1]))
+            if (pool_mask >> l) & 1:
+                if h % 2 or w % 2:
+                    raise ValueError("2x2 pooling needs even image sides")
+                h, w = h // 2, w // 2
+        elif l == n_conv:
+            shapes.append((h * w * dims[l], dims[l + 1]))
+        else:
+            shapes.append((dims[l], dims[l + 1]))
+    return shapes, (h, w)
+
+
+class Cnn:
+    """Small convolutional ReLU classifier (the paper's experiments train convolutional
+    networks on 32x32x3 images; Section "Experiments" names a five-layer one without giving
+    its layers, so the shape is a parameter here).
+
+    Layers l < n_conv: 3x3 convolution, stride 1, zero padding 1, C_l -> C_{l+1} channels,
+    bias, ReLU, then a 2x2/stride-2 max-pool if bit l of pool_mask is set.  The remaining
+    layers are dense as in `Mlp`, the first of them reading the image flattened in (row,
+    column, channel) order.  dims = (C_0, ..., C_{n_conv}, F_1, ..., classes).
+    Tensors are [B, H, W, C].  Flat parameters per layer: W_l [out, 3, 3, C_l] (dense:
+    [out, in]) row-major, then b_l [out].
+
+      Z[b,i,j,o] = b[o] + sum_{u,v,c} Xpad[b,i+u,j+v,c] W[o,u,v,c]     (Xpad: X with a zero rim)
+      P[b,i,j,c] = max_{u,v in {0,1}} A[b,2i+u,2j+v,c]
+    The pool's gradient goes to the first maximal element of each window in (u, v) order."""
+
+    def __init__(self, dims, n_conv, img_h, img_w, pool_mask):
+        self.dims = tuple(int(v) for v in dims)
+        self.L = len(self.dims) - 1
+        self.n_conv = int(n_conv)
+        self.H, self.W = int(img_h), int(img_w)
+        self.pool_mask = int(pool_mask)
+        self.shapes, self.final_hw = conv_layer_shapes(self.dims, self.n_conv, self.H, self.W,
+                                                       self.pool_mask)
+        self.offsets = []
+        off = 0
+        for fi, fo in self.shapes:
+            self.offsets.append((off, off + fo * fi, off + fo * fi + fo))
+            off += fo * fi + fo
+        self.d = off
+        self.last_margin = np.inf
+
+    def loss_and_grad(self, x, X, labels):
+        x = np.asarray(x, dtype=np.float64)
+        X = np.asarray(X, dtype=np.float64)
+        B = X.shape[0]
+        self.last_margin = np.inf
+        # ---- forward ----
+        conv_in, conv_act, pooled_from = [], [], []
+        A = X
+        for l in range(self.n_conv):
+            o0, o1, o2 = self.offsets[l]
+            cin, cout = self.dims[l], self.dims[l + 1]
+            Wl = x[o0:o1].reshape(cout, 3, 3, cin)
+            h, w = A.shape[1], A.shape[2]
+            Ap = np.zeros((B, h + 2, w + 2, cin))
+            Ap[:, 1:h + 1, 1:w + 1, :] = A
+            Z = np.zeros((B, h, w, cout)) + x[o1:o2]
+            for u in range(3):
+                for v in range(3):
+                    Z += Ap[:, u:u + h, v:v + w, :] @ Wl[:, u, v, :].T
+            self.last_margin = min(self.last_margin, float(np.min(np.abs(Z))))
+            R = np.maximum(Z, 0.0)
+            conv_in.append(Ap)
+            conv_act.append(R)
+            if (self.pool_mask >> l) & 1:
+                win = R.reshape(B, h // 2, 2, w // 2, 2, cout).transpose(0, 1, 3, 5, 2, 4)
+                win = win.reshape(B, h // 2, w // 2, cout, 4)       # window order (u, v)
+                pooled_from.append(np.argmax(win, axis=-1))          # first maximum
+                A = win.max(axis=-1)
+            else:
+                pooled_from.append(None)
+                A = R
+        acts = [A.reshape(B, -1)]
+        for l in range(self.n_conv, self.L):
+            o0, o1, o2 = self.offsets[l]
+            fi, fo = self.shapes[l]
+            Z = acts[-1] @ x[o0:o1].reshape(fo, fi).T + x[o1:o2]
+            if l < self.L - 1:
+                self.last_margin = min(self.last_margin, float(np.min(np.abs(Z))))
+                acts.append(np.maximum(Z, 0.0))
+            else:
+                acts.append(Z)
+        logits = acts[-1]
+        zmax = logits.max(axis=1, keepdims=True)
+        e = np.exp(logits - zmax)
+        se = e.sum(axis=1, keepdims=True)
+        rows = np.arange(B)
+        loss = float(np.mean((np.log(se) + zmax)[:, 0] - logits[rows, labels]))
+        # ---- backward ----
+        dZ = e / se
+        dZ[rows, labels] -= 1.0
+        dZ /= B
+        grad = np.zeros(self.d)
+        dA = None
+        for l in range(self.L - 1, self.n_conv - 1, -1):
+            o0, o1, o2 = self.offsets[l]
+            fi, fo = self.shapes[l]
+            a_in = acts[l - self.n_conv]
+            grad[o0:o1] = (dZ.T @ a_in).ravel()
+            grad[o1:o2] = dZ.sum(axis=0)
+            dA = dZ @ x[o0:o1].reshape(fo, fi)
+            if l > self.n_conv:
+                dZ = dA * (a_in > 0.0)
+        for l in range(self.n_conv - 1, -1, -1):
+            o0, o1, o2 = self.offsets[l]
+            cin, cout = self.dims[l], self.dims[l + 1]
+            R = conv_act[l]
+            h, w = R.shape[1], R.shape[2]
+            if pooled_from[l] is not None:
+                dP = dA.reshape(B, h // 2, w // 2, cout)
+                dwin = np.zeros((B, h // 2, w // 2, cout, 4))
+                np.put_along_axis(dwin, pooled_from[l][..., None], dP[..., None], axis=-1)
+                dR = dwin.reshape(B, h // 2, w // 2, cout, 2, 2).transpose(0, 1, 4, 2, 5, 3)
+                dR = dR.reshape(B, h, w, cout)
+            else:
+                dR = dA.reshape(B, h, w, cout)
+            dZc = dR * (R > 0.0)
+            Wl = x[o0:o1].reshape(cout, 3, 3, cin)
+            Ap = conv_in[l]
+            dW = np.zeros((cout, 3, 3, cin))
+            dAp = np.zeros_like(Ap)
+            flat = dZc.reshape(-1, cout)
+            for u in range(3):
+                for v in range(3):
+                    dW[:, u, v, :] = flat.T @ Ap[:, u:u + h, v:v + w, :].reshape(-1, cin)
+                    dAp[:, u:u + h, v:v + w, :] += dZc @ Wl[:, u, v, :]
+            grad[o0:o1] = dW.ravel()
+            grad[o1:o2] = flat.sum(axis=0)
+            dA = dAp[:, 1:h + 1, 1:w + 1, :]
+        return loss, grad
+
+
 # ---- Langevin noise of the sampler ----------------------------------------------------------------
 # Section "Langevin Dynamics for Sampling" names SGLD as the Sampler of Algorithm 2; the
 # experiments run it noise-free.  With noise_scale = sigma > 0 the sampler step becomes
@@ -214,8 +359,10 @@ def normals_from_counters(counter, key):
     return out
 
 
-def langevin_noise(dims, d_raw, replica, step, seed):
-    """xi for one replica and step, in the flat parameter layout."""
+def langevin_noise(dims, d_raw, replica, step, seed, shapes=None):
+    """xi for one replica and step, in the flat parameter layout.  `shapes`: (fan_in, out) per
+    layer when they are not the consecutive pairs of `dims` (convolutional layers: a filter
+    bank [out, 3, 3, C] is the matrix [out, 9 C])."""
     key = (seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF)
     if not len(dims):
         groups = np.arange((d_raw + 3) // 4, dtype=np.uint64)
@@ -223,8 +370,9 @@ def langevin_noise(dims, d_raw, replica, step, seed):
                                    np.uint64(replica << 16), np.uint64(step)), key)
         return z.reshape(-1)[:d_raw]
     parts = []
-    for l in range(len(dims) - 1):
-        fi, fo = dims[l], dims[l + 1]
+    if shapes is None:
+        shapes = [(dims[l], dims[l + 1]) for l in range(len(dims) - 1)]
+    for l, (fi, fo) in enumerate(shapes):
         for is_bias, rows, cols in ((0, fo, fi), (1, 1, fo)):
             cg = np.arange((cols + 3) // 4, dtype=np.uint64)[None, :]
             rr = np.arange(rows, dtype=np.uint64)[:, None]
@@ -250,13 +398,19 @@ class LsamOracle:
                  rho=0.05, gamma=1e-12, lr=0.1, lr_center=1.0, momentum=0.9, beta=0.9,
                  lambda0=0.5, lambda_abs=-1.0, nesterov=1, tau=None, tau_min=1, tau_max=1,
                  sched_seed=0, sched_mode=SCHED_FIXED, algorithm=ALG_LSAM, noise_scale=0.0,
-                 noise_seed=0):
+                 noise_seed=0, n_conv=0, img_h=0, img_w=0, pool_mask=0):
         self.K = int(K)
         self.algorithm = int(algorithm)
         self.noise_scale, self.noise_seed = float(noise_scale), int(noise_seed)
         self.dims = tuple(dims)
         self.t = 0                      # sampler steps taken so far
-        self.model = Mlp(dims, gemm_dtype) if len(dims) else None
+        if n_conv:
+            if gemm_dtype != 0:
+                raise ValueError("the convolutional model is float32 only")
+            self.model = Cnn(dims, n_conv, img_h, img_w, pool_mask)
+        else:
+            self.model = Mlp(dims, gemm_dtype) if len(dims) else None
+        self.shapes = self.model.shapes if n_conv else None
         self.d = self.model.d if self.model else int(d_raw)
         self.batch = int(batch)
         self.rho, self.gamma = float(rho), float(gamma)
@@ -311,7 +465,7 @@ class LsamOracle:
         else:
             self.x[i] = self.x[i] - self.lr * self.v[i]
         if self.noise_scale != 0.0:
-            xi = langevin_noise(self.dims, self.d, i, self.t, self.noise_seed)
+            xi = langevin_noise(self.dims, self.d, i, self.t, self.noise_seed, self.shapes)
             self.x[i] = self.x[i] + self.noise_scale * np.sqrt(2.0 * self.lr) * xi
         self.S[i] += self.x[i]
 

@@ -459,3 +459,150 @@ def test_langevin_sampler_reaches_the_stationary_variance():
     expect = 2 * eta * sigma ** 2 / (1 - (1 - eta * lam) ** 2)
     assert abs(var / expect - 1) < 0.03, (var, expect)
     assert abs(o.get_params(0).mean()) < 4 * np.sqrt(expect / d)
+
+
+# ---- convolutional model ---------------------------------------------------------------------
+def _torch_cnn_loss(xt, X, lab, dims, n_conv, pool_mask, shapes):
+    """The same network written with torch's own convolution, pooling and loss routines."""
+    import torch.nn.functional as F
+    A = torch.tensor(X).permute(0, 3, 1, 2)
+    off = 0
+    for l in range(n_conv):
+        fi, fo = shapes[l]
+        W = xt[off:off + fo * fi].reshape(fo, 3, 3, dims[l]).permute(0, 3, 1, 2)
+        off += fo * fi
+        A = F.relu(F.conv2d(A, W, xt[off:off + fo], padding=1))
+        off += fo
+        if (pool_mask >> l) & 1:
+            A = F.max_pool2d(A, 2)
+    A = A.permute(0, 2, 3, 1).reshape(X.shape[0], -1)
+    for l in range(n_conv, len(shapes)):
+        fi, fo = shapes[l]
+        A = A @ xt[off:off + fo * fi].reshape(fo, fi).T + xt[off + fo * fi:off + fo * fi + fo]
+        off += fo * fi + fo
+        if l < len(shapes) - 1:
+            A = F.relu(A)
+    return F.cross_entropy(A, torch.tensor(lab))
+
+
+@pytest.mark.parametrize("dims,n_conv,H,W,pool_mask,B", [
+    ((3, 8, 16, 12, 5), 2, 8, 8, 0b01, 4),
+    ((2, 4, 4, 4, 3), 3, 4, 8, 0b101, 3),
+    ((1, 3, 6), 1, 6, 4, 0, 2),
+    ((3, 5, 7, 4), 2, 4, 4, 0b11, 5),
+])
+def test_cnn_gradient_matches_torch_autograd(dims, n_conv, H, W, pool_mask, B):
+    from oracle.lsam_oracle import Cnn
+    m = Cnn(dims, n_conv, H, W, pool_mask)
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal(m.d) * 0.3
+    X = rng.standard_normal((B, H, W, dims[0]))
+    lab = rng.integers(0, dims[-1], B)
+    loss, g = m.loss_and_grad(x, X, lab)
+    xt = torch.tensor(x, requires_grad=True)
+    L = _torch_cnn_loss(xt, X, lab, dims, n_conv, pool_mask, m.shapes)
+    L.backward()
+    assert abs(loss - L.item()) < 1e-12
+    assert np.max(np.abs(g - xt.grad.numpy())) / np.max(np.abs(g)) < 1e-12
+
+
+def test_cnn_gradient_matches_finite_differences():
+    from oracle.lsam_oracle import Cnn
+    m = Cnn((2, 3, 4, 3), 2, 4, 4, 0b10)
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal(m.d) * 0.4
+    X = rng.standard_normal((3, 4, 4, 2))
+    lab = rng.integers(0, 3, 3)
+    _, g = m.loss_and_grad(x, X, lab)
+    h = 1e-6
+    fd = np.zeros(m.d)
+    for j in range(m.d):
+        e = np.zeros(m.d)
+        e[j] = h
+        fd[j] = (m.loss_and_grad(x + e, X, lab)[0] - m.loss_and_grad(x - e, X, lab)[0]) / (2 * h)
+    assert np.max(np.abs(fd - g)) / np.max(np.abs(g)) < 1e-6
+
+
+@pytest.mark.parametrize("u,v", [(0, 0), (0, 2), (1, 1), (2, 1)])
+def test_conv_tap_orientation_and_flatten_order(u, v):
+    # one 1->1 channel filter with a single 1 at tap (u, v), then an identity dense layer:
+    # Z[i, j] = X[i + u - 1, j + v - 1], so an impulse of height a at (i0, j0) shows up at
+    # (i0 - u + 1, j0 - v + 1), position 3 (i0 - u + 1) + (j0 - v + 1) of the 9 logits, and
+    # the loss is log(8 + e^a) - a when that position is the label
+    from oracle.lsam_oracle import Cnn
+    m = Cnn((1, 1, 9), 1, 3, 3, 0)
+    x = np.zeros(m.d)
+    x[3 * u + v] = 1.0
+    o0, o1, _ = m.offsets[1]
+    x[o0:o1] = np.eye(9).ravel()
+    a, i0, j0 = 1.7, 1, 1
+    X = np.zeros((1, 3, 3, 1))
+    X[0, i0, j0, 0] = a
+    pos = 3 * (i0 - u + 1) + (j0 - v + 1)
+    loss, _ = m.loss_and_grad(x, X, np.array([pos]))
+    assert abs(loss - (np.log(8.0 + np.exp(a)) - a)) < 1e-14
+    other, _ = m.loss_and_grad(x, X, np.array([(pos + 1) % 9]))
+    assert abs(other - np.log(8.0 + np.exp(a))) < 1e-14
+
+
+def test_pool_gradient_goes_to_the_first_maximum():
+    # 1->1 channel identity filter on a 2x2 image, pool to one value, dense 1->2 with weights
+    # (1, -1): logits (p, -p).  With X = [[1, 3], [3, 2]] the maximum 3 occurs twice; the
+    # gradient w.r.t. the filter's centre tap is dL/dp * X[argmax] either way, but the bias of
+    # tap (1, 2) (right neighbour) sees X[argmax + 1 column]: 0 rim for the first maximum at
+    # (0, 1), and 2 for the second at (1, 0)
+    from oracle.lsam_oracle import Cnn
+    m = Cnn((1, 1, 2), 1, 2, 2, 0b1)
+    x = np.zeros(m.d)
+    x[4] = 1.0                       # centre tap
+    o0, o1, _ = m.offsets[1]
+    x[o0:o1] = [1.0, -1.0]
+    X = np.array([[1.0, 3.0], [3.0, 2.0]]).reshape(1, 2, 2, 1)
+    loss, g = m.loss_and_grad(x, X, np.array([0]))
+    p = 3.0
+    assert abs(loss - np.log1p(np.exp(-2 * p))) < 1e-14
+    dp = -2.0 / (1.0 + np.exp(2 * p))        # d loss / d p
+    assert abs(g[4] - dp * 3.0) < 1e-14      # centre tap
+    assert abs(g[5]) < 1e-14                 # tap (1, 2): right neighbour of (0, 1) is the rim
+    assert abs(g[7] - dp * 2.0) < 1e-14      # tap (2, 1): lower neighbour of (0, 1) is X[1, 1]
+
+
+def test_noise_layout_with_explicit_layer_shapes():
+    dims = (6, 5, 3)
+    a = langevin_noise(dims, 0, 1, 4, 99)
+    b = langevin_noise(dims, 0, 1, 4, 99, shapes=[(6, 5), (5, 3)])
+    assert np.array_equal(a, b)
+    # a filter bank [out, 3, 3, C] draws its noise as the matrix [out, 9 C]
+    c = langevin_noise((2, 4, 3), 0, 0, 0, 7, shapes=[(18, 4), (4 * 4 * 4, 3)])
+    d = langevin_noise((18, 4), 0, 0, 0, 7)
+    assert np.array_equal(c[:18 * 4 + 4], d)
+
+
+def test_cnn_lsam_step_matches_sgd_witness():
+    # K = 1, lambda = 0, mu = 0: one LSAM step is one SAM step of plain SGD; torch autograd and
+    # torch.optim.SGD on the torch-written network are the witness
+    from oracle.lsam_oracle import Cnn
+    w = workloads.Workload("c", K=1, dims=(3, 4, 6, 5, 3), batch=4, n_conv=2, img_h=4, img_w=4,
+                           pool_mask=0b10, n_classes=3, rho=0.1, lr=0.05, momentum=0.0,
+                           lambda_abs=0.0, tau=(4,), data_seed=21)
+    x0 = workloads.init_params(w).astype(np.float64)
+    X, lab = workloads.batch(w, 0)
+    o = LsamOracle(K=1, init_params=x0, dims=w.dims, batch=w.batch, rho=w.rho, lr=w.lr,
+                   momentum=0.0, lambda_abs=0.0, tau=(4,), n_conv=2, img_h=4, img_w=4,
+                   pool_mask=0b10)
+    o.step(X, lab)
+    shapes = Cnn(w.dims, 2, 4, 4, 0b10).shapes
+    xt = torch.tensor(x0, requires_grad=True)
+    opt = torch.optim.SGD([xt], lr=w.lr)
+    Xd, ld = X[0].astype(np.float64), lab[0].astype(np.int64)
+    _torch_cnn_loss(xt, Xd, ld, w.dims, 2, 0b10, shapes).backward()
+    g1 = xt.grad.clone()
+    with torch.no_grad():
+        eps = w.rho * g1 / (g1.norm() + 1e-12)
+        xt.add_(eps)
+    xt.grad = None
+    _torch_cnn_loss(xt, Xd, ld, w.dims, 2, 0b10, shapes).backward()
+    with torch.no_grad():
+        xt.sub_(eps)
+    opt.step()
+    assert np.max(np.abs(o.get_params(0) - xt.detach().numpy())) < 1e-13

@@ -10,7 +10,9 @@ any computation.
 The shapes mirror the paper's image-classification set-up (Experiments,
 "Experiment Setup": n = 4 workers, per-worker batch 128; CIFAR-shaped
 3x32x32 = 3072-dim inputs, 10/100 classes), with dense MLPs standing in for
-the paper's convolutional models.
+the paper's convolutional models, plus a small convolutional classifier on
+32x32x3 inputs (the paper's SVHN model is a five-layer convolutional network
+whose layers it does not list).
 """
 from __future__ import annotations
 
@@ -48,6 +50,10 @@ class Workload:
     algorithm: int = 0                      # 0 = LSAM, 1 = synchronous data-parallel baseline
     noise_scale: float = 0.0                # sigma of the Langevin sampler, 0 = noise-free
     noise_seed: int = 0
+    n_conv: int = 0                         # leading 3x3 convolution layers (0: dense model);
+    img_h: int = 0                          # then dims = (C_0..C_n_conv, F_1.., classes) and the
+    img_w: int = 0                          # input is [K, B, img_h, img_w, C_0]
+    pool_mask: int = 0                      # bit l: 2x2 max-pool after convolution l
     steps: int = 20
     data_seed: int = 0
     n_classes: int = field(default=0)
@@ -55,11 +61,31 @@ class Workload:
     batch_pool: int = 0                     # 0 => fresh batch each step, else pool size cycled
 
     @property
+    def layer_shapes(self):
+        """(fan_in, out) per layer: a 3x3 filter bank counts 9 C_in inputs, the first dense
+        layer after the convolutions reads the whole (pooled) image."""
+        h, w = self.img_h, self.img_w
+        out = []
+        for l in range(len(self.dims) - 1):
+            fan_in = self.dims[l]
+            if l < self.n_conv:
+                fan_in = 9 * self.dims[l]
+                if (self.pool_mask >> l) & 1:
+                    h, w = h // 2, w // 2
+            elif self.n_conv and l == self.n_conv:
+                fan_in = h * w * self.dims[l]
+            out.append((fan_in, self.dims[l + 1]))
+        return out
+
+    @property
+    def input_shape(self):
+        return (self.img_h, self.img_w, self.dims[0]) if self.n_conv else (self.dims[0],)
+
+    @property
     def d(self) -> int:
         if not self.dims:
             return self.d_raw
-        return sum(self.dims[l] * self.dims[l + 1] + self.dims[l + 1]
-                   for l in range(len(self.dims) - 1))
+        return sum(fi * fo + fo for fi, fo in self.layer_shapes)
 
     def scaled(self, **kw) -> "Workload":
         return replace(self, **kw)
@@ -102,8 +128,7 @@ def init_params(w: Workload, seed: Optional[int] = None) -> np.ndarray:
     if not w.dims:
         return rng.standard_normal(w.d_raw, dtype=np.float32)
     parts = []
-    for l in range(len(w.dims) - 1):
-        fan_in, out = w.dims[l], w.dims[l + 1]
+    for fan_in, out in w.layer_shapes:
         bound = np.float32(1.0 / np.sqrt(fan_in))
         parts.append((rng.random(out * fan_in, dtype=np.float32) * 2 - 1) * bound)
         parts.append((rng.random(out, dtype=np.float32) * 2 - 1) * bound)
@@ -121,8 +146,7 @@ def init_params_margin(w: Workload, seed: Optional[int] = None) -> np.ndarray:
     off = 0
     L = len(w.dims) - 1
     c_prev = None
-    for l in range(L):
-        fan_in, out = w.dims[l], w.dims[l + 1]
+    for l, (fan_in, out) in enumerate(w.layer_shapes):
         if l < L - 1:
             c = 2.0 / np.sqrt(out)
             natural_std = 0.577 if l == 0 else 0.408 * c_prev
@@ -135,13 +159,14 @@ def init_params_margin(w: Workload, seed: Optional[int] = None) -> np.ndarray:
 
 
 def batch(w: Workload, step: int):
-    """Inputs X [K,B,in_0] fp32 ~ N(0,1) and labels [K,B] int32 uniform over the classes
+    """Inputs X [K,B,in_0] (convolutional workloads: [K,B,H,W,C_0]) fp32 ~ N(0,1) and labels
+    [K,B] int32 uniform over the classes
     for tick `step` (a pool index when the workload cycles a fixed pool).  For bf16
     workloads the low 16 mantissa bits are cleared so every value is exactly
     representable in bf16 and no rounding rule enters the data."""
     idx = step % w.batch_pool if w.batch_pool else step
     rng = _rng(w.data_seed, 1000 + idx)
-    X = rng.standard_normal((w.K, w.batch, w.dims[0]), dtype=np.float32)
+    X = rng.standard_normal((w.K, w.batch) + w.input_shape, dtype=np.float32)
     if w.gemm_dtype == 1:
         X = (X.view(np.uint32) & np.uint32(0xFFFF0000)).view(np.float32)
     labels = rng.integers(0, w.n_classes, size=(w.K, w.batch), dtype=np.int32)

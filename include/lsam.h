@@ -28,6 +28,15 @@
  * Flat parameter layout of one replica and of the center y (what `init_params` holds and
  * what `lsam_get_params` returns): for l = 1..L: W_l row-major [out_l, in_l], then
  * b_l [out_l].  In raw-vector mode (n_layers == 0) it is a plain vector of d_raw floats.
+ *
+ * Convolutional model (n_conv > 0; the paper's experiments train convolutional networks on
+ * 32x32x3 images, Section "Experiments"): dims = C_0, ..., C_{n_conv}, F_1, ..., classes.
+ * Layer l < n_conv maps C_l to C_{l+1} channels and stores its filters as W_l
+ * [C_{l+1}, 3, 3, C_l] row-major, i.e. in_l = 9 C_l in the layout above; the first dense layer
+ * reads the (pooled) image flattened in (row, column, channel) order, in_l = H' W' C_{n_conv}.
+ * Images are [H, W, C] with the channel contiguous.  fp32 only; C_1..C_{n_conv} must be
+ * multiples of 8 and every pooled image must have even sides.  The pool's gradient goes to
+ * the first maximum of a window in row-major order.
  */
 #ifndef LSAM_H
 #define LSAM_H
@@ -73,7 +82,8 @@ typedef struct lsam_ctx lsam_ctx;
 typedef struct {
   int32_t K;              /* number of replicas = the paper's n workers, 1..LSAM_MAX_REPLICAS */
   int32_t n_layers;       /* L dense layers; 0 selects raw-vector mode                */
-  const int32_t* dims;    /* [host] L+1 entries in_0, out_1, ..., out_L (MLP mode)    */
+  const int32_t* dims;    /* [host] L+1 entries in_0, out_1, ..., out_L (MLP mode);
+                             channel counts for the convolution layers, see above     */
   int64_t d_raw;          /* parameters per replica, raw-vector mode only             */
   int32_t batch;          /* B samples per replica per step (MLP mode)                */
   int32_t gemm_dtype;     /* LSAM_GEMM_FP32 or LSAM_GEMM_BF16                         */
@@ -98,6 +108,10 @@ typedef struct {
                              Philox4x32-10 counters (see csrc/langevin.h); 0 = noise-free,
                              as the paper's experiments run                            */
   uint64_t noise_seed;    /* key of that generator                                    */
+  int32_t n_conv;         /* 0: dense model.  > 0: the first n_conv layers are 3x3 convolutions
+                             (stride 1, zero rim 1, bias, ReLU), the rest dense; see below   */
+  int32_t img_h, img_w;   /* input image sides (n_conv > 0)                           */
+  uint32_t pool_mask;     /* bit l set: a 2x2/stride-2 max-pool follows convolution l */
 } lsam_config;
 
 /* Which per-replica buffer `lsam_get_buffer` copies out. */
@@ -128,7 +142,8 @@ int lsam_init(const lsam_config* cfg, const float* init_params, int64_t n_init,
  * Perturbation"): forward/backward at x_i on (X_i, labels_i) -> g1; n = ||g1||_2 over the
  * whole replica; x~ = x + rho g1/(n + gamma); forward/backward at x~ on the same batch
  * -> g2; G = g2 + lambda_i (x_i - y); momentum update of x_i; S_i += x_i; c_i += 1.
- *   X      [device] [K, B, in_0] row-major; float in fp32 mode, bfloat16 in bf16 mode
+ *   X      [device] [K, B, in_0] row-major; float in fp32 mode, bfloat16 in bf16 mode;
+ *          convolutional model: [K, B, img_h, img_w, C_0] floats
  *   labels [device] [K, B] int32 class indices in [0, out_L)
  *   loss   [device] [K] floats receiving the first-pass mean cross-entropy, or NULL
  * MLP mode only (LSAM_ESTATE otherwise).  Labels are not range-checked on the host. */

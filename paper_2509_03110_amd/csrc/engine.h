@@ -137,6 +137,30 @@ int launch_head_weight_grad(const float* dz, int ld_dz, const float* A, int ldA,
                             float* db, int64_t strideG, int K, int B, int C, int in, double* sumsq,
                             int64_t sumsq_stride, hipStream_t s);
 
+// 3x3 convolution support (fp32, tensors [K][B][H][W][C], C contiguous).  All return 0, or -1
+// when the shape does not fit the kernel (pitches and channel counts that are not multiples
+// of 4 where stated).
+// col[k][(b,i,j)][(u,v,c)] = X[k][b][i+u-1][j+v-1][c], zero outside the image and in the
+// padding columns 9C..ld-1 (ld % 4 == 0; any C).
+int launch_unfold3x3(const float* X, int64_t strideX, float* col, int64_t strideCol, int ld, int K,
+                     int B, int H, int W, int C, hipStream_t s);
+// dX[k][b][i][j][c] = sum_{u,v} dcol[k][(b,i-u+1,j-v+1)][(u,v,c)], taps added in (u,v) order,
+// set to zero where mask (same shape as dX, may be null) is not positive.  C % 4 == 0.
+int launch_fold3x3(const float* dcol, int64_t strideCol, int ld, float* dX, const float* mask,
+                   int64_t strideX, int K, int B, int H, int W, int C, hipStream_t s);
+// Column sums of K contiguous [rows][N] matrices, first stage: partial[k][chunk][n] = sum of
+// the rows of chunk `chunk` (colsum_chunks(rows) chunks of equal height, the last one ragged);
+// returns the chunk count, -1 if N is not a multiple of 4 in 4..1024.  launch_bias_grad over
+// the partials finishes the sum.
+int colsum_chunks(int64_t rows);
+int launch_colsum_partials(const float* A, int64_t rows, int N, int K, float* partial, hipStream_t s);
+// 2x2/stride-2 max-pool over `images` contiguous [H][W][C] images, and the backward pass of
+// ReLU-then-pool: dA = dP at the first maximum of each window if it is positive, else 0
+// (A: the ReLU output that was pooled).  C % 4 == 0, H and W even.
+int launch_maxpool2(const float* A, float* P, int64_t images, int H, int W, int C, hipStream_t s);
+int launch_maxpool2_backward(const float* A, const float* dP, float* dA, int64_t images, int H,
+                             int W, int C, hipStream_t s);
+
 // Measured ceilings: device copy (GB/s, read + written) between the halves of `scratch`, and
 // MFMA-only loops (TFLOP/s, bf16 32x32x16 and fp32 32x32x2).  Blocks until done; 0 or -1.
 int probe_peaks(void* scratch, size_t bytes, hipStream_t s, double* copy_gbs, double* bf16_tflops,

@@ -548,7 +548,10 @@ Plan make_plan(const GemmDesc& d, int tile_override) {
     int want = (int)((512 + nt - 1) / nt);
     int cap = ksteps / 4;
     int sp = want < cap ? want : cap;
-    if (sp > 16) sp = 16;
+    // up to 16 splits; more only for the very long contractions of convolution weight
+    // gradients (batch x image rows), whose outputs are a handful of tiles
+    const int most = ksteps >= 4096 ? 64 : (ksteps >= 1024 ? 32 : 16);
+    if (sp > most) sp = most;
     if (sp > 1) {
       pl.steps_per_split = (ksteps + sp - 1) / sp;
       pl.splits = (ksteps + pl.steps_per_split - 1) / pl.steps_per_split;

@@ -100,8 +100,20 @@ struct Layer {
   int64_t w_flat, b_flat; // offsets inside the public flat layout
 };
 
+// One 3x3 convolution layer: image [H][W][Cin] -> [H][W][Cout] (-> [H/2][W/2][Cout] if pooled).
+struct ConvLayer {
+  int H, W, Cin, Cout, pool;
+  int64_t rows;        // B H W: rows of the unfolded image and of the layer's output
+  int ldc;             // pitch of the unfolded image, 9 Cin rounded up to 8
+  size_t col, out, pooled, dout, dpooled;   // workspace offsets ([K] contiguous replicas each)
+};
+
 struct Layout {
   int K = 0, L = 0, B = 0;
+  int n_conv = 0;              // layers 0..n_conv-1 are convolutions
+  std::vector<ConvLayer> conv;
+  size_t dcol = 0;             // gradient of an unfolded image (largest layer that needs one)
+  size_t colsum = 0;           // first-stage column sums of the bias gradients
   bool bf16 = false, raw = false;
   int64_t d = 0, d_pad = 0;
   std::vector<Layer> layers;
@@ -140,6 +152,33 @@ int check_config(const lsam_config* c) {
     if ((int64_t)c->K * c->batch > (1 << 24)) return fail(LSAM_EINVAL, "K*batch too large");
     if (c->gemm_dtype != LSAM_GEMM_FP32 && c->gemm_dtype != LSAM_GEMM_BF16)
       return fail(LSAM_EINVAL, "gemm_dtype must be 0 (fp32) or 1 (bf16)");
+    if (c->n_conv < 0 || c->n_conv >= c->n_layers)
+      return fail(LSAM_EINVAL, "n_conv=%d must leave at least one dense layer of %d", c->n_conv,
+                  c->n_layers);
+    if (c->n_conv > 0) {
+      if (c->gemm_dtype != LSAM_GEMM_FP32)
+        return fail(LSAM_EINVAL, "the convolutional model runs in fp32 only");
+      if (c->img_h < 1 || c->img_w < 1) return fail(LSAM_EINVAL, "img_h, img_w must be >= 1");
+      int64_t h = c->img_h, w = c->img_w;
+      for (int l = 0; l < c->n_conv; ++l) {
+        if (c->dims[l + 1] % 8)
+          return fail(LSAM_EINVAL, "dims[%d]=%d: convolution outputs must be multiples of 8", l + 1,
+                      c->dims[l + 1]);
+        // one replica's unfolded image is a GEMM operand addressed with 32-bit byte offsets
+        const int64_t widest = std::max<int64_t>(round_up(9 * (int64_t)c->dims[l], 8), c->dims[l + 1]);
+        if ((int64_t)c->batch * h * w * widest * 4 >= 0x7FFFFFF0LL)
+          return fail(LSAM_EINVAL, "convolution %d: batch * image * channels too large", l);
+        if ((c->pool_mask >> l) & 1u) {
+          if (h % 2 || w % 2)
+            return fail(LSAM_EINVAL, "convolution %d: pooling needs even image sides (%lldx%lld)", l,
+                        (long long)h, (long long)w);
+          h /= 2;
+          w /= 2;
+        }
+      }
+      if (h * w * c->dims[c->n_conv] > (1 << 24))
+        return fail(LSAM_EINVAL, "flattened image too wide for the dense layers");
+    }
   }
   if (!(c->rho >= 0.f) || !(c->gamma >= 0.f)) return fail(LSAM_EINVAL, "rho, gamma must be >= 0");
   if (!(c->lr > 0.f) && c->lambda_abs < 0.f)
@@ -182,12 +221,33 @@ void build_layout(const lsam_config& c, Layout& lo) {
     lo.d = c.d_raw;
     lo.d_pad = round_up(c.d_raw, 64);
   } else {
+    lo.n_conv = c.n_conv;
+    // width[l]: columns of the matrix layer l reads (l < L), of the logits (l = L)
+    std::vector<int> width(lo.L + 1);
+    {
+      int h = c.img_h, w = c.img_w;
+      for (int l = 0; l <= lo.L; ++l) {
+        width[l] = c.dims[l];
+        if (l < lo.n_conv) {
+          ConvLayer cv{};
+          cv.H = h; cv.W = w; cv.Cin = c.dims[l]; cv.Cout = c.dims[l + 1];
+          cv.pool = (int)((c.pool_mask >> l) & 1u);
+          cv.rows = (int64_t)c.batch * h * w;
+          cv.ldc = (int)round_up(9 * (int64_t)cv.Cin, 8);
+          lo.conv.push_back(cv);
+          width[l] = 9 * cv.Cin;
+          if (cv.pool) { h /= 2; w /= 2; }
+        } else if (lo.n_conv > 0 && l == lo.n_conv) {
+          width[l] = h * w * c.dims[l];
+        }
+      }
+    }
     lo.ld.resize(lo.L + 1);
-    for (int l = 0; l <= lo.L; ++l) lo.ld[l] = (int)round_up(c.dims[l], 8);
-    lo.need_a0 = (c.dims[0] % 8) != 0;
+    for (int l = 0; l <= lo.L; ++l) lo.ld[l] = (int)round_up(width[l], 8);
+    lo.need_a0 = lo.n_conv == 0 && (c.dims[0] % 8) != 0;
     for (int l = 0; l < lo.L; ++l) {
       Layer s;
-      s.in = c.dims[l];
+      s.in = width[l];
       s.out = c.dims[l + 1];
       s.ldw = lo.ld[l];
       s.w_off = off;
@@ -250,9 +310,37 @@ void build_layout(const lsam_config& c, Layout& lo) {
     lo.loss_rows = take(cur, rows * 4);
     lo.act.assign(lo.L + 1, 0);
     lo.dz.assign(lo.L + 1, 0);
-    auto act_bytes = [&](int l) { return (size_t)lo.K * lo.act_elems(c.dims[l], lo.ld[l]) * lo.es(); };
-    for (int l = 1; l < lo.L; ++l) lo.act[l] = take(cur, act_bytes(l));
-    for (int l = 1; l <= lo.L; ++l) lo.dz[l] = take(cur, act_bytes(l));
+    auto wd = [&](int l) { return l < lo.L ? lo.layers[l].in : lo.layers[lo.L - 1].out; };
+    auto act_bytes = [&](int l) { return (size_t)lo.K * lo.act_elems(wd(l), lo.ld[l]) * lo.es(); };
+    size_t dcol_bytes = 0;
+    for (int l = 0; l < lo.n_conv; ++l) {
+      ConvLayer& cv = lo.conv[l];
+      const size_t full = (size_t)lo.K * cv.rows * cv.Cout * 4;
+      cv.col = take(cur, (size_t)lo.K * cv.rows * cv.ldc * 4);
+      cv.out = take(cur, full);
+      cv.dout = take(cur, full);
+      if (cv.pool) {
+        cv.pooled = take(cur, full / 4);
+        cv.dpooled = take(cur, full / 4);
+      }
+      if (l > 0) dcol_bytes = std::max(dcol_bytes, (size_t)lo.K * cv.rows * cv.ldc * 4);
+    }
+    if (dcol_bytes) lo.dcol = take(cur, dcol_bytes);
+    if (lo.n_conv > 0) {
+      size_t most = 0;
+      for (const ConvLayer& cv : lo.conv)
+        most = std::max(most, (size_t)lo.K * colsum_chunks(cv.rows) * cv.Cout * 4);
+      lo.colsum = take(cur, most);
+    }
+    // the dense layers start at n_conv; their input and its gradient are the last
+    // convolution's (pooled) output and that buffer's gradient
+    if (lo.n_conv > 0) {
+      const ConvLayer& cv = lo.conv[lo.n_conv - 1];
+      lo.act[lo.n_conv] = cv.pool ? cv.pooled : cv.out;
+      lo.dz[lo.n_conv] = cv.pool ? cv.dpooled : cv.dout;
+    }
+    for (int l = lo.n_conv + 1; l < lo.L; ++l) lo.act[l] = take(cur, act_bytes(l));
+    for (int l = lo.n_conv + 1; l <= lo.L; ++l) lo.dz[l] = take(cur, act_bytes(l));
     lo.logits = take(cur, rows * lo.ld[lo.L] * 4);
     if (lo.need_a0) lo.a0 = take(cur, act_bytes(0));
     // scratch for split-K partial sums: the largest request among this model's GEMMs
@@ -262,13 +350,14 @@ void build_layout(const lsam_config& c, Layout& lo) {
       if (lo.bf16) break;      // split-K serves the fp32 kernel only
       GemmDesc d{};
       d.batch = lo.K; d.in_bf16 = lo.bf16;
-      d.M = lo.B; d.N = ly.out; d.Kd = ly.in; d.a_kmajor = 1; d.b_kmajor = 1;     // forward
+      const int rows = l < lo.n_conv ? (int)lo.conv[l].rows : lo.B;
+      d.M = rows; d.N = ly.out; d.Kd = ly.in; d.a_kmajor = 1; d.b_kmajor = 1;     // forward
       d.out_bf16 = lo.bf16 && l + 1 < lo.L;
       need = std::max(need, gemm_splitk_bytes(d));
-      d.M = lo.B; d.N = ly.in; d.Kd = ly.out; d.a_kmajor = 1; d.b_kmajor = 0;     // dX
+      d.M = rows; d.N = ly.in; d.Kd = ly.out; d.a_kmajor = 1; d.b_kmajor = 0;     // dX
       d.out_bf16 = lo.bf16;
       if (l > 0) need = std::max(need, gemm_splitk_bytes(d));
-      d.M = ly.out; d.N = ly.in; d.Kd = lo.B; d.a_kmajor = 0; d.b_kmajor = 0;     // dW
+      d.M = ly.out; d.N = ly.in; d.Kd = rows; d.a_kmajor = 0; d.b_kmajor = 0;     // dW
       d.out_bf16 = 0;
       need = std::max(need, gemm_splitk_bytes(d));
     }
@@ -281,11 +370,11 @@ void build_layout(const lsam_config& c, Layout& lo) {
 // ---- per-kernel timing ---------------------------------------------------------------------------
 enum KernelClass {
   KC_GEMM_FWD = 0, KC_GEMM_DX, KC_GEMM_DW, KC_SOFTMAX_CE, KC_BIAS_GRAD, KC_SUMSQ, KC_NORM_FINISH,
-  KC_PERTURB, KC_DESCENT, KC_CENTER, KC_MISC, KC_HEAD, KC_COUNT
+  KC_PERTURB, KC_DESCENT, KC_CENTER, KC_MISC, KC_HEAD, KC_UNFOLD, KC_POOL, KC_COUNT
 };
 const char* const kClassNames[KC_COUNT] = {
     "gemm_fwd", "gemm_dx", "gemm_dw", "softmax_ce", "bias_grad", "sumsq_partials", "norm_finish",
-    "perturb", "descent", "center", "misc", "head"};
+    "perturb", "descent", "center", "misc", "head", "unfold_fold", "pool"};
 
 struct TimedLaunch {
   int cls;
@@ -378,40 +467,157 @@ float coupling(const lsam_ctx* c, int i) {
   return (float)((double)c->cfg.lambda0 / ((double)c->lr * (double)c->sched.tau()[i]));
 }
 
+// Split-K scratch shared by all GEMMs of a step.
+void split(const lsam_ctx* c, GemmDesc& d) {
+  d.splitk_ws = c->lo.splitk_bytes ? c->at<float>(c->lo.splitk) : nullptr;
+  d.splitk_bytes = c->lo.splitk_bytes;
+}
+
+// Forward pass of the convolution layers: unfold, GEMM with bias + ReLU, pool.  `params`: x or
+// the perturbed copy (fp32).  The result is the dense layers' input, lo.act[n_conv].
+int conv_forward(lsam_ctx* c, const float* X, const float* params) {
+  const Layout& lo = c->lo;
+  hipStream_t s = c->stream;
+  const float* in = X;
+  for (int l = 0; l < lo.n_conv; ++l) {
+    const ConvLayer& cv = lo.conv[l];
+    const Layer& ly = lo.layers[l];
+    float* col = c->at<float>(cv.col);
+    {
+      LaunchTimer t(c, KC_UNFOLD);
+      if (launch_unfold3x3(in, cv.rows * cv.Cin, col, cv.rows * cv.ldc, cv.ldc, lo.K, lo.B, cv.H,
+                           cv.W, cv.Cin, s) != 0)
+        return fail(LSAM_EINVAL, "unfold of convolution %d rejected", l);
+    }
+    {
+      GemmDesc d{};
+      d.A = col; d.strideA = cv.rows * cv.ldc; d.ldA = cv.ldc; d.a_kmajor = 1;
+      d.B = params + ly.w_off; d.strideB = lo.d_pad; d.ldB = ly.ldw; d.b_kmajor = 1;
+      d.C = c->at<float>(cv.out); d.strideC = cv.rows * cv.Cout; d.ldC = cv.Cout;
+      d.M = (int)cv.rows; d.N = cv.Cout; d.Kd = ly.in; d.batch = lo.K;
+      d.epilogue = EPI_BIAS_RELU;
+      d.bias = params + ly.b_off; d.strideBias = lo.d_pad;
+      split(c, d);
+      LaunchTimer t(c, KC_GEMM_FWD);
+      if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "forward GEMM of convolution %d rejected", l);
+    }
+    in = c->at<float>(cv.out);
+    if (cv.pool) {
+      LaunchTimer t(c, KC_POOL);
+      if (launch_maxpool2(in, c->at<float>(cv.pooled), (int64_t)lo.K * lo.B, cv.H, cv.W, cv.Cout, s) != 0)
+        return fail(LSAM_EINVAL, "pool of convolution %d rejected", l);
+      in = c->at<float>(cv.pooled);
+    }
+  }
+  return LSAM_OK;
+}
+
+// Backward pass of the convolution layers.  On entry lo.dz[n_conv] holds the gradient of the
+// dense layers' input (already zero where that input is zero).  Appends the layers' partial
+// sums of squares at ssq[*slots...] when ssq is non-null.
+int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq, int* slots) {
+  const Layout& lo = c->lo;
+  hipStream_t s = c->stream;
+  float* g = c->at<float>(lo.g);
+  for (int l = lo.n_conv - 1; l >= 0; --l) {
+    const ConvLayer& cv = lo.conv[l];
+    const Layer& ly = lo.layers[l];
+    float* dout = c->at<float>(cv.dout);
+    if (cv.pool) {
+      LaunchTimer t(c, KC_POOL);
+      if (launch_maxpool2_backward(c->at<float>(cv.out), c->at<float>(cv.dpooled), dout,
+                                   (int64_t)lo.K * lo.B, cv.H, cv.W, cv.Cout, s) != 0)
+        return fail(LSAM_EINVAL, "pool backward of convolution %d rejected", l);
+    }
+    {
+      GemmDesc d{};
+      d.A = dout; d.strideA = cv.rows * cv.Cout; d.ldA = cv.Cout; d.a_kmajor = 0;
+      d.B = c->at<float>(cv.col); d.strideB = cv.rows * cv.ldc; d.ldB = cv.ldc; d.b_kmajor = 0;
+      d.C = g + ly.w_off; d.strideC = lo.d_pad; d.ldC = ly.ldw;
+      d.M = cv.Cout; d.N = ly.in; d.Kd = (int)cv.rows; d.batch = lo.K;
+      d.epilogue = EPI_PLAIN;
+      split(c, d);
+      if (ssq) { d.sumsq = ssq + *slots; d.sumsq_stride = lo.nblk; }
+      int used = 0;
+      LaunchTimer t(c, KC_GEMM_DW);
+      if (launch_gemm(d, s, &used) != 0) return fail(LSAM_EINVAL, "dW GEMM of convolution %d rejected", l);
+      if (ssq) *slots += used;
+    }
+    {
+      // bias gradient: column sums of dout, in two fixed-order stages
+      LaunchTimer t(c, KC_BIAS_GRAD);
+      const int chunks = launch_colsum_partials(dout, cv.rows, cv.Cout, lo.K, c->at<float>(lo.colsum), s);
+      if (chunks < 0) return fail(LSAM_EINVAL, "bias gradient of convolution %d rejected", l);
+      const int used = launch_bias_grad(c->at<float>(lo.colsum), cv.Cout, 0, g + ly.b_off, lo.d_pad,
+                                        lo.K, chunks, cv.Cout, ssq ? ssq + *slots : nullptr, lo.nblk, s);
+      if (ssq) *slots += used;
+    }
+    if (l > 0) {
+      const ConvLayer& below = lo.conv[l - 1];
+      float* dcol = c->at<float>(lo.dcol);
+      {
+        GemmDesc d{};
+        d.A = dout; d.strideA = cv.rows * cv.Cout; d.ldA = cv.Cout; d.a_kmajor = 1;
+        d.B = params + ly.w_off; d.strideB = lo.d_pad; d.ldB = ly.ldw; d.b_kmajor = 0;
+        d.C = dcol; d.strideC = cv.rows * cv.ldc; d.ldC = cv.ldc;
+        d.M = (int)cv.rows; d.N = ly.in; d.Kd = cv.Cout; d.batch = lo.K;
+        d.epilogue = EPI_PLAIN;
+        split(c, d);
+        LaunchTimer t(c, KC_GEMM_DX);
+        if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "dX GEMM of convolution %d rejected", l);
+      }
+      // the image this layer read is the layer below's pooled output (its gradient then still
+      // has to pass that pool and ReLU) or its ReLU output (masked here)
+      LaunchTimer t(c, KC_UNFOLD);
+      if (launch_fold3x3(dcol, cv.rows * cv.ldc, cv.ldc,
+                         c->at<float>(below.pool ? below.dpooled : below.dout),
+                         below.pool ? nullptr : c->at<float>(below.out), cv.rows * cv.Cin, lo.K, lo.B,
+                         cv.H, cv.W, cv.Cin, s) != 0)
+        return fail(LSAM_EINVAL, "fold of convolution %d rejected", l);
+    }
+  }
+  (void)X;
+  return LSAM_OK;
+}
+
 // forward + backward of all replicas; weights taken from `wts` (fp32 or bf16 per mode).
 // `second` selects the pass at the perturbed point: its biases are x_b + scale * g1_b, which in
 // fp32 mode sit in the perturbed copy and in bf16 mode are formed in the GEMM epilogue from
 // the fp32 master bias and the first-pass bias gradient (only matrix operands are rounded).
-int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const void* wts,
+// With convolution layers (fp32) the dense layers are l0 = n_conv .. L-1 and read what the
+// convolution stack produced.
+int forward_backward(lsam_ctx* c, const void* X, const int32_t* labels, const void* wts,
                      bool second, bool fuse_norm) {
   const bool want_loss = !second;
   const Layout& lo = c->lo;
-  const int K = lo.K, B = lo.B, L = lo.L;
+  const int K = lo.K, B = lo.B, L = lo.L, l0 = lo.n_conv;
   const int bf = lo.bf16 ? 1 : 0;
   hipStream_t s = c->stream;
+  const float* params = static_cast<const float*>(wts);   // fp32 mode: x or the perturbed copy
+  const void* A0 = X;
+  if (l0 > 0) {
+    int rc = conv_forward(c, static_cast<const float*>(X), params);
+    if (rc != LSAM_OK) return rc;
+    A0 = c->at<char>(lo.act[l0]);
+  }
   // weight matrix l as a GEMM operand: fp32 rows inside the flat vector, or its blocked bf16 copy
   auto wptr = [&](int l) {
     return bf ? (const char*)wts + (size_t)lo.shadow_off[l] * 2
               : (const char*)wts + (size_t)lo.layers[l].w_off * 4;
   };
   const int64_t wstride = bf ? lo.shadow_stride : lo.d_pad;
-  auto width = [&](int l) { return l == 0 ? lo.layers[0].in : lo.layers[l - 1].out; };
+  auto width = [&](int l) { return l < L ? lo.layers[l].in : lo.layers[L - 1].out; };
   auto astride = [&](int l) { return lo.act_elems(width(l), lo.ld[l]); };
-  auto split = [&](GemmDesc& d) {
-    d.splitk_ws = lo.splitk_bytes ? c->at<float>(lo.splitk) : nullptr;
-    d.splitk_bytes = lo.splitk_bytes;
-  };
 
   // A narrow fp32 classifier head is not run as GEMMs: two fused kernels cover its forward
   // pass, the loss, dZ, dX, dW and db.
   const bool head = !bf && head_fits(B, lo.layers[L - 1].out, lo.layers[L - 1].in);
-  const float* params = static_cast<const float*>(wts);   // fp32 mode: x or the perturbed copy
-  for (int l = 0; l < (head ? L - 1 : L); ++l) {
+  for (int l = l0; l < (head ? L - 1 : L); ++l) {
     const Layer& ly = lo.layers[l];
     const bool last = l == L - 1;
     GemmDesc d{};
     d.b32s = bf;
-    d.A = l == 0 ? A0 : c->at<char>(lo.act[l]);
+    d.A = l == l0 ? A0 : c->at<char>(lo.act[l]);
     d.strideA = astride(l); d.ldA = lo.ld[l]; d.a_kmajor = 1; d.cbA = b32s_blocks(ly.in);
     d.B = wptr(l); d.strideB = wstride; d.ldB = ly.ldw; d.b_kmajor = 1; d.cbB = b32s_blocks(ly.in);
     d.C = last ? c->at<char>(lo.logits) : c->at<char>(lo.act[l + 1]);
@@ -426,19 +632,21 @@ int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const v
       d.bias_dir = c->at<float>(lo.g) + ly.b_off;
       d.bias_scale = c->at<float>(lo.scale);
     }
-    split(d);
+    split(c, d);
     LaunchTimer t(c, KC_GEMM_FWD);
     if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "forward GEMM of layer %d rejected", l);
   }
+  // the gradient of the first dense layer's input is needed when convolutions sit below it
+  const bool need_dA0 = l0 > 0;
   if (head) {
     const Layer& ly = lo.layers[L - 1];
-    const float* in_act = L == 1 ? static_cast<const float*>(A0) : c->at<float>(lo.act[L - 1]);
+    const float* in_act = L - 1 == l0 ? static_cast<const float*>(A0) : c->at<float>(lo.act[L - 1]);
     LaunchTimer t(c, KC_HEAD);
     if (launch_head_forward_backward(in_act, params + ly.w_off, params + ly.b_off, lo.d_pad, labels,
                                      c->at<float>(lo.dz[L]), lo.ld[L],
                                      want_loss ? c->at<float>(lo.loss_rows) : nullptr,
-                                     L > 1 ? c->at<float>(lo.dz[L - 1]) : nullptr, K, B, ly.out,
-                                     ly.in, s) != 0)
+                                     (L - 1 > l0 || need_dA0) ? c->at<float>(lo.dz[L - 1]) : nullptr,
+                                     K, B, ly.out, ly.in, s) != 0)
       return fail(LSAM_EHIP, "classifier-head kernel could not be launched");
   } else {
     LaunchTimer t(c, KC_SOFTMAX_CE);
@@ -450,11 +658,11 @@ int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const v
   // first pass: the kernels that write the gradient also leave the partial sums of its squares
   double* ssq = fuse_norm ? c->at<double>(lo.partials) : nullptr;
   int slots = 0;
-  for (int l = L - 1; l >= 0; --l) {
+  for (int l = L - 1; l >= l0; --l) {
     const Layer& ly = lo.layers[l];
     const char* dz = c->at<char>(lo.dz[l + 1]);
     const int ld_dz = lo.ld[l + 1];
-    const void* act = l == 0 ? A0 : (const void*)c->at<char>(lo.act[l]);
+    const void* act = l == l0 ? A0 : (const void*)c->at<char>(lo.act[l]);
     if (head && l == L - 1) {
       LaunchTimer t(c, KC_HEAD);
       const int used = launch_head_weight_grad(
@@ -472,7 +680,7 @@ int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const v
       d.C = g + ly.w_off; d.strideC = lo.d_pad; d.ldC = ly.ldw;
       d.M = ly.out; d.N = ly.in; d.Kd = B; d.batch = K;
       d.in_bf16 = bf; d.out_bf16 = 0; d.epilogue = EPI_PLAIN;
-      split(d);
+      split(c, d);
       if (ssq) { d.sumsq = ssq + slots; d.sumsq_stride = lo.nblk; }
       int used = 0;
       LaunchTimer t(c, KC_GEMM_DW);
@@ -486,7 +694,7 @@ int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const v
                                         lo.nblk, s);
       if (ssq) slots += used;
     }
-    if (l > 0) {
+    if (l > l0 || need_dA0) {
       GemmDesc d{};
       d.b32s = bf;
       d.A = dz; d.strideA = astride(l + 1); d.ldA = ld_dz; d.a_kmajor = 1; d.cbA = b32s_blocks(ly.out);
@@ -495,10 +703,14 @@ int forward_backward(lsam_ctx* c, const void* A0, const int32_t* labels, const v
       d.M = B; d.N = ly.in; d.Kd = ly.out; d.batch = K;
       d.in_bf16 = bf; d.out_bf16 = bf; d.epilogue = EPI_MASK;
       d.mask = act; d.strideMask = astride(l); d.ldMask = lo.ld[l]; d.cbMask = b32s_blocks(ly.in);
-      split(d);
+      split(c, d);
       LaunchTimer t(c, KC_GEMM_DX);
       if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "dX GEMM of layer %d rejected", l);
     }
+  }
+  if (l0 > 0) {
+    int rc = conv_backward(c, static_cast<const float*>(X), params, ssq, &slots);
+    if (rc != LSAM_OK) return rc;
   }
   if (ssq) {
     if (slots > lo.nblk) return fail(LSAM_ESTATE, "gradient-norm partials overran their buffer");

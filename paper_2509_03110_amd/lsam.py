@@ -39,6 +39,8 @@ class lsam_config(C.Structure):
         ("tau_min", C.c_int32), ("tau_max", C.c_int32), ("sched_seed", C.c_uint64),
         ("sched_mode", C.c_int32), ("algorithm", C.c_int32),
         ("noise_scale", C.c_float), ("noise_seed", C.c_uint64),
+        ("n_conv", C.c_int32), ("img_h", C.c_int32), ("img_w", C.c_int32),
+        ("pool_mask", C.c_uint32),
     ]
 
 
@@ -112,7 +114,8 @@ def _check(rc):
 def make_config(K, dims=(), d_raw=0, batch=0, gemm_dtype=GEMM_FP32, rho=0.05, gamma=1e-12,
                 lr=0.1, lr_center=1.0, momentum=0.9, beta=0.9, lambda0=0.5, lambda_abs=-1.0,
                 nesterov=1, tau=None, tau_min=1, tau_max=1, sched_seed=0,
-                sched_mode=SCHED_FIXED, algorithm=ALG_LSAM, noise_scale=0.0, noise_seed=0):
+                sched_mode=SCHED_FIXED, algorithm=ALG_LSAM, noise_scale=0.0, noise_seed=0,
+                n_conv=0, img_h=0, img_w=0, pool_mask=0):
     """Fills an lsam_config; returns (config, keepalive) -- keep `keepalive` referenced while
     the config is in use (it owns the dims / tau arrays the struct points to)."""
     cfg = lsam_config()
@@ -137,6 +140,7 @@ def make_config(K, dims=(), d_raw=0, batch=0, gemm_dtype=GEMM_FP32, rho=0.05, ga
     cfg.sched_seed, cfg.sched_mode = sched_seed, sched_mode
     cfg.algorithm = algorithm
     cfg.noise_scale, cfg.noise_seed = noise_scale, noise_seed
+    cfg.n_conv, cfg.img_h, cfg.img_w, cfg.pool_mask = n_conv, img_h, img_w, pool_mask
     return cfg, keep
 
 
@@ -146,7 +150,8 @@ def config_from_workload(w, **over):
               beta=w.beta, lambda0=w.lambda0, lambda_abs=w.lambda_abs, nesterov=w.nesterov,
               tau=w.tau, tau_min=w.tau_min, tau_max=w.tau_max, sched_seed=w.sched_seed,
               sched_mode=w.sched_mode, algorithm=w.algorithm, noise_scale=w.noise_scale,
-              noise_seed=w.noise_seed)
+              noise_seed=w.noise_seed, n_conv=w.n_conv, img_h=w.img_h, img_w=w.img_w,
+              pool_mask=w.pool_mask)
     kw.update(over)
     return make_config(**kw)
 

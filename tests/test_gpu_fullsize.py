@@ -135,3 +135,37 @@ def test_fp32_large_tile_variants_one_replica():
         assert np.array_equal(eng.lsam_get_buffer(lsam.BUF_GRAD, k), g2), "replica %d differs" % k
     assert np.all(np.isfinite(gl)) and np.all(np.isfinite(eng.lsam_get_norms()))
     eng.close()
+
+
+def test_cnn5_full_size_two_steps_all_replicas():
+    # the paper's own shape (4 workers, batch 128, 32x32x3 images): the oracle still reaches
+    # every replica in seconds, so the whole state is compared.  A replica takes about 5e6 ReLU
+    # and 1.3e6 pooling decisions per pass; a pre-activation (or two values of a pooling
+    # window) within fp32 rounding distance can fall differently in float64, and one such
+    # decision moves one of the 1.3e5 terms of a first-layer weight-gradient row.  Gradients
+    # are therefore held to the looser bound, layer by layer, parameters to the tight one
+    # (tests/test_gpu_parity.py holds the gradients to 1e-5 where every decision is exact).
+    w = workloads.WORKLOADS["cnn5"].scaled(tau=(2, 2, 2, 2))
+    init = workloads.init_params(w)
+    cfg, keep = lsam.config_from_workload(w)
+    eng = lsam.Lsam(cfg, init, device=DEV, keep=keep)
+    ora = oracle_from(w, init)
+    loss = torch.zeros(w.K, dtype=torch.float32, device=DEV)
+    for t in range(2):
+        X, lab = workloads.batch(w, t)
+        eng.lsam_step(torch.from_numpy(X).to(DEV), torch.from_numpy(lab).to(DEV), loss)
+        ol = ora.step(X, lab)
+        assert np.allclose(loss.cpu().numpy(), ol, rtol=1e-5)
+        assert np.allclose(eng.lsam_get_norms(), ora.last_norm, rtol=1e-3)
+        if t == 0:
+            for i in range(w.K):
+                g2 = eng.lsam_get_buffer(lsam.BUF_GRAD, i)
+                for l, (o0, o1, o2) in enumerate(ora.model.offsets):
+                    close_enough(g2[o0:o1], ora.last_g2[i][o0:o1], 2e-2, "dW%d of replica %d" % (l + 1, i))
+                    close_enough(g2[o1:o2], ora.last_g2[i][o1:o2], 2e-2, "db%d of replica %d" % (l + 1, i))
+        assert eng.lsam_sync() == ora.sync()
+        for i in list(range(w.K)) + [-1]:
+            close_enough(eng.lsam_get_params(i), ora.get_params(i), 1e-4 if t == 0 else 1e-3,
+                         "x of replica %d after step %d" % (i, t + 1))
+    assert eng.lsam_get_schedule() == ora.get_schedule()
+    eng.close()

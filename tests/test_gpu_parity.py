@@ -496,3 +496,96 @@ def test_step_can_be_captured_and_replayed_as_a_hip_graph(name):
                 assert np.array_equal(a.lsam_get_buffer(which, i), b.lsam_get_buffer(which, i)), (i, which)
         a.close()
         b.close()
+
+
+# ---- convolutional model -------------------------------------------------------------------------
+CNN_SMALL = workloads.Workload("cnn_small", K=2, dims=(3, 8, 16, 24, 5), batch=6, n_conv=2,
+                               img_h=8, img_w=8, pool_mask=0b11, rho=0.05, lr=0.05, tau=(2, 3),
+                               n_classes=5, data_seed=31)
+
+
+@pytest.mark.parametrize("name,over", [
+    ("pool after both", {}),
+    ("no pool below a convolution", dict(pool_mask=0b10)),
+    ("no pool at all", dict(pool_mask=0, img_h=4, img_w=6)),
+    ("head directly on the image", dict(dims=(3, 8, 16, 10), n_classes=10)),
+    ("wide softmax output", dict(dims=(3, 8, 16, 40, 20), n_classes=20)),
+    ("one convolution, odd input channels", dict(dims=(5, 16, 12, 3), n_conv=1, pool_mask=1,
+                                                 n_classes=3, img_h=6, img_w=10)),
+    ("three convolutions", dict(dims=(1, 8, 8, 16, 32, 4), n_conv=3, pool_mask=0b101, n_classes=4,
+                                batch=9)),
+])
+def test_cnn_matches_oracle(name, over):
+    w = CNN_SMALL.scaled(**over)
+    worst = run_mlp(w, 6, 1e-4, 1e-3)
+    print("cnn %s: worst parameter error %.3e" % (name, worst))
+
+
+def test_cnn_gradients_layer_by_layer():
+    # one step from a common point: both gradients and the norm, every layer on its own
+    w = CNN_SMALL.scaled(K=3, batch=10, tau=(2, 2, 2))
+    g, o = make_pair(w)
+    X, lab = workloads.batch(w, 0)
+    Xd, ld = to_dev(X, lab, w)
+    g.lsam_step(Xd, ld)
+    o.step(X, lab)
+    assert np.allclose(g.lsam_get_norms(), o.last_norm, rtol=1e-4)
+    for i in range(w.K):
+        g2 = g.lsam_get_buffer(lsam.BUF_GRAD, i)
+        for l, (o0, o1, o2) in enumerate(o.model.offsets):
+            close_enough(g2[o0:o1], o.last_g2[i][o0:o1], 1e-3, "dW%d of replica %d" % (l + 1, i))
+            close_enough(g2[o1:o2], o.last_g2[i][o1:o2], 1e-3, "db%d of replica %d" % (l + 1, i))
+        xt = g.lsam_get_buffer(lsam.BUF_PERTURBED, i)
+        assert rel_max(xt, o.last_perturbed[i]) < 1e-5
+    g.close()
+
+
+def test_cnn_exact_decisions_tight_gradients():
+    # Inputs and parameters on coarse binary grids: every pre-activation of the two convolutions
+    # is then a short sum of exactly representable products, the same number in fp32 (in any
+    # summation order) and in float64, so every ReLU mask and every pooling choice -- ties
+    # included, which the grid makes frequent -- is the same on both sides and the gradients
+    # must agree to fp32 rounding.  rho = 0: one pass, at the grid point itself.
+    w = CNN_SMALL.scaled(K=2, dims=(3, 16, 32, 10), n_conv=2, img_h=16, img_w=16, pool_mask=0b11,
+                         batch=64, n_classes=10, rho=0.0, tau=(2, 2))
+    init = workloads.init_params(w).astype(np.float64)
+    off = 0
+    for l, (fi, fo) in enumerate(w.layer_shapes):
+        n = fi * fo + fo
+        if l < 2:                       # multiples of 1/16 (first layer) and 1/32 (second)
+            q = 16.0 * (l + 1)
+            init[off:off + n] = np.round(init[off:off + n] * q) / q
+        off += n
+    X, lab = workloads.batch(w, 0)
+    X = (np.round(X * 2.0) / 2.0).astype(np.float32)          # multiples of 1/2
+    g, o = make_pair(w, init.astype(np.float32))
+    loss_d = torch.zeros(w.K, dtype=torch.float32, device=DEV)
+    g.lsam_step(torch.from_numpy(X).to(DEV), torch.from_numpy(lab).to(DEV), loss_d)
+    ol = o.step(X, lab)
+    assert np.allclose(loss_d.cpu().numpy(), ol, rtol=1e-6)
+    assert np.allclose(g.lsam_get_norms(), o.last_norm, rtol=1e-5)
+    for i in range(w.K):
+        gi = g.lsam_get_buffer(lsam.BUF_GRAD, i)
+        for l, (o0, o1, o2) in enumerate(o.model.offsets):
+            assert rel_max(gi[o0:o1], o.last_g1[i][o0:o1]) < 1e-5, (i, l)
+            assert rel_max(gi[o1:o2], o.last_g1[i][o1:o2]) < 1e-5, (i, l)
+    check_state(g, o, 1e-6, "grid-valued cnn")
+    g.close()
+
+
+def test_cnn_data_parallel_and_langevin():
+    for over in (dict(algorithm=lsam.ALG_DATA_PARALLEL), dict(noise_scale=0.01, noise_seed=5),
+                 dict(rho=0.0)):
+        w = CNN_SMALL.scaled(**over)
+        run_mlp(w, 4, 1e-4, 1e-3)
+
+
+def test_cnn_rejects_what_it_cannot_run():
+    for over, msg in ((dict(dims=(3, 8, 12, 24, 5)), "multiples of 8"),
+                      (dict(img_h=6, img_w=6), "even image sides"),
+                      (dict(gemm_dtype=1), "fp32 only"),
+                      (dict(n_conv=4), "at least one dense layer")):
+        w = CNN_SMALL.scaled(**over)
+        cfg, keep = lsam.config_from_workload(w)
+        assert lsam.lsam_workspace_bytes(cfg) == 0
+        assert msg in lsam.last_error(), lsam.last_error()

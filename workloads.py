@@ -114,6 +114,13 @@ WORKLOADS = {
     "cfg5": Workload("cfg5", K=16, dims=_mlp(3072, 8192, 6, 1000), batch=512, gemm_dtype=1,
                      rho=0.1, tau_min=4, tau_max=16, sched_seed=5, steps=20, data_seed=5,
                      n_classes=1000, batch_pool=4),
+    # the paper's own set-up (Experiments, "Experiment Setup": n = 4 workers, batch 128 each,
+    # communication interval 16, learning rate 0.02 for the small CNN, rho = 0.1) on
+    # SVHN-shaped 32x32x3 inputs: three 3x3 convolutions, each followed by a 2x2 max-pool,
+    # and two dense layers (five weight layers; the paper does not list its CNN-5's layers)
+    "cnn5": Workload("cnn5", K=4, dims=(3, 32, 64, 128, 256, 10), batch=128, n_conv=3, img_h=32,
+                     img_w=32, pool_mask=0b111, rho=0.1, lr=0.02, tau=(16, 16, 16, 16),
+                     steps=20, data_seed=6, n_classes=10, batch_pool=4),
 }
 
 

@@ -60,16 +60,46 @@ def kernel_sources_digest():
     return h.hexdigest()[:16]
 
 
+def layer_rows(w):
+    """Rows of the GEMMs of each layer: B for a dense layer, B * H * W for a convolution."""
+    rows, h, wd = [], w.img_h, w.img_w
+    for l in range(len(w.dims) - 1):
+        if l < w.n_conv:
+            rows.append(w.batch * h * wd)
+            if (w.pool_mask >> l) & 1:
+                h, wd = h // 2, wd // 2
+        else:
+            rows.append(w.batch)
+    return rows
+
+
 def gemm_flops(w):
     """Per all-replica step: flops of the forward, dX and dW GEMM classes (both passes)."""
-    B, K = w.batch, w.K
-    L = len(w.dims) - 1
-    if w.gemm_dtype == 0 and w.dims[-1] <= 16 and w.dims[-2] <= 1024 and B <= 512:
-        L -= 1      # a narrow fp32 classifier head runs as two fused non-MFMA kernels ("head")
-    sw = sum(w.dims[l] * w.dims[l + 1] for l in range(L))
-    sw_dx = sum(w.dims[l] * w.dims[l + 1] for l in range(1, L))
-    return {"gemm_fwd": 2 * 2.0 * B * sw * K, "gemm_dw": 2 * 2.0 * B * sw * K,
-            "gemm_dx": 2 * 2.0 * B * sw_dx * K}
+    K = w.K
+    shapes, rows = list(w.layer_shapes), layer_rows(w)
+    fi, fo = shapes[-1]
+    if w.gemm_dtype == 0 and fo <= 16 and fi <= 1024 and w.batch <= 512:
+        shapes.pop()   # a narrow fp32 classifier head runs as two fused non-MFMA kernels ("head")
+    sw = sum(r * a * b for r, (a, b) in zip(rows, shapes))
+    sw_dx = sum(r * a * b for r, (a, b) in list(zip(rows, shapes))[1:])
+    return {"gemm_fwd": 2 * 2.0 * sw * K, "gemm_dw": 2 * 2.0 * sw * K, "gemm_dx": 2 * 2.0 * sw_dx * K}
+
+
+def conv_bytes(w):
+    """Algorithmic bytes per all-replica step (both passes) of the kernels around the
+    convolution GEMMs: the unfolded image is written once and its gradient read once per pass
+    (plus the image itself), the pool reads its input and writes a quarter of it, its backward
+    pass reads both and writes the full-size gradient."""
+    unfold = pool = 0.0
+    rows = layer_rows(w)
+    for l in range(w.n_conv):
+        cin, cout = w.dims[l], w.dims[l + 1]
+        unfold += rows[l] * (cin + 9 * cin) * 4.0
+        if l > 0:
+            unfold += rows[l] * (9 * cin + cin) * 4.0
+        if (w.pool_mask >> l) & 1:
+            pool += rows[l] * cout * 4.0 * (1.25 + 2.25)
+    return {"unfold_fold": 2 * unfold * w.K, "pool": 2 * pool * w.K} if w.n_conv else {}
 
 
 def stream_bytes(w):
@@ -179,7 +209,7 @@ def main():
     w = workloads.WORKLOADS[args.workload]
     if args.algorithm or args.noise_scale:
         w = w.scaled(algorithm=args.algorithm, noise_scale=args.noise_scale, noise_seed=1)
-    steps = args.steps if args.steps is not None else {"cfg1": 200, "cfg2": 200}.get(w.name, 20)
+    steps = args.steps if args.steps is not None else {"cfg1": 200, "cfg2": 200, "cnn5": 100}.get(w.name, 20)
 
     cfg, keep = lsam.config_from_workload(w)
     eng = lsam.Lsam(cfg, workloads.init_params(w), device=dev, keep=keep)
@@ -220,6 +250,7 @@ def main():
         eng.lsam_timing_enable(False)
         flops = gemm_flops(w) if w.dims else {}
         nbytes = stream_bytes(w)
+        nbytes.update(conv_bytes(w))
         # center update: 8 B/param per due replica (S read, S cleared) + 16 B/param (y and
         # g'_prev read and written), summed over the ticks of this run that had a sync
         first = args.warmup + steps
@@ -258,7 +289,8 @@ def main():
         "vs_baseline": None,
         "dtype": "f32" if (w.gemm_dtype == 0) else "bf16 operands, f32 accumulate and master weights",
         "data": "synthetic",
-        "config": {"workload": w.name, "K": w.K, "dims": list(w.dims), "d": w.d, "batch": w.batch,
+        "config": {"workload": w.name, "K": w.K, "dims": list(w.dims), "n_conv": w.n_conv,
+                   "image": [w.img_h, w.img_w], "d": w.d, "batch": w.batch,
                    "rho": w.rho, "lr": w.lr, "momentum": w.momentum, "algorithm": w.algorithm,
                    "noise_scale": w.noise_scale,
                    "periods": eng.lsam_get_schedule()[0]},

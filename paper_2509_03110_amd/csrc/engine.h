@@ -97,6 +97,13 @@ struct GemmDesc {
   // their squares, in double, to sumsq[k * sumsq_stride + slot], slot = 0 .. slots-1 inside a
   // replica; `slots` comes back through launch_gemm.  Fixed summation order.
   double* sumsq; int64_t sumsq_stride;
+  // fp32 only.  unfold = 1: A is not stored as [M][Kd]; it is the unfolded image of a 3x3
+  // convolution (stride 1, zero rim 1) read straight from the image A points to, [M pixels]
+  // [unfold_C] with M a multiple of unfold_H * unfold_W, Kd = 9 * unfold_C, both operands
+  // k-major.  unfold = 2: the same for B as an m-major operand: B points to the image
+  // [Kd pixels][unfold_C], N = 9 * unfold_C, both operands m-major.  unfold_C must be a
+  // multiple of 32; ldA resp. ldB is then ignored apart from the alignment checks.
+  int unfold, unfold_C, unfold_H, unfold_W;
 };
 // 0 ok, <0 unsupported shape; *sumsq_slots (if non-null) = slots written per replica
 int launch_gemm(const GemmDesc& d, hipStream_t s, int* sumsq_slots = nullptr);
@@ -148,6 +155,10 @@ int launch_unfold3x3(const float* X, int64_t strideX, float* col, int64_t stride
 // set to zero where mask (same shape as dX, may be null) is not positive.  C % 4 == 0.
 int launch_fold3x3(const float* dcol, int64_t strideCol, int ld, float* dX, const float* mask,
                    int64_t strideX, int K, int B, int H, int W, int C, hipStream_t s);
+// Wt[k][c][(u,v,o)] = W[k][o][(2-u,2-v,c)] for K filter banks W [Cout][3][3][Cin] (row pitch ldw,
+// replica stride strideW); Wt is dense, [K][Cin][9 Cout].
+void launch_flip_filters(const float* W, int64_t strideW, int ldw, float* Wt, int K, int Cout, int Cin,
+                         hipStream_t s);
 // Column sums of K contiguous [rows][N] matrices, first stage: partial[k][chunk][n] = sum of
 // the rows of chunk `chunk` (colsum_chunks(rows) chunks of equal height, the last one ragged);
 // returns the chunk count, -1 if N is not a multiple of 4 in 4..1024.  launch_bias_grad over

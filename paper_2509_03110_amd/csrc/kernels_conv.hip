@@ -166,9 +166,10 @@ __global__ __launch_bounds__(kThreads) void maxpool2_backward_kernel(const float
 }
 
 // First stage of the column sums of a tall matrix [rows][N] (N % 4 == 0, N <= 1024): workgroup
-// (chunk, k) adds kColsumRows rows.  Thread = (column word, row group); the row groups are
+// (chunk, k) adds kColsumRows rows (short chunks: the matrices are tall and few, and the
+// launch needs thousands of workgroups to use the memory system).  Thread = (column word, row group); the row groups are
 // combined through LDS in a fixed order.
-constexpr int kColsumRows = 1024;
+constexpr int kColsumRows = 256;
 __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const float* __restrict__ A,
                                                                   float* __restrict__ partial,
                                                                   long long rows, int N, int chunks) {
@@ -191,6 +192,24 @@ __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const float* _
     for (int gq = 1; gq < groups; ++gq) tot += part[gq * words + threadIdx.x];
     *reinterpret_cast<f32x4*>(partial + ((long long)k * chunks + blockIdx.x) * N + 4 * threadIdx.x) = tot;
   }
+}
+
+// Wt[k][c][(u,v,o)] = W[k][o][(2-u, 2-v, c)]: the filter bank as the weight matrix of the
+// convolution that maps the output gradient back to the input (taps mirrored, channels
+// swapped).  One thread per element of Wt, o fastest.
+__global__ __launch_bounds__(kThreads) void flip_filters_kernel(const float* __restrict__ W,
+                                                                long long strideW, int ldw,
+                                                                float* __restrict__ Wt, int Cout,
+                                                                int Cin, long long total) {
+  const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= total) return;
+  const int o = (int)(idx % Cout);
+  long long rest = idx / Cout;
+  const int tap = (int)(rest % 9);
+  rest /= 9;
+  const int c = (int)(rest % Cin);
+  const long long k = rest / Cin;
+  Wt[idx] = W[k * strideW + (long long)o * ldw + (8 - tap) * Cin + c];
 }
 
 unsigned blocks_for(long long total) { return (unsigned)((total + kThreads - 1) / kThreads); }
@@ -216,6 +235,12 @@ int launch_fold3x3(const float* dcol, int64_t strideCol, int ld, float* dX, cons
   if (C % 4 || ld < 9 * C || sh.total <= 0 || sh.total >= (1ll << 31) * kThreads) return -1;
   fold3x3_kernel<<<blocks_for(sh.total), kThreads, 0, s>>>(dcol, dX, mask, sh, strideCol, strideX);
   return 0;
+}
+
+void launch_flip_filters(const float* W, int64_t strideW, int ldw, float* Wt, int K, int Cout, int Cin,
+                         hipStream_t s) {
+  const long long total = (long long)K * Cin * 9 * Cout;
+  flip_filters_kernel<<<blocks_for(total), kThreads, 0, s>>>(W, strideW, ldw, Wt, Cout, Cin, total);
 }
 
 int colsum_chunks(int64_t rows) { return (int)((rows + kColsumRows - 1) / kColsumRows); }

@@ -33,7 +33,17 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
+// An operand that is the unfolded image of a 3x3 convolution (stride 1, zero rim 1) without
+// the unfolded image being stored: element (pixel, tap * C + c) is image[pixel shifted by the
+// tap][c], zero outside the image.  Pixels are rows of [B][H][W][C]; 1/W and 1/H serve the
+// pixel -> (row, column) decode (exact for pixel indices below 2^24).
+struct ConvMap {
+  int C, H, W;
+  float invW, invH;
+};
+
 struct GemmParams {
+  ConvMap cm;
   const char* A; long long strideA; int ldA;
   const char* B; long long strideB; int ldB;
   char* C; long long strideC; int ldC;
@@ -83,7 +93,22 @@ __device__ __forceinline__ int swz(int r) { return r ^ ((r / (2 * UE)) & (UE - 1
 
 // Loads one operand tile (R rows x BKU units of 16 bytes: 16*BKU bytes of k per k-step) from
 // global memory into registers and writes it to LDS laid out as units [BKU][R + 1].
-template <typename T, int R, bool KMAJOR, int BKU>
+__device__ __forceinline__ void pixel_coords(int k, const ConvMap& cm, int& i, int& j) {
+  int q = (int)((float)k * cm.invW);
+  int r = k - q * cm.W;
+  if (r < 0) { r += cm.W; --q; } else if (r >= cm.W) { r -= cm.W; ++q; }
+  j = r;
+  const int q2 = (int)((float)q * cm.invH);
+  int r2 = q - q2 * cm.H;
+  if (r2 < 0) r2 += cm.H; else if (r2 >= cm.H) r2 -= cm.H;
+  i = r2;
+}
+
+// IMPL: 0 = the operand is stored as described by (ld, rows); 1 = k-major operand that is an
+// unfolded image (rows = pixels, k = tap * C + c; C a multiple of the k-step so that a k-step
+// lies inside one tap); 2 = m-major operand that is an unfolded image (k = pixels, columns =
+// tap * C + c).
+template <typename T, int R, bool KMAJOR, int BKU, int IMPL = 0>
 struct TileLoader {
   static constexpr int UE = Op<T>::UE;
   static constexpr int ES = sizeof(T);
@@ -93,6 +118,79 @@ struct TileLoader {
   static constexpr int NREG = KMAJOR ? (NUNITS > 0 ? NUNITS : 1) : NBLK * UE;
   static constexpr int NSTORE = NREG;   // 16-byte LDS writes per thread and k-step
   u32x4 reg[NREG];
+  static constexpr int NPRE = IMPL == 1 ? NUNITS : (IMPL == 2 ? NBLK : 1);
+  int pre_off[IMPL ? NPRE : 1];   // byte offset that does not change from k-step to k-step
+  int pre_i[IMPL ? NPRE : 1];     // IMPL 1: image row of the unit's pixel; 2: row shift of its tap
+  int pre_j[IMPL ? NPRE : 1];     // IMPL 1: image column;                 2: column shift
+
+  // What stays fixed while a tile is computed.  row0/rows: first tile row and row extent
+  // (IMPL 1: pixels; IMPL 2: columns tap * C + c, extent 9 C).
+  __device__ __forceinline__ void prepare(const ConvMap& cm, int row0, int rows, int tid) {
+    static_assert(IMPL == 0 || UE == 4, "implicit unfolding is built for fp32 operands");
+    if constexpr (IMPL == 1) {
+#pragma unroll
+      for (int j = 0; j < NUNITS; ++j) {
+        const int u = tid + kThreads * j;
+        const int r = row0 + u / BKU;
+        if (r < rows) {
+          pixel_coords(r, cm, pre_i[j], pre_j[j]);
+          pre_off[j] = (r * cm.C + (u % BKU) * UE) * ES;
+        } else {
+          pre_i[j] = pre_j[j] = 1 << 20;   // fails every bounds test
+          pre_off[j] = 0;
+        }
+      }
+    } else if constexpr (IMPL == 2) {
+#pragma unroll
+      for (int j = 0; j < NBLK; ++j) {
+        const int b = tid + kThreads * j;
+        const int m = row0 + (b % (R / UE)) * UE;
+        if (b < NBLK_TOTAL && m < rows) {
+          const int tap = m / cm.C, c = m - tap * cm.C;
+          pre_i[j] = tap / 3 - 1;
+          pre_j[j] = tap % 3 - 1;
+          pre_off[j] = ((pre_i[j] * cm.W + pre_j[j]) * cm.C + c) * ES;
+        } else {
+          pre_i[j] = pre_j[j] = 1 << 20;
+          pre_off[j] = 0;
+        }
+      }
+    }
+  }
+
+  // k0u: first k-unit of this step; kd: true k extent (IMPL 1: 9 C; IMPL 2: pixels).
+  __device__ __forceinline__ void load_unfolded(__amdgpu_buffer_rsrc_t rsrc, const ConvMap& cm, int k0u,
+                                                int kd, int tid) {
+    if constexpr (IMPL == 1) {
+      const int e0 = k0u * UE;
+      const int tap = e0 / cm.C, c0 = e0 - tap * cm.C;
+      const int du = tap / 3 - 1, dv = tap % 3 - 1;
+      const int shift = ((du * cm.W + dv) * cm.C + c0) * ES;
+#pragma unroll
+      for (int j = 0; j < NUNITS; ++j) {
+        const bool ok = e0 < kd && (unsigned)(pre_i[j] + du) < (unsigned)cm.H &&
+                        (unsigned)(pre_j[j] + dv) < (unsigned)cm.W;
+        reg[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, ok ? (unsigned)(pre_off[j] + shift) : kOob,
+                                                       0, 0);
+      }
+    } else if constexpr (IMPL == 2) {
+#pragma unroll
+      for (int j = 0; j < NBLK; ++j) {
+        const int b = tid + kThreads * j;
+        const int kb = b / (R / UE);
+#pragma unroll
+        for (int i = 0; i < UE; ++i) {
+          const int k = (k0u + kb) * UE + i;
+          int pi, pj;
+          pixel_coords(k, cm, pi, pj);
+          const bool ok = k < kd && (unsigned)(pi + pre_i[j]) < (unsigned)cm.H &&
+                          (unsigned)(pj + pre_j[j]) < (unsigned)cm.W;
+          reg[j * UE + i] = __builtin_amdgcn_raw_buffer_load_b128(
+              rsrc, ok ? (unsigned)(k * cm.C * ES + pre_off[j]) : kOob, 0, 0);
+        }
+      }
+    }
+  }
 
   // rsrc covers the operand of this replica: rows*ld elements (k-major) or kd*ld (m-major),
   // so a row index past the end is out of range by construction.  row0: first tile row;
@@ -228,8 +326,11 @@ struct Pipeline {
 __device__ __forceinline__ float widen(float v) { return v; }
 __device__ __forceinline__ float widen(__bf16 v) { return static_cast<float>(v); }
 
-template <typename T, typename TC, int BM, int BN, int BKU, bool A_KMAJOR, bool B_KMAJOR, int OCC>
+// CONV: 0 = both operands stored; 1 = A is an unfolded image (k-major); 2 = B is one (m-major).
+template <typename T, typename TC, int BM, int BN, int BKU, bool A_KMAJOR, bool B_KMAJOR, int OCC,
+          int CONV = 0>
 __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
+  static_assert(CONV == 0 || (CONV == 1 && A_KMAJOR) || (CONV == 2 && !B_KMAJOR), "operand layout");
   constexpr int UE = Op<T>::UE;
   constexpr int TM = BM / 64, TN = BN / 64;
   constexpr int A_UNITS = BKU * (BM + 1), B_UNITS = BKU * (BN + 1);
@@ -262,8 +363,10 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
 
   const T* A = reinterpret_cast<const T*>(p.A) + (long long)bat * p.strideA;
   const T* B = reinterpret_cast<const T*>(p.B) + (long long)bat * p.strideB;
-  const unsigned bytesA = (unsigned)((A_KMAJOR ? p.M : p.Kd) * p.ldA) * sizeof(T);
-  const unsigned bytesB = (unsigned)((B_KMAJOR ? p.N : p.Kd) * p.ldB) * sizeof(T);
+  const unsigned bytesA = CONV == 1 ? (unsigned)(p.M * p.cm.C) * sizeof(T)
+                                    : (unsigned)((A_KMAJOR ? p.M : p.Kd) * p.ldA) * sizeof(T);
+  const unsigned bytesB = CONV == 2 ? (unsigned)(p.Kd * p.cm.C) * sizeof(T)
+                                    : (unsigned)((B_KMAJOR ? p.N : p.Kd) * p.ldB) * sizeof(T);
   const __amdgpu_buffer_rsrc_t rsrcA = make_rsrc(A, bytesA);
   const __amdgpu_buffer_rsrc_t rsrcB = make_rsrc(B, bytesB);
 
@@ -280,8 +383,18 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  TileLoader<T, BM, A_KMAJOR, BKU> la;
-  TileLoader<T, BN, B_KMAJOR, BKU> lb;
+  TileLoader<T, BM, A_KMAJOR, BKU, CONV == 1 ? 1 : 0> la;
+  TileLoader<T, BN, B_KMAJOR, BKU, CONV == 2 ? 2 : 0> lb;
+  if constexpr (CONV == 1) la.prepare(p.cm, m0, p.M, tid);
+  if constexpr (CONV == 2) lb.prepare(p.cm, n0, p.N, tid);
+  auto load_a = [&](int k0u) {
+    if constexpr (CONV == 1) la.load_unfolded(rsrcA, p.cm, k0u, p.Kd, tid);
+    else la.load(rsrcA, p.ldA, m0, p.M, k0u, p.Kd, tid);
+  };
+  auto load_b = [&](int k0u) {
+    if constexpr (CONV == 2) lb.load_unfolded(rsrcB, p.cm, k0u, p.Kd, tid);
+    else lb.load(rsrcB, p.ldB, n0, p.N, k0u, p.Kd, tid);
+  };
   constexpr int NKC = BKU / 2;                        // k-chunks (one MFMA depth each) per k-step
   constexpr int ND = TM + TN;                         // LDS fragment reads per k-chunk
   constexpr int NM = TM * TN * (UE == 4 ? 4 : 1);     // MFMAs per k-chunk
@@ -336,12 +449,12 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
   //                    issue of the global loads of tile ks+2.
   // The scheduling hints fix that interleaving; left alone, the compiler sinks every LDS read
   // next to its first use and the single wavefront per SIMD stalls on each one.
-  la.load(rsrcA, p.ldA, m0, p.M, kb, p.Kd, tid);
-  lb.load(rsrcB, p.ldB, n0, p.N, kb, p.Kd, tid);
+  load_a(kb);
+  load_b(kb);
   la.store(lds, tid);
   lb.store(lds + A_UNITS, tid);
-  la.load(rsrcA, p.ldA, m0, p.M, kb + BKU, p.Kd, tid);      // past the end: reads as zeros
-  lb.load(rsrcB, p.ldB, n0, p.N, kb + BKU, p.Kd, tid);
+  load_a(kb + BKU);      // past the end: reads as zeros
+  load_b(kb + BKU);
   __syncthreads();
   read_frags(lds, 0, 0);
 
@@ -363,8 +476,8 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
     __syncthreads();
     read_frags(nxt, 0, 0);
     mfma_chunk((NKC - 1) & 1);
-    la.load(rsrcA, p.ldA, m0, p.M, kb + (ks + 2) * BKU, p.Kd, tid);
-    lb.load(rsrcB, p.ldB, n0, p.N, kb + (ks + 2) * BKU, p.Kd, tid);
+    load_a(kb + (ks + 2) * BKU);
+    load_b(kb + (ks + 2) * BKU);
     Pipeline<ND, NV, 0x020, NM>::run();
   }
   {
@@ -470,47 +583,70 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
   }
 }
 
-// Sums the split-K partials in split order and applies the epilogue the GEMM skipped.
-// Grid: x over the M * ldP/4 vector words of one replica, y = replica.
-__global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(GemmParams p) {
+// Sums the split-K partials in a fixed order and applies the epilogue the GEMM skipped.
+// Grid: x over groups of 256 of the M * ldP/4 vector words of one replica, y = replica.  A
+// workgroup is LANES x 256 threads; with LANES = 4, thread (lane group q, word) adds the partials q, q+4, q+8, ...
+// of its word (four chains of loads in flight instead of one: with up to 128 partials the
+// single chain was the whole run time), the four sums are combined through LDS as
+// ((q0 + q1) + (q2 + q3)), and lane group 0 finishes the word.
+// (With fewer than 8 partials one chain is short enough: LANES = 1, a workgroup of 256.)
+template <int LANES>
+__global__ __launch_bounds__(kThreads * LANES) void splitk_reduce_kernel(GemmParams p) {
+  constexpr int kReduceLanes = LANES;
+  __shared__ f32x4 part[LANES > 1 ? LANES - 1 : 1][kThreads];
+  __shared__ double wsum[kThreads / 64];
   const int n4 = p.ldP / 4;
   const long long per_rep = (long long)p.M * n4;
-  const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+  const int word = threadIdx.x % kThreads, q = threadIdx.x / kThreads;
+  const long long idx = (long long)blockIdx.x * kThreads + word;
   const int bat = blockIdx.y;
+  const bool live = idx < per_rep;
+  const int c = live ? (int)(idx % n4) * 4 : 0;
+  const int m = live ? (int)(idx / n4) : 0;
+  const long long row = (long long)bat * p.M + m;
+  f32x4 v = {0.f, 0.f, 0.f, 0.f};
+  if (live && c < p.N)
+    for (int s = q; s < p.splits; s += kReduceLanes)
+      v += *reinterpret_cast<const f32x4*>(p.partial + (long long)s * p.strideSplit + row * p.ldP + c);
+  if constexpr (LANES > 1) {
+    if (q > 0) part[q - 1][word] = v;
+    __syncthreads();
+  }
   float ssq = 0.f;
-  if (idx < per_rep) {
-    const int c = (int)(idx % n4) * 4;
-    const int m = (int)(idx / n4);
-    const long long row = (long long)bat * p.M + m;
-    if (c < p.N) {
-      f32x4 v = {0.f, 0.f, 0.f, 0.f};
-      for (int s = 0; s < p.splits; ++s)
-        v += *reinterpret_cast<const f32x4*>(p.partial + (long long)s * p.strideSplit + row * p.ldP + c);
-      const bool has_bias = p.epilogue == EPI_BIAS || p.epilogue == EPI_BIAS_RELU;
-      float* C = reinterpret_cast<float*>(p.C) + (long long)bat * p.strideC + (long long)m * p.ldC;
-      const float* mask = p.mask ? reinterpret_cast<const float*>(p.mask) +
-                                       (long long)bat * p.strideMask + (long long)m * p.ldMask
-                                 : nullptr;
+  if (q == 0 && live && c < p.N) {
+    if constexpr (LANES == 4) v = (v + part[0][word]) + (part[1][word] + part[2][word]);
+    const bool has_bias = p.epilogue == EPI_BIAS || p.epilogue == EPI_BIAS_RELU;
+    float* C = reinterpret_cast<float*>(p.C) + (long long)bat * p.strideC + (long long)m * p.ldC;
+    const float* mask = p.mask ? reinterpret_cast<const float*>(p.mask) +
+                                     (long long)bat * p.strideMask + (long long)m * p.ldMask
+                               : nullptr;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int n = c + r;
-        if (n >= p.N) break;
-        float o = v[r];
-        if (has_bias) {
-          float bv = p.bias[(long long)bat * p.strideBias + n];
-          if (p.bias_dir) bv = bv + p.bias_scale[bat] * p.bias_dir[(long long)bat * p.strideBias + n];
-          o += bv;
-        }
-        if (p.epilogue == EPI_BIAS_RELU) o = o > 0.f ? o : 0.f;
-        if (p.epilogue == EPI_MASK && !(mask[n] > 0.f)) o = 0.f;
-        C[n] = o;
-        ssq += o * o;
+    for (int r = 0; r < 4; ++r) {
+      const int n = c + r;
+      if (n >= p.N) break;
+      float o = v[r];
+      if (has_bias) {
+        float bv = p.bias[(long long)bat * p.strideBias + n];
+        if (p.bias_dir) bv = bv + p.bias_scale[bat] * p.bias_dir[(long long)bat * p.strideBias + n];
+        o += bv;
       }
+      if (p.epilogue == EPI_BIAS_RELU) o = o > 0.f ? o : 0.f;
+      if (p.epilogue == EPI_MASK && !(mask[n] > 0.f)) o = 0.f;
+      C[n] = o;
+      ssq += o * o;
     }
   }
   if (p.sumsq != nullptr) {
-    const double tot = workgroup_sum((double)ssq);
-    if (threadIdx.x == 0) p.sumsq[(long long)bat * p.strideSumsq + blockIdx.x] = tot;
+    // lane group 0 is the first four wavefronts: lanes by xor-shuffle, then the four in turn
+    if (q == 0) {
+      double t = (double)ssq;
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) t += __shfl_xor(t, off, 64);
+      if ((word & 63) == 0) wsum[word >> 6] = t;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0)
+      p.sumsq[(long long)bat * p.strideSumsq + blockIdx.x] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
   }
 }
 
@@ -537,6 +673,12 @@ Plan make_plan(const GemmDesc& d, int tile_override) {
   else if (tile_override == 2) { pl.bm = 256; pl.bn = 128; pl.bku = 4; }
   else if (tile_override == 4) { pl.bm = 128; pl.bn = 128; }
   else if (tile_override == 5) { pl.bm = 64; pl.bn = 64; }
+  else if (d.unfold) {      // implicit unfolding is instantiated for the two smaller tiles
+    // (for the weight gradients, few output tiles and a split contraction, the smaller tile
+    // measured faster: 71 us against 84 us at M = 128, N = 576, 8192 pixels, 4 replicas;
+    // k-steps twice as deep changed nothing)
+    if (d.M >= 128 && d.N >= 128 && tiles(128, 128) >= 256) { pl.bm = 128; pl.bn = 128; }
+  }
   else if (kk && d.M >= 256 && d.N >= 128 && tiles(256, 128) >= 512) { pl.bm = 256; pl.bn = 128; pl.bku = 4; }
   else if (d.M >= 256 && d.N >= 256 && tiles(256, 256) >= 512) { pl.bm = 256; pl.bn = 256; }
   else if (d.M >= 128 && d.N >= 128 && tiles(128, 128) >= 256) { pl.bm = 128; pl.bn = 128; }
@@ -544,13 +686,18 @@ Plan make_plan(const GemmDesc& d, int tile_override) {
   const int ksteps = (d.Kd + pl.bku * ue - 1) / (pl.bku * ue);
   pl.steps_per_split = ksteps;
   const long long nt = tiles(pl.bm, pl.bn);
-  if (!d.out_bf16 && !d.in_bf16 && nt < 512 && ksteps >= 8) {
-    int want = (int)((512 + nt - 1) / nt);
+  // 512 workgroups measured best for the dense layers' shapes; the convolutions' weight
+  // gradients (tiny outputs, contractions of 10^4..10^5) want more of the small tiles in
+  // flight: a wavefront of a 64x64 tile has little work per k-step to cover the latency of
+  // its next loads with
+  const int target = (pl.bm == 64 && d.Kd >= 8192) ? 2048 : 512;
+  if (!d.out_bf16 && !d.in_bf16 && nt < target && ksteps >= 8) {
+    int want = (int)((target + nt - 1) / nt);
     int cap = ksteps / 4;
     int sp = want < cap ? want : cap;
     // up to 16 splits; more only for the very long contractions of convolution weight
     // gradients (batch x image rows), whose outputs are a handful of tiles
-    const int most = ksteps >= 4096 ? 64 : (ksteps >= 1024 ? 32 : 16);
+    const int most = d.Kd >= 131072 ? 128 : (d.Kd >= 32768 ? 64 : (d.Kd >= 8192 ? 32 : 16));
     if (sp > most) sp = most;
     if (sp > 1) {
       pl.steps_per_split = (ksteps + sp - 1) / sp;
@@ -562,7 +709,7 @@ Plan make_plan(const GemmDesc& d, int tile_override) {
   return pl;
 }
 
-template <typename T, typename TC, int BM, int BN, int BKU, bool AK, bool BK_>
+template <typename T, typename TC, int BM, int BN, int BKU, bool AK, bool BK_, int CONV = 0>
 int launch_one(const GemmParams& p0, hipStream_t s, int* sumsq_slots) {
   constexpr int OCC = (BM * BN >= 256 * 256) ? 1 : 2;
   GemmParams p = p0;
@@ -573,7 +720,7 @@ int launch_one(const GemmParams& p0, hipStream_t s, int* sumsq_slots) {
   const size_t loop_smem = (size_t)2 * BKU * ((BM + 1) + (BN + 1)) * 16;
   const size_t epi_smem = (size_t)64 * (BN + 4) * 4;
   const size_t smem = loop_smem > epi_smem ? loop_smem : epi_smem;
-  auto kern = gemm_kernel<T, TC, BM, BN, BKU, AK, BK_, OCC>;
+  auto kern = gemm_kernel<T, TC, BM, BN, BKU, AK, BK_, OCC, CONV>;
   static std::atomic<bool> attr_set{false};   // per instantiation; setting it twice is harmless
   if (!attr_set.load(std::memory_order_relaxed)) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -586,7 +733,10 @@ int launch_one(const GemmParams& p0, hipStream_t s, int* sumsq_slots) {
   if (p.splits > 1) {
     const long long per_rep = (long long)p.M * (p.ldP / 4);
     slots = (int)((per_rep + kThreads - 1) / kThreads);
-    splitk_reduce_kernel<<<dim3((unsigned)slots, (unsigned)p.batch), kThreads, 0, s>>>(p);
+    if (p.splits >= 8)
+      splitk_reduce_kernel<4><<<dim3((unsigned)slots, (unsigned)p.batch), kThreads * 4, 0, s>>>(p);
+    else
+      splitk_reduce_kernel<1><<<dim3((unsigned)slots, (unsigned)p.batch), kThreads, 0, s>>>(p);
   }
   if (sumsq_slots) *sumsq_slots = slots;
   return 0;
@@ -602,6 +752,16 @@ int launch_tiled(const GemmParams& p, const Plan& pl, hipStream_t s, int* slots)
 
 template <typename T, typename TC>
 int launch_layout(const GemmDesc& d, const GemmParams& p, const Plan& pl, hipStream_t s, int* slots) {
+  if (d.unfold == 1) {
+    if (!(d.a_kmajor && d.b_kmajor)) return -1;
+    if (pl.bm == 128) return launch_one<T, TC, 128, 128, 8, true, true, 1>(p, s, slots);
+    return launch_one<T, TC, 64, 64, 8, true, true, 1>(p, s, slots);
+  }
+  if (d.unfold == 2) {
+    if (d.a_kmajor || d.b_kmajor) return -1;
+    if (pl.bm == 128) return launch_one<T, TC, 128, 128, 8, false, false, 2>(p, s, slots);
+    return launch_one<T, TC, 64, 64, 8, false, false, 2>(p, s, slots);
+  }
   if (d.a_kmajor && d.b_kmajor) return launch_tiled<T, TC, true, true>(p, pl, s, slots);
   if (d.a_kmajor && !d.b_kmajor) return launch_tiled<T, TC, true, false>(p, pl, s, slots);
   if (!d.a_kmajor && !d.b_kmajor) return launch_tiled<T, TC, false, false>(p, pl, s, slots);
@@ -641,6 +801,17 @@ int launch_gemm(const GemmDesc& d, hipStream_t s, int* sumsq_slots) {
   p.partial = nullptr; p.strideSplit = 0; p.ldP = 0; p.splits = 1; p.steps_per_split = 1 << 30;
   p.sumsq = d.sumsq; p.strideSumsq = d.sumsq_stride;
   if (d.M <= 0 || d.N <= 0 || d.Kd <= 0 || d.batch <= 0) return -1;
+  p.cm = ConvMap{0, 1, 1, 1.f, 1.f};
+  if (d.unfold) {
+    // a k-step (32 floats) must lie inside one tap; pixel indices must be exact in fp32; the
+    // contraction (mode 1) or the column extent (mode 2) is the unfolded width 9 C
+    const long long pixels = d.unfold == 1 ? d.M : d.Kd;
+    if (d.in_bf16 || d.unfold_C % 32 || d.unfold_H < 1 || d.unfold_W < 1 ||
+        pixels % ((long long)d.unfold_H * d.unfold_W) || pixels >= (1 << 24) ||
+        pixels * d.unfold_C * 4 >= 0x7FFFFFF0LL || (d.unfold == 1 ? d.Kd : d.N) != 9 * d.unfold_C)
+      return -1;
+    p.cm = ConvMap{d.unfold_C, d.unfold_H, d.unfold_W, 1.f / (float)d.unfold_W, 1.f / (float)d.unfold_H};
+  }
   // 16-byte units: pitches must be multiples of 8 elements and bases 16-byte aligned.
   if ((d.ldA % 8) || (d.ldB % 8) || (d.ldC % 8) || ((uintptr_t)d.A & 15) ||
       ((uintptr_t)d.B & 15) || ((uintptr_t)d.C & 15))

@@ -105,7 +105,12 @@ struct ConvLayer {
   int H, W, Cin, Cout, pool;
   int64_t rows;        // B H W: rows of the unfolded image and of the layer's output
   int ldc;             // pitch of the unfolded image, 9 Cin rounded up to 8
-  size_t col, out, pooled, dout, dpooled;   // workspace offsets ([K] contiguous replicas each)
+  // The GEMM kernels can read an unfolded image straight from the image when its channel
+  // count is a multiple of 32: `direct_in` for the layer's input (forward and dW), `direct_dx`
+  // for its output gradient (dX, with the mirrored filters `wt`).  Otherwise the unfolded
+  // image (`col`) resp. its gradient (the shared `dcol`) is stored.
+  bool direct_in, direct_dx;
+  size_t col, out, pooled, dout, dpooled, wt;   // workspace offsets ([K] contiguous replicas each)
 };
 
 struct Layout {
@@ -316,14 +321,18 @@ void build_layout(const lsam_config& c, Layout& lo) {
     for (int l = 0; l < lo.n_conv; ++l) {
       ConvLayer& cv = lo.conv[l];
       const size_t full = (size_t)lo.K * cv.rows * cv.Cout * 4;
-      cv.col = take(cur, (size_t)lo.K * cv.rows * cv.ldc * 4);
+      const bool small = cv.rows < (1 << 24);      // pixel indices exact in fp32
+      cv.direct_in = small && cv.Cin % 32 == 0;
+      cv.direct_dx = small && l > 0 && cv.Cout % 32 == 0;
+      if (!cv.direct_in) cv.col = take(cur, (size_t)lo.K * cv.rows * cv.ldc * 4);
+      if (cv.direct_dx) cv.wt = take(cur, (size_t)lo.K * cv.Cin * 9 * cv.Cout * 4);
       cv.out = take(cur, full);
       cv.dout = take(cur, full);
       if (cv.pool) {
         cv.pooled = take(cur, full / 4);
         cv.dpooled = take(cur, full / 4);
       }
-      if (l > 0) dcol_bytes = std::max(dcol_bytes, (size_t)lo.K * cv.rows * cv.ldc * 4);
+      if (l > 0 && !cv.direct_dx) dcol_bytes = std::max(dcol_bytes, (size_t)lo.K * cv.rows * cv.ldc * 4);
     }
     if (dcol_bytes) lo.dcol = take(cur, dcol_bytes);
     if (lo.n_conv > 0) {
@@ -350,15 +359,20 @@ void build_layout(const lsam_config& c, Layout& lo) {
       if (lo.bf16) break;      // split-K serves the fp32 kernel only
       GemmDesc d{};
       d.batch = lo.K; d.in_bf16 = lo.bf16;
-      const int rows = l < lo.n_conv ? (int)lo.conv[l].rows : lo.B;
+      const ConvLayer* cv = l < lo.n_conv ? &lo.conv[l] : nullptr;
+      const int rows = cv ? (int)cv->rows : lo.B;
       d.M = rows; d.N = ly.out; d.Kd = ly.in; d.a_kmajor = 1; d.b_kmajor = 1;     // forward
       d.out_bf16 = lo.bf16 && l + 1 < lo.L;
+      d.unfold = cv && cv->direct_in ? 1 : 0;
       need = std::max(need, gemm_splitk_bytes(d));
       d.M = rows; d.N = ly.in; d.Kd = ly.out; d.a_kmajor = 1; d.b_kmajor = 0;     // dX
       d.out_bf16 = lo.bf16;
+      d.unfold = 0;
+      if (cv && cv->direct_dx) { d.N = cv->Cin; d.Kd = 9 * cv->Cout; d.b_kmajor = 1; d.unfold = 1; }
       if (l > 0) need = std::max(need, gemm_splitk_bytes(d));
       d.M = ly.out; d.N = ly.in; d.Kd = rows; d.a_kmajor = 0; d.b_kmajor = 0;     // dW
       d.out_bf16 = 0;
+      d.unfold = cv && cv->direct_in ? 2 : 0;
       need = std::max(need, gemm_splitk_bytes(d));
     }
     lo.splitk_bytes = need;
@@ -482,8 +496,8 @@ int conv_forward(lsam_ctx* c, const float* X, const float* params) {
   for (int l = 0; l < lo.n_conv; ++l) {
     const ConvLayer& cv = lo.conv[l];
     const Layer& ly = lo.layers[l];
-    float* col = c->at<float>(cv.col);
-    {
+    float* col = cv.direct_in ? nullptr : c->at<float>(cv.col);
+    if (!cv.direct_in) {
       LaunchTimer t(c, KC_UNFOLD);
       if (launch_unfold3x3(in, cv.rows * cv.Cin, col, cv.rows * cv.ldc, cv.ldc, lo.K, lo.B, cv.H,
                            cv.W, cv.Cin, s) != 0)
@@ -492,6 +506,10 @@ int conv_forward(lsam_ctx* c, const float* X, const float* params) {
     {
       GemmDesc d{};
       d.A = col; d.strideA = cv.rows * cv.ldc; d.ldA = cv.ldc; d.a_kmajor = 1;
+      if (cv.direct_in) {
+        d.A = in; d.strideA = cv.rows * cv.Cin; d.ldA = cv.Cin;
+        d.unfold = 1; d.unfold_C = cv.Cin; d.unfold_H = cv.H; d.unfold_W = cv.W;
+      }
       d.B = params + ly.w_off; d.strideB = lo.d_pad; d.ldB = ly.ldw; d.b_kmajor = 1;
       d.C = c->at<float>(cv.out); d.strideC = cv.rows * cv.Cout; d.ldC = cv.Cout;
       d.M = (int)cv.rows; d.N = cv.Cout; d.Kd = ly.in; d.batch = lo.K;
@@ -533,6 +551,11 @@ int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq,
       GemmDesc d{};
       d.A = dout; d.strideA = cv.rows * cv.Cout; d.ldA = cv.Cout; d.a_kmajor = 0;
       d.B = c->at<float>(cv.col); d.strideB = cv.rows * cv.ldc; d.ldB = cv.ldc; d.b_kmajor = 0;
+      if (cv.direct_in) {
+        d.B = l == 0 ? X : c->at<float>(lo.conv[l - 1].pool ? lo.conv[l - 1].pooled : lo.conv[l - 1].out);
+        d.strideB = cv.rows * cv.Cin; d.ldB = cv.Cin;
+        d.unfold = 2; d.unfold_C = cv.Cin; d.unfold_H = cv.H; d.unfold_W = cv.W;
+      }
       d.C = g + ly.w_off; d.strideC = lo.d_pad; d.ldC = ly.ldw;
       d.M = cv.Cout; d.N = ly.in; d.Kd = (int)cv.rows; d.batch = lo.K;
       d.epilogue = EPI_PLAIN;
@@ -552,7 +575,31 @@ int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq,
                                         lo.K, chunks, cv.Cout, ssq ? ssq + *slots : nullptr, lo.nblk, s);
       if (ssq) *slots += used;
     }
-    if (l > 0) {
+    if (l > 0 && cv.direct_dx) {
+      // dX as a convolution of the output gradient with the mirrored filters, written straight
+      // into the gradient of the image this layer read (masked by the ReLU output it came
+      // from when no pool sits in between; a pool's backward pass applies the mask itself)
+      const ConvLayer& below = lo.conv[l - 1];
+      float* wt = c->at<float>(cv.wt);
+      {
+        LaunchTimer t(c, KC_MISC);
+        launch_flip_filters(params + ly.w_off, lo.d_pad, ly.ldw, wt, lo.K, cv.Cout, cv.Cin, s);
+      }
+      GemmDesc d{};
+      d.A = dout; d.strideA = cv.rows * cv.Cout; d.ldA = cv.Cout; d.a_kmajor = 1;
+      d.unfold = 1; d.unfold_C = cv.Cout; d.unfold_H = cv.H; d.unfold_W = cv.W;
+      d.B = wt; d.strideB = (int64_t)cv.Cin * 9 * cv.Cout; d.ldB = 9 * cv.Cout; d.b_kmajor = 1;
+      d.C = c->at<float>(below.pool ? below.dpooled : below.dout);
+      d.strideC = cv.rows * cv.Cin; d.ldC = cv.Cin;
+      d.M = (int)cv.rows; d.N = cv.Cin; d.Kd = 9 * cv.Cout; d.batch = lo.K;
+      d.epilogue = below.pool ? EPI_PLAIN : EPI_MASK;
+      if (!below.pool) {
+        d.mask = c->at<float>(below.out); d.strideMask = cv.rows * cv.Cin; d.ldMask = cv.Cin;
+      }
+      split(c, d);
+      LaunchTimer t(c, KC_GEMM_DX);
+      if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "dX GEMM of convolution %d rejected", l);
+    } else if (l > 0) {
       const ConvLayer& below = lo.conv[l - 1];
       float* dcol = c->at<float>(lo.dcol);
       {
@@ -576,7 +623,6 @@ int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq,
         return fail(LSAM_EINVAL, "fold of convolution %d rejected", l);
     }
   }
-  (void)X;
   return LSAM_OK;
 }
 

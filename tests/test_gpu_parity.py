@@ -514,6 +514,12 @@ CNN_SMALL = workloads.Workload("cnn_small", K=2, dims=(3, 8, 16, 24, 5), batch=6
                                                  n_classes=3, img_h=6, img_w=10)),
     ("three convolutions", dict(dims=(1, 8, 8, 16, 32, 4), n_conv=3, pool_mask=0b101, n_classes=4,
                                 batch=9)),
+    # channel counts that are multiples of 32: the GEMMs then read the unfolded images straight
+    # from the images (forward, dW and dX), with and without a pool below the layer
+    ("unfolding inside the GEMM", dict(dims=(3, 32, 32, 64, 10), n_conv=3, pool_mask=0b101,
+                                       n_classes=10, batch=5)),
+    ("unfolding inside the GEMM, sides not powers of two", dict(
+        dims=(4, 32, 64, 12, 6), n_conv=2, pool_mask=0b10, img_h=6, img_w=10, n_classes=6, batch=7)),
 ])
 def test_cnn_matches_oracle(name, over):
     w = CNN_SMALL.scaled(**over)
@@ -546,7 +552,7 @@ def test_cnn_exact_decisions_tight_gradients():
     # summation order) and in float64, so every ReLU mask and every pooling choice -- ties
     # included, which the grid makes frequent -- is the same on both sides and the gradients
     # must agree to fp32 rounding.  rho = 0: one pass, at the grid point itself.
-    w = CNN_SMALL.scaled(K=2, dims=(3, 16, 32, 10), n_conv=2, img_h=16, img_w=16, pool_mask=0b11,
+    w = CNN_SMALL.scaled(K=2, dims=(3, 32, 32, 10), n_conv=2, img_h=16, img_w=16, pool_mask=0b11,
                          batch=64, n_classes=10, rho=0.0, tau=(2, 2))
     init = workloads.init_params(w).astype(np.float64)
     off = 0

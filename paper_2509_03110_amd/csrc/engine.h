@@ -155,6 +155,23 @@ int launch_unfold3x3(const float* X, int64_t strideX, float* col, int64_t stride
 // set to zero where mask (same shape as dX, may be null) is not positive.  C % 4 == 0.
 int launch_fold3x3(const float* dcol, int64_t strideCol, int ld, float* dX, const float* mask,
                    int64_t strideX, int K, int B, int H, int W, int C, hipStream_t s);
+// A first convolution layer with C = 1..3 input channels and a multiple of 32 output channels
+// (first_conv_fits) has kernels of its own that gather the image straight into the MFMA
+// operands.  Forward: out[k][p][o] = relu(b[o] + conv), parameters taken from
+// params + k * strideParams at w_off (row pitch ldw) and b_off.  Weight gradient: dW and db
+// into grad + k * strideParams at the same offsets, through `partial`
+// ([K][first_conv_chunks(rows)][Cout][32] floats of scratch), plus, if sumsq is non-null, the
+// sums of their squares in sumsq[k * sumsq_stride + slot]; returns the slots written per
+// replica (Cout / 2), or -1.
+bool first_conv_fits(int C, int Cout, int64_t rows);
+int first_conv_chunks(int64_t rows);
+int launch_first_conv_forward(const float* X, const float* params, int64_t strideParams, int64_t w_off,
+                              int64_t b_off, int ldw, float* out, int K, int64_t rows, int H, int W,
+                              int C, int Cout, hipStream_t s);
+int launch_first_conv_wgrad(const float* X, const float* dout, float* partial, float* grad,
+                            int64_t strideParams, int64_t w_off, int64_t b_off, int ldw, int K,
+                            int64_t rows, int H, int W, int C, int Cout, double* sumsq,
+                            int64_t sumsq_stride, hipStream_t s);
 // Wt[k][c][(u,v,o)] = W[k][o][(2-u,2-v,c)] for K filter banks W [Cout][3][3][Cin] (row pitch ldw,
 // replica stride strideW); Wt is dense, [K][Cin][9 Cout].
 void launch_flip_filters(const float* W, int64_t strideW, int ldw, float* Wt, int K, int Cout, int Cin,

@@ -212,6 +212,206 @@ __global__ __launch_bounds__(kThreads) void flip_filters_kernel(const float* __r
   Wt[idx] = W[k * strideW + (long long)o * ldw + (8 - tap) * Cin + c];
 }
 
+// ---- first convolution layer (1..3 input channels) -------------------------------------------------
+// With C <= 3 the contraction is 9 C <= 27 long: too short to be worth staging through LDS, and
+// a 16-byte unit of the unfolded image would straddle taps.  These two kernels feed the MFMA
+// units (v_mfma_f32_32x32x2_f32) straight from global memory instead: every lane gathers the
+// image values of its pixel (the image of one replica is a few MB and stays in cache), the
+// filters sit in registers.  Lane (l32, h) supplies element (index l32, k = h) of each operand;
+// accumulator element e of a lane belongs to (second operand's index l32, first operand's
+// index (e/4)*8 + h*4 + e%4).
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+struct FirstConv {
+  int H, W, Cout;
+  float invW, invH;
+  long long rows;          // B H W pixels per replica
+  long long strideParams;  // floats between replicas' parameter (or gradient) vectors
+  int ldw;                 // row pitch of the filter bank [Cout][9 C (+ padding)]
+};
+
+__device__ __forceinline__ void pixel_rc(int p, const FirstConv& f, int& i, int& j) {
+  int q = (int)((float)p * f.invW);
+  int r = p - q * f.W;
+  if (r < 0) { r += f.W; --q; } else if (r >= f.W) { r -= f.W; ++q; }
+  j = r;
+  const int q2 = (int)((float)q * f.invH);
+  int r2 = q - q2 * f.H;
+  if (r2 < 0) r2 += f.H; else if (r2 >= f.H) r2 -= f.H;
+  i = r2;
+}
+
+// Value t of the unfolded image of pixel p at (i, j): X[p shifted by tap t / C][t % C].
+template <int C>
+__device__ __forceinline__ float unfolded(const float* __restrict__ img, int p, int i, int j, int t,
+                                          const FirstConv& f) {
+  const int tap = t / C, c = t - tap * C;
+  const int du = tap / 3 - 1, dv = tap % 3 - 1;
+  const bool ok = tap < 9 && (unsigned)(i + du) < (unsigned)f.H && (unsigned)(j + dv) < (unsigned)f.W;
+  return ok ? img[(long long)(p + du * f.W + dv) * C + c] : 0.f;
+}
+
+// out[k][p][o] = relu(b[o] + sum_t unfolded(p, t) W[o][t]).  One wavefront per 32 pixels.
+template <int C>
+__global__ __launch_bounds__(kThreads) void first_conv_forward_kernel(const float* __restrict__ X,
+                                                                      const float* __restrict__ params,
+                                                                      long long w_off, long long b_off,
+                                                                      float* __restrict__ out,
+                                                                      FirstConv f) {
+  constexpr int KS = (9 * C + 1) / 2;          // MFMA steps of depth 2
+  constexpr int WP = 33;                       // LDS pitch of a filter: lanes o, o+1 on different banks
+  extern __shared__ float wl[];                // [Cout][WP]: the filters, zero for t >= 9 C
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l32 = lane & 31, h = lane >> 5;
+  const int k = blockIdx.y;
+  {
+    // rows of 32 floats (lanes along t: whole 128-byte lines of the filter bank)
+    const float* Wg = params + (long long)k * f.strideParams + w_off;
+    for (int e = threadIdx.x; e < f.Cout * 32; e += kThreads) {
+      const int o = e >> 5, t = e & 31;
+      wl[o * WP + t] = t < 9 * C ? Wg[(long long)o * f.ldw + t] : 0.f;
+    }
+  }
+  __syncthreads();
+  const int p = (blockIdx.x * 4 + wave) * 32 + l32;
+  const bool live = p < f.rows;
+  const float* img = X + (long long)k * f.rows * C;
+  const float* bias = params + (long long)k * f.strideParams + b_off;
+  int i = 0, j = 0;
+  if (live) pixel_rc(p, f, i, j);
+  float x[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) x[s] = live ? unfolded<C>(img, p, i, j, 2 * s + h, f) : 0.f;
+  // acc[e] of lane (l32, h): output channel ob + l32 of pixel tile*32 + (e/4)*8 + h*4 + e%4, so
+  // that a store instruction writes two whole 128-byte rows
+  const int tile0 = (blockIdx.x * 4 + wave) * 32;
+  for (int ob = 0; ob < f.Cout; ob += 32) {
+    f32x16 acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const float w = wl[(ob + l32) * WP + 2 * s + h];
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(x[s], w, acc, 0, 0, 0);
+    }
+    const float bv = bias[ob + l32];
+    float* dst = out + ((long long)k * f.rows + tile0) * f.Cout + ob + l32;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int pp = (e / 4) * 8 + h * 4 + e % 4;
+      const float z = acc[e] + bv;
+      if (tile0 + pp < f.rows) dst[(long long)pp * f.Cout] = z > 0.f ? z : 0.f;
+    }
+  }
+}
+
+// Weight and bias gradient, first stage: workgroup (chunk, k) covers kFirstChunk pixels, 128 per
+// wavefront; partial[k][chunk][o][t] = sum over its pixels of dout[p][o] unfolded(p, t), with
+// t = 9 C standing for the constant 1 (that column is the bias gradient).  The four
+// wavefronts' sums are added in wave order through LDS.
+constexpr int kFirstChunk = 512;
+template <int C>
+__global__ __launch_bounds__(kThreads) void first_conv_wgrad_kernel(const float* __restrict__ X,
+                                                                    const float* __restrict__ dout,
+                                                                    float* __restrict__ partial,
+                                                                    int chunks, FirstConv f) {
+  __shared__ float red[3][32 * 32];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l32 = lane & 31, h = lane >> 5;
+  const int k = blockIdx.y;
+  const float* img = X + (long long)k * f.rows * C;
+  const float* dz = dout + (long long)k * f.rows * f.Cout;
+  const int p0 = blockIdx.x * kFirstChunk + wave * (kFirstChunk / 4);
+  // this lane's column of the unfolded image: fixed tap and channel
+  const int t = l32;
+  const int tap = t / C, c = t - tap * C;
+  const int du = tap / 3 - 1, dv = tap % 3 - 1;
+  const int shift = (du * f.W + dv) * C + c;
+  for (int ob = 0; ob < f.Cout; ob += 32) {
+    f32x16 acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+    // loads are issued unconditionally (from a clamped pixel) and zeroed afterwards, so that the
+    // unrolled loop can have many of them in flight
+    const int last = (int)f.rows - 1;
+#pragma unroll 8
+    for (int s = 0; s < kFirstChunk / 8; ++s) {
+      const int p = p0 + 2 * s + h;
+      const int pc = p < last ? p : last;
+      int i, j;
+      pixel_rc(pc, f, i, j);
+      const bool in_img = t < 9 * C && (unsigned)(i + du) < (unsigned)f.H && (unsigned)(j + dv) < (unsigned)f.W;
+      float a = dz[(long long)pc * f.Cout + ob + l32];
+      float b = img[in_img ? (long long)pc * C + shift : 0];
+      b = in_img ? b : (t == 9 * C ? 1.f : 0.f);
+      if (p > last) { a = 0.f; b = 0.f; }
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(b, a, acc, 0, 0, 0);
+    }
+    // acc[e]: o = ob + l32, t = (e/4)*8 + h*4 + e%4
+    if (wave > 0) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) red[wave - 1][l32 * 32 + (e / 4) * 8 + h * 4 + e % 4] = acc[e];
+    }
+    __syncthreads();
+    if (wave == 0) {
+      float* dst = partial + (((long long)k * chunks + blockIdx.x) * f.Cout + ob + l32) * 32;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int tt = q * 8 + h * 4;
+        f32x4 v;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int at = l32 * 32 + tt + r;
+          v[r] = ((acc[q * 4 + r] + red[0][at]) + red[1][at]) + red[2][at];
+        }
+        *reinterpret_cast<f32x4*>(dst + tt) = v;
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// Second stage: dW[k][o][t] (t < 9 C) and db[k][o] (t = 9 C) = sum over the chunks.  Workgroup
+// (block, k) finishes 64 elements with 16 chains of loads each (chain q adds chunks q, q+16,
+// ...), combined pairwise in a fixed tree through LDS; it also writes the sum of the squares of
+// what it stored to its own slot.
+constexpr int kFinishChains = 16;
+__global__ __launch_bounds__(1024) void first_conv_wgrad_finish_kernel(const float* __restrict__ partial,
+                                                                       int chunks, int C,
+                                                                       float* __restrict__ grad,
+                                                                       long long w_off, long long b_off,
+                                                                       double* __restrict__ sumsq,
+                                                                       long long strideSumsq,
+                                                                       FirstConv f) {
+  __shared__ float part[kFinishChains][64];
+  const int word = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int k = blockIdx.y;
+  const int total = f.Cout * 32;
+  const int e = blockIdx.x * 64 + word;       // o * 32 + t; total is a multiple of 64
+  float v = 0.f;
+  for (int ch = q; ch < chunks; ch += kFinishChains) v += partial[((long long)k * chunks + ch) * total + e];
+  part[q][word] = v;
+  __syncthreads();
+#pragma unroll
+  for (int half = kFinishChains / 2; half > 0; half >>= 1) {
+    if (q < half) part[q][word] += part[q + half][word];
+    __syncthreads();
+  }
+  if (q == 0) {
+    v = part[0][word];
+    float* g = grad + (long long)k * f.strideParams;
+    const int o = e >> 5, t = e & 31;
+    double ssq = 0.0;
+    if (t < 9 * C) { g[w_off + (long long)o * f.ldw + t] = v; ssq = (double)v * (double)v; }
+    else if (t == 9 * C) { g[b_off + o] = v; ssq = (double)v * (double)v; }
+    if (sumsq != nullptr) {
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) ssq += __shfl_xor(ssq, off, 64);
+      if (word == 0) sumsq[(long long)k * strideSumsq + blockIdx.x] = ssq;
+    }
+  }
+}
+
 unsigned blocks_for(long long total) { return (unsigned)((total + kThreads - 1) / kThreads); }
 
 }  // namespace
@@ -241,6 +441,45 @@ void launch_flip_filters(const float* W, int64_t strideW, int ldw, float* Wt, in
                          hipStream_t s) {
   const long long total = (long long)K * Cin * 9 * Cout;
   flip_filters_kernel<<<blocks_for(total), kThreads, 0, s>>>(W, strideW, ldw, Wt, Cout, Cin, total);
+}
+
+bool first_conv_fits(int C, int Cout, int64_t rows) {
+  return C >= 1 && C <= 3 && Cout % 32 == 0 && Cout <= 256 && rows < (1 << 24);
+}
+
+int first_conv_chunks(int64_t rows) { return (int)((rows + kFirstChunk - 1) / kFirstChunk); }
+
+static FirstConv first_shape(int H, int W, int Cout, int64_t rows, int64_t strideParams, int ldw) {
+  return FirstConv{H, W, Cout, 1.f / (float)W, 1.f / (float)H, rows, strideParams, ldw};
+}
+
+int launch_first_conv_forward(const float* X, const float* params, int64_t strideParams, int64_t w_off,
+                              int64_t b_off, int ldw, float* out, int K, int64_t rows, int H, int W,
+                              int C, int Cout, hipStream_t s) {
+  if (!first_conv_fits(C, Cout, rows)) return -1;
+  const FirstConv f = first_shape(H, W, Cout, rows, strideParams, ldw);
+  const dim3 grid((unsigned)((rows + 127) / 128), (unsigned)K);
+  const size_t lds = (size_t)Cout * 33 * 4;
+  if (C == 1) first_conv_forward_kernel<1><<<grid, kThreads, lds, s>>>(X, params, w_off, b_off, out, f);
+  else if (C == 2) first_conv_forward_kernel<2><<<grid, kThreads, lds, s>>>(X, params, w_off, b_off, out, f);
+  else first_conv_forward_kernel<3><<<grid, kThreads, lds, s>>>(X, params, w_off, b_off, out, f);
+  return 0;
+}
+
+int launch_first_conv_wgrad(const float* X, const float* dout, float* partial, float* grad,
+                            int64_t strideParams, int64_t w_off, int64_t b_off, int ldw, int K,
+                            int64_t rows, int H, int W, int C, int Cout, double* sumsq,
+                            int64_t sumsq_stride, hipStream_t s) {
+  if (!first_conv_fits(C, Cout, rows)) return -1;
+  const FirstConv f = first_shape(H, W, Cout, rows, strideParams, ldw);
+  const int chunks = first_conv_chunks(rows);
+  const dim3 grid((unsigned)chunks, (unsigned)K);
+  if (C == 1) first_conv_wgrad_kernel<1><<<grid, kThreads, 0, s>>>(X, dout, partial, chunks, f);
+  else if (C == 2) first_conv_wgrad_kernel<2><<<grid, kThreads, 0, s>>>(X, dout, partial, chunks, f);
+  else first_conv_wgrad_kernel<3><<<grid, kThreads, 0, s>>>(X, dout, partial, chunks, f);
+  first_conv_wgrad_finish_kernel<<<dim3((unsigned)(Cout / 2), (unsigned)K), 1024, 0, s>>>(
+      partial, chunks, C, grad, w_off, b_off, sumsq, sumsq_stride, f);
+  return Cout / 2;     // sum-of-squares slots written per replica
 }
 
 int colsum_chunks(int64_t rows) { return (int)((rows + kColsumRows - 1) / kColsumRows); }

@@ -109,7 +109,10 @@ struct ConvLayer {
   // count is a multiple of 32: `direct_in` for the layer's input (forward and dW), `direct_dx`
   // for its output gradient (dX, with the mirrored filters `wt`).  Otherwise the unfolded
   // image (`col`) resp. its gradient (the shared `dcol`) is stored.
-  bool direct_in, direct_dx;
+  // `first`: layer 0 with 1..3 input channels runs its forward pass and its weight gradient
+  // in kernels of their own (no unfolded image at all).
+  bool direct_in, direct_dx, first;
+  size_t first_partial;   // scratch of the first layer's weight gradient
   size_t col, out, pooled, dout, dpooled, wt;   // workspace offsets ([K] contiguous replicas each)
 };
 
@@ -292,7 +295,8 @@ void build_layout(const lsam_config& c, Layout& lo) {
     // piece of the gradient: room for the most any tile choice can produce
     int64_t cap = 0;
     for (const Layer& ly : lo.layers)
-      cap += std::max(gemm_sumsq_capacity(ly.out, ly.in) + (ly.out + 63) / 64, head_sumsq_slots(ly.in));
+      cap += std::max(gemm_sumsq_capacity(ly.out, ly.in) + (ly.out + 63) / 64,
+                      std::max(head_sumsq_slots(ly.in), ly.out / 2));   // ly.out / 2: first-layer kernels
     lo.nblk = (int)cap;
   }
 
@@ -324,7 +328,10 @@ void build_layout(const lsam_config& c, Layout& lo) {
       const bool small = cv.rows < (1 << 24);      // pixel indices exact in fp32
       cv.direct_in = small && cv.Cin % 32 == 0;
       cv.direct_dx = small && l > 0 && cv.Cout % 32 == 0;
-      if (!cv.direct_in) cv.col = take(cur, (size_t)lo.K * cv.rows * cv.ldc * 4);
+      cv.first = l == 0 && first_conv_fits(cv.Cin, cv.Cout, cv.rows);
+      if (cv.first)
+        cv.first_partial = take(cur, (size_t)lo.K * first_conv_chunks(cv.rows) * cv.Cout * 32 * 4);
+      else if (!cv.direct_in) cv.col = take(cur, (size_t)lo.K * cv.rows * cv.ldc * 4);
       if (cv.direct_dx) cv.wt = take(cur, (size_t)lo.K * cv.Cin * 9 * cv.Cout * 4);
       cv.out = take(cur, full);
       cv.dout = take(cur, full);
@@ -384,11 +391,11 @@ void build_layout(const lsam_config& c, Layout& lo) {
 // ---- per-kernel timing ---------------------------------------------------------------------------
 enum KernelClass {
   KC_GEMM_FWD = 0, KC_GEMM_DX, KC_GEMM_DW, KC_SOFTMAX_CE, KC_BIAS_GRAD, KC_SUMSQ, KC_NORM_FINISH,
-  KC_PERTURB, KC_DESCENT, KC_CENTER, KC_MISC, KC_HEAD, KC_UNFOLD, KC_POOL, KC_COUNT
+  KC_PERTURB, KC_DESCENT, KC_CENTER, KC_MISC, KC_HEAD, KC_UNFOLD, KC_POOL, KC_CONV_FIRST, KC_COUNT
 };
 const char* const kClassNames[KC_COUNT] = {
     "gemm_fwd", "gemm_dx", "gemm_dw", "softmax_ce", "bias_grad", "sumsq_partials", "norm_finish",
-    "perturb", "descent", "center", "misc", "head", "unfold_fold", "pool"};
+    "perturb", "descent", "center", "misc", "head", "unfold_fold", "pool", "conv_first"};
 
 struct TimedLaunch {
   int cls;
@@ -497,13 +504,19 @@ int conv_forward(lsam_ctx* c, const float* X, const float* params) {
     const ConvLayer& cv = lo.conv[l];
     const Layer& ly = lo.layers[l];
     float* col = cv.direct_in ? nullptr : c->at<float>(cv.col);
-    if (!cv.direct_in) {
+    if (cv.first) {
+      LaunchTimer t(c, KC_CONV_FIRST);
+      if (launch_first_conv_forward(in, params, lo.d_pad, ly.w_off, ly.b_off, ly.ldw,
+                                    c->at<float>(cv.out), lo.K, cv.rows, cv.H, cv.W, cv.Cin, cv.Cout,
+                                    s) != 0)
+        return fail(LSAM_EINVAL, "first convolution rejected");
+    } else if (!cv.direct_in) {
       LaunchTimer t(c, KC_UNFOLD);
       if (launch_unfold3x3(in, cv.rows * cv.Cin, col, cv.rows * cv.ldc, cv.ldc, lo.K, lo.B, cv.H,
                            cv.W, cv.Cin, s) != 0)
         return fail(LSAM_EINVAL, "unfold of convolution %d rejected", l);
     }
-    {
+    if (!cv.first) {
       GemmDesc d{};
       d.A = col; d.strideA = cv.rows * cv.ldc; d.ldA = cv.ldc; d.a_kmajor = 1;
       if (cv.direct_in) {
@@ -546,6 +559,15 @@ int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq,
       if (launch_maxpool2_backward(c->at<float>(cv.out), c->at<float>(cv.dpooled), dout,
                                    (int64_t)lo.K * lo.B, cv.H, cv.W, cv.Cout, s) != 0)
         return fail(LSAM_EINVAL, "pool backward of convolution %d rejected", l);
+    }
+    if (cv.first) {
+      LaunchTimer t(c, KC_CONV_FIRST);
+      const int used = launch_first_conv_wgrad(X, dout, c->at<float>(cv.first_partial), g, lo.d_pad,
+                                               ly.w_off, ly.b_off, ly.ldw, lo.K, cv.rows, cv.H, cv.W,
+                                               cv.Cin, cv.Cout, ssq ? ssq + *slots : nullptr, lo.nblk, s);
+      if (used < 0) return fail(LSAM_EINVAL, "first convolution's weight gradient rejected");
+      if (ssq) *slots += used;
+      continue;
     }
     {
       GemmDesc d{};

@@ -518,6 +518,11 @@ CNN_SMALL = workloads.Workload("cnn_small", K=2, dims=(3, 8, 16, 24, 5), batch=6
     # from the images (forward, dW and dX), with and without a pool below the layer
     ("unfolding inside the GEMM", dict(dims=(3, 32, 32, 64, 10), n_conv=3, pool_mask=0b101,
                                        n_classes=10, batch=5)),
+    # first layers with 1..3 input channels and 32 | C_out have kernels of their own
+    ("one-channel first layer, 64 filters", dict(dims=(1, 64, 16, 4), n_conv=1, pool_mask=1,
+                                                 n_classes=4, img_h=6, img_w=10, batch=5)),
+    ("two-channel first layer, no pool", dict(dims=(2, 32, 8, 24, 5), n_conv=2, pool_mask=0b10,
+                                              img_h=4, img_w=6, batch=43)),
     ("unfolding inside the GEMM, sides not powers of two", dict(
         dims=(4, 32, 64, 12, 6), n_conv=2, pool_mask=0b10, img_h=6, img_w=10, n_classes=6, batch=7)),
 ])

@@ -32,17 +32,20 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "adf91bc39256b53b"
+TRAFFIC_SOURCES = "9dc1539e2998936a"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43652597,
-             "gemm_dx": 42123264, "gemm_fwd": 62131520, "perturb": 201945685},
-    "cfg3": {"bias_grad": 13681894, "center": 1773569920, "descent": 17231767701, "gemm_dw":
-             445968794, "gemm_dx": 250125365, "gemm_fwd": 233099030, "perturb": 5065974059,
-             "softmax_ce": 1428971},
-    "cfg4": {"center": 3200045824, "descent": 25600045867, "perturb": 9600050389,
-             "sumsq_partials": 3415938837},
-    "cfg5": {"bias_grad": 118037751, "descent": 188959045440, "gemm_dw": 4953648477, "gemm_dx":
-             2333095758, "gemm_fwd": 2034256238, "perturb": 59024470869, "softmax_ce": 95613467},
+    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43724032,
+             "gemm_dx": 42126677, "gemm_fwd": 62121845, "perturb": 201945557},
+    "cfg3": {"bias_grad": 13681877, "center": 1773570112, "descent": 17231926208, "gemm_dw":
+             446145738, "gemm_dx": 250125387, "gemm_fwd": 233098514, "perturb": 5065989035,
+             "softmax_ce": 1428821},
+    "cfg4": {"center": 3200044544, "descent": 25600046635, "perturb": 9600050432,
+             "sumsq_partials": 3416541867},
+    "cfg5": {"bias_grad": 118030350, "descent": 188962528704, "gemm_dw": 4957139288, "gemm_dx":
+             2332894119, "gemm_fwd": 2034389497, "perturb": 59024472619, "softmax_ce": 95545392},
+    "cnn5": {"bias_grad": 17140316, "conv_first": 80455893, "descent": 79476736, "gemm_dw":
+             168179214, "gemm_dx": 34786645, "gemm_fwd": 38359868, "perturb": 29813760, "pool":
+             68581963},
 }
 
 
@@ -73,33 +76,65 @@ def layer_rows(w):
     return rows
 
 
+def conv_modes(w):
+    """Per convolution layer, which kernels serve it (the library's own rules, restated):
+    'first' = the first-layer kernels (1..3 input channels, 32 | C_out <= 256), 'direct' = the
+    GEMM reads the unfolded image from the image (32 | C_in), 'stored' = unfold + GEMM; and
+    whether its dX needs a stored unfolded gradient (not 32 | C_out)."""
+    out = []
+    for l in range(w.n_conv):
+        cin, cout = w.dims[l], w.dims[l + 1]
+        if l == 0 and cin <= 3 and cout % 32 == 0 and cout <= 256:
+            mode = "first"
+        else:
+            mode = "direct" if cin % 32 == 0 else "stored"
+        out.append((mode, l > 0 and cout % 32 != 0))
+    return out
+
+
 def gemm_flops(w):
-    """Per all-replica step: flops of the forward, dX and dW GEMM classes (both passes)."""
+    """Per all-replica step (both passes): flops of the forward, dX and dW GEMM classes and of
+    the first convolution layer's own kernels."""
     K = w.K
     shapes, rows = list(w.layer_shapes), layer_rows(w)
     fi, fo = shapes[-1]
     if w.gemm_dtype == 0 and fo <= 16 and fi <= 1024 and w.batch <= 512:
         shapes.pop()   # a narrow fp32 classifier head runs as two fused non-MFMA kernels ("head")
-    sw = sum(r * a * b for r, (a, b) in zip(rows, shapes))
-    sw_dx = sum(r * a * b for r, (a, b) in list(zip(rows, shapes))[1:])
-    return {"gemm_fwd": 2 * 2.0 * sw * K, "gemm_dw": 2 * 2.0 * sw * K, "gemm_dx": 2 * 2.0 * sw_dx * K}
+    per = [r * a * b for r, (a, b) in zip(rows, shapes)]
+    first = 0.0
+    if w.n_conv and conv_modes(w)[0][0] == "first":
+        first, per[0] = per[0], 0.0
+    sw = sum(per)
+    sw_dx = sum(per[1:])
+    out = {"gemm_fwd": 2 * 2.0 * sw * K, "gemm_dw": 2 * 2.0 * sw * K, "gemm_dx": 2 * 2.0 * sw_dx * K}
+    if first:
+        out["conv_first"] = 2 * 2 * 2.0 * first * K      # forward and weight gradient
+    return out
 
 
 def conv_bytes(w):
     """Algorithmic bytes per all-replica step (both passes) of the kernels around the
-    convolution GEMMs: the unfolded image is written once and its gradient read once per pass
-    (plus the image itself), the pool reads its input and writes a quarter of it, its backward
-    pass reads both and writes the full-size gradient."""
+    convolution GEMMs: where an unfolded image is stored it is written once (plus the image
+    read), where its gradient is stored that is read once (plus the image gradient written);
+    the pool reads its input and writes a quarter of it, its backward pass reads both and
+    writes the full-size gradient."""
     unfold = pool = 0.0
     rows = layer_rows(w)
+    modes = conv_modes(w) if w.n_conv else []
     for l in range(w.n_conv):
         cin, cout = w.dims[l], w.dims[l + 1]
-        unfold += rows[l] * (cin + 9 * cin) * 4.0
-        if l > 0:
+        if modes[l][0] == "stored":
+            unfold += rows[l] * (cin + 9 * cin) * 4.0
+        if modes[l][1]:
             unfold += rows[l] * (9 * cin + cin) * 4.0
         if (w.pool_mask >> l) & 1:
             pool += rows[l] * cout * 4.0 * (1.25 + 2.25)
-    return {"unfold_fold": 2 * unfold * w.K, "pool": 2 * pool * w.K} if w.n_conv else {}
+    out = {}
+    if unfold:
+        out["unfold_fold"] = 2 * unfold * w.K
+    if pool:
+        out["pool"] = 2 * pool * w.K
+    return out
 
 
 def stream_bytes(w):

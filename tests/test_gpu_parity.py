@@ -455,7 +455,7 @@ def test_peak_probe_reports_plausible_ceilings():
         lsam.lsam_probe_peaks(scratch[:16])          # too small
 
 
-@pytest.mark.parametrize("name", ["cfg1", "bf16"])
+@pytest.mark.parametrize("name", ["cfg1", "bf16", "cnn"])
 def test_step_can_be_captured_and_replayed_as_a_hip_graph(name):
     """`lsam_step` allocates nothing and never synchronises, so a caller may capture it.  Four
     replays of the captured step, with eager work and synchronisations between them, must
@@ -464,6 +464,12 @@ def test_step_can_be_captured_and_replayed_as_a_hip_graph(name):
     point is crossed here)."""
     if name == "cfg1":
         w = workloads.WORKLOADS["cfg1"].scaled(tau=(100, 100))
+    elif name == "cnn":
+        # all three ways a convolution is served: first-layer kernels, unfolding inside the
+        # GEMM, stored unfolded image
+        w = workloads.Workload("cnn_graph", K=2, dims=(3, 32, 32, 24, 40, 10), batch=8, n_conv=4,
+                               img_h=8, img_w=8, pool_mask=0b0110, rho=0.05, lr=0.05,
+                               tau=(100, 100), n_classes=10, data_seed=41)
     else:
         full = workloads.WORKLOADS["cfg3"]
         dims = (full.dims[0] // 8,) + (256,) * (len(full.dims) - 2) + (full.dims[-1],)
@@ -523,6 +529,8 @@ CNN_SMALL = workloads.Workload("cnn_small", K=2, dims=(3, 8, 16, 24, 5), batch=6
                                                  n_classes=4, img_h=6, img_w=10, batch=5)),
     ("two-channel first layer, no pool", dict(dims=(2, 32, 8, 24, 5), n_conv=2, pool_mask=0b10,
                                               img_h=4, img_w=6, batch=43)),
+    ("four convolutions, one of each kind and two pools", dict(
+        dims=(3, 32, 32, 24, 40, 10), n_conv=4, pool_mask=0b0110, n_classes=10, batch=8)),
     ("unfolding inside the GEMM, sides not powers of two", dict(
         dims=(4, 32, 64, 12, 6), n_conv=2, pool_mask=0b10, img_h=6, img_w=10, n_classes=6, batch=7)),
 ])

@@ -197,17 +197,28 @@ class Cnn:
     its layers, so the shape is a parameter here).
 
     Layers l < n_conv: 3x3 convolution, stride 1, zero padding 1, C_l -> C_{l+1} channels,
-    bias, ReLU, then a 2x2/stride-2 max-pool if bit l of pool_mask is set.  The remaining
+    bias, [batch normalisation if bit l of bn_mask is set,] ReLU, then a 2x2/stride-2 max-pool
+    if bit l of pool_mask is set.  The remaining
     layers are dense as in `Mlp`, the first of them reading the image flattened in (row,
     column, channel) order.  dims = (C_0, ..., C_{n_conv}, F_1, ..., classes).
     Tensors are [B, H, W, C].  Flat parameters per layer: W_l [out, 3, 3, C_l] (dense:
-    [out, in]) row-major, then b_l [out].
+    [out, in]) row-major, then b_l [out], then, for a batch-normalised layer, gamma_l [out] and
+    beta_l [out].
+
+    Batch normalisation is the training-mode one (Appendix "Batch Normalization": every worker
+    normalises with the statistics of its own minibatch, nothing is synchronised): per channel,
+    over the B H W positions of the replica's batch,
+      mu = mean Z, var = mean (Z - mu)^2, Xh = (Z - mu) / sqrt(var + eps), Y = gamma Xh + beta,
+    and its backward pass carries the dependence of mu and var on Z:
+      dbeta = sum dY, dgamma = sum dY Xh, dZ = gamma / sqrt(var + eps) (dY - dbeta/N - Xh dgamma/N).
+    Running averages for inference are not part of a training step and are not kept.
 
       Z[b,i,j,o] = b[o] + sum_{u,v,c} Xpad[b,i+u,j+v,c] W[o,u,v,c]     (Xpad: X with a zero rim)
       P[b,i,j,c] = max_{u,v in {0,1}} A[b,2i+u,2j+v,c]
     The pool's gradient goes to the first maximal element of each window in (u, v) order."""
 
-    def __init__(self, dims, n_conv, img_h, img_w, pool_mask):
+    def __init__(self, dims, n_conv, img_h, img_w, pool_mask, bn_mask=0, bn_eps=1e-5):
+        self.bn_mask, self.bn_eps = int(bn_mask), float(bn_eps)
         self.dims = tuple(int(v) for v in dims)
         self.L = len(self.dims) - 1
         self.n_conv = int(n_conv)
@@ -216,16 +227,21 @@ class Cnn:
         self.shapes, self.final_hw = conv_layer_shapes(self.dims, self.n_conv, self.H, self.W,
                                                        self.pool_mask)
         self.offsets = []
+        self.bn_offsets = {}        # layer -> (start of gamma, start of beta, end)
         off = 0
-        for fi, fo in self.shapes:
+        for l, (fi, fo) in enumerate(self.shapes):
             self.offsets.append((off, off + fo * fi, off + fo * fi + fo))
             off += fo * fi + fo
+            if l < self.n_conv and (self.bn_mask >> l) & 1:
+                self.bn_offsets[l] = (off, off + fo, off + 2 * fo)
+                off += 2 * fo
         self.d = off
         self.last_margin = np.inf
 
     def loss_and_grad(self, x, X, labels):
         x = np.asarray(x, dtype=np.float64)
         X = np.asarray(X, dtype=np.float64)
+        bn_saved = {}
         B = X.shape[0]
         self.last_margin = np.inf
         # ---- forward ----
@@ -242,6 +258,14 @@ class Cnn:
             for u in range(3):
                 for v in range(3):
                     Z += Ap[:, u:u + h, v:v + w, :] @ Wl[:, u, v, :].T
+            if l in self.bn_offsets:
+                g0, g1, g2 = self.bn_offsets[l]
+                mu = Z.mean(axis=(0, 1, 2))
+                var = ((Z - mu) ** 2).mean(axis=(0, 1, 2))
+                inv = 1.0 / np.sqrt(var + self.bn_eps)
+                Xh = (Z - mu) * inv
+                bn_saved[l] = (Xh, inv)
+                Z = x[g0:g1] * Xh + x[g1:g2]
             self.last_margin = min(self.last_margin, float(np.min(np.abs(Z))))
             R = np.maximum(Z, 0.0)
             conv_in.append(Ap)
@@ -299,6 +323,15 @@ class Cnn:
             else:
                 dR = dA.reshape(B, h, w, cout)
             dZc = dR * (R > 0.0)
+            if l in self.bn_offsets:
+                g0, g1, g2 = self.bn_offsets[l]
+                Xh, inv = bn_saved[l]
+                n = B * h * w
+                dbeta = dZc.sum(axis=(0, 1, 2))
+                dgamma = (dZc * Xh).sum(axis=(0, 1, 2))
+                grad[g0:g1] = dgamma
+                grad[g1:g2] = dbeta
+                dZc = x[g0:g1] * inv * (dZc - dbeta / n - Xh * dgamma / n)
             Wl = x[o0:o1].reshape(cout, 3, 3, cin)
             Ap = conv_in[l]
             dW = np.zeros((cout, 3, 3, cin))
@@ -359,10 +392,12 @@ def normals_from_counters(counter, key):
     return out
 
 
-def langevin_noise(dims, d_raw, replica, step, seed, shapes=None):
+def langevin_noise(dims, d_raw, replica, step, seed, shapes=None, bn_mask=0):
     """xi for one replica and step, in the flat parameter layout.  `shapes`: (fan_in, out) per
     layer when they are not the consecutive pairs of `dims` (convolutional layers: a filter
-    bank [out, 3, 3, C] is the matrix [out, 9 C])."""
+    bank [out, 3, 3, C] is the matrix [out, 9 C]).  The gamma and beta vectors of a
+    batch-normalised layer l follow its bias, as one-row matrices with the codes 32 + 2 l and
+    33 + 2 l."""
     key = (seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF)
     if not len(dims):
         groups = np.arange((d_raw + 3) // 4, dtype=np.uint64)
@@ -373,10 +408,13 @@ def langevin_noise(dims, d_raw, replica, step, seed, shapes=None):
     if shapes is None:
         shapes = [(dims[l], dims[l + 1]) for l in range(len(dims) - 1)]
     for l, (fi, fo) in enumerate(shapes):
-        for is_bias, rows, cols in ((0, fo, fi), (1, 1, fo)):
+        pieces = [(2 * l, fo, fi), (2 * l + 1, 1, fo)]
+        if (bn_mask >> l) & 1:
+            pieces += [(32 + 2 * l, 1, fo), (33 + 2 * l, 1, fo)]
+        for which, rows, cols in pieces:
             cg = np.arange((cols + 3) // 4, dtype=np.uint64)[None, :]
             rr = np.arange(rows, dtype=np.uint64)[:, None]
-            code = np.uint64((2 * l + is_bias) | (replica << 16))
+            code = np.uint64(which | (replica << 16))
             z = normals_from_counters((cg, rr, code, np.uint64(step)), key)
             parts.append(z.reshape(rows, -1)[:, :cols].ravel())
     return np.concatenate(parts)
@@ -398,7 +436,7 @@ class LsamOracle:
                  rho=0.05, gamma=1e-12, lr=0.1, lr_center=1.0, momentum=0.9, beta=0.9,
                  lambda0=0.5, lambda_abs=-1.0, nesterov=1, tau=None, tau_min=1, tau_max=1,
                  sched_seed=0, sched_mode=SCHED_FIXED, algorithm=ALG_LSAM, noise_scale=0.0,
-                 noise_seed=0, n_conv=0, img_h=0, img_w=0, pool_mask=0):
+                 noise_seed=0, n_conv=0, img_h=0, img_w=0, pool_mask=0, bn_mask=0, bn_eps=1e-5):
         self.K = int(K)
         self.algorithm = int(algorithm)
         self.noise_scale, self.noise_seed = float(noise_scale), int(noise_seed)
@@ -407,10 +445,11 @@ class LsamOracle:
         if n_conv:
             if gemm_dtype != 0:
                 raise ValueError("the convolutional model is float32 only")
-            self.model = Cnn(dims, n_conv, img_h, img_w, pool_mask)
+            self.model = Cnn(dims, n_conv, img_h, img_w, pool_mask, bn_mask, bn_eps)
         else:
             self.model = Mlp(dims, gemm_dtype) if len(dims) else None
         self.shapes = self.model.shapes if n_conv else None
+        self.bn_mask = int(bn_mask) if n_conv else 0
         self.d = self.model.d if self.model else int(d_raw)
         self.batch = int(batch)
         self.rho, self.gamma = float(rho), float(gamma)
@@ -465,7 +504,7 @@ class LsamOracle:
         else:
             self.x[i] = self.x[i] - self.lr * self.v[i]
         if self.noise_scale != 0.0:
-            xi = langevin_noise(self.dims, self.d, i, self.t, self.noise_seed, self.shapes)
+            xi = langevin_noise(self.dims, self.d, i, self.t, self.noise_seed, self.shapes, self.bn_mask)
             self.x[i] = self.x[i] + self.noise_scale * np.sqrt(2.0 * self.lr) * xi
         self.S[i] += self.x[i]
 

@@ -462,8 +462,9 @@ def test_langevin_sampler_reaches_the_stationary_variance():
 
 
 # ---- convolutional model ---------------------------------------------------------------------
-def _torch_cnn_loss(xt, X, lab, dims, n_conv, pool_mask, shapes):
-    """The same network written with torch's own convolution, pooling and loss routines."""
+def _torch_cnn_loss(xt, X, lab, dims, n_conv, pool_mask, shapes, bn_mask=0, bn_eps=1e-5):
+    """The same network written with torch's own convolution, batch-norm, pooling and loss
+    routines."""
     import torch.nn.functional as F
     A = torch.tensor(X).permute(0, 3, 1, 2)
     off = 0
@@ -471,8 +472,13 @@ def _torch_cnn_loss(xt, X, lab, dims, n_conv, pool_mask, shapes):
         fi, fo = shapes[l]
         W = xt[off:off + fo * fi].reshape(fo, 3, 3, dims[l]).permute(0, 3, 1, 2)
         off += fo * fi
-        A = F.relu(F.conv2d(A, W, xt[off:off + fo], padding=1))
+        A = F.conv2d(A, W, xt[off:off + fo], padding=1)
         off += fo
+        if (bn_mask >> l) & 1:
+            A = F.batch_norm(A, None, None, xt[off:off + fo], xt[off + fo:off + 2 * fo],
+                             training=True, eps=bn_eps)
+            off += 2 * fo
+        A = F.relu(A)
         if (pool_mask >> l) & 1:
             A = F.max_pool2d(A, 2)
     A = A.permute(0, 2, 3, 1).reshape(X.shape[0], -1)
@@ -606,3 +612,82 @@ def test_cnn_lsam_step_matches_sgd_witness():
         xt.sub_(eps)
     opt.step()
     assert np.max(np.abs(o.get_params(0) - xt.detach().numpy())) < 1e-13
+
+
+# ---- batch normalisation ---------------------------------------------------------------------
+@pytest.mark.parametrize("dims,n_conv,H,W,pool_mask,bn_mask,B", [
+    ((3, 8, 16, 12, 5), 2, 8, 8, 0b01, 0b11, 4),
+    ((2, 4, 4, 4, 3), 3, 4, 8, 0b101, 0b010, 3),
+    ((1, 3, 6), 1, 6, 4, 0, 0b1, 5),
+])
+def test_batchnorm_gradient_matches_torch_autograd(dims, n_conv, H, W, pool_mask, bn_mask, B):
+    from oracle.lsam_oracle import Cnn
+    m = Cnn(dims, n_conv, H, W, pool_mask, bn_mask, 1e-5)
+    rng = np.random.default_rng(12)
+    x = rng.standard_normal(m.d) * 0.3
+    for l, (g0, g1, g2) in m.bn_offsets.items():
+        x[g0:g1] = 1.0 + 0.3 * rng.standard_normal(g1 - g0)
+    X = rng.standard_normal((B, H, W, dims[0]))
+    lab = rng.integers(0, dims[-1], B)
+    loss, g = m.loss_and_grad(x, X, lab)
+    xt = torch.tensor(x, requires_grad=True)
+    L = _torch_cnn_loss(xt, X, lab, dims, n_conv, pool_mask, m.shapes, bn_mask, 1e-5)
+    L.backward()
+    assert abs(loss - L.item()) < 1e-12
+    assert np.max(np.abs(g - xt.grad.numpy())) / np.max(np.abs(g)) < 1e-10
+
+
+def test_batchnorm_invariances():
+    # what normalisation removes cannot move the loss: the convolution's bias (its gradient is
+    # zero) and, with eps = 0, the scale of every filter (Euler: W_o . dW_o = 0 per filter)
+    from oracle.lsam_oracle import Cnn
+    m = Cnn((2, 4, 6, 3), 2, 4, 4, 0b10, 0b11, 0.0)
+    rng = np.random.default_rng(4)
+    x = rng.standard_normal(m.d) * 0.5
+    X = rng.standard_normal((6, 4, 4, 2))
+    lab = rng.integers(0, 3, 6)
+    loss, g = m.loss_and_grad(x, X, lab)
+    scale = np.max(np.abs(g))
+    for l in (0, 1):
+        o0, o1, o2 = m.offsets[l]
+        assert np.max(np.abs(g[o1:o2])) < 1e-12 * max(scale, 1.0)
+        fo = m.shapes[l][1]
+        W, dW = x[o0:o1].reshape(fo, -1), g[o0:o1].reshape(fo, -1)
+        assert np.max(np.abs(np.sum(W * dW, axis=1))) < 1e-12 * max(scale, 1.0)
+    # and shifting / scaling the filter bank of a normalised layer leaves the loss where it was
+    y = x.copy()
+    o0, o1, o2 = m.offsets[0]
+    y[o0:o1] *= 3.0
+    y[o1:o2] += 0.7
+    assert abs(m.loss_and_grad(y, X, lab)[0] - loss) < 1e-12
+
+
+def test_batchnorm_output_statistics():
+    # gamma = 1, beta = 0, one normalised convolution feeding a dense layer of ones: the logits'
+    # sum over the batch is then sum relu(Xh); instead of that, check the definition directly on
+    # a case small enough to do by hand: 1 channel, 1x2 image, B = 2, identity centre tap
+    from oracle.lsam_oracle import Cnn
+    m = Cnn((1, 1, 2), 1, 1, 2, 0, 0b1, 0.0)
+    x = np.zeros(m.d)
+    x[4] = 1.0                                   # centre tap: Z = X
+    g0, g1, g2 = m.bn_offsets[0]
+    x[g0:g1], x[g1:g2] = 2.0, 0.5                # gamma, beta
+    o0, o1, _ = m.offsets[1]
+    x[o0:o1] = [1.0, 0.0, 0.0, 1.0]              # logits = the two normalised, rectified pixels
+    X = np.array([[1.0, 3.0], [5.0, 7.0]]).reshape(2, 1, 2, 1)
+    # Z = 1, 3, 5, 7: mu = 4, var = 5, Xh = (-3, -1, 1, 3)/sqrt(5), Y = 2 Xh + 0.5
+    Y = 2.0 * np.array([-3.0, -1.0, 1.0, 3.0]) / np.sqrt(5.0) + 0.5
+    A = np.maximum(Y, 0.0).reshape(2, 2)
+    expect = np.mean([np.log(np.sum(np.exp(A[b]))) - A[b, 0] for b in range(2)])
+    loss, _ = m.loss_and_grad(x, X, np.array([0, 0]))
+    assert abs(loss - expect) < 1e-14
+
+
+def test_noise_layout_with_batchnorm_vectors():
+    shapes = [(18, 4), (64, 3)]
+    a = langevin_noise((2, 4, 3), 0, 1, 2, 7, shapes=shapes)
+    b = langevin_noise((2, 4, 3), 0, 1, 2, 7, shapes=shapes, bn_mask=0b1)
+    n0 = 18 * 4 + 4
+    assert b.size == a.size + 8
+    assert np.array_equal(b[:n0], a[:n0]) and np.array_equal(b[n0 + 8:], a[n0:])
+    assert np.all(np.isfinite(b[n0:n0 + 8])) and len(set(b[n0:n0 + 8])) == 8

@@ -11,7 +11,8 @@ def oracle_from(w, init, **over):
               lambda_abs=w.lambda_abs, nesterov=w.nesterov, tau=w.tau, tau_min=w.tau_min,
               tau_max=w.tau_max, sched_seed=w.sched_seed, sched_mode=w.sched_mode,
               algorithm=w.algorithm, noise_scale=w.noise_scale, noise_seed=w.noise_seed,
-              n_conv=w.n_conv, img_h=w.img_h, img_w=w.img_w, pool_mask=w.pool_mask)
+              n_conv=w.n_conv, img_h=w.img_h, img_w=w.img_w, pool_mask=w.pool_mask,
+              bn_mask=w.bn_mask, bn_eps=w.bn_eps)
     kw.update(over)
     return LsamOracle(**kw)
 

@@ -54,6 +54,8 @@ class Workload:
     img_h: int = 0                          # then dims = (C_0..C_n_conv, F_1.., classes) and the
     img_w: int = 0                          # input is [K, B, img_h, img_w, C_0]
     pool_mask: int = 0                      # bit l: 2x2 max-pool after convolution l
+    bn_mask: int = 0                        # bit l: batch normalisation in convolution l
+    bn_eps: float = 1e-5
     steps: int = 20
     data_seed: int = 0
     n_classes: int = field(default=0)
@@ -85,7 +87,8 @@ class Workload:
     def d(self) -> int:
         if not self.dims:
             return self.d_raw
-        return sum(fi * fo + fo for fi, fo in self.layer_shapes)
+        return sum(fi * fo + fo + (2 * fo if (self.bn_mask >> l) & 1 and l < self.n_conv else 0)
+                   for l, (fi, fo) in enumerate(self.layer_shapes))
 
     def scaled(self, **kw) -> "Workload":
         return replace(self, **kw)
@@ -130,15 +133,20 @@ def _rng(seed: int, stream: int) -> np.random.Generator:
 
 def init_params(w: Workload, seed: Optional[int] = None) -> np.ndarray:
     """One flat fp32 parameter vector [d]: per layer W [out,in] row-major then b [out],
-    each drawn U(-1/sqrt(in), 1/sqrt(in)); raw mode: N(0,1)."""
+    each drawn U(-1/sqrt(in), 1/sqrt(in)), then gamma ~ U(0.9, 1.1) and beta ~ U(-0.1, 0.1) for a
+    batch-normalised layer; raw mode: N(0,1)."""
     rng = _rng(w.data_seed if seed is None else seed, 1)
     if not w.dims:
         return rng.standard_normal(w.d_raw, dtype=np.float32)
     parts = []
-    for fan_in, out in w.layer_shapes:
+    for l, (fan_in, out) in enumerate(w.layer_shapes):
         bound = np.float32(1.0 / np.sqrt(fan_in))
         parts.append((rng.random(out * fan_in, dtype=np.float32) * 2 - 1) * bound)
         parts.append((rng.random(out, dtype=np.float32) * 2 - 1) * bound)
+        if l < w.n_conv and (w.bn_mask >> l) & 1:
+            # gamma around 1, beta around 0 (not exactly, so that tests see both)
+            parts.append(1 + (rng.random(out, dtype=np.float32) - np.float32(0.5)) * np.float32(0.2))
+            parts.append((rng.random(out, dtype=np.float32) - np.float32(0.5)) * np.float32(0.2))
     return np.concatenate(parts).astype(np.float32)
 
 
@@ -162,6 +170,8 @@ def init_params_margin(w: Workload, seed: Optional[int] = None) -> np.ndarray:
                 np.arange(out) % 2 == 0, c, -c).astype(np.float32)
             c_prev = c
         off += out * fan_in + out
+        if l < w.n_conv and (w.bn_mask >> l) & 1:
+            off += 2 * out
     return p
 
 

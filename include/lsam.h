@@ -37,6 +37,11 @@
  * Images are [H, W, C] with the channel contiguous.  fp32 only; C_1..C_{n_conv} must be
  * multiples of 8 and every pooled image must have even sides.  The pool's gradient goes to
  * the first maximum of a window in row-major order.
+ * A batch-normalised convolution (bn_mask) computes, per replica and channel over the B H W
+ * positions of that replica's minibatch, Y = gamma (Z - mean) / sqrt(var + bn_eps) + beta before
+ * the ReLU (training mode; the backward pass differentiates through mean and var; Appendix
+ * "Batch Normalization": workers do not synchronise these statistics).  Its gamma [C_{l+1}]
+ * and beta [C_{l+1}] follow b_l in the flat layout.  No running averages are kept.
  */
 #ifndef LSAM_H
 #define LSAM_H
@@ -112,6 +117,8 @@ typedef struct {
                              (stride 1, zero rim 1, bias, ReLU), the rest dense; see below   */
   int32_t img_h, img_w;   /* input image sides (n_conv > 0)                           */
   uint32_t pool_mask;     /* bit l set: a 2x2/stride-2 max-pool follows convolution l */
+  uint32_t bn_mask;       /* bit l set: convolution l is batch-normalised before its ReLU */
+  float bn_eps;           /* epsilon of the normalisation, > 0 (or 0 with bn_mask = 0) */
 } lsam_config;
 
 /* Which per-replica buffer `lsam_get_buffer` copies out. */

@@ -157,7 +157,7 @@ int launch_fold3x3(const float* dcol, int64_t strideCol, int ld, float* dX, cons
                    int64_t strideX, int K, int B, int H, int W, int C, hipStream_t s);
 // A first convolution layer with C = 1..3 input channels and a multiple of 32 output channels
 // (first_conv_fits) has kernels of its own that gather the image straight into the MFMA
-// operands.  Forward: out[k][p][o] = relu(b[o] + conv), parameters taken from
+// operands.  Forward: out[k][p][o] = b[o] + conv, rectified if `relu`, parameters taken from
 // params + k * strideParams at w_off (row pitch ldw) and b_off.  Weight gradient: dW and db
 // into grad + k * strideParams at the same offsets, through `partial`
 // ([K][first_conv_chunks(rows)][Cout][32] floats of scratch), plus, if sumsq is non-null, the
@@ -166,12 +166,30 @@ int launch_fold3x3(const float* dcol, int64_t strideCol, int ld, float* dX, cons
 bool first_conv_fits(int C, int Cout, int64_t rows);
 int first_conv_chunks(int64_t rows);
 int launch_first_conv_forward(const float* X, const float* params, int64_t strideParams, int64_t w_off,
-                              int64_t b_off, int ldw, float* out, int K, int64_t rows, int H, int W,
-                              int C, int Cout, hipStream_t s);
+                              int64_t b_off, int ldw, float* out, int relu, int K, int64_t rows, int H,
+                              int W, int C, int Cout, hipStream_t s);
 int launch_first_conv_wgrad(const float* X, const float* dout, float* partial, float* grad,
                             int64_t strideParams, int64_t w_off, int64_t b_off, int ldw, int K,
                             int64_t rows, int H, int W, int C, int Cout, double* sumsq,
                             int64_t sumsq_stride, hipStream_t s);
+// Training-mode batch normalisation of K matrices Z [rows][C] (C % 4 == 0, C <= 1024), per
+// replica and column over the rows.  Forward: stats[k][0][c] = mean, stats[k][1][c] =
+// 1/sqrt(biased variance + eps); out = relu(gamma Xh + beta), Xh = (Z - mean) stats[1], gamma
+// and beta read from params + k * strideParams at gam_off / bet_off.  `scratch`: 2 * K *
+// bn_chunks(rows) * C floats.  Backward: launch_bn_backward_partials leaves chunk sums
+// part[k][chunk][0..C) = sum dY Xh and [C..2C) = sum dY (returns the chunk count; launch_bias_grad
+// over them gives dgamma and dbeta); launch_bn_backward_apply then overwrites dY with
+// dZ = gamma stats[1] (dY - dbeta/rows - Xh dgamma/rows), dgamma and dbeta read from
+// grad + k * strideParams at the same offsets.  -1: shape not supported.
+int bn_chunks(int64_t rows);
+int launch_bn_forward(const float* Z, float* scratch, float* stats, const float* params,
+                      int64_t strideParams, int64_t gam_off, int64_t bet_off, float* out, int K,
+                      int64_t rows, int C, float eps, hipStream_t s);
+int launch_bn_backward_partials(const float* Z, const float* dY, const float* stats, float* part, int K,
+                                int64_t rows, int C, hipStream_t s);
+void launch_bn_backward_apply(const float* Z, float* dY, const float* stats, const float* params,
+                              const float* grad, int64_t strideParams, int64_t gam_off, int64_t bet_off,
+                              int K, int64_t rows, int C, hipStream_t s);
 // Wt[k][c][(u,v,o)] = W[k][o][(2-u,2-v,c)] for K filter banks W [Cout][3][3][Cin] (row pitch ldw,
 // replica stride strideW); Wt is dense, [K][Cin][9 Cout].
 void launch_flip_filters(const float* W, int64_t strideW, int ldw, float* Wt, int K, int Cout, int Cin,

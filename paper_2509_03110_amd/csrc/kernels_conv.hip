@@ -257,7 +257,7 @@ __global__ __launch_bounds__(kThreads) void first_conv_forward_kernel(const floa
                                                                       const float* __restrict__ params,
                                                                       long long w_off, long long b_off,
                                                                       float* __restrict__ out,
-                                                                      FirstConv f) {
+                                                                      FirstConv f, int relu) {
   constexpr int KS = (9 * C + 1) / 2;          // MFMA steps of depth 2
   constexpr int WP = 33;                       // LDS pitch of a filter: lanes o, o+1 on different banks
   extern __shared__ float wl[];                // [Cout][WP]: the filters, zero for t >= 9 C
@@ -300,7 +300,7 @@ __global__ __launch_bounds__(kThreads) void first_conv_forward_kernel(const floa
     for (int e = 0; e < 16; ++e) {
       const int pp = (e / 4) * 8 + h * 4 + e % 4;
       const float z = acc[e] + bv;
-      if (tile0 + pp < f.rows) dst[(long long)pp * f.Cout] = z > 0.f ? z : 0.f;
+      if (tile0 + pp < f.rows) dst[(long long)pp * f.Cout] = (relu && !(z > 0.f)) ? 0.f : z;
     }
   }
 }
@@ -412,6 +412,175 @@ __global__ __launch_bounds__(1024) void first_conv_wgrad_finish_kernel(const flo
   }
 }
 
+// ---- batch normalisation (training mode, per replica and channel over the B H W rows) -------------
+// (Appendix "Batch Normalization": each worker uses the statistics of its own minibatch.)
+// Z is [K][rows][C] (C % 4 == 0, C <= 1024).  Statistics in one pass over Z that does not lose
+// digits when |mean| >> spread: every chunk of kBnRows rows gets its own mean and its own sum of
+// squared deviations from that mean; the chunks are combined with the pairwise-update formula
+// in double, in chunk order.
+constexpr int kBnRows = 256;
+
+// Column sums of up to two quantities over a chunk of rows; thread = (column word, row group).
+// Returns the totals of this thread's column word in threads with grp == 0 (others: garbage).
+struct ChunkThread {
+  int words, groups, w, grp;
+};
+__device__ __forceinline__ ChunkThread chunk_thread(int C) {
+  ChunkThread t;
+  t.words = C / 4;
+  t.groups = kThreads / t.words;
+  t.w = threadIdx.x % t.words;
+  t.grp = threadIdx.x / t.words;
+  return t;
+}
+// Adds `v` over the row groups in group order; result valid for grp == 0.  `buf`: kThreads words.
+__device__ __forceinline__ f32x4 combine_groups(f32x4 v, const ChunkThread& t, f32x4* buf) {
+  __syncthreads();
+  buf[threadIdx.x] = v;
+  __syncthreads();
+  f32x4 tot = v;
+  if (t.grp == 0)
+    for (int gq = 1; gq < t.groups; ++gq) tot += buf[gq * t.words + t.w];
+  return tot;
+}
+
+__global__ __launch_bounds__(kThreads) void bn_stats_partial_kernel(const float* __restrict__ Z,
+                                                                    float* __restrict__ pmean,
+                                                                    float* __restrict__ pm2,
+                                                                    long long rows, int C, int chunks) {
+  __shared__ f32x4 buf[kThreads];
+  __shared__ f32x4 mean_s[kThreads];
+  const ChunkThread t = chunk_thread(C);
+  const int k = blockIdx.y;
+  const long long r0 = (long long)blockIdx.x * kBnRows;
+  const long long r1 = r0 + kBnRows < rows ? r0 + kBnRows : rows;
+  const float* base = Z + ((long long)k * rows) * C + 4 * t.w;
+  const bool live = t.grp < t.groups;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  if (live)
+    for (long long r = r0 + t.grp; r < r1; r += t.groups) acc += *reinterpret_cast<const f32x4*>(base + r * C);
+  f32x4 tot = combine_groups(acc, t, buf);
+  const float inv_n = 1.f / (float)(r1 - r0);
+  if (live && t.grp == 0) mean_s[t.w] = tot * inv_n;
+  __syncthreads();
+  const f32x4 mu = live ? mean_s[t.w] : acc;
+  acc = f32x4{0.f, 0.f, 0.f, 0.f};
+  if (live)
+    for (long long r = r0 + t.grp; r < r1; r += t.groups) {
+      const f32x4 dlt = *reinterpret_cast<const f32x4*>(base + r * C) - mu;
+      acc += dlt * dlt;
+    }
+  tot = combine_groups(acc, t, buf);
+  if (live && t.grp == 0) {
+    const long long at = ((long long)k * chunks + blockIdx.x) * C + 4 * t.w;
+    *reinterpret_cast<f32x4*>(pmean + at) = mu;
+    *reinterpret_cast<f32x4*>(pm2 + at) = tot;
+  }
+}
+
+// stats[k][0][c] = mean, stats[k][1][c] = 1 / sqrt(var + eps), var = M2 / rows (biased).
+// One thread per (k, c): the chunks' (n, mean, M2) are merged in chunk order.
+__global__ __launch_bounds__(kThreads) void bn_stats_finish_kernel(const float* __restrict__ pmean,
+                                                                   const float* __restrict__ pm2,
+                                                                   float* __restrict__ stats,
+                                                                   long long rows, int C, int chunks,
+                                                                   float eps) {
+  const int c = blockIdx.x * kThreads + threadIdx.x;
+  const int k = blockIdx.y;
+  if (c >= C) return;
+  double n = 0.0, mean = 0.0, m2 = 0.0;
+  for (int ch = 0; ch < chunks; ++ch) {
+    const long long left = rows - (long long)ch * kBnRows;
+    const double nb = (double)(left < kBnRows ? left : kBnRows);
+    const long long at = ((long long)k * chunks + ch) * C + c;
+    const double mb = (double)pmean[at], m2b = (double)pm2[at];
+    const double tot = n + nb, dlt = mb - mean;
+    mean += dlt * (nb / tot);
+    m2 += m2b + dlt * dlt * (n * nb / tot);
+    n = tot;
+  }
+  stats[((long long)k * 2) * C + c] = (float)mean;
+  stats[((long long)k * 2 + 1) * C + c] = (float)(1.0 / sqrt(m2 / n + (double)eps));
+}
+
+// out = relu(gamma (Z - mean) inv_std + beta).  One thread per 16-byte word.
+__global__ __launch_bounds__(kThreads) void bn_apply_kernel(const float* __restrict__ Z,
+                                                            const float* __restrict__ stats,
+                                                            const float* __restrict__ params,
+                                                            long long strideParams, long long gam_off,
+                                                            long long bet_off, float* __restrict__ out,
+                                                            long long rows, int C, long long total) {
+  const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= total) return;
+  const int words = C / 4;
+  const int c = (int)(idx % words) * 4;
+  const int k = (int)(idx / words / rows);
+  const f32x4 mu = *reinterpret_cast<const f32x4*>(stats + ((long long)k * 2) * C + c);
+  const f32x4 inv = *reinterpret_cast<const f32x4*>(stats + ((long long)k * 2 + 1) * C + c);
+  const f32x4 ga = *reinterpret_cast<const f32x4*>(params + k * strideParams + gam_off + c);
+  const f32x4 be = *reinterpret_cast<const f32x4*>(params + k * strideParams + bet_off + c);
+  const f32x4 z = *reinterpret_cast<const f32x4*>(Z + idx * 4);
+  f32x4 y = ga * ((z - mu) * inv) + be;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) y[r] = y[r] > 0.f ? y[r] : 0.f;
+  *reinterpret_cast<f32x4*>(out + idx * 4) = y;
+}
+
+// Chunk sums for the backward pass: part[k][chunk][0..C) = sum dY Xh, [C..2C) = sum dY, with
+// Xh = (Z - mean) inv_std recomputed from Z.
+__global__ __launch_bounds__(kThreads) void bn_backward_partial_kernel(const float* __restrict__ Z,
+                                                                       const float* __restrict__ dY,
+                                                                       const float* __restrict__ stats,
+                                                                       float* __restrict__ part,
+                                                                       long long rows, int C, int chunks) {
+  __shared__ f32x4 buf[kThreads];
+  const ChunkThread t = chunk_thread(C);
+  const int k = blockIdx.y;
+  const long long r0 = (long long)blockIdx.x * kBnRows;
+  const long long r1 = r0 + kBnRows < rows ? r0 + kBnRows : rows;
+  const long long base = ((long long)k * rows) * C + 4 * t.w;
+  const bool live = t.grp < t.groups;
+  f32x4 sg = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+  if (live) {
+    const f32x4 mu = *reinterpret_cast<const f32x4*>(stats + ((long long)k * 2) * C + 4 * t.w);
+    const f32x4 inv = *reinterpret_cast<const f32x4*>(stats + ((long long)k * 2 + 1) * C + 4 * t.w);
+    for (long long r = r0 + t.grp; r < r1; r += t.groups) {
+      const f32x4 dy = *reinterpret_cast<const f32x4*>(dY + base + r * C);
+      const f32x4 xh = (*reinterpret_cast<const f32x4*>(Z + base + r * C) - mu) * inv;
+      sg += dy * xh;
+      sb += dy;
+    }
+  }
+  const f32x4 tg = combine_groups(sg, t, buf);
+  const f32x4 tb = combine_groups(sb, t, buf);
+  if (live && t.grp == 0) {
+    float* dst = part + ((long long)k * chunks + blockIdx.x) * 2 * C + 4 * t.w;
+    *reinterpret_cast<f32x4*>(dst) = tg;
+    *reinterpret_cast<f32x4*>(dst + C) = tb;
+  }
+}
+
+// dZ = gamma inv_std (dY - dbeta / N - Xh dgamma / N), in place over dY.
+__global__ __launch_bounds__(kThreads) void bn_backward_apply_kernel(
+    const float* __restrict__ Z, float* __restrict__ dY, const float* __restrict__ stats,
+    const float* __restrict__ params, const float* __restrict__ grad, long long strideParams,
+    long long gam_off, long long bet_off, long long rows, int C, long long total) {
+  const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= total) return;
+  const int words = C / 4;
+  const int c = (int)(idx % words) * 4;
+  const int k = (int)(idx / words / rows);
+  const f32x4 mu = *reinterpret_cast<const f32x4*>(stats + ((long long)k * 2) * C + c);
+  const f32x4 inv = *reinterpret_cast<const f32x4*>(stats + ((long long)k * 2 + 1) * C + c);
+  const f32x4 ga = *reinterpret_cast<const f32x4*>(params + k * strideParams + gam_off + c);
+  const f32x4 dga = *reinterpret_cast<const f32x4*>(grad + k * strideParams + gam_off + c);
+  const f32x4 dbe = *reinterpret_cast<const f32x4*>(grad + k * strideParams + bet_off + c);
+  const float inv_n = 1.f / (float)rows;
+  const f32x4 xh = (*reinterpret_cast<const f32x4*>(Z + idx * 4) - mu) * inv;
+  const f32x4 dy = *reinterpret_cast<const f32x4*>(dY + idx * 4);
+  *reinterpret_cast<f32x4*>(dY + idx * 4) = ga * inv * (dy - dbe * inv_n - xh * (dga * inv_n));
+}
+
 unsigned blocks_for(long long total) { return (unsigned)((total + kThreads - 1) / kThreads); }
 
 }  // namespace
@@ -454,15 +623,15 @@ static FirstConv first_shape(int H, int W, int Cout, int64_t rows, int64_t strid
 }
 
 int launch_first_conv_forward(const float* X, const float* params, int64_t strideParams, int64_t w_off,
-                              int64_t b_off, int ldw, float* out, int K, int64_t rows, int H, int W,
-                              int C, int Cout, hipStream_t s) {
+                              int64_t b_off, int ldw, float* out, int relu, int K, int64_t rows, int H,
+                              int W, int C, int Cout, hipStream_t s) {
   if (!first_conv_fits(C, Cout, rows)) return -1;
   const FirstConv f = first_shape(H, W, Cout, rows, strideParams, ldw);
   const dim3 grid((unsigned)((rows + 127) / 128), (unsigned)K);
   const size_t lds = (size_t)Cout * 33 * 4;
-  if (C == 1) first_conv_forward_kernel<1><<<grid, kThreads, lds, s>>>(X, params, w_off, b_off, out, f);
-  else if (C == 2) first_conv_forward_kernel<2><<<grid, kThreads, lds, s>>>(X, params, w_off, b_off, out, f);
-  else first_conv_forward_kernel<3><<<grid, kThreads, lds, s>>>(X, params, w_off, b_off, out, f);
+  if (C == 1) first_conv_forward_kernel<1><<<grid, kThreads, lds, s>>>(X, params, w_off, b_off, out, f, relu);
+  else if (C == 2) first_conv_forward_kernel<2><<<grid, kThreads, lds, s>>>(X, params, w_off, b_off, out, f, relu);
+  else first_conv_forward_kernel<3><<<grid, kThreads, lds, s>>>(X, params, w_off, b_off, out, f, relu);
   return 0;
 }
 
@@ -480,6 +649,42 @@ int launch_first_conv_wgrad(const float* X, const float* dout, float* partial, f
   first_conv_wgrad_finish_kernel<<<dim3((unsigned)(Cout / 2), (unsigned)K), 1024, 0, s>>>(
       partial, chunks, C, grad, w_off, b_off, sumsq, sumsq_stride, f);
   return Cout / 2;     // sum-of-squares slots written per replica
+}
+
+int bn_chunks(int64_t rows) { return (int)((rows + kBnRows - 1) / kBnRows); }
+
+int launch_bn_forward(const float* Z, float* scratch, float* stats, const float* params,
+                      int64_t strideParams, int64_t gam_off, int64_t bet_off, float* out, int K,
+                      int64_t rows, int C, float eps, hipStream_t s) {
+  if (C % 4 || C < 4 || C > 4 * kThreads || rows < 1) return -1;
+  const int chunks = bn_chunks(rows);
+  float* pmean = scratch;
+  float* pm2 = scratch + (long long)K * chunks * C;
+  bn_stats_partial_kernel<<<dim3((unsigned)chunks, (unsigned)K), kThreads, 0, s>>>(Z, pmean, pm2, rows, C,
+                                                                                  chunks);
+  bn_stats_finish_kernel<<<dim3((unsigned)((C + kThreads - 1) / kThreads), (unsigned)K), kThreads, 0, s>>>(
+      pmean, pm2, stats, rows, C, chunks, eps);
+  const long long total = (long long)K * rows * (C / 4);
+  bn_apply_kernel<<<blocks_for(total), kThreads, 0, s>>>(Z, stats, params, strideParams, gam_off, bet_off,
+                                                        out, rows, C, total);
+  return 0;
+}
+
+int launch_bn_backward_partials(const float* Z, const float* dY, const float* stats, float* part, int K,
+                                int64_t rows, int C, hipStream_t s) {
+  if (C % 4 || C < 4 || C > 4 * kThreads || rows < 1) return -1;
+  const int chunks = bn_chunks(rows);
+  bn_backward_partial_kernel<<<dim3((unsigned)chunks, (unsigned)K), kThreads, 0, s>>>(Z, dY, stats, part,
+                                                                                     rows, C, chunks);
+  return chunks;
+}
+
+void launch_bn_backward_apply(const float* Z, float* dY, const float* stats, const float* params,
+                              const float* grad, int64_t strideParams, int64_t gam_off, int64_t bet_off,
+                              int K, int64_t rows, int C, hipStream_t s) {
+  const long long total = (long long)K * rows * (C / 4);
+  bn_backward_apply_kernel<<<blocks_for(total), kThreads, 0, s>>>(Z, dY, stats, params, grad, strideParams,
+                                                                 gam_off, bet_off, rows, C, total);
 }
 
 int colsum_chunks(int64_t rows) { return (int)((rows + kColsumRows - 1) / kColsumRows); }

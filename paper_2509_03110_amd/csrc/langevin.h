@@ -21,7 +21,7 @@ namespace lsam {
 struct NoiseSeg {
   int64_t begin, end;     // flat offsets inside a replica
   int32_t ld, cols;
-  int32_t code;           // 2 * layer + is_bias
+  int32_t code;           // 2 * layer + is_bias; 32 + 2 * layer (+ 1) for a layer's gamma (beta)
   int32_t pad_;
 };
 struct NoiseMap {
@@ -29,7 +29,7 @@ struct NoiseMap {
   uint32_t key0, key1, step;
   float amp;                              // sigma * sqrt(2 eta)
   int64_t raw_n;
-  NoiseSeg seg[2 * LSAM_MAX_LAYERS];
+  NoiseSeg seg[4 * LSAM_MAX_LAYERS];
 };
 struct NoNoise {};
 

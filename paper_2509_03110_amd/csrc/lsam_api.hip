@@ -98,6 +98,8 @@ struct Layer {
   int ldw;              // row pitch of W in the padded layout (floats)
   int64_t w_off, b_off; // offsets inside one replica of the padded layout (floats)
   int64_t w_flat, b_flat; // offsets inside the public flat layout
+  bool bn = false;        // batch-normalised convolution: gamma and beta follow the bias
+  int64_t gam_off = 0, bet_off = 0, gam_flat = 0, bet_flat = 0;
 };
 
 // One 3x3 convolution layer: image [H][W][Cin] -> [H][W][Cout] (-> [H/2][W/2][Cout] if pooled).
@@ -113,6 +115,8 @@ struct ConvLayer {
   // in kernels of their own (no unfolded image at all).
   bool direct_in, direct_dx, first;
   size_t first_partial;   // scratch of the first layer's weight gradient
+  bool bn;                // batch-normalised: `z` keeps the convolution's output, `stats` the
+  size_t z, stats;        // per-channel mean and 1/sqrt(var + eps) of each replica
   size_t col, out, pooled, dout, dpooled, wt;   // workspace offsets ([K] contiguous replicas each)
 };
 
@@ -163,10 +167,13 @@ int check_config(const lsam_config* c) {
     if (c->n_conv < 0 || c->n_conv >= c->n_layers)
       return fail(LSAM_EINVAL, "n_conv=%d must leave at least one dense layer of %d", c->n_conv,
                   c->n_layers);
+    if (c->n_conv == 0 && c->bn_mask) return fail(LSAM_EINVAL, "bn_mask needs convolution layers");
     if (c->n_conv > 0) {
       if (c->gemm_dtype != LSAM_GEMM_FP32)
         return fail(LSAM_EINVAL, "the convolutional model runs in fp32 only");
       if (c->img_h < 1 || c->img_w < 1) return fail(LSAM_EINVAL, "img_h, img_w must be >= 1");
+      if (c->bn_mask >> c->n_conv) return fail(LSAM_EINVAL, "bn_mask names a layer that is no convolution");
+      if (c->bn_mask && !(c->bn_eps > 0.f)) return fail(LSAM_EINVAL, "bn_eps must be > 0");
       int64_t h = c->img_h, w = c->img_w;
       for (int l = 0; l < c->n_conv; ++l) {
         if (c->dims[l + 1] % 8)
@@ -266,6 +273,16 @@ void build_layout(const lsam_config& c, Layout& lo) {
       flat += (int64_t)s.out * s.in;
       s.b_flat = flat;
       flat += s.out;
+      if (l < lo.n_conv && ((c.bn_mask >> l) & 1u)) {
+        s.bn = true;
+        s.gam_off = off;
+        off = round_up(off + s.out, 64);
+        s.bet_off = off;
+        off = round_up(off + s.out, 64);
+        s.gam_flat = flat;
+        s.bet_flat = flat + s.out;
+        flat += 2 * (int64_t)s.out;
+      }
       lo.layers.push_back(s);
     }
     lo.d = flat;
@@ -296,7 +313,8 @@ void build_layout(const lsam_config& c, Layout& lo) {
     int64_t cap = 0;
     for (const Layer& ly : lo.layers)
       cap += std::max(gemm_sumsq_capacity(ly.out, ly.in) + (ly.out + 63) / 64,
-                      std::max(head_sumsq_slots(ly.in), ly.out / 2));   // ly.out / 2: first-layer kernels
+                      std::max(head_sumsq_slots(ly.in), ly.out / 2)) +   // ly.out / 2: first-layer kernels
+             (ly.bn ? 2 * ((ly.out + 63) / 64) : 0);
     lo.nblk = (int)cap;
   }
 
@@ -335,6 +353,11 @@ void build_layout(const lsam_config& c, Layout& lo) {
       if (cv.direct_dx) cv.wt = take(cur, (size_t)lo.K * cv.Cin * 9 * cv.Cout * 4);
       cv.out = take(cur, full);
       cv.dout = take(cur, full);
+      cv.bn = lo.layers[l].bn;
+      if (cv.bn) {
+        cv.z = take(cur, full);
+        cv.stats = take(cur, (size_t)lo.K * 2 * cv.Cout * 4);
+      }
       if (cv.pool) {
         cv.pooled = take(cur, full / 4);
         cv.dpooled = take(cur, full / 4);
@@ -346,6 +369,8 @@ void build_layout(const lsam_config& c, Layout& lo) {
       size_t most = 0;
       for (const ConvLayer& cv : lo.conv)
         most = std::max(most, (size_t)lo.K * colsum_chunks(cv.rows) * cv.Cout * 4);
+      for (const ConvLayer& cv : lo.conv)
+        if (cv.bn) most = std::max(most, (size_t)lo.K * bn_chunks(cv.rows) * 2 * cv.Cout * 4);
       lo.colsum = take(cur, most);
     }
     // the dense layers start at n_conv; their input and its gradient are the last
@@ -391,11 +416,11 @@ void build_layout(const lsam_config& c, Layout& lo) {
 // ---- per-kernel timing ---------------------------------------------------------------------------
 enum KernelClass {
   KC_GEMM_FWD = 0, KC_GEMM_DX, KC_GEMM_DW, KC_SOFTMAX_CE, KC_BIAS_GRAD, KC_SUMSQ, KC_NORM_FINISH,
-  KC_PERTURB, KC_DESCENT, KC_CENTER, KC_MISC, KC_HEAD, KC_UNFOLD, KC_POOL, KC_CONV_FIRST, KC_COUNT
+  KC_PERTURB, KC_DESCENT, KC_CENTER, KC_MISC, KC_HEAD, KC_UNFOLD, KC_POOL, KC_CONV_FIRST, KC_BATCHNORM, KC_COUNT
 };
 const char* const kClassNames[KC_COUNT] = {
     "gemm_fwd", "gemm_dx", "gemm_dw", "softmax_ce", "bias_grad", "sumsq_partials", "norm_finish",
-    "perturb", "descent", "center", "misc", "head", "unfold_fold", "pool", "conv_first"};
+    "perturb", "descent", "center", "misc", "head", "unfold_fold", "pool", "conv_first", "batchnorm"};
 
 struct TimedLaunch {
   int cls;
@@ -507,8 +532,8 @@ int conv_forward(lsam_ctx* c, const float* X, const float* params) {
     if (cv.first) {
       LaunchTimer t(c, KC_CONV_FIRST);
       if (launch_first_conv_forward(in, params, lo.d_pad, ly.w_off, ly.b_off, ly.ldw,
-                                    c->at<float>(cv.out), lo.K, cv.rows, cv.H, cv.W, cv.Cin, cv.Cout,
-                                    s) != 0)
+                                    c->at<float>(cv.bn ? cv.z : cv.out), cv.bn ? 0 : 1, lo.K, cv.rows,
+                                    cv.H, cv.W, cv.Cin, cv.Cout, s) != 0)
         return fail(LSAM_EINVAL, "first convolution rejected");
     } else if (!cv.direct_in) {
       LaunchTimer t(c, KC_UNFOLD);
@@ -524,13 +549,20 @@ int conv_forward(lsam_ctx* c, const float* X, const float* params) {
         d.unfold = 1; d.unfold_C = cv.Cin; d.unfold_H = cv.H; d.unfold_W = cv.W;
       }
       d.B = params + ly.w_off; d.strideB = lo.d_pad; d.ldB = ly.ldw; d.b_kmajor = 1;
-      d.C = c->at<float>(cv.out); d.strideC = cv.rows * cv.Cout; d.ldC = cv.Cout;
+      d.C = c->at<float>(cv.bn ? cv.z : cv.out); d.strideC = cv.rows * cv.Cout; d.ldC = cv.Cout;
       d.M = (int)cv.rows; d.N = cv.Cout; d.Kd = ly.in; d.batch = lo.K;
-      d.epilogue = EPI_BIAS_RELU;
+      d.epilogue = cv.bn ? EPI_BIAS : EPI_BIAS_RELU;
       d.bias = params + ly.b_off; d.strideBias = lo.d_pad;
       split(c, d);
       LaunchTimer t(c, KC_GEMM_FWD);
       if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "forward GEMM of convolution %d rejected", l);
+    }
+    if (cv.bn) {
+      LaunchTimer t(c, KC_BATCHNORM);
+      if (launch_bn_forward(c->at<float>(cv.z), c->at<float>(lo.colsum), c->at<float>(cv.stats), params,
+                            lo.d_pad, ly.gam_off, ly.bet_off, c->at<float>(cv.out), lo.K, cv.rows,
+                            cv.Cout, c->cfg.bn_eps, s) != 0)
+        return fail(LSAM_EINVAL, "batch normalisation of convolution %d rejected", l);
     }
     in = c->at<float>(cv.out);
     if (cv.pool) {
@@ -559,6 +591,23 @@ int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq,
       if (launch_maxpool2_backward(c->at<float>(cv.out), c->at<float>(cv.dpooled), dout,
                                    (int64_t)lo.K * lo.B, cv.H, cv.W, cv.Cout, s) != 0)
         return fail(LSAM_EINVAL, "pool backward of convolution %d rejected", l);
+    }
+    if (cv.bn) {
+      // dout holds the gradient behind the ReLU; turn it into the gradient of the convolution's
+      // output and leave dgamma, dbeta in g
+      LaunchTimer t(c, KC_BATCHNORM);
+      float* part = c->at<float>(lo.colsum);
+      const int chunks = launch_bn_backward_partials(c->at<float>(cv.z), dout, c->at<float>(cv.stats),
+                                                     part, lo.K, cv.rows, cv.Cout, s);
+      if (chunks < 0) return fail(LSAM_EINVAL, "batch normalisation of convolution %d rejected", l);
+      int used = launch_bias_grad(part, 2 * cv.Cout, 0, g + ly.gam_off, lo.d_pad, lo.K, chunks, cv.Cout,
+                                  ssq ? ssq + *slots : nullptr, lo.nblk, s);
+      if (ssq) *slots += used;
+      used = launch_bias_grad(part + cv.Cout, 2 * cv.Cout, 0, g + ly.bet_off, lo.d_pad, lo.K, chunks,
+                              cv.Cout, ssq ? ssq + *slots : nullptr, lo.nblk, s);
+      if (ssq) *slots += used;
+      launch_bn_backward_apply(c->at<float>(cv.z), dout, c->at<float>(cv.stats), params, g, lo.d_pad,
+                               ly.gam_off, ly.bet_off, lo.K, cv.rows, cv.Cout, s);
     }
     if (cv.first) {
       LaunchTimer t(c, KC_CONV_FIRST);
@@ -901,6 +950,12 @@ int copy_in(lsam_ctx* c, const float* src_flat, float* dst_dev) {
     }
     if ((rc = to_device(c, dst_dev + ly.b_off, src_flat + ly.b_flat, (size_t)ly.out * 4)) != LSAM_OK)
       return rc;
+    if (ly.bn) {
+      if ((rc = to_device(c, dst_dev + ly.gam_off, src_flat + ly.gam_flat, (size_t)ly.out * 4)) != LSAM_OK)
+        return rc;
+      if ((rc = to_device(c, dst_dev + ly.bet_off, src_flat + ly.bet_flat, (size_t)ly.out * 4)) != LSAM_OK)
+        return rc;
+    }
   }
   return LSAM_OK;
 }
@@ -923,6 +978,12 @@ int copy_out(lsam_ctx* c, const float* src_dev, float* dst_flat) {
     }
     if ((rc = to_host(c, dst_flat + ly.b_flat, src_dev + ly.b_off, (size_t)ly.out * 4)) != LSAM_OK)
       return rc;
+    if (ly.bn) {
+      if ((rc = to_host(c, dst_flat + ly.gam_flat, src_dev + ly.gam_off, (size_t)ly.out * 4)) != LSAM_OK)
+        return rc;
+      if ((rc = to_host(c, dst_flat + ly.bet_flat, src_dev + ly.bet_off, (size_t)ly.out * 4)) != LSAM_OK)
+        return rc;
+    }
   }
   return LSAM_OK;
 }
@@ -1016,6 +1077,12 @@ int lsam_init(const lsam_config* cfg, const float* init_params, int64_t n_init, 
       NoiseSeg b{ly.b_off, ly.b_off + ly.out, (int32_t)round_up(ly.out, 4), ly.out, 2 * l + 1, 0};
       nm.seg[nm.n++] = w;
       nm.seg[nm.n++] = b;
+      if (ly.bn) {
+        NoiseSeg ga{ly.gam_off, ly.gam_off + ly.out, (int32_t)round_up(ly.out, 4), ly.out, 32 + 2 * l, 0};
+        NoiseSeg be{ly.bet_off, ly.bet_off + ly.out, (int32_t)round_up(ly.out, 4), ly.out, 33 + 2 * l, 0};
+        nm.seg[nm.n++] = ga;
+        nm.seg[nm.n++] = be;
+      }
     }
   }
   c->lr = cfg->lr;

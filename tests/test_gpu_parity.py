@@ -531,6 +531,13 @@ CNN_SMALL = workloads.Workload("cnn_small", K=2, dims=(3, 8, 16, 24, 5), batch=6
                                               img_h=4, img_w=6, batch=43)),
     ("four convolutions, one of each kind and two pools", dict(
         dims=(3, 32, 32, 24, 40, 10), n_conv=4, pool_mask=0b0110, n_classes=10, batch=8)),
+    # batch normalisation, on each kind of convolution
+    ("batch norm on stored-unfold layers", dict(bn_mask=0b11)),
+    ("batch norm on the second layer only, no pools", dict(bn_mask=0b10, pool_mask=0, img_h=4, img_w=6)),
+    ("batch norm with first-layer kernels and unfolding inside the GEMM", dict(
+        dims=(3, 32, 32, 64, 10), n_conv=3, pool_mask=0b101, bn_mask=0b111, n_classes=10, batch=5)),
+    ("batch norm in a four-convolution stack", dict(
+        dims=(3, 32, 32, 24, 40, 10), n_conv=4, pool_mask=0b0110, bn_mask=0b1010, n_classes=10, batch=8)),
     ("unfolding inside the GEMM, sides not powers of two", dict(
         dims=(4, 32, 64, 12, 6), n_conv=2, pool_mask=0b10, img_h=6, img_w=10, n_classes=6, batch=7)),
 ])
@@ -592,9 +599,34 @@ def test_cnn_exact_decisions_tight_gradients():
     g.close()
 
 
+def test_batchnorm_gradients_layer_by_layer():
+    # gamma, beta and everything below a normalised layer, one step from a common point; the
+    # batch is large enough that the chunked statistics span several chunks and a ragged one
+    w = CNN_SMALL.scaled(K=2, batch=11, img_h=8, img_w=8, bn_mask=0b11, tau=(2, 2))
+    g, o = make_pair(w)
+    X, lab = workloads.batch(w, 0)
+    X = X + np.float32(3.0)            # a mean far from zero: the variance must not lose digits
+    Xd, ld = to_dev(X, lab, w)
+    g.lsam_step(Xd, ld)
+    o.step(X, lab)
+    assert np.allclose(g.lsam_get_norms(), o.last_norm, rtol=1e-4)
+    for i in range(w.K):
+        g2 = g.lsam_get_buffer(lsam.BUF_GRAD, i)
+        for l, (o0, o1, o2) in enumerate(o.model.offsets):
+            close_enough(g2[o0:o1], o.last_g2[i][o0:o1], 1e-3, "dW%d of replica %d" % (l + 1, i))
+        for l, (g0, g1, g2_) in o.model.bn_offsets.items():
+            close_enough(g2[g0:g1], o.last_g2[i][g0:g1], 1e-3, "dgamma%d of replica %d" % (l + 1, i))
+            close_enough(g2[g1:g2_], o.last_g2[i][g1:g2_], 1e-3, "dbeta%d of replica %d" % (l + 1, i))
+        # the bias below a normalisation has no influence: its gradient is rounding noise
+        for l in o.model.bn_offsets:
+            o0, o1, o2 = o.model.offsets[l]
+            assert np.max(np.abs(g2[o1:o2])) < 1e-4 * np.max(np.abs(g2[o0:o1]))
+    g.close()
+
+
 def test_cnn_data_parallel_and_langevin():
     for over in (dict(algorithm=lsam.ALG_DATA_PARALLEL), dict(noise_scale=0.01, noise_seed=5),
-                 dict(rho=0.0)):
+                 dict(rho=0.0), dict(noise_scale=0.01, noise_seed=6, bn_mask=0b01)):
         w = CNN_SMALL.scaled(**over)
         run_mlp(w, 4, 1e-4, 1e-3)
 
@@ -603,7 +635,9 @@ def test_cnn_rejects_what_it_cannot_run():
     for over, msg in ((dict(dims=(3, 8, 12, 24, 5)), "multiples of 8"),
                       (dict(img_h=6, img_w=6), "even image sides"),
                       (dict(gemm_dtype=1), "fp32 only"),
-                      (dict(n_conv=4), "at least one dense layer")):
+                      (dict(n_conv=4), "at least one dense layer"),
+                      (dict(bn_mask=0b100), "no convolution"),
+                      (dict(bn_mask=0b1, bn_eps=0.0), "bn_eps")):
         w = CNN_SMALL.scaled(**over)
         cfg, keep = lsam.config_from_workload(w)
         assert lsam.lsam_workspace_bytes(cfg) == 0

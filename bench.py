@@ -32,20 +32,23 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "9dc1539e2998936a"
+TRAFFIC_SOURCES = "572b3fedd0efe275"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43724032,
-             "gemm_dx": 42126677, "gemm_fwd": 62121845, "perturb": 201945557},
-    "cfg3": {"bias_grad": 13681877, "center": 1773570112, "descent": 17231926208, "gemm_dw":
-             446145738, "gemm_dx": 250125387, "gemm_fwd": 233098514, "perturb": 5065989035,
+    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43722571,
+             "gemm_dx": 42126677, "gemm_fwd": 62121835, "perturb": 201945600},
+    "cfg3": {"bias_grad": 13681916, "center": 1773570304, "descent": 17232014251, "gemm_dw":
+             445810751, "gemm_dx": 250125371, "gemm_fwd": 233098089, "perturb": 5065988309,
              "softmax_ce": 1428821},
-    "cfg4": {"center": 3200044544, "descent": 25600046635, "perturb": 9600050432,
-             "sumsq_partials": 3416541867},
-    "cfg5": {"bias_grad": 118030350, "descent": 188962528704, "gemm_dw": 4957139288, "gemm_dx":
-             2332894119, "gemm_fwd": 2034389497, "perturb": 59024472619, "softmax_ce": 95545392},
-    "cnn5": {"bias_grad": 17140316, "conv_first": 80455893, "descent": 79476736, "gemm_dw":
-             168179214, "gemm_dx": 34786645, "gemm_fwd": 38359868, "perturb": 29813760, "pool":
-             68581963},
+    "cfg4": {"center": 3200045056, "descent": 25600046165, "perturb": 9600050261,
+             "sumsq_partials": 3417012992},
+    "cfg5": {"bias_grad": 118063809, "descent": 188958937195, "gemm_dw": 4962797405, "gemm_dx":
+             2332908786, "gemm_fwd": 2035124414, "perturb": 59024470997, "softmax_ce": 95326320},
+    "cnn5": {"bias_grad": 17140316, "conv_first": 80458912, "descent": 79476736, "gemm_dw":
+             168374187, "gemm_dx": 34786645, "gemm_fwd": 38356015, "perturb": 29813760, "pool":
+             68574805},
+    "cnn5bn": {"batchnorm": 172308839, "bias_grad": 17140316, "conv_first": 80454155, "descent":
+             79542272, "gemm_dw": 168964395, "gemm_dx": 34786645, "gemm_fwd": 38355328, "perturb":
+             29838336, "pool": 68574588},
 }
 
 
@@ -118,7 +121,7 @@ def conv_bytes(w):
     read), where its gradient is stored that is read once (plus the image gradient written);
     the pool reads its input and writes a quarter of it, its backward pass reads both and
     writes the full-size gradient."""
-    unfold = pool = 0.0
+    unfold = pool = bn = 0.0
     rows = layer_rows(w)
     modes = conv_modes(w) if w.n_conv else []
     for l in range(w.n_conv):
@@ -129,7 +132,13 @@ def conv_bytes(w):
             unfold += rows[l] * (9 * cin + cin) * 4.0
         if (w.pool_mask >> l) & 1:
             pool += rows[l] * cout * 4.0 * (1.25 + 2.25)
+        if (w.bn_mask >> l) & 1:
+            # statistics read Z; normalise+ReLU reads Z, writes the activation; the backward
+            # sums read Z and dY; the backward apply reads Z and dY and writes dZ
+            bn += rows[l] * cout * 4.0 * (1 + 2 + 2 + 3)
     out = {}
+    if bn:
+        out["batchnorm"] = 2 * bn * w.K
     if unfold:
         out["unfold_fold"] = 2 * unfold * w.K
     if pool:
@@ -244,7 +253,7 @@ def main():
     w = workloads.WORKLOADS[args.workload]
     if args.algorithm or args.noise_scale:
         w = w.scaled(algorithm=args.algorithm, noise_scale=args.noise_scale, noise_seed=1)
-    steps = args.steps if args.steps is not None else {"cfg1": 200, "cfg2": 200, "cnn5": 100}.get(w.name, 20)
+    steps = args.steps if args.steps is not None else {"cfg1": 200, "cfg2": 200, "cnn5": 100, "cnn5bn": 100}.get(w.name, 20)
 
     cfg, keep = lsam.config_from_workload(w)
     eng = lsam.Lsam(cfg, workloads.init_params(w), device=dev, keep=keep)
@@ -325,7 +334,8 @@ def main():
         "dtype": "f32" if (w.gemm_dtype == 0) else "bf16 operands, f32 accumulate and master weights",
         "data": "synthetic",
         "config": {"workload": w.name, "K": w.K, "dims": list(w.dims), "n_conv": w.n_conv,
-                   "image": [w.img_h, w.img_w], "d": w.d, "batch": w.batch,
+                   "image": [w.img_h, w.img_w], "pool_mask": w.pool_mask, "bn_mask": w.bn_mask,
+                   "d": w.d, "batch": w.batch,
                    "rho": w.rho, "lr": w.lr, "momentum": w.momentum, "algorithm": w.algorithm,
                    "noise_scale": w.noise_scale,
                    "periods": eng.lsam_get_schedule()[0]},

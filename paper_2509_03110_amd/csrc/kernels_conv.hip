@@ -416,8 +416,7 @@ __global__ __launch_bounds__(1024) void first_conv_wgrad_finish_kernel(const flo
 // (Appendix "Batch Normalization": each worker uses the statistics of its own minibatch.)
 // Z is [K][rows][C] (C % 4 == 0, C <= 1024).  Statistics in one pass over Z that does not lose
 // digits when |mean| >> spread: every chunk of kBnRows rows gets its own mean and its own sum of
-// squared deviations from that mean; the chunks are combined with the pairwise-update formula
-// in double, in chunk order.
+// squared deviations from that mean; the chunks are then combined in double, in a fixed order.
 constexpr int kBnRows = 256;
 
 // Column sums of up to two quantities over a chunk of rows; thread = (column word, row group).
@@ -478,29 +477,51 @@ __global__ __launch_bounds__(kThreads) void bn_stats_partial_kernel(const float*
   }
 }
 
-// stats[k][0][c] = mean, stats[k][1][c] = 1 / sqrt(var + eps), var = M2 / rows (biased).
-// One thread per (k, c): the chunks' (n, mean, M2) are merged in chunk order.
-__global__ __launch_bounds__(kThreads) void bn_stats_finish_kernel(const float* __restrict__ pmean,
-                                                                   const float* __restrict__ pm2,
-                                                                   float* __restrict__ stats,
-                                                                   long long rows, int C, int chunks,
-                                                                   float eps) {
-  const int c = blockIdx.x * kThreads + threadIdx.x;
-  const int k = blockIdx.y;
-  if (c >= C) return;
-  double n = 0.0, mean = 0.0, m2 = 0.0;
-  for (int ch = 0; ch < chunks; ++ch) {
-    const long long left = rows - (long long)ch * kBnRows;
-    const double nb = (double)(left < kBnRows ? left : kBnRows);
-    const long long at = ((long long)k * chunks + ch) * C + c;
-    const double mb = (double)pmean[at], m2b = (double)pm2[at];
-    const double tot = n + nb, dlt = mb - mean;
-    mean += dlt * (nb / tot);
-    m2 += m2b + dlt * dlt * (n * nb / tot);
-    n = tot;
+// stats[k][0][c] = mean, stats[k][1][c] = 1 / sqrt(var + eps), var = M2 / rows (biased):
+//   mean = sum_i n_i mean_i / rows,   M2 = sum_i [M2_i + n_i (mean_i - mean)^2]
+// over the chunks i, in double.  Workgroup (block, k) serves 64 columns with 16 chains each
+// (chain q takes chunks q, q + 16, ...); the chains are added in a fixed tree through LDS.
+constexpr int kBnChains = 16;
+__device__ __forceinline__ double chain_total(double v, double (*buf)[64], int q, int col) {
+  __syncthreads();
+  buf[q][col] = v;
+  __syncthreads();
+#pragma unroll
+  for (int half = kBnChains / 2; half > 0; half >>= 1) {
+    if (q < half) buf[q][col] += buf[q + half][col];
+    __syncthreads();
   }
-  stats[((long long)k * 2) * C + c] = (float)mean;
-  stats[((long long)k * 2 + 1) * C + c] = (float)(1.0 / sqrt(m2 / n + (double)eps));
+  return buf[0][col];
+}
+__global__ __launch_bounds__(64 * kBnChains) void bn_stats_finish_kernel(
+    const float* __restrict__ pmean, const float* __restrict__ pm2, float* __restrict__ stats,
+    long long rows, int C, int chunks, float eps) {
+  __shared__ double buf[kBnChains][64];
+  const int col = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + col;
+  const int k = blockIdx.y;
+  const bool live = c < C;
+  auto count = [&](int ch) {
+    const long long left = rows - (long long)ch * kBnRows;
+    return (double)(left < kBnRows ? left : kBnRows);
+  };
+  double s1 = 0.0;
+  if (live)
+    for (int ch = q; ch < chunks; ch += kBnChains)
+      s1 += count(ch) * (double)pmean[((long long)k * chunks + ch) * C + c];
+  const double mean = chain_total(s1, buf, q, col) / (double)rows;
+  double s2 = 0.0;
+  if (live)
+    for (int ch = q; ch < chunks; ch += kBnChains) {
+      const long long at = ((long long)k * chunks + ch) * C + c;
+      const double dlt = (double)pmean[at] - mean;
+      s2 += (double)pm2[at] + count(ch) * dlt * dlt;
+    }
+  const double m2 = chain_total(s2, buf, q, col);
+  if (live && q == 0) {
+    stats[((long long)k * 2) * C + c] = (float)mean;
+    stats[((long long)k * 2 + 1) * C + c] = (float)(1.0 / sqrt(m2 / (double)rows + (double)eps));
+  }
 }
 
 // out = relu(gamma (Z - mean) inv_std + beta).  One thread per 16-byte word.
@@ -662,7 +683,7 @@ int launch_bn_forward(const float* Z, float* scratch, float* stats, const float*
   float* pm2 = scratch + (long long)K * chunks * C;
   bn_stats_partial_kernel<<<dim3((unsigned)chunks, (unsigned)K), kThreads, 0, s>>>(Z, pmean, pm2, rows, C,
                                                                                   chunks);
-  bn_stats_finish_kernel<<<dim3((unsigned)((C + kThreads - 1) / kThreads), (unsigned)K), kThreads, 0, s>>>(
+  bn_stats_finish_kernel<<<dim3((unsigned)((C + 63) / 64), (unsigned)K), 64 * kBnChains, 0, s>>>(
       pmean, pm2, stats, rows, C, chunks, eps);
   const long long total = (long long)K * rows * (C / 4);
   bn_apply_kernel<<<blocks_for(total), kThreads, 0, s>>>(Z, stats, params, strideParams, gam_off, bet_off,

@@ -124,6 +124,11 @@ WORKLOADS = {
     "cnn5": Workload("cnn5", K=4, dims=(3, 32, 64, 128, 256, 10), batch=128, n_conv=3, img_h=32,
                      img_w=32, pool_mask=0b111, rho=0.1, lr=0.02, tau=(16, 16, 16, 16),
                      steps=20, data_seed=6, n_classes=10, batch_pool=4),
+    # the same network with every convolution batch-normalised (the paper's deeper models
+    # normalise every layer and keep the statistics per worker, Appendix "Batch Normalization")
+    "cnn5bn": Workload("cnn5bn", K=4, dims=(3, 32, 64, 128, 256, 10), batch=128, n_conv=3, img_h=32,
+                       img_w=32, pool_mask=0b111, bn_mask=0b111, rho=0.1, lr=0.02,
+                       tau=(16, 16, 16, 16), steps=20, data_seed=7, n_classes=10, batch_pool=4),
 }
 
 

@@ -183,7 +183,7 @@ def cpu_baseline(w, budget_s=20.0):
     with threadpool_limits(limits=1):
         if w.dims:
             # one replica; shrink the batch for the two largest workloads
-            frac = {"cfg5": 8, "cfg3": 2}.get(w.name, 1)
+            frac = {"cfg5": 8, "cfg3": 2, "vgg16": 16}.get(w.name, 1)
             ws = w.scaled(K=1, batch=max(w.batch // frac, 1), tau=(10 ** 6,))
             o = oracle_from(ws, workloads.init_params(ws))
             X, lab = workloads.batch(ws, 0)

@@ -176,12 +176,12 @@ int launch_first_conv_wgrad(const float* X, const float* dout, float* partial, f
 // replica and column over the rows.  Forward: stats[k][0][c] = mean, stats[k][1][c] =
 // 1/sqrt(biased variance + eps); out = relu(gamma Xh + beta), Xh = (Z - mean) stats[1], gamma
 // and beta read from params + k * strideParams at gam_off / bet_off.  `scratch`: 2 * K *
-// bn_chunks(rows) * C floats.  Backward: launch_bn_backward_partials leaves chunk sums
+// bn_chunks(rows, C, K) * C floats.  Backward: launch_bn_backward_partials leaves chunk sums
 // part[k][chunk][0..C) = sum dY Xh and [C..2C) = sum dY (returns the chunk count; launch_bias_grad
 // over them gives dgamma and dbeta); launch_bn_backward_apply then overwrites dY with
 // dZ = gamma stats[1] (dY - dbeta/rows - Xh dgamma/rows), dgamma and dbeta read from
 // grad + k * strideParams at the same offsets.  -1: shape not supported.
-int bn_chunks(int64_t rows);
+int bn_chunks(int64_t rows, int C, int K);
 int launch_bn_forward(const float* Z, float* scratch, float* stats, const float* params,
                       int64_t strideParams, int64_t gam_off, int64_t bet_off, float* out, int K,
                       int64_t rows, int C, float eps, hipStream_t s);
@@ -191,14 +191,14 @@ void launch_bn_backward_apply(const float* Z, float* dY, const float* stats, con
                               const float* grad, int64_t strideParams, int64_t gam_off, int64_t bet_off,
                               int K, int64_t rows, int C, hipStream_t s);
 // Wt[k][c][(u,v,o)] = W[k][o][(2-u,2-v,c)] for K filter banks W [Cout][3][3][Cin] (row pitch ldw,
-// replica stride strideW); Wt is dense, [K][Cin][9 Cout].
+// replica stride strideW); Wt is dense, [K][Cin][9 Cout].  Cout must be a multiple of 32.
 void launch_flip_filters(const float* W, int64_t strideW, int ldw, float* Wt, int K, int Cout, int Cin,
                          hipStream_t s);
 // Column sums of K contiguous [rows][N] matrices, first stage: partial[k][chunk][n] = sum of
-// the rows of chunk `chunk` (colsum_chunks(rows) chunks of equal height, the last one ragged);
+// the rows of chunk `chunk` (colsum_chunks(rows, N, K) chunks of equal height, the last one ragged);
 // returns the chunk count, -1 if N is not a multiple of 4 in 4..1024.  launch_bias_grad over
 // the partials finishes the sum.
-int colsum_chunks(int64_t rows);
+int colsum_chunks(int64_t rows, int N, int K);
 int launch_colsum_partials(const float* A, int64_t rows, int N, int K, float* partial, hipStream_t s);
 // 2x2/stride-2 max-pool over `images` contiguous [H][W][C] images, and the backward pass of
 // ReLU-then-pool: dA = dP at the first maximum of each window if it is positive, else 0

@@ -165,51 +165,91 @@ __global__ __launch_bounds__(kThreads) void maxpool2_backward_kernel(const float
   for (int t = 0; t < 4; ++t) *reinterpret_cast<f32x4*>(dA + base + offs[t]) = o[t];
 }
 
-// First stage of the column sums of a tall matrix [rows][N] (N % 4 == 0, N <= 1024): workgroup
-// (chunk, k) adds kColsumRows rows (short chunks: the matrices are tall and few, and the
-// launch needs thousands of workgroups to use the memory system).  Thread = (column word, row group); the row groups are
-// combined through LDS in a fixed order.
-constexpr int kColsumRows = 256;
+// Column reductions over the rows of tall matrices [K][rows][C] (C % 4 == 0) are done in two
+// fixed-order stages.  First stage: workgroup (chunk, k, column block) covers `chunk_rows` rows
+// of 64 columns; thread = (column word w of 16, row group of 16), each group strides over the
+// chunk's rows, the groups are added in group order through LDS.  chunk_rows shrinks from 256
+// towards 32 until the launch has about a thousand workgroups (short matrices would otherwise
+// leave most of the chip idle behind a few long serial sums).
+struct ChunkPlan {
+  int chunk_rows, chunks, col_blocks;
+};
+ChunkPlan chunk_plan(long long rows, int C, int K) {
+  ChunkPlan p;
+  p.col_blocks = (C + 63) / 64;
+  p.chunk_rows = 256;
+  while (p.chunk_rows > 32 &&
+         ((rows + p.chunk_rows - 1) / p.chunk_rows) * p.col_blocks * K < 1024)
+    p.chunk_rows /= 2;
+  p.chunks = (int)((rows + p.chunk_rows - 1) / p.chunk_rows);
+  return p;
+}
+struct ChunkThread {
+  int cw;          // column word (4 columns) of this thread
+  int grp;         // row group 0..15
+  bool live;       // the column word exists
+  long long r0, r1;
+};
+__device__ __forceinline__ ChunkThread chunk_thread(long long rows, int C, int chunk_rows) {
+  ChunkThread t;
+  t.cw = blockIdx.z * 16 + (threadIdx.x & 15);
+  t.grp = threadIdx.x >> 4;
+  t.live = t.cw < C / 4;
+  t.r0 = (long long)blockIdx.x * chunk_rows;
+  t.r1 = t.r0 + chunk_rows < rows ? t.r0 + chunk_rows : rows;
+  return t;
+}
+// Adds `v` over the 16 row groups in group order; the result is valid for grp == 0.
+__device__ __forceinline__ f32x4 combine_groups(f32x4 v, const ChunkThread& t, f32x4* buf) {
+  __syncthreads();
+  buf[threadIdx.x] = v;
+  __syncthreads();
+  f32x4 tot = v;
+  if (t.grp == 0)
+    for (int gq = 1; gq < 16; ++gq) tot += buf[gq * 16 + (threadIdx.x & 15)];
+  return tot;
+}
+
+// partial[k][chunk][c] = sum of the chunk's rows of A.
 __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const float* __restrict__ A,
                                                                   float* __restrict__ partial,
-                                                                  long long rows, int N, int chunks) {
-  __shared__ f32x4 part[kThreads];
-  const int words = N / 4;
-  const int groups = kThreads / words;
-  const int w = threadIdx.x % words, grp = threadIdx.x / words;
+                                                                  long long rows, int N, int chunks,
+                                                                  int chunk_rows) {
+  __shared__ f32x4 buf[kThreads];
+  const ChunkThread t = chunk_thread(rows, N, chunk_rows);
   const int k = blockIdx.y;
-  const long long r0 = (long long)blockIdx.x * kColsumRows;
-  const long long r1 = r0 + kColsumRows < rows ? r0 + kColsumRows : rows;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  if (grp < groups) {
-    const float* base = A + ((long long)k * rows) * N + 4 * w;
-    for (long long r = r0 + grp; r < r1; r += groups) acc += *reinterpret_cast<const f32x4*>(base + r * N);
+  if (t.live) {
+    const float* base = A + ((long long)k * rows) * N + 4 * t.cw;
+    for (long long r = t.r0 + t.grp; r < t.r1; r += 16) acc += *reinterpret_cast<const f32x4*>(base + r * N);
   }
-  part[threadIdx.x] = acc;
-  __syncthreads();
-  if (threadIdx.x < words) {
-    f32x4 tot = part[threadIdx.x];
-    for (int gq = 1; gq < groups; ++gq) tot += part[gq * words + threadIdx.x];
-    *reinterpret_cast<f32x4*>(partial + ((long long)k * chunks + blockIdx.x) * N + 4 * threadIdx.x) = tot;
-  }
+  const f32x4 tot = combine_groups(acc, t, buf);
+  if (t.live && t.grp == 0)
+    *reinterpret_cast<f32x4*>(partial + ((long long)k * chunks + blockIdx.x) * N + 4 * t.cw) = tot;
 }
 
 // Wt[k][c][(u,v,o)] = W[k][o][(2-u, 2-v, c)]: the filter bank as the weight matrix of the
 // convolution that maps the output gradient back to the input (taps mirrored, channels
-// swapped).  One thread per element of Wt, o fastest.
+// swapped).  A 32 x 32 (o, c) tile of one tap per workgroup, transposed through LDS so that both
+// the reads (c contiguous) and the writes (o contiguous) are whole 128-byte rows.  32 | Cout.
 __global__ __launch_bounds__(kThreads) void flip_filters_kernel(const float* __restrict__ W,
                                                                 long long strideW, int ldw,
                                                                 float* __restrict__ Wt, int Cout,
-                                                                int Cin, long long total) {
-  const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
-  if (idx >= total) return;
-  const int o = (int)(idx % Cout);
-  long long rest = idx / Cout;
-  const int tap = (int)(rest % 9);
-  rest /= 9;
-  const int c = (int)(rest % Cin);
-  const long long k = rest / Cin;
-  Wt[idx] = W[k * strideW + (long long)o * ldw + (8 - tap) * Cin + c];
+                                                                int Cin, int cblocks) {
+  __shared__ float tile[32][33];
+  const int ob = (blockIdx.x / cblocks) * 32, cb = (blockIdx.x % cblocks) * 32;
+  const int tap = blockIdx.y;
+  const long long k = blockIdx.z;
+  const int x = threadIdx.x & 31, y = threadIdx.x >> 5;
+  const float* src = W + k * strideW + (long long)(8 - tap) * Cin;
+#pragma unroll
+  for (int r = 0; r < 32; r += 8)
+    tile[y + r][x] = cb + x < Cin ? src[(long long)(ob + y + r) * ldw + cb + x] : 0.f;
+  __syncthreads();
+  float* dst = Wt + k * (long long)Cin * 9 * Cout + (long long)tap * Cout + ob + x;
+#pragma unroll
+  for (int r = 0; r < 32; r += 8)
+    if (cb + y + r < Cin) dst[(long long)(cb + y + r) * 9 * Cout] = tile[x][y + r];
 }
 
 // ---- first convolution layer (1..3 input channels) -------------------------------------------------
@@ -415,63 +455,36 @@ __global__ __launch_bounds__(1024) void first_conv_wgrad_finish_kernel(const flo
 // ---- batch normalisation (training mode, per replica and channel over the B H W rows) -------------
 // (Appendix "Batch Normalization": each worker uses the statistics of its own minibatch.)
 // Z is [K][rows][C] (C % 4 == 0, C <= 1024).  Statistics in one pass over Z that does not lose
-// digits when |mean| >> spread: every chunk of kBnRows rows gets its own mean and its own sum of
+// digits when |mean| >> spread: every chunk of rows gets its own mean and its own sum of
 // squared deviations from that mean; the chunks are then combined in double, in a fixed order.
-constexpr int kBnRows = 256;
-
-// Column sums of up to two quantities over a chunk of rows; thread = (column word, row group).
-// Returns the totals of this thread's column word in threads with grp == 0 (others: garbage).
-struct ChunkThread {
-  int words, groups, w, grp;
-};
-__device__ __forceinline__ ChunkThread chunk_thread(int C) {
-  ChunkThread t;
-  t.words = C / 4;
-  t.groups = kThreads / t.words;
-  t.w = threadIdx.x % t.words;
-  t.grp = threadIdx.x / t.words;
-  return t;
-}
-// Adds `v` over the row groups in group order; result valid for grp == 0.  `buf`: kThreads words.
-__device__ __forceinline__ f32x4 combine_groups(f32x4 v, const ChunkThread& t, f32x4* buf) {
-  __syncthreads();
-  buf[threadIdx.x] = v;
-  __syncthreads();
-  f32x4 tot = v;
-  if (t.grp == 0)
-    for (int gq = 1; gq < t.groups; ++gq) tot += buf[gq * t.words + t.w];
-  return tot;
-}
-
+// (Chunks and thread layout: see colsum_partial_kernel.)
 __global__ __launch_bounds__(kThreads) void bn_stats_partial_kernel(const float* __restrict__ Z,
                                                                     float* __restrict__ pmean,
                                                                     float* __restrict__ pm2,
-                                                                    long long rows, int C, int chunks) {
+                                                                    long long rows, int C, int chunks,
+                                                                    int chunk_rows) {
   __shared__ f32x4 buf[kThreads];
-  __shared__ f32x4 mean_s[kThreads];
-  const ChunkThread t = chunk_thread(C);
+  __shared__ f32x4 mean_s[16];
+  const ChunkThread t = chunk_thread(rows, C, chunk_rows);
   const int k = blockIdx.y;
-  const long long r0 = (long long)blockIdx.x * kBnRows;
-  const long long r1 = r0 + kBnRows < rows ? r0 + kBnRows : rows;
-  const float* base = Z + ((long long)k * rows) * C + 4 * t.w;
-  const bool live = t.grp < t.groups;
+  const float* base = Z + ((long long)k * rows) * C + 4 * t.cw;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  if (live)
-    for (long long r = r0 + t.grp; r < r1; r += t.groups) acc += *reinterpret_cast<const f32x4*>(base + r * C);
+  if (t.live)
+    for (long long r = t.r0 + t.grp; r < t.r1; r += 16) acc += *reinterpret_cast<const f32x4*>(base + r * C);
   f32x4 tot = combine_groups(acc, t, buf);
-  const float inv_n = 1.f / (float)(r1 - r0);
-  if (live && t.grp == 0) mean_s[t.w] = tot * inv_n;
+  const float inv_n = 1.f / (float)(t.r1 - t.r0);
+  if (t.grp == 0) mean_s[threadIdx.x & 15] = tot * inv_n;
   __syncthreads();
-  const f32x4 mu = live ? mean_s[t.w] : acc;
+  const f32x4 mu = mean_s[threadIdx.x & 15];
   acc = f32x4{0.f, 0.f, 0.f, 0.f};
-  if (live)
-    for (long long r = r0 + t.grp; r < r1; r += t.groups) {
+  if (t.live)
+    for (long long r = t.r0 + t.grp; r < t.r1; r += 16) {
       const f32x4 dlt = *reinterpret_cast<const f32x4*>(base + r * C) - mu;
       acc += dlt * dlt;
     }
   tot = combine_groups(acc, t, buf);
-  if (live && t.grp == 0) {
-    const long long at = ((long long)k * chunks + blockIdx.x) * C + 4 * t.w;
+  if (t.live && t.grp == 0) {
+    const long long at = ((long long)k * chunks + blockIdx.x) * C + 4 * t.cw;
     *reinterpret_cast<f32x4*>(pmean + at) = mu;
     *reinterpret_cast<f32x4*>(pm2 + at) = tot;
   }
@@ -495,15 +508,15 @@ __device__ __forceinline__ double chain_total(double v, double (*buf)[64], int q
 }
 __global__ __launch_bounds__(64 * kBnChains) void bn_stats_finish_kernel(
     const float* __restrict__ pmean, const float* __restrict__ pm2, float* __restrict__ stats,
-    long long rows, int C, int chunks, float eps) {
+    long long rows, int C, int chunks, int chunk_rows, float eps) {
   __shared__ double buf[kBnChains][64];
   const int col = threadIdx.x & 63, q = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + col;
   const int k = blockIdx.y;
   const bool live = c < C;
   auto count = [&](int ch) {
-    const long long left = rows - (long long)ch * kBnRows;
-    return (double)(left < kBnRows ? left : kBnRows);
+    const long long left = rows - (long long)ch * chunk_rows;
+    return (double)(left < chunk_rows ? left : chunk_rows);
   };
   double s1 = 0.0;
   if (live)
@@ -553,19 +566,17 @@ __global__ __launch_bounds__(kThreads) void bn_backward_partial_kernel(const flo
                                                                        const float* __restrict__ dY,
                                                                        const float* __restrict__ stats,
                                                                        float* __restrict__ part,
-                                                                       long long rows, int C, int chunks) {
+                                                                       long long rows, int C, int chunks,
+                                                                       int chunk_rows) {
   __shared__ f32x4 buf[kThreads];
-  const ChunkThread t = chunk_thread(C);
+  const ChunkThread t = chunk_thread(rows, C, chunk_rows);
   const int k = blockIdx.y;
-  const long long r0 = (long long)blockIdx.x * kBnRows;
-  const long long r1 = r0 + kBnRows < rows ? r0 + kBnRows : rows;
-  const long long base = ((long long)k * rows) * C + 4 * t.w;
-  const bool live = t.grp < t.groups;
+  const long long base = ((long long)k * rows) * C + 4 * t.cw;
   f32x4 sg = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
-  if (live) {
-    const f32x4 mu = *reinterpret_cast<const f32x4*>(stats + ((long long)k * 2) * C + 4 * t.w);
-    const f32x4 inv = *reinterpret_cast<const f32x4*>(stats + ((long long)k * 2 + 1) * C + 4 * t.w);
-    for (long long r = r0 + t.grp; r < r1; r += t.groups) {
+  if (t.live) {
+    const f32x4 mu = *reinterpret_cast<const f32x4*>(stats + ((long long)k * 2) * C + 4 * t.cw);
+    const f32x4 inv = *reinterpret_cast<const f32x4*>(stats + ((long long)k * 2 + 1) * C + 4 * t.cw);
+    for (long long r = t.r0 + t.grp; r < t.r1; r += 16) {
       const f32x4 dy = *reinterpret_cast<const f32x4*>(dY + base + r * C);
       const f32x4 xh = (*reinterpret_cast<const f32x4*>(Z + base + r * C) - mu) * inv;
       sg += dy * xh;
@@ -574,8 +585,8 @@ __global__ __launch_bounds__(kThreads) void bn_backward_partial_kernel(const flo
   }
   const f32x4 tg = combine_groups(sg, t, buf);
   const f32x4 tb = combine_groups(sb, t, buf);
-  if (live && t.grp == 0) {
-    float* dst = part + ((long long)k * chunks + blockIdx.x) * 2 * C + 4 * t.w;
+  if (t.live && t.grp == 0) {
+    float* dst = part + ((long long)k * chunks + blockIdx.x) * 2 * C + 4 * t.cw;
     *reinterpret_cast<f32x4*>(dst) = tg;
     *reinterpret_cast<f32x4*>(dst + C) = tb;
   }
@@ -629,8 +640,9 @@ int launch_fold3x3(const float* dcol, int64_t strideCol, int ld, float* dX, cons
 
 void launch_flip_filters(const float* W, int64_t strideW, int ldw, float* Wt, int K, int Cout, int Cin,
                          hipStream_t s) {
-  const long long total = (long long)K * Cin * 9 * Cout;
-  flip_filters_kernel<<<blocks_for(total), kThreads, 0, s>>>(W, strideW, ldw, Wt, Cout, Cin, total);
+  const int cblocks = (Cin + 31) / 32;
+  flip_filters_kernel<<<dim3((unsigned)(Cout / 32 * cblocks), 9u, (unsigned)K), kThreads, 0, s>>>(
+      W, strideW, ldw, Wt, Cout, Cin, cblocks);
 }
 
 bool first_conv_fits(int C, int Cout, int64_t rows) {
@@ -672,19 +684,20 @@ int launch_first_conv_wgrad(const float* X, const float* dout, float* partial, f
   return Cout / 2;     // sum-of-squares slots written per replica
 }
 
-int bn_chunks(int64_t rows) { return (int)((rows + kBnRows - 1) / kBnRows); }
+int bn_chunks(int64_t rows, int C, int K) { return chunk_plan(rows, C, K).chunks; }
 
 int launch_bn_forward(const float* Z, float* scratch, float* stats, const float* params,
                       int64_t strideParams, int64_t gam_off, int64_t bet_off, float* out, int K,
                       int64_t rows, int C, float eps, hipStream_t s) {
   if (C % 4 || C < 4 || C > 4 * kThreads || rows < 1) return -1;
-  const int chunks = bn_chunks(rows);
+  const ChunkPlan pl = chunk_plan(rows, C, K);
+  const int chunks = pl.chunks;
   float* pmean = scratch;
   float* pm2 = scratch + (long long)K * chunks * C;
-  bn_stats_partial_kernel<<<dim3((unsigned)chunks, (unsigned)K), kThreads, 0, s>>>(Z, pmean, pm2, rows, C,
-                                                                                  chunks);
+  bn_stats_partial_kernel<<<dim3((unsigned)chunks, (unsigned)K, (unsigned)pl.col_blocks), kThreads, 0, s>>>(
+      Z, pmean, pm2, rows, C, chunks, pl.chunk_rows);
   bn_stats_finish_kernel<<<dim3((unsigned)((C + 63) / 64), (unsigned)K), 64 * kBnChains, 0, s>>>(
-      pmean, pm2, stats, rows, C, chunks, eps);
+      pmean, pm2, stats, rows, C, chunks, pl.chunk_rows, eps);
   const long long total = (long long)K * rows * (C / 4);
   bn_apply_kernel<<<blocks_for(total), kThreads, 0, s>>>(Z, stats, params, strideParams, gam_off, bet_off,
                                                         out, rows, C, total);
@@ -694,10 +707,10 @@ int launch_bn_forward(const float* Z, float* scratch, float* stats, const float*
 int launch_bn_backward_partials(const float* Z, const float* dY, const float* stats, float* part, int K,
                                 int64_t rows, int C, hipStream_t s) {
   if (C % 4 || C < 4 || C > 4 * kThreads || rows < 1) return -1;
-  const int chunks = bn_chunks(rows);
-  bn_backward_partial_kernel<<<dim3((unsigned)chunks, (unsigned)K), kThreads, 0, s>>>(Z, dY, stats, part,
-                                                                                     rows, C, chunks);
-  return chunks;
+  const ChunkPlan pl = chunk_plan(rows, C, K);
+  bn_backward_partial_kernel<<<dim3((unsigned)pl.chunks, (unsigned)K, (unsigned)pl.col_blocks), kThreads, 0,
+                               s>>>(Z, dY, stats, part, rows, C, pl.chunks, pl.chunk_rows);
+  return pl.chunks;
 }
 
 void launch_bn_backward_apply(const float* Z, float* dY, const float* stats, const float* params,
@@ -708,14 +721,14 @@ void launch_bn_backward_apply(const float* Z, float* dY, const float* stats, con
                                                                  gam_off, bet_off, rows, C, total);
 }
 
-int colsum_chunks(int64_t rows) { return (int)((rows + kColsumRows - 1) / kColsumRows); }
+int colsum_chunks(int64_t rows, int N, int K) { return chunk_plan(rows, N, K).chunks; }
 
 int launch_colsum_partials(const float* A, int64_t rows, int N, int K, float* partial, hipStream_t s) {
   if (N % 4 || N < 4 || N > 4 * kThreads || rows < 1) return -1;
-  const int chunks = colsum_chunks(rows);
-  colsum_partial_kernel<<<dim3((unsigned)chunks, (unsigned)K), kThreads, 0, s>>>(A, partial, rows, N,
-                                                                                 chunks);
-  return chunks;
+  const ChunkPlan pl = chunk_plan(rows, N, K);
+  colsum_partial_kernel<<<dim3((unsigned)pl.chunks, (unsigned)K, (unsigned)pl.col_blocks), kThreads, 0, s>>>(
+      A, partial, rows, N, pl.chunks, pl.chunk_rows);
+  return pl.chunks;
 }
 
 int launch_maxpool2(const float* A, float* P, int64_t images, int H, int W, int C, hipStream_t s) {

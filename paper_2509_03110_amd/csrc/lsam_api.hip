@@ -368,9 +368,9 @@ void build_layout(const lsam_config& c, Layout& lo) {
     if (lo.n_conv > 0) {
       size_t most = 0;
       for (const ConvLayer& cv : lo.conv)
-        most = std::max(most, (size_t)lo.K * colsum_chunks(cv.rows) * cv.Cout * 4);
+        most = std::max(most, (size_t)lo.K * colsum_chunks(cv.rows, cv.Cout, lo.K) * cv.Cout * 4);
       for (const ConvLayer& cv : lo.conv)
-        if (cv.bn) most = std::max(most, (size_t)lo.K * bn_chunks(cv.rows) * 2 * cv.Cout * 4);
+        if (cv.bn) most = std::max(most, (size_t)lo.K * bn_chunks(cv.rows, cv.Cout, lo.K) * 2 * cv.Cout * 4);
       lo.colsum = take(cur, most);
     }
     // the dense layers start at n_conv; their input and its gradient are the last

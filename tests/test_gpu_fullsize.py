@@ -178,3 +178,49 @@ def test_cnn5_full_size_two_steps_all_replicas(name):
                          "x of replica %d after step %d" % (i, t + 1))
     assert eng.lsam_get_schedule() == ora.get_schedule()
     eng.close()
+
+
+def test_vgg16_reduced_batch_against_oracle_and_full_batch_properties():
+    # Sixteen weight layers, thirteen of them batch-normalised convolutions.  The float64 oracle
+    # needs two minutes for one replica at batch 128, and batch normalisation ties the samples of
+    # a batch together, so no subset of a batch can be checked on its own: the oracle comparison
+    # runs one replica at batch 8 (same layers, same kernels, other grid sizes), and the full
+    # shape is checked for what must hold at any size: replicas that are given the same batch
+    # reproduce each other bit for bit (kernels are deterministic and replica-independent), the
+    # loss at the initial point is near log(10), the schedule is exact.
+    full = workloads.WORKLOADS["vgg16"]
+    w = full.scaled(K=1, batch=8, tau=(2,))
+    init = workloads.init_params(w)
+    cfg, keep = lsam.config_from_workload(w)
+    eng = lsam.Lsam(cfg, init, device=DEV, keep=keep)
+    ora = oracle_from(w, init)
+    loss = torch.zeros(w.K, dtype=torch.float32, device=DEV)
+    X, lab = workloads.batch(w, 0)
+    eng.lsam_step(torch.from_numpy(X).to(DEV), torch.from_numpy(lab).to(DEV), loss)
+    ol = ora.step(X, lab)
+    assert np.allclose(loss.cpu().numpy(), ol, rtol=1e-4)
+    assert np.allclose(eng.lsam_get_norms(), ora.last_norm, rtol=5e-3)
+    close_enough(eng.lsam_get_buffer(lsam.BUF_GRAD, 0), ora.last_g2[0], 5e-2, "g2")
+    close_enough(eng.lsam_get_params(0), ora.get_params(0), 1e-4, "x after one step")
+    eng.close()
+
+    w = full.scaled(tau=(2, 2, 2, 2))
+    cfg, keep = lsam.config_from_workload(w)
+    eng = lsam.Lsam(cfg, init, device=DEV, keep=keep)
+    loss = torch.zeros(w.K, dtype=torch.float32, device=DEV)
+    X, lab = workloads.batch(w, 0)
+    X[2], lab[2] = X[0], lab[0]                    # replicas 0 and 2 see the same batch
+    for t in range(2):
+        eng.lsam_step(torch.from_numpy(X).to(DEV), torch.from_numpy(lab).to(DEV), loss)
+        lg = loss.cpu().numpy()
+        assert np.all(np.isfinite(lg)) and lg[0] == lg[2]
+        if t == 0:
+            assert np.all(np.abs(lg - np.log(10.0)) < 0.5), lg
+        # before the first center update the two replicas are the same computation
+        assert np.array_equal(eng.lsam_get_buffer(lsam.BUF_GRAD, 0), eng.lsam_get_buffer(lsam.BUF_GRAD, 2))
+        if t == 0:
+            assert np.array_equal(eng.lsam_get_params(0), eng.lsam_get_params(2))
+            assert not np.array_equal(eng.lsam_get_params(0), eng.lsam_get_params(1))
+    assert eng.lsam_sync() == 4
+    assert eng.lsam_get_schedule() == ([2, 2, 2, 2], [0, 0, 0, 0], 1)
+    eng.close()

@@ -543,7 +543,10 @@ CNN_SMALL = workloads.Workload("cnn_small", K=2, dims=(3, 8, 16, 24, 5), batch=6
 ])
 def test_cnn_matches_oracle(name, over):
     w = CNN_SMALL.scaled(**over)
-    worst = run_mlp(w, 6, 1e-4, 1e-3)
+    # free-running for two steps, then every step from the oracle's state: one ReLU or pooling
+    # decision that falls differently in fp32 (these nets take 10^4 of them per step on batches
+    # of 5 to 43) would otherwise be amplified by the momentum into a diverging trajectory
+    worst = run_mlp(w, 6, 1e-4, 1e-3, anchor_after=2)
     print("cnn %s: worst parameter error %.3e" % (name, worst))
 
 

@@ -129,6 +129,16 @@ WORKLOADS = {
     "cnn5bn": Workload("cnn5bn", K=4, dims=(3, 32, 64, 128, 256, 10), batch=128, n_conv=3, img_h=32,
                        img_w=32, pool_mask=0b111, bn_mask=0b111, rho=0.1, lr=0.02,
                        tau=(16, 16, 16, 16), steps=20, data_seed=7, n_classes=10, batch_pool=4),
+    # VGG-16 as the paper trains it on CIFAR-10 (Experiments: VGG-16, 4 workers, batch 128,
+    # learning rate 0.2): thirteen 3x3 convolutions in five groups, each group closed by a 2x2
+    # max-pool, every convolution batch-normalised, then dense 512-512-512-10 (sixteen weight
+    # layers).  The paper does not say which VGG-16 variant it uses; this is the usual CIFAR one.
+    "vgg16": Workload("vgg16", K=4, dims=(3, 64, 64, 128, 128, 256, 256, 256, 512, 512, 512, 512,
+                                          512, 512, 512, 512, 10),
+                      batch=128, n_conv=13, img_h=32, img_w=32,
+                      pool_mask=(1 << 1) | (1 << 3) | (1 << 6) | (1 << 9) | (1 << 12),
+                      bn_mask=(1 << 13) - 1, rho=0.1, lr=0.2, tau=(16, 16, 16, 16), steps=20,
+                      data_seed=8, n_classes=10, batch_pool=2),
 }
 
 

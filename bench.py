@@ -32,23 +32,26 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "572b3fedd0efe275"
+TRAFFIC_SOURCES = "0c1356102c5ce636"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43722571,
-             "gemm_dx": 42126677, "gemm_fwd": 62121835, "perturb": 201945600},
-    "cfg3": {"bias_grad": 13681916, "center": 1773570304, "descent": 17232014251, "gemm_dw":
-             445810751, "gemm_dx": 250125371, "gemm_fwd": 233098089, "perturb": 5065988309,
+    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43640192,
+             "gemm_dx": 42139989, "gemm_fwd": 62121813, "perturb": 201945387},
+    "cfg3": {"bias_grad": 13681920, "center": 1773569984, "descent": 17231867819, "gemm_dw":
+             445888161, "gemm_dx": 250125365, "gemm_fwd": 233100639, "perturb": 5065988608,
              "softmax_ce": 1428821},
-    "cfg4": {"center": 3200045056, "descent": 25600046165, "perturb": 9600050261,
-             "sumsq_partials": 3417012992},
-    "cfg5": {"bias_grad": 118063809, "descent": 188958937195, "gemm_dw": 4962797405, "gemm_dx":
-             2332908786, "gemm_fwd": 2035124414, "perturb": 59024470997, "softmax_ce": 95326320},
-    "cnn5": {"bias_grad": 17140316, "conv_first": 80458912, "descent": 79476736, "gemm_dw":
-             168374187, "gemm_dx": 34786645, "gemm_fwd": 38356015, "perturb": 29813760, "pool":
-             68574805},
-    "cnn5bn": {"batchnorm": 172308839, "bias_grad": 17140316, "conv_first": 80454155, "descent":
-             79542272, "gemm_dw": 168964395, "gemm_dx": 34786645, "gemm_fwd": 38355328, "perturb":
-             29838336, "pool": 68574588},
+    "cfg4": {"center": 3200045184, "descent": 25600045952, "perturb": 9600051712,
+             "sumsq_partials": 3416580395},
+    "cfg5": {"bias_grad": 118044677, "descent": 188957729515, "gemm_dw": 4958862660, "gemm_dx":
+             2332915292, "gemm_fwd": 2035377192, "perturb": 59024611029, "softmax_ce": 95661248},
+    "cnn5": {"bias_grad": 17357404, "conv_first": 80445152, "descent": 79476736, "gemm_dw":
+             67235093, "gemm_dx": 34799957, "gemm_fwd": 38358383, "perturb": 29813760, "pool":
+             68572245},
+    "cnn5bn": {"batchnorm": 169162254, "bias_grad": 17357404, "conv_first": 80445813, "descent":
+             79542272, "gemm_dw": 67230428, "gemm_dx": 34799957, "gemm_fwd": 38357333, "perturb":
+             29838336, "pool": 68572025},
+    "vgg16": {"batchnorm": 193736548, "bias_grad": 31509414, "conv_first": 155188224, "descent":
+             1952545835, "gemm_dw": 143541691, "gemm_dx": 16973995, "gemm_fwd": 137517643,
+             "perturb": 732214784, "pool": 89613634},
 }
 
 

@@ -53,6 +53,30 @@ def test_bad_configs_are_rejected_with_a_message():
     assert lsam.lib().lsam_sync(None) == lsam.EINVAL
 
 
+def test_convolutional_configs_are_checked_on_the_host():
+    base = workloads.Workload("c", K=2, dims=(3, 8, 16, 24, 5), batch=6, n_conv=2, img_h=8, img_w=8,
+                              pool_mask=0b11, n_classes=5)
+    cfg, keep = lsam.config_from_workload(base)
+    assert lsam.lsam_num_params(cfg) == base.d == 27 * 8 + 8 + 72 * 16 + 16 + 64 * 24 + 24 + 24 * 5 + 5
+    bn = base.scaled(bn_mask=0b10)
+    cfg, keep = lsam.config_from_workload(bn)
+    assert lsam.lsam_num_params(cfg) == bn.d == base.d + 2 * 16
+    for over, msg in ((dict(dims=(3, 8, 12, 24, 5)), "multiples of 8"),
+                      (dict(img_h=6, img_w=6), "even image sides"),
+                      (dict(gemm_dtype=1), "fp32 only"),
+                      (dict(n_conv=4), "at least one dense layer"),
+                      (dict(img_h=0), "img_h"),
+                      (dict(bn_mask=0b100), "no convolution"),
+                      (dict(bn_mask=0b1, bn_eps=0.0), "bn_eps"),
+                      (dict(batch=1 << 22, img_h=64, img_w=64), "too large")):
+        cfg, keep = lsam.config_from_workload(base.scaled(**over))
+        assert lsam.lsam_workspace_bytes(cfg) == 0, over
+        assert msg in lsam.last_error(), (over, lsam.last_error())
+    # a dense model must not name normalised layers
+    cfg, keep = lsam.config_from_workload(workloads.WORKLOADS["cfg1"].scaled(bn_mask=1))
+    assert lsam.lsam_workspace_bytes(cfg) == 0 and "bn_mask" in lsam.last_error()
+
+
 @pytest.mark.parametrize("mode", [lsam.SCHED_FIXED, lsam.SCHED_REDRAW])
 @pytest.mark.parametrize("seed,lo,hi,K", [(0, 2, 8, 4), (5, 4, 16, 16), (123456789, 1, 3, 7)])
 def test_schedule_replay_is_bit_exact_with_oracle(mode, seed, lo, hi, K):

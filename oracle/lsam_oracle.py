@@ -217,8 +217,13 @@ class Cnn:
       P[b,i,j,c] = max_{u,v in {0,1}} A[b,2i+u,2j+v,c]
     The pool's gradient goes to the first maximal element of each window in (u, v) order."""
 
-    def __init__(self, dims, n_conv, img_h, img_w, pool_mask, bn_mask=0, bn_eps=1e-5):
+    def __init__(self, dims, n_conv, img_h, img_w, pool_mask, bn_mask=0, bn_eps=1e-5, gemm_dtype=0):
         self.bn_mask, self.bn_eps = int(bn_mask), float(bn_eps)
+        # gemm_dtype 1: every matrix product (each tap of a convolution, each dense layer, and
+        # their dW and dX) takes its two operands rounded to bfloat16 and accumulates exactly;
+        # everything stored -- activations, gradients, biases, normalisation -- stays unrounded
+        # (the bias gradients therefore sum the unrounded dZ)
+        self.q = bf16_round if gemm_dtype == 1 else _identity
         self.dims = tuple(int(v) for v in dims)
         self.L = len(self.dims) - 1
         self.n_conv = int(n_conv)
@@ -241,6 +246,7 @@ class Cnn:
     def loss_and_grad(self, x, X, labels):
         x = np.asarray(x, dtype=np.float64)
         X = np.asarray(X, dtype=np.float64)
+        q = self.q
         bn_saved = {}
         B = X.shape[0]
         self.last_margin = np.inf
@@ -255,9 +261,10 @@ class Cnn:
             Ap = np.zeros((B, h + 2, w + 2, cin))
             Ap[:, 1:h + 1, 1:w + 1, :] = A
             Z = np.zeros((B, h, w, cout)) + x[o1:o2]
+            Apq, Wq = q(Ap), q(Wl)
             for u in range(3):
                 for v in range(3):
-                    Z += Ap[:, u:u + h, v:v + w, :] @ Wl[:, u, v, :].T
+                    Z += Apq[:, u:u + h, v:v + w, :] @ Wq[:, u, v, :].T
             if l in self.bn_offsets:
                 g0, g1, g2 = self.bn_offsets[l]
                 mu = Z.mean(axis=(0, 1, 2))
@@ -282,7 +289,7 @@ class Cnn:
         for l in range(self.n_conv, self.L):
             o0, o1, o2 = self.offsets[l]
             fi, fo = self.shapes[l]
-            Z = acts[-1] @ x[o0:o1].reshape(fo, fi).T + x[o1:o2]
+            Z = q(acts[-1]) @ q(x[o0:o1].reshape(fo, fi)).T + x[o1:o2]
             if l < self.L - 1:
                 self.last_margin = min(self.last_margin, float(np.min(np.abs(Z))))
                 acts.append(np.maximum(Z, 0.0))
@@ -304,9 +311,9 @@ class Cnn:
             o0, o1, o2 = self.offsets[l]
             fi, fo = self.shapes[l]
             a_in = acts[l - self.n_conv]
-            grad[o0:o1] = (dZ.T @ a_in).ravel()
+            grad[o0:o1] = (q(dZ).T @ q(a_in)).ravel()
             grad[o1:o2] = dZ.sum(axis=0)
-            dA = dZ @ x[o0:o1].reshape(fo, fi)
+            dA = q(dZ) @ q(x[o0:o1].reshape(fo, fi))
             if l > self.n_conv:
                 dZ = dA * (a_in > 0.0)
         for l in range(self.n_conv - 1, -1, -1):
@@ -337,10 +344,11 @@ class Cnn:
             dW = np.zeros((cout, 3, 3, cin))
             dAp = np.zeros_like(Ap)
             flat = dZc.reshape(-1, cout)
+            flatq, dZq, Apq, Wq = q(flat), q(dZc), q(Ap), q(Wl)
             for u in range(3):
                 for v in range(3):
-                    dW[:, u, v, :] = flat.T @ Ap[:, u:u + h, v:v + w, :].reshape(-1, cin)
-                    dAp[:, u:u + h, v:v + w, :] += dZc @ Wl[:, u, v, :]
+                    dW[:, u, v, :] = flatq.T @ Apq[:, u:u + h, v:v + w, :].reshape(-1, cin)
+                    dAp[:, u:u + h, v:v + w, :] += dZq @ Wq[:, u, v, :]
             grad[o0:o1] = dW.ravel()
             grad[o1:o2] = flat.sum(axis=0)
             dA = dAp[:, 1:h + 1, 1:w + 1, :]
@@ -443,9 +451,7 @@ class LsamOracle:
         self.dims = tuple(dims)
         self.t = 0                      # sampler steps taken so far
         if n_conv:
-            if gemm_dtype != 0:
-                raise ValueError("the convolutional model is float32 only")
-            self.model = Cnn(dims, n_conv, img_h, img_w, pool_mask, bn_mask, bn_eps)
+            self.model = Cnn(dims, n_conv, img_h, img_w, pool_mask, bn_mask, bn_eps, gemm_dtype)
         else:
             self.model = Mlp(dims, gemm_dtype) if len(dims) else None
         self.shapes = self.model.shapes if n_conv else None

@@ -691,3 +691,38 @@ def test_noise_layout_with_batchnorm_vectors():
     assert b.size == a.size + 8
     assert np.array_equal(b[:n0], a[:n0]) and np.array_equal(b[n0 + 8:], a[n0:])
     assert np.all(np.isfinite(b[n0:n0 + 8])) and len(set(b[n0:n0 + 8])) == 8
+
+
+def test_cnn_bf16_products_round_their_operands_only():
+    # operands that are bf16 numbers already: the forward pass is untouched; in the backward
+    # pass only dZ gets rounded, so gradients move by at most a bf16 half-ulp of their size;
+    # bias gradients, which sum the unrounded dZ, do not move at all in the last layer
+    from oracle.lsam_oracle import Cnn
+    args = ((2, 4, 3), 1, 4, 4, 0b1)
+    m32, m16 = Cnn(*args), Cnn(*args, gemm_dtype=1)
+    rng = np.random.default_rng(2)
+    x = bf16_round(rng.standard_normal(m32.d).astype(np.float32) * 0.5)
+    X = bf16_round(rng.standard_normal((3, 4, 4, 2)).astype(np.float32))
+    lab = rng.integers(0, 3, 3)
+    l32, g32 = m32.loss_and_grad(x, X, lab)
+    l16, g16 = m16.loss_and_grad(x, X, lab)
+    # the dense layer reads relu(conv) pooled: not a bf16 number in general, so the loss moves a
+    # little; the convolution itself (operands exact) does not: compare through the first layer
+    assert abs(l16 - l32) < 2.0 ** -7 * abs(l32)
+    assert np.max(np.abs(g16 - g32)) <= 2.0 ** -6 * np.max(np.abs(g32))
+    assert np.max(np.abs(g16 - g32)) > 0.0
+    # and against the library's own rounding: a single convolution on bf16-cast tensors
+    import torch.nn.functional as F
+    m = Cnn((2, 4, 3), 1, 4, 4, 0, gemm_dtype=1)
+    x = (rng.standard_normal(m.d) * 0.5).astype(np.float32).astype(np.float64)
+    Xr = rng.standard_normal((2, 4, 4, 2)).astype(np.float32).astype(np.float64)
+    o0, o1, o2 = m.offsets[0]
+    cast = lambda a: torch.tensor(a, dtype=torch.float32).to(torch.bfloat16).to(torch.float64)
+    W = cast(x[o0:o1].astype(np.float32)).reshape(4, 3, 3, 2).permute(0, 3, 1, 2)
+    A = F.relu(F.conv2d(cast(Xr.astype(np.float32)).permute(0, 3, 1, 2), W, torch.tensor(x[o1:o2]), padding=1))
+    A = cast(A.permute(0, 2, 3, 1).reshape(2, -1).numpy().astype(np.float32))
+    p0, p1, p2 = m.offsets[1]
+    Z = A @ cast(x[p0:p1].astype(np.float32)).reshape(3, -1).T + torch.tensor(x[p1:p2])
+    expect = F.cross_entropy(Z, torch.tensor([0, 2])).item()
+    got, _ = m.loss_and_grad(x, Xr, np.array([0, 2]))
+    assert abs(got - expect) < 1e-12

@@ -32,26 +32,29 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "0c1356102c5ce636"
+TRAFFIC_SOURCES = "ab789f3d1293f900"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43640192,
-             "gemm_dx": 42139989, "gemm_fwd": 62121813, "perturb": 201945387},
-    "cfg3": {"bias_grad": 13681920, "center": 1773569984, "descent": 17231867819, "gemm_dw":
-             445888161, "gemm_dx": 250125365, "gemm_fwd": 233100639, "perturb": 5065988608,
+    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43633597,
+             "gemm_dx": 42139989, "gemm_fwd": 62126059, "perturb": 201945600},
+    "cfg3": {"bias_grad": 13681937, "center": 1773569984, "descent": 17232204928, "gemm_dw":
+             445917155, "gemm_dx": 250125376, "gemm_fwd": 233098242, "perturb": 5065988608,
              "softmax_ce": 1428821},
-    "cfg4": {"center": 3200045184, "descent": 25600045952, "perturb": 9600051712,
-             "sumsq_partials": 3416580395},
-    "cfg5": {"bias_grad": 118044677, "descent": 188957729515, "gemm_dw": 4958862660, "gemm_dx":
-             2332915292, "gemm_fwd": 2035377192, "perturb": 59024611029, "softmax_ce": 95661248},
-    "cnn5": {"bias_grad": 17357404, "conv_first": 80445152, "descent": 79476736, "gemm_dw":
-             67235093, "gemm_dx": 34799957, "gemm_fwd": 38358383, "perturb": 29813760, "pool":
-             68572245},
-    "cnn5bn": {"batchnorm": 169162254, "bias_grad": 17357404, "conv_first": 80445813, "descent":
-             79542272, "gemm_dw": 67230428, "gemm_dx": 34799957, "gemm_fwd": 38357333, "perturb":
-             29838336, "pool": 68572025},
-    "vgg16": {"batchnorm": 193736548, "bias_grad": 31509414, "conv_first": 155188224, "descent":
-             1952545835, "gemm_dw": 143541691, "gemm_dx": 16973995, "gemm_fwd": 137517643,
-             "perturb": 732214784, "pool": 89613634},
+    "cfg4": {"center": 3200045568, "descent": 25600046208, "perturb": 9600050261,
+             "sumsq_partials": 3415856277},
+    "cfg5": {"bias_grad": 118053374, "descent": 188955331947, "gemm_dw": 4959434994, "gemm_dx":
+             2332895989, "gemm_fwd": 2034707386, "perturb": 59024471040, "softmax_ce": 95531083},
+    "cnn5": {"bias_grad": 17357404, "conv_first": 80461280, "descent": 79476736, "gemm_dw":
+             67281020, "gemm_dx": 34799957, "gemm_fwd": 38353647, "perturb": 29813760, "pool":
+             68580946},
+    "cnn5bn": {"batchnorm": 169147303, "bias_grad": 17357404, "conv_first": 80450389, "descent":
+             79542272, "gemm_dw": 67278880, "gemm_dx": 34799957, "gemm_fwd": 38354138, "perturb":
+             29838336, "pool": 68580725},
+    "vgg16": {"batchnorm": 193738025, "bias_grad": 31509417, "conv_first": 155206165, "descent":
+             1952545920, "gemm_dw": 143431330, "gemm_dx": 16973995, "gemm_fwd": 138047581,
+             "perturb": 732214784, "pool": 89622359},
+    "vgg16bf": {"batchnorm": 193735578, "bias_grad": 36031441, "conv_first": 155208277, "descent":
+             1952546560, "gemm_dw": 133284921, "gemm_dx": 12109141, "gemm_fwd": 135372404,
+             "perturb": 732214741, "pool": 89622432, "softmax_ce": 114005},
 }
 
 
@@ -165,7 +168,7 @@ def make_inputs(w, torch, dev, n_sets):
         for s in range(n_sets):
             X, lab = workloads.batch(w, s)
             Xd = torch.from_numpy(X).to(dev)
-            if w.gemm_dtype == 1:
+            if w.gemm_dtype == 1 and not w.n_conv:
                 Xd = Xd.to(torch.bfloat16)
             sets.append((Xd.contiguous(), torch.from_numpy(lab).to(dev)))
     else:
@@ -186,7 +189,7 @@ def cpu_baseline(w, budget_s=20.0):
     with threadpool_limits(limits=1):
         if w.dims:
             # one replica; shrink the batch for the two largest workloads
-            frac = {"cfg5": 8, "cfg3": 2, "vgg16": 16}.get(w.name, 1)
+            frac = {"cfg5": 8, "cfg3": 2, "vgg16": 16, "vgg16bf": 16}.get(w.name, 1)
             ws = w.scaled(K=1, batch=max(w.batch // frac, 1), tau=(10 ** 6,))
             o = oracle_from(ws, workloads.init_params(ws))
             X, lab = workloads.batch(ws, 0)

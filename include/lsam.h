@@ -34,8 +34,12 @@
  * Layer l < n_conv maps C_l to C_{l+1} channels and stores its filters as W_l
  * [C_{l+1}, 3, 3, C_l] row-major, i.e. in_l = 9 C_l in the layout above; the first dense layer
  * reads the (pooled) image flattened in (row, column, channel) order, in_l = H' W' C_{n_conv}.
- * Images are [H, W, C] with the channel contiguous.  fp32 only; C_1..C_{n_conv} must be
- * multiples of 8 and every pooled image must have even sides.  The pool's gradient goes to
+ * Images are [H, W, C] with the channel contiguous.  C_1..C_{n_conv} must be multiples of 8
+ * and every pooled image must have even sides.  All tensors of this model, the input X
+ * included, are fp32 in memory in both arithmetic modes: with LSAM_GEMM_BF16 every matrix
+ * product (each convolution and dense layer, forward, dW and dX) rounds its two operands to
+ * bfloat16 (nearest even) on their way into the matrix unit and accumulates in fp32; biases,
+ * normalisation, pooling, the loss and the bias gradients (sums of the unrounded dZ) are fp32.  The pool's gradient goes to
  * the first maximum of a window in row-major order.
  * A batch-normalised convolution (bn_mask) computes, per replica and channel over the B H W
  * positions of that replica's minibatch, Y = gamma (Z - mean) / sqrt(var + bn_eps) + beta before

@@ -104,6 +104,9 @@ struct GemmDesc {
   // [Kd pixels][unfold_C], N = 9 * unfold_C, both operands m-major.  unfold_C must be a
   // multiple of 32; ldA resp. ldB is then ignored apart from the alignment checks.
   int unfold, unfold_C, unfold_H, unfold_W;
+  // fp32 operands only: round both operands to bfloat16 on their way into the matrix unit
+  // (v_mfma_f32_32x32x16_bf16, fp32 accumulate); memory traffic and results stay fp32.
+  int bf16_math;
 };
 // 0 ok, <0 unsupported shape; *sumsq_slots (if non-null) = slots written per replica
 int launch_gemm(const GemmDesc& d, hipStream_t s, int* sumsq_slots = nullptr);
@@ -162,15 +165,17 @@ int launch_fold3x3(const float* dcol, int64_t strideCol, int ld, float* dX, cons
 // into grad + k * strideParams at the same offsets, through `partial`
 // ([K][first_conv_chunks(rows)][Cout][32] floats of scratch), plus, if sumsq is non-null, the
 // sums of their squares in sumsq[k * sumsq_stride + slot]; returns the slots written per
-// replica (Cout / 2), or -1.
+// replica (Cout / 2), or -1.  `round`: both operands of every product are rounded to bfloat16
+// first; the weight-gradient kernel then leaves db alone (it would sum rounded values): the
+// caller takes the column sums of dout instead.
 bool first_conv_fits(int C, int Cout, int64_t rows);
 int first_conv_chunks(int64_t rows);
 int launch_first_conv_forward(const float* X, const float* params, int64_t strideParams, int64_t w_off,
-                              int64_t b_off, int ldw, float* out, int relu, int K, int64_t rows, int H,
-                              int W, int C, int Cout, hipStream_t s);
+                              int64_t b_off, int ldw, float* out, int relu, int round, int K,
+                              int64_t rows, int H, int W, int C, int Cout, hipStream_t s);
 int launch_first_conv_wgrad(const float* X, const float* dout, float* partial, float* grad,
-                            int64_t strideParams, int64_t w_off, int64_t b_off, int ldw, int K,
-                            int64_t rows, int H, int W, int C, int Cout, double* sumsq,
+                            int64_t strideParams, int64_t w_off, int64_t b_off, int ldw, int round,
+                            int K, int64_t rows, int H, int W, int C, int Cout, double* sumsq,
                             int64_t sumsq_stride, hipStream_t s);
 // Training-mode batch normalisation of K matrices Z [rows][C] (C % 4 == 0, C <= 1024), per
 // replica and column over the rows.  Forward: stats[k][0][c] = mean, stats[k][1][c] =

@@ -281,6 +281,10 @@ __device__ __forceinline__ void pixel_rc(int p, const FirstConv& f, int& i, int&
   i = r2;
 }
 
+// bfloat16 value nearest to v (ties to even), as a float: products of two such values are exact
+// in fp32, so fp32 MFMAs on rounded operands give what the bf16 matrix instructions give.
+__device__ __forceinline__ float to_bf16(float v) { return static_cast<float>(static_cast<__bf16>(v)); }
+
 // Value t of the unfolded image of pixel p at (i, j): X[p shifted by tap t / C][t % C].
 template <int C>
 __device__ __forceinline__ float unfolded(const float* __restrict__ img, int p, int i, int j, int t,
@@ -297,7 +301,7 @@ __global__ __launch_bounds__(kThreads) void first_conv_forward_kernel(const floa
                                                                       const float* __restrict__ params,
                                                                       long long w_off, long long b_off,
                                                                       float* __restrict__ out,
-                                                                      FirstConv f, int relu) {
+                                                                      FirstConv f, int relu, int round) {
   constexpr int KS = (9 * C + 1) / 2;          // MFMA steps of depth 2
   constexpr int WP = 33;                       // LDS pitch of a filter: lanes o, o+1 on different banks
   extern __shared__ float wl[];                // [Cout][WP]: the filters, zero for t >= 9 C
@@ -309,7 +313,8 @@ __global__ __launch_bounds__(kThreads) void first_conv_forward_kernel(const floa
     const float* Wg = params + (long long)k * f.strideParams + w_off;
     for (int e = threadIdx.x; e < f.Cout * 32; e += kThreads) {
       const int o = e >> 5, t = e & 31;
-      wl[o * WP + t] = t < 9 * C ? Wg[(long long)o * f.ldw + t] : 0.f;
+      const float wv = t < 9 * C ? Wg[(long long)o * f.ldw + t] : 0.f;
+      wl[o * WP + t] = round ? to_bf16(wv) : wv;
     }
   }
   __syncthreads();
@@ -321,7 +326,10 @@ __global__ __launch_bounds__(kThreads) void first_conv_forward_kernel(const floa
   if (live) pixel_rc(p, f, i, j);
   float x[KS];
 #pragma unroll
-  for (int s = 0; s < KS; ++s) x[s] = live ? unfolded<C>(img, p, i, j, 2 * s + h, f) : 0.f;
+  for (int s = 0; s < KS; ++s) {
+    x[s] = live ? unfolded<C>(img, p, i, j, 2 * s + h, f) : 0.f;
+    if (round) x[s] = to_bf16(x[s]);
+  }
   // acc[e] of lane (l32, h): output channel ob + l32 of pixel tile*32 + (e/4)*8 + h*4 + e%4, so
   // that a store instruction writes two whole 128-byte rows
   const int tile0 = (blockIdx.x * 4 + wave) * 32;
@@ -354,7 +362,7 @@ template <int C>
 __global__ __launch_bounds__(kThreads) void first_conv_wgrad_kernel(const float* __restrict__ X,
                                                                     const float* __restrict__ dout,
                                                                     float* __restrict__ partial,
-                                                                    int chunks, FirstConv f) {
+                                                                    int chunks, FirstConv f, int round) {
   __shared__ float red[3][32 * 32];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int l32 = lane & 31, h = lane >> 5;
@@ -385,6 +393,7 @@ __global__ __launch_bounds__(kThreads) void first_conv_wgrad_kernel(const float*
       float b = img[in_img ? (long long)pc * C + shift : 0];
       b = in_img ? b : (t == 9 * C ? 1.f : 0.f);
       if (p > last) { a = 0.f; b = 0.f; }
+      if (round) { a = to_bf16(a); b = to_bf16(b); }
       acc = __builtin_amdgcn_mfma_f32_32x32x2f32(b, a, acc, 0, 0, 0);
     }
     // acc[e]: o = ob + l32, t = (e/4)*8 + h*4 + e%4
@@ -422,7 +431,7 @@ __global__ __launch_bounds__(1024) void first_conv_wgrad_finish_kernel(const flo
                                                                        long long w_off, long long b_off,
                                                                        double* __restrict__ sumsq,
                                                                        long long strideSumsq,
-                                                                       FirstConv f) {
+                                                                       FirstConv f, int skip_bias) {
   __shared__ float part[kFinishChains][64];
   const int word = threadIdx.x & 63, q = threadIdx.x >> 6;
   const int k = blockIdx.y;
@@ -443,7 +452,7 @@ __global__ __launch_bounds__(1024) void first_conv_wgrad_finish_kernel(const flo
     const int o = e >> 5, t = e & 31;
     double ssq = 0.0;
     if (t < 9 * C) { g[w_off + (long long)o * f.ldw + t] = v; ssq = (double)v * (double)v; }
-    else if (t == 9 * C) { g[b_off + o] = v; ssq = (double)v * (double)v; }
+    else if (t == 9 * C && !skip_bias) { g[b_off + o] = v; ssq = (double)v * (double)v; }
     if (sumsq != nullptr) {
 #pragma unroll
       for (int off = 32; off > 0; off >>= 1) ssq += __shfl_xor(ssq, off, 64);
@@ -656,31 +665,31 @@ static FirstConv first_shape(int H, int W, int Cout, int64_t rows, int64_t strid
 }
 
 int launch_first_conv_forward(const float* X, const float* params, int64_t strideParams, int64_t w_off,
-                              int64_t b_off, int ldw, float* out, int relu, int K, int64_t rows, int H,
-                              int W, int C, int Cout, hipStream_t s) {
+                              int64_t b_off, int ldw, float* out, int relu, int round, int K,
+                              int64_t rows, int H, int W, int C, int Cout, hipStream_t s) {
   if (!first_conv_fits(C, Cout, rows)) return -1;
   const FirstConv f = first_shape(H, W, Cout, rows, strideParams, ldw);
   const dim3 grid((unsigned)((rows + 127) / 128), (unsigned)K);
   const size_t lds = (size_t)Cout * 33 * 4;
-  if (C == 1) first_conv_forward_kernel<1><<<grid, kThreads, lds, s>>>(X, params, w_off, b_off, out, f, relu);
-  else if (C == 2) first_conv_forward_kernel<2><<<grid, kThreads, lds, s>>>(X, params, w_off, b_off, out, f, relu);
-  else first_conv_forward_kernel<3><<<grid, kThreads, lds, s>>>(X, params, w_off, b_off, out, f, relu);
+  if (C == 1) first_conv_forward_kernel<1><<<grid, kThreads, lds, s>>>(X, params, w_off, b_off, out, f, relu, round);
+  else if (C == 2) first_conv_forward_kernel<2><<<grid, kThreads, lds, s>>>(X, params, w_off, b_off, out, f, relu, round);
+  else first_conv_forward_kernel<3><<<grid, kThreads, lds, s>>>(X, params, w_off, b_off, out, f, relu, round);
   return 0;
 }
 
 int launch_first_conv_wgrad(const float* X, const float* dout, float* partial, float* grad,
-                            int64_t strideParams, int64_t w_off, int64_t b_off, int ldw, int K,
-                            int64_t rows, int H, int W, int C, int Cout, double* sumsq,
+                            int64_t strideParams, int64_t w_off, int64_t b_off, int ldw, int round,
+                            int K, int64_t rows, int H, int W, int C, int Cout, double* sumsq,
                             int64_t sumsq_stride, hipStream_t s) {
   if (!first_conv_fits(C, Cout, rows)) return -1;
   const FirstConv f = first_shape(H, W, Cout, rows, strideParams, ldw);
   const int chunks = first_conv_chunks(rows);
   const dim3 grid((unsigned)chunks, (unsigned)K);
-  if (C == 1) first_conv_wgrad_kernel<1><<<grid, kThreads, 0, s>>>(X, dout, partial, chunks, f);
-  else if (C == 2) first_conv_wgrad_kernel<2><<<grid, kThreads, 0, s>>>(X, dout, partial, chunks, f);
-  else first_conv_wgrad_kernel<3><<<grid, kThreads, 0, s>>>(X, dout, partial, chunks, f);
+  if (C == 1) first_conv_wgrad_kernel<1><<<grid, kThreads, 0, s>>>(X, dout, partial, chunks, f, round);
+  else if (C == 2) first_conv_wgrad_kernel<2><<<grid, kThreads, 0, s>>>(X, dout, partial, chunks, f, round);
+  else first_conv_wgrad_kernel<3><<<grid, kThreads, 0, s>>>(X, dout, partial, chunks, f, round);
   first_conv_wgrad_finish_kernel<<<dim3((unsigned)(Cout / 2), (unsigned)K), 1024, 0, s>>>(
-      partial, chunks, C, grad, w_off, b_off, sumsq, sumsq_stride, f);
+      partial, chunks, C, grad, w_off, b_off, sumsq, sumsq_stride, f, round);
   return Cout / 2;     // sum-of-squares slots written per replica
 }
 

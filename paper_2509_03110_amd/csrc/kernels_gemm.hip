@@ -327,9 +327,16 @@ __device__ __forceinline__ float widen(float v) { return v; }
 __device__ __forceinline__ float widen(__bf16 v) { return static_cast<float>(v); }
 
 // CONV: 0 = both operands stored; 1 = A is an unfolded image (k-major); 2 = B is one (m-major).
+// BF16MATH (fp32 operands only): the operands stay fp32 in memory and in LDS, but each pair of
+// k-chunks is rounded to bfloat16 in registers (round to nearest even) and fed to one
+// v_mfma_f32_32x32x16_bf16 instead of eight v_mfma_f32_32x32x2_f32 -- the rounding rule of the
+// bf16 configurations (only what enters the matrix unit is rounded) at fp32 memory traffic.
+// Which k a lane's eight values stand for does not matter as long as both operands agree: a
+// lane takes the four of its unit in the even chunk and the four of its unit in the odd one.
 template <typename T, typename TC, int BM, int BN, int BKU, bool A_KMAJOR, bool B_KMAJOR, int OCC,
-          int CONV = 0>
+          int CONV = 0, bool BF16MATH = false>
 __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
+  static_assert(!BF16MATH || Op<T>::UE == 4, "bf16 math is a mode of the fp32-operand kernel");
   static_assert(CONV == 0 || (CONV == 1 && A_KMAJOR) || (CONV == 2 && !B_KMAJOR), "operand layout");
   constexpr int UE = Op<T>::UE;
   constexpr int TM = BM / 64, TN = BN / 64;
@@ -428,7 +435,37 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
 #pragma unroll
     for (int j = 0; j < TN; ++j) fb[buf][j] = stage[posB[j] + kc * 2 * (BN + 1)];
   };
+  u32x2 ha[TM], hb[TN];     // BF16MATH: the even chunk's operands, rounded, waiting for the odd one
   auto mfma_chunk = [&](int buf) {
+    if constexpr (BF16MATH) {
+      // chunk parity equals the fragment buffer index (an even number of chunks per k-step)
+      if (buf == 0) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) ha[i] = Pack<__bf16>::from(__builtin_bit_cast(f32x4, fa[0][i]));
+#pragma unroll
+        for (int j = 0; j < TN; ++j) hb[j] = Pack<__bf16>::from(__builtin_bit_cast(f32x4, fb[0][j]));
+      } else {
+        u32x4 qa[TM], qb[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const u32x2 hi = Pack<__bf16>::from(__builtin_bit_cast(f32x4, fa[1][i]));
+          qa[i] = u32x4{ha[i][0], ha[i][1], hi[0], hi[1]};
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const u32x2 hi = Pack<__bf16>::from(__builtin_bit_cast(f32x4, fb[1][j]));
+          qb[j] = u32x4{hb[j][0], hb[j][1], hi[0], hi[1]};
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, qb[j]),
+                                                                __builtin_bit_cast(bf16x8, qa[i]),
+                                                                acc[i][j], 0, 0, 0);
+      }
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -475,9 +512,9 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
       if (kc + 2 == NKC) {
         la.store(nxt, tid);
         lb.store(nxt + A_UNITS, tid);
-        Pipeline<ND, NW, 0x200, NM>::run();
+        if constexpr (!BF16MATH) Pipeline<ND, NW, 0x200, NM>::run();
       } else {
-        Pipeline<ND, 0, 0, NM>::run();
+        if constexpr (!BF16MATH) Pipeline<ND, 0, 0, NM>::run();
       }
     }
     __syncthreads();
@@ -485,7 +522,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
     mfma_chunk((NKC - 1) & 1);
     load_a(kb + (ks + 2) * BKU);
     load_b(kb + (ks + 2) * BKU);
-    Pipeline<ND, NV, 0x020, NM>::run();
+    if constexpr (!BF16MATH) Pipeline<ND, NV, 0x020, NM>::run();
   }
   {
     const u32x4* cur = lds + ((ksteps - 1) & 1) * STAGE_UNITS;
@@ -493,7 +530,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
     for (int kc = 0; kc < NKC; ++kc) {
       if (kc + 1 < NKC) read_frags(cur, kc + 1, (kc + 1) & 1);
       mfma_chunk(kc & 1);
-      if (kc + 1 < NKC) Pipeline<ND, 0, 0, NM>::run();
+      if constexpr (!BF16MATH) if (kc + 1 < NKC) Pipeline<ND, 0, 0, NM>::run();
     }
   }
   __syncthreads();
@@ -680,11 +717,11 @@ Plan make_plan(const GemmDesc& d, int tile_override) {
   else if (tile_override == 2) { pl.bm = 256; pl.bn = 128; pl.bku = 4; }
   else if (tile_override == 4) { pl.bm = 128; pl.bn = 128; }
   else if (tile_override == 5) { pl.bm = 64; pl.bn = 64; }
-  else if (d.unfold) {      // implicit unfolding is instantiated for the two smaller tiles
+  else if (d.unfold || d.bf16_math) {   // instantiated for the two smaller tiles only
     // (for the weight gradients, few output tiles and a split contraction, the smaller tile
     // measured faster: 71 us against 84 us at M = 128, N = 576, 8192 pixels, 4 replicas;
     // k-steps twice as deep, and 128x64 / 64x128 tiles, changed nothing)
-    if (d.M >= 128 && d.N >= 128 && tiles(128, 128) >= 512) { pl.bm = 128; pl.bn = 128; }
+    if (d.M >= 128 && d.N >= 128 && tiles(128, 128) >= (d.bf16_math ? 192 : 512)) { pl.bm = 128; pl.bn = 128; }
   }
   else if (kk && d.M >= 256 && d.N >= 128 && tiles(256, 128) >= 512) { pl.bm = 256; pl.bn = 128; pl.bku = 4; }
   else if (d.M >= 256 && d.N >= 256 && tiles(256, 256) >= 512) { pl.bm = 256; pl.bn = 256; }
@@ -716,7 +753,8 @@ Plan make_plan(const GemmDesc& d, int tile_override) {
   return pl;
 }
 
-template <typename T, typename TC, int BM, int BN, int BKU, bool AK, bool BK_, int CONV = 0>
+template <typename T, typename TC, int BM, int BN, int BKU, bool AK, bool BK_, int CONV = 0,
+          bool BF16MATH = false>
 int launch_one(const GemmParams& p0, hipStream_t s, int* sumsq_slots) {
   constexpr int OCC = (BM * BN >= 256 * 256) ? 1 : 2;
   GemmParams p = p0;
@@ -727,7 +765,7 @@ int launch_one(const GemmParams& p0, hipStream_t s, int* sumsq_slots) {
   const size_t loop_smem = (size_t)2 * BKU * ((BM + 1) + (BN + 1)) * 16;
   const size_t epi_smem = (size_t)64 * (BN + 4) * 4;
   const size_t smem = loop_smem > epi_smem ? loop_smem : epi_smem;
-  auto kern = gemm_kernel<T, TC, BM, BN, BKU, AK, BK_, OCC, CONV>;
+  auto kern = gemm_kernel<T, TC, BM, BN, BKU, AK, BK_, OCC, CONV, BF16MATH>;
   static std::atomic<bool> attr_set{false};   // per instantiation; setting it twice is harmless
   if (!attr_set.load(std::memory_order_relaxed)) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -759,6 +797,29 @@ int launch_tiled(const GemmParams& p, const Plan& pl, hipStream_t s, int* slots)
 
 template <typename T, typename TC>
 int launch_layout(const GemmDesc& d, const GemmParams& p, const Plan& pl, hipStream_t s, int* slots) {
+  if (d.bf16_math) {
+    const bool big = pl.bm == 128;
+    if (d.unfold == 1) {
+      if (!(d.a_kmajor && d.b_kmajor)) return -1;
+      return big ? launch_one<T, TC, 128, 128, 8, true, true, 1, true>(p, s, slots)
+                 : launch_one<T, TC, 64, 64, 8, true, true, 1, true>(p, s, slots);
+    }
+    if (d.unfold == 2) {
+      if (d.a_kmajor || d.b_kmajor) return -1;
+      return big ? launch_one<T, TC, 128, 128, 8, false, false, 2, true>(p, s, slots)
+                 : launch_one<T, TC, 64, 64, 8, false, false, 2, true>(p, s, slots);
+    }
+    if (d.a_kmajor && d.b_kmajor)
+      return big ? launch_one<T, TC, 128, 128, 8, true, true, 0, true>(p, s, slots)
+                 : launch_one<T, TC, 64, 64, 8, true, true, 0, true>(p, s, slots);
+    if (d.a_kmajor && !d.b_kmajor)
+      return big ? launch_one<T, TC, 128, 128, 8, true, false, 0, true>(p, s, slots)
+                 : launch_one<T, TC, 64, 64, 8, true, false, 0, true>(p, s, slots);
+    if (!d.a_kmajor && !d.b_kmajor)
+      return big ? launch_one<T, TC, 128, 128, 8, false, false, 0, true>(p, s, slots)
+                 : launch_one<T, TC, 64, 64, 8, false, false, 0, true>(p, s, slots);
+    return -1;
+  }
   if (d.unfold == 1) {
     if (!(d.a_kmajor && d.b_kmajor)) return -1;
     if (pl.bm == 128) return launch_one<T, TC, 128, 128, 8, true, true, 1>(p, s, slots);
@@ -794,7 +855,7 @@ int gemm_sumsq_capacity(int M, int N) {
 int launch_gemm(const GemmDesc& d, hipStream_t s, int* sumsq_slots) {
   // bf16 operands live in the blocked layout and have their own kernel; this file's kernel
   // serves the fp32 configurations
-  if (d.in_bf16) return launch_gemm_bf16(d, g_tile_override, s, sumsq_slots);
+  if (d.in_bf16) return (d.unfold || d.bf16_math) ? -1 : launch_gemm_bf16(d, g_tile_override, s, sumsq_slots);
   GemmParams p;
   p.A = (const char*)d.A; p.strideA = d.strideA; p.ldA = d.ldA;
   p.B = (const char*)d.B; p.strideB = d.strideB; p.ldB = d.ldB;
@@ -813,7 +874,7 @@ int launch_gemm(const GemmDesc& d, hipStream_t s, int* sumsq_slots) {
     // a k-step (32 floats) must lie inside one tap; pixel indices must be exact in fp32; the
     // contraction (mode 1) or the column extent (mode 2) is the unfolded width 9 C
     const long long pixels = d.unfold == 1 ? d.M : d.Kd;
-    if (d.in_bf16 || d.unfold_C % 32 || d.unfold_H < 1 || d.unfold_W < 1 ||
+    if (d.unfold_C % 32 || d.unfold_H < 1 || d.unfold_W < 1 ||
         pixels % ((long long)d.unfold_H * d.unfold_W) || pixels >= (1 << 24) ||
         pixels * d.unfold_C * 4 >= 0x7FFFFFF0LL || (d.unfold == 1 ? d.Kd : d.N) != 9 * d.unfold_C)
       return -1;

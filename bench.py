@@ -32,29 +32,29 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "ab789f3d1293f900"
+TRAFFIC_SOURCES = "a854636fc32541b0"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43633597,
-             "gemm_dx": 42139989, "gemm_fwd": 62126059, "perturb": 201945600},
-    "cfg3": {"bias_grad": 13681937, "center": 1773569984, "descent": 17232204928, "gemm_dw":
-             445917155, "gemm_dx": 250125376, "gemm_fwd": 233098242, "perturb": 5065988608,
-             "softmax_ce": 1428821},
-    "cfg4": {"center": 3200045568, "descent": 25600046208, "perturb": 9600050261,
-             "sumsq_partials": 3415856277},
-    "cfg5": {"bias_grad": 118053374, "descent": 188955331947, "gemm_dw": 4959434994, "gemm_dx":
-             2332895989, "gemm_fwd": 2034707386, "perturb": 59024471040, "softmax_ce": 95531083},
-    "cnn5": {"bias_grad": 17357404, "conv_first": 80461280, "descent": 79476736, "gemm_dw":
-             67281020, "gemm_dx": 34799957, "gemm_fwd": 38353647, "perturb": 29813760, "pool":
-             68580946},
-    "cnn5bn": {"batchnorm": 169147303, "bias_grad": 17357404, "conv_first": 80450389, "descent":
-             79542272, "gemm_dw": 67278880, "gemm_dx": 34799957, "gemm_fwd": 38354138, "perturb":
-             29838336, "pool": 68580725},
-    "vgg16": {"batchnorm": 193738025, "bias_grad": 31509417, "conv_first": 155206165, "descent":
-             1952545920, "gemm_dw": 143431330, "gemm_dx": 16973995, "gemm_fwd": 138047581,
-             "perturb": 732214784, "pool": 89622359},
-    "vgg16bf": {"batchnorm": 193735578, "bias_grad": 36031441, "conv_first": 155208277, "descent":
-             1952546560, "gemm_dw": 133284921, "gemm_dx": 12109141, "gemm_fwd": 135372404,
-             "perturb": 732214741, "pool": 89622432, "softmax_ce": 114005},
+    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43637723,
+             "gemm_dx": 42139989, "gemm_fwd": 62126048, "perturb": 201945515},
+    "cfg3": {"bias_grad": 13681839, "center": 1773571904, "descent": 17231771605, "gemm_dw":
+             445792775, "gemm_dx": 250125392, "gemm_fwd": 233096379, "perturb": 5065985707,
+             "softmax_ce": 1429163},
+    "cfg4": {"center": 3200046208, "descent": 25600045696, "perturb": 9600050773,
+             "sumsq_partials": 3416879744},
+    "cfg5": {"bias_grad": 118056567, "descent": 188969451947, "gemm_dw": 4955259089, "gemm_dx":
+             2332944796, "gemm_fwd": 2034451980, "perturb": 59024472875, "softmax_ce": 95750080},
+    "cnn5": {"bias_grad": 17357404, "conv_first": 80454123, "descent": 79476736, "gemm_dw":
+             67284491, "gemm_dx": 34799957, "gemm_fwd": 38354453, "perturb": 29813760, "pool":
+             68580971},
+    "cnn5bn": {"batchnorm": 169146827, "bias_grad": 17357404, "conv_first": 80452533, "descent":
+             79542272, "gemm_dw": 67280558, "gemm_dx": 34799957, "gemm_fwd": 38354560, "perturb":
+             29838336, "pool": 68580743},
+    "vgg16": {"batchnorm": 193733794, "bias_grad": 31509416, "conv_first": 155211531, "descent":
+             1952546133, "gemm_dw": 143461108, "gemm_dx": 16973995, "gemm_fwd": 138024610,
+             "perturb": 732214827, "pool": 89622364},
+    "vgg16bf": {"batchnorm": 193728038, "bias_grad": 36031437, "conv_first": 155217344, "descent":
+             1952546987, "gemm_dw": 129604125, "gemm_dx": 12109141, "gemm_fwd": 135383642,
+             "perturb": 732214997, "pool": 89622451, "softmax_ce": 114005},
 }
 
 

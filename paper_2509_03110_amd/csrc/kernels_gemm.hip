@@ -722,6 +722,7 @@ Plan make_plan(const GemmDesc& d, int tile_override) {
     // measured faster: 71 us against 84 us at M = 128, N = 576, 8192 pixels, 4 replicas;
     // k-steps twice as deep, and 128x64 / 64x128 tiles, changed nothing)
     if (d.M >= 128 && d.N >= 128 && tiles(128, 128) >= (d.bf16_math ? 192 : 512)) { pl.bm = 128; pl.bn = 128; }
+    else if (d.bf16_math && d.unfold == 2 && d.M >= 128 && d.N >= 128 && d.Kd >= 2048) { pl.bm = 128; pl.bn = 128; }
   }
   else if (kk && d.M >= 256 && d.N >= 128 && tiles(256, 128) >= 512) { pl.bm = 256; pl.bn = 128; pl.bku = 4; }
   else if (d.M >= 256 && d.N >= 256 && tiles(256, 256) >= 512) { pl.bm = 256; pl.bn = 256; }

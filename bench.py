@@ -32,29 +32,29 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "a854636fc32541b0"
+TRAFFIC_SOURCES = "94470dba05c6a169"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43637723,
-             "gemm_dx": 42139989, "gemm_fwd": 62126048, "perturb": 201945515},
-    "cfg3": {"bias_grad": 13681839, "center": 1773571904, "descent": 17231771605, "gemm_dw":
-             445792775, "gemm_dx": 250125392, "gemm_fwd": 233096379, "perturb": 5065985707,
-             "softmax_ce": 1429163},
-    "cfg4": {"center": 3200046208, "descent": 25600045696, "perturb": 9600050773,
-             "sumsq_partials": 3416879744},
-    "cfg5": {"bias_grad": 118056567, "descent": 188969451947, "gemm_dw": 4955259089, "gemm_dx":
-             2332944796, "gemm_fwd": 2034451980, "perturb": 59024472875, "softmax_ce": 95750080},
-    "cnn5": {"bias_grad": 17357404, "conv_first": 80454123, "descent": 79476736, "gemm_dw":
-             67284491, "gemm_dx": 34799957, "gemm_fwd": 38354453, "perturb": 29813760, "pool":
-             68580971},
-    "cnn5bn": {"batchnorm": 169146827, "bias_grad": 17357404, "conv_first": 80452533, "descent":
-             79542272, "gemm_dw": 67280558, "gemm_dx": 34799957, "gemm_fwd": 38354560, "perturb":
-             29838336, "pool": 68580743},
-    "vgg16": {"batchnorm": 193733794, "bias_grad": 31509416, "conv_first": 155211531, "descent":
-             1952546133, "gemm_dw": 143461108, "gemm_dx": 16973995, "gemm_fwd": 138024610,
-             "perturb": 732214827, "pool": 89622364},
-    "vgg16bf": {"batchnorm": 193728038, "bias_grad": 36031437, "conv_first": 155217344, "descent":
-             1952546987, "gemm_dw": 129604125, "gemm_dx": 12109141, "gemm_fwd": 135383642,
-             "perturb": 732214997, "pool": 89622451, "softmax_ce": 114005},
+    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43589232,
+             "gemm_dx": 42146133, "gemm_fwd": 62122997, "perturb": 201945429},
+    "cfg3": {"bias_grad": 13681890, "center": 1773570112, "descent": 17231501333, "gemm_dw":
+             445826255, "gemm_dx": 250125365, "gemm_fwd": 233098194, "perturb": 5065988821,
+             "softmax_ce": 1428821},
+    "cfg4": {"center": 3200044544, "descent": 25600045867, "perturb": 9600049877,
+             "sumsq_partials": 3416543712},
+    "cfg5": {"bias_grad": 118044799, "descent": 188957322731, "gemm_dw": 4961568366, "gemm_dx":
+             2332863538, "gemm_fwd": 2034720605, "perturb": 59024614101, "softmax_ce": 95614747},
+    "cnn5": {"bias_grad": 17357404, "conv_first": 80460864, "descent": 79476736, "gemm_dw":
+             67374660, "gemm_dx": 34806101, "gemm_fwd": 38355959, "perturb": 29813760, "pool":
+             68580939},
+    "cnn5bn": {"batchnorm": 169144843, "bias_grad": 17357404, "conv_first": 80450133, "descent":
+             79542272, "gemm_dw": 67408871, "gemm_dx": 34806101, "gemm_fwd": 38355149, "perturb":
+             29838336, "pool": 68580732},
+    "vgg16": {"batchnorm": 193743347, "bias_grad": 31509419, "conv_first": 155205899, "descent":
+             1952545835, "gemm_dw": 140501765, "gemm_dx": 16980139, "gemm_fwd": 138096834,
+             "perturb": 732214656, "pool": 89622317},
+    "vgg16bf": {"batchnorm": 193735147, "bias_grad": 36031441, "conv_first": 155206752, "descent":
+             1952546944, "gemm_dw": 129598630, "gemm_dx": 12106752, "gemm_fwd": 135390572,
+             "perturb": 732214784, "pool": 89622381, "softmax_ce": 114005},
 }
 
 

@@ -40,6 +40,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 struct ConvMap {
   int C, H, W;
   float invW, invH;
+  int step_rows;   // image rows a k-step of 32 pixels advances, if 4 | W and W | 32; else 0
 };
 
 struct GemmParams {
@@ -122,6 +123,11 @@ struct TileLoader {
   int pre_off[IMPL ? NPRE : 1];   // byte offset that does not change from k-step to k-step
   int pre_i[IMPL ? NPRE : 1];     // IMPL 1: image row of the unit's pixel; 2: row shift of its tap
   int pre_j[IMPL ? NPRE : 1];     // IMPL 1: image column;                 2: column shift
+  // IMPL 2: image row and column of each block's first pixel, carried from one k-step to the
+  // next (k-steps come in order: 32 pixels further the column is the same when W | 32 and the
+  // row has advanced by 32 / W), so that only the first k-step pays for a decode
+  int cur_i[IMPL == 2 ? NPRE : 1], cur_j[IMPL == 2 ? NPRE : 1];
+  int next_k0u = -1;
 
   // What stays fixed while a tile is computed.  row0/rows: first tile row and row extent
   // (IMPL 1: pixels; IMPL 2: columns tap * C + c, extent 9 C).
@@ -178,17 +184,34 @@ struct TileLoader {
       for (int j = 0; j < NBLK; ++j) {
         const int b = tid + kThreads * j;
         const int kb = b / (R / UE);
+        // the block's four pixels start at a multiple of 4: with 4 | W they share an image row
+        // and one decode serves them all
+        const bool one_row = (cm.W & 3) == 0;
+        int pi0 = 0, pj0 = 0;
+        if (BKU * UE == 32 && cm.step_rows > 0 && k0u == next_k0u) {
+          pi0 = cur_i[j];
+          pj0 = cur_j[j];
+        } else if (one_row) {
+          pixel_coords((k0u + kb) * UE, cm, pi0, pj0);
+        }
+        if (BKU * UE == 32 && cm.step_rows > 0) {
+          int ni = pi0 + cm.step_rows;
+          while (ni >= cm.H) ni -= cm.H;
+          cur_i[j] = ni;
+          cur_j[j] = pj0;
+        }
 #pragma unroll
         for (int i = 0; i < UE; ++i) {
           const int k = (k0u + kb) * UE + i;
-          int pi, pj;
-          pixel_coords(k, cm, pi, pj);
+          int pi = pi0, pj = pj0 + i;
+          if (!one_row) pixel_coords(k, cm, pi, pj);
           const bool ok = k < kd && (unsigned)(pi + pre_i[j]) < (unsigned)cm.H &&
                           (unsigned)(pj + pre_j[j]) < (unsigned)cm.W;
           reg[j * UE + i] = __builtin_amdgcn_raw_buffer_load_b128(
               rsrc, ok ? (unsigned)(k * cm.C * ES + pre_off[j]) : kOob, 0, 0);
         }
       }
+      next_k0u = k0u + BKU;
     }
   }
 
@@ -870,7 +893,7 @@ int launch_gemm(const GemmDesc& d, hipStream_t s, int* sumsq_slots) {
   p.partial = nullptr; p.strideSplit = 0; p.ldP = 0; p.splits = 1; p.steps_per_split = 1 << 30;
   p.sumsq = d.sumsq; p.strideSumsq = d.sumsq_stride;
   if (d.M <= 0 || d.N <= 0 || d.Kd <= 0 || d.batch <= 0) return -1;
-  p.cm = ConvMap{0, 1, 1, 1.f, 1.f};
+  p.cm = ConvMap{0, 1, 1, 1.f, 1.f, 0};
   if (d.unfold) {
     // a k-step (32 floats) must lie inside one tap; pixel indices must be exact in fp32; the
     // contraction (mode 1) or the column extent (mode 2) is the unfolded width 9 C
@@ -879,7 +902,8 @@ int launch_gemm(const GemmDesc& d, hipStream_t s, int* sumsq_slots) {
         pixels % ((long long)d.unfold_H * d.unfold_W) || pixels >= (1 << 24) ||
         pixels * d.unfold_C * 4 >= 0x7FFFFFF0LL || (d.unfold == 1 ? d.Kd : d.N) != 9 * d.unfold_C)
       return -1;
-    p.cm = ConvMap{d.unfold_C, d.unfold_H, d.unfold_W, 1.f / (float)d.unfold_W, 1.f / (float)d.unfold_H};
+    p.cm = ConvMap{d.unfold_C, d.unfold_H, d.unfold_W, 1.f / (float)d.unfold_W, 1.f / (float)d.unfold_H,
+                   (d.unfold_W % 4 == 0 && 32 % d.unfold_W == 0) ? 32 / d.unfold_W : 0};
   }
   // 16-byte units: pitches must be multiples of 8 elements and bases 16-byte aligned.
   if ((d.ldA % 8) || (d.ldB % 8) || (d.ldC % 8) || ((uintptr_t)d.A & 15) ||

@@ -32,29 +32,29 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "94470dba05c6a169"
+TRAFFIC_SOURCES = "c607415c9c3d3b32"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43589232,
-             "gemm_dx": 42146133, "gemm_fwd": 62122997, "perturb": 201945429},
-    "cfg3": {"bias_grad": 13681890, "center": 1773570112, "descent": 17231501333, "gemm_dw":
-             445826255, "gemm_dx": 250125365, "gemm_fwd": 233098194, "perturb": 5065988821,
-             "softmax_ce": 1428821},
-    "cfg4": {"center": 3200044544, "descent": 25600045867, "perturb": 9600049877,
-             "sumsq_partials": 3416543712},
-    "cfg5": {"bias_grad": 118044799, "descent": 188957322731, "gemm_dw": 4961568366, "gemm_dx":
-             2332863538, "gemm_fwd": 2034720605, "perturb": 59024614101, "softmax_ce": 95614747},
-    "cnn5": {"bias_grad": 17357404, "conv_first": 80460864, "descent": 79476736, "gemm_dw":
-             67374660, "gemm_dx": 34806101, "gemm_fwd": 38355959, "perturb": 29813760, "pool":
-             68580939},
-    "cnn5bn": {"batchnorm": 169144843, "bias_grad": 17357404, "conv_first": 80450133, "descent":
-             79542272, "gemm_dw": 67408871, "gemm_dx": 34806101, "gemm_fwd": 38355149, "perturb":
-             29838336, "pool": 68580732},
-    "vgg16": {"batchnorm": 193743347, "bias_grad": 31509419, "conv_first": 155205899, "descent":
-             1952545835, "gemm_dw": 140501765, "gemm_dx": 16980139, "gemm_fwd": 138096834,
-             "perturb": 732214656, "pool": 89622317},
-    "vgg16bf": {"batchnorm": 193735147, "bias_grad": 36031441, "conv_first": 155206752, "descent":
-             1952546944, "gemm_dw": 129598630, "gemm_dx": 12106752, "gemm_fwd": 135390572,
-             "perturb": 732214784, "pool": 89622381, "softmax_ce": 114005},
+    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43579616,
+             "gemm_dx": 42146133, "gemm_fwd": 62123040, "perturb": 201945344},
+    "cfg3": {"bias_grad": 13681920, "center": 1773571840, "descent": 17232323925, "gemm_dw":
+             445895622, "gemm_dx": 250125371, "gemm_fwd": 233099093, "perturb": 5065986347,
+             "softmax_ce": 1429163},
+    "cfg4": {"center": 3200044032, "descent": 25600045952, "perturb": 9600050731,
+             "sumsq_partials": 3415772139},
+    "cfg5": {"bias_grad": 118065312, "descent": 188960032021, "gemm_dw": 4959211998, "gemm_dx":
+             2332894030, "gemm_fwd": 2034535115, "perturb": 59024471637, "softmax_ce": 95421264},
+    "cnn5": {"bias_grad": 17357404, "conv_first": 80455925, "descent": 79476736, "gemm_dw":
+             67383392, "gemm_dx": 34806101, "gemm_fwd": 38355546, "perturb": 29813760, "pool":
+             68580985},
+    "cnn5bn": {"batchnorm": 157818916, "bias_grad": 565845, "conv_first": 80454208, "descent":
+             79542272, "gemm_dw": 67409596, "gemm_dx": 34806101, "gemm_fwd": 38355593, "perturb":
+             29838336, "pool": 68580729},
+    "vgg16": {"batchnorm": 175721739, "bias_grad": 1094747, "conv_first": 155190027, "descent":
+             1952545877, "gemm_dw": 140545010, "gemm_dx": 16980139, "gemm_fwd": 138108989,
+             "perturb": 732214741, "pool": 89622327},
+    "vgg16bf": {"batchnorm": 175688327, "bias_grad": 1014282, "conv_first": 155200544, "descent":
+             1952546261, "gemm_dw": 129612735, "gemm_dx": 12106752, "gemm_fwd": 135395507,
+             "perturb": 732214827, "pool": 89622409, "softmax_ce": 114005},
 }
 
 

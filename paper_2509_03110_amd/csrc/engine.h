@@ -166,8 +166,9 @@ int launch_fold3x3(const float* dcol, int64_t strideCol, int ld, float* dX, cons
 // ([K][first_conv_chunks(rows)][Cout][32] floats of scratch), plus, if sumsq is non-null, the
 // sums of their squares in sumsq[k * sumsq_stride + slot]; returns the slots written per
 // replica (Cout / 2), or -1.  `round`: both operands of every product are rounded to bfloat16
-// first; the weight-gradient kernel then leaves db alone (it would sum rounded values): the
-// caller takes the column sums of dout instead.
+// first.  `skip_bias`: the weight-gradient kernels leave db alone (with rounded operands they
+// would sum rounded values, the caller then takes the column sums of dout instead; below a
+// batch normalisation the bias gradient is zero).
 bool first_conv_fits(int C, int Cout, int64_t rows);
 int first_conv_chunks(int64_t rows);
 int launch_first_conv_forward(const float* X, const float* params, int64_t strideParams, int64_t w_off,
@@ -175,8 +176,8 @@ int launch_first_conv_forward(const float* X, const float* params, int64_t strid
                               int64_t rows, int H, int W, int C, int Cout, hipStream_t s);
 int launch_first_conv_wgrad(const float* X, const float* dout, float* partial, float* grad,
                             int64_t strideParams, int64_t w_off, int64_t b_off, int ldw, int round,
-                            int K, int64_t rows, int H, int W, int C, int Cout, double* sumsq,
-                            int64_t sumsq_stride, hipStream_t s);
+                            int skip_bias, int K, int64_t rows, int H, int W, int C, int Cout,
+                            double* sumsq, int64_t sumsq_stride, hipStream_t s);
 // Training-mode batch normalisation of K matrices Z [rows][C] (C % 4 == 0, C <= 1024), per
 // replica and column over the rows.  Forward: stats[k][0][c] = mean, stats[k][1][c] =
 // 1/sqrt(biased variance + eps); out = relu(gamma Xh + beta), Xh = (Z - mean) stats[1], gamma

@@ -465,7 +465,8 @@ __global__ __launch_bounds__(1024) void first_conv_wgrad_finish_kernel(const flo
 // (Appendix "Batch Normalization": each worker uses the statistics of its own minibatch.)
 // Z is [K][rows][C] (C % 4 == 0, C <= 1024).  Statistics in one pass over Z that does not lose
 // digits when |mean| >> spread: every chunk of rows gets its own mean and its own sum of
-// squared deviations from that mean; the chunks are then combined in double, in a fixed order.
+// squared deviations from that mean (computed around the chunk's first row); the chunks are
+// then combined in double, in a fixed order.
 // (Chunks and thread layout: see colsum_partial_kernel.)
 __global__ __launch_bounds__(kThreads) void bn_stats_partial_kernel(const float* __restrict__ Z,
                                                                     float* __restrict__ pmean,
@@ -473,29 +474,31 @@ __global__ __launch_bounds__(kThreads) void bn_stats_partial_kernel(const float*
                                                                     long long rows, int C, int chunks,
                                                                     int chunk_rows) {
   __shared__ f32x4 buf[kThreads];
-  __shared__ f32x4 mean_s[16];
   const ChunkThread t = chunk_thread(rows, C, chunk_rows);
   const int k = blockIdx.y;
   const float* base = Z + ((long long)k * rows) * C + 4 * t.cw;
-  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  if (t.live)
-    for (long long r = t.r0 + t.grp; r < t.r1; r += 16) acc += *reinterpret_cast<const f32x4*>(base + r * C);
-  f32x4 tot = combine_groups(acc, t, buf);
-  const float inv_n = 1.f / (float)(t.r1 - t.r0);
-  if (t.grp == 0) mean_s[threadIdx.x & 15] = tot * inv_n;
-  __syncthreads();
-  const f32x4 mu = mean_s[threadIdx.x & 15];
-  acc = f32x4{0.f, 0.f, 0.f, 0.f};
-  if (t.live)
+  // One sweep: sums of (z - z0) and (z - z0)^2 with z0 the chunk's first row, a value of the
+  // data's own size, so neither sum loses digits to a mean far from zero; then
+  //   mean = z0 + s1 / n,   M2 = s2 - s1^2 / n.
+  f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f}, z0 = {0.f, 0.f, 0.f, 0.f};
+  if (t.live) {
+    z0 = *reinterpret_cast<const f32x4*>(base + t.r0 * C);
     for (long long r = t.r0 + t.grp; r < t.r1; r += 16) {
-      const f32x4 dlt = *reinterpret_cast<const f32x4*>(base + r * C) - mu;
-      acc += dlt * dlt;
+      const f32x4 dlt = *reinterpret_cast<const f32x4*>(base + r * C) - z0;
+      s1 += dlt;
+      s2 += dlt * dlt;
     }
-  tot = combine_groups(acc, t, buf);
+  }
+  const f32x4 t1 = combine_groups(s1, t, buf);
+  const f32x4 t2 = combine_groups(s2, t, buf);
   if (t.live && t.grp == 0) {
+    const float inv_n = 1.f / (float)(t.r1 - t.r0);
     const long long at = ((long long)k * chunks + blockIdx.x) * C + 4 * t.cw;
-    *reinterpret_cast<f32x4*>(pmean + at) = mu;
-    *reinterpret_cast<f32x4*>(pm2 + at) = tot;
+    *reinterpret_cast<f32x4*>(pmean + at) = z0 + t1 * inv_n;
+    f32x4 m2 = t2 - t1 * t1 * inv_n;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) m2[r] = m2[r] > 0.f ? m2[r] : 0.f;
+    *reinterpret_cast<f32x4*>(pm2 + at) = m2;
   }
 }
 
@@ -679,8 +682,8 @@ int launch_first_conv_forward(const float* X, const float* params, int64_t strid
 
 int launch_first_conv_wgrad(const float* X, const float* dout, float* partial, float* grad,
                             int64_t strideParams, int64_t w_off, int64_t b_off, int ldw, int round,
-                            int K, int64_t rows, int H, int W, int C, int Cout, double* sumsq,
-                            int64_t sumsq_stride, hipStream_t s) {
+                            int skip_bias, int K, int64_t rows, int H, int W, int C, int Cout,
+                            double* sumsq, int64_t sumsq_stride, hipStream_t s) {
   if (!first_conv_fits(C, Cout, rows)) return -1;
   const FirstConv f = first_shape(H, W, Cout, rows, strideParams, ldw);
   const int chunks = first_conv_chunks(rows);
@@ -689,7 +692,7 @@ int launch_first_conv_wgrad(const float* X, const float* dout, float* partial, f
   else if (C == 2) first_conv_wgrad_kernel<2><<<grid, kThreads, 0, s>>>(X, dout, partial, chunks, f, round);
   else first_conv_wgrad_kernel<3><<<grid, kThreads, 0, s>>>(X, dout, partial, chunks, f, round);
   first_conv_wgrad_finish_kernel<<<dim3((unsigned)(Cout / 2), (unsigned)K), 1024, 0, s>>>(
-      partial, chunks, C, grad, w_off, b_off, sumsq, sumsq_stride, f, round);
+      partial, chunks, C, grad, w_off, b_off, sumsq, sumsq_stride, f, skip_bias);
   return Cout / 2;     // sum-of-squares slots written per replica
 }
 

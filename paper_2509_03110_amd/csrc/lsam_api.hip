@@ -602,19 +602,27 @@ int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq,
       const int chunks = launch_bn_backward_partials(c->at<float>(cv.z), dout, c->at<float>(cv.stats),
                                                      part, lo.K, cv.rows, cv.Cout, s);
       if (chunks < 0) return fail(LSAM_EINVAL, "batch normalisation of convolution %d rejected", l);
-      int used = launch_bias_grad(part, 2 * cv.Cout, 0, g + ly.gam_off, lo.d_pad, lo.K, chunks, cv.Cout,
-                                  ssq ? ssq + *slots : nullptr, lo.nblk, s);
-      if (ssq) *slots += used;
-      used = launch_bias_grad(part + cv.Cout, 2 * cv.Cout, 0, g + ly.bet_off, lo.d_pad, lo.K, chunks,
-                              cv.Cout, ssq ? ssq + *slots : nullptr, lo.nblk, s);
-      if (ssq) *slots += used;
+      if (ly.bet_off == ly.gam_off + cv.Cout) {
+        // gamma and beta are neighbours in the layout (64 | C_out): one sum over both halves
+        const int used = launch_bias_grad(part, 2 * cv.Cout, 0, g + ly.gam_off, lo.d_pad, lo.K, chunks,
+                                          2 * cv.Cout, ssq ? ssq + *slots : nullptr, lo.nblk, s);
+        if (ssq) *slots += used;
+      } else {
+        int used = launch_bias_grad(part, 2 * cv.Cout, 0, g + ly.gam_off, lo.d_pad, lo.K, chunks,
+                                    cv.Cout, ssq ? ssq + *slots : nullptr, lo.nblk, s);
+        if (ssq) *slots += used;
+        used = launch_bias_grad(part + cv.Cout, 2 * cv.Cout, 0, g + ly.bet_off, lo.d_pad, lo.K, chunks,
+                                cv.Cout, ssq ? ssq + *slots : nullptr, lo.nblk, s);
+        if (ssq) *slots += used;
+      }
       launch_bn_backward_apply(c->at<float>(cv.z), dout, c->at<float>(cv.stats), params, g, lo.d_pad,
                                ly.gam_off, ly.bet_off, lo.K, cv.rows, cv.Cout, s);
     }
     if (cv.first) {
       LaunchTimer t(c, KC_CONV_FIRST);
       const int used = launch_first_conv_wgrad(X, dout, c->at<float>(cv.first_partial), g, lo.d_pad,
-                                               ly.w_off, ly.b_off, ly.ldw, lo.bf16_math ? 1 : 0, lo.K,
+                                               ly.w_off, ly.b_off, ly.ldw, lo.bf16_math ? 1 : 0,
+                                               (lo.bf16_math || cv.bn) ? 1 : 0, lo.K,
                                                cv.rows, cv.H, cv.W, cv.Cin, cv.Cout,
                                                ssq ? ssq + *slots : nullptr, lo.nblk, s);
       if (used < 0) return fail(LSAM_EINVAL, "first convolution's weight gradient rejected");
@@ -641,7 +649,11 @@ int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq,
       if (launch_gemm(d, s, &used) != 0) return fail(LSAM_EINVAL, "dW GEMM of convolution %d rejected", l);
       if (ssq) *slots += used;
     }
-    {
+    // The bias of a normalised convolution has no influence on the loss: its gradient, the
+    // column sums of dZ = gamma/sigma (dY - mean dY - Xh mean(dY Xh)), is zero because Xh sums
+    // to zero.  It is left at the zero the gradient buffer starts from instead of being summed
+    // up as rounding noise.
+    if (!cv.bn) {
       // bias gradient: column sums of dout, in two fixed-order stages
       LaunchTimer t(c, KC_BIAS_GRAD);
       const int chunks = launch_colsum_partials(dout, cv.rows, cv.Cout, lo.K, c->at<float>(lo.colsum), s);

@@ -538,6 +538,12 @@ CNN_SMALL = workloads.Workload("cnn_small", K=2, dims=(3, 8, 16, 24, 5), batch=6
         dims=(3, 32, 32, 64, 10), n_conv=3, pool_mask=0b101, bn_mask=0b111, n_classes=10, batch=5)),
     ("batch norm in a four-convolution stack", dict(
         dims=(3, 32, 32, 24, 40, 10), n_conv=4, pool_mask=0b0110, bn_mask=0b1010, n_classes=10, batch=8)),
+    # degenerate sizes: one sample per replica (normalisation over the pixels only), an image
+    # that pools down to a single pixel, the largest replica count
+    ("batch of one, normalised", dict(batch=1, bn_mask=0b11, img_h=4, img_w=4)),
+    ("2x2 image pooled to one pixel", dict(dims=(3, 32, 32, 7), n_conv=2, pool_mask=0b10, img_h=2,
+                                           img_w=2, n_classes=7, batch=9)),
+    ("64 replicas", dict(K=64, batch=2, img_h=4, img_w=4, pool_mask=0b01, tau=tuple([2, 3] * 32))),
     ("unfolding inside the GEMM, sides not powers of two", dict(
         dims=(4, 32, 64, 12, 6), n_conv=2, pool_mask=0b10, img_h=6, img_w=10, n_classes=6, batch=7)),
 ])

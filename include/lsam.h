@@ -39,13 +39,15 @@
  * included, are fp32 in memory in both arithmetic modes: with LSAM_GEMM_BF16 every matrix
  * product (each convolution and dense layer, forward, dW and dX) rounds its two operands to
  * bfloat16 (nearest even) on their way into the matrix unit and accumulates in fp32; biases,
- * normalisation, pooling, the loss and the bias gradients (sums of the unrounded dZ) are fp32.  The pool's gradient goes to
- * the first maximum of a window in row-major order.
+ * normalisation, pooling, the loss and the bias gradients (sums of the unrounded dZ) are fp32.
+ * The pool's gradient goes to the first maximum of a window in row-major order.
  * A batch-normalised convolution (bn_mask) computes, per replica and channel over the B H W
  * positions of that replica's minibatch, Y = gamma (Z - mean) / sqrt(var + bn_eps) + beta before
  * the ReLU (training mode; the backward pass differentiates through mean and var; Appendix
  * "Batch Normalization": workers do not synchronise these statistics).  Its gamma [C_{l+1}]
- * and beta [C_{l+1}] follow b_l in the flat layout.  No running averages are kept.
+ * and beta [C_{l+1}] follow b_l in the flat layout.  No running averages are kept.  The bias
+ * b_l of such a layer cannot influence the loss; its gradient is reported as exactly zero.
+ * LSAM_BUF_PERTURBED holds x~_i in both arithmetic modes of this model (no bf16 copy exists).
  */
 #ifndef LSAM_H
 #define LSAM_H

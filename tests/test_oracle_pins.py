@@ -726,3 +726,132 @@ def test_cnn_bf16_products_round_their_operands_only():
     expect = F.cross_entropy(Z, torch.tensor([0, 2])).item()
     got, _ = m.loss_and_grad(x, Xr, np.array([0, 2]))
     assert abs(got - expect) < 1e-12
+
+
+# ---- where bf16 rounding sits in a two-layer model: a case worked by hand ------------------
+# Network 2-3-3, one sample, label 0.  u = 2^-8 is half a bf16 step in [1, 2), so 1 + u and
+# 1 + 3u are ties: nearest-even sends 1 + u to 1 and 1 + 3u to 1 + 4u = 1.015625.
+#   X  = (1 + u, 2)                                    -> fed as (1, 2)
+#   W1 = [[1 + 3u, 0.5 - u], [-1, 0.25], [1 + u, 1]]   -> fed as [[1.015625, 0.49609375], [-1, .25], [1, 1]]
+#   b1 = (1 + 3u, 0, 2u)                               (biases are never rounded)
+#   Z1 = (1.015625 + 0.9921875 + 1.01171875, -1 + 0.5, 1 + 2 + 0.0078125)
+#      = (3.01953125, -0.5, 3.0078125)
+#   A1 = bf16(relu Z1): the step in [2, 4) is 2^-6; 3.01953125 = 3 + 1.25 steps -> 3.015625;
+#        3.0078125 = 3 + half a step, a tie -> the even neighbour 3.0.   A1 = (3.015625, 0, 3)
+#   W2 = [[1 + u, 7, 0.5], [1 + 3u, -3, 0.25], [0.5, 2, -1]]   -> first column fed as (1, 1.015625, 0.5)
+#   b2 chosen so that all three logits are exactly 5:
+#        5 - (3.015625 + 1.5), 5 - (3.015625 * 1.015625 + 0.75), 5 - (1.5078125 - 3)
+#   softmax = (1/3, 1/3, 1/3), loss = ln 3, dZ2 = (-2/3, 1/3, 1/3)
+#   bf16(1/3): 1/3 = 1.0101010|1010..b x 2^-2, the cut-off part is above half -> 1.0101011b x 2^-2
+#        = 171/512 =: a;  bf16(-2/3) = -2a.     fed dZ2 = (-2a, a, a)
+#   dW2[c][j] = fed dZ2[c] * A1[j];   db2 = fed dZ2 (dense model) / unrounded dZ2 (convolutional model)
+#   dA1[j] = sum_c fed dZ2[c] * fed W2[c][j]:
+#        j=0: a (-2 + 1.015625 + 0.5) = -0.484375 a;  j=1: a (-14 - 3 + 2) = -15 a, masked (A1[1] = 0);
+#        j=2: a (-1 + 0.25 - 1) = -1.75 a
+#   dZ1 = (-0.161773681640625, 0, -0.58447265625)
+#   bf16(dZ1): 0.16177.. = 165.66/128 x 2^-3 -> 166/128 x 2^-3 = 0.162109375;
+#              0.58447.. = 149.63/128 x 2^-1 -> 150/128 x 2^-1 = 0.5859375
+#   dW1[j][i] = fed dZ1[j] * fed X[i];  db1 = fed dZ1 (dense) / unrounded dZ1 (convolutional)
+# Every alternative placement changes a number below: X or W1 unrounded moves A1[0] resp. A1[2]
+# to the next bf16 value; b1 rounded makes Z1[0] a tie that goes up to 3.03125; A1 unrounded
+# breaks the equal logits; W2 unrounded in dX gives dZ1[0] -> 0.166015625; dZ2 unrounded in dX
+# gives 0.1611328125; dZ1 unrounded before dW1 gives 0.16177...; a forgotten mask fills row 1 of dW1.
+_U = 2.0 ** -8
+_A = 171.0 / 512.0
+_HAND_X = np.array([[1 + _U, 2.0]])
+_HAND_W1 = np.array([[1 + 3 * _U, 0.5 - _U], [-1.0, 0.25], [1 + _U, 1.0]])
+_HAND_B1 = np.array([1 + 3 * _U, 0.0, 2 * _U])
+_HAND_W2 = np.array([[1 + _U, 7.0, 0.5], [1 + 3 * _U, -3.0, 0.25], [0.5, 2.0, -1.0]])
+_HAND_B2 = np.array([5 - 4.515625, 5 - (3.015625 * 1.015625 + 0.75), 5 + 1.4921875])
+_HAND_DW2 = np.array([[-2 * _A * 3.015625, 0.0, -2 * _A * 3.0],
+                      [_A * 3.015625, 0.0, _A * 3.0],
+                      [_A * 3.015625, 0.0, _A * 3.0]])
+_HAND_DZ2_FED = np.array([-2 * _A, _A, _A])
+_HAND_DZ1 = np.array([-0.161773681640625, 0.0, -0.58447265625])
+_HAND_DZ1_FED = np.array([-0.162109375, 0.0, -0.5859375])
+_HAND_DW1 = np.array([[-0.162109375, -0.32421875], [0.0, 0.0], [-0.5859375, -1.171875]])
+
+
+def test_bf16_rounding_placement_two_layer_dense_hand_case():
+    assert _HAND_DW2[0, 0] == -2.01434326171875 and _HAND_DW2[1, 2] == 1.001953125   # as worked above
+    m = Mlp((2, 3, 3), gemm_dtype=1)
+    x = np.concatenate([_HAND_W1.ravel(), _HAND_B1, _HAND_W2.ravel(), _HAND_B2])
+    assert np.array_equal(x.astype(np.float32).astype(np.float64), x)     # all inputs are fp32 numbers
+    loss, g = m.loss_and_grad(x, _HAND_X, np.array([0]))
+    (w1a, w1b, b1b), (w2a, w2b, b2b) = m.offsets
+    tol = 1e-15
+    assert abs(loss - np.log(3.0)) < 1e-15
+    assert np.max(np.abs(g[w2a:w2b].reshape(3, 3) - _HAND_DW2)) < tol
+    assert np.max(np.abs(g[w2b:b2b] - _HAND_DZ2_FED)) < tol            # db sums the rounded dZ
+    assert np.max(np.abs(g[w1a:w1b].reshape(3, 2) - _HAND_DW1)) < tol
+    assert np.max(np.abs(g[w1b:b1b] - _HAND_DZ1_FED)) < tol
+
+
+def test_bf16_rounding_placement_convolutional_model_hand_case():
+    # The same numbers through the convolutional model: a 3x3 convolution on a 1x1 image only
+    # ever sees its centre tap, so it is the dense layer W1 above; the other eight taps read the
+    # zero rim and must get a zero gradient.  Here tensors are stored unrounded and only the
+    # operands of a product are rounded, so the two bias gradients are the unrounded dZ.
+    from oracle.lsam_oracle import Cnn
+    m = Cnn((2, 3, 3), 1, 1, 1, 0, gemm_dtype=1)
+    filt = np.zeros((3, 3, 3, 2))
+    filt[:, 1, 1, :] = _HAND_W1
+    rng = np.random.default_rng(4)
+    other = rng.standard_normal((3, 3, 3, 2))
+    other[:, 1, 1, :] = 0.0
+    x = np.concatenate([(filt + other).ravel(), _HAND_B1, _HAND_W2.ravel(), _HAND_B2])
+    loss, g = m.loss_and_grad(x, _HAND_X.reshape(1, 1, 1, 2), np.array([0]))
+    (w1a, w1b, b1b), (w2a, w2b, b2b) = m.offsets
+    tol = 1e-15
+    assert abs(loss - np.log(3.0)) < 1e-15
+    assert np.max(np.abs(g[w2a:w2b].reshape(3, 3) - _HAND_DW2)) < tol
+    assert np.max(np.abs(g[w2b:b2b] - np.array([-2.0, 1.0, 1.0]) / 3.0)) < tol
+    dw1 = g[w1a:w1b].reshape(3, 3, 3, 2)
+    assert np.max(np.abs(dw1[:, 1, 1, :] - _HAND_DW1)) < tol
+    dw1[:, 1, 1, :] = 0.0
+    assert np.max(np.abs(dw1)) == 0.0
+    assert np.max(np.abs(g[w1b:b1b] - _HAND_DZ1)) < tol
+
+
+_MISPLACED_ROUNDINGS = [
+    # (model the planted mistake belongs to, text of the oracle, what it is replaced by)
+    ("dense", "acts.append(q(np.maximum(Z, 0.0)) if l < self.L - 1 else Z)", "acts.append(np.maximum(Z, 0.0))"),
+    ("dense", "acts = [q(X)]", "acts = [np.asarray(X, dtype=np.float64)]"),
+    ("dense", "Z = acts[l] @ q(W).T + b", "Z = acts[l] @ W.T + b"),
+    ("dense", "Z = acts[l] @ q(W).T + b", "Z = acts[l] @ q(W).T + q(b)"),
+    ("dense", "grad[o0:o1] = (dZq.T @ acts[l]).ravel()", "grad[o0:o1] = (dZ.T @ acts[l]).ravel()"),
+    ("dense", "grad[o1:o2] = dZq.sum(axis=0)", "grad[o1:o2] = dZ.sum(axis=0)"),
+    ("dense", "dA = dZq @ q(W)", "dA = dZ @ q(W)"),
+    ("dense", "dA = dZq @ q(W)", "dA = dZq @ W"),
+    ("dense", "dZ = dA * (acts[l] > 0.0)", "dZ = dA"),
+    ("conv", "grad[o1:o2] = dZ.sum(axis=0)", "grad[o1:o2] = q(dZ).sum(axis=0)"),
+    ("conv", "grad[o1:o2] = flat.sum(axis=0)", "grad[o1:o2] = flatq.sum(axis=0)"),
+    ("conv", "Z = q(acts[-1]) @ q(x[o0:o1].reshape(fo, fi)).T", "Z = acts[-1] @ q(x[o0:o1].reshape(fo, fi)).T"),
+    ("conv", "grad[o0:o1] = (q(dZ).T @ q(a_in)).ravel()", "grad[o0:o1] = (dZ.T @ q(a_in)).ravel()"),
+    ("conv", "grad[o0:o1] = (q(dZ).T @ q(a_in)).ravel()", "grad[o0:o1] = (q(dZ).T @ a_in).ravel()"),
+    ("conv", "dA = q(dZ) @ q(x[o0:o1].reshape(fo, fi))", "dA = q(dZ) @ x[o0:o1].reshape(fo, fi)"),
+    ("conv", "dW[:, u, v, :] = flatq.T @", "dW[:, u, v, :] = flat.T @"),
+    ("conv", "Z += Apq[:, u:u + h, v:v + w, :] @ Wq[:, u, v, :].T", "Z += Ap[:, u:u + h, v:v + w, :] @ Wq[:, u, v, :].T"),
+    ("conv", "Z += Apq[:, u:u + h, v:v + w, :] @ Wq[:, u, v, :].T", "Z += Apq[:, u:u + h, v:v + w, :] @ Wl[:, u, v, :].T"),
+]
+
+
+@pytest.mark.parametrize("case", range(len(_MISPLACED_ROUNDINGS)))
+def test_hand_cases_catch_a_misplaced_rounding(case, monkeypatch):
+    """Plants one misplaced (or dropped) rounding in a copy of the oracle's source and checks
+    that the hand-worked case of that model fails on it."""
+    import types
+    import oracle.lsam_oracle as real
+    which, old, new = _MISPLACED_ROUNDINGS[case]
+    src = open(real.__file__).read()
+    assert src.count(old) >= 1, "the oracle no longer contains: " + old
+    planted = types.ModuleType("planted_oracle")
+    exec(compile(src.replace(old, new, 1), "planted_oracle", "exec"), planted.__dict__)
+    if which == "dense":
+        monkeypatch.setitem(globals(), "Mlp", planted.Mlp)
+        check = test_bf16_rounding_placement_two_layer_dense_hand_case
+    else:
+        monkeypatch.setattr(real, "Cnn", planted.Cnn)
+        check = test_bf16_rounding_placement_convolutional_model_hand_case
+    with pytest.raises(AssertionError):
+        check()

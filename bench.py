@@ -154,12 +154,14 @@ def conv_bytes(w):
 
 def stream_bytes(w):
     """Algorithmic bytes per all-replica step of the update-path kernels (reads + writes
-    the method itself requires; y is shared by the K replicas)."""
+    the method itself requires; y is shared by the K replicas): descent reads x, g2, v, S
+    (16 B per parameter) and writes x, v, S (12 B), plus the bf16 operand copy (2 B) in bf16
+    mode, plus y once for all replicas."""
     n = float(w.K) * w.d
-    bf = w.gemm_dtype == 1
+    bf = w.gemm_dtype == 1 and not w.n_conv
     return {"sumsq_partials": 4 * n,
             "perturb": (10 if bf else 12) * n,
-            "descent": (34 if bf else 32) * n + 4.0 * w.d}
+            "descent": (30 if bf else 28) * n + 4.0 * w.d}
 
 
 def make_inputs(w, torch, dev, n_sets):
@@ -201,7 +203,9 @@ def cpu_baseline(w, budget_s=20.0):
                     break
             dt = time.perf_counter() - t0
             value = n * ws.batch / dt
-            sample = "%d step(s) of 1 replica at batch %d (of K=%d, B=%d)" % (n, ws.batch, w.K, w.batch)
+            sample = ("%d step(s) of 1 replica at batch %d (of K=%d, B=%d); samples/s of that bounded "
+                      "sample, taken as the rate of the whole workload (work per sample is the same: "
+                      "extrapolated)" % (n, ws.batch, w.K, w.batch))
             unit = "replica-samples/s"
         else:
             d = min(w.d_raw, 10_000_000)
@@ -217,7 +221,8 @@ def cpu_baseline(w, budget_s=20.0):
                     break
             dt = time.perf_counter() - t0
             value = n * d / dt
-            sample = "%d iteration(s) of 1 replica at d=%d (of K=%d, d=%d)" % (n, d, w.K, w.d_raw)
+            sample = ("%d iteration(s) of 1 replica at d=%d (of K=%d, d=%d); extrapolated as above"
+                      % (n, d, w.K, w.d_raw))
             unit = "replica-params/s"
     model = "unknown"
     try:
@@ -232,35 +237,16 @@ def cpu_baseline(w, budget_s=20.0):
             "host_cpu": model, "host_cores": os.cpu_count()}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg2", choices=sorted(workloads.WORKLOADS))
-    ap.add_argument("--algorithm", type=int, default=0, choices=[0, 1],
-                    help="0 = LSAM (default), 1 = synchronous data-parallel baseline")
-    ap.add_argument("--noise-scale", type=float, default=0.0,
-                    help="sigma of the Langevin sampler (0 = noise-free, the default)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-kernel-timing", action="store_true")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: the path holds all K replicas on a single MI355X and "
-              "uses no collectives, so --gpus %d is not supported." % args.gpus, file=sys.stderr)
-        sys.exit(2)
+def default_steps(w):
+    return {"cfg1": 200, "cfg2": 200, "cnn5": 100, "cnn5bn": 100}.get(w.name, 20)
 
+
+def run_workload(w, steps, warmup, kernel_timing=True):
+    """Times `steps` steps of workload `w` after `warmup` untimed ones; returns the fields of
+    the JSON line that belong to this workload."""
     import torch
     from paper_2509_03110_amd import lsam
-    if not torch.cuda.is_available():
-        print("no GPU visible", file=sys.stderr)
-        sys.exit(1)
     dev = torch.device("cuda:0")
-    w = workloads.WORKLOADS[args.workload]
-    if args.algorithm or args.noise_scale:
-        w = w.scaled(algorithm=args.algorithm, noise_scale=args.noise_scale, noise_seed=1)
-    steps = args.steps if args.steps is not None else {"cfg1": 200, "cfg2": 200, "cnn5": 100, "cnn5bn": 100}.get(w.name, 20)
-
     cfg, keep = lsam.config_from_workload(w)
     eng = lsam.Lsam(cfg, workloads.init_params(w), device=dev, keep=keep)
     sets = make_inputs(w, torch, dev, w.batch_pool or 8)
@@ -274,7 +260,7 @@ def main():
             eng.lsam_step_grads(a, b)
         eng.lsam_sync()
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         one(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -292,7 +278,7 @@ def main():
             "replica-params/sec per LSAM update iteration"
 
     roof, kernels = None, {}
-    if not args.no_kernel_timing:
+    if kernel_timing:
         eng.lsam_timing_enable(True)
         for i in range(steps):
             one(i)
@@ -303,7 +289,7 @@ def main():
         nbytes.update(conv_bytes(w))
         # center update: 8 B/param per due replica (S read, S cleared) + 16 B/param (y and
         # g'_prev read and written), summed over the ticks of this run that had a sync
-        first = args.warmup + steps
+        first = warmup + steps
         due, _ = lsam.lsam_schedule_replay(cfg, first + steps)
         nd = due[first:].sum(axis=1)
         nbytes["center"] = float(np.sum((8.0 * nd + 16.0) * (nd > 0))) * w.d / steps
@@ -335,7 +321,7 @@ def main():
 
     out = {
         "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": steps,
-        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "warmup": warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32" if (w.gemm_dtype == 0) else "bf16 operands, f32 accumulate and master weights",
         "data": "synthetic",
@@ -348,19 +334,80 @@ def main():
         "roofline": roof, "kernels": kernels,
     }
     eng.close()
-    if not args.no_kernel_timing:
-        # the same fractions against what the simplest kernels reach on this very device
+    del eng, sets
+    torch.cuda.empty_cache()
+    return out
+
+
+def add_measured_fractions(out, w, peaks):
+    """The same fractions against what the simplest kernels reach on this very device."""
+    copy_gbs, bf16_tf, f32_tf = peaks
+    mfma_meas = bf16_tf if w.gemm_dtype == 1 else f32_tf
+    for k in list(out["kernels"].values()) + ([out["roofline"]] if out["roofline"] else []):
+        if k.get("bound") == "mfma":
+            k["frac_of_measured"] = k["achieved"] / mfma_meas
+        elif k.get("bound") == "hbm":
+            k["frac_of_measured"] = k["achieved"] / copy_gbs
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg5", choices=sorted(workloads.WORKLOADS),
+                    help="the timed workload (default: the largest configuration that fits one GPU)")
+    ap.add_argument("--also", default=None,
+                    help="comma-separated workloads reported in short form under `other_workloads` "
+                         "(default: cfg2,cfg3,cfg4 when the workload is cfg5; 'none' for none)")
+    ap.add_argument("--algorithm", type=int, default=0, choices=[0, 1],
+                    help="0 = LSAM (default), 1 = synchronous data-parallel baseline")
+    ap.add_argument("--noise-scale", type=float, default=0.0,
+                    help="sigma of the Langevin sampler (0 = noise-free, the default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the path holds all K replicas on a single MI355X and "
+              "uses no collectives, so --gpus %d is not supported." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2509_03110_amd import lsam
+    if not torch.cuda.is_available():
+        print("no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    w = workloads.WORKLOADS[args.workload]
+    if args.algorithm or args.noise_scale:
+        w = w.scaled(algorithm=args.algorithm, noise_scale=args.noise_scale, noise_seed=1)
+    steps = args.steps if args.steps is not None else default_steps(w)
+    timing = not args.no_kernel_timing
+
+    out = run_workload(w, steps, args.warmup, timing)
+    also = args.also if args.also is not None else ("cfg2,cfg3,cfg4" if w.name == "cfg5" else "none")
+    others = {}
+    for name in [n for n in also.split(",") if n and n != "none" and n != w.name]:
+        wo = workloads.WORKLOADS[name]
+        others[name] = (wo, run_workload(wo, min(default_steps(wo), 50), args.warmup, timing))
+    if timing:
         scratch = torch.empty(1 << 28, dtype=torch.float32, device=dev)          # 1 GiB
-        copy_gbs, bf16_tf, f32_tf = lsam.lsam_probe_peaks(scratch)
+        peaks = lsam.lsam_probe_peaks(scratch)
         del scratch
-        out["measured_peaks"] = {"copy_GBps": copy_gbs, "mfma_bf16_TFLOPs": bf16_tf,
-                                 "mfma_f32_TFLOPs": f32_tf}
-        mfma_meas = bf16_tf if w.gemm_dtype == 1 else f32_tf
-        for k in list(kernels.values()) + ([roof] if roof else []):
-            if k.get("bound") == "mfma":
-                k["frac_of_measured"] = k["achieved"] / mfma_meas
-            elif k.get("bound") == "hbm":
-                k["frac_of_measured"] = k["achieved"] / copy_gbs
+        out["measured_peaks"] = {"copy_GBps": peaks[0], "mfma_bf16_TFLOPs": peaks[1],
+                                 "mfma_f32_TFLOPs": peaks[2]}
+        add_measured_fractions(out, w, peaks)
+        for wo, r in others.values():
+            add_measured_fractions(r, wo, peaks)
+    if others:
+        keep = ("bound", "achieved", "peak", "unit", "frac", "frac_of_measured", "ms_per_step",
+                "avg_launch_ms", "launches_per_step")
+        out["other_workloads"] = {
+            name: {"value": r["value"], "unit": r["unit"], "ms_per_step": r["ms_per_step"],
+                   "steps": r["steps"], "dtype": r["dtype"],
+                   "kernels": {k: {f: v[f] for f in keep if f in v} for k, v in r["kernels"].items()
+                               if "achieved" in v}}
+            for name, (wo, r) in others.items()}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

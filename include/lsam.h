@@ -19,7 +19,8 @@
  *   - All kernels are enqueued on the caller's stream (a hipStream_t passed as void*,
  *     NULL = the default stream).  `lsam_step` and `lsam_sync` do not block the host,
  *     allocate nothing and may be captured into a HIP graph (the host-side counters --
- *     periods, local counts, the noise step -- advance at capture, not at replay).  The
+ *     periods, local counts, the noise step -- advance at capture, not at replay; see
+ *     lsam_note_replay).  The
  *     read-out and restore calls synchronise the stream and move data through a pinned
  *     host staging buffer (64 MiB, allocated by the context on first use, freed by
  *     `lsam_destroy`).
@@ -88,8 +89,8 @@ extern "C" {
 
 typedef struct lsam_ctx lsam_ctx;
 
-/* Inputs of Algorithm 2 ("pulling coefficient lambda, perturbation radius rho, learning
- * rates (eta, eta'), sync period tau, momentum factor beta") plus the model shape. */
+/* The fields follow the input list of Algorithm 2 (coupling strength, perturbation radius, the
+ * two step sizes, communication period, look-ahead factor), plus the model shape. */
 typedef struct {
   int32_t K;              /* number of replicas = the paper's n workers, 1..LSAM_MAX_REPLICAS */
   int32_t n_layers;       /* L dense layers; 0 selects raw-vector mode                */
@@ -181,7 +182,9 @@ int lsam_get_params(lsam_ctx* ctx, int32_t replica, float* dst, int64_t n);
 int lsam_get_buffer(lsam_ctx* ctx, int32_t which, int32_t replica, float* dst, int64_t n);
 
 /* Overwrites one buffer from `src` [host] in the flat layout (restoring a snapshot taken
- * with lsam_get_buffer; together with lsam_init this is the checkpoint/resume path).
+ * with lsam_get_buffer).  Checkpoint/resume of a run is: lsam_init with the same configuration,
+ * this call for x_i, v_i, S_i, y and g'_prev, lsam_set_counters for the integer state, and
+ * lsam_set_scalars if eta or rho had been changed.
  * Valid for LSAM_BUF_PARAMS (replica -1: y), LSAM_BUF_VELOCITY, LSAM_BUF_ITER_SUM and
  * LSAM_BUF_CENTER_DIR.  In bf16 mode setting a replica's parameters also refreshes its bf16
  * operand copy.  Synchronises the stream before and after the copy. */
@@ -192,6 +195,34 @@ int lsam_get_norms(lsam_ctx* ctx, float* dst);
 
 /* Schedule state: any of the outputs may be NULL.  tau_out, count_out [host] [K]. */
 int lsam_get_schedule(lsam_ctx* ctx, int32_t* tau_out, int32_t* count_out, int64_t* t_y_out);
+
+/* Tells the context that a HIP graph holding one captured lsam_step (or lsam_step_grads) has
+ * been replayed once: the local counts c_i and the step number advance as they do in an eager
+ * step, with no GPU work, so that an eager lsam_sync after the replay finds the replicas that
+ * are due.  (Capturing a step advances them once as well.)  A captured step keeps the kernel
+ * arguments it was captured with -- eta, rho, lambda_i = lambda0/(eta tau_i), the noise
+ * counter -- so replay is only meaningful while those stay what they were: the call returns
+ * LSAM_ESTATE with Langevin noise switched on, and in redraw mode when lambda_i depends on the
+ * redrawn periods.  Call lsam_sync eagerly between replays: a captured lsam_sync would repeat the
+ * center update for the due set it was captured with. */
+int lsam_note_replay(lsam_ctx* ctx);
+
+/* The integer state of Algorithm 2 that no buffer holds, `state` [host] [2K+3] int64:
+ * the local iteration counts c_0..c_{K-1} since each replica's last sync (its t_x), the periods
+ * tau_0..tau_{K-1} in force, the state of the period generator (as a bit pattern), the number
+ * of center updates so far (t_y; 0 means g'_prev is not used by the next one) and the number of
+ * sampler steps taken (the step word of the Langevin noise counters).  `n` must be 2K+3.
+ * lsam_set_counters overwrites all of them (counts >= 0, periods >= 1, else LSAM_EINVAL and
+ * nothing is changed).  Host-only, no GPU work. */
+int lsam_get_counters(lsam_ctx* ctx, int64_t* state, int64_t n);
+int lsam_set_counters(lsam_ctx* ctx, const int64_t* state, int64_t n);
+
+/* Hidden activations A_layer = ReLU(Z_layer) [B, out_layer] of replica `replica` as the last
+ * forward pass left them (after lsam_step: the pass at the perturbed point; the only pass when
+ * rho = 0), for diagnosis: `dst` [host] row-major floats (bf16 mode: the stored bf16 values
+ * widened), `n` = B * out_layer, layer in 1..L-1.  Dense models only (LSAM_ESTATE otherwise).
+ * Synchronises the stream. */
+int lsam_get_activation(lsam_ctx* ctx, int32_t layer, int32_t replica, float* dst, int64_t n);
 
 /* Changes eta and rho from the next step on (decaying schedules eta_t, rho_t of the
  * convergence theorems are driven from the host through this call). */

@@ -127,6 +127,10 @@ class Mlp:
             off += fo * fi + fo
         self.d = off
         self.last_margin = np.inf   # diagnostic: smallest |hidden pre-activation| seen last call
+        # diagnostic, filled when keep_hidden is set: per hidden layer (Z, |A||W|^T + |b|) of the
+        # last call -- the pre-activations and the magnitude their rounding error scales with
+        self.keep_hidden = False
+        self.last_hidden = []
 
     def unpack(self, x):
         out = []
@@ -144,10 +148,13 @@ class Mlp:
         B = X.shape[0]
         acts = [q(X)]
         self.last_margin = np.inf
+        self.last_hidden = []
         for l, (W, b) in enumerate(layers):
             Z = acts[l] @ q(W).T + b
             if l < self.L - 1:
                 self.last_margin = min(self.last_margin, float(np.min(np.abs(Z))))
+                if self.keep_hidden:
+                    self.last_hidden.append((Z, np.abs(acts[l]) @ np.abs(q(W)).T + np.abs(b)))
             acts.append(q(np.maximum(Z, 0.0)) if l < self.L - 1 else Z)
         logits = acts[-1]
         zmax = logits.max(axis=1, keepdims=True)
@@ -481,6 +488,8 @@ class LsamOracle:
         self.last_perturbed = np.zeros((self.K, self.d))
         self.last_g1 = np.zeros((self.K, self.d))
         self.last_g2 = np.zeros((self.K, self.d))
+        # per replica: the dense model's `last_hidden` diagnostic of the first and second pass
+        self.last_hidden = [None] * self.K
 
     # -- hyper-parameters -------------------------------------------------------------
     def set_scalars(self, lr, rho):
@@ -536,9 +545,11 @@ class LsamOracle:
             Xi = np.asarray(X[i], dtype=np.float64)
             li = np.asarray(labels[i]).astype(np.int64)
             losses[i], g1 = self.model.loss_and_grad(self.x[i], Xi, li)
+            hidden1 = getattr(self.model, "last_hidden", None)
             xt = self._ascend(i, g1)
             _, g2 = self.model.loss_and_grad(xt, Xi, li)
             self.last_g1[i], self.last_g2[i] = g1, g2
+            self.last_hidden[i] = (hidden1, getattr(self.model, "last_hidden", None))
             self._descend(i, g2)
         self.sched.tick()
         self.t += 1

@@ -22,6 +22,9 @@ struct DueList {
   int32_t idx[kMaxK];
 };
 
+// Message that lsam_last_error() returns on the calling thread (copied).
+void set_last_error(const char* msg);
+
 // ---- streaming kernels (update path) ---------------------------------------------------
 
 // Sum of squares, pass 1: per (replica, block) partial sums in double.
@@ -115,7 +118,6 @@ int gemm_sumsq_capacity(int M, int N);
 size_t gemm_splitk_bytes(const GemmDesc& d);          // scratch this GEMM would like (0: none)
 // bf16 fast path (direct-to-LDS ring); returns 1 when the shape is left to the generic kernel.
 int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s, int* sumsq_slots);
-void set_gemm_tile_override(int code);               // tuning hook: 0 = choose by shape
 
 // Softmax cross-entropy, forward and backward.  logits [K,B,ld] fp32; labels [K,B];
 // dz = (softmax - onehot)/B: fp32 [K,B,ld_dz] row-major with zeros in the padded columns, or

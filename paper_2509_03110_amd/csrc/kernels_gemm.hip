@@ -73,8 +73,6 @@ __device__ __forceinline__ double workgroup_sum(double v) {
   return threadIdx.x == 0 ? (part[0] + part[1]) + (part[2] + part[3]) : 0.0;
 }
 
-int g_tile_override = 0;   // tuning hook, 0 = choose by shape
-
 template <typename T> struct Op;
 template <> struct Op<float> { static constexpr int UE = 4; };
 template <> struct Op<__bf16> { static constexpr int UE = 8; };
@@ -864,10 +862,6 @@ int launch_layout(const GemmDesc& d, const GemmParams& p, const Plan& pl, hipStr
 
 size_t gemm_splitk_bytes(const GemmDesc& d) { return make_plan(d, 0).ws_bytes; }
 
-void set_gemm_tile_override(int code) {
-  g_tile_override = code;
-}
-
 // Smallest tiles are 64x64; a split-K reduce uses one workgroup per 256 vector words of
 // [M][N rounded up to 4].
 int gemm_sumsq_capacity(int M, int N) {
@@ -879,7 +873,7 @@ int gemm_sumsq_capacity(int M, int N) {
 int launch_gemm(const GemmDesc& d, hipStream_t s, int* sumsq_slots) {
   // bf16 operands live in the blocked layout and have their own kernel; this file's kernel
   // serves the fp32 configurations
-  if (d.in_bf16) return (d.unfold || d.bf16_math) ? -1 : launch_gemm_bf16(d, g_tile_override, s, sumsq_slots);
+  if (d.in_bf16) return (d.unfold || d.bf16_math) ? -1 : launch_gemm_bf16(d, 0, s, sumsq_slots);
   GemmParams p;
   p.A = (const char*)d.A; p.strideA = d.strideA; p.ldA = d.ldA;
   p.B = (const char*)d.B; p.strideB = d.strideB; p.ldB = d.ldB;
@@ -916,7 +910,7 @@ int launch_gemm(const GemmDesc& d, hipStream_t s, int* sumsq_slots) {
   if (rowsA * d.ldA * es >= 0x7FFFFFF0LL || rowsB * d.ldB * es >= 0x7FFFFFF0LL) return -1;
   if ((d.strideA % 4) || (d.strideB % 4) || (d.strideC % 4)) return -1;
   if (d.out_bf16) return -1;
-  Plan pl = make_plan(d, g_tile_override);
+  Plan pl = make_plan(d, 0);
   if (pl.splits > 1 && d.splitk_ws != nullptr && d.splitk_bytes >= pl.ws_bytes &&
       ((uintptr_t)d.splitk_ws & 15) == 0) {
     p.partial = d.splitk_ws;

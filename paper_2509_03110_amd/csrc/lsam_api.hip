@@ -1,6 +1,7 @@
 // Host engine behind include/lsam.h: configuration checks, workspace carve-up, the integer
 // communication schedule, and the kernel sequence of one LSAM step / one center update.
 #include <algorithm>
+#include <climits>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -36,9 +37,10 @@ inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 
 // ---- communication schedule (integers only) -------------------------------------------------
 // Period generator: s_{j+1} = A s_j + C mod 2^64, draw_j = (s_{j+1} >> 33) mod range + min.
-// Replica i is due when its local count reaches its period (Algorithm 2's trigger
-// "sum_i t_x^(i) mod n tau = 0", taken per replica so that periods may differ; with equal
-// periods every replica is due at the same tick and the two coincide).
+// Replica i is due when its local count reaches its period: the trigger of Algorithm 2's
+// synchronous optimization step (total local iterations reaching a multiple of n tau), taken
+// per replica so that periods may differ; with equal periods every replica is due at the same
+// tick and the two coincide.
 class Schedule {
  public:
   void init(const lsam_config& c) {
@@ -83,6 +85,20 @@ class Schedule {
   const std::vector<int32_t>& tau() const { return tau_; }
   const std::vector<int32_t>& count() const { return count_; }
   int64_t t_y() const { return t_y_; }
+  uint64_t generator_state() const { return state_; }
+  // Overwrites counts, periods in force, the generator state and the sync count (resume).
+  bool restore(const int64_t* count, const int64_t* tau, uint64_t state, int64_t t_y) {
+    if (t_y < 0) return false;
+    for (int i = 0; i < K_; ++i)
+      if (count[i] < 0 || count[i] > INT32_MAX || tau[i] < 1 || tau[i] > INT32_MAX) return false;
+    for (int i = 0; i < K_; ++i) {
+      count_[i] = (int32_t)count[i];
+      tau_[i] = (int32_t)tau[i];
+    }
+    state_ = state;
+    t_y_ = t_y;
+    return true;
+  }
 
  private:
   int K_ = 0, lo_ = 1, hi_ = 1;
@@ -430,6 +446,10 @@ struct TimedLaunch {
 }  // namespace
 }  // namespace lsam
 
+namespace lsam {
+void set_last_error(const char* msg) { g_err = msg ? msg : ""; }
+}  // namespace lsam
+
 using namespace lsam;
 
 struct lsam_ctx {
@@ -588,6 +608,10 @@ int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq,
     const ConvLayer& cv = lo.conv[l];
     const Layer& ly = lo.layers[l];
     float* dout = c->at<float>(cv.dout);
+    // room for every partial sum of squares this layer's kernels may write, checked up front
+    if (ssq && *slots + std::max(gemm_sumsq_capacity(ly.out, ly.in), ly.out / 2) + (ly.out + 63) / 64 +
+                       (ly.bn ? 2 * ((ly.out + 63) / 64) : 0) > lo.nblk)
+      return fail(LSAM_ESTATE, "gradient-norm partials would overrun their buffer at convolution %d", l);
     if (cv.pool) {
       LaunchTimer t(c, KC_POOL);
       if (launch_maxpool2_backward(c->at<float>(cv.out), c->at<float>(cv.dpooled), dout,
@@ -796,6 +820,10 @@ int forward_backward(lsam_ctx* c, const void* X, const int32_t* labels, const vo
     const char* dz = c->at<char>(lo.dz[l + 1]);
     const int ld_dz = lo.ld[l + 1];
     const void* act = l == l0 ? A0 : (const void*)c->at<char>(lo.act[l]);
+    // the layer's kernels may write this many partial sums of squares: checked before they run
+    if (ssq && slots + std::max(gemm_sumsq_capacity(ly.out, ly.in), head_sumsq_slots(ly.in)) +
+                       (ly.out + 63) / 64 > lo.nblk)
+      return fail(LSAM_ESTATE, "gradient-norm partials would overrun their buffer at layer %d", l);
     if (head && l == L - 1) {
       LaunchTimer t(c, KC_HEAD);
       const int used = launch_head_weight_grad(
@@ -1315,6 +1343,77 @@ int lsam_get_schedule(lsam_ctx* c, int32_t* tau_out, int32_t* count_out, int64_t
     if (count_out) count_out[i] = c->sched.count()[i];
   }
   if (t_y_out) *t_y_out = c->sched.t_y();
+  return LSAM_OK;
+}
+
+int lsam_note_replay(lsam_ctx* c) {
+  if (!c) return fail(LSAM_EINVAL, "ctx is NULL");
+  // a captured step carries the kernel arguments of the step it was captured from: the coupling
+  // coefficients lambda0/(lr tau_i) and the noise counter are frozen in the graph
+  if (c->cfg.noise_scale > 0.f)
+    return fail(LSAM_ESTATE, "a replayed step would repeat its Langevin noise");
+  if (c->cfg.sched_mode == LSAM_SCHED_REDRAW && !c->cfg.tau && c->cfg.lambda_abs < 0.f &&
+      c->cfg.algorithm == LSAM_ALG_LSAM)
+    return fail(LSAM_ESTATE, "redrawn periods change lambda_i, which a replayed step cannot follow");
+  ++c->t_step;
+  c->sched.tick();
+  return LSAM_OK;
+}
+
+int lsam_get_counters(lsam_ctx* c, int64_t* state, int64_t n) {
+  if (!c || !state) return fail(LSAM_EINVAL, "ctx or state is NULL");
+  const int K = c->lo.K;
+  if (n != 2 * (int64_t)K + 3) return fail(LSAM_EINVAL, "n=%lld must equal 2K+3=%d", (long long)n, 2 * K + 3);
+  for (int i = 0; i < K; ++i) {
+    state[i] = c->sched.count()[i];
+    state[K + i] = c->sched.tau()[i];
+  }
+  state[2 * K] = (int64_t)c->sched.generator_state();
+  state[2 * K + 1] = c->sched.t_y();
+  state[2 * K + 2] = (int64_t)c->t_step;
+  return LSAM_OK;
+}
+
+int lsam_set_counters(lsam_ctx* c, const int64_t* state, int64_t n) {
+  if (!c || !state) return fail(LSAM_EINVAL, "ctx or state is NULL");
+  const int K = c->lo.K;
+  if (n != 2 * (int64_t)K + 3) return fail(LSAM_EINVAL, "n=%lld must equal 2K+3=%d", (long long)n, 2 * K + 3);
+  if (state[2 * K + 2] < 0 || state[2 * K + 2] > (int64_t)UINT32_MAX)
+    return fail(LSAM_EINVAL, "noise step %lld out of range", (long long)state[2 * K + 2]);
+  if (!c->sched.restore(state, state + K, (uint64_t)state[2 * K], state[2 * K + 1]))
+    return fail(LSAM_EINVAL, "counts must be >= 0, periods >= 1, the sync count >= 0");
+  c->t_step = (uint32_t)state[2 * K + 2];
+  return LSAM_OK;
+}
+
+int lsam_get_activation(lsam_ctx* c, int32_t layer, int32_t replica, float* dst, int64_t n) {
+  if (!c || !dst) return fail(LSAM_EINVAL, "ctx or dst is NULL");
+  const Layout& lo = c->lo;
+  if (lo.raw || lo.n_conv > 0) return fail(LSAM_ESTATE, "activations can be read from a dense model only");
+  if (layer < 1 || layer >= lo.L) return fail(LSAM_EINVAL, "layer %d is not a hidden layer (1..%d)", layer, lo.L - 1);
+  if (replica < 0 || replica >= lo.K) return fail(LSAM_EINVAL, "replica %d out of range", replica);
+  const int width = lo.layers[layer].in, B = lo.B;
+  if (n != (int64_t)B * width)
+    return fail(LSAM_EINVAL, "n=%lld must equal batch*width=%lld", (long long)n, (long long)B * width);
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  const int64_t elems = lo.act_elems(width, lo.ld[layer]);
+  if (!lo.bf16) {
+    std::vector<float> h((size_t)elems);
+    int rc = to_host(c, h.data(), c->at<float>(lo.act[layer]) + (int64_t)replica * elems, (size_t)elems * 4);
+    if (rc != LSAM_OK) return rc;
+    for (int b = 0; b < B; ++b)
+      memcpy(dst + (int64_t)b * width, h.data() + (int64_t)b * lo.ld[layer], (size_t)width * 4);
+    return LSAM_OK;
+  }
+  std::vector<uint16_t> h((size_t)elems);
+  int rc = to_host(c, h.data(), c->at<uint16_t>(lo.act[layer]) + (int64_t)replica * elems, (size_t)elems * 2);
+  if (rc != LSAM_OK) return rc;
+  const int cb = b32s_blocks(width);
+  for (int b = 0; b < B; ++b)
+    for (int q = 0; q < width; ++q) {
+      const uint32_t u = (uint32_t)h[(size_t)b32s_offset(b, q, cb)] << 16;
+      memcpy(dst + (int64_t)b * width + q, &u, 4);
+    }
   return LSAM_OK;
 }
 

@@ -26,6 +26,7 @@ EXPORTS = [
     "lsam_get_params", "lsam_get_buffer", "lsam_set_buffer", "lsam_get_norms", "lsam_get_schedule",
     "lsam_set_scalars", "lsam_num_params", "lsam_schedule_replay", "lsam_timing_enable",
     "lsam_timing_read", "lsam_probe_peaks", "lsam_destroy", "lsam_last_error",
+    "lsam_get_counters", "lsam_set_counters", "lsam_get_activation", "lsam_note_replay",
 ]
 
 
@@ -85,6 +86,14 @@ def lib():
         L.lsam_get_schedule.argtypes = [vp, vp, vp, vp]
         L.lsam_set_scalars.restype = C.c_int
         L.lsam_set_scalars.argtypes = [vp, C.c_float, C.c_float]
+        L.lsam_note_replay.restype = C.c_int
+        L.lsam_note_replay.argtypes = [vp]
+        L.lsam_get_counters.restype = C.c_int
+        L.lsam_get_counters.argtypes = [vp, vp, i64]
+        L.lsam_set_counters.restype = C.c_int
+        L.lsam_set_counters.argtypes = [vp, vp, i64]
+        L.lsam_get_activation.restype = C.c_int
+        L.lsam_get_activation.argtypes = [vp, i32, i32, vp, i64]
         L.lsam_schedule_replay.restype = C.c_int
         L.lsam_schedule_replay.argtypes = [cfgp, i32, vp, vp]
         L.lsam_timing_enable.restype = C.c_int
@@ -242,6 +251,24 @@ class Lsam:
         ty = C.c_int64(0)
         _check(lib().lsam_get_schedule(self._h, tau.ctypes.data, cnt.ctypes.data, C.byref(ty)))
         return tau.tolist(), cnt.tolist(), ty.value
+
+    def lsam_note_replay(self):
+        return _check(lib().lsam_note_replay(self._h))
+
+    def lsam_get_counters(self):
+        out = np.zeros(2 * self.K + 3, dtype=np.int64)
+        _check(lib().lsam_get_counters(self._h, out.ctypes.data, out.size))
+        return out
+
+    def lsam_set_counters(self, state):
+        a = np.ascontiguousarray(state, dtype=np.int64).ravel()
+        return _check(lib().lsam_set_counters(self._h, a.ctypes.data, a.size))
+
+    def lsam_get_activation(self, layer, replica):
+        width, batch = self.cfg.dims[layer], self.cfg.batch
+        out = np.empty((batch, width), dtype=np.float32)
+        _check(lib().lsam_get_activation(self._h, layer, replica, out.ctypes.data, out.size))
+        return out
 
     def lsam_set_scalars(self, lr, rho):
         return _check(lib().lsam_set_scalars(self._h, lr, rho))

@@ -167,11 +167,11 @@ def init_params(w: Workload, seed: Optional[int] = None) -> np.ndarray:
     return np.concatenate(parts).astype(np.float32)
 
 
-def init_params_margin(w: Workload, seed: Optional[int] = None) -> np.ndarray:
+def init_params_margin(w: Workload, seed: Optional[int] = None, ratio: float = 8.0) -> np.ndarray:
     """Like init_params, but every hidden unit is pushed away from the ReLU kink: hidden
     unit j of a layer of width n gets bias +c (j even) or -c (j odd) with c = 2/sqrt(n), and
     the weights feeding hidden units are scaled down so that the data-dependent part of
-    every hidden pre-activation has a standard deviation near c/8.  The activation vectors
+    every hidden pre-activation has a standard deviation near c/ratio.  The activation vectors
     keep a norm of order one, so training stays as stable as from init_params.
     Used where a comparison must not depend on which side of zero a rounded value falls."""
     p = init_params(w, seed).copy()
@@ -182,7 +182,7 @@ def init_params_margin(w: Workload, seed: Optional[int] = None) -> np.ndarray:
         if l < L - 1:
             c = 2.0 / np.sqrt(out)
             natural_std = 0.577 if l == 0 else 0.408 * c_prev
-            p[off:off + out * fan_in] *= np.float32((c / 8.0) / natural_std)
+            p[off:off + out * fan_in] *= np.float32((c / ratio) / natural_std)
             p[off + out * fan_in: off + out * fan_in + out] = np.where(
                 np.arange(out) % 2 == 0, c, -c).astype(np.float32)
             c_prev = c

@@ -255,6 +255,41 @@ int lsam_timing_read(lsam_ctx* ctx, int32_t cap, const char** names, int64_t* co
 int lsam_probe_peaks(void* scratch, size_t scratch_bytes, void* stream, double* copy_gbytes_per_s,
                      double* mfma_bf16_tflops, double* mfma_fp32_tflops);
 
+/* For callers that cannot allocate device memory or hold a context -- code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc: the raw-vector iteration of
+ * lsam_step_grads as one stateless call.  Every array is the caller's; the scratch memory of
+ * the gradient-norm reduction (K x 1024 partial sums, norms, scales: 512.5 KiB) is a fixed
+ * device array inside the library, one copy per GPU, kept until the process ends.  The call
+ * allocates and frees no device memory, calls no allocating library routine and does not
+ * synchronise.
+ *   x, v, S [device] [K, stride] floats, updated in place (x_i, v_i, S_i += new x_i)
+ *   y       [device] [d] center, read only
+ *   g1, g2  [device] [K, g_stride] gradients at x_i and at the perturbed point, read only
+ *   xt      [device] [K, stride] receives x~_i = x_i + rho g1_i / (||g1_i|| + gamma); may be NULL
+ *           when rho = 0 (then nothing is written)
+ *   norms   [device] [K] receives ||g1_i||, or NULL
+ *   lambda  [host] K coupling coefficients (the context-based call uses lambda0/(lr tau_i))
+ * x, v, S, y, xt must be 16-byte aligned and `stride` a multiple of 4.  Limits: K <=
+ * LSAM_MAX_REPLICAS, d <= LSAM_STATIC_MAX_D; beyond them the call returns LSAM_EINVAL and
+ * launches nothing.  Results equal those of lsam_step_grads on the same values (same kernels).
+ * All calls on one GPU share that GPU's scratch array: calls that may overlap in time on one
+ * GPU (different streams, or different threads) race on it and must be serialised by the
+ * caller; calls on one stream are ordered and safe.  Nothing in the array has to survive
+ * between calls and every slot is written before it is read, so no clearing is needed. */
+#define LSAM_STATIC_MAX_D (1LL << 34)
+typedef struct {
+  int32_t K;            /* replicas                                                  */
+  int64_t d;            /* parameters per replica                                    */
+  int64_t stride;       /* row stride of x, v, S, xt in floats, >= d                 */
+  int64_t g_stride;     /* row stride of g1, g2 in floats, >= d                      */
+  float rho, gamma;     /* perturbation radius and stabiliser                        */
+  float lr, momentum;   /* eta and mu of the sampler step                            */
+  int32_t nesterov;     /* 1: x -= lr (G + mu v);  0: x -= lr v                      */
+  const float* lambda;  /* [host] K values                                           */
+} lsam_update_desc;
+int lsam_step_grads_static(const lsam_update_desc* u, float* x, float* v, float* S, const float* y,
+                           const float* g1, const float* g2, float* xt, float* norms, void* stream);
+
 void lsam_destroy(lsam_ctx* ctx);
 
 const char* lsam_last_error(void);

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblsam.so")
 SOURCES = ["lsam_api.hip", "kernels_stream.hip", "kernels_gemm.hip", "kernels_gemm_bf16.hip", "kernels_ce.hip", "kernels_conv.hip",
-           "kernels_probe.hip"]
+           "kernels_probe.hip", "lsam_static.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

@@ -19,6 +19,7 @@ OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4
 GEMM_FP32, GEMM_BF16 = 0, 1
 SCHED_FIXED, SCHED_REDRAW = 0, 1
 ALG_LSAM, ALG_DATA_PARALLEL = 0, 1
+STATIC_MAX_D = 1 << 34
 BUF_PARAMS, BUF_VELOCITY, BUF_ITER_SUM, BUF_GRAD, BUF_PERTURBED, BUF_CENTER_DIR = range(6)
 
 EXPORTS = [
@@ -26,7 +27,7 @@ EXPORTS = [
     "lsam_get_params", "lsam_get_buffer", "lsam_set_buffer", "lsam_get_norms", "lsam_get_schedule",
     "lsam_set_scalars", "lsam_num_params", "lsam_schedule_replay", "lsam_timing_enable",
     "lsam_timing_read", "lsam_probe_peaks", "lsam_destroy", "lsam_last_error",
-    "lsam_get_counters", "lsam_set_counters", "lsam_get_activation", "lsam_note_replay",
+    "lsam_get_counters", "lsam_set_counters", "lsam_get_activation", "lsam_step_grads_static", "lsam_note_replay",
 ]
 
 
@@ -42,6 +43,14 @@ class lsam_config(C.Structure):
         ("noise_scale", C.c_float), ("noise_seed", C.c_uint64),
         ("n_conv", C.c_int32), ("img_h", C.c_int32), ("img_w", C.c_int32),
         ("pool_mask", C.c_uint32), ("bn_mask", C.c_uint32), ("bn_eps", C.c_float),
+    ]
+
+
+class lsam_update_desc(C.Structure):
+    _fields_ = [
+        ("K", C.c_int32), ("d", C.c_int64), ("stride", C.c_int64), ("g_stride", C.c_int64),
+        ("rho", C.c_float), ("gamma", C.c_float), ("lr", C.c_float), ("momentum", C.c_float),
+        ("nesterov", C.c_int32), ("lambda_", C.POINTER(C.c_float)),
     ]
 
 
@@ -94,6 +103,8 @@ def lib():
         L.lsam_set_counters.argtypes = [vp, vp, i64]
         L.lsam_get_activation.restype = C.c_int
         L.lsam_get_activation.argtypes = [vp, i32, i32, vp, i64]
+        L.lsam_step_grads_static.restype = C.c_int
+        L.lsam_step_grads_static.argtypes = [C.POINTER(lsam_update_desc)] + [vp] * 9
         L.lsam_schedule_replay.restype = C.c_int
         L.lsam_schedule_replay.argtypes = [cfgp, i32, vp, vp]
         L.lsam_timing_enable.restype = C.c_int
@@ -175,6 +186,24 @@ def lsam_probe_peaks(scratch, stream=None):
     _check(lib().lsam_probe_peaks(scratch.data_ptr(), scratch.numel() * scratch.element_size(), st,
                                   C.addressof(out), C.addressof(out) + 8, C.addressof(out) + 16))
     return out[0], out[1], out[2]
+
+
+def lsam_step_grads_static(x, v, S, y, g1, g2, xt, norms, lam, rho, gamma, lr, momentum, nesterov,
+                           d=None, stream=None):
+    """x, v, S, xt: device tensors [K, stride]; g1, g2: [K, g_stride]; y: [>= d]; norms: [K] or
+    None; lam: K host floats.  d defaults to the row length of x."""
+    import torch
+    K = x.shape[0]
+    u = lsam_update_desc()
+    u.K, u.d = K, (x.shape[1] if d is None else d)
+    u.stride, u.g_stride = x.stride(0), g1.stride(0)
+    u.rho, u.gamma, u.lr, u.momentum, u.nesterov = rho, gamma, lr, momentum, nesterov
+    arr = (C.c_float * K)(*[float(a) for a in lam])
+    u.lambda_ = C.cast(arr, C.POINTER(C.c_float))
+    st = torch.cuda.current_stream(x.device).cuda_stream if stream is None else stream
+    ptr = lambda t: None if t is None else t.data_ptr()
+    return _check(lib().lsam_step_grads_static(C.byref(u), ptr(x), ptr(v), ptr(S), ptr(y), ptr(g1),
+                                               ptr(g2), ptr(xt), ptr(norms), st))
 
 
 def lsam_workspace_bytes(cfg) -> int:

@@ -99,3 +99,23 @@ def test_schedule_replay_explicit_periods():
     expected = {2: [0], 3: [1], 4: [0, 2], 6: [0, 1], 8: [0, 2], 9: [1], 10: [0], 12: [0, 1, 2]}
     for t in range(12):
         assert np.flatnonzero(due[t]).tolist() == expected.get(t + 1, [])
+
+
+def test_static_entry_checks_its_arguments_before_touching_the_gpu():
+    # limits and null pointers are refused on the host; no device call is reached
+    u = lsam.lsam_update_desc()
+    lam = (C.c_float * 65)()
+    u.K, u.d, u.stride, u.g_stride = 65, 64, 64, 64
+    u.lambda_ = C.cast(lam, C.POINTER(C.c_float))
+    fake = 4096                                   # never dereferenced: the checks fail first
+    call = lsam.lib().lsam_step_grads_static
+    assert call(C.byref(u), fake, fake, fake, fake, fake, fake, fake, None, None) == lsam.EINVAL
+    assert "K outside" in lsam.last_error()
+    u.K, u.d = 4, lsam.STATIC_MAX_D + 1
+    u.stride = u.g_stride = u.d
+    assert call(C.byref(u), fake, fake, fake, fake, fake, fake, fake, None, None) == lsam.EINVAL
+    assert "d outside" in lsam.last_error()
+    u.d, u.stride, u.g_stride = 100, 64, 100
+    assert call(C.byref(u), fake, fake, fake, fake, fake, fake, fake, None, None) == lsam.EINVAL
+    assert "strides" in lsam.last_error()
+    assert call(C.byref(u), None, fake, fake, fake, fake, fake, fake, None, None) == lsam.EINVAL

@@ -101,9 +101,10 @@ def conv_modes(w):
     return out
 
 
-def gemm_flops(w):
+def gemm_flops(w, fused_step=False):
     """Per all-replica step (both passes): flops of the forward, dX and dW GEMM classes and of
-    the first convolution layer's own kernels."""
+    the first convolution layer's own kernels.  With the sampler step fused into the second
+    pass's weight-gradient kernels, that pass's dW flops belong to the class gemm_dw_step."""
     K = w.K
     shapes, rows = list(w.layer_shapes), layer_rows(w)
     fi, fo = shapes[-1]
@@ -118,6 +119,9 @@ def gemm_flops(w):
     out = {"gemm_fwd": 2 * 2.0 * sw * K, "gemm_dw": 2 * 2.0 * sw * K, "gemm_dx": 2 * 2.0 * sw_dx * K}
     if first:
         out["conv_first"] = 2 * 2 * 2.0 * first * K      # forward and weight gradient
+    if fused_step:
+        out["gemm_dw"] /= 2
+        out["gemm_dw_step"] = out["gemm_dw"]
     return out
 
 
@@ -152,16 +156,26 @@ def conv_bytes(w):
     return out
 
 
-def stream_bytes(w):
+def stream_bytes(w, fused_step=False):
     """Algorithmic bytes per all-replica step of the update-path kernels (reads + writes
     the method itself requires; y is shared by the K replicas): descent reads x, g2, v, S
     (16 B per parameter) and writes x, v, S (12 B), plus the bf16 operand copy (2 B) in bf16
     mode, plus y once for all replicas."""
     n = float(w.K) * w.d
     bf = w.gemm_dtype == 1 and not w.n_conv
-    return {"sumsq_partials": 4 * n,
-            "perturb": (10 if bf else 12) * n,
-            "descent": (30 if bf else 28) * n + 4.0 * w.d}
+    out = {"sumsq_partials": 4 * n,
+           "perturb": (10 if bf else 12) * n,
+           "descent": (30 if bf else 28) * n + 4.0 * w.d}
+    if fused_step:
+        # the weight matrices take their step where the second-pass gradient is produced: that
+        # kernel reads x, v, S (12 B per parameter) and y once, writes x, v, S (12 B) and the
+        # bf16 operand copy (2 B), and neither writes nor reads g2; the separate kernel is left
+        # with the bias vectors
+        nw = sum(a * b for a, b in w.layer_shapes)
+        nb = w.d - nw
+        out["gemm_dw_step"] = 26.0 * w.K * nw + 4.0 * nw
+        out["descent"] = 28.0 * w.K * nb + 4.0 * nb
+    return out
 
 
 def make_inputs(w, torch, dev, n_sets):
@@ -284,8 +298,9 @@ def run_workload(w, steps, warmup, kernel_timing=True):
             one(i)
         stats = eng.lsam_timing_read()
         eng.lsam_timing_enable(False)
-        flops = gemm_flops(w) if w.dims else {}
-        nbytes = stream_bytes(w)
+        fused_step = bool(w.dims) and eng.lsam_set_fused_step(True) == 1 and w.rho != 0.0
+        flops = gemm_flops(w, fused_step) if w.dims else {}
+        nbytes = stream_bytes(w, fused_step)
         nbytes.update(conv_bytes(w))
         # center update: 8 B/param per due replica (S read, S cleared) + 16 B/param (y and
         # g'_prev read and written), summed over the ticks of this run that had a sync
@@ -299,7 +314,14 @@ def run_workload(w, steps, warmup, kernel_timing=True):
                 continue
             k = {"launches_per_step": cnt / steps, "ms_per_step": tot / steps,
                  "avg_launch_ms": tot / cnt}
-            if name in flops and tot > 0:
+            if name == "gemm_dw_step" and tot > 0:
+                # a contraction whose epilogue streams the sampler state: priced against the
+                # roof that binds it (HBM), with its matrix-unit rate beside it
+                k.update(bound="hbm", achieved=nbytes[name] * steps / (tot * 1e-3) / 1e9,
+                         peak=PEAK_HBM_GBS, unit="GB/s",
+                         algorithmic_bytes_per_launch=nbytes[name] * steps / cnt,
+                         mfma_tflops=flops[name] * steps / (tot * 1e-3) / 1e12)
+            elif name in flops and tot > 0:
                 k.update(bound="mfma", achieved=flops[name] * steps / (tot * 1e-3) / 1e12,
                          peak=PEAK_TFLOPS[w.gemm_dtype], unit="TFLOP/s",
                          algorithmic_flops_per_launch=flops[name] * steps / cnt)

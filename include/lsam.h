@@ -132,7 +132,8 @@ typedef struct {
 #define LSAM_BUF_PARAMS     0  /* x_i (replica -1: center y)                          */
 #define LSAM_BUF_VELOCITY   1  /* v_i                                                  */
 #define LSAM_BUF_ITER_SUM   2  /* S_i = sum of x_i's iterates since its last sync     */
-#define LSAM_BUF_GRAD       3  /* gradient buffer (g2 after a step; MLP mode only)    */
+#define LSAM_BUF_GRAD       3  /* gradient buffer (g2 after a step, but see
+                                  lsam_set_fused_step; MLP mode only)                 */
 #define LSAM_BUF_PERTURBED  4  /* fp32 mode: x~_i of the last step.  bf16 mode: the bf16
                                   operand copy of the weight matrices widened to fp32
                                   (it holds bf16(x_i) once a step has finished), with the
@@ -195,6 +196,19 @@ int lsam_get_norms(lsam_ctx* ctx, float* dst);
 
 /* Schedule state: any of the outputs may be NULL.  tau_out, count_out [host] [K]. */
 int lsam_get_schedule(lsam_ctx* ctx, int32_t* tau_out, int32_t* count_out, int64_t* t_y_out);
+
+/* In the bf16 dense model running Algorithm 2 without Langevin noise (and rho > 0), neither
+ * gradient of a weight matrix is stored: both are used element by element only.  The
+ * weight-gradient kernels of the first pass leave just the sums of squares the norm needs; once
+ * the norm is known the same products are formed again and their epilogue writes the bf16
+ * operand copy of x~ = x + rho g1/(||g1|| + gamma); the weight-gradient kernels of the pass at
+ * the perturbed point take the sampler step on x, v, S and the operand copy where g2 is
+ * produced.  Biases take the ordinary kernels.  Results are those of the separate kernels, bit
+ * for bit.  With the fusion active the weight-matrix part of LSAM_BUF_GRAD is not written
+ * (the bias parts hold g2); switch it off (on = 0) to have g1 / g2 stored as in the other
+ * modes.  Returns 1 if steps of this context will use the fusion, 0 if not (other modes never
+ * do), or a negative error. */
+int lsam_set_fused_step(lsam_ctx* ctx, int32_t on);
 
 /* Tells the context that a HIP graph holding one captured lsam_step (or lsam_step_grads) has
  * been replayed once: the local counts c_i and the step number advance as they do in an eager

@@ -25,6 +25,27 @@ struct DueList {
 // Message that lsam_last_error() returns on the calling thread (copied).
 void set_last_error(const char* msg);
 
+// One coordinate of the sampler step (Algorithm 2, asynchronous sampling step, driven by
+// momentum SGD): G = g + lam (x - y); v <- mu v + G; x <- x - lr (G + mu v) [Nesterov] or
+// x - lr v [heavy ball], plus the Langevin term xi (0 without noise); S <- S + x.  The one
+// definition both the streaming kernel and the fused GEMM epilogue use, so that they round alike.
+__device__ __forceinline__ void sampler_step(float g, float y, float lam, float lr, float mu,
+                                             int nesterov, float xi, float& x, float& v, float& S) {
+  const float G = g + lam * (x - y);
+  const float vn = mu * v + G;
+  const float xn = (nesterov ? x - lr * (G + mu * vn) : x - lr * vn) + xi;
+  v = vn;
+  x = xn;
+  S += xn;
+}
+
+// One coordinate of the ascent step x~ = x + scale g, scale = rho / (||g|| + gamma) (Formulation,
+// first-order solution of the inner maximisation); shared by the streaming kernel and the
+// GEMM epilogue for the same reason.
+__device__ __forceinline__ float ascent_point(float x, float scale, float g) {
+  return __builtin_fmaf(scale, g, x);
+}
+
 // ---- streaming kernels (update path) ---------------------------------------------------
 
 // Sum of squares, pass 1: per (replica, block) partial sums in double.
@@ -110,6 +131,31 @@ struct GemmDesc {
   // fp32 operands only: round both operands to bfloat16 on their way into the matrix unit
   // (v_mfma_f32_32x32x16_bf16, fp32 accumulate); memory traffic and results stay fp32.
   int bf16_math;
+  // If set (bf16 operands, fp32 result, EPI_PLAIN): the result, a weight gradient at the
+  // perturbed point, is not stored.  The epilogue takes the sampler step on it instead
+  // (Algorithm 2, asynchronous sampling step, with Nesterov or heavy-ball momentum), element
+  // (m, n) of replica k living at offset k * strideC + m * ldC + n of x, v and S and at
+  // m * ldC + n of y:  G = C + lam[k] (x - y);  v = mu v + G;  x -= lr (G + mu v)  [or lr v];
+  // S += x;  and bf16(x) goes to the blocked operand copy `shadow` (replica stride
+  // shadow_stride elements, cbShadow column blocks).  C is ignored.
+  const struct SamplerFusion* fuse;
+  // If set (same kind of launch, a weight gradient of the first pass recomputed once its norm
+  // is known): the result is not stored either; the epilogue writes the operand copy of the
+  // perturbed weights, bf16(x + scale[k] * C), x addressed like the result.
+  const struct AscentFusion* ascend;
+  // If set (same kind of launch, `sumsq` given): only the sums of squares are written.
+  int sumsq_only;
+};
+struct AscentFusion {
+  const float* x; const float* scale;
+  uint16_t* shadow; int64_t shadow_stride; int cbShadow;
+};
+struct SamplerFusion {
+  float* x; float* v; float* S; const float* y;
+  uint16_t* shadow; int64_t shadow_stride; int cbShadow;
+  ReplicaScalars lam;
+  float lr, mu;
+  int nesterov;
 };
 // 0 ok, <0 unsupported shape; *sumsq_slots (if non-null) = slots written per replica
 int launch_gemm(const GemmDesc& d, hipStream_t s, int* sumsq_slots = nullptr);

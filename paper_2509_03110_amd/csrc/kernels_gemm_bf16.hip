@@ -45,6 +45,15 @@ struct Bf16GemmParams {
   int cbA, cbB, cbC, cbMask;          // column blocks of the stored A, B, C (bf16 out) and mask
   unsigned bytesA, bytesB;            // size of one replica's stored A and B
   double* sumsq; long long strideSumsq;   // optional: sum of squares of each tile's results
+  // EPI_STEP kernels: the sampler step taken on the result instead of storing it
+  float* fx; float* fv; float* fS; const float* fy;
+  unsigned short* fshadow; long long strideShadow; int cbShadow;
+  float lr, mu; int nesterov;
+  ReplicaScalars lam;
+  // EPI_ASCEND kernels: x (same addressing as the result), the per-replica scale rho/(||g||+gamma),
+  // and the operand copy that receives bf16(x + scale g) (fshadow, strideShadow, cbShadow above)
+  const float* ax; const float* ascale;
+  int mode;                               // EPI_* the launch asks for
 };
 
 // s_waitcnt immediate: vmcnt = vm (0..63), lgkmcnt = lgkm (0..15), expcnt untouched.
@@ -173,8 +182,17 @@ template <> struct Out<__bf16> {
   static __device__ __forceinline__ __bf16 one(float v) { return static_cast<__bf16>(v); }
 };
 
-template <typename TC, int BM, int BN, int NSTAGE, bool A_KMAJOR, bool B_KMAJOR, int OCC>
+// What the epilogue does with the result tile.
+//   EPI_STORE   store it (with bias / ReLU / mask as the launch says, optionally the sum of squares)
+//   EPI_STEP    weight gradient at the perturbed point: take the sampler step on it
+//   EPI_SUMSQ   weight gradient of the first pass: only its sum of squares is wanted
+//   EPI_ASCEND  weight gradient of the first pass, recomputed once the norm is known: write
+//               the operand copy of the perturbed weights, bf16(x + scale * g)
+enum { EPI_STORE = 0, EPI_STEP = 1, EPI_SUMSQ = 2, EPI_ASCEND = 3 };
+
+template <typename TC, int BM, int BN, int NSTAGE, bool A_KMAJOR, bool B_KMAJOR, int OCC, int MODE = EPI_STORE>
 __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams p) {
+  static_assert(MODE == EPI_STORE || sizeof(TC) == 4, "the fused epilogues work on fp32 results");
   static_assert(NSTAGE == 3 || NSTAGE == 4, "ring of 3 or 4 stages");
   constexpr int TM = BM / 64, TN = BN / 64;
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
@@ -320,6 +338,130 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
   const int rsub = lane / LANES_PER_ROW;
   const int n = n0 + wn0 + c4;
   float ssq = 0.f;                                 // squares of what this thread stores
+  if constexpr (MODE == EPI_STEP) {
+    // The sampler step on the tile instead of storing it.  x, v, S, y and the operand copy are
+    // addressed as buffers (one descriptor each, a 32-bit byte offset per lane), so that rows
+    // past M and columns past N fall out of range -- their loads return zero and their stores
+    // are dropped -- and no lane needs 64-bit addresses.  The state of NB passes is requested
+    // in one go before the first result is touched: a wavefront then has 4 NB 16-byte loads
+    // per lane in flight instead of 4, which lets these streams run at memory speed rather
+    // than at one round trip per pass.  Columns N..ldC-1 are row padding holding zeros in x, v,
+    // S and y; the gradient there is zero (the operands are zero-padded), so they stay zero.
+    float lam = 0.f;
+    // picked with constant indices: a variable index would move the whole argument block to
+    // private memory
+#pragma unroll
+    for (int k = 0; k < kMaxK; ++k)
+      if (k == bat) lam = p.lam.v[k];
+    constexpr int PASSES = 32 / ROWS_PER_PASS;
+    constexpr int NB = PASSES < 4 ? PASSES : 4;
+    constexpr unsigned kOut = 0x7FFFFFF0u;          // beyond every buffer: ignored by the hardware
+    constexpr int NT = 2;                           // streaming access: do not keep in the caches
+    const unsigned wbytes = (unsigned)p.M * (unsigned)p.ldC * 4u;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.fx + (long long)bat * p.strideC, wbytes);
+    const __amdgpu_buffer_rsrc_t rv = make_rsrc(p.fv + (long long)bat * p.strideC, wbytes);
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(p.fS + (long long)bat * p.strideC, wbytes);
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(p.fy, wbytes);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.fshadow + (long long)bat * p.strideShadow,
+                                                (unsigned)(b32s_blocks(p.M) * p.cbShadow) * 2048u);
+    const bool col_ok = n < p.N;
+    const unsigned rowbytes = (unsigned)p.ldC * 4u;
+    const unsigned off0 = (unsigned)(m0 + wm0 + rsub) * rowbytes + (unsigned)n * 4u;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          f32x4 v;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) v[r] = acc[i][j][q * 4 + r];
+          *reinterpret_cast<f32x4*>(stage + l32 * EPI_PITCH + j * 32 + q * 8 + h * 4) = v;
+        }
+#pragma unroll
+      for (int pb = 0; pb < PASSES; pb += NB) {
+        u32x4 xv[NB], vv[NB], sv[NB], yv[NB];
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+          const unsigned off = col_ok ? off0 + (unsigned)(i * 32 + (pb + u) * ROWS_PER_PASS) * rowbytes : kOut;
+          xv[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, NT);
+          vv[u] = __builtin_amdgcn_raw_buffer_load_b128(rv, off, 0, NT);
+          sv[u] = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, NT);
+          yv[u] = __builtin_amdgcn_raw_buffer_load_b128(ry, off, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+          const int rr = (pb + u) * ROWS_PER_PASS + rsub;
+          const int m = m0 + wm0 + i * 32 + rr;
+          const unsigned off = col_ok ? off0 + (unsigned)(i * 32 + (pb + u) * ROWS_PER_PASS) * rowbytes : kOut;
+          const f32x4 gv = *reinterpret_cast<const f32x4*>(stage + rr * EPI_PITCH + c4);
+          f32x4 xe = __builtin_bit_cast(f32x4, xv[u]), ve = __builtin_bit_cast(f32x4, vv[u]);
+          f32x4 se = __builtin_bit_cast(f32x4, sv[u]);
+          const f32x4 ye = __builtin_bit_cast(f32x4, yv[u]);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            float a = xe[r], b = ve[r], c = se[r];
+            sampler_step(gv[r], ye[r], lam, p.lr, p.mu, p.nesterov, 0.f, a, b, c);
+            xe[r] = a; ve[r] = b; se[r] = c;
+          }
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, xe), rx, off, 0, NT);
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, ve), rv, off, 0, NT);
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, se), rs, off, 0, NT);
+          const unsigned woff = col_ok ? (unsigned)b32s_offset(m, n, p.cbShadow) * 2u : kOut;
+          __builtin_amdgcn_raw_buffer_store_b64(Out<__bf16>::from(xe), rw, woff, 0, 0);
+        }
+      }
+    }
+    return;
+  }
+  if constexpr (MODE == EPI_ASCEND) {
+    // The ascent perturbation on the tile: x~ = x + scale g, rounded to bf16 into the operand
+    // copy.  Same buffer addressing; x is streamed in once, four passes at a time.
+    constexpr int PASSES = 32 / ROWS_PER_PASS;
+    constexpr int NB = PASSES < 4 ? PASSES : 4;
+    constexpr unsigned kOut = 0x7FFFFFF0u;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.ax + (long long)bat * p.strideC,
+                                                (unsigned)p.M * (unsigned)p.ldC * 4u);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.fshadow + (long long)bat * p.strideShadow,
+                                                (unsigned)(b32s_blocks(p.M) * p.cbShadow) * 2048u);
+    const float sc = p.ascale[bat];
+    const bool col_ok = n < p.N;
+    const unsigned rowbytes = (unsigned)p.ldC * 4u;
+    const unsigned off0 = (unsigned)(m0 + wm0 + rsub) * rowbytes + (unsigned)n * 4u;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          f32x4 v;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) v[r] = acc[i][j][q * 4 + r];
+          *reinterpret_cast<f32x4*>(stage + l32 * EPI_PITCH + j * 32 + q * 8 + h * 4) = v;
+        }
+#pragma unroll
+      for (int pb = 0; pb < PASSES; pb += NB) {
+        u32x4 xv[NB];
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+          const unsigned off = col_ok ? off0 + (unsigned)(i * 32 + (pb + u) * ROWS_PER_PASS) * rowbytes : kOut;
+          xv[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, 2);
+        }
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+          const int rr = (pb + u) * ROWS_PER_PASS + rsub;
+          const int m = m0 + wm0 + i * 32 + rr;
+          const f32x4 gv = *reinterpret_cast<const f32x4*>(stage + rr * EPI_PITCH + c4);
+          f32x4 xe = __builtin_bit_cast(f32x4, xv[u]);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) xe[r] = ascent_point(xe[r], sc, gv[r]);
+          const unsigned woff = col_ok ? (unsigned)b32s_offset(m, n, p.cbShadow) * 2u : kOut;
+          __builtin_amdgcn_raw_buffer_store_b64(Out<__bf16>::from(xe), rw, woff, 0, 0);
+        }
+      }
+    }
+    return;
+  }
   f32x4 bv = {0.f, 0.f, 0.f, 0.f};
   if (has_bias) {
 #pragma unroll
@@ -365,7 +507,8 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
             for (int r = 0; r < 4; ++r)
               if (!(static_cast<float>(me[r]) > 0.f)) v[r] = 0.f;
           }
-          __builtin_nontemporal_store(Out<TC>::from(v), reinterpret_cast<cvec*>(C + coff));
+          if constexpr (MODE != EPI_SUMSQ)
+            __builtin_nontemporal_store(Out<TC>::from(v), reinterpret_cast<cvec*>(C + coff));
           ssq += (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
         } else {
 #pragma unroll
@@ -373,7 +516,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
             if (n + r < p.N) {
               float o = v[r];
               if (masked && !(static_cast<float>(mask[moff + r]) > 0.f)) o = 0.f;
-              C[coff + r] = Out<TC>::one(o);
+              if constexpr (MODE != EPI_SUMSQ) C[coff + r] = Out<TC>::one(o);
               ssq += o * o;
             }
         }
@@ -405,6 +548,14 @@ LSAM_INSTANTIATE(__bf16, true, true)
 LSAM_INSTANTIATE(__bf16, true, false)
 LSAM_INSTANTIATE(__bf16, false, false)
 #undef LSAM_INSTANTIATE
+#define LSAM_INSTANTIATE_MODE(M)                                                                         \
+  template __global__ void gemm_bf16_kernel<float, 256, 256, 4, false, false, 1, M>(Bf16GemmParams);  \
+  template __global__ void gemm_bf16_kernel<float, 256, 128, 3, false, false, 2, M>(Bf16GemmParams);  \
+  template __global__ void gemm_bf16_kernel<float, 128, 128, 4, false, false, 2, M>(Bf16GemmParams);
+LSAM_INSTANTIATE_MODE(EPI_STEP)
+LSAM_INSTANTIATE_MODE(EPI_SUMSQ)
+LSAM_INSTANTIATE_MODE(EPI_ASCEND)
+#undef LSAM_INSTANTIATE_MODE
 
 template <typename TC, int BM, int BN, int NSTAGE, bool AK, bool BK_>
 int launch_one(const Bf16GemmParams& p0, hipStream_t s, int* slots) {
@@ -414,6 +565,25 @@ int launch_one(const Bf16GemmParams& p0, hipStream_t s, int* slots) {
   p.tilesN = (p.N + BN - 1) / BN;
   p.total = p.tilesM * p.tilesN * p.batch;
   p.chunks = (p.total + 7) / 8;
+  if constexpr (sizeof(TC) == 4 && !AK && !BK_) {
+    // the fused epilogues exist for weight-gradient launches (both operands m-major) only
+    if (p.mode == EPI_STEP) {
+      gemm_bf16_kernel<TC, BM, BN, NSTAGE, AK, BK_, OCC, EPI_STEP><<<p.chunks * 8, kThreads, 0, s>>>(p);
+      if (slots) *slots = 0;
+      return 0;
+    }
+    if (p.mode == EPI_ASCEND) {
+      gemm_bf16_kernel<TC, BM, BN, NSTAGE, AK, BK_, OCC, EPI_ASCEND><<<p.chunks * 8, kThreads, 0, s>>>(p);
+      if (slots) *slots = 0;
+      return 0;
+    }
+    if (p.mode == EPI_SUMSQ) {
+      gemm_bf16_kernel<TC, BM, BN, NSTAGE, AK, BK_, OCC, EPI_SUMSQ><<<p.chunks * 8, kThreads, 0, s>>>(p);
+      if (slots) *slots = p.tilesM * p.tilesN;
+      return 0;
+    }
+  }
+  if (p.mode != EPI_STORE) return -1;
   gemm_bf16_kernel<TC, BM, BN, NSTAGE, AK, BK_, OCC><<<p.chunks * 8, kThreads, 0, s>>>(p);
   if (slots) *slots = p.tilesM * p.tilesN;
   return 0;
@@ -484,6 +654,37 @@ int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s, int* s
   p.bytesB = (unsigned)(blocksB * 2048);
   p.sumsq = d.out_bf16 ? nullptr : d.sumsq;
   p.strideSumsq = d.sumsq_stride;
+  p.fx = nullptr;
+  p.mode = EPI_STORE;
+  const bool plain_f32 = !d.out_bf16 && d.epilogue == EPI_PLAIN && (d.ldC % 4) == 0 && (d.strideC % 4) == 0;
+  // 32-bit byte offsets inside one replica's W_l, rows of a ragged last tile included
+  const bool offsets_fit = ((long long)d.M + 256) * d.ldC * 4 < 0x7FFFFFF0LL;
+  if (d.fuse != nullptr) {
+    const SamplerFusion& f = *d.fuse;
+    // 16-byte accesses at k * strideC + m * ldC + n with n a multiple of 4
+    if (!plain_f32 || !offsets_fit || ((uintptr_t)f.x & 15) || ((uintptr_t)f.v & 15) ||
+        ((uintptr_t)f.S & 15) || ((uintptr_t)f.y & 15) || ((uintptr_t)f.shadow & 7) ||
+        f.cbShadow < b32s_blocks(d.N) || (long long)b32s_blocks(d.M) * f.cbShadow * 2048 >= 0x7FFFFFF0LL)
+      return -1;
+    p.fx = f.x; p.fv = f.v; p.fS = f.S; p.fy = f.y;
+    p.fshadow = f.shadow; p.strideShadow = f.shadow_stride; p.cbShadow = f.cbShadow;
+    p.lr = f.lr; p.mu = f.mu; p.nesterov = f.nesterov;
+    p.lam = f.lam;
+    p.sumsq = nullptr;
+    p.mode = EPI_STEP;
+  } else if (d.ascend != nullptr) {
+    const AscentFusion& f = *d.ascend;
+    if (!plain_f32 || !offsets_fit || ((uintptr_t)f.x & 15) || ((uintptr_t)f.shadow & 7) || !f.scale ||
+        f.cbShadow < b32s_blocks(d.N) || (long long)b32s_blocks(d.M) * f.cbShadow * 2048 >= 0x7FFFFFF0LL)
+      return -1;
+    p.ax = f.x; p.ascale = f.scale;
+    p.fshadow = f.shadow; p.strideShadow = f.shadow_stride; p.cbShadow = f.cbShadow;
+    p.sumsq = nullptr;
+    p.mode = EPI_ASCEND;
+  } else if (d.sumsq_only) {
+    if (!plain_f32 || d.sumsq == nullptr) return -1;
+    p.mode = EPI_SUMSQ;
+  }
   return d.out_bf16 ? launch_layout<__bf16>(d, p, tile, s, sumsq_slots)
                     : launch_layout<float>(d, p, tile, s, sumsq_slots);
 }

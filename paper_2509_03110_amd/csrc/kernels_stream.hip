@@ -164,7 +164,7 @@ __global__ __launch_bounds__(kThreads) void perturb_kernel(
   auto gv = ldv<VEC>(g + (int64_t)k * g_stride + i * VEC);
   typename Vec<VEC>::type o;
 #pragma unroll
-  for (int e = 0; e < VEC; ++e) set_elem(o, e, elem(xv, e) + sc * elem(gv, e));
+  for (int e = 0; e < VEC; ++e) set_elem(o, e, ascent_point(elem(xv, e), sc, elem(gv, e)));
   if constexpr (BF16_OUT) {
     store_bf16<VEC>(xt16 + (int64_t)k * shadow_stride + so, o);
   } else {
@@ -203,7 +203,7 @@ __global__ __launch_bounds__(kThreads) void perturb_tiled_kernel(
   const auto gv = ldv<4>(g + (int64_t)k * g_stride + flat);
   typename Vec<4>::type o;
 #pragma unroll
-  for (int e = 0; e < 4; ++e) set_elem(o, e, elem(xv, e) + sc * elem(gv, e));
+  for (int e = 0; e < 4; ++e) set_elem(o, e, ascent_point(elem(xv, e), sc, elem(gv, e)));
   store_bf16<4>(xt16 + (int64_t)k * shadow_stride + map.shadow[s] + b32s_offset(r, c, map.cblocks[s]), o);
 }
 
@@ -243,13 +243,11 @@ __global__ __launch_bounds__(kThreads) void descent_kernel(
   }
 #pragma unroll
   for (int e = 0; e < VEC; ++e) {
-    const float xe = elem(xv, e);
-    const float G = elem(gv, e) + lk * (xe - elem(yv, e));
-    const float vn = mu * elem(vv, e) + G;
-    const float xn = (nesterov ? xe - lr * (G + mu * vn) : xe - lr * vn) + xi[e];
-    set_elem(vv, e, vn);
-    set_elem(xv, e, xn);
-    set_elem(sv, e, elem(sv, e) + xn);
+    float xe = elem(xv, e), ve = elem(vv, e), se = elem(sv, e);
+    sampler_step(elem(gv, e), elem(yv, e), lk, lr, mu, nesterov, xi[e], xe, ve, se);
+    set_elem(vv, e, ve);
+    set_elem(xv, e, xe);
+    set_elem(sv, e, se);
   }
   st_param<VEC, STREAM>(x + o, xv);
   stv<VEC>(v + o, vv);

@@ -432,11 +432,13 @@ void build_layout(const lsam_config& c, Layout& lo) {
 // ---- per-kernel timing ---------------------------------------------------------------------------
 enum KernelClass {
   KC_GEMM_FWD = 0, KC_GEMM_DX, KC_GEMM_DW, KC_SOFTMAX_CE, KC_BIAS_GRAD, KC_SUMSQ, KC_NORM_FINISH,
-  KC_PERTURB, KC_DESCENT, KC_CENTER, KC_MISC, KC_HEAD, KC_UNFOLD, KC_POOL, KC_CONV_FIRST, KC_BATCHNORM, KC_COUNT
+  KC_PERTURB, KC_DESCENT, KC_CENTER, KC_MISC, KC_HEAD, KC_UNFOLD, KC_POOL, KC_CONV_FIRST, KC_BATCHNORM,
+  KC_GEMM_DW_STEP, KC_GEMM_DW_NORM, KC_GEMM_DW_ASCEND, KC_COUNT
 };
 const char* const kClassNames[KC_COUNT] = {
     "gemm_fwd", "gemm_dx", "gemm_dw", "softmax_ce", "bias_grad", "sumsq_partials", "norm_finish",
-    "perturb", "descent", "center", "misc", "head", "unfold_fold", "pool", "conv_first", "batchnorm"};
+    "perturb", "descent", "center", "misc", "head", "unfold_fold", "pool", "conv_first", "batchnorm",
+    "gemm_dw_step", "gemm_dw_norm", "gemm_dw_ascend"};
 
 struct TimedLaunch {
   int cls;
@@ -464,6 +466,7 @@ struct lsam_ctx {
   uint32_t t_step = 0;  // sampler steps taken (counter word of the Langevin noise)
   void* stage = nullptr;   // pinned host staging buffer for the read-out / restore calls (lazy)
   NoiseMap noise{};     // where the Langevin noise goes; used when cfg.noise_scale > 0
+  bool fuse_step = true;   // take the sampler step inside the second pass's dW epilogues where possible
   // timing
   bool timing = false;
   std::vector<TimedLaunch> pending;
@@ -744,7 +747,8 @@ int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq,
 // With convolution layers (fp32) the dense layers are l0 = n_conv .. L-1 and read what the
 // convolution stack produced.
 int forward_backward(lsam_ctx* c, const void* X, const int32_t* labels, const void* wts,
-                     bool second, bool fuse_norm) {
+                     bool second, bool fuse_norm, const SamplerFusion* fuse = nullptr,
+                     bool norm_only = false) {
   const bool want_loss = !second;
   const Layout& lo = c->lo;
   const int K = lo.K, B = lo.B, L = lo.L, l0 = lo.n_conv;
@@ -833,7 +837,7 @@ int forward_backward(lsam_ctx* c, const void* X, const int32_t* labels, const vo
       if (ssq) slots += used;
       continue;
     }
-    {
+    auto weight_grad = [&]() -> int {
       GemmDesc d{};
       d.b32s = bf;
       d.A = dz; d.strideA = astride(l + 1); d.ldA = ld_dz; d.a_kmajor = 0; d.cbA = b32s_blocks(ly.out);
@@ -843,19 +847,40 @@ int forward_backward(lsam_ctx* c, const void* X, const int32_t* labels, const vo
       d.in_bf16 = bf; d.out_bf16 = 0; d.epilogue = EPI_PLAIN;
       split(c, d);
       if (ssq) { d.sumsq = ssq + slots; d.sumsq_stride = lo.nblk; }
+      d.sumsq_only = (ssq && norm_only) ? 1 : 0;   // the gradient itself is recomputed by ascend_pass
+      SamplerFusion f;
+      if (fuse) {
+        // this layer's share of the sampler step happens in the epilogue: W_l of x, v, S, y
+        f = *fuse;
+        f.x += ly.w_off; f.v += ly.w_off; f.S += ly.w_off; f.y += ly.w_off;
+        f.shadow += lo.shadow_off[l];
+        f.cbShadow = b32s_blocks(ly.in);
+        d.fuse = &f;
+      }
       int used = 0;
-      LaunchTimer t(c, KC_GEMM_DW);
+      LaunchTimer t(c, fuse ? KC_GEMM_DW_STEP : d.sumsq_only ? KC_GEMM_DW_NORM : KC_GEMM_DW);
       if (launch_gemm(d, s, &used) != 0) return fail(LSAM_EINVAL, "dW GEMM of layer %d rejected", l);
       if (ssq) slots += used;
-    }
-    {
-      LaunchTimer t(c, KC_BIAS_GRAD);
-      const int used = launch_bias_grad(dz, bf ? astride(l + 1) : (int64_t)ld_dz, bf, g + ly.b_off,
-                                        lo.d_pad, K, B, ly.out, ssq ? ssq + slots : nullptr,
-                                        lo.nblk, s);
-      if (ssq) slots += used;
-    }
-    if (l > l0 || need_dA0) {
+      return LSAM_OK;
+    };
+    auto bias_grad = [&]() {
+      {
+        LaunchTimer t(c, KC_BIAS_GRAD);
+        const int used = launch_bias_grad(dz, bf ? astride(l + 1) : (int64_t)ld_dz, bf, g + ly.b_off,
+                                          lo.d_pad, K, B, ly.out, ssq ? ssq + slots : nullptr,
+                                          lo.nblk, s);
+        if (ssq) slots += used;
+      }
+      if (fuse) {
+        // the bias vector's share of the sampler step (the slot of b_l is padded to 64 floats
+        // with zeros, which the step leaves zero)
+        LaunchTimer t(c, KC_DESCENT);
+        launch_descent(fuse->x + ly.b_off, g + ly.b_off, lo.d_pad, fuse->v + ly.b_off,
+                       fuse->S + ly.b_off, fuse->y + ly.b_off, nullptr, nullptr, 0, lo.d_pad,
+                       round_up(ly.out, 4), K, fuse->lam, fuse->lr, fuse->mu, fuse->nesterov, nullptr, s);
+      }
+    };
+    auto input_grad = [&]() -> int {
       GemmDesc d{};
       d.b32s = bf;
       d.A = dz; d.strideA = astride(l + 1); d.ldA = ld_dz; d.a_kmajor = 1; d.cbA = b32s_blocks(ly.out);
@@ -867,7 +892,16 @@ int forward_backward(lsam_ctx* c, const void* X, const int32_t* labels, const vo
       split(c, d);
       LaunchTimer t(c, KC_GEMM_DX);
       if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "dX GEMM of layer %d rejected", l);
-    }
+      return LSAM_OK;
+    };
+    const bool want_dx = l > l0 || need_dA0;
+    int rc = LSAM_OK;
+    // With the fused step the weight-gradient kernel overwrites the operand copy of W_l that
+    // the input gradient still has to read, so that one goes first.
+    if (fuse && want_dx && (rc = input_grad()) != LSAM_OK) return rc;
+    if ((rc = weight_grad()) != LSAM_OK) return rc;
+    bias_grad();
+    if (!fuse && want_dx && (rc = input_grad()) != LSAM_OK) return rc;
   }
   if (l0 > 0) {
     int rc = conv_backward(c, static_cast<const float*>(X), params, ssq, &slots);
@@ -880,11 +914,47 @@ int forward_backward(lsam_ctx* c, const void* X, const int32_t* labels, const vo
   return check_launch("forward/backward");
 }
 
+// bf16 dense model with the fused step: the weight gradients of the first pass were only summed
+// (their squares), not stored.  Now that the norm is known each is computed once more from the
+// dZ_l and A_{l-1} the first pass left behind, and its epilogue writes the operand copy of the
+// perturbed weights bf16(x + scale g1) directly: 6 bytes per parameter (x read, copy written)
+// instead of the 14 of storing g1, reading it back with x and writing the copy, at the price of
+// one more contraction per layer, which the matrix units have room for.  Biases need no copy:
+// the second pass's GEMMs form x_b + scale g1_b from the stored bias gradient.
+int ascend_pass(lsam_ctx* c, const void* A0) {
+  const Layout& lo = c->lo;
+  const int K = lo.K, B = lo.B, L = lo.L;
+  auto width = [&](int l) { return l < L ? lo.layers[l].in : lo.layers[L - 1].out; };
+  auto astride = [&](int l) { return lo.act_elems(width(l), lo.ld[l]); };
+  for (int l = L - 1; l >= 0; --l) {
+    const Layer& ly = lo.layers[l];
+    GemmDesc d{};
+    d.b32s = 1;
+    d.A = c->at<char>(lo.dz[l + 1]); d.strideA = astride(l + 1); d.ldA = lo.ld[l + 1]; d.a_kmajor = 0;
+    d.cbA = b32s_blocks(ly.out);
+    d.B = l == 0 ? A0 : (const void*)c->at<char>(lo.act[l]); d.strideB = astride(l); d.ldB = lo.ld[l];
+    d.b_kmajor = 0; d.cbB = b32s_blocks(ly.in);
+    d.C = c->at<float>(lo.g) + ly.w_off; d.strideC = lo.d_pad; d.ldC = ly.ldw;
+    d.M = ly.out; d.N = ly.in; d.Kd = B; d.batch = K;
+    d.in_bf16 = 1; d.out_bf16 = 0; d.epilogue = EPI_PLAIN;
+    AscentFusion f;
+    f.x = c->at<float>(lo.x) + ly.w_off;
+    f.scale = c->at<float>(lo.scale);
+    f.shadow = c->at<uint16_t>(lo.xt) + lo.shadow_off[l];
+    f.shadow_stride = lo.shadow_stride;
+    f.cbShadow = b32s_blocks(ly.in);
+    d.ascend = &f;
+    LaunchTimer t(c, KC_GEMM_DW_ASCEND);
+    if (launch_gemm(d, c->stream) != 0) return fail(LSAM_EINVAL, "ascent GEMM of layer %d rejected", l);
+  }
+  return check_launch("ascent GEMMs");
+}
+
 // Norm of g1 and the perturbed point.  `partials_ready`: the kernels that wrote g1 already
 // left the partial sums of its squares.  With rho = 0 the perturbed point is x itself and is
 // not written.
 int update_tail_first(lsam_ctx* c, const float* g1, int64_t g_stride, int64_t n, float* loss,
-                      bool partials_ready) {
+                      bool partials_ready, bool perturb = true) {
   const Layout& lo = c->lo;
   hipStream_t s = c->stream;
   int nparts = partials_ready ? c->norm_slots : (lo.nblk < 1024 ? lo.nblk : 1024);
@@ -900,7 +970,7 @@ int update_tail_first(lsam_ctx* c, const float* g1, int64_t g_stride, int64_t n,
                        lo.raw ? nullptr : c->at<float>(lo.loss_rows), lo.B,
                        lo.raw ? nullptr : (loss ? loss : c->at<float>(lo.loss)), s);
   }
-  if (c->rho != 0.f) {
+  if (c->rho != 0.f && perturb) {
     LaunchTimer t(c, KC_PERTURB);
     launch_perturb(c->at<float>(lo.x), g1, g_stride, c->at<float>(lo.scale),
                    lo.bf16 ? nullptr : c->at<float>(lo.xt),
@@ -910,8 +980,20 @@ int update_tail_first(lsam_ctx* c, const float* g1, int64_t g_stride, int64_t n,
   return check_launch("norm/perturb");
 }
 
-int update_tail_second(lsam_ctx* c, const float* g2, int64_t g_stride, int64_t n) {
+// Whether the sampler step of this configuration can ride in the epilogues of the second
+// pass's weight-gradient GEMMs: bf16 dense model, Algorithm 2 (the data-parallel baseline needs
+// the averaged gradient first), no Langevin noise.
+bool can_fuse_step(const lsam_ctx* c) {
+  return c->lo.bf16 && c->cfg.algorithm == LSAM_ALG_LSAM && !(c->cfg.noise_scale > 0.f) && c->fuse_step;
+}
+
+int update_tail_second(lsam_ctx* c, const float* g2, int64_t g_stride, int64_t n, bool already_stepped = false) {
   const Layout& lo = c->lo;
+  if (already_stepped) {
+    ++c->t_step;
+    c->sched.tick();
+    return check_launch("descent");
+  }
   ReplicaScalars lam;
   for (int i = 0; i < lo.K; ++i) lam.v[i] = coupling(c, i);
   const NoiseMap* noise = nullptr;
@@ -1190,15 +1272,30 @@ int lsam_step(lsam_ctx* c, const void* X, const int32_t* labels, float* loss) {
     launch_grad_mean(g, lo.d_pad, g, lo.d_pad, lo.d_pad, lo.K, lo.K, c->stream);
   };
   const void* w1 = lo.bf16 ? (const void*)c->at<char>(lo.xt) : (const void*)c->at<char>(lo.x);
-  if ((rc = forward_backward(c, A0, labels, w1, false, !dp)) != LSAM_OK) return rc;
+  // bf16 dense model, Algorithm 2, no noise: neither gradient of a weight matrix is stored.
+  // First pass: sums of squares only; then the ascent GEMMs; second pass: the sampler step in
+  // the weight-gradient epilogues.
+  const bool fused = c->rho != 0.f && can_fuse_step(c);
+  if ((rc = forward_backward(c, A0, labels, w1, false, !dp, nullptr, fused)) != LSAM_OK) return rc;
   if (dp) average();
-  if ((rc = update_tail_first(c, g, lo.d_pad, lo.d_pad, loss, !dp)) != LSAM_OK) return rc;
+  if ((rc = update_tail_first(c, g, lo.d_pad, lo.d_pad, loss, !dp, !fused)) != LSAM_OK) return rc;
+  if (fused && (rc = ascend_pass(c, A0)) != LSAM_OK) return rc;
+  bool stepped = false;
   if (c->rho != 0.f) {     // otherwise the perturbed point is x and g already is its gradient
-    if ((rc = forward_backward(c, A0, labels, c->at<char>(lo.xt), true, false)) != LSAM_OK)
+    SamplerFusion f;
+    if (fused) {
+      f.x = c->at<float>(lo.x); f.v = c->at<float>(lo.v); f.S = c->at<float>(lo.S);
+      f.y = c->at<float>(lo.y);
+      f.shadow = c->at<uint16_t>(lo.xt); f.shadow_stride = lo.shadow_stride; f.cbShadow = 0;
+      for (int i = 0; i < lo.K; ++i) f.lam.v[i] = coupling(c, i);
+      f.lr = c->lr; f.mu = c->cfg.momentum; f.nesterov = c->cfg.nesterov;
+      stepped = true;
+    }
+    if ((rc = forward_backward(c, A0, labels, c->at<char>(lo.xt), true, false, stepped ? &f : nullptr)) != LSAM_OK)
       return rc;
     if (dp) average();
   }
-  return update_tail_second(c, g, lo.d_pad, lo.d_pad);
+  return update_tail_second(c, g, lo.d_pad, lo.d_pad, stepped);
 }
 
 int lsam_step_grads(lsam_ctx* c, const float* g1, const float* g2) {
@@ -1344,6 +1441,12 @@ int lsam_get_schedule(lsam_ctx* c, int32_t* tau_out, int32_t* count_out, int64_t
   }
   if (t_y_out) *t_y_out = c->sched.t_y();
   return LSAM_OK;
+}
+
+int lsam_set_fused_step(lsam_ctx* c, int32_t on) {
+  if (!c) return fail(LSAM_EINVAL, "ctx is NULL");
+  c->fuse_step = on != 0;
+  return can_fuse_step(c) ? 1 : 0;
 }
 
 int lsam_note_replay(lsam_ctx* c) {

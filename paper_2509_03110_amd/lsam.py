@@ -27,7 +27,7 @@ EXPORTS = [
     "lsam_get_params", "lsam_get_buffer", "lsam_set_buffer", "lsam_get_norms", "lsam_get_schedule",
     "lsam_set_scalars", "lsam_num_params", "lsam_schedule_replay", "lsam_timing_enable",
     "lsam_timing_read", "lsam_probe_peaks", "lsam_destroy", "lsam_last_error",
-    "lsam_get_counters", "lsam_set_counters", "lsam_get_activation", "lsam_step_grads_static", "lsam_note_replay",
+    "lsam_get_counters", "lsam_set_counters", "lsam_get_activation", "lsam_step_grads_static", "lsam_note_replay", "lsam_set_fused_step",
 ]
 
 
@@ -95,6 +95,8 @@ def lib():
         L.lsam_get_schedule.argtypes = [vp, vp, vp, vp]
         L.lsam_set_scalars.restype = C.c_int
         L.lsam_set_scalars.argtypes = [vp, C.c_float, C.c_float]
+        L.lsam_set_fused_step.restype = C.c_int
+        L.lsam_set_fused_step.argtypes = [vp, i32]
         L.lsam_note_replay.restype = C.c_int
         L.lsam_note_replay.argtypes = [vp]
         L.lsam_get_counters.restype = C.c_int
@@ -280,6 +282,9 @@ class Lsam:
         ty = C.c_int64(0)
         _check(lib().lsam_get_schedule(self._h, tau.ctypes.data, cnt.ctypes.data, C.byref(ty)))
         return tau.tolist(), cnt.tolist(), ty.value
+
+    def lsam_set_fused_step(self, on):
+        return _check(lib().lsam_set_fused_step(self._h, 1 if on else 0))
 
     def lsam_note_replay(self):
         return _check(lib().lsam_note_replay(self._h))

@@ -63,7 +63,7 @@ def anchor(g, o):
 
 
 def run_mlp(w, steps, tol1, tol_run, check_every=1, margin=False, tol_flip=5e-2,
-            anchor_after=None, margin_ratio=None, min_margin=1e-3):
+            anchor_after=None, margin_ratio=None, min_margin=1e-3, fused=True):
     """Runs GPU and oracle side by side.
 
     margin=True starts from parameters whose hidden pre-activations are far from zero, so no
@@ -85,6 +85,7 @@ def run_mlp(w, steps, tol1, tol_run, check_every=1, margin=False, tol_flip=5e-2,
     else:
         init = workloads.init_params(w)
     g, o = make_pair(w, init)
+    fused_step = bool(g.lsam_set_fused_step(fused)) and w.rho != 0.0
     tol_v = None if margin else tol_flip
     loss_d = torch.zeros(w.K, dtype=torch.float32, device=DEV)
     worst = 0.0
@@ -105,10 +106,14 @@ def run_mlp(w, steps, tol1, tol_run, check_every=1, margin=False, tol_flip=5e-2,
             assert np.allclose(norms, o.last_norm, rtol=(tol1 if margin else tol_flip)), (norms, o.last_norm)
             for i in range(w.K):
                 g2 = g.lsam_get_buffer(lsam.BUF_GRAD, i)
-                if margin:
+                # with the fused step neither gradient of a weight matrix is ever stored (their
+                # effect is checked through x~, v and x); the bias parts hold g2 as always
+                if fused_step or margin:
                     for l, (o0, o1, o2) in enumerate(o.model.offsets):
-                        close_enough(g2[o0:o1], o.last_g2[i][o0:o1], tol1, "dW%d of replica %d" % (l + 1, i))
-                        close_enough(g2[o1:o2], o.last_g2[i][o1:o2], tol1, "db%d of replica %d" % (l + 1, i))
+                        t_g = tol1 if margin else tol_flip
+                        if not fused_step:
+                            close_enough(g2[o0:o1], o.last_g2[i][o0:o1], t_g, "dW%d of replica %d" % (l + 1, i))
+                        close_enough(g2[o1:o2], o.last_g2[i][o1:o2], t_g, "db%d of replica %d" % (l + 1, i))
                 else:
                     close_enough(g2, o.last_g2[i], tol_flip, "g2 of replica %d" % i)
         ng, no = g.lsam_sync(), o.sync()
@@ -337,6 +342,8 @@ def test_bf16_reduced_shapes(name, width, B):
     print("%s reduced, margin init: worst relative error %.3e" % (name, worst))
     worst = run_mlp(w, w.steps, 2e-2, 2e-2, margin=False, tol_flip=1e-1, anchor_after=2)
     print("%s reduced: worst relative error %.3e" % (name, worst))
+    # the same with the sampler step as a kernel of its own (g2 stored and compared)
+    run_mlp(w, 4, 2e-2, 2e-2, margin=True, fused=False)
 
 
 @pytest.mark.parametrize("name,width,B", [("cfg3", 256, 32), ("cfg5", 128, 64)])
@@ -348,6 +355,38 @@ def test_bf16_reduced_shapes_free_running_twenty_steps(name, width, B):
     w = full.scaled(dims=dims, batch=B, steps=20)
     worst = run_mlp(w, w.steps, 2e-2, 2e-2, margin=True, margin_ratio=64.0, min_margin=1e-4)
     print("%s reduced, free-running, lr %.2f: worst relative error over 20 steps %.3e" % (name, w.lr, worst))
+
+
+@pytest.mark.parametrize("dims,B,K,tau,nesterov", [
+    ((384, 256, 256, 256, 100), 32, 3, (2, 3, 4), 1),
+    ((40, 72, 100, 9), 20, 2, (1, 2), 0),              # widths that are no multiples of 4, 8 or 32
+    ((352, 288, 288, 160), 160, 2, (2, 3), 1),         # ragged 128x128 tiles
+    ((512, 512, 520, 24), 256, 2, (2, 2), 1)])         # 256x128 tiles with a ragged last column tile
+def test_fused_sampler_step_equals_the_separate_kernel(dims, B, K, tau, nesterov):
+    """The sampler step taken inside the weight-gradient epilogues against the same step as a
+    kernel of its own (which the other bf16 tests hold to the oracle): identical arithmetic on
+    identical values, so parameters, velocities, iterate sums, the center and the bf16 operand
+    copy must agree bit for bit after several steps and center updates."""
+    w = workloads.WORKLOADS["cfg3"].scaled(name="fuse", K=K, dims=dims, batch=B, tau=tau,
+                                           nesterov=nesterov, n_classes=dims[-1], batch_pool=0)
+    init = workloads.init_params(w)
+    cfg, keep = lsam.config_from_workload(w)
+    a = lsam.Lsam(cfg, init, device=DEV, keep=keep)
+    b = lsam.Lsam(cfg, init, device=DEV, keep=keep)
+    assert a.lsam_set_fused_step(True) == 1 and b.lsam_set_fused_step(False) == 0
+    for t in range(5):
+        X, lab = workloads.batch(w, t)
+        Xd, ld = to_dev(X, lab, w)
+        a.lsam_step(Xd, ld, None)
+        b.lsam_step(Xd, ld, None)
+        assert a.lsam_sync() == b.lsam_sync()
+        for i in list(range(K)) + [-1]:
+            assert np.array_equal(a.lsam_get_params(i), b.lsam_get_params(i)), (t, i)
+        for i in range(K):
+            for which in (lsam.BUF_VELOCITY, lsam.BUF_ITER_SUM, lsam.BUF_PERTURBED):
+                assert np.array_equal(a.lsam_get_buffer(which, i), b.lsam_get_buffer(which, i)), (t, i, which)
+    a.close()
+    b.close()
 
 
 def test_bf16_ragged_shapes():

@@ -407,7 +407,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
           __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, xe), rx, off, 0, NT);
           __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, ve), rv, off, 0, NT);
           __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, se), rs, off, 0, NT);
-          const unsigned woff = col_ok ? (unsigned)b32s_offset(m, n, p.cbShadow) * 2u : kOut;
+          const unsigned woff = (col_ok && m < p.M) ? (unsigned)b32s_offset(m, n, p.cbShadow) * 2u : kOut;
           __builtin_amdgcn_raw_buffer_store_b64(Out<__bf16>::from(xe), rw, woff, 0, 0);
         }
       }
@@ -455,7 +455,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
           f32x4 xe = __builtin_bit_cast(f32x4, xv[u]);
 #pragma unroll
           for (int r = 0; r < 4; ++r) xe[r] = ascent_point(xe[r], sc, gv[r]);
-          const unsigned woff = col_ok ? (unsigned)b32s_offset(m, n, p.cbShadow) * 2u : kOut;
+          const unsigned woff = (col_ok && m < p.M) ? (unsigned)b32s_offset(m, n, p.cbShadow) * 2u : kOut;
           __builtin_amdgcn_raw_buffer_store_b64(Out<__bf16>::from(xe), rw, woff, 0, 0);
         }
       }

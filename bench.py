@@ -120,8 +120,10 @@ def gemm_flops(w, fused_step=False):
     if first:
         out["conv_first"] = 2 * 2 * 2.0 * first * K      # forward and weight gradient
     if fused_step:
-        out["gemm_dw"] /= 2
-        out["gemm_dw_step"] = out["gemm_dw"]
+        # the weight-gradient product is formed three times per step: for the norm, for the
+        # perturbed operand copy, and at the perturbed point for the sampler step
+        one = out.pop("gemm_dw") / 2
+        out["gemm_dw_norm"] = out["gemm_dw_ascend"] = out["gemm_dw_step"] = one
     return out
 
 
@@ -175,6 +177,9 @@ def stream_bytes(w, fused_step=False):
         nb = w.d - nw
         out["gemm_dw_step"] = 26.0 * w.K * nw + 4.0 * nw
         out["descent"] = 28.0 * w.K * nb + 4.0 * nb
+        # the ascent GEMMs read x and write the bf16 copy of x~; no perturbation kernel runs
+        out["gemm_dw_ascend"] = 6.0 * w.K * nw
+        del out["perturb"]
     return out
 
 
@@ -314,7 +319,7 @@ def run_workload(w, steps, warmup, kernel_timing=True):
                 continue
             k = {"launches_per_step": cnt / steps, "ms_per_step": tot / steps,
                  "avg_launch_ms": tot / cnt}
-            if name == "gemm_dw_step" and tot > 0:
+            if name in ("gemm_dw_step", "gemm_dw_ascend") and name in nbytes and tot > 0:
                 # a contraction whose epilogue streams the sampler state: priced against the
                 # roof that binds it (HBM), with its matrix-unit rate beside it
                 k.update(bound="hbm", achieved=nbytes[name] * steps / (tot * 1e-3) / 1e9,

@@ -179,7 +179,7 @@ class Mlp:
         return loss, grad
 
 
-def conv_layer_shapes(dims, n_conv, img_h, img_w, pool_mask):
+def conv_layer_shapes(dims, n_conv, img_h, img_w, pool_mask, stride_mask=0, global_avg_pool=0):
     """(fan_in, out) of every layer of the convolutional model described at `Cnn`, plus the
     image size after the convolution stack."""
     h, w = int(img_h), int(img_w)
@@ -187,12 +187,16 @@ def conv_layer_shapes(dims, n_conv, img_h, img_w, pool_mask):
     for l in range(len(dims) - 1):
         if l < n_conv:
             shapes.append((9 * dims[l], dims[l + 1]))
+            if (stride_mask >> l) & 1:
+                if h % 2 or w % 2:
+                    raise ValueError("a stride-2 convolution needs even image sides")
+                h, w = h // 2, w // 2
             if (pool_mask >> l) & 1:
                 if h % 2 or w % 2:
                     raise ValueError("2x2 pooling needs even image sides")
                 h, w = h // 2, w // 2
         elif l == n_conv:
-            shapes.append((h * w * dims[l], dims[l + 1]))
+            shapes.append(((1 if global_avg_pool else h * w) * dims[l], dims[l + 1]))
         else:
             shapes.append((dims[l], dims[l + 1]))
     return shapes, (h, w)
@@ -220,12 +224,26 @@ class Cnn:
       dbeta = sum dY, dgamma = sum dY Xh, dZ = gamma / sqrt(var + eps) (dY - dbeta/N - Xh dgamma/N).
     Running averages for inference are not part of a training step and are not kept.
 
-      Z[b,i,j,o] = b[o] + sum_{u,v,c} Xpad[b,i+u,j+v,c] W[o,u,v,c]     (Xpad: X with a zero rim)
+    Residual networks (the ResNet models of Section "Experiments"; He et al., "Deep Residual
+    Learning for Image Recognition", CIFAR variant): bit l of stride_mask gives convolution l
+    stride 2 (output [H/2, W/2]); bit l of skip_mask closes a basic block of the two
+    convolutions l-1 and l: the block's input, i.e. the image convolution l-1 read, is added
+    to the (normalised) output of convolution l before its ReLU.  Where the two differ in shape
+    the shortcut is that paper's parameter-free one: every second pixel of the block input in
+    both directions, channels padded with zeros.  global_avg_pool: the dense layers read the
+    mean of the last image over its positions, one value per channel.
+
+      Z[b,i,j,o] = b[o] + sum_{u,v,c} Xpad[b,s i+u,s j+v,c] W[o,u,v,c]     (Xpad: X with a zero rim, s: stride)
       P[b,i,j,c] = max_{u,v in {0,1}} A[b,2i+u,2j+v,c]
     The pool's gradient goes to the first maximal element of each window in (u, v) order."""
 
-    def __init__(self, dims, n_conv, img_h, img_w, pool_mask, bn_mask=0, bn_eps=1e-5, gemm_dtype=0):
+    def __init__(self, dims, n_conv, img_h, img_w, pool_mask, bn_mask=0, bn_eps=1e-5, gemm_dtype=0,
+                 stride_mask=0, skip_mask=0, global_avg_pool=0):
         self.bn_mask, self.bn_eps = int(bn_mask), float(bn_eps)
+        self.stride_mask, self.skip_mask = int(stride_mask), int(skip_mask)
+        self.gap = int(global_avg_pool)
+        if self.skip_mask & 0b11:
+            raise ValueError("a block needs two convolutions below its closing one")
         # gemm_dtype 1: every matrix product (each tap of a convolution, each dense layer, and
         # their dW and dX) takes its two operands rounded to bfloat16 and accumulates exactly;
         # everything stored -- activations, gradients, biases, normalisation -- stays unrounded
@@ -237,7 +255,7 @@ class Cnn:
         self.H, self.W = int(img_h), int(img_w)
         self.pool_mask = int(pool_mask)
         self.shapes, self.final_hw = conv_layer_shapes(self.dims, self.n_conv, self.H, self.W,
-                                                       self.pool_mask)
+                                                       self.pool_mask, self.stride_mask, self.gap)
         self.offsets = []
         self.bn_offsets = {}        # layer -> (start of gamma, start of beta, end)
         off = 0
@@ -250,6 +268,31 @@ class Cnn:
         self.d = off
         self.last_margin = np.inf
 
+    @staticmethod
+    def _shortcut(src, shape):
+        """The block input `src` [B, H, W, C] brought to `shape` [B, H', W', C']: every second
+        pixel when the block halved the image, zero channels appended when it widened it."""
+        s = src
+        if s.shape[1] != shape[1]:
+            s = s[:, ::2, ::2, :]
+        if s.shape[1:3] != tuple(shape[1:3]) or s.shape[3] > shape[3]:
+            raise ValueError("shortcut and block output do not fit")
+        out = np.zeros(shape)
+        out[..., :s.shape[3]] = s
+        return out
+
+    @staticmethod
+    def _shortcut_adjoint(g, shape):
+        """Adjoint of `_shortcut`: the gradient of the block output `g`, sent back to the shape
+        of the block input."""
+        out = np.zeros(shape)
+        part = g[..., :shape[3]]
+        if shape[1] != g.shape[1]:
+            out[:, ::2, ::2, :] = part
+        else:
+            out[...] = part
+        return out
+
     def loss_and_grad(self, x, X, labels):
         x = np.asarray(x, dtype=np.float64)
         X = np.asarray(X, dtype=np.float64)
@@ -258,20 +301,22 @@ class Cnn:
         B = X.shape[0]
         self.last_margin = np.inf
         # ---- forward ----
-        conv_in, conv_act, pooled_from = [], [], []
+        conv_in, conv_act, pooled_from, conv_src = [], [], [], []
         A = X
         for l in range(self.n_conv):
             o0, o1, o2 = self.offsets[l]
             cin, cout = self.dims[l], self.dims[l + 1]
+            st = 2 if (self.stride_mask >> l) & 1 else 1
             Wl = x[o0:o1].reshape(cout, 3, 3, cin)
-            h, w = A.shape[1], A.shape[2]
-            Ap = np.zeros((B, h + 2, w + 2, cin))
-            Ap[:, 1:h + 1, 1:w + 1, :] = A
+            hin, win = A.shape[1], A.shape[2]
+            h, w = hin // st, win // st
+            Ap = np.zeros((B, hin + 2, win + 2, cin))
+            Ap[:, 1:hin + 1, 1:win + 1, :] = A
             Z = np.zeros((B, h, w, cout)) + x[o1:o2]
             Apq, Wq = q(Ap), q(Wl)
             for u in range(3):
                 for v in range(3):
-                    Z += Apq[:, u:u + h, v:v + w, :] @ Wq[:, u, v, :].T
+                    Z += Apq[:, u:u + st * h:st, v:v + st * w:st, :] @ Wq[:, u, v, :].T
             if l in self.bn_offsets:
                 g0, g1, g2 = self.bn_offsets[l]
                 mu = Z.mean(axis=(0, 1, 2))
@@ -280,18 +325,24 @@ class Cnn:
                 Xh = (Z - mu) * inv
                 bn_saved[l] = (Xh, inv)
                 Z = x[g0:g1] * Xh + x[g1:g2]
+            if (self.skip_mask >> l) & 1:
+                Z = Z + self._shortcut(conv_src[l - 1], Z.shape)
             self.last_margin = min(self.last_margin, float(np.min(np.abs(Z))))
             R = np.maximum(Z, 0.0)
+            conv_src.append(A)
             conv_in.append(Ap)
             conv_act.append(R)
             if (self.pool_mask >> l) & 1:
-                win = R.reshape(B, h // 2, 2, w // 2, 2, cout).transpose(0, 1, 3, 5, 2, 4)
-                win = win.reshape(B, h // 2, w // 2, cout, 4)       # window order (u, v)
-                pooled_from.append(np.argmax(win, axis=-1))          # first maximum
-                A = win.max(axis=-1)
+                win_ = R.reshape(B, h // 2, 2, w // 2, 2, cout).transpose(0, 1, 3, 5, 2, 4)
+                win_ = win_.reshape(B, h // 2, w // 2, cout, 4)     # window order (u, v)
+                pooled_from.append(np.argmax(win_, axis=-1))         # first maximum
+                A = win_.max(axis=-1)
             else:
                 pooled_from.append(None)
                 A = R
+        final_image = A
+        if self.gap:
+            A = A.mean(axis=(1, 2))
         acts = [A.reshape(B, -1)]
         for l in range(self.n_conv, self.L):
             o0, o1, o2 = self.offsets[l]
@@ -323,9 +374,14 @@ class Cnn:
             dA = q(dZ) @ q(x[o0:o1].reshape(fo, fi))
             if l > self.n_conv:
                 dZ = dA * (a_in > 0.0)
+        if self.gap and self.n_conv:
+            bh, bw = final_image.shape[1], final_image.shape[2]
+            dA = np.broadcast_to(dA[:, None, None, :] / (bh * bw), final_image.shape)
+        skip_grad = {}       # layer whose input receives it -> gradient of the shortcut
         for l in range(self.n_conv - 1, -1, -1):
             o0, o1, o2 = self.offsets[l]
             cin, cout = self.dims[l], self.dims[l + 1]
+            st = 2 if (self.stride_mask >> l) & 1 else 1
             R = conv_act[l]
             h, w = R.shape[1], R.shape[2]
             if pooled_from[l] is not None:
@@ -337,6 +393,8 @@ class Cnn:
             else:
                 dR = dA.reshape(B, h, w, cout)
             dZc = dR * (R > 0.0)
+            if (self.skip_mask >> l) & 1:
+                skip_grad[l - 1] = dZc            # the sum's gradient reaches both of its terms
             if l in self.bn_offsets:
                 g0, g1, g2 = self.bn_offsets[l]
                 Xh, inv = bn_saved[l]
@@ -348,17 +406,20 @@ class Cnn:
                 dZc = x[g0:g1] * inv * (dZc - dbeta / n - Xh * dgamma / n)
             Wl = x[o0:o1].reshape(cout, 3, 3, cin)
             Ap = conv_in[l]
+            hin, win = Ap.shape[1] - 2, Ap.shape[2] - 2
             dW = np.zeros((cout, 3, 3, cin))
             dAp = np.zeros_like(Ap)
             flat = dZc.reshape(-1, cout)
             flatq, dZq, Apq, Wq = q(flat), q(dZc), q(Ap), q(Wl)
             for u in range(3):
                 for v in range(3):
-                    dW[:, u, v, :] = flatq.T @ Apq[:, u:u + h, v:v + w, :].reshape(-1, cin)
-                    dAp[:, u:u + h, v:v + w, :] += dZq @ Wq[:, u, v, :]
+                    dW[:, u, v, :] = flatq.T @ Apq[:, u:u + st * h:st, v:v + st * w:st, :].reshape(-1, cin)
+                    dAp[:, u:u + st * h:st, v:v + st * w:st, :] += dZq @ Wq[:, u, v, :]
             grad[o0:o1] = dW.ravel()
             grad[o1:o2] = flat.sum(axis=0)
-            dA = dAp[:, 1:h + 1, 1:w + 1, :]
+            dA = dAp[:, 1:hin + 1, 1:win + 1, :]
+            if l in skip_grad:
+                dA = dA + self._shortcut_adjoint(skip_grad.pop(l), dA.shape)
         return loss, grad
 
 
@@ -451,14 +512,16 @@ class LsamOracle:
                  rho=0.05, gamma=1e-12, lr=0.1, lr_center=1.0, momentum=0.9, beta=0.9,
                  lambda0=0.5, lambda_abs=-1.0, nesterov=1, tau=None, tau_min=1, tau_max=1,
                  sched_seed=0, sched_mode=SCHED_FIXED, algorithm=ALG_LSAM, noise_scale=0.0,
-                 noise_seed=0, n_conv=0, img_h=0, img_w=0, pool_mask=0, bn_mask=0, bn_eps=1e-5):
+                 noise_seed=0, n_conv=0, img_h=0, img_w=0, pool_mask=0, bn_mask=0, bn_eps=1e-5,
+                 stride_mask=0, skip_mask=0, global_avg_pool=0):
         self.K = int(K)
         self.algorithm = int(algorithm)
         self.noise_scale, self.noise_seed = float(noise_scale), int(noise_seed)
         self.dims = tuple(dims)
         self.t = 0                      # sampler steps taken so far
         if n_conv:
-            self.model = Cnn(dims, n_conv, img_h, img_w, pool_mask, bn_mask, bn_eps, gemm_dtype)
+            self.model = Cnn(dims, n_conv, img_h, img_w, pool_mask, bn_mask, bn_eps, gemm_dtype,
+                             stride_mask, skip_mask, global_avg_pool)
         else:
             self.model = Mlp(dims, gemm_dtype) if len(dims) else None
         self.shapes = self.model.shapes if n_conv else None

@@ -831,8 +831,10 @@ _MISPLACED_ROUNDINGS = [
     ("conv", "grad[o0:o1] = (q(dZ).T @ q(a_in)).ravel()", "grad[o0:o1] = (q(dZ).T @ a_in).ravel()"),
     ("conv", "dA = q(dZ) @ q(x[o0:o1].reshape(fo, fi))", "dA = q(dZ) @ x[o0:o1].reshape(fo, fi)"),
     ("conv", "dW[:, u, v, :] = flatq.T @", "dW[:, u, v, :] = flat.T @"),
-    ("conv", "Z += Apq[:, u:u + h, v:v + w, :] @ Wq[:, u, v, :].T", "Z += Ap[:, u:u + h, v:v + w, :] @ Wq[:, u, v, :].T"),
-    ("conv", "Z += Apq[:, u:u + h, v:v + w, :] @ Wq[:, u, v, :].T", "Z += Apq[:, u:u + h, v:v + w, :] @ Wl[:, u, v, :].T"),
+    ("conv", "Z += Apq[:, u:u + st * h:st, v:v + st * w:st, :] @ Wq[:, u, v, :].T",
+     "Z += Ap[:, u:u + st * h:st, v:v + st * w:st, :] @ Wq[:, u, v, :].T"),
+    ("conv", "Z += Apq[:, u:u + st * h:st, v:v + st * w:st, :] @ Wq[:, u, v, :].T",
+     "Z += Apq[:, u:u + st * h:st, v:v + st * w:st, :] @ Wl[:, u, v, :].T"),
 ]
 
 
@@ -855,3 +857,128 @@ def test_hand_cases_catch_a_misplaced_rounding(case, monkeypatch):
         check = test_bf16_rounding_placement_convolutional_model_hand_case
     with pytest.raises(AssertionError):
         check()
+
+
+# ---- residual networks: stride-2 convolutions, shortcuts, global average pooling ----------------
+def _torch_resnet_loss(xt, X, lab, dims, n_conv, shapes, bn_mask, stride_mask, skip_mask, gap, pool_mask=0,
+                       bn_eps=1e-5):
+    """The residual model written with torch's own routines: conv2d with a stride, batch_norm in
+    training mode, slicing and F.pad for the parameter-free shortcut, mean for the pooling."""
+    import torch.nn.functional as F
+    A = torch.tensor(X).permute(0, 3, 1, 2)
+    off = 0
+    inputs = []
+    for l in range(n_conv):
+        fi, fo = shapes[l]
+        W = xt[off:off + fo * fi].reshape(fo, 3, 3, dims[l]).permute(0, 3, 1, 2)
+        off += fo * fi
+        inputs.append(A)
+        Z = F.conv2d(A, W, xt[off:off + fo], padding=1, stride=2 if (stride_mask >> l) & 1 else 1)
+        off += fo
+        if (bn_mask >> l) & 1:
+            Z = F.batch_norm(Z, None, None, xt[off:off + fo], xt[off + fo:off + 2 * fo],
+                             training=True, eps=bn_eps)
+            off += 2 * fo
+        if (skip_mask >> l) & 1:
+            S = inputs[l - 1]
+            if S.shape[2] != Z.shape[2]:
+                S = S[:, :, ::2, ::2]
+            S = F.pad(S, (0, 0, 0, 0, 0, Z.shape[1] - S.shape[1]))
+            Z = Z + S
+        A = F.relu(Z)
+        if (pool_mask >> l) & 1:
+            A = F.max_pool2d(A, 2)
+    A = A.mean(dim=(2, 3)) if gap else A.permute(0, 2, 3, 1).reshape(X.shape[0], -1)
+    for l in range(n_conv, len(shapes)):
+        fi, fo = shapes[l]
+        A = A @ xt[off:off + fo * fi].reshape(fo, fi).T + xt[off + fo * fi:off + fo * fi + fo]
+        off += fo * fi + fo
+        if l < len(shapes) - 1:
+            A = F.relu(A)
+    return F.cross_entropy(A, torch.tensor(lab))
+
+
+@pytest.mark.parametrize("dims,n_conv,H,W,bn_mask,stride_mask,skip_mask,gap,B", [
+    # a stem and one block on the same shape
+    ((3, 4, 4, 4, 5), 3, 4, 4, 0b111, 0, 0b100, 1, 3),
+    # a stem, a block that halves the image and doubles the channels, a block on the new shape
+    ((2, 4, 8, 8, 8, 8, 3), 5, 8, 4, 0b11111, 0b00010, 0b10100, 1, 2),
+    # stride without shortcut or normalisation, flattened image into the dense layers
+    ((3, 6, 5, 4), 2, 6, 6, 0, 0b10, 0, 0, 4),
+    # shortcut that only widens (no stride), followed by a second dense layer
+    ((2, 3, 3, 6, 7, 3), 3, 4, 4, 0b111, 0, 0b100, 1, 3),
+])
+def test_residual_model_gradient_matches_torch_autograd(dims, n_conv, H, W, bn_mask, stride_mask,
+                                                        skip_mask, gap, B):
+    from oracle.lsam_oracle import Cnn
+    m = Cnn(dims, n_conv, H, W, 0, bn_mask, 1e-5, 0, stride_mask, skip_mask, gap)
+    rng = np.random.default_rng(21)
+    x = rng.standard_normal(m.d) * 0.3
+    for l, (g0, g1, g2) in m.bn_offsets.items():
+        x[g0:g1] = 1.0 + 0.3 * rng.standard_normal(g1 - g0)
+    X = rng.standard_normal((B, H, W, dims[0]))
+    lab = rng.integers(0, dims[-1], B)
+    loss, g = m.loss_and_grad(x, X, lab)
+    xt = torch.tensor(x, requires_grad=True)
+    L = _torch_resnet_loss(xt, X, lab, dims, n_conv, m.shapes, bn_mask, stride_mask, skip_mask, gap)
+    L.backward()
+    assert abs(loss - L.item()) < 1e-12
+    assert np.max(np.abs(g - xt.grad.numpy())) / np.max(np.abs(g)) < 1e-10
+
+
+def test_residual_model_gradient_matches_finite_differences():
+    from oracle.lsam_oracle import Cnn
+    m = Cnn((2, 4, 8, 8, 3), 3, 4, 4, 0, 0b111, 1e-5, 0, 0b010, 0b100, 1)
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal(m.d) * 0.4
+    X = rng.standard_normal((3, 4, 4, 2))
+    lab = np.array([0, 2, 1])
+    _, g = m.loss_and_grad(x, X, lab)
+    h = 1e-6
+    for j in rng.choice(m.d, 60, replace=False):
+        e = np.zeros(m.d)
+        e[j] = h
+        fd = (m.loss_and_grad(x + e, X, lab)[0] - m.loss_and_grad(x - e, X, lab)[0]) / (2 * h)
+        assert abs(fd - g[j]) < 1e-6 * max(1.0, np.max(np.abs(g))), j
+
+
+def test_shortcut_takes_every_second_pixel_and_pads_channels():
+    # with all filters zero, the normalised output of a block is beta, so the block output is
+    # relu(beta + shortcut) and can be written down: input channel c of pixel (2i, 2j) lands in
+    # channel c of pixel (i, j); the appended channels see beta alone
+    from oracle.lsam_oracle import Cnn
+    m = Cnn((2, 2, 4, 3), 2, 4, 4, 0, 0b11, 1e-5, 0, 0b01, 0b00, 0)
+    assert m.shapes == [(18, 2), (18, 4), (2 * 2 * 4, 3)]
+    src = np.arange(2 * 4 * 4 * 2, dtype=np.float64).reshape(2, 4, 4, 2) - 20.0
+    out = Cnn._shortcut(src, (2, 2, 2, 4))
+    assert out.shape == (2, 2, 2, 4)
+    for b in range(2):
+        for i in range(2):
+            for j in range(2):
+                assert np.array_equal(out[b, i, j, :2], src[b, 2 * i, 2 * j, :])
+                assert np.array_equal(out[b, i, j, 2:], [0.0, 0.0])
+    g = np.arange(2 * 2 * 2 * 4, dtype=np.float64).reshape(2, 2, 2, 4)
+    back = Cnn._shortcut_adjoint(g, src.shape)
+    # <shortcut(s), g> = <s, adjoint(g)> for the pair above
+    assert abs(np.sum(out * g) - np.sum(src * back)) < 1e-9
+    assert np.count_nonzero(back) <= 2 * 2 * 2 * 2
+
+
+def test_global_average_pool_of_a_constant_image():
+    # zero filters, beta = 3 in the only convolution: every pixel of every channel is relu(3),
+    # the pooled vector is 3 in each channel, and the logits are W 3 + b
+    from oracle.lsam_oracle import Cnn
+    m = Cnn((1, 2, 3), 1, 4, 6, 0, 0b1, 1e-5, 0, 0, 0, 1)
+    x = np.zeros(m.d)
+    g0, g1, g2 = m.bn_offsets[0]
+    x[g0:g1] = 1.0
+    x[g1:g2] = 3.0
+    o0, o1, o2 = m.offsets[1]
+    Wd = np.array([[1.0, 2.0], [0.0, -1.0], [0.5, 0.5]])
+    x[o0:o1] = Wd.ravel()
+    x[o1:o2] = [0.1, 0.2, 0.3]
+    X = np.random.default_rng(0).standard_normal((2, 4, 6, 1))
+    loss, _ = m.loss_and_grad(x, X, np.array([0, 1]))
+    logits = Wd @ np.array([3.0, 3.0]) + np.array([0.1, 0.2, 0.3])
+    lse = np.log(np.sum(np.exp(logits)))
+    assert abs(loss - 0.5 * ((lse - logits[0]) + (lse - logits[1]))) < 1e-12

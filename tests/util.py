@@ -12,7 +12,8 @@ def oracle_from(w, init, **over):
               tau_max=w.tau_max, sched_seed=w.sched_seed, sched_mode=w.sched_mode,
               algorithm=w.algorithm, noise_scale=w.noise_scale, noise_seed=w.noise_seed,
               n_conv=w.n_conv, img_h=w.img_h, img_w=w.img_w, pool_mask=w.pool_mask,
-              bn_mask=w.bn_mask, bn_eps=w.bn_eps)
+              bn_mask=w.bn_mask, bn_eps=w.bn_eps, stride_mask=w.stride_mask,
+              skip_mask=w.skip_mask, global_avg_pool=w.global_avg_pool)
     kw.update(over)
     return LsamOracle(**kw)
 

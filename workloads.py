@@ -56,6 +56,10 @@ class Workload:
     pool_mask: int = 0                      # bit l: 2x2 max-pool after convolution l
     bn_mask: int = 0                        # bit l: batch normalisation in convolution l
     bn_eps: float = 1e-5
+    stride_mask: int = 0                    # bit l: convolution l has stride 2
+    skip_mask: int = 0                      # bit l: the input of convolution l-1 is added to the
+                                            # output of convolution l before its ReLU (basic block)
+    global_avg_pool: int = 0                # 1: the dense layers read the per-channel mean of the last image
     steps: int = 20
     data_seed: int = 0
     n_classes: int = field(default=0)
@@ -72,10 +76,12 @@ class Workload:
             fan_in = self.dims[l]
             if l < self.n_conv:
                 fan_in = 9 * self.dims[l]
+                if (self.stride_mask >> l) & 1:
+                    h, w = h // 2, w // 2
                 if (self.pool_mask >> l) & 1:
                     h, w = h // 2, w // 2
             elif self.n_conv and l == self.n_conv:
-                fan_in = h * w * self.dims[l]
+                fan_in = self.dims[l] if self.global_avg_pool else h * w * self.dims[l]
             out.append((fan_in, self.dims[l + 1]))
         return out
 

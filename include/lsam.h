@@ -49,6 +49,15 @@
  * and beta [C_{l+1}] follow b_l in the flat layout.  No running averages are kept.  The bias
  * b_l of such a layer cannot influence the loss; its gradient is reported as exactly zero.
  * LSAM_BUF_PERTURBED holds x~_i in both arithmetic modes of this model (no bf16 copy exists).
+ * Residual networks (Section "Experiments" trains ResNet models; the blocks are the basic
+ * blocks of He et al., "Deep Residual Learning for Image Recognition", in their CIFAR form):
+ * stride_mask gives a convolution stride 2; skip_mask closes a block of two convolutions with a
+ * shortcut from the block's input, which must be the ReLU output of a convolution (not a pool,
+ * not the input image) and is taken as it is when the shapes agree and otherwise -- the block
+ * halved the image and/or widened the channels -- as every second pixel in both directions with
+ * zero channels appended (that paper's parameter-free shortcut).  The closing convolution must
+ * be batch-normalised and must not be followed by a pool inside the block; channel counts of
+ * the block input must be multiples of 4 and at most the block's output channels.
  */
 #ifndef LSAM_H
 #define LSAM_H
@@ -67,7 +76,7 @@ extern "C" {
 #define LSAM_ESTATE  -4   /* call not valid for this context (e.g. wrong mode)   */
 
 #define LSAM_MAX_REPLICAS 64
-#define LSAM_MAX_LAYERS   16
+#define LSAM_MAX_LAYERS   24
 
 #define LSAM_GEMM_FP32 0  /* fp32 operands, fp32 accumulate                      */
 #define LSAM_GEMM_BF16 1  /* bf16 operands, fp32 accumulate, fp32 master weights */
@@ -126,6 +135,12 @@ typedef struct {
   uint32_t pool_mask;     /* bit l set: a 2x2/stride-2 max-pool follows convolution l */
   uint32_t bn_mask;       /* bit l set: convolution l is batch-normalised before its ReLU */
   float bn_eps;           /* epsilon of the normalisation, > 0 (or 0 with bn_mask = 0) */
+  uint32_t stride_mask;   /* bit l set: convolution l has stride 2 (its output is [H/2, W/2]) */
+  uint32_t skip_mask;     /* bit l set (l >= 2): convolutions l-1 and l form a residual block; the
+                             block's input -- the image convolution l-1 read -- is added to the
+                             normalised output of convolution l before its ReLU; see below   */
+  int32_t global_avg_pool; /* 1: the dense layers read the mean of the last image over its
+                             positions (one value per channel) instead of the flattened image */
 } lsam_config;
 
 /* Which per-replica buffer `lsam_get_buffer` copies out. */

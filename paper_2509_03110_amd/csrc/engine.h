@@ -200,12 +200,14 @@ int launch_head_weight_grad(const float* dz, int ld_dz, const float* A, int ldA,
 // of 4 where stated).
 // col[k][(b,i,j)][(u,v,c)] = X[k][b][i+u-1][j+v-1][c], zero outside the image and in the
 // padding columns 9C..ld-1 (ld % 4 == 0; any C).
+// `stride` 1 or 2: the image is [stride H][stride W][C] and col row (b,i,j) holds the window
+// around pixel (stride i, stride j); H x W is the convolution's output.
 int launch_unfold3x3(const float* X, int64_t strideX, float* col, int64_t strideCol, int ld, int K,
-                     int B, int H, int W, int C, hipStream_t s);
+                     int B, int H, int W, int C, int stride, hipStream_t s);
 // dX[k][b][i][j][c] = sum_{u,v} dcol[k][(b,i-u+1,j-v+1)][(u,v,c)], taps added in (u,v) order,
 // set to zero where mask (same shape as dX, may be null) is not positive.  C % 4 == 0.
 int launch_fold3x3(const float* dcol, int64_t strideCol, int ld, float* dX, const float* mask,
-                   int64_t strideX, int K, int B, int H, int W, int C, hipStream_t s);
+                   int64_t strideX, int K, int B, int H, int W, int C, int stride, hipStream_t s);
 // A first convolution layer with C = 1..3 input channels and a multiple of 32 output channels
 // (first_conv_fits) has kernels of its own that gather the image straight into the MFMA
 // operands.  Forward: out[k][p][o] = b[o] + conv, rectified if `relu`, parameters taken from
@@ -232,18 +234,35 @@ int launch_first_conv_wgrad(const float* X, const float* dout, float* partial, f
 // and beta read from params + k * strideParams at gam_off / bet_off.  `scratch`: 2 * K *
 // bn_chunks(rows, C, K) * C floats.  Backward: launch_bn_backward_partials leaves chunk sums
 // part[k][chunk][0..C) = sum dY Xh and [C..2C) = sum dY (returns the chunk count; launch_bias_grad
-// over them gives dgamma and dbeta); launch_bn_backward_apply then overwrites dY with
-// dZ = gamma stats[1] (dY - dbeta/rows - Xh dgamma/rows), dgamma and dbeta read from
-// grad + k * strideParams at the same offsets.  -1: shape not supported.
+// over them gives dgamma and dbeta); launch_bn_backward_apply then writes
+// dZ = gamma stats[1] (dY - dbeta/rows - Xh dgamma/rows) to `dZ`, which may be dY itself or Z,
+// dgamma and dbeta read from grad + k * strideParams at the same offsets.  -1: shape not supported.
+// Shortcut of a residual block (He et al., CIFAR variant, parameter-free): the block input
+// src [K][B][step H][step W][Cs] (replica stride `stride` floats) enters the block output
+// [B][H][W][C] as src[b][step i][step j][c] for c < Cs and 0 for the channels beyond.  Cs % 4 == 0.
+struct ShortcutDesc {
+  const float* src; int64_t stride;
+  int H, W, Cs, step;
+};
 int bn_chunks(int64_t rows, int C, int K);
+// `shortcut` (may be null): added to the normalised output before the ReLU.
 int launch_bn_forward(const float* Z, float* scratch, float* stats, const float* params,
                       int64_t strideParams, int64_t gam_off, int64_t bet_off, float* out, int K,
-                      int64_t rows, int C, float eps, hipStream_t s);
+                      int64_t rows, int C, float eps, const ShortcutDesc* shortcut, hipStream_t s);
+// dIn (shape of d.src) += the gradient dY [K][rows][C] of the block output, through the shortcut,
+// kept only where mask (shape of dIn, the ReLU output the block read; may be null) is positive.
+int launch_shortcut_backward(const float* dY, float* dIn, const float* mask, const ShortcutDesc& d, int K,
+                             int64_t rows, int C, hipStream_t s);
+// Global average pooling over `images` images [HW][C] into rows of pitch ldp, and its backward
+// pass fused with the ReLU mask of the image (mask may be null).
+int launch_avgpool(const float* A, float* P, int64_t images, int HW, int C, int ldp, hipStream_t s);
+int launch_avgpool_backward(const float* dP, const float* mask, float* dA, int64_t images, int HW, int C,
+                            int ldp, hipStream_t s);
 int launch_bn_backward_partials(const float* Z, const float* dY, const float* stats, float* part, int K,
                                 int64_t rows, int C, hipStream_t s);
-void launch_bn_backward_apply(const float* Z, float* dY, const float* stats, const float* params,
-                              const float* grad, int64_t strideParams, int64_t gam_off, int64_t bet_off,
-                              int K, int64_t rows, int C, hipStream_t s);
+void launch_bn_backward_apply(const float* Z, const float* dY, float* dZ, const float* stats,
+                              const float* params, const float* grad, int64_t strideParams,
+                              int64_t gam_off, int64_t bet_off, int K, int64_t rows, int C, hipStream_t s);
 // Wt[k][c][(u,v,o)] = W[k][o][(2-u,2-v,c)] for K filter banks W [Cout][3][3][Cin] (row pitch ldw,
 // replica stride strideW); Wt is dense, [K][Cin][9 Cout].  Cout must be a multiple of 32.
 void launch_flip_filters(const float* W, int64_t strideW, int ldw, float* Wt, int K, int Cout, int Cin,

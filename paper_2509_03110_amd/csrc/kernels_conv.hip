@@ -17,10 +17,11 @@ constexpr int kThreads = 256;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 struct ImgShape {
-  int H, W, C;     // one image
+  int H, W, C;     // one output image of the convolution (H x W positions), C input channels
   int ld;          // pitch of a col row (floats), multiple of 4, >= 9 C
   long long rows;  // B H W
   long long total; // threads needed
+  int st;          // stride: the input image is [st H][st W][C]
 };
 
 // One thread per 16-byte word of col.  VEC: C % 4 == 0, a word then lies inside one tap.
@@ -38,15 +39,16 @@ __global__ __launch_bounds__(kThreads) void unfold3x3_kernel(const float* __rest
   const int j = (int)(m % sh.W);
   const int i = (int)((m / sh.W) % sh.H);
   const long long b = m / ((long long)sh.W * sh.H);
-  const float* img = X + (long long)k * strideX + b * ((long long)sh.H * sh.W * sh.C);
+  const int Hin = sh.st * sh.H, Win = sh.st * sh.W;
+  const float* img = X + (long long)k * strideX + b * ((long long)Hin * Win * sh.C);
   f32x4 o = {0.f, 0.f, 0.f, 0.f};
   if constexpr (VEC) {
     const int e = 4 * q;
     if (e < 9 * sh.C) {
       const int tap = e / sh.C, c = e - tap * sh.C;
-      const int ii = i + tap / 3 - 1, jj = j + tap % 3 - 1;
-      if (ii >= 0 && ii < sh.H && jj >= 0 && jj < sh.W)
-        o = *reinterpret_cast<const f32x4*>(img + ((long long)ii * sh.W + jj) * sh.C + c);
+      const int ii = sh.st * i + tap / 3 - 1, jj = sh.st * j + tap % 3 - 1;
+      if (ii >= 0 && ii < Hin && jj >= 0 && jj < Win)
+        o = *reinterpret_cast<const f32x4*>(img + ((long long)ii * Win + jj) * sh.C + c);
     }
   } else {
 #pragma unroll
@@ -54,18 +56,19 @@ __global__ __launch_bounds__(kThreads) void unfold3x3_kernel(const float* __rest
       const int e = 4 * q + r;
       if (e < 9 * sh.C) {
         const int tap = e / sh.C, c = e - tap * sh.C;
-        const int ii = i + tap / 3 - 1, jj = j + tap % 3 - 1;
-        if (ii >= 0 && ii < sh.H && jj >= 0 && jj < sh.W)
-          o[r] = img[((long long)ii * sh.W + jj) * sh.C + c];
+        const int ii = sh.st * i + tap / 3 - 1, jj = sh.st * j + tap % 3 - 1;
+        if (ii >= 0 && ii < Hin && jj >= 0 && jj < Win)
+          o[r] = img[((long long)ii * Win + jj) * sh.C + c];
       }
     }
   }
   *reinterpret_cast<f32x4*>(col + (long long)k * strideCol + m * sh.ld + 4 * q) = o;
 }
 
-// Adjoint of the unfold: dX[b,i,j,c] = sum_{u,v} dcol[(b, i-u+1, j-v+1), (u,v,c)], taps in
-// (u, v) order; with a mask, zero where mask <= 0 (the ReLU output the image came from).
-// One thread per 16-byte word of dX; C % 4 == 0.
+// Adjoint of the unfold: dX[b,y,x,c] = sum over the taps (u,v) and output positions (i,j) with
+// st i + u - 1 = y, st j + v - 1 = x of dcol[(b,i,j), (u,v,c)], taps in (u, v) order; with a
+// mask, zero where mask <= 0 (the ReLU output the image came from).
+// One thread per 16-byte word of dX; C % 4 == 0.  sh.rows counts the pixels of dX here.
 __global__ __launch_bounds__(kThreads) void fold3x3_kernel(const float* __restrict__ dcol,
                                                            float* __restrict__ dX,
                                                            const float* __restrict__ mask, ImgShape sh,
@@ -77,16 +80,21 @@ __global__ __launch_bounds__(kThreads) void fold3x3_kernel(const float* __restri
   long long m = idx / words;
   const int k = (int)(m / sh.rows);
   m -= (long long)k * sh.rows;
-  const int j = (int)(m % sh.W);
-  const int i = (int)((m / sh.W) % sh.H);
+  const int Hin = sh.st * sh.H, Win = sh.st * sh.W;
+  const int x = (int)(m % Win);
+  const int y = (int)((m / Win) % Hin);
+  const long long b = m / ((long long)Win * Hin);
   const float* src = dcol + (long long)k * strideCol;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int tap = 0; tap < 9; ++tap) {
-    const int ii = i - (tap / 3 - 1), jj = j - (tap % 3 - 1);
-    if (ii >= 0 && ii < sh.H && jj >= 0 && jj < sh.W) {
-      const long long mm = m + (long long)(ii - i) * sh.W + (jj - j);
-      acc += *reinterpret_cast<const f32x4*>(src + mm * sh.ld + tap * sh.C + c);
+    const int yy = y - (tap / 3 - 1), xx = x - (tap % 3 - 1);     // st i and st j
+    if (yy >= 0 && xx >= 0 && yy % sh.st == 0 && xx % sh.st == 0) {
+      const int ii = yy / sh.st, jj = xx / sh.st;
+      if (ii < sh.H && jj < sh.W) {
+        const long long mm = (b * sh.H + ii) * sh.W + jj;
+        acc += *reinterpret_cast<const f32x4*>(src + mm * sh.ld + tap * sh.C + c);
+      }
     }
   }
   const long long at = (long long)k * strideX + m * sh.C + c;
@@ -549,13 +557,22 @@ __global__ __launch_bounds__(64 * kBnChains) void bn_stats_finish_kernel(
   }
 }
 
-// out = relu(gamma (Z - mean) inv_std + beta).  One thread per 16-byte word.
+// The shortcut of a residual block as the kernels read it: the block input [B][st H][st W][Cs]
+// seen from an output pixel (i, j) and channel c is src[b][st i][st j][c] for c < Cs, 0 beyond.
+struct Shortcut {
+  const float* src;     // null: no shortcut
+  long long stride;     // floats from one replica's block input to the next
+  int H, W, Cs, st;     // output image, channels of the block input, pixel step
+};
+
+// out = relu(gamma (Z - mean) inv_std + beta [+ shortcut]).  One thread per 16-byte word.
 __global__ __launch_bounds__(kThreads) void bn_apply_kernel(const float* __restrict__ Z,
                                                             const float* __restrict__ stats,
                                                             const float* __restrict__ params,
                                                             long long strideParams, long long gam_off,
                                                             long long bet_off, float* __restrict__ out,
-                                                            long long rows, int C, long long total) {
+                                                            long long rows, int C, long long total,
+                                                            Shortcut sc) {
   const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
   if (idx >= total) return;
   const int words = C / 4;
@@ -567,9 +584,80 @@ __global__ __launch_bounds__(kThreads) void bn_apply_kernel(const float* __restr
   const f32x4 be = *reinterpret_cast<const f32x4*>(params + k * strideParams + bet_off + c);
   const f32x4 z = *reinterpret_cast<const f32x4*>(Z + idx * 4);
   f32x4 y = ga * ((z - mu) * inv) + be;
+  if (sc.src != nullptr && c < sc.Cs) {       // Cs % 4 == 0: a word lies inside or outside
+    const long long m = idx / words - (long long)k * rows;       // (b, i, j) of this replica
+    const int j = (int)(m % sc.W), i = (int)((m / sc.W) % sc.H);
+    const long long b = m / ((long long)sc.W * sc.H);
+    const long long at = ((b * (sc.st * sc.H) + sc.st * i) * (sc.st * sc.W) + sc.st * j) * sc.Cs + c;
+    y += *reinterpret_cast<const f32x4*>(sc.src + k * sc.stride + at);
+  }
 #pragma unroll
   for (int r = 0; r < 4; ++r) y[r] = y[r] > 0.f ? y[r] : 0.f;
   *reinterpret_cast<f32x4*>(out + idx * 4) = y;
+}
+
+// The shortcut's share of the block input's gradient: dIn[b][st i][st j][c] += dY[b][i][j][c]
+// for c < Cs (dY: gradient of the block output behind its ReLU), where the block input, itself
+// a ReLU output `mask`, is positive (mask null: no such condition, the input came from a
+// pool).  One thread per 16-byte word of the part of dY that has a counterpart.
+__global__ __launch_bounds__(kThreads) void shortcut_backward_kernel(const float* __restrict__ dY,
+                                                                     float* __restrict__ dIn,
+                                                                     const float* __restrict__ mask,
+                                                                     long long rows, int C, Shortcut sc,
+                                                                     long long total) {
+  const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= total) return;
+  const int words = sc.Cs / 4;
+  const int c = (int)(idx % words) * 4;
+  long long m = idx / words;
+  const int k = (int)(m / rows);
+  m -= (long long)k * rows;
+  const int j = (int)(m % sc.W), i = (int)((m / sc.W) % sc.H);
+  const long long b = m / ((long long)sc.W * sc.H);
+  const long long at = k * sc.stride + ((b * (sc.st * sc.H) + sc.st * i) * (sc.st * sc.W) + sc.st * j) * sc.Cs + c;
+  f32x4 g = *reinterpret_cast<const f32x4*>(dY + ((long long)k * rows + m) * C + c);
+  if (mask != nullptr) {
+    const f32x4 keep = *reinterpret_cast<const f32x4*>(mask + at);
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (!(keep[r] > 0.f)) g[r] = 0.f;
+  }
+  *reinterpret_cast<f32x4*>(dIn + at) += g;
+}
+
+// Global average pooling: P[k][b][c] = mean over the H W positions of A[k][b][.][.][c] (summed
+// in position order), P rows of pitch ldp; and its backward pass fused with the ReLU the image
+// came from: dA[k][b][i][j][c] = dP[k][b][c] / (H W) where A > 0 (mask null: everywhere).
+__global__ __launch_bounds__(kThreads) void avgpool_kernel(const float* __restrict__ A, float* __restrict__ P,
+                                                           long long images, int HW, int C, int ldp) {
+  const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+  const int words = C / 4;
+  if (idx >= images * words) return;
+  const int c = (int)(idx % words) * 4;
+  const long long img = idx / words;
+  const float* a = A + img * (long long)HW * C + c;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int p = 0; p < HW; ++p) acc += *reinterpret_cast<const f32x4*>(a + (long long)p * C);
+  const float inv = 1.f / (float)HW;
+  *reinterpret_cast<f32x4*>(P + img * ldp + c) = acc * inv;
+}
+__global__ __launch_bounds__(kThreads) void avgpool_backward_kernel(const float* __restrict__ dP,
+                                                                    const float* __restrict__ mask,
+                                                                    float* __restrict__ dA, long long images,
+                                                                    int HW, int C, int ldp) {
+  const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+  const int words = C / 4;
+  if (idx >= images * HW * words) return;
+  const int c = (int)(idx % words) * 4;
+  const long long img = idx / words / HW;
+  f32x4 g = *reinterpret_cast<const f32x4*>(dP + img * ldp + c) * (1.f / (float)HW);
+  if (mask != nullptr) {
+    const f32x4 keep = *reinterpret_cast<const f32x4*>(mask + idx * 4);
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (!(keep[r] > 0.f)) g[r] = 0.f;
+  }
+  *reinterpret_cast<f32x4*>(dA + idx * 4) = g;
 }
 
 // Chunk sums for the backward pass: part[k][chunk][0..C) = sum dY Xh, [C..2C) = sum dY, with
@@ -604,9 +692,10 @@ __global__ __launch_bounds__(kThreads) void bn_backward_partial_kernel(const flo
   }
 }
 
-// dZ = gamma inv_std (dY - dbeta / N - Xh dgamma / N), in place over dY.
+// dZ = gamma inv_std (dY - dbeta / N - Xh dgamma / N), written to dZ, which may be dY itself or Z
+// (every thread reads its own word of both before it writes).
 __global__ __launch_bounds__(kThreads) void bn_backward_apply_kernel(
-    const float* __restrict__ Z, float* __restrict__ dY, const float* __restrict__ stats,
+    const float* Z, const float* dY, float* dZ, const float* __restrict__ stats,
     const float* __restrict__ params, const float* __restrict__ grad, long long strideParams,
     long long gam_off, long long bet_off, long long rows, int C, long long total) {
   const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
@@ -622,7 +711,7 @@ __global__ __launch_bounds__(kThreads) void bn_backward_apply_kernel(
   const float inv_n = 1.f / (float)rows;
   const f32x4 xh = (*reinterpret_cast<const f32x4*>(Z + idx * 4) - mu) * inv;
   const f32x4 dy = *reinterpret_cast<const f32x4*>(dY + idx * 4);
-  *reinterpret_cast<f32x4*>(dY + idx * 4) = ga * inv * (dy - dbe * inv_n - xh * (dga * inv_n));
+  *reinterpret_cast<f32x4*>(dZ + idx * 4) = ga * inv * (dy - dbe * inv_n - xh * (dga * inv_n));
 }
 
 unsigned blocks_for(long long total) { return (unsigned)((total + kThreads - 1) / kThreads); }
@@ -630,10 +719,11 @@ unsigned blocks_for(long long total) { return (unsigned)((total + kThreads - 1) 
 }  // namespace
 
 int launch_unfold3x3(const float* X, int64_t strideX, float* col, int64_t strideCol, int ld, int K,
-                     int B, int H, int W, int C, hipStream_t s) {
-  ImgShape sh{H, W, C, ld, (long long)B * H * W, 0};
+                     int B, int H, int W, int C, int stride, hipStream_t s) {
+  ImgShape sh{H, W, C, ld, (long long)B * H * W, 0, stride};
   sh.total = (long long)K * sh.rows * (ld / 4);
-  if (ld % 4 || ld < 9 * C || sh.total <= 0 || sh.total >= (1ll << 31) * kThreads) return -1;
+  if (ld % 4 || ld < 9 * C || sh.total <= 0 || sh.total >= (1ll << 31) * kThreads || stride < 1 || stride > 2)
+    return -1;
   if (C % 4 == 0)
     unfold3x3_kernel<true><<<blocks_for(sh.total), kThreads, 0, s>>>(X, col, sh, strideX, strideCol);
   else
@@ -642,10 +732,11 @@ int launch_unfold3x3(const float* X, int64_t strideX, float* col, int64_t stride
 }
 
 int launch_fold3x3(const float* dcol, int64_t strideCol, int ld, float* dX, const float* mask,
-                   int64_t strideX, int K, int B, int H, int W, int C, hipStream_t s) {
-  ImgShape sh{H, W, C, ld, (long long)B * H * W, 0};
+                   int64_t strideX, int K, int B, int H, int W, int C, int stride, hipStream_t s) {
+  ImgShape sh{H, W, C, ld, (long long)B * H * W * stride * stride, 0, stride};
   sh.total = (long long)K * sh.rows * (C / 4);
-  if (C % 4 || ld < 9 * C || sh.total <= 0 || sh.total >= (1ll << 31) * kThreads) return -1;
+  if (C % 4 || ld < 9 * C || sh.total <= 0 || sh.total >= (1ll << 31) * kThreads || stride < 1 || stride > 2)
+    return -1;
   fold3x3_kernel<<<blocks_for(sh.total), kThreads, 0, s>>>(dcol, dX, mask, sh, strideCol, strideX);
   return 0;
 }
@@ -700,8 +791,15 @@ int bn_chunks(int64_t rows, int C, int K) { return chunk_plan(rows, C, K).chunks
 
 int launch_bn_forward(const float* Z, float* scratch, float* stats, const float* params,
                       int64_t strideParams, int64_t gam_off, int64_t bet_off, float* out, int K,
-                      int64_t rows, int C, float eps, hipStream_t s) {
+                      int64_t rows, int C, float eps, const ShortcutDesc* shortcut, hipStream_t s) {
   if (C % 4 || C < 4 || C > 4 * kThreads || rows < 1) return -1;
+  Shortcut sc{nullptr, 0, 1, 1, 0, 1};
+  if (shortcut != nullptr) {
+    if (shortcut->Cs % 4 || shortcut->Cs > C || shortcut->H < 1 || shortcut->W < 1 ||
+        rows % ((int64_t)shortcut->H * shortcut->W) || shortcut->step < 1 || shortcut->step > 2)
+      return -1;
+    sc = Shortcut{shortcut->src, shortcut->stride, shortcut->H, shortcut->W, shortcut->Cs, shortcut->step};
+  }
   const ChunkPlan pl = chunk_plan(rows, C, K);
   const int chunks = pl.chunks;
   float* pmean = scratch;
@@ -712,7 +810,29 @@ int launch_bn_forward(const float* Z, float* scratch, float* stats, const float*
       pmean, pm2, stats, rows, C, chunks, pl.chunk_rows, eps);
   const long long total = (long long)K * rows * (C / 4);
   bn_apply_kernel<<<blocks_for(total), kThreads, 0, s>>>(Z, stats, params, strideParams, gam_off, bet_off,
-                                                        out, rows, C, total);
+                                                        out, rows, C, total, sc);
+  return 0;
+}
+
+int launch_shortcut_backward(const float* dY, float* dIn, const float* mask, const ShortcutDesc& d, int K,
+                             int64_t rows, int C, hipStream_t s) {
+  if (d.Cs % 4 || d.Cs > C || d.Cs < 4 || rows % ((int64_t)d.H * d.W) || d.step < 1 || d.step > 2) return -1;
+  const Shortcut sc{nullptr, d.stride, d.H, d.W, d.Cs, d.step};
+  const long long total = (long long)K * rows * (d.Cs / 4);
+  shortcut_backward_kernel<<<blocks_for(total), kThreads, 0, s>>>(dY, dIn, mask, rows, C, sc, total);
+  return 0;
+}
+
+int launch_avgpool(const float* A, float* P, int64_t images, int HW, int C, int ldp, hipStream_t s) {
+  if (C % 4 || HW < 1 || ldp < C || ldp % 4) return -1;
+  avgpool_kernel<<<blocks_for(images * (C / 4)), kThreads, 0, s>>>(A, P, images, HW, C, ldp);
+  return 0;
+}
+
+int launch_avgpool_backward(const float* dP, const float* mask, float* dA, int64_t images, int HW, int C,
+                            int ldp, hipStream_t s) {
+  if (C % 4 || HW < 1 || ldp < C || ldp % 4) return -1;
+  avgpool_backward_kernel<<<blocks_for(images * HW * (C / 4)), kThreads, 0, s>>>(dP, mask, dA, images, HW, C, ldp);
   return 0;
 }
 
@@ -725,11 +845,11 @@ int launch_bn_backward_partials(const float* Z, const float* dY, const float* st
   return pl.chunks;
 }
 
-void launch_bn_backward_apply(const float* Z, float* dY, const float* stats, const float* params,
-                              const float* grad, int64_t strideParams, int64_t gam_off, int64_t bet_off,
-                              int K, int64_t rows, int C, hipStream_t s) {
+void launch_bn_backward_apply(const float* Z, const float* dY, float* dZ, const float* stats,
+                              const float* params, const float* grad, int64_t strideParams,
+                              int64_t gam_off, int64_t bet_off, int K, int64_t rows, int C, hipStream_t s) {
   const long long total = (long long)K * rows * (C / 4);
-  bn_backward_apply_kernel<<<blocks_for(total), kThreads, 0, s>>>(Z, dY, stats, params, grad, strideParams,
+  bn_backward_apply_kernel<<<blocks_for(total), kThreads, 0, s>>>(Z, dY, dZ, stats, params, grad, strideParams,
                                                                  gam_off, bet_off, rows, C, total);
 }
 

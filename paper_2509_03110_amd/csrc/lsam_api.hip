@@ -120,7 +120,10 @@ struct Layer {
 
 // One 3x3 convolution layer: image [H][W][Cin] -> [H][W][Cout] (-> [H/2][W/2][Cout] if pooled).
 struct ConvLayer {
-  int H, W, Cin, Cout, pool;
+  int H, W, Cin, Cout, pool;   // H x W: the convolution's output image (before the pool)
+  int stride;          // 1 or 2: the layer reads an image of [stride H][stride W][Cin]
+  bool skip;           // closes a residual block: the input of the layer below is added before the ReLU
+  int skip_C, skip_step;   // channels of that block input; 2 if the block halved the image, else 1
   int64_t rows;        // B H W: rows of the unfolded image and of the layer's output
   int ldc;             // pitch of the unfolded image, 9 Cin rounded up to 8
   // The GEMM kernels can read an unfolded image straight from the image when its channel
@@ -141,6 +144,8 @@ struct Layout {
   int n_conv = 0;              // layers 0..n_conv-1 are convolutions
   std::vector<ConvLayer> conv;
   size_t dcol = 0;             // gradient of an unfolded image (largest layer that needs one)
+  int gap_hw = 0;              // > 0: global average pooling over that many positions feeds the dense layers
+  size_t gap_out = 0, gap_grad = 0;   // [K][B][ld] pooled vector and its gradient
   size_t colsum = 0;           // first-stage column sums of the bias gradients
   bool bf16 = false, raw = false;
   bool bf16_math = false;      // convolutional model with bf16 matrix products on fp32 tensors
@@ -185,15 +190,42 @@ int check_config(const lsam_config* c) {
       return fail(LSAM_EINVAL, "n_conv=%d must leave at least one dense layer of %d", c->n_conv,
                   c->n_layers);
     if (c->n_conv == 0 && c->bn_mask) return fail(LSAM_EINVAL, "bn_mask needs convolution layers");
+    if (c->n_conv == 0 && (c->stride_mask || c->skip_mask || c->global_avg_pool))
+      return fail(LSAM_EINVAL, "stride_mask, skip_mask and global_avg_pool need convolution layers");
     if (c->n_conv > 0) {
       if (c->img_h < 1 || c->img_w < 1) return fail(LSAM_EINVAL, "img_h, img_w must be >= 1");
       if (c->bn_mask >> c->n_conv) return fail(LSAM_EINVAL, "bn_mask names a layer that is no convolution");
       if (c->bn_mask && !(c->bn_eps > 0.f)) return fail(LSAM_EINVAL, "bn_eps must be > 0");
+      if (c->n_conv < 32 && ((c->stride_mask >> c->n_conv) || (c->skip_mask >> c->n_conv)))
+        return fail(LSAM_EINVAL, "stride_mask or skip_mask names a layer that is no convolution");
+      if (c->global_avg_pool != 0 && c->global_avg_pool != 1)
+        return fail(LSAM_EINVAL, "global_avg_pool must be 0 or 1");
       int64_t h = c->img_h, w = c->img_w;
+      int64_t in_h[LSAM_MAX_LAYERS + 1], in_w[LSAM_MAX_LAYERS + 1];   // image each convolution reads
       for (int l = 0; l < c->n_conv; ++l) {
+        in_h[l] = h; in_w[l] = w;
         if (c->dims[l + 1] % 8)
           return fail(LSAM_EINVAL, "dims[%d]=%d: convolution outputs must be multiples of 8", l + 1,
                       c->dims[l + 1]);
+        if ((c->stride_mask >> l) & 1u) {
+          if (h % 2 || w % 2)
+            return fail(LSAM_EINVAL, "convolution %d: stride 2 needs even image sides (%lldx%lld)", l,
+                        (long long)h, (long long)w);
+          h /= 2;
+          w /= 2;
+        }
+        if ((c->skip_mask >> l) & 1u) {
+          if (l < 2) return fail(LSAM_EINVAL, "convolution %d: a residual block needs two convolutions below its closing one", l);
+          if (!((c->bn_mask >> l) & 1u))
+            return fail(LSAM_EINVAL, "convolution %d: the closing convolution of a residual block must be batch-normalised", l);
+          if (((c->pool_mask >> (l - 1)) & 1u) || ((c->pool_mask >> (l - 2)) & 1u))
+            return fail(LSAM_EINVAL, "convolution %d: no pool may sit inside a residual block or in front of it", l);
+          const int64_t sh = in_h[l - 1], sw = in_w[l - 1];
+          if (!((sh == h && sw == w) || (sh == 2 * h && sw == 2 * w)) || c->dims[l - 1] > c->dims[l + 1] ||
+              c->dims[l - 1] % 4)
+            return fail(LSAM_EINVAL, "convolution %d: the block input (%lldx%lldx%d) does not fit the block output (%lldx%lldx%d)",
+                        l, (long long)sh, (long long)sw, c->dims[l - 1], (long long)h, (long long)w, c->dims[l + 1]);
+        }
         // one replica's unfolded image is a GEMM operand addressed with 32-bit byte offsets
         const int64_t widest = std::max<int64_t>(round_up(9 * (int64_t)c->dims[l], 8), c->dims[l + 1]);
         if ((int64_t)c->batch * h * w * widest * 4 >= 0x7FFFFFF0LL)
@@ -206,7 +238,7 @@ int check_config(const lsam_config* c) {
           w /= 2;
         }
       }
-      if (h * w * c->dims[c->n_conv] > (1 << 24))
+      if (!c->global_avg_pool && h * w * c->dims[c->n_conv] > (1 << 24))
         return fail(LSAM_EINVAL, "flattened image too wide for the dense layers");
     }
   }
@@ -261,15 +293,25 @@ void build_layout(const lsam_config& c, Layout& lo) {
         width[l] = c.dims[l];
         if (l < lo.n_conv) {
           ConvLayer cv{};
+          cv.stride = ((c.stride_mask >> l) & 1u) ? 2 : 1;
+          h /= cv.stride; w /= cv.stride;
           cv.H = h; cv.W = w; cv.Cin = c.dims[l]; cv.Cout = c.dims[l + 1];
           cv.pool = (int)((c.pool_mask >> l) & 1u);
+          cv.skip = ((c.skip_mask >> l) & 1u) != 0;
+          if (cv.skip) {
+            // the block input is what convolution l-1 read: [stride_{l-1} H_{l-1}] rows of C_{l-1} channels
+            const ConvLayer& first = lo.conv[l - 1];
+            cv.skip_C = first.Cin;
+            cv.skip_step = first.stride * first.H / h;
+          }
           cv.rows = (int64_t)c.batch * h * w;
           cv.ldc = (int)round_up(9 * (int64_t)cv.Cin, 8);
           lo.conv.push_back(cv);
           width[l] = 9 * cv.Cin;
           if (cv.pool) { h /= 2; w /= 2; }
         } else if (lo.n_conv > 0 && l == lo.n_conv) {
-          width[l] = h * w * c.dims[l];
+          width[l] = c.global_avg_pool ? c.dims[l] : h * w * c.dims[l];
+          lo.gap_hw = c.global_avg_pool ? h * w : 0;
         }
       }
     }
@@ -360,9 +402,10 @@ void build_layout(const lsam_config& c, Layout& lo) {
       ConvLayer& cv = lo.conv[l];
       const size_t full = (size_t)lo.K * cv.rows * cv.Cout * 4;
       const bool small = cv.rows < (1 << 24);      // pixel indices exact in fp32
-      cv.direct_in = small && cv.Cin % 32 == 0;
-      cv.direct_dx = small && l > 0 && cv.Cout % 32 == 0;
-      cv.first = l == 0 && first_conv_fits(cv.Cin, cv.Cout, cv.rows);
+      // the kernels that unfold on the fly, and the first layer's own, know stride 1 only
+      cv.direct_in = small && cv.Cin % 32 == 0 && cv.stride == 1;
+      cv.direct_dx = small && l > 0 && cv.Cout % 32 == 0 && cv.stride == 1;
+      cv.first = l == 0 && cv.stride == 1 && first_conv_fits(cv.Cin, cv.Cout, cv.rows);
       if (cv.first)
         cv.first_partial = take(cur, (size_t)lo.K * first_conv_chunks(cv.rows) * cv.Cout * 32 * 4);
       else if (!cv.direct_in) cv.col = take(cur, (size_t)lo.K * cv.rows * cv.ldc * 4);
@@ -395,6 +438,12 @@ void build_layout(const lsam_config& c, Layout& lo) {
       const ConvLayer& cv = lo.conv[lo.n_conv - 1];
       lo.act[lo.n_conv] = cv.pool ? cv.pooled : cv.out;
       lo.dz[lo.n_conv] = cv.pool ? cv.dpooled : cv.dout;
+      if (lo.gap_hw) {
+        lo.gap_out = take(cur, rows * lo.ld[lo.n_conv] * 4);
+        lo.gap_grad = take(cur, rows * lo.ld[lo.n_conv] * 4);
+        lo.act[lo.n_conv] = lo.gap_out;
+        lo.dz[lo.n_conv] = lo.gap_grad;
+      }
     }
     for (int l = lo.n_conv + 1; l < lo.L; ++l) lo.act[l] = take(cur, act_bytes(l));
     for (int l = lo.n_conv + 1; l <= lo.L; ++l) lo.dz[l] = take(cur, act_bytes(l));
@@ -562,8 +611,8 @@ int conv_forward(lsam_ctx* c, const float* X, const float* params) {
         return fail(LSAM_EINVAL, "first convolution rejected");
     } else if (!cv.direct_in) {
       LaunchTimer t(c, KC_UNFOLD);
-      if (launch_unfold3x3(in, cv.rows * cv.Cin, col, cv.rows * cv.ldc, cv.ldc, lo.K, lo.B, cv.H,
-                           cv.W, cv.Cin, s) != 0)
+      if (launch_unfold3x3(in, cv.rows * cv.stride * cv.stride * cv.Cin, col, cv.rows * cv.ldc, cv.ldc,
+                           lo.K, lo.B, cv.H, cv.W, cv.Cin, cv.stride, s) != 0)
         return fail(LSAM_EINVAL, "unfold of convolution %d rejected", l);
     }
     if (!cv.first) {
@@ -584,9 +633,16 @@ int conv_forward(lsam_ctx* c, const float* X, const float* params) {
     }
     if (cv.bn) {
       LaunchTimer t(c, KC_BATCHNORM);
+      ShortcutDesc sc{};
+      if (cv.skip) {
+        // the block input: what convolution l-1 read, i.e. the ReLU output of convolution l-2
+        sc.src = c->at<float>(lo.conv[l - 2].out);
+        sc.stride = lo.conv[l - 2].rows * cv.skip_C;
+        sc.H = cv.H; sc.W = cv.W; sc.Cs = cv.skip_C; sc.step = cv.skip_step;
+      }
       if (launch_bn_forward(c->at<float>(cv.z), c->at<float>(lo.colsum), c->at<float>(cv.stats), params,
                             lo.d_pad, ly.gam_off, ly.bet_off, c->at<float>(cv.out), lo.K, cv.rows,
-                            cv.Cout, c->cfg.bn_eps, s) != 0)
+                            cv.Cout, c->cfg.bn_eps, cv.skip ? &sc : nullptr, s) != 0)
         return fail(LSAM_EINVAL, "batch normalisation of convolution %d rejected", l);
     }
     in = c->at<float>(cv.out);
@@ -596,6 +652,13 @@ int conv_forward(lsam_ctx* c, const float* X, const float* params) {
         return fail(LSAM_EINVAL, "pool of convolution %d rejected", l);
       in = c->at<float>(cv.pooled);
     }
+  }
+  if (lo.gap_hw) {
+    LaunchTimer t(c, KC_POOL);
+    const ConvLayer& cv = lo.conv[lo.n_conv - 1];
+    if (launch_avgpool(in, c->at<float>(lo.gap_out), (int64_t)lo.K * lo.B, lo.gap_hw, cv.Cout,
+                       lo.ld[lo.n_conv], s) != 0)
+      return fail(LSAM_EINVAL, "global average pooling rejected");
   }
   return LSAM_OK;
 }
@@ -607,6 +670,16 @@ int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq,
   const Layout& lo = c->lo;
   hipStream_t s = c->stream;
   float* g = c->at<float>(lo.g);
+  if (lo.gap_hw) {
+    // the pooled vector's gradient goes back to every position, through the ReLU the image came
+    // from unless a pool sits in between (whose backward pass applies that mask)
+    LaunchTimer t(c, KC_POOL);
+    const ConvLayer& cv = lo.conv[lo.n_conv - 1];
+    if (launch_avgpool_backward(c->at<float>(lo.gap_grad), cv.pool ? nullptr : c->at<float>(cv.out),
+                                c->at<float>(cv.pool ? cv.dpooled : cv.dout), (int64_t)lo.K * lo.B,
+                                lo.gap_hw, cv.Cout, lo.ld[lo.n_conv], s) != 0)
+      return fail(LSAM_EINVAL, "global average pooling (backward) rejected");
+  }
   for (int l = lo.n_conv - 1; l >= 0; --l) {
     const ConvLayer& cv = lo.conv[l];
     const Layer& ly = lo.layers[l];
@@ -642,8 +715,12 @@ int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq,
                                 cv.Cout, ssq ? ssq + *slots : nullptr, lo.nblk, s);
         if (ssq) *slots += used;
       }
-      launch_bn_backward_apply(c->at<float>(cv.z), dout, c->at<float>(cv.stats), params, g, lo.d_pad,
+      // A block's closing convolution keeps dY: it is also the gradient of the shortcut, added
+      // to the block input's gradient further down.  Its dZ goes where Z was (Z is not needed again).
+      float* dz = cv.skip ? c->at<float>(cv.z) : dout;
+      launch_bn_backward_apply(c->at<float>(cv.z), dout, dz, c->at<float>(cv.stats), params, g, lo.d_pad,
                                ly.gam_off, ly.bet_off, lo.K, cv.rows, cv.Cout, s);
+      dout = dz;
     }
     if (cv.first) {
       LaunchTimer t(c, KC_CONV_FIRST);
@@ -732,9 +809,21 @@ int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq,
       LaunchTimer t(c, KC_UNFOLD);
       if (launch_fold3x3(dcol, cv.rows * cv.ldc, cv.ldc,
                          c->at<float>(below.pool ? below.dpooled : below.dout),
-                         below.pool ? nullptr : c->at<float>(below.out), cv.rows * cv.Cin, lo.K, lo.B,
-                         cv.H, cv.W, cv.Cin, s) != 0)
+                         below.pool ? nullptr : c->at<float>(below.out),
+                         cv.rows * cv.stride * cv.stride * cv.Cin, lo.K, lo.B, cv.H, cv.W, cv.Cin,
+                         cv.stride, s) != 0)
         return fail(LSAM_EINVAL, "fold of convolution %d rejected", l);
+    }
+    if (l + 1 < lo.n_conv && lo.conv[l + 1].skip) {
+      // this convolution opened a residual block: the gradient of the block output (kept by the
+      // closing convolution) also reaches the block input through the shortcut
+      const ConvLayer& top = lo.conv[l + 1];
+      const ConvLayer& below = lo.conv[l - 1];
+      const ShortcutDesc sc{nullptr, below.rows * top.skip_C, top.H, top.W, top.skip_C, top.skip_step};
+      LaunchTimer t(c, KC_POOL);
+      if (launch_shortcut_backward(c->at<float>(top.dout), c->at<float>(below.dout), c->at<float>(below.out),
+                                   sc, lo.K, top.rows, top.Cout, s) != 0)
+        return fail(LSAM_EINVAL, "shortcut of the block closed by convolution %d rejected", l + 1);
     }
   }
   return LSAM_OK;

@@ -1005,3 +1005,81 @@ def test_checkpoint_mid_period_resumes_in_a_new_context(mode):
     assert np.array_equal(c.lsam_get_counters(), a.lsam_get_counters())
     a.close()
     c.close()
+
+
+# ---- residual networks: stride-2 convolutions, parameter-free shortcuts, global average pooling -----
+RES_SMALL = workloads.Workload("res_small", K=2, dims=(3, 8, 8, 8, 5), batch=6, n_conv=3, img_h=8,
+                               img_w=8, bn_mask=0b111, skip_mask=0b100, global_avg_pool=1, rho=0.05,
+                               lr=0.05, tau=(2, 3), n_classes=5, data_seed=51)
+
+
+@pytest.mark.parametrize("name,over", [
+    ("a stem and one block on the same shape", {}),
+    ("a block that halves the image and doubles the channels, then one on the new shape", dict(
+        dims=(3, 8, 16, 16, 16, 16, 5), n_conv=5, bn_mask=0b11111, stride_mask=0b00010, skip_mask=0b10100)),
+    ("stride without shortcut or normalisation, flattened image into the dense layers", dict(
+        dims=(3, 8, 16, 12, 5), n_conv=2, bn_mask=0, stride_mask=0b10, skip_mask=0, global_avg_pool=0)),
+    ("a shortcut that only widens, image sides that are no powers of two, two dense layers", dict(
+        dims=(4, 8, 8, 24, 12, 5), n_conv=3, img_h=6, img_w=10)),
+    ("blocks on 32- and 64-channel images (unfolding inside the GEMM), first-layer kernels", dict(
+        dims=(3, 32, 32, 32, 64, 64, 10), n_conv=5, bn_mask=0b11111, stride_mask=0b01000,
+        skip_mask=0b10100, n_classes=10, batch=4)),
+    ("stride on the first convolution, a pool after the block", dict(
+        dims=(3, 8, 8, 8, 5), stride_mask=0b001, pool_mask=0b100, img_h=16, img_w=8)),
+    ("three stages of one block each, ResNet-20's shape in small", dict(
+        dims=(3, 16, 16, 16, 32, 32, 64, 64, 10), n_conv=7, bn_mask=0b1111111, stride_mask=0b0101000,
+        skip_mask=0b1010100, img_h=16, img_w=16, n_classes=10, batch=4, K=3, tau=(2, 3, 4))),
+])
+def test_residual_model_matches_oracle(name, over):
+    w = RES_SMALL.scaled(**over)
+    worst = run_mlp(w, 6, 1e-4, 1e-3, anchor_after=2)
+    print("residual %s: worst parameter error %.3e" % (name, worst))
+
+
+def test_residual_model_gradients_layer_by_layer():
+    """One step of a two-stage residual model from the common start: every layer's dW, db,
+    dgamma and dbeta of the pass at the perturbed point against the oracle's."""
+    w = RES_SMALL.scaled(dims=(3, 8, 16, 16, 16, 16, 5), n_conv=5, bn_mask=0b11111, stride_mask=0b00010,
+                         skip_mask=0b10100, batch=16)
+    g, o = make_pair(w)
+    X, lab = workloads.batch(w, 0)
+    Xd, ld = to_dev(X, lab, w)
+    loss_d = torch.zeros(w.K, device=DEV)
+    g.lsam_step(Xd, ld, loss_d)
+    ol = o.step(X, lab)
+    assert np.allclose(loss_d.cpu().numpy(), ol, rtol=1e-5)
+    assert np.allclose(g.lsam_get_norms(), o.last_norm, rtol=1e-3)
+    for i in range(w.K):
+        g2 = g.lsam_get_buffer(lsam.BUF_GRAD, i)
+        for l, (o0, o1, o2) in enumerate(o.model.offsets):
+            close_enough(g2[o0:o1], o.last_g2[i][o0:o1], 2e-3, "dW%d of replica %d" % (l + 1, i))
+            if l in o.model.bn_offsets:
+                b0, b1, b2 = o.model.bn_offsets[l]
+                close_enough(g2[b0:b1], o.last_g2[i][b0:b1], 2e-3, "dgamma%d of replica %d" % (l + 1, i))
+                close_enough(g2[b1:b2], o.last_g2[i][b1:b2], 2e-3, "dbeta%d of replica %d" % (l + 1, i))
+            else:
+                close_enough(g2[o1:o2], o.last_g2[i][o1:o2], 2e-3, "db%d of replica %d" % (l + 1, i))
+    g.close()
+
+
+def test_residual_model_with_bf16_products_and_the_comparators():
+    w = RES_SMALL.scaled(dims=(3, 8, 16, 16, 16, 16, 5), n_conv=5, bn_mask=0b11111, stride_mask=0b00010,
+                         skip_mask=0b10100)
+    # velocities see each rounding-boundary difference of a bf16 operand undamped: the looser bound
+    # of the other bf16 runs
+    run_mlp(w.scaled(gemm_dtype=1, batch=16), 5, 2e-2, 2e-2, anchor_after=1, tol_flip=1e-1)
+    run_mlp(w.scaled(algorithm=lsam.ALG_DATA_PARALLEL), 4, 1e-4, 1e-3, anchor_after=1)
+    run_mlp(w.scaled(noise_scale=1e-3, noise_seed=11), 4, 1e-4, 1e-3, anchor_after=1)
+
+
+def test_residual_configurations_that_cannot_run_are_rejected():
+    for over, msg in ((dict(skip_mask=0b010), "two convolutions below"),
+                      (dict(bn_mask=0b011), "must be batch-normalised"),
+                      (dict(pool_mask=0b010), "no pool"),
+                      (dict(stride_mask=0b110), "does not fit"),
+                      (dict(dims=(3, 16, 8, 8, 5)), "does not fit"),
+                      (dict(stride_mask=0b1000), "no convolution"),
+                      (dict(img_h=6, img_w=6, stride_mask=0b011), "even image sides")):
+        cfg, keep = lsam.config_from_workload(RES_SMALL.scaled(**over))
+        assert lsam.lsam_workspace_bytes(cfg) == 0, over
+        assert msg in lsam.last_error(), (over, lsam.last_error())

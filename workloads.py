@@ -146,6 +146,17 @@ WORKLOADS = {
                       bn_mask=(1 << 13) - 1, rho=0.1, lr=0.2, tau=(16, 16, 16, 16), steps=20,
                       data_seed=8, n_classes=10, batch_pool=2),
 }
+# ResNet-20 as the paper trains it on CIFAR-10 (Experiments: ResNet-20, 4 workers, batch 128,
+# learning rate 0.2, rho 0.1, communication interval 16), in the CIFAR form of He et al.: a 3x3
+# stem of 16 channels, three stages of three basic blocks (two batch-normalised 3x3 convolutions
+# each) with 16, 32 and 64 channels, the first convolution of stages two and three with stride 2,
+# parameter-free shortcuts, global average pooling and one dense layer (twenty weight layers,
+# 0.27 M parameters).
+WORKLOADS["resnet20"] = Workload(
+    "resnet20", K=4, dims=(3, 16) + (16,) * 6 + (32,) * 6 + (64,) * 6 + (10,), batch=128, n_conv=19,
+    img_h=32, img_w=32, bn_mask=(1 << 19) - 1, stride_mask=(1 << 7) | (1 << 13),
+    skip_mask=sum(1 << l for l in range(2, 19, 2)), global_avg_pool=1, rho=0.1, lr=0.2,
+    tau=(16, 16, 16, 16), steps=20, data_seed=10, n_classes=10, batch_pool=2)
 # the same model with bf16 matrix products (tensors stay fp32; see the boundary's gemm_dtype)
 WORKLOADS["vgg16bf"] = replace(WORKLOADS["vgg16"], name="vgg16bf", gemm_dtype=1)
 

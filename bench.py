@@ -77,6 +77,8 @@ def layer_rows(w):
     rows, h, wd = [], w.img_h, w.img_w
     for l in range(len(w.dims) - 1):
         if l < w.n_conv:
+            if (w.stride_mask >> l) & 1:
+                h, wd = h // 2, wd // 2
             rows.append(w.batch * h * wd)
             if (w.pool_mask >> l) & 1:
                 h, wd = h // 2, wd // 2
@@ -93,11 +95,12 @@ def conv_modes(w):
     out = []
     for l in range(w.n_conv):
         cin, cout = w.dims[l], w.dims[l + 1]
-        if l == 0 and cin <= 3 and cout % 32 == 0 and cout <= 256:
+        strided = (w.stride_mask >> l) & 1            # stride 2: always through a stored unfold
+        if l == 0 and cin <= 3 and cout % 32 == 0 and cout <= 256 and not strided:
             mode = "first"
         else:
-            mode = "direct" if cin % 32 == 0 else "stored"
-        out.append((mode, l > 0 and cout % 32 != 0))
+            mode = "direct" if cin % 32 == 0 and not strided else "stored"
+        out.append((mode, l > 0 and (cout % 32 != 0 or strided)))
     return out
 
 
@@ -138,10 +141,15 @@ def conv_bytes(w):
     modes = conv_modes(w) if w.n_conv else []
     for l in range(w.n_conv):
         cin, cout = w.dims[l], w.dims[l + 1]
+        st2 = 4 if (w.stride_mask >> l) & 1 else 1    # pixels of the image read per output pixel
         if modes[l][0] == "stored":
-            unfold += rows[l] * (cin + 9 * cin) * 4.0
+            unfold += rows[l] * (st2 * cin + 9 * cin) * 4.0
         if modes[l][1]:
-            unfold += rows[l] * (9 * cin + cin) * 4.0
+            unfold += rows[l] * (9 * cin + st2 * cin) * 4.0
+        if (w.skip_mask >> l) & 1:
+            # shortcut: read with the normalisation (forward); backward reads dY, the mask and the
+            # block input's gradient and writes the latter
+            pool += rows[l] * w.dims[l - 1] * 4.0 * (1 + 4)
         if (w.pool_mask >> l) & 1:
             pool += rows[l] * cout * 4.0 * (1.25 + 2.25)
         if (w.bn_mask >> l) & 1:
@@ -210,7 +218,7 @@ def cpu_baseline(w, budget_s=20.0):
     with threadpool_limits(limits=1):
         if w.dims:
             # one replica; shrink the batch for the two largest workloads
-            frac = {"cfg5": 8, "cfg3": 2, "vgg16": 16, "vgg16bf": 16}.get(w.name, 1)
+            frac = {"cfg5": 8, "cfg3": 2, "vgg16": 16, "vgg16bf": 16, "resnet20": 4}.get(w.name, 1)
             ws = w.scaled(K=1, batch=max(w.batch // frac, 1), tau=(10 ** 6,))
             o = oracle_from(ws, workloads.init_params(ws))
             X, lab = workloads.batch(ws, 0)

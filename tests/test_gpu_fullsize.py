@@ -241,3 +241,64 @@ def test_vgg16_reduced_batch_against_oracle_and_full_batch_properties(name, tol)
     assert eng.lsam_sync() == 4
     assert eng.lsam_get_schedule() == ([2, 2, 2, 2], [0, 0, 0, 0], 1)
     eng.close()
+
+
+def _bn_away_from_zero(w, init):
+    """Every normalised layer gets gamma = 0.25 and beta = +1.5 (even channels) or -1.5 (odd
+    channels): normalised values lie within about four standard deviations, so a channel is
+    either positive everywhere (its ReLU passes everything; shortcuts only add non-negative
+    values to it) or negative everywhere (dead, and the shortcut into it comes from a dead
+    channel as well), and almost no ReLU decision is taken near zero."""
+    init = init.copy()
+    model = oracle_from(w.scaled(K=1, tau=(1,)), init).model
+    for l, (b0, b1, b2) in model.bn_offsets.items():
+        init[b0:b1] = 0.25
+        init[b1:b2] = np.where(np.arange(b1 - b0) % 2 == 0, 1.5, -1.5)
+    return init
+
+
+@pytest.mark.parametrize("natural", [False, True])
+def test_resnet20_full_size_one_step_against_the_oracle(natural):
+    # ResNet-20 at the paper's shape (4 workers, batch 128, 32x32x3 images, 19 batch-normalised
+    # convolutions in 9 residual blocks, global average pooling).  The GPU steps all four
+    # replicas; the oracle, at 18 s per replica, follows the last one (replicas are independent
+    # until the first center update).
+    # natural = False: normalisation parameters that keep the ReLU decisions away from zero.
+    # Then the gradient of the pass at the perturbed point must agree layer by layer to 2e-3
+    # (measured: 1e-6 in the first two stages, up to 6e-4 in the third, whose sums run over
+    # 8192 positions only) and the parameters after the step to 1e-6.
+    # natural = True: the workload's own initialisation.  Each of the 19 layers takes 0.5 to
+    # 2 million ReLU decisions per pass on values the normalisation has centred at zero; those
+    # within fp32 rounding of zero fall differently in float64, and each one moves one of the
+    # B H W terms of a weight-gradient row, so the gradients agree to a few percent only
+    # (measured 1e-2 at the top to 3e-2 at the stem) while loss and norm agree to 1e-5 / 1e-3.
+    w = workloads.WORKLOADS["resnet20"]
+    init = workloads.init_params(w)
+    if not natural:
+        init = _bn_away_from_zero(w, init)
+    cfg, keep = lsam.config_from_workload(w)
+    eng = lsam.Lsam(cfg, init, device=DEV, keep=keep)
+    loss = torch.zeros(w.K, dtype=torch.float32, device=DEV)
+    X, lab = workloads.batch(w, 0)
+    eng.lsam_step(torch.from_numpy(X).to(DEV), torch.from_numpy(lab).to(DEV), loss)
+    gl, norms = loss.cpu().numpy(), eng.lsam_get_norms()
+    i = w.K - 1
+    ora = oracle_from(w.scaled(K=1, tau=(w.tau[i],)), init)
+    ol = ora.step(X[i:i + 1], lab[i:i + 1])
+    tol_g, tol_x = (1e-1, 2e-3) if natural else (2e-3, 1e-6)
+    assert abs(gl[i] - ol[0]) <= 1e-5 * abs(ol[0])
+    assert abs(norms[i] - ora.last_norm[0]) <= 1e-3 * ora.last_norm[0]
+    g2 = eng.lsam_get_buffer(lsam.BUF_GRAD, i)
+    worst = 0.0
+    for l, (o0, o1, o2) in enumerate(ora.model.offsets):
+        worst = max(worst, close_enough(g2[o0:o1], ora.last_g2[0][o0:o1], tol_g, "dW%d" % (l + 1)))
+        if l in ora.model.bn_offsets:
+            b0, b1, b2 = ora.model.bn_offsets[l]
+            close_enough(g2[b0:b1], ora.last_g2[0][b0:b1], tol_g, "dgamma%d" % (l + 1))
+            close_enough(g2[b1:b2], ora.last_g2[0][b1:b2], tol_g, "dbeta%d" % (l + 1))
+        else:
+            close_enough(g2[o1:o2], ora.last_g2[0][o1:o2], tol_g, "db%d" % (l + 1))
+    ex = close_enough(eng.lsam_get_params(i), ora.get_params(0), tol_x, "x after one step")
+    print("resnet20 full size, natural=%s: worst weight-gradient error %.2e, parameters %.2e" % (natural, worst, ex))
+    assert eng.lsam_sync() == 0
+    eng.close()

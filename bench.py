@@ -32,29 +32,33 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "c607415c9c3d3b32"
+TRAFFIC_SOURCES = "dc6fe7f589e4d611"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43579616,
-             "gemm_dx": 42146133, "gemm_fwd": 62123040, "perturb": 201945344},
-    "cfg3": {"bias_grad": 13681920, "center": 1773571840, "descent": 17232323925, "gemm_dw":
-             445895622, "gemm_dx": 250125371, "gemm_fwd": 233099093, "perturb": 5065986347,
-             "softmax_ce": 1429163},
-    "cfg4": {"center": 3200044032, "descent": 25600045952, "perturb": 9600050731,
-             "sumsq_partials": 3415772139},
-    "cfg5": {"bias_grad": 118065312, "descent": 188960032021, "gemm_dw": 4959211998, "gemm_dx":
-             2332894030, "gemm_fwd": 2034535115, "perturb": 59024471637, "softmax_ce": 95421264},
-    "cnn5": {"bias_grad": 17357404, "conv_first": 80455925, "descent": 79476736, "gemm_dw":
-             67383392, "gemm_dx": 34806101, "gemm_fwd": 38355546, "perturb": 29813760, "pool":
-             68580985},
-    "cnn5bn": {"batchnorm": 157818916, "bias_grad": 565845, "conv_first": 80454208, "descent":
-             79542272, "gemm_dw": 67409596, "gemm_dx": 34806101, "gemm_fwd": 38355593, "perturb":
-             29838336, "pool": 68580729},
-    "vgg16": {"batchnorm": 175721739, "bias_grad": 1094747, "conv_first": 155190027, "descent":
-             1952545877, "gemm_dw": 140545010, "gemm_dx": 16980139, "gemm_fwd": 138108989,
-             "perturb": 732214741, "pool": 89622327},
-    "vgg16bf": {"batchnorm": 175688327, "bias_grad": 1014282, "conv_first": 155200544, "descent":
-             1952546261, "gemm_dw": 129612735, "gemm_dx": 12106752, "gemm_fwd": 135395507,
-             "perturb": 732214827, "pool": 89622409, "softmax_ce": 114005},
+    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43604829,
+             "gemm_dx": 42146133, "gemm_fwd": 62123008, "perturb": 201945771},
+    "cfg3": {"bias_grad": 13682027, "center": 1773570816, "descent": 883866, "gemm_dw_ascend":
+             667498257, "gemm_dw_norm": 30883556, "gemm_dw_step": 3165084860, "gemm_dx":
+             250126400, "gemm_fwd": 233870669, "softmax_ce": 1428821},
+    "cfg4": {"center": 3200044672, "descent": 25600046037, "perturb": 9600050859,
+             "sumsq_partials": 3416298229},
+    "cfg5": {"bias_grad": 118025778, "descent": 3481527, "gemm_dw_ascend": 7042551333,
+             "gemm_dw_norm": 1333559570, "gemm_dw_step": 28891494345, "gemm_dx": 2333172907,
+             "gemm_fwd": 2034185839, "softmax_ce": 95815579},
+    "cnn5": {"bias_grad": 17357404, "conv_first": 80448981, "descent": 79476736, "gemm_dw":
+             67379730, "gemm_dx": 34806101, "gemm_fwd": 38356749, "perturb": 29813760, "pool":
+             68582500},
+    "cnn5bn": {"batchnorm": 157832220, "bias_grad": 565845, "conv_first": 80450528, "descent":
+             79542272, "gemm_dw": 67383520, "gemm_dx": 34806101, "gemm_fwd": 38355482, "perturb":
+             29838336, "pool": 68582265},
+    "resnet20": {"batchnorm": 86672327, "descent": 34871296, "gemm_dw": 212855069, "gemm_dx":
+             269489085, "gemm_fwd": 100370211, "perturb": 13086720, "pool": 64190801,
+             "unfold_fold": 328636392},
+    "vgg16": {"batchnorm": 175735471, "bias_grad": 1094784, "conv_first": 155184192, "descent":
+             1952546048, "gemm_dw": 140515626, "gemm_dx": 16980139, "gemm_fwd": 137906665,
+             "perturb": 732214869, "pool": 89623913},
+    "vgg16bf": {"batchnorm": 175702069, "bias_grad": 1014282, "conv_first": 155193632, "descent":
+             1952546005, "gemm_dw": 129611248, "gemm_dx": 12106752, "gemm_fwd": 135410792,
+             "perturb": 732214784, "pool": 89623930, "softmax_ce": 114005},
 }
 
 

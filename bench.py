@@ -130,7 +130,13 @@ def gemm_flops(w, fused_step=False):
         # the weight-gradient product is formed three times per step: for the norm, for the
         # perturbed operand copy, and at the perturbed point for the sampler step
         one = out.pop("gemm_dw") / 2
-        out["gemm_dw_norm"] = out["gemm_dw_ascend"] = out["gemm_dw_step"] = one
+        out["gemm_dw_ascend"] = out["gemm_dw_step"] = one
+        # the norm of the first-pass weight gradients: from the Gram matrices of a layer's two
+        # factors, 2 B^2 (out + in) flops each, where the library takes that route (when it is at
+        # most half of the product's 2 B out in), else from a product whose result is only summed
+        B = w.batch
+        out["gemm_dw_norm"] = K * sum(2.0 * B * B * (a + b) if 2 * B * (a + b) <= a * b else 2.0 * B * a * b
+                                      for a, b in w.layer_shapes)
     return out
 
 

@@ -52,6 +52,10 @@ __device__ __forceinline__ float ascent_point(float x, float scale, float g) {
 // g: [K] rows of `n` floats with row stride `g_stride`; partials: [K, nblk] doubles.
 void launch_sumsq_partials(const float* g, int64_t g_stride, int64_t n, int K, double* partials,
                            int nblk, hipStream_t s);
+// Inner product of K pairs of matrices G1, G2 (each `n` floats, replica stride `stride`, both
+// multiples of 4, 16-byte aligned): partials[k * pstride + j] for j < the returned count (<= 64).
+int launch_gram_dot(const float* G1, const float* G2, int64_t stride, int64_t n, int K, double* partials,
+                    int64_t pstride, hipStream_t s);
 // Pass 2: norms[k] = sqrt(sum_{b<nblk} partials[k * partials_stride + b]); scale[k] = rho / (norm + gamma).
 // If loss_rows != nullptr also reduces loss_rows [K,B] to loss_out[k] = mean (both passes of
 // the tree are fixed-order, so the result is run-to-run deterministic).

@@ -120,6 +120,40 @@ __global__ __launch_bounds__(kThreads) void sumsq_partials_kernel(
   if (threadIdx.x == 0) partials[(int64_t)k * nblk + blockIdx.x] = s;
 }
 
+// ---- gradient norm of a dense layer's weight gradient from two Gram matrices ---------------------
+// ||dZ^T A||_F^2 = sum_{b,b'} (dZ dZ^T)[b,b'] (A A^T)[b,b']: the squared norm of the weight
+// gradient dW = dZ^T A [out x in] of a layer with batch B is the inner product of the two B x B
+// Gram matrices of its factors, which take 2 B^2 (out + in) flops instead of 2 B out in.  This
+// kernel is the inner product: partial sums in the fixed order of sumsq_partials_kernel.
+__global__ __launch_bounds__(kThreads) void gram_dot_partials_kernel(
+    const float* __restrict__ G1, const float* __restrict__ G2, int64_t stride, int64_t nv,
+    double* __restrict__ partials, int64_t pstride, int nblk) {
+  const int k = blockIdx.y;
+  const int64_t chunk = (nv + nblk - 1) / nblk;
+  const int64_t beg = (int64_t)blockIdx.x * chunk;
+  const int64_t end = beg + chunk < nv ? beg + chunk : nv;
+  const float* a = G1 + (int64_t)k * stride;
+  const float* b = G2 + (int64_t)k * stride;
+  float a0 = 0.f, a1 = 0.f;
+  int64_t i = beg + threadIdx.x;
+  for (; i + kThreads < end; i += 2 * kThreads) {
+    const auto u0 = ldc<4>(a + i * 4), w0 = ldc<4>(b + i * 4);
+    const auto u1 = ldc<4>(a + (i + kThreads) * 4), w1 = ldc<4>(b + (i + kThreads) * 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      a0 += u0[e] * w0[e];
+      a1 += u1[e] * w1[e];
+    }
+  }
+  for (; i < end; i += kThreads) {
+    const auto u0 = ldc<4>(a + i * 4), w0 = ldc<4>(b + i * 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) a0 += u0[e] * w0[e];
+  }
+  const double s = block_sum((double)a0 + (double)a1);
+  if (threadIdx.x == 0) partials[(int64_t)k * pstride + blockIdx.x] = s;
+}
+
 // ---- gradient norm, pass 2 (+ mean loss) ----------------------------------------------------
 __global__ __launch_bounds__(kThreads) void norm_finish_kernel(
     const double* __restrict__ partials, int nblk, int64_t pstride, float rho, float gamma,
@@ -385,6 +419,16 @@ void launch_sumsq_partials(const float* g, int64_t g_stride, int64_t n, int K, d
   } else {
     sumsq_partials_kernel<1><<<grid, kThreads, 0, s>>>(g, g_stride, n, partials, nblk);
   }
+}
+
+int launch_gram_dot(const float* G1, const float* G2, int64_t stride, int64_t n, int K, double* partials,
+                    int64_t pstride, hipStream_t s) {
+  // n and stride are multiples of 4 (rows padded to 8 floats), the matrices 16-byte aligned
+  const int64_t nv = n / 4;
+  int64_t nb = (nv + 4 * kThreads - 1) / (4 * kThreads);
+  const int nblk = (int)(nb < 1 ? 1 : (nb > 64 ? 64 : nb));
+  gram_dot_partials_kernel<<<dim3(nblk, K), kThreads, 0, s>>>(G1, G2, stride, nv, partials, pstride, nblk);
+  return nblk;
 }
 
 void launch_norm_finish(const double* partials, int nblk, int64_t partials_stride, int K, float rho,

@@ -144,6 +144,8 @@ struct Layout {
   int n_conv = 0;              // layers 0..n_conv-1 are convolutions
   std::vector<ConvLayer> conv;
   size_t dcol = 0;             // gradient of an unfolded image (largest layer that needs one)
+  size_t gram1 = 0, gram2 = 0; // bf16 dense model: Gram matrices [K][B][ldg] of a layer's dZ and of its input
+  int ldg = 0;
   int gap_hw = 0;              // > 0: global average pooling over that many positions feeds the dense layers
   size_t gap_out = 0, gap_grad = 0;   // [K][B][ld] pooled vector and its gradient
   size_t colsum = 0;           // first-stage column sums of the bias gradients
@@ -474,6 +476,11 @@ void build_layout(const lsam_config& c, Layout& lo) {
     }
     lo.splitk_bytes = need;
     if (need) lo.splitk = take(cur, need);
+    if (lo.bf16) {
+      lo.ldg = (int)round_up(lo.B, 8);
+      lo.gram1 = take(cur, (size_t)lo.K * lo.B * lo.ldg * 4);
+      lo.gram2 = take(cur, (size_t)lo.K * lo.B * lo.ldg * 4);
+    }
   }
   lo.total = cur;
 }
@@ -937,6 +944,29 @@ int forward_backward(lsam_ctx* c, const void* X, const int32_t* labels, const vo
       split(c, d);
       if (ssq) { d.sumsq = ssq + slots; d.sumsq_stride = lo.nblk; }
       d.sumsq_only = (ssq && norm_only) ? 1 : 0;   // the gradient itself is recomputed by ascend_pass
+      // Of a gradient that is not stored only the norm is wanted, and ||dZ^T A||_F^2 is the inner
+      // product of the B x B Gram matrices dZ dZ^T and A A^T: 2 B^2 (out + in) flops instead of
+      // 2 B out in.  Taken when that is at most half the work.
+      if (d.sumsq_only && 2 * (int64_t)B * (ly.out + ly.in) <= (int64_t)ly.out * ly.in) {
+        LaunchTimer t(c, KC_GEMM_DW_NORM);
+        for (int which = 0; which < 2; ++which) {
+          GemmDesc q{};
+          q.b32s = 1;
+          q.A = q.B = which == 0 ? (const void*)dz : act;
+          q.strideA = q.strideB = which == 0 ? astride(l + 1) : astride(l);
+          q.ldA = q.ldB = which == 0 ? ld_dz : lo.ld[l];
+          q.a_kmajor = q.b_kmajor = 1;
+          q.cbA = q.cbB = b32s_blocks(which == 0 ? ly.out : ly.in);
+          q.C = c->at<float>(which == 0 ? lo.gram1 : lo.gram2);
+          q.strideC = (int64_t)B * lo.ldg; q.ldC = lo.ldg;
+          q.M = q.N = B; q.Kd = which == 0 ? ly.out : ly.in; q.batch = K;
+          q.in_bf16 = 1; q.out_bf16 = 0; q.epilogue = EPI_PLAIN;
+          if (launch_gemm(q, s) != 0) return fail(LSAM_EINVAL, "Gram GEMM of layer %d rejected", l);
+        }
+        slots += launch_gram_dot(c->at<float>(lo.gram1), c->at<float>(lo.gram2), (int64_t)B * lo.ldg,
+                                 (int64_t)B * lo.ldg, K, ssq + slots, lo.nblk, s);
+        return LSAM_OK;
+      }
       SamplerFusion f;
       if (fuse) {
         // this layer's share of the sampler step happens in the epilogue: W_l of x, v, S, y

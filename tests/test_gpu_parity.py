@@ -363,10 +363,15 @@ def test_bf16_reduced_shapes_free_running_twenty_steps(name, width, B):
     ((352, 288, 288, 160), 160, 2, (2, 3), 1),         # ragged 128x128 tiles
     ((512, 512, 520, 24), 256, 2, (2, 2), 1)])         # 256x128 tiles with a ragged last column tile
 def test_fused_sampler_step_equals_the_separate_kernel(dims, B, K, tau, nesterov):
-    """The sampler step taken inside the weight-gradient epilogues against the same step as a
-    kernel of its own (which the other bf16 tests hold to the oracle): identical arithmetic on
-    identical values, so parameters, velocities, iterate sums, the center and the bf16 operand
-    copy must agree bit for bit after several steps and center updates."""
+    """The fused path (norm of the first-pass weight gradients from Gram matrices or from a
+    norm-only product, ascent in the epilogue of the recomputed products, sampler step in the
+    epilogues of the second pass) against the same step with every gradient stored and the
+    streaming kernels run on it (which the other bf16 tests hold to the oracle).  Where the
+    two sum the squares of the same values in another order the norm may differ in its last
+    bits; everything else is the same arithmetic on the same values.  So: norms equal to 2e-6,
+    the bf16 operand copy of x~ equal except for a few elements on a rounding boundary (one
+    bf16 step apart), parameters, velocities, iterate sums and the center equal to 2e-6 after
+    several steps and center updates."""
     w = workloads.WORKLOADS["cfg3"].scaled(name="fuse", K=K, dims=dims, batch=B, tau=tau,
                                            nesterov=nesterov, n_classes=dims[-1], batch_pool=0)
     init = workloads.init_params(w)
@@ -379,12 +384,17 @@ def test_fused_sampler_step_equals_the_separate_kernel(dims, B, K, tau, nesterov
         Xd, ld = to_dev(X, lab, w)
         a.lsam_step(Xd, ld, None)
         b.lsam_step(Xd, ld, None)
+        assert np.allclose(a.lsam_get_norms(), b.lsam_get_norms(), rtol=2e-6, atol=0)
         assert a.lsam_sync() == b.lsam_sync()
         for i in list(range(K)) + [-1]:
-            assert np.array_equal(a.lsam_get_params(i), b.lsam_get_params(i)), (t, i)
+            assert rel_max(a.lsam_get_params(i), b.lsam_get_params(i)) < 2e-6, (t, i)
         for i in range(K):
-            for which in (lsam.BUF_VELOCITY, lsam.BUF_ITER_SUM, lsam.BUF_PERTURBED):
-                assert np.array_equal(a.lsam_get_buffer(which, i), b.lsam_get_buffer(which, i)), (t, i, which)
+            for which in (lsam.BUF_VELOCITY, lsam.BUF_ITER_SUM):
+                assert rel_max(a.lsam_get_buffer(which, i), b.lsam_get_buffer(which, i)) < 2e-6, (t, i, which)
+            pa, pb = a.lsam_get_buffer(lsam.BUF_PERTURBED, i), b.lsam_get_buffer(lsam.BUF_PERTURBED, i)
+            differ = pa != pb
+            assert np.mean(differ) < 1e-3, (t, i, np.mean(differ))
+            assert np.all(np.abs(pa - pb)[differ] <= 2.0 ** -7 * np.abs(pb)[differ]), (t, i)
     a.close()
     b.close()
 

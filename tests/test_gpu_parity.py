@@ -585,11 +585,21 @@ def test_maximum_replica_count_raw_mode():
     g.close()
 
 
-def test_maximum_depth_mlp():
-    dims = (24,) + (16,) * 15 + (5,)               # LSAM_MAX_LAYERS = 16 dense layers
+@pytest.mark.parametrize("bf16", [0, 1])
+def test_maximum_depth_mlp(bf16):
+    dims = (24,) + (16,) * 23 + (5,)               # LSAM_MAX_LAYERS = 24 dense layers
     w = workloads.WORKLOADS["cfg1"].scaled(name="deep", K=2, dims=dims, batch=6, tau=(2, 3),
-                                           n_classes=5, steps=4, data_seed=4)
-    run_mlp(w, w.steps, 1e-4, 1e-3, margin=True)
+                                           n_classes=5, steps=4, data_seed=4, gemm_dtype=bf16)
+    if bf16:
+        # (the fused path with every table of per-layer offsets full; Langevin noise as well, which
+        # takes the unfused kernels and the largest argument block)
+        run_mlp(w, w.steps, 2e-2, 2e-2, margin=True)
+        run_mlp(w.scaled(noise_scale=1e-4, noise_seed=3), w.steps, 2e-2, 2e-2, margin=True)
+    else:
+        run_mlp(w, w.steps, 1e-4, 1e-3, margin=True)
+        run_mlp(w.scaled(noise_scale=1e-4, noise_seed=3), w.steps, 1e-4, 1e-3, margin=True)
+    cfg, keep = lsam.config_from_workload(w.scaled(dims=dims[:-1] + (16, 5)))
+    assert lsam.lsam_workspace_bytes(cfg) == 0 and "n_layers" in lsam.last_error()
 
 
 def test_zero_gradients_leave_only_the_coupling():

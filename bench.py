@@ -76,96 +76,63 @@ def kernel_sources_digest():
     return h.hexdigest()[:16]
 
 
-def layer_rows(w):
-    """Rows of the GEMMs of each layer: B for a dense layer, B * H * W for a convolution."""
-    rows, h, wd = [], w.img_h, w.img_w
-    for l in range(len(w.dims) - 1):
-        if l < w.n_conv:
-            if (w.stride_mask >> l) & 1:
-                h, wd = h // 2, wd // 2
-            rows.append(w.batch * h * wd)
-            if (w.pool_mask >> l) & 1:
-                h, wd = h // 2, wd // 2
-        else:
-            rows.append(w.batch)
-    return rows
+def layer_table(eng, w):
+    """What the library reports about each layer (`lsam_layer_info`): which kernels serve it, the
+    rows of its matrix products, whether its gradients are stored."""
+    return [eng.lsam_layer_info(l) for l in range(len(w.dims) - 1)]
 
 
-def conv_modes(w):
-    """Per convolution layer, which kernels serve it (the library's own rules, restated):
-    'first' = the first-layer kernels (1..3 input channels, 32 | C_out <= 256), 'direct' = the
-    GEMM reads the unfolded image from the image (32 | C_in), 'stored' = unfold + GEMM; and
-    whether its dX needs a stored unfolded gradient (not 32 | C_out)."""
-    out = []
-    for l in range(w.n_conv):
-        cin, cout = w.dims[l], w.dims[l + 1]
-        strided = (w.stride_mask >> l) & 1            # stride 2: always through a stored unfold
-        if l == 0 and cin <= 3 and cout % 32 == 0 and cout <= 256 and not strided:
-            mode = "first"
-        else:
-            mode = "direct" if cin % 32 == 0 and not strided else "stored"
-        out.append((mode, l > 0 and (cout % 32 != 0 or strided)))
-    return out
-
-
-def gemm_flops(w, fused_step=False):
+def gemm_flops(w, layers):
     """Per all-replica step (both passes): flops of the forward, dX and dW GEMM classes and of
-    the first convolution layer's own kernels.  With the sampler step fused into the second
-    pass's weight-gradient kernels, that pass's dW flops belong to the class gemm_dw_step."""
+    the first convolution layer's own kernels.  On the fused path (bf16 dense model) the
+    weight-gradient product is formed for the perturbed operand copy and, at the perturbed
+    point, for the sampler step; the norm of the first-pass gradient comes from the Gram
+    matrices of the product's factors, 2 B^2 (out + in) flops, or from a product whose result
+    is only summed."""
+    from paper_2509_03110_amd import lsam
     K = w.K
-    shapes, rows = list(w.layer_shapes), layer_rows(w)
-    fi, fo = shapes[-1]
-    if w.gemm_dtype == 0 and fo <= 16 and fi <= 1024 and w.batch <= 512:
-        shapes.pop()   # a narrow fp32 classifier head runs as two fused non-MFMA kernels ("head")
-    per = [r * a * b for r, (a, b) in zip(rows, shapes)]
-    first = 0.0
-    if w.n_conv and conv_modes(w)[0][0] == "first":
-        first, per[0] = per[0], 0.0
-    sw = sum(per)
-    sw_dx = sum(per[1:])
-    out = {"gemm_fwd": 2 * 2.0 * sw * K, "gemm_dw": 2 * 2.0 * sw * K, "gemm_dx": 2 * 2.0 * sw_dx * K}
+    per = [float(rows) * fi * fo if kind not in (lsam.LAYER_HEAD, lsam.LAYER_CONV_FIRST) else 0.0
+           for kind, _, _, rows, fi, fo in layers]
+    first = sum(float(rows) * fi * fo for kind, _, _, rows, fi, fo in layers if kind == lsam.LAYER_CONV_FIRST)
+    sw, sw_dx = sum(per), sum(per[1:])
+    out = {"gemm_fwd": 2 * 2.0 * sw * K, "gemm_dx": 2 * 2.0 * sw_dx * K}
     if first:
         out["conv_first"] = 2 * 2 * 2.0 * first * K      # forward and weight gradient
-    if fused_step:
-        # the weight-gradient product is formed three times per step: for the norm, for the
-        # perturbed operand copy, and at the perturbed point for the sampler step
-        one = out.pop("gemm_dw") / 2
-        out["gemm_dw_ascend"] = out["gemm_dw_step"] = one
-        # the norm of the first-pass weight gradients: from the Gram matrices of a layer's two
-        # factors, 2 B^2 (out + in) flops each, where the library takes that route (when it is at
-        # most half of the product's 2 B out in), else from a product whose result is only summed
-        B = w.batch
-        out["gemm_dw_norm"] = K * sum(2.0 * B * B * (a + b) if 2 * B * (a + b) <= a * b else 2.0 * B * a * b
-                                      for a, b in w.layer_shapes)
+    if any(route for _, _, route, _, _, _ in layers):
+        out["gemm_dw_ascend"] = out["gemm_dw_step"] = 2.0 * sw * K
+        out["gemm_dw_norm"] = K * sum(2.0 * rows * rows * (fi + fo) if route == 2 else 2.0 * rows * fi * fo
+                                      for _, _, route, rows, fi, fo in layers)
+    else:
+        out["gemm_dw"] = 2 * 2.0 * sw * K
     return out
 
 
-def conv_bytes(w):
+def conv_bytes(w, layers):
     """Algorithmic bytes per all-replica step (both passes) of the kernels around the
     convolution GEMMs: where an unfolded image is stored it is written once (plus the image
     read), where its gradient is stored that is read once (plus the image gradient written);
     the pool reads its input and writes a quarter of it, its backward pass reads both and
     writes the full-size gradient."""
+    from paper_2509_03110_amd import lsam
     unfold = pool = bn = 0.0
-    rows = layer_rows(w)
-    modes = conv_modes(w) if w.n_conv else []
     for l in range(w.n_conv):
+        kind, dx_stored, _, rows, _, _ = layers[l]
         cin, cout = w.dims[l], w.dims[l + 1]
         st2 = 4 if (w.stride_mask >> l) & 1 else 1    # pixels of the image read per output pixel
-        if modes[l][0] == "stored":
-            unfold += rows[l] * (st2 * cin + 9 * cin) * 4.0
-        if modes[l][1]:
-            unfold += rows[l] * (9 * cin + st2 * cin) * 4.0
+        if kind == lsam.LAYER_CONV_STORED:
+            unfold += rows * (st2 * cin + 9 * cin) * 4.0
+        if dx_stored:
+            unfold += rows * (9 * cin + st2 * cin) * 4.0
         if (w.skip_mask >> l) & 1:
             # shortcut: read with the normalisation (forward); backward reads dY, the mask and the
             # block input's gradient and writes the latter
-            pool += rows[l] * w.dims[l - 1] * 4.0 * (1 + 4)
+            pool += rows * w.dims[l - 1] * 4.0 * (1 + 4)
         if (w.pool_mask >> l) & 1:
-            pool += rows[l] * cout * 4.0 * (1.25 + 2.25)
+            pool += rows * cout * 4.0 * (1.25 + 2.25)
         if (w.bn_mask >> l) & 1:
             # statistics read Z; normalise+ReLU reads Z, writes the activation; the backward
             # sums read Z and dY; the backward apply reads Z and dY and writes dZ
-            bn += rows[l] * cout * 4.0 * (1 + 2 + 2 + 3)
+            bn += rows * cout * 4.0 * (1 + 2 + 2 + 3)
     out = {}
     if bn:
         out["batchnorm"] = 2 * bn * w.K
@@ -321,10 +288,11 @@ def run_workload(w, steps, warmup, kernel_timing=True):
             one(i)
         stats = eng.lsam_timing_read()
         eng.lsam_timing_enable(False)
-        fused_step = bool(w.dims) and eng.lsam_set_fused_step(True) == 1 and w.rho != 0.0
-        flops = gemm_flops(w, fused_step) if w.dims else {}
+        layers = layer_table(eng, w) if w.dims else []
+        fused_step = any(route for _, _, route, _, _, _ in layers)
+        flops = gemm_flops(w, layers) if w.dims else {}
         nbytes = stream_bytes(w, fused_step)
-        nbytes.update(conv_bytes(w))
+        nbytes.update(conv_bytes(w, layers))
         # center update: 8 B/param per due replica (S read, S cleared) + 16 B/param (y and
         # g'_prev read and written), summed over the ticks of this run that had a sync
         first = warmup + steps

@@ -225,6 +225,26 @@ int lsam_get_schedule(lsam_ctx* ctx, int32_t* tau_out, int32_t* count_out, int64
  * do), or a negative error. */
 int lsam_set_fused_step(lsam_ctx* ctx, int32_t on);
 
+/* Which kernels serve layer `layer` (0-based) of this context, for reports that attribute time
+ * and work to kernel classes without restating the library's choices.  `info` [host] gets
+ * LSAM_LAYER_INFO_FIELDS (6) values, `n` its capacity:
+ *   [0] LSAM_LAYER_DENSE (GEMM kernels), LSAM_LAYER_HEAD (the two fused kernels of a narrow fp32
+ *       classifier head), LSAM_LAYER_CONV_FIRST (first-layer convolution kernels),
+ *       LSAM_LAYER_CONV_DIRECT (GEMM that unfolds the image on the fly), LSAM_LAYER_CONV_STORED
+ *       (stored unfolded image + GEMM)
+ *   [1] 1 if its input gradient goes through a stored unfolded gradient (convolutions)
+ *   [2] 0: both weight gradients are stored; 1: fused path, norm from a weight-gradient product
+ *       whose result is only summed; 2: fused path, norm from the Gram matrices of its factors
+ *   [3] rows of its matrix products (B, or B H W of the layer's output for a convolution)
+ *   [4], [5] columns of its weight matrix (fan-in) and its outputs */
+#define LSAM_LAYER_INFO_FIELDS 6
+#define LSAM_LAYER_DENSE 0
+#define LSAM_LAYER_HEAD 1
+#define LSAM_LAYER_CONV_FIRST 2
+#define LSAM_LAYER_CONV_DIRECT 3
+#define LSAM_LAYER_CONV_STORED 4
+int lsam_layer_info(lsam_ctx* ctx, int32_t layer, int32_t* info, int32_t n);
+
 /* Tells the context that a HIP graph holding one captured lsam_step (or lsam_step_grads) has
  * been replayed once: the local counts c_i and the step number advance as they do in an eager
  * step, with no GPU work, so that an eager lsam_sync after the replay finds the replicas that

@@ -836,6 +836,18 @@ int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq,
   return LSAM_OK;
 }
 
+// Whether the narrow-classifier-head kernels serve the last layer (fp32 dense arithmetic only).
+bool head_is_fused(const Layout& lo) {
+  return !lo.raw && !lo.bf16 && !lo.bf16_math &&
+         head_fits(lo.B, lo.layers[lo.L - 1].out, lo.layers[lo.L - 1].in);
+}
+
+// Whether the norm of a layer's unsaved first-pass weight gradient comes from the Gram matrices
+// of its factors: when they take at most half the flops of the product itself.
+bool gram_norm_pays(int B, int out, int in) {
+  return 2 * (int64_t)B * (out + in) <= (int64_t)out * in;
+}
+
 // forward + backward of all replicas; weights taken from `wts` (fp32 or bf16 per mode).
 // `second` selects the pass at the perturbed point: its biases are x_b + scale * g1_b, which in
 // fp32 mode sit in the perturbed copy and in bf16 mode are formed in the GEMM epilogue from
@@ -868,7 +880,7 @@ int forward_backward(lsam_ctx* c, const void* X, const int32_t* labels, const vo
 
   // A narrow fp32 classifier head is not run as GEMMs: two fused kernels cover its forward
   // pass, the loss, dZ, dX, dW and db.
-  const bool head = !bf && !lo.bf16_math && head_fits(B, lo.layers[L - 1].out, lo.layers[L - 1].in);
+  const bool head = head_is_fused(lo);
   for (int l = l0; l < (head ? L - 1 : L); ++l) {
     const Layer& ly = lo.layers[l];
     const bool last = l == L - 1;
@@ -947,7 +959,7 @@ int forward_backward(lsam_ctx* c, const void* X, const int32_t* labels, const vo
       // Of a gradient that is not stored only the norm is wanted, and ||dZ^T A||_F^2 is the inner
       // product of the B x B Gram matrices dZ dZ^T and A A^T: 2 B^2 (out + in) flops instead of
       // 2 B out in.  Taken when that is at most half the work.
-      if (d.sumsq_only && 2 * (int64_t)B * (ly.out + ly.in) <= (int64_t)ly.out * ly.in) {
+      if (d.sumsq_only && gram_norm_pays(B, ly.out, ly.in)) {
         LaunchTimer t(c, KC_GEMM_DW_NORM);
         for (int which = 0; which < 2; ++which) {
           GemmDesc q{};
@@ -1559,6 +1571,33 @@ int lsam_get_schedule(lsam_ctx* c, int32_t* tau_out, int32_t* count_out, int64_t
     if (count_out) count_out[i] = c->sched.count()[i];
   }
   if (t_y_out) *t_y_out = c->sched.t_y();
+  return LSAM_OK;
+}
+
+int lsam_layer_info(lsam_ctx* c, int32_t layer, int32_t* info, int32_t n) {
+  if (!c || !info) return fail(LSAM_EINVAL, "ctx or info is NULL");
+  const Layout& lo = c->lo;
+  if (lo.raw) return fail(LSAM_ESTATE, "raw-vector mode has no layers");
+  if (layer < 0 || layer >= lo.L) return fail(LSAM_EINVAL, "layer %d out of range 0..%d", layer, lo.L - 1);
+  if (n < LSAM_LAYER_INFO_FIELDS) return fail(LSAM_EINVAL, "info needs %d entries", LSAM_LAYER_INFO_FIELDS);
+  const Layer& ly = lo.layers[layer];
+  int kind = LSAM_LAYER_DENSE, dx_stored = 0;
+  int64_t rows = lo.B;
+  if (layer < lo.n_conv) {
+    const ConvLayer& cv = lo.conv[layer];
+    kind = cv.first ? LSAM_LAYER_CONV_FIRST : cv.direct_in ? LSAM_LAYER_CONV_DIRECT : LSAM_LAYER_CONV_STORED;
+    dx_stored = (layer > 0 && !cv.direct_dx) ? 1 : 0;
+    rows = cv.rows;
+  } else if (layer == lo.L - 1 && head_is_fused(lo)) {
+    kind = LSAM_LAYER_HEAD;
+  }
+  const bool fused = c->rho != 0.f && can_fuse_step(c);
+  info[0] = kind;
+  info[1] = dx_stored;
+  info[2] = fused ? (gram_norm_pays(lo.B, ly.out, ly.in) ? 2 : 1) : 0;
+  info[3] = (int32_t)rows;
+  info[4] = ly.in;
+  info[5] = ly.out;
   return LSAM_OK;
 }
 

@@ -20,6 +20,7 @@ GEMM_FP32, GEMM_BF16 = 0, 1
 SCHED_FIXED, SCHED_REDRAW = 0, 1
 ALG_LSAM, ALG_DATA_PARALLEL = 0, 1
 STATIC_MAX_D = 1 << 34
+LAYER_DENSE, LAYER_HEAD, LAYER_CONV_FIRST, LAYER_CONV_DIRECT, LAYER_CONV_STORED = range(5)
 BUF_PARAMS, BUF_VELOCITY, BUF_ITER_SUM, BUF_GRAD, BUF_PERTURBED, BUF_CENTER_DIR = range(6)
 
 EXPORTS = [
@@ -27,7 +28,7 @@ EXPORTS = [
     "lsam_get_params", "lsam_get_buffer", "lsam_set_buffer", "lsam_get_norms", "lsam_get_schedule",
     "lsam_set_scalars", "lsam_num_params", "lsam_schedule_replay", "lsam_timing_enable",
     "lsam_timing_read", "lsam_probe_peaks", "lsam_destroy", "lsam_last_error",
-    "lsam_get_counters", "lsam_set_counters", "lsam_get_activation", "lsam_step_grads_static", "lsam_note_replay", "lsam_set_fused_step",
+    "lsam_get_counters", "lsam_set_counters", "lsam_get_activation", "lsam_step_grads_static", "lsam_note_replay", "lsam_set_fused_step", "lsam_layer_info",
 ]
 
 
@@ -96,6 +97,8 @@ def lib():
         L.lsam_get_schedule.argtypes = [vp, vp, vp, vp]
         L.lsam_set_scalars.restype = C.c_int
         L.lsam_set_scalars.argtypes = [vp, C.c_float, C.c_float]
+        L.lsam_layer_info.restype = C.c_int
+        L.lsam_layer_info.argtypes = [vp, i32, vp, i32]
         L.lsam_set_fused_step.restype = C.c_int
         L.lsam_set_fused_step.argtypes = [vp, i32]
         L.lsam_note_replay.restype = C.c_int
@@ -286,6 +289,12 @@ class Lsam:
         ty = C.c_int64(0)
         _check(lib().lsam_get_schedule(self._h, tau.ctypes.data, cnt.ctypes.data, C.byref(ty)))
         return tau.tolist(), cnt.tolist(), ty.value
+
+    def lsam_layer_info(self, layer):
+        """(kind, dx_stored, norm_route, rows, fan_in, out) of layer `layer`; see include/lsam.h."""
+        out = np.zeros(6, dtype=np.int32)
+        _check(lib().lsam_layer_info(self._h, layer, out.ctypes.data, out.size))
+        return tuple(int(v) for v in out)
 
     def lsam_set_fused_step(self, on):
         return _check(lib().lsam_set_fused_step(self._h, 1 if on else 0))

@@ -1103,3 +1103,29 @@ def test_residual_configurations_that_cannot_run_are_rejected():
         cfg, keep = lsam.config_from_workload(RES_SMALL.scaled(**over))
         assert lsam.lsam_workspace_bytes(cfg) == 0, over
         assert msg in lsam.last_error(), (over, lsam.last_error())
+
+
+def test_layer_info_reports_which_kernels_serve_a_layer():
+    def table(w):
+        cfg, keep = lsam.config_from_workload(w)
+        eng = lsam.Lsam(cfg, workloads.init_params(w), device=DEV, keep=keep)
+        out = [eng.lsam_layer_info(l) for l in range(len(w.dims) - 1)]
+        with pytest.raises(lsam.LsamError):
+            eng.lsam_layer_info(len(w.dims) - 1)
+        eng.close()
+        return out
+    # fp32 MLP with a narrow head: GEMM layers, then the fused head kernels; gradients stored
+    t = table(workloads.WORKLOADS["cfg1"])
+    assert [r[0] for r in t] == [lsam.LAYER_DENSE, lsam.LAYER_HEAD] and all(r[2] == 0 for r in t)
+    assert t[0][3:] == (32, 784, 128)
+    # bf16 MLP: fused path; the Gram route only where 2 B (out + in) <= out in
+    w = workloads.WORKLOADS["cfg3"].scaled(K=2, dims=(384, 256, 256, 40), batch=32, tau=(2, 3), n_classes=40)
+    assert [r[2] for r in table(w)] == [2, 2, 1] and [r[2] for r in table(w.scaled(rho=0.0))] == [0, 0, 0]
+    # convolutions: first-layer kernels, unfolding inside the GEMM, stored unfold (24 channels);
+    # the input gradient of the 24-output layer goes through a stored unfolded gradient
+    w = workloads.Workload("kinds", K=2, dims=(3, 32, 32, 24, 40, 10), batch=8, n_conv=4, img_h=8,
+                           img_w=8, pool_mask=0b0110, tau=(2, 2), n_classes=10, data_seed=41)
+    t = table(w)
+    assert [r[0] for r in t] == [lsam.LAYER_CONV_FIRST, lsam.LAYER_CONV_DIRECT, lsam.LAYER_CONV_DIRECT,
+                                 lsam.LAYER_CONV_STORED, lsam.LAYER_HEAD]
+    assert [r[1] for r in t[:4]] == [0, 0, 1, 1] and [r[3] for r in t] == [512, 512, 128, 32, 8]

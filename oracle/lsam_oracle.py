@@ -230,7 +230,11 @@ class Cnn:
     convolutions l-1 and l: the block's input, i.e. the image convolution l-1 read, is added
     to the (normalised) output of convolution l before its ReLU.  Where the two differ in shape
     the shortcut is that paper's parameter-free one: every second pixel of the block input in
-    both directions, channels padded with zeros.  global_avg_pool: the dense layers read the
+    both directions, channels padded with zeros.  Bit l of proj_mask (with bit l of skip_mask)
+    replaces that shortcut by that paper's projection: a 1x1 convolution of the block input with
+    the block's stride, C_{l-1} -> C_{l+1} channels, with bias and its own batch normalisation
+    (no ReLU); its parameters W_p [C_{l+1}, C_{l-1}], b_p, gamma_p, beta_p follow those of
+    convolution l in the flat vector.  global_avg_pool: the dense layers read the
     mean of the last image over its positions, one value per channel.
 
       Z[b,i,j,o] = b[o] + sum_{u,v,c} Xpad[b,s i+u,s j+v,c] W[o,u,v,c]     (Xpad: X with a zero rim, s: stride)
@@ -238,9 +242,12 @@ class Cnn:
     The pool's gradient goes to the first maximal element of each window in (u, v) order."""
 
     def __init__(self, dims, n_conv, img_h, img_w, pool_mask, bn_mask=0, bn_eps=1e-5, gemm_dtype=0,
-                 stride_mask=0, skip_mask=0, global_avg_pool=0):
+                 stride_mask=0, skip_mask=0, global_avg_pool=0, proj_mask=0):
         self.bn_mask, self.bn_eps = int(bn_mask), float(bn_eps)
         self.stride_mask, self.skip_mask = int(stride_mask), int(skip_mask)
+        self.proj_mask = int(proj_mask)
+        if self.proj_mask & ~self.skip_mask:
+            raise ValueError("a projection belongs to a shortcut")
         self.gap = int(global_avg_pool)
         if self.skip_mask & 0b11:
             raise ValueError("a block needs two convolutions below its closing one")
@@ -258,6 +265,7 @@ class Cnn:
                                                        self.pool_mask, self.stride_mask, self.gap)
         self.offsets = []
         self.bn_offsets = {}        # layer -> (start of gamma, start of beta, end)
+        self.proj_offsets = {}      # layer -> (start of W_p, of b_p, of gamma_p, of beta_p, end)
         off = 0
         for l, (fi, fo) in enumerate(self.shapes):
             self.offsets.append((off, off + fo * fi, off + fo * fi + fo))
@@ -265,6 +273,11 @@ class Cnn:
             if l < self.n_conv and (self.bn_mask >> l) & 1:
                 self.bn_offsets[l] = (off, off + fo, off + 2 * fo)
                 off += 2 * fo
+            if l < self.n_conv and (self.proj_mask >> l) & 1:
+                cs = self.dims[l - 1]
+                self.proj_offsets[l] = (off, off + fo * cs, off + fo * cs + fo, off + fo * cs + 2 * fo,
+                                        off + fo * cs + 3 * fo)
+                off += fo * cs + 3 * fo
         self.d = off
         self.last_margin = np.inf
 
@@ -298,6 +311,7 @@ class Cnn:
         X = np.asarray(X, dtype=np.float64)
         q = self.q
         bn_saved = {}
+        proj_saved = {}
         B = X.shape[0]
         self.last_margin = np.inf
         # ---- forward ----
@@ -325,7 +339,19 @@ class Cnn:
                 Xh = (Z - mu) * inv
                 bn_saved[l] = (Xh, inv)
                 Z = x[g0:g1] * Xh + x[g1:g2]
-            if (self.skip_mask >> l) & 1:
+            if l in self.proj_offsets:
+                p0, p1, p2, p3, p4 = self.proj_offsets[l]
+                S = conv_src[l - 1]
+                if S.shape[1] != h:
+                    S = S[:, ::2, ::2, :]
+                Wp = x[p0:p1].reshape(cout, S.shape[3])
+                Zp = q(S) @ q(Wp).T + x[p1:p2]
+                mup = Zp.mean(axis=(0, 1, 2))
+                invp = 1.0 / np.sqrt(((Zp - mup) ** 2).mean(axis=(0, 1, 2)) + self.bn_eps)
+                Xhp = (Zp - mup) * invp
+                proj_saved[l] = (S, Xhp, invp)
+                Z = Z + x[p2:p3] * Xhp + x[p3:p4]
+            elif (self.skip_mask >> l) & 1:
                 Z = Z + self._shortcut(conv_src[l - 1], Z.shape)
             self.last_margin = min(self.last_margin, float(np.min(np.abs(Z))))
             R = np.maximum(Z, 0.0)
@@ -393,8 +419,29 @@ class Cnn:
             else:
                 dR = dA.reshape(B, h, w, cout)
             dZc = dR * (R > 0.0)
-            if (self.skip_mask >> l) & 1:
-                skip_grad[l - 1] = dZc            # the sum's gradient reaches both of its terms
+            if l in self.proj_offsets:
+                # through the projection's normalisation and 1x1 convolution, back to the block input
+                p0, p1, p2, p3, p4 = self.proj_offsets[l]
+                S, Xhp, invp = proj_saved[l]
+                n = B * h * w
+                dbp = dZc.sum(axis=(0, 1, 2))
+                dgp = (dZc * Xhp).sum(axis=(0, 1, 2))
+                grad[p2:p3] = dgp
+                grad[p3:p4] = dbp
+                dZp = x[p2:p3] * invp * (dZc - dbp / n - Xhp * dgp / n)
+                Wp = x[p0:p1].reshape(cout, S.shape[3])
+                flatp = dZp.reshape(-1, cout)
+                grad[p0:p1] = (q(flatp).T @ q(S.reshape(-1, S.shape[3]))).ravel()
+                grad[p1:p2] = flatp.sum(axis=0)
+                dS = q(dZp) @ q(Wp)
+                full = np.zeros(conv_src[l - 1].shape)
+                if full.shape[1] != h:
+                    full[:, ::2, ::2, :] = dS
+                else:
+                    full[...] = dS
+                skip_grad[l - 1] = ("full", full)
+            elif (self.skip_mask >> l) & 1:
+                skip_grad[l - 1] = ("out", dZc)   # the sum's gradient reaches both of its terms
             if l in self.bn_offsets:
                 g0, g1, g2 = self.bn_offsets[l]
                 Xh, inv = bn_saved[l]
@@ -419,7 +466,8 @@ class Cnn:
             grad[o1:o2] = flat.sum(axis=0)
             dA = dAp[:, 1:hin + 1, 1:win + 1, :]
             if l in skip_grad:
-                dA = dA + self._shortcut_adjoint(skip_grad.pop(l), dA.shape)
+                kind, gsk = skip_grad.pop(l)
+                dA = dA + (gsk if kind == "full" else self._shortcut_adjoint(gsk, dA.shape))
         return loss, grad
 
 
@@ -431,7 +479,8 @@ class Cnn:
 # xi comes from the counter-based generator Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel
 # random numbers: as easy as 1, 2, 3", SC'11), so that any element of any step can be produced
 # on its own.  One call yields the four normals of four neighbouring columns:
-#   counter = (column // 4, row, (2 * layer + is_bias) | replica << 16, step)   [MLP]
+#   counter = (column // 4, row, (8 * layer + piece) | replica << 16, step)     [MLP]
+#             piece: 0 W, 1 b, 2 gamma, 3 beta, 4..7 the same of the layer's projection shortcut
 #   counter = (j // 4 mod 2^32, j // 4 >> 32, replica << 16, step)               [raw vector]
 #   key     = (seed mod 2^32, seed >> 32)
 #   u_i = ((r_i >> 8) + 1/2) / 2^24;  z0, z1 = sqrt(-2 ln u0) (cos, sin)(2 pi u1);  z2, z3 from u2, u3
@@ -468,12 +517,12 @@ def normals_from_counters(counter, key):
     return out
 
 
-def langevin_noise(dims, d_raw, replica, step, seed, shapes=None, bn_mask=0):
+def langevin_noise(dims, d_raw, replica, step, seed, shapes=None, bn_mask=0, proj_mask=0):
     """xi for one replica and step, in the flat parameter layout.  `shapes`: (fan_in, out) per
     layer when they are not the consecutive pairs of `dims` (convolutional layers: a filter
-    bank [out, 3, 3, C] is the matrix [out, 9 C]).  The gamma and beta vectors of a
-    batch-normalised layer l follow its bias, as one-row matrices with the codes 32 + 2 l and
-    33 + 2 l."""
+    bank [out, 3, 3, C] is the matrix [out, 9 C]).  The pieces of layer l carry the codes
+    8 l + 0 (W), 1 (b), 2 (gamma), 3 (beta), 4..7 (the same four of its projection shortcut);
+    vectors count as one-row matrices."""
     key = (seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF)
     if not len(dims):
         groups = np.arange((d_raw + 3) // 4, dtype=np.uint64)
@@ -484,9 +533,11 @@ def langevin_noise(dims, d_raw, replica, step, seed, shapes=None, bn_mask=0):
     if shapes is None:
         shapes = [(dims[l], dims[l + 1]) for l in range(len(dims) - 1)]
     for l, (fi, fo) in enumerate(shapes):
-        pieces = [(2 * l, fo, fi), (2 * l + 1, 1, fo)]
+        pieces = [(8 * l, fo, fi), (8 * l + 1, 1, fo)]
         if (bn_mask >> l) & 1:
-            pieces += [(32 + 2 * l, 1, fo), (33 + 2 * l, 1, fo)]
+            pieces += [(8 * l + 2, 1, fo), (8 * l + 3, 1, fo)]
+        if (proj_mask >> l) & 1:
+            pieces += [(8 * l + 4, fo, dims[l - 1]), (8 * l + 5, 1, fo), (8 * l + 6, 1, fo), (8 * l + 7, 1, fo)]
         for which, rows, cols in pieces:
             cg = np.arange((cols + 3) // 4, dtype=np.uint64)[None, :]
             rr = np.arange(rows, dtype=np.uint64)[:, None]
@@ -513,7 +564,7 @@ class LsamOracle:
                  lambda0=0.5, lambda_abs=-1.0, nesterov=1, tau=None, tau_min=1, tau_max=1,
                  sched_seed=0, sched_mode=SCHED_FIXED, algorithm=ALG_LSAM, noise_scale=0.0,
                  noise_seed=0, n_conv=0, img_h=0, img_w=0, pool_mask=0, bn_mask=0, bn_eps=1e-5,
-                 stride_mask=0, skip_mask=0, global_avg_pool=0):
+                 stride_mask=0, skip_mask=0, global_avg_pool=0, proj_mask=0):
         self.K = int(K)
         self.algorithm = int(algorithm)
         self.noise_scale, self.noise_seed = float(noise_scale), int(noise_seed)
@@ -521,11 +572,12 @@ class LsamOracle:
         self.t = 0                      # sampler steps taken so far
         if n_conv:
             self.model = Cnn(dims, n_conv, img_h, img_w, pool_mask, bn_mask, bn_eps, gemm_dtype,
-                             stride_mask, skip_mask, global_avg_pool)
+                             stride_mask, skip_mask, global_avg_pool, proj_mask)
         else:
             self.model = Mlp(dims, gemm_dtype) if len(dims) else None
         self.shapes = self.model.shapes if n_conv else None
         self.bn_mask = int(bn_mask) if n_conv else 0
+        self.proj_mask = int(proj_mask) if n_conv else 0
         self.d = self.model.d if self.model else int(d_raw)
         self.batch = int(batch)
         self.rho, self.gamma = float(rho), float(gamma)
@@ -582,7 +634,8 @@ class LsamOracle:
         else:
             self.x[i] = self.x[i] - self.lr * self.v[i]
         if self.noise_scale != 0.0:
-            xi = langevin_noise(self.dims, self.d, i, self.t, self.noise_seed, self.shapes, self.bn_mask)
+            xi = langevin_noise(self.dims, self.d, i, self.t, self.noise_seed, self.shapes, self.bn_mask,
+                                self.proj_mask)
             self.x[i] = self.x[i] + self.noise_scale * np.sqrt(2.0 * self.lr) * xi
         self.S[i] += self.x[i]
 

@@ -429,7 +429,8 @@ def test_box_muller_normals_have_the_right_law():
 
 def test_noise_layout_follows_rows_and_columns():
     """Element (layer, row, column) takes lane column % 4 of the call with counter
-    (column // 4, row, 2*layer + is_bias | replica << 16, step), whatever the widths."""
+    (column // 4, row, 8*layer + piece | replica << 16, step), piece 0 for W and 1 for b,
+    whatever the widths."""
     dims, rep, step, seed = (6, 5, 3), 2, 9, (77 << 32) | 5
     xi = langevin_noise(dims, 0, rep, step, seed)
     assert xi.size == 6 * 5 + 5 + 5 * 3 + 3
@@ -439,7 +440,7 @@ def test_noise_layout_follows_rows_and_columns():
     b1 = xi[30:35]
     assert b1[4] == normals_from_counters((1, 0, 1 | rep << 16, step), key)[0]
     W2 = xi[35:50].reshape(3, 5)
-    assert W2[2, 2] == normals_from_counters((0, 2, 2 | rep << 16, step), key)[2]
+    assert W2[2, 2] == normals_from_counters((0, 2, 8 | rep << 16, step), key)[2]
     raw = langevin_noise((), 10, rep, step, seed)
     assert raw.size == 10 and raw[9] == normals_from_counters((2, 0, rep << 16, step), key)[1]
 
@@ -693,6 +694,33 @@ def test_noise_layout_with_batchnorm_vectors():
     assert np.all(np.isfinite(b[n0:n0 + 8])) and len(set(b[n0:n0 + 8])) == 8
 
 
+def test_noise_of_every_parameter_group_is_a_stream_of_its_own():
+    # 20 normalised convolutions, two of them with a projection: the first element of every
+    # group (row 0, column 0 of its matrix) comes from a different counter, so no two agree;
+    # the projection's four groups follow the closing convolution's four, W_p as [C_out, C_src]
+    n_conv = 20
+    dims = (4,) * (n_conv + 1) + (3,)
+    shapes = [(36, 4)] * n_conv + [(4, 3)]
+    bn = (1 << n_conv) - 1
+    proj = (1 << 5) | (1 << 17)
+    xi = langevin_noise(dims, 0, 1, 3, 11, shapes=shapes, bn_mask=bn, proj_mask=proj)
+    firsts, off = [], 0
+    for l, (fi, fo) in enumerate(shapes):
+        sizes = [fo * fi, fo] + ([fo, fo] if l < n_conv else []) + ([fo * 4, fo, fo, fo] if (proj >> l) & 1 else [])
+        for n in sizes:
+            firsts.append(xi[off])
+            off += n
+    assert off == xi.size and len(firsts) == 4 * n_conv + 2 + 8
+    assert len(set(firsts)) == len(firsts)
+    key = (11, 0)
+    at = sum(36 * 4 + 12 for _ in range(5)) + 36 * 4 + 12        # behind convolution 5's beta
+    Wp = xi[at:at + 16].reshape(4, 4)
+    assert Wp[2, 1] == normals_from_counters((0, 2, (8 * 5 + 4) | 1 << 16, 3), key)[1]
+    assert xi[at + 16 + 3] == normals_from_counters((0, 0, (8 * 5 + 5) | 1 << 16, 3), key)[3]     # b_p
+    assert xi[at + 20 + 0] == normals_from_counters((0, 0, (8 * 5 + 6) | 1 << 16, 3), key)[0]     # gamma_p
+    assert xi[at + 24 + 2] == normals_from_counters((0, 0, (8 * 5 + 7) | 1 << 16, 3), key)[2]     # beta_p
+
+
 def test_cnn_bf16_products_round_their_operands_only():
     # operands that are bf16 numbers already: the forward pass is untouched; in the backward
     # pass only dZ gets rounded, so gradients move by at most a bf16 half-ulp of their size;
@@ -861,9 +889,10 @@ def test_hand_cases_catch_a_misplaced_rounding(case, monkeypatch):
 
 # ---- residual networks: stride-2 convolutions, shortcuts, global average pooling ----------------
 def _torch_resnet_loss(xt, X, lab, dims, n_conv, shapes, bn_mask, stride_mask, skip_mask, gap, pool_mask=0,
-                       bn_eps=1e-5):
+                       bn_eps=1e-5, proj_mask=0):
     """The residual model written with torch's own routines: conv2d with a stride, batch_norm in
-    training mode, slicing and F.pad for the parameter-free shortcut, mean for the pooling."""
+    training mode, slicing and F.pad for the parameter-free shortcut, a strided 1x1 conv2d and a
+    second batch_norm for the projection shortcut, mean for the pooling."""
     import torch.nn.functional as F
     A = torch.tensor(X).permute(0, 3, 1, 2)
     off = 0
@@ -879,7 +908,18 @@ def _torch_resnet_loss(xt, X, lab, dims, n_conv, shapes, bn_mask, stride_mask, s
             Z = F.batch_norm(Z, None, None, xt[off:off + fo], xt[off + fo:off + 2 * fo],
                              training=True, eps=bn_eps)
             off += 2 * fo
-        if (skip_mask >> l) & 1:
+        if (proj_mask >> l) & 1:
+            S = inputs[l - 1]
+            cs = S.shape[1]
+            Wp = xt[off:off + fo * cs].reshape(fo, cs, 1, 1)
+            off += fo * cs
+            P = F.conv2d(S, Wp, xt[off:off + fo], stride=S.shape[2] // Z.shape[2])
+            off += fo
+            P = F.batch_norm(P, None, None, xt[off:off + fo], xt[off + fo:off + 2 * fo],
+                             training=True, eps=bn_eps)
+            off += 2 * fo
+            Z = Z + P
+        elif (skip_mask >> l) & 1:
             S = inputs[l - 1]
             if S.shape[2] != Z.shape[2]:
                 S = S[:, :, ::2, ::2]
@@ -924,6 +964,258 @@ def test_residual_model_gradient_matches_torch_autograd(dims, n_conv, H, W, bn_m
     L.backward()
     assert abs(loss - L.item()) < 1e-12
     assert np.max(np.abs(g - xt.grad.numpy())) / np.max(np.abs(g)) < 1e-10
+
+
+@pytest.mark.parametrize("dims,n_conv,H,W,stride_mask,skip_mask,proj_mask,B", [
+    # a stem, then a block whose projection halves the image and doubles the channels
+    ((2, 4, 8, 8, 3), 3, 4, 4, 0b010, 0b100, 0b100, 3),
+    # projection without stride that changes the channel count downwards, then a plain block,
+    # then a strided projection block (three kinds of shortcut in one model)
+    ((3, 8, 6, 4, 4, 4, 8, 8, 5), 7, 8, 4, 0b0100000, 0b1010100, 0b1000100, 2),
+    # projection on equal shapes (C_src = C_out, stride 1)
+    ((2, 4, 4, 4, 3), 3, 4, 6, 0, 0b100, 0b100, 3),
+])
+def test_projection_shortcut_gradient_matches_torch_autograd(dims, n_conv, H, W, stride_mask, skip_mask,
+                                                             proj_mask, B):
+    from oracle.lsam_oracle import Cnn
+    bn_mask = (1 << n_conv) - 1
+    m = Cnn(dims, n_conv, H, W, 0, bn_mask, 1e-5, 0, stride_mask, skip_mask, 1, proj_mask)
+    # the projection's parameters follow the closing convolution's: W_p, b_p, gamma_p, beta_p
+    d = 0
+    for l, (fi, fo) in enumerate(m.shapes):
+        d += fi * fo + fo + (2 * fo if l < n_conv else 0)
+        if (proj_mask >> l) & 1:
+            assert m.proj_offsets[l][0] == d
+            d += fo * dims[l - 1] + 3 * fo
+            assert m.proj_offsets[l][4] == d
+    assert m.d == d
+    rng = np.random.default_rng(33)
+    x = rng.standard_normal(m.d) * 0.3
+    for l, (g0, g1, g2) in m.bn_offsets.items():
+        x[g0:g1] = 1.0 + 0.3 * rng.standard_normal(g1 - g0)
+    for l, (p0, p1, p2, p3, p4) in m.proj_offsets.items():
+        x[p2:p3] = 1.0 + 0.3 * rng.standard_normal(p3 - p2)
+    X = rng.standard_normal((B, H, W, dims[0]))
+    lab = rng.integers(0, dims[-1], B)
+    loss, g = m.loss_and_grad(x, X, lab)
+    xt = torch.tensor(x, requires_grad=True)
+    L = _torch_resnet_loss(xt, X, lab, dims, n_conv, m.shapes, bn_mask, stride_mask, skip_mask, 1,
+                           proj_mask=proj_mask)
+    L.backward()
+    assert abs(loss - L.item()) < 1e-12
+    assert np.max(np.abs(g - xt.grad.numpy())) / np.max(np.abs(g)) < 1e-10
+    # every group of projection parameters but its bias (whose gradient the normalisation
+    # cancels) has a gradient of its own
+    for l, (p0, p1, p2, p3, p4) in m.proj_offsets.items():
+        assert np.max(np.abs(g[p0:p1])) > 1e-6 and np.max(np.abs(g[p2:p3])) > 1e-6
+        assert np.max(np.abs(g[p3:p4])) > 1e-6 and np.max(np.abs(g[p1:p2])) < 1e-12
+
+
+def test_projection_shortcut_gradient_matches_finite_differences():
+    from oracle.lsam_oracle import Cnn
+    m = Cnn((2, 4, 8, 8, 3), 3, 4, 4, 0, 0b111, 1e-5, 0, 0b010, 0b100, 1, 0b100)
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal(m.d) * 0.4
+    X = rng.standard_normal((3, 4, 4, 2))
+    lab = np.array([0, 2, 1])
+    _, g = m.loss_and_grad(x, X, lab)
+    h = 1e-6
+    p0, _, _, _, p4 = m.proj_offsets[2]
+    picks = np.concatenate([rng.choice(m.d, 40, replace=False), rng.choice(np.arange(p0, p4), 25, replace=False)])
+    for j in picks:
+        e = np.zeros(m.d)
+        e[j] = h
+        fd = (m.loss_and_grad(x + e, X, lab)[0] - m.loss_and_grad(x - e, X, lab)[0]) / (2 * h)
+        assert abs(fd - g[j]) < 1e-6 * max(1.0, np.max(np.abs(g))), j
+
+
+def test_projection_shortcut_of_a_known_block():
+    # All 3x3 filters zero: the main branch of the block is its beta.  The block input is then
+    # relu(beta_0) = a constant image per channel ... which a normalisation would map to zero,
+    # so the stem gets distinct values instead: stem filters zero but for the centre tap of
+    # channel 0 -> channel 0 (weight 1), gamma_0 = 1, beta_0 = 0, so the stem output is
+    # relu(normalised input).  The projection (stride 2) then sees pixels (2i, 2j) only, and its
+    # output can be written with numpy's mean/var over exactly those pixels.
+    from oracle.lsam_oracle import Cnn
+    m = Cnn((1, 2, 2, 4, 3), 3, 4, 4, 0, 0b111, 1e-5, 0, 0b010, 0b100, 1, 0b100)
+    x = np.zeros(m.d)
+    o0, o1, o2 = m.offsets[0]
+    W0 = np.zeros((2, 3, 3, 1))
+    W0[0, 1, 1, 0] = 1.0
+    W0[1, 1, 1, 0] = -1.0
+    x[o0:o1] = W0.ravel()
+    g0, g1, g2 = m.bn_offsets[0]
+    x[g0:g1] = 1.0
+    for l in (1, 2):
+        a, b, c = m.bn_offsets[l]
+        x[a:b] = 1.0
+    a, b, c = m.bn_offsets[2]
+    beta2 = np.array([0.1, -0.2, 0.3, 0.0])
+    x[b:c] = beta2
+    p0, p1, p2, p3, p4 = m.proj_offsets[2]
+    Wp = np.array([[1.0, 0.0], [0.0, 2.0], [1.0, 1.0], [-1.0, 0.5]])
+    x[p0:p1] = Wp.ravel()
+    x[p1:p2] = [5.0, -3.0, 0.0, 1.0]          # cancelled by the normalisation
+    gp, bp = np.array([1.0, 0.5, 2.0, 1.5]), np.array([0.0, 0.1, -0.1, 0.2])
+    x[p2:p3], x[p3:p4] = gp, bp
+    rng = np.random.default_rng(4)
+    X = rng.standard_normal((2, 4, 4, 1))
+    # head: logits = mean over pixels of the block output, times W + b
+    h0, h1, h2 = m.offsets[3]
+    Wd = rng.standard_normal((3, 4))
+    x[h0:h1] = Wd.ravel()
+    lab = np.array([1, 2])
+    loss, _ = m.loss_and_grad(x, X, lab)
+    z = X[..., 0]
+    xh = (z - z.mean()) / np.sqrt(z.var() + 1e-5)
+    stem = np.stack([np.maximum(xh, 0), np.maximum(-xh, 0)], axis=-1)      # [2, 4, 4, 2]
+    sub = stem[:, ::2, ::2, :]
+    P = sub @ Wp.T
+    Pn = (P - P.mean(axis=(0, 1, 2))) / np.sqrt(P.var(axis=(0, 1, 2)) + 1e-5)
+    out = np.maximum(beta2 + gp * Pn + bp, 0)                               # [2, 2, 2, 4]
+    logits = out.mean(axis=(1, 2)) @ Wd.T
+    lse = np.log(np.exp(logits).sum(axis=1))
+    assert abs(loss - np.mean(lse - logits[np.arange(2), lab])) < 1e-12
+
+
+def _torch_rounded_product():
+    """A @ W^T with both operands cast to bfloat16 by torch; its backward pass casts the incoming
+    gradient and the other operand the same way (the rule every product of the bf16 arithmetic
+    mode follows).  Everything around the products is left to autograd in float64."""
+    cast = lambda t: t.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+
+    class Product(torch.autograd.Function):
+        @staticmethod
+        def forward(ctx, A, W):
+            ctx.save_for_backward(A, W)
+            return cast(A) @ cast(W).T
+
+        @staticmethod
+        def backward(ctx, dP):
+            A, W = ctx.saved_tensors
+            return cast(dP) @ cast(W), cast(dP).T @ cast(A)
+
+    return Product.apply
+
+
+def _torch_resnet_loss_bf16(xt, X, lab, dims, n_conv, shapes, bn_mask, stride_mask, skip_mask, proj_mask,
+                            bn_eps=1e-5):
+    """The residual model with global average pooling, every matrix product replaced by the
+    bfloat16 product above: convolutions as F.unfold (torch's own im2col, channel-major
+    columns) times the filter matrix."""
+    import torch.nn.functional as F
+    prod = _torch_rounded_product()
+    A = torch.tensor(X).permute(0, 3, 1, 2)
+    B = A.shape[0]
+    off = 0
+    inputs = []
+    for l in range(n_conv):
+        fi, fo = shapes[l]
+        C = dims[l]
+        W = xt[off:off + fo * fi].reshape(fo, 3, 3, C).permute(0, 3, 1, 2).reshape(fo, 9 * C)
+        off += fo * fi
+        inputs.append(A)
+        st = 2 if (stride_mask >> l) & 1 else 1
+        h, w = A.shape[2] // st, A.shape[3] // st
+        cols = F.unfold(A, 3, padding=1, stride=st).transpose(1, 2).reshape(B * h * w, 9 * C)
+        Z = prod(cols, W) + xt[off:off + fo]
+        Z = Z.reshape(B, h, w, fo).permute(0, 3, 1, 2)
+        off += fo
+        if (bn_mask >> l) & 1:
+            Z = F.batch_norm(Z, None, None, xt[off:off + fo], xt[off + fo:off + 2 * fo],
+                             training=True, eps=bn_eps)
+            off += 2 * fo
+        if (proj_mask >> l) & 1:
+            S = inputs[l - 1]
+            if S.shape[2] != h:
+                S = S[:, :, ::2, ::2]
+            cs = S.shape[1]
+            Wp = xt[off:off + fo * cs].reshape(fo, cs)
+            off += fo * cs
+            P = prod(S.permute(0, 2, 3, 1).reshape(B * h * w, cs), Wp) + xt[off:off + fo]
+            off += fo
+            P = P.reshape(B, h, w, fo).permute(0, 3, 1, 2)
+            P = F.batch_norm(P, None, None, xt[off:off + fo], xt[off + fo:off + 2 * fo],
+                             training=True, eps=bn_eps)
+            off += 2 * fo
+            Z = Z + P
+        elif (skip_mask >> l) & 1:
+            S = inputs[l - 1]
+            if S.shape[2] != h:
+                S = S[:, :, ::2, ::2]
+            Z = Z + F.pad(S, (0, 0, 0, 0, 0, fo - S.shape[1]))
+        A = F.relu(Z)
+    A = A.mean(dim=(2, 3))
+    for l in range(n_conv, len(shapes)):
+        fi, fo = shapes[l]
+        A = prod(A, xt[off:off + fo * fi].reshape(fo, fi)) + xt[off + fo * fi:off + fo * fi + fo]
+        off += fo * fi + fo
+        if l < len(shapes) - 1:
+            A = F.relu(A)
+    return F.cross_entropy(A, torch.tensor(lab))
+
+
+@pytest.mark.parametrize("dims,n_conv,H,W,stride_mask,skip_mask,proj_mask,B", [
+    ((2, 4, 8, 8, 3), 3, 4, 4, 0b010, 0b100, 0b100, 3),
+    ((3, 8, 6, 4, 4, 4, 8, 8, 5), 7, 8, 4, 0b0100000, 0b1010100, 0b1000100, 2),
+    ((2, 4, 8, 8, 8, 8, 3), 5, 8, 4, 0b00010, 0b10100, 0, 2),
+])
+def test_bf16_residual_model_matches_torch_with_bfloat16_products(dims, n_conv, H, W, stride_mask,
+                                                                  skip_mask, proj_mask, B):
+    """Pins where the bf16 arithmetic mode rounds in the convolutional and residual model, the
+    projection's two products included: torch's bfloat16 cast on both operands of every
+    product, forward and backward, nothing else rounded."""
+    from oracle.lsam_oracle import Cnn
+    bn_mask = (1 << n_conv) - 1
+    m = Cnn(dims, n_conv, H, W, 0, bn_mask, 1e-5, 1, stride_mask, skip_mask, 1, proj_mask)
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal(m.d) * 0.3).astype(np.float32).astype(np.float64)
+    for l, (g0, g1, g2) in m.bn_offsets.items():
+        x[g0:g1] = (1.0 + 0.3 * rng.standard_normal(g1 - g0)).astype(np.float32)
+    for l, (p0, p1, p2, p3, p4) in m.proj_offsets.items():
+        x[p2:p3] = (1.0 + 0.3 * rng.standard_normal(p3 - p2)).astype(np.float32)
+    X = rng.standard_normal((B, H, W, dims[0])).astype(np.float32).astype(np.float64)
+    lab = rng.integers(0, dims[-1], B)
+    loss, g = m.loss_and_grad(x, X, lab)
+    xt = torch.tensor(x, requires_grad=True)
+    L = _torch_resnet_loss_bf16(xt, X, lab, dims, n_conv, m.shapes, bn_mask, stride_mask, skip_mask, proj_mask)
+    L.backward()
+    assert abs(loss - L.item()) < 1e-12
+    assert np.max(np.abs(g - xt.grad.numpy())) / np.max(np.abs(g)) < 1e-10
+    # and the rounding is not a no-op here
+    l64, g64 = Cnn(dims, n_conv, H, W, 0, bn_mask, 1e-5, 0, stride_mask, skip_mask, 1, proj_mask).loss_and_grad(x, X, lab)
+    assert np.max(np.abs(g - g64)) / np.max(np.abs(g)) > 1e-4
+
+
+_PROJECTION_MISTAKES = [
+    ("Zp = q(S) @ q(Wp).T + x[p1:p2]", "Zp = S @ q(Wp).T + x[p1:p2]"),
+    ("Zp = q(S) @ q(Wp).T + x[p1:p2]", "Zp = q(S) @ Wp.T + x[p1:p2]"),
+    ("grad[p0:p1] = (q(flatp).T @ q(S.reshape(-1, S.shape[3]))).ravel()",
+     "grad[p0:p1] = (flatp.T @ q(S.reshape(-1, S.shape[3]))).ravel()"),
+    ("dS = q(dZp) @ q(Wp)", "dS = dZp @ q(Wp)"),
+    ("dS = q(dZp) @ q(Wp)", "dS = q(dZp) @ Wp"),
+    ("                    S = S[:, ::2, ::2, :]\n                Wp", "                    S = S[:, 1::2, 1::2, :]\n                Wp"),
+    ("dZp = x[p2:p3] * invp * (dZc - dbp / n - Xhp * dgp / n)", "dZp = x[p2:p3] * invp * (dZc - dbp / n)"),
+    ("full[:, ::2, ::2, :] = dS", "full[:, 1::2, 1::2, :] = dS"),
+    ("Z = Z + x[p2:p3] * Xhp + x[p3:p4]", "Z = Z + x[p2:p3] * Xhp"),
+]
+
+
+@pytest.mark.parametrize("case", range(len(_PROJECTION_MISTAKES)))
+def test_torch_witness_catches_a_mistake_in_the_projection(case, monkeypatch):
+    """Plants one mistake in a copy of the oracle's projection shortcut and checks that the
+    comparison with torch's bfloat16 products fails on it."""
+    import types
+    import oracle.lsam_oracle as real
+    old, new = _PROJECTION_MISTAKES[case]
+    src = open(real.__file__).read()
+    assert src.count(old) == 1, "the oracle no longer contains: " + old
+    planted = types.ModuleType("planted_oracle")
+    exec(compile(src.replace(old, new, 1), "planted_oracle", "exec"), planted.__dict__)
+    monkeypatch.setattr(real, "Cnn", planted.Cnn)
+    with pytest.raises(AssertionError):
+        test_bf16_residual_model_matches_torch_with_bfloat16_products(
+            (3, 8, 6, 4, 4, 4, 8, 8, 5), 7, 8, 4, 0b0100000, 0b1010100, 0b1000100, 2)
 
 
 def test_residual_model_gradient_matches_finite_differences():

@@ -58,6 +58,13 @@
  * zero channels appended (that paper's parameter-free shortcut).  The closing convolution must
  * be batch-normalised and must not be followed by a pool inside the block; channel counts of
  * the block input must be multiples of 4 and at most the block's output channels.
+ * proj_mask (a subset of skip_mask) replaces the shortcut of a block by that paper's projection,
+ * as its ResNet-18/34 use where a block changes shape: a 1x1 convolution of the block input
+ * with the block's stride, C_{l-1} -> C_{l+1} channels, with bias, followed by a batch
+ * normalisation of its own (same bn_eps, no ReLU).  Its parameters W_p [C_{l+1}, C_{l-1}],
+ * b_p, gamma_p, beta_p [C_{l+1}] follow those of the closing convolution l in the flat layout;
+ * b_p, like b_l, cannot influence the loss and its gradient is reported as exactly zero.  Any
+ * channel counts (multiples of 8) are allowed on both sides of a projection.
  */
 #ifndef LSAM_H
 #define LSAM_H
@@ -76,7 +83,7 @@ extern "C" {
 #define LSAM_ESTATE  -4   /* call not valid for this context (e.g. wrong mode)   */
 
 #define LSAM_MAX_REPLICAS 64
-#define LSAM_MAX_LAYERS   24
+#define LSAM_MAX_LAYERS   40
 
 #define LSAM_GEMM_FP32 0  /* fp32 operands, fp32 accumulate                      */
 #define LSAM_GEMM_BF16 1  /* bf16 operands, fp32 accumulate, fp32 master weights */
@@ -132,13 +139,15 @@ typedef struct {
   int32_t n_conv;         /* 0: dense model.  > 0: the first n_conv layers are 3x3 convolutions
                              (stride 1, zero rim 1, bias, ReLU), the rest dense; see below   */
   int32_t img_h, img_w;   /* input image sides (n_conv > 0)                           */
-  uint32_t pool_mask;     /* bit l set: a 2x2/stride-2 max-pool follows convolution l */
-  uint32_t bn_mask;       /* bit l set: convolution l is batch-normalised before its ReLU */
   float bn_eps;           /* epsilon of the normalisation, > 0 (or 0 with bn_mask = 0) */
-  uint32_t stride_mask;   /* bit l set: convolution l has stride 2 (its output is [H/2, W/2]) */
-  uint32_t skip_mask;     /* bit l set (l >= 2): convolutions l-1 and l form a residual block; the
+  uint64_t pool_mask;     /* bit l set: a 2x2/stride-2 max-pool follows convolution l */
+  uint64_t bn_mask;       /* bit l set: convolution l is batch-normalised before its ReLU */
+  uint64_t stride_mask;   /* bit l set: convolution l has stride 2 (its output is [H/2, W/2]) */
+  uint64_t skip_mask;     /* bit l set (l >= 2): convolutions l-1 and l form a residual block; the
                              block's input -- the image convolution l-1 read -- is added to the
                              normalised output of convolution l before its ReLU; see below   */
+  uint64_t proj_mask;     /* bit l set (with bit l of skip_mask): that shortcut is a projection, a
+                             1x1 convolution with batch normalisation; see below            */
   int32_t global_avg_pool; /* 1: the dense layers read the mean of the last image over its
                              positions (one value per channel) instead of the flattened image */
 } lsam_config;

@@ -244,10 +244,20 @@ int launch_first_conv_wgrad(const float* X, const float* dout, float* partial, f
 // Shortcut of a residual block (He et al., CIFAR variant, parameter-free): the block input
 // src [K][B][step H][step W][Cs] (replica stride `stride` floats) enters the block output
 // [B][H][W][C] as src[b][step i][step j][c] for c < Cs and 0 for the channels beyond.  Cs % 4 == 0.
+// A projection shortcut instead (that paper's 1x1 convolution with batch normalisation): `pz`
+// [K][rows][C] is the 1x1 convolution's output, `pstats` its statistics (launch_bn_stats), and
+// gamma_p, beta_p sit at pgam_off, pbet_off of each replica's parameters; pz null: no projection.
 struct ShortcutDesc {
   const float* src; int64_t stride;
   int H, W, Cs, step;
+  const float* pz = nullptr; const float* pstats = nullptr;
+  int64_t pgam_off = 0, pbet_off = 0;
 };
+// stats[k] = (mean, 1/sqrt(var + eps)) per channel of Z [K][rows][C]; scratch as for launch_bn_forward.
+int launch_bn_stats(const float* Z, float* scratch, float* stats, int K, int64_t rows, int C, float eps,
+                    hipStream_t s);
+// dst[img][i][j][c] = src[img][2 i][2 j][c] for `images` images [2H][2W][C] (C % 4 == 0).
+int launch_subsample2(const float* src, float* dst, int64_t images, int H, int W, int C, hipStream_t s);
 int bn_chunks(int64_t rows, int C, int K);
 // `shortcut` (may be null): added to the normalised output before the ReLU.
 int launch_bn_forward(const float* Z, float* scratch, float* stats, const float* params,

@@ -559,10 +559,15 @@ __global__ __launch_bounds__(64 * kBnChains) void bn_stats_finish_kernel(
 
 // The shortcut of a residual block as the kernels read it: the block input [B][st H][st W][Cs]
 // seen from an output pixel (i, j) and channel c is src[b][st i][st j][c] for c < Cs, 0 beyond.
+// A projection shortcut instead: pz [K][rows][C] is the 1x1 convolution of the block input,
+// normalised here with its own statistics pstats and gamma_p, beta_p (offsets into params).
 struct Shortcut {
-  const float* src;     // null: no shortcut
+  const float* src;     // null: no parameter-free shortcut
   long long stride;     // floats from one replica's block input to the next
   int H, W, Cs, st;     // output image, channels of the block input, pixel step
+  const float* pz;      // null: no projection
+  const float* pstats;
+  long long pgam_off, pbet_off;
 };
 
 // out = relu(gamma (Z - mean) inv_std + beta [+ shortcut]).  One thread per 16-byte word.
@@ -584,7 +589,13 @@ __global__ __launch_bounds__(kThreads) void bn_apply_kernel(const float* __restr
   const f32x4 be = *reinterpret_cast<const f32x4*>(params + k * strideParams + bet_off + c);
   const f32x4 z = *reinterpret_cast<const f32x4*>(Z + idx * 4);
   f32x4 y = ga * ((z - mu) * inv) + be;
-  if (sc.src != nullptr && c < sc.Cs) {       // Cs % 4 == 0: a word lies inside or outside
+  if (sc.pz != nullptr) {
+    const f32x4 pmu = *reinterpret_cast<const f32x4*>(sc.pstats + ((long long)k * 2) * C + c);
+    const f32x4 pinv = *reinterpret_cast<const f32x4*>(sc.pstats + ((long long)k * 2 + 1) * C + c);
+    const f32x4 pga = *reinterpret_cast<const f32x4*>(params + k * strideParams + sc.pgam_off + c);
+    const f32x4 pbe = *reinterpret_cast<const f32x4*>(params + k * strideParams + sc.pbet_off + c);
+    y += pga * ((*reinterpret_cast<const f32x4*>(sc.pz + idx * 4) - pmu) * pinv) + pbe;
+  } else if (sc.src != nullptr && c < sc.Cs) {       // Cs % 4 == 0: a word lies inside or outside
     const long long m = idx / words - (long long)k * rows;       // (b, i, j) of this replica
     const int j = (int)(m % sc.W), i = (int)((m / sc.W) % sc.H);
     const long long b = m / ((long long)sc.W * sc.H);
@@ -623,6 +634,24 @@ __global__ __launch_bounds__(kThreads) void shortcut_backward_kernel(const float
       if (!(keep[r] > 0.f)) g[r] = 0.f;
   }
   *reinterpret_cast<f32x4*>(dIn + at) += g;
+}
+
+// dst[k][b][i][j][c] = src[k][b][2 i][2 j][c]: the pixels a stride-2 1x1 convolution reads, as a
+// dense matrix [K][B H W][C].  One thread per 16-byte word of dst.
+__global__ __launch_bounds__(kThreads) void subsample2_kernel(const float* __restrict__ src,
+                                                              float* __restrict__ dst, long long images,
+                                                              int H, int W, int C, long long total) {
+  const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= total) return;
+  const int words = C / 4;
+  const int c = (int)(idx % words) * 4;
+  long long m = idx / words;
+  const int j = (int)(m % W);
+  m /= W;
+  const int i = (int)(m % H);
+  const long long img = m / H;
+  const long long at = ((img * (2 * H) + 2 * i) * (2 * W) + 2 * j) * C + c;
+  *reinterpret_cast<f32x4*>(dst + idx * 4) = *reinterpret_cast<const f32x4*>(src + at);
 }
 
 // Global average pooling: P[k][b][c] = mean over the H W positions of A[k][b][.][.][c] (summed
@@ -789,16 +818,42 @@ int launch_first_conv_wgrad(const float* X, const float* dout, float* partial, f
 
 int bn_chunks(int64_t rows, int C, int K) { return chunk_plan(rows, C, K).chunks; }
 
+int launch_bn_stats(const float* Z, float* scratch, float* stats, int K, int64_t rows, int C, float eps,
+                    hipStream_t s) {
+  if (C % 4 || C < 4 || C > 4 * kThreads || rows < 1) return -1;
+  const ChunkPlan pl = chunk_plan(rows, C, K);
+  const int chunks = pl.chunks;
+  float* pmean = scratch;
+  float* pm2 = scratch + (long long)K * chunks * C;
+  bn_stats_partial_kernel<<<dim3((unsigned)chunks, (unsigned)K, (unsigned)pl.col_blocks), kThreads, 0, s>>>(
+      Z, pmean, pm2, rows, C, chunks, pl.chunk_rows);
+  bn_stats_finish_kernel<<<dim3((unsigned)((C + 63) / 64), (unsigned)K), 64 * kBnChains, 0, s>>>(
+      pmean, pm2, stats, rows, C, chunks, pl.chunk_rows, eps);
+  return 0;
+}
+
+int launch_subsample2(const float* src, float* dst, int64_t images, int H, int W, int C, hipStream_t s) {
+  if (C % 4 || C < 4 || H < 1 || W < 1 || images < 1) return -1;
+  const long long total = images * H * W * (C / 4);
+  subsample2_kernel<<<blocks_for(total), kThreads, 0, s>>>(src, dst, images, H, W, C, total);
+  return 0;
+}
+
 int launch_bn_forward(const float* Z, float* scratch, float* stats, const float* params,
                       int64_t strideParams, int64_t gam_off, int64_t bet_off, float* out, int K,
                       int64_t rows, int C, float eps, const ShortcutDesc* shortcut, hipStream_t s) {
   if (C % 4 || C < 4 || C > 4 * kThreads || rows < 1) return -1;
-  Shortcut sc{nullptr, 0, 1, 1, 0, 1};
-  if (shortcut != nullptr) {
+  Shortcut sc{nullptr, 0, 1, 1, 0, 1, nullptr, nullptr, 0, 0};
+  if (shortcut != nullptr && shortcut->pz != nullptr) {
+    if (shortcut->pstats == nullptr) return -1;
+    sc.pz = shortcut->pz; sc.pstats = shortcut->pstats;
+    sc.pgam_off = shortcut->pgam_off; sc.pbet_off = shortcut->pbet_off;
+  } else if (shortcut != nullptr) {
     if (shortcut->Cs % 4 || shortcut->Cs > C || shortcut->H < 1 || shortcut->W < 1 ||
         rows % ((int64_t)shortcut->H * shortcut->W) || shortcut->step < 1 || shortcut->step > 2)
       return -1;
-    sc = Shortcut{shortcut->src, shortcut->stride, shortcut->H, shortcut->W, shortcut->Cs, shortcut->step};
+    sc = Shortcut{shortcut->src, shortcut->stride, shortcut->H, shortcut->W, shortcut->Cs, shortcut->step,
+                  nullptr, nullptr, 0, 0};
   }
   const ChunkPlan pl = chunk_plan(rows, C, K);
   const int chunks = pl.chunks;
@@ -817,7 +872,7 @@ int launch_bn_forward(const float* Z, float* scratch, float* stats, const float*
 int launch_shortcut_backward(const float* dY, float* dIn, const float* mask, const ShortcutDesc& d, int K,
                              int64_t rows, int C, hipStream_t s) {
   if (d.Cs % 4 || d.Cs > C || d.Cs < 4 || rows % ((int64_t)d.H * d.W) || d.step < 1 || d.step > 2) return -1;
-  const Shortcut sc{nullptr, d.stride, d.H, d.W, d.Cs, d.step};
+  const Shortcut sc{nullptr, d.stride, d.H, d.W, d.Cs, d.step, nullptr, nullptr, 0, 0};
   const long long total = (long long)K * rows * (d.Cs / 4);
   shortcut_backward_kernel<<<blocks_for(total), kThreads, 0, s>>>(dY, dIn, mask, rows, C, sc, total);
   return 0;

@@ -3,11 +3,12 @@
 //
 // xi comes from Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11), a counter-based generator:
 // the four normals of four neighbouring columns are a function of where they are and when,
-//   counter = (column / 4, row, (2 * layer + is_bias) | replica << 16, step)      MLP layout
+//   counter = (column / 4, row, (8 * layer + piece) | replica << 16, step)        layered models
 //   counter = (j / 4 mod 2^32, j / 4 >> 32, replica << 16, step)                  raw vector
+//   piece: 0 W, 1 b, 2 gamma, 3 beta of the layer; 4..7 the same four of its projection shortcut
 //   key     = (seed mod 2^32, seed >> 32)
 //   u_i = ((r_i >> 8) + 1/2) / 2^24;  z0, z1 = sqrt(-2 ln u0) (cos, sin)(2 pi u1);  z2, z3 from u2, u3
-// (a bias vector counts as one row), so no generator state is stored and the kernel that
+// (a vector counts as one row), so no generator state is stored and the kernel that
 // streams the parameters produces the noise on the way.
 #pragma once
 #include <stdint.h>
@@ -16,12 +17,12 @@
 
 namespace lsam {
 
-// One run of the padded flat layout that takes noise: a weight matrix (rows of `ld` floats,
-// the first `cols` of each real) or a bias vector (one row).
+// One run of the padded flat layout that takes noise: a matrix (rows of `ld` floats, the first
+// `cols` of each real) or a vector (one row).
 struct NoiseSeg {
   int64_t begin, end;     // flat offsets inside a replica
   int32_t ld, cols;
-  int32_t code;           // 2 * layer + is_bias; 32 + 2 * layer (+ 1) for a layer's gamma (beta)
+  int32_t code;           // 8 * layer + piece
   int32_t pad_;
 };
 struct NoiseMap {
@@ -29,7 +30,7 @@ struct NoiseMap {
   uint32_t key0, key1, step;
   float amp;                              // sigma * sqrt(2 eta)
   int64_t raw_n;
-  NoiseSeg seg[4 * LSAM_MAX_LAYERS];
+  const NoiseSeg* seg;                    // device memory, n runs in increasing order of `begin`
 };
 struct NoNoise {};
 
@@ -75,16 +76,20 @@ __device__ inline void langevin4(const NoiseMap& m, int replica, int64_t flat, f
     c0 = (uint32_t)grp; c1 = (uint32_t)(grp >> 32); c2 = (uint32_t)replica << 16;
     if (m.raw_n - flat < 4) valid = (int)(m.raw_n - flat);
   } else {
-    int s = -1;
-    for (int i = 0; i < m.n; ++i)
-      if (flat >= m.seg[i].begin && flat < m.seg[i].end) s = i;
-    if (s < 0) return;
-    const uint32_t rel = (uint32_t)(flat - m.seg[s].begin);
-    const uint32_t row = rel / (uint32_t)m.seg[s].ld;
-    const uint32_t col = rel - row * (uint32_t)m.seg[s].ld;
-    if ((int)col >= m.seg[s].cols) return;
-    if (m.seg[s].cols - (int)col < 4) valid = m.seg[s].cols - (int)col;
-    c0 = col >> 2; c1 = row; c2 = (uint32_t)m.seg[s].code | ((uint32_t)replica << 16);
+    // the last run that begins at or before `flat`
+    int lo = 0, hi = m.n;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (m.seg[mid].begin <= flat) lo = mid; else hi = mid;
+    }
+    const NoiseSeg sg = m.seg[lo];
+    if (flat < sg.begin || flat >= sg.end) return;
+    const uint32_t rel = (uint32_t)(flat - sg.begin);
+    const uint32_t row = rel / (uint32_t)sg.ld;
+    const uint32_t col = rel - row * (uint32_t)sg.ld;
+    if ((int)col >= sg.cols) return;
+    if (sg.cols - (int)col < 4) valid = sg.cols - (int)col;
+    c0 = col >> 2; c1 = row; c2 = (uint32_t)sg.code | ((uint32_t)replica << 16);
   }
   uint32_t r[4];
   float z[4];

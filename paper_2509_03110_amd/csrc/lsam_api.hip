@@ -116,6 +116,19 @@ struct Layer {
   int64_t w_flat, b_flat; // offsets inside the public flat layout
   bool bn = false;        // batch-normalised convolution: gamma and beta follow the bias
   int64_t gam_off = 0, bet_off = 0, gam_flat = 0, bet_flat = 0;
+  // projection shortcut closed by this convolution: W_p [out][proj_in] (row pitch proj_in, a
+  // multiple of 8), b_p, gamma_p, beta_p follow the layer's own parameters
+  bool proj = false;
+  int proj_in = 0;
+  int64_t pw_off = 0, pb_off = 0, pgam_off = 0, pbet_off = 0;
+};
+
+// One parameter group as the copies between the flat and the padded layout and the noise
+// generator see it: `rows` rows of `cols` values, row pitch `ld` in the padded layout.
+struct Piece {
+  int64_t off, flat;
+  int rows, cols, ld;
+  int code;               // 8 * layer + {0 W, 1 b, 2 gamma, 3 beta, 4..7 the projection's four}
 };
 
 // One 3x3 convolution layer: image [H][W][Cin] -> [H][W][Cout] (-> [H/2][W/2][Cout] if pooled).
@@ -124,6 +137,9 @@ struct ConvLayer {
   int stride;          // 1 or 2: the layer reads an image of [stride H][stride W][Cin]
   bool skip;           // closes a residual block: the input of the layer below is added before the ReLU
   int skip_C, skip_step;   // channels of that block input; 2 if the block halved the image, else 1
+  bool proj;           // that shortcut is a projection (1x1 convolution + batch normalisation)
+  size_t psub, pz, pstats; // its input pixels [K][rows][skip_C] (later: their gradient), its
+                           // convolution output [K][rows][Cout] (later: that output's gradient), its statistics
   int64_t rows;        // B H W: rows of the unfolded image and of the layer's output
   int ldc;             // pitch of the unfolded image, 9 Cin rounded up to 8
   // The GEMM kernels can read an unfolded image straight from the image when its channel
@@ -153,6 +169,8 @@ struct Layout {
   bool bf16_math = false;      // convolutional model with bf16 matrix products on fp32 tensors
   int64_t d = 0, d_pad = 0;
   std::vector<Layer> layers;
+  std::vector<Piece> pieces; // every parameter group, in the order of the flat layout
+  size_t noise_segs = 0;     // device copy of the noise generator's table (Langevin sampler only)
   std::vector<int> ld;       // activation pitches ld[0..L]
   bool need_a0 = false;
   int nblk = 1;
@@ -192,14 +210,16 @@ int check_config(const lsam_config* c) {
       return fail(LSAM_EINVAL, "n_conv=%d must leave at least one dense layer of %d", c->n_conv,
                   c->n_layers);
     if (c->n_conv == 0 && c->bn_mask) return fail(LSAM_EINVAL, "bn_mask needs convolution layers");
-    if (c->n_conv == 0 && (c->stride_mask || c->skip_mask || c->global_avg_pool))
-      return fail(LSAM_EINVAL, "stride_mask, skip_mask and global_avg_pool need convolution layers");
+    if (c->n_conv == 0 && (c->stride_mask || c->skip_mask || c->proj_mask || c->global_avg_pool))
+      return fail(LSAM_EINVAL, "stride_mask, skip_mask, proj_mask and global_avg_pool need convolution layers");
     if (c->n_conv > 0) {
       if (c->img_h < 1 || c->img_w < 1) return fail(LSAM_EINVAL, "img_h, img_w must be >= 1");
       if (c->bn_mask >> c->n_conv) return fail(LSAM_EINVAL, "bn_mask names a layer that is no convolution");
       if (c->bn_mask && !(c->bn_eps > 0.f)) return fail(LSAM_EINVAL, "bn_eps must be > 0");
-      if (c->n_conv < 32 && ((c->stride_mask >> c->n_conv) || (c->skip_mask >> c->n_conv)))
-        return fail(LSAM_EINVAL, "stride_mask or skip_mask names a layer that is no convolution");
+      if ((c->stride_mask >> c->n_conv) || (c->skip_mask >> c->n_conv) || (c->pool_mask >> c->n_conv))
+        return fail(LSAM_EINVAL, "stride_mask, skip_mask or pool_mask names a layer that is no convolution");
+      if (c->proj_mask & ~c->skip_mask)
+        return fail(LSAM_EINVAL, "proj_mask names a layer that closes no residual block");
       if (c->global_avg_pool != 0 && c->global_avg_pool != 1)
         return fail(LSAM_EINVAL, "global_avg_pool must be 0 or 1");
       int64_t h = c->img_h, w = c->img_w;
@@ -223,8 +243,9 @@ int check_config(const lsam_config* c) {
           if (((c->pool_mask >> (l - 1)) & 1u) || ((c->pool_mask >> (l - 2)) & 1u))
             return fail(LSAM_EINVAL, "convolution %d: no pool may sit inside a residual block or in front of it", l);
           const int64_t sh = in_h[l - 1], sw = in_w[l - 1];
-          if (!((sh == h && sw == w) || (sh == 2 * h && sw == 2 * w)) || c->dims[l - 1] > c->dims[l + 1] ||
-              c->dims[l - 1] % 4)
+          const bool proj = ((c->proj_mask >> l) & 1u) != 0;
+          if (!((sh == h && sw == w) || (sh == 2 * h && sw == 2 * w)) ||
+              (!proj && c->dims[l - 1] > c->dims[l + 1]) || c->dims[l - 1] % (proj ? 8 : 4))
             return fail(LSAM_EINVAL, "convolution %d: the block input (%lldx%lldx%d) does not fit the block output (%lldx%lldx%d)",
                         l, (long long)sh, (long long)sw, c->dims[l - 1], (long long)h, (long long)w, c->dims[l + 1]);
         }
@@ -305,6 +326,7 @@ void build_layout(const lsam_config& c, Layout& lo) {
             const ConvLayer& first = lo.conv[l - 1];
             cv.skip_C = first.Cin;
             cv.skip_step = first.stride * first.H / h;
+            cv.proj = ((c.proj_mask >> l) & 1u) != 0;
           }
           cv.rows = (int64_t)c.batch * h * w;
           cv.ldc = (int)round_up(9 * (int64_t)cv.Cin, 8);
@@ -343,6 +365,27 @@ void build_layout(const lsam_config& c, Layout& lo) {
         s.bet_flat = flat + s.out;
         flat += 2 * (int64_t)s.out;
       }
+      lo.pieces.push_back(Piece{s.w_off, s.w_flat, s.out, s.in, s.ldw, 8 * l});
+      lo.pieces.push_back(Piece{s.b_off, s.b_flat, 1, s.out, (int)round_up(s.out, 4), 8 * l + 1});
+      if (s.bn) {
+        lo.pieces.push_back(Piece{s.gam_off, s.gam_flat, 1, s.out, (int)round_up(s.out, 4), 8 * l + 2});
+        lo.pieces.push_back(Piece{s.bet_off, s.bet_flat, 1, s.out, (int)round_up(s.out, 4), 8 * l + 3});
+      }
+      if (l < lo.n_conv && lo.conv[l].proj) {
+        s.proj = true;
+        s.proj_in = lo.conv[l].skip_C;
+        s.pw_off = off;
+        off = round_up(off + (int64_t)s.out * s.proj_in, 64);
+        int64_t* slot[3] = {&s.pb_off, &s.pgam_off, &s.pbet_off};
+        lo.pieces.push_back(Piece{s.pw_off, flat, s.out, s.proj_in, s.proj_in, 8 * l + 4});
+        flat += (int64_t)s.out * s.proj_in;
+        for (int q = 0; q < 3; ++q) {
+          *slot[q] = off;
+          lo.pieces.push_back(Piece{off, flat, 1, s.out, (int)round_up(s.out, 4), 8 * l + 5 + q});
+          off = round_up(off + s.out, 64);
+          flat += s.out;
+        }
+      }
       lo.layers.push_back(s);
     }
     lo.d = flat;
@@ -374,7 +417,8 @@ void build_layout(const lsam_config& c, Layout& lo) {
     for (const Layer& ly : lo.layers)
       cap += std::max(gemm_sumsq_capacity(ly.out, ly.in),
                       std::max(head_sumsq_slots(ly.in), ly.out / 2)) +   // ly.out / 2: first-layer kernels
-             (ly.out + 63) / 64 + (ly.bn ? 2 * ((ly.out + 63) / 64) : 0);
+             (ly.out + 63) / 64 + (ly.bn ? 2 * ((ly.out + 63) / 64) : 0) +
+             (ly.proj ? gemm_sumsq_capacity(ly.out, ly.proj_in) + 2 * ((ly.out + 63) / 64) : 0);
     lo.nblk = (int)cap;
   }
 
@@ -422,6 +466,11 @@ void build_layout(const lsam_config& c, Layout& lo) {
       if (cv.pool) {
         cv.pooled = take(cur, full / 4);
         cv.dpooled = take(cur, full / 4);
+      }
+      if (cv.proj) {
+        cv.psub = take(cur, (size_t)lo.K * cv.rows * cv.skip_C * 4);
+        cv.pz = take(cur, full);
+        cv.pstats = take(cur, (size_t)lo.K * 2 * cv.Cout * 4);
       }
       if (l > 0 && !cv.direct_dx) dcol_bytes = std::max(dcol_bytes, (size_t)lo.K * cv.rows * cv.ldc * 4);
     }
@@ -473,6 +522,15 @@ void build_layout(const lsam_config& c, Layout& lo) {
       d.out_bf16 = 0;
       d.unfold = cv && cv->direct_in ? 2 : 0;
       need = std::max(need, gemm_splitk_bytes(d));
+      if (ly.proj) {       // the projection's three products
+        d.unfold = 0;
+        d.M = rows; d.N = ly.out; d.Kd = ly.proj_in; d.a_kmajor = 1; d.b_kmajor = 1;
+        need = std::max(need, gemm_splitk_bytes(d));
+        d.M = rows; d.N = ly.proj_in; d.Kd = ly.out; d.a_kmajor = 1; d.b_kmajor = 0;
+        need = std::max(need, gemm_splitk_bytes(d));
+        d.M = ly.out; d.N = ly.proj_in; d.Kd = rows; d.a_kmajor = 0; d.b_kmajor = 0;
+        need = std::max(need, gemm_splitk_bytes(d));
+      }
     }
     lo.splitk_bytes = need;
     if (need) lo.splitk = take(cur, need);
@@ -481,6 +539,7 @@ void build_layout(const lsam_config& c, Layout& lo) {
       lo.gram1 = take(cur, (size_t)lo.K * lo.B * lo.ldg * 4);
       lo.gram2 = take(cur, (size_t)lo.K * lo.B * lo.ldg * 4);
     }
+    if (c.noise_scale > 0.f) lo.noise_segs = take(cur, lo.pieces.size() * sizeof(NoiseSeg));
   }
   lo.total = cur;
 }
@@ -638,10 +697,41 @@ int conv_forward(lsam_ctx* c, const float* X, const float* params) {
       LaunchTimer t(c, KC_GEMM_FWD);
       if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "forward GEMM of convolution %d rejected", l);
     }
+    if (cv.proj) {
+      // projection shortcut: the block input's pixels (every second one if the block halved
+      // the image) through a 1x1 convolution, then that output's own statistics
+      const ConvLayer& src = lo.conv[l - 2];
+      const float* sub = c->at<float>(src.out);
+      if (cv.skip_step == 2) {
+        LaunchTimer t(c, KC_UNFOLD);
+        if (launch_subsample2(sub, c->at<float>(cv.psub), (int64_t)lo.K * lo.B, cv.H, cv.W, cv.skip_C, s) != 0)
+          return fail(LSAM_EINVAL, "projection of convolution %d: gather rejected", l);
+        sub = c->at<float>(cv.psub);
+      }
+      GemmDesc d{};
+      d.A = sub; d.strideA = cv.rows * cv.skip_C; d.ldA = cv.skip_C; d.a_kmajor = 1;
+      d.B = params + ly.pw_off; d.strideB = lo.d_pad; d.ldB = ly.proj_in; d.b_kmajor = 1;
+      d.C = c->at<float>(cv.pz); d.strideC = cv.rows * cv.Cout; d.ldC = cv.Cout;
+      d.M = (int)cv.rows; d.N = cv.Cout; d.Kd = ly.proj_in; d.batch = lo.K;
+      d.epilogue = EPI_BIAS;
+      d.bias = params + ly.pb_off; d.strideBias = lo.d_pad;
+      split(c, d);
+      {
+        LaunchTimer t(c, KC_GEMM_FWD);
+        if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "projection of convolution %d rejected", l);
+      }
+      LaunchTimer t(c, KC_BATCHNORM);
+      if (launch_bn_stats(c->at<float>(cv.pz), c->at<float>(lo.colsum), c->at<float>(cv.pstats), lo.K,
+                          cv.rows, cv.Cout, c->cfg.bn_eps, s) != 0)
+        return fail(LSAM_EINVAL, "projection of convolution %d: statistics rejected", l);
+    }
     if (cv.bn) {
       LaunchTimer t(c, KC_BATCHNORM);
       ShortcutDesc sc{};
-      if (cv.skip) {
+      if (cv.proj) {
+        sc.pz = c->at<float>(cv.pz); sc.pstats = c->at<float>(cv.pstats);
+        sc.pgam_off = ly.pgam_off; sc.pbet_off = ly.pbet_off;
+      } else if (cv.skip) {
         // the block input: what convolution l-1 read, i.e. the ReLU output of convolution l-2
         sc.src = c->at<float>(lo.conv[l - 2].out);
         sc.stride = lo.conv[l - 2].rows * cv.skip_C;
@@ -693,7 +783,8 @@ int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq,
     float* dout = c->at<float>(cv.dout);
     // room for every partial sum of squares this layer's kernels may write, checked up front
     if (ssq && *slots + std::max(gemm_sumsq_capacity(ly.out, ly.in), ly.out / 2) + (ly.out + 63) / 64 +
-                       (ly.bn ? 2 * ((ly.out + 63) / 64) : 0) > lo.nblk)
+                       (ly.bn ? 2 * ((ly.out + 63) / 64) : 0) +
+                       (ly.proj ? gemm_sumsq_capacity(ly.out, ly.proj_in) + 2 * ((ly.out + 63) / 64) : 0) > lo.nblk)
       return fail(LSAM_ESTATE, "gradient-norm partials would overrun their buffer at convolution %d", l);
     if (cv.pool) {
       LaunchTimer t(c, KC_POOL);
@@ -727,7 +818,53 @@ int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq,
       float* dz = cv.skip ? c->at<float>(cv.z) : dout;
       launch_bn_backward_apply(c->at<float>(cv.z), dout, dz, c->at<float>(cv.stats), params, g, lo.d_pad,
                                ly.gam_off, ly.bet_off, lo.K, cv.rows, cv.Cout, s);
+      if (cv.proj) {
+        // the same gradient dY enters the projection's normalisation: dgamma_p, dbeta_p, then
+        // the gradient of the 1x1 convolution's output, which takes that output's place
+        float* pz = c->at<float>(cv.pz);
+        const int pchunks = launch_bn_backward_partials(pz, dout, c->at<float>(cv.pstats), part, lo.K,
+                                                        cv.rows, cv.Cout, s);
+        if (pchunks < 0) return fail(LSAM_EINVAL, "projection of convolution %d: normalisation rejected", l);
+        int used = launch_bias_grad(part, 2 * cv.Cout, 0, g + ly.pgam_off, lo.d_pad, lo.K, pchunks, cv.Cout,
+                                    ssq ? ssq + *slots : nullptr, lo.nblk, s);
+        if (ssq) *slots += used;
+        used = launch_bias_grad(part + cv.Cout, 2 * cv.Cout, 0, g + ly.pbet_off, lo.d_pad, lo.K, pchunks,
+                                cv.Cout, ssq ? ssq + *slots : nullptr, lo.nblk, s);
+        if (ssq) *slots += used;
+        launch_bn_backward_apply(pz, dout, pz, c->at<float>(cv.pstats), params, g, lo.d_pad, ly.pgam_off,
+                                 ly.pbet_off, lo.K, cv.rows, cv.Cout, s);
+      }
       dout = dz;
+    }
+    if (cv.proj) {
+      // dW_p = dZ_p^T S and dS = dZ_p W_p; dS replaces the gathered pixels and reaches the block
+      // input's gradient once the block's opening convolution has written that gradient
+      const float* dzp = c->at<float>(cv.pz);
+      float* psub = c->at<float>(cv.psub);
+      {
+        GemmDesc d{};
+        d.A = dzp; d.strideA = cv.rows * cv.Cout; d.ldA = cv.Cout; d.a_kmajor = 0;
+        d.B = cv.skip_step == 2 ? psub : c->at<float>(lo.conv[l - 2].out);
+        d.strideB = cv.rows * cv.skip_C; d.ldB = cv.skip_C; d.b_kmajor = 0;
+        d.C = g + ly.pw_off; d.strideC = lo.d_pad; d.ldC = ly.proj_in;
+        d.M = cv.Cout; d.N = ly.proj_in; d.Kd = (int)cv.rows; d.batch = lo.K;
+        d.epilogue = EPI_PLAIN;
+        split(c, d);
+        if (ssq) { d.sumsq = ssq + *slots; d.sumsq_stride = lo.nblk; }
+        int used = 0;
+        LaunchTimer t(c, KC_GEMM_DW);
+        if (launch_gemm(d, s, &used) != 0) return fail(LSAM_EINVAL, "projection of convolution %d: dW rejected", l);
+        if (ssq) *slots += used;
+      }
+      GemmDesc d{};
+      d.A = dzp; d.strideA = cv.rows * cv.Cout; d.ldA = cv.Cout; d.a_kmajor = 1;
+      d.B = params + ly.pw_off; d.strideB = lo.d_pad; d.ldB = ly.proj_in; d.b_kmajor = 0;
+      d.C = psub; d.strideC = cv.rows * cv.skip_C; d.ldC = cv.skip_C;
+      d.M = (int)cv.rows; d.N = ly.proj_in; d.Kd = cv.Cout; d.batch = lo.K;
+      d.epilogue = EPI_PLAIN;
+      split(c, d);
+      LaunchTimer t(c, KC_GEMM_DX);
+      if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "projection of convolution %d: dX rejected", l);
     }
     if (cv.first) {
       LaunchTimer t(c, KC_CONV_FIRST);
@@ -828,8 +965,9 @@ int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq,
       const ConvLayer& below = lo.conv[l - 1];
       const ShortcutDesc sc{nullptr, below.rows * top.skip_C, top.H, top.W, top.skip_C, top.skip_step};
       LaunchTimer t(c, KC_POOL);
-      if (launch_shortcut_backward(c->at<float>(top.dout), c->at<float>(below.dout), c->at<float>(below.out),
-                                   sc, lo.K, top.rows, top.Cout, s) != 0)
+      if (launch_shortcut_backward(c->at<float>(top.proj ? top.psub : top.dout), c->at<float>(below.dout),
+                                   c->at<float>(below.out), sc, lo.K, top.rows,
+                                   top.proj ? top.skip_C : top.Cout, s) != 0)
         return fail(LSAM_EINVAL, "shortcut of the block closed by convolution %d rejected", l + 1);
     }
   }
@@ -1193,25 +1331,21 @@ int copy_in(lsam_ctx* c, const float* src_flat, float* dst_dev) {
   int rc = ensure_stage(c);
   if (rc != LSAM_OK) return rc;
   float* stage = static_cast<float*>(c->stage);
-  for (const Layer& ly : lo.layers) {
-    const int64_t rows_per = std::max<int64_t>(1, (int64_t)(kStageBytes / 4) / ly.ldw);
-    for (int64_t r0 = 0; r0 < ly.out; r0 += rows_per) {
-      const int64_t nr = std::min<int64_t>(rows_per, ly.out - r0);
+  for (const Piece& p : lo.pieces) {
+    if (p.rows == 1) {
+      if ((rc = to_device(c, dst_dev + p.off, src_flat + p.flat, (size_t)p.cols * 4)) != LSAM_OK) return rc;
+      continue;
+    }
+    const int64_t rows_per = std::max<int64_t>(1, (int64_t)(kStageBytes / 4) / p.ld);
+    for (int64_t r0 = 0; r0 < p.rows; r0 += rows_per) {
+      const int64_t nr = std::min<int64_t>(rows_per, p.rows - r0);
       for (int64_t r = 0; r < nr; ++r) {
-        memcpy(stage + r * ly.ldw, src_flat + ly.w_flat + (r0 + r) * ly.in, (size_t)ly.in * 4);
-        if (ly.ldw > ly.in) memset(stage + r * ly.ldw + ly.in, 0, (size_t)(ly.ldw - ly.in) * 4);
+        memcpy(stage + r * p.ld, src_flat + p.flat + (r0 + r) * p.cols, (size_t)p.cols * 4);
+        if (p.ld > p.cols) memset(stage + r * p.ld + p.cols, 0, (size_t)(p.ld - p.cols) * 4);
       }
-      HIP_TRY(hipMemcpyAsync(dst_dev + ly.w_off + r0 * ly.ldw, stage, (size_t)nr * ly.ldw * 4,
+      HIP_TRY(hipMemcpyAsync(dst_dev + p.off + r0 * p.ld, stage, (size_t)nr * p.ld * 4,
                              hipMemcpyHostToDevice, c->stream));
       HIP_TRY(hipStreamSynchronize(c->stream));
-    }
-    if ((rc = to_device(c, dst_dev + ly.b_off, src_flat + ly.b_flat, (size_t)ly.out * 4)) != LSAM_OK)
-      return rc;
-    if (ly.bn) {
-      if ((rc = to_device(c, dst_dev + ly.gam_off, src_flat + ly.gam_flat, (size_t)ly.out * 4)) != LSAM_OK)
-        return rc;
-      if ((rc = to_device(c, dst_dev + ly.bet_off, src_flat + ly.bet_flat, (size_t)ly.out * 4)) != LSAM_OK)
-        return rc;
     }
   }
   return LSAM_OK;
@@ -1223,23 +1357,19 @@ int copy_out(lsam_ctx* c, const float* src_dev, float* dst_flat) {
   int rc = ensure_stage(c);
   if (rc != LSAM_OK) return rc;
   const float* stage = static_cast<const float*>(c->stage);
-  for (const Layer& ly : lo.layers) {
-    const int64_t rows_per = std::max<int64_t>(1, (int64_t)(kStageBytes / 4) / ly.ldw);
-    for (int64_t r0 = 0; r0 < ly.out; r0 += rows_per) {
-      const int64_t nr = std::min<int64_t>(rows_per, ly.out - r0);
-      HIP_TRY(hipMemcpyAsync(c->stage, src_dev + ly.w_off + r0 * ly.ldw, (size_t)nr * ly.ldw * 4,
+  for (const Piece& p : lo.pieces) {
+    if (p.rows == 1) {
+      if ((rc = to_host(c, dst_flat + p.flat, src_dev + p.off, (size_t)p.cols * 4)) != LSAM_OK) return rc;
+      continue;
+    }
+    const int64_t rows_per = std::max<int64_t>(1, (int64_t)(kStageBytes / 4) / p.ld);
+    for (int64_t r0 = 0; r0 < p.rows; r0 += rows_per) {
+      const int64_t nr = std::min<int64_t>(rows_per, p.rows - r0);
+      HIP_TRY(hipMemcpyAsync(c->stage, src_dev + p.off + r0 * p.ld, (size_t)nr * p.ld * 4,
                              hipMemcpyDeviceToHost, c->stream));
       HIP_TRY(hipStreamSynchronize(c->stream));
       for (int64_t r = 0; r < nr; ++r)
-        memcpy(dst_flat + ly.w_flat + (r0 + r) * ly.in, stage + r * ly.ldw, (size_t)ly.in * 4);
-    }
-    if ((rc = to_host(c, dst_flat + ly.b_flat, src_dev + ly.b_off, (size_t)ly.out * 4)) != LSAM_OK)
-      return rc;
-    if (ly.bn) {
-      if ((rc = to_host(c, dst_flat + ly.gam_flat, src_dev + ly.gam_off, (size_t)ly.out * 4)) != LSAM_OK)
-        return rc;
-      if ((rc = to_host(c, dst_flat + ly.bet_flat, src_dev + ly.bet_off, (size_t)ly.out * 4)) != LSAM_OK)
-        return rc;
+        memcpy(dst_flat + p.flat + (r0 + r) * p.cols, stage + r * p.ld, (size_t)p.cols * 4);
     }
   }
   return LSAM_OK;
@@ -1328,19 +1458,7 @@ int lsam_init(const lsam_config* cfg, const float* init_params, int64_t n_init, 
     nm.key1 = (uint32_t)(c->cfg.noise_seed >> 32);
     nm.raw_n = lo.raw ? lo.d : 0;
     nm.n = 0;
-    for (int l = 0; l < lo.L; ++l) {
-      const Layer& ly = lo.layers[l];
-      NoiseSeg w{ly.w_off, ly.w_off + (int64_t)ly.out * ly.ldw, ly.ldw, ly.in, 2 * l, 0};
-      NoiseSeg b{ly.b_off, ly.b_off + ly.out, (int32_t)round_up(ly.out, 4), ly.out, 2 * l + 1, 0};
-      nm.seg[nm.n++] = w;
-      nm.seg[nm.n++] = b;
-      if (ly.bn) {
-        NoiseSeg ga{ly.gam_off, ly.gam_off + ly.out, (int32_t)round_up(ly.out, 4), ly.out, 32 + 2 * l, 0};
-        NoiseSeg be{ly.bet_off, ly.bet_off + ly.out, (int32_t)round_up(ly.out, 4), ly.out, 33 + 2 * l, 0};
-        nm.seg[nm.n++] = ga;
-        nm.seg[nm.n++] = be;
-      }
-    }
+    nm.seg = nullptr;
   }
   c->lr = cfg->lr;
   c->rho = cfg->rho;
@@ -1355,6 +1473,17 @@ int lsam_init(const lsam_config* cfg, const float* init_params, int64_t n_init, 
   if (check_launch("zero fill") != LSAM_OK) return bail(LSAM_EHIP);
   if (hipStreamSynchronize(c->stream) != hipSuccess)
     return bail(fail(LSAM_EHIP, "stream synchronize failed during init"));
+  if (lo.noise_segs) {
+    // the noise generator's table: one run per parameter group, in the layout's order
+    std::vector<NoiseSeg> segs;
+    for (const Piece& p : lo.pieces)
+      segs.push_back(NoiseSeg{p.off, p.off + (p.rows == 1 ? (int64_t)p.cols : (int64_t)p.rows * p.ld), p.ld,
+                              p.cols, p.code, 0});
+    if ((rc = to_device(c, c->at<char>(lo.noise_segs), segs.data(), segs.size() * sizeof(NoiseSeg))) != LSAM_OK)
+      return bail(rc);
+    c->noise.seg = c->at<NoiseSeg>(lo.noise_segs);
+    c->noise.n = (int)segs.size();
+  }
   float* x = c->at<float>(lo.x);
   float* y = c->at<float>(lo.y);
   if (n_init == lo.d) {

@@ -587,7 +587,7 @@ def test_maximum_replica_count_raw_mode():
 
 @pytest.mark.parametrize("bf16", [0, 1])
 def test_maximum_depth_mlp(bf16):
-    dims = (24,) + (16,) * 23 + (5,)               # LSAM_MAX_LAYERS = 24 dense layers
+    dims = (24,) + (16,) * 39 + (5,)               # LSAM_MAX_LAYERS = 40 dense layers
     w = workloads.WORKLOADS["cfg1"].scaled(name="deep", K=2, dims=dims, batch=6, tau=(2, 3),
                                            n_classes=5, steps=4, data_seed=4, gemm_dtype=bf16)
     if bf16:
@@ -1092,6 +1092,94 @@ def test_residual_model_with_bf16_products_and_the_comparators():
     run_mlp(w.scaled(noise_scale=1e-3, noise_seed=11), 4, 1e-4, 1e-3, anchor_after=1)
 
 
+# ---- projection shortcuts (1x1 convolution + batch normalisation where a block changes shape) ----
+PROJ_SMALL = RES_SMALL.scaled(dims=(3, 8, 16, 16, 16, 16, 5), n_conv=5, bn_mask=0b11111, stride_mask=0b00010,
+                              skip_mask=0b10100, proj_mask=0b00100)
+
+
+@pytest.mark.parametrize("name,over", [
+    ("a projection that halves the image and doubles the channels, then a plain block", {}),
+    ("a projection on equal shapes", dict(dims=(3, 8, 8, 8, 5), n_conv=3, bn_mask=0b111, stride_mask=0,
+                                          skip_mask=0b100, proj_mask=0b100)),
+    ("a projection to fewer channels without stride, then a strided one; sides no powers of two", dict(
+        dims=(4, 24, 16, 8, 8, 8, 16, 16, 5), n_conv=7, bn_mask=0b1111111, stride_mask=0b0100000,
+        skip_mask=0b1010100, proj_mask=0b1000100, img_h=6, img_w=10)),
+    ("projections on 32- to 64-channel images (unfolding inside the GEMM beside them)", dict(
+        dims=(3, 32, 32, 32, 64, 64, 10), n_conv=5, bn_mask=0b11111, stride_mask=0b01000,
+        skip_mask=0b10100, proj_mask=0b10000, n_classes=10, batch=4)),
+    ("four stages of one block each, ResNet-18's shape in small", dict(
+        dims=(3, 8, 8, 8, 16, 16, 32, 32, 64, 64, 10), n_conv=9, bn_mask=(1 << 9) - 1,
+        stride_mask=0b010101000, skip_mask=0b101010100, proj_mask=0b101010000, img_h=16, img_w=16,
+        n_classes=10, batch=4, K=3, tau=(2, 3, 4))),
+])
+def test_projection_shortcut_model_matches_oracle(name, over):
+    w = PROJ_SMALL.scaled(**over)
+    worst = run_mlp(w, 6, 1e-4, 1e-3, anchor_after=2)
+    print("projection %s: worst parameter error %.3e" % (name, worst))
+
+
+def test_projection_shortcut_gradients_group_by_group():
+    """One step from the common start: the gradients of the projection's own parameters (W_p,
+    gamma_p, beta_p; b_p exactly zero) and of every other group against the oracle's."""
+    w = PROJ_SMALL.scaled(batch=16)
+    g, o = make_pair(w)
+    X, lab = workloads.batch(w, 0)
+    Xd, ld = to_dev(X, lab, w)
+    loss_d = torch.zeros(w.K, device=DEV)
+    g.lsam_step(Xd, ld, loss_d)
+    ol = o.step(X, lab)
+    assert np.allclose(loss_d.cpu().numpy(), ol, rtol=1e-5)
+    assert np.allclose(g.lsam_get_norms(), o.last_norm, rtol=1e-3)
+    assert list(o.model.proj_offsets) == [2]
+    p0, p1, p2, p3, p4 = o.model.proj_offsets[2]
+    for i in range(w.K):
+        g2 = g.lsam_get_buffer(lsam.BUF_GRAD, i)
+        close_enough(g2[p0:p1], o.last_g2[i][p0:p1], 2e-3, "dW_p of replica %d" % i)
+        close_enough(g2[p2:p3], o.last_g2[i][p2:p3], 2e-3, "dgamma_p of replica %d" % i)
+        close_enough(g2[p3:p4], o.last_g2[i][p3:p4], 2e-3, "dbeta_p of replica %d" % i)
+        assert np.all(g2[p1:p2] == 0.0) and np.max(np.abs(o.last_g2[i][p1:p2])) < 1e-12
+        for l, (o0, o1, o2) in enumerate(o.model.offsets):
+            close_enough(g2[o0:o1], o.last_g2[i][o0:o1], 2e-3, "dW%d of replica %d" % (l + 1, i))
+            if l in o.model.bn_offsets:
+                b0, b1, b2 = o.model.bn_offsets[l]
+                close_enough(g2[b0:b2], o.last_g2[i][b0:b2], 2e-3, "dgamma, dbeta %d of replica %d" % (l + 1, i))
+    g.close()
+
+
+def test_projection_shortcut_with_bf16_products_the_comparators_and_noise():
+    w = PROJ_SMALL
+    run_mlp(w.scaled(gemm_dtype=1, batch=16), 5, 2e-2, 2e-2, anchor_after=1, tol_flip=1e-1)
+    run_mlp(w.scaled(algorithm=lsam.ALG_DATA_PARALLEL), 4, 1e-4, 1e-3, anchor_after=1)
+    # the noise of the projection's four groups has counters of its own
+    run_mlp(w.scaled(noise_scale=1e-3, noise_seed=11), 4, 1e-4, 1e-3, anchor_after=1)
+    run_mlp(w.scaled(rho=0.0), 4, 1e-4, 1e-3, anchor_after=1)
+
+
+def test_maximum_depth_residual_model():
+    """LSAM_MAX_LAYERS = 40 layers: 39 convolutions (a stem and 19 blocks, three of them with a
+    projection, bits above 31 of every mask in use) and one dense layer."""
+    n_conv = 39
+    dims = [3, 8]
+    stride = proj = skip = 0
+    for b in range(19):
+        l = 1 + 2 * b
+        c = 8 if b < 6 else 16 if b < 12 else 24
+        if b in (6, 12, 17):
+            proj |= 1 << (l + 1)
+            if b != 17:
+                stride |= 1 << l
+        skip |= 1 << (l + 1)
+        dims += [c, c]
+    w = RES_SMALL.scaled(dims=tuple(dims) + (5,), n_conv=n_conv, bn_mask=(1 << n_conv) - 1, stride_mask=stride,
+                         skip_mask=skip, proj_mask=proj, img_h=8, img_w=8, batch=4, noise_scale=1e-4,
+                         noise_seed=3)
+    assert len(w.dims) - 1 == 40 and proj >> 32 and skip >> 32
+    worst = run_mlp(w, 3, 2e-4, 2e-3, anchor_after=1)
+    print("40-layer residual model: worst parameter error %.3e" % worst)
+    cfg, keep = lsam.config_from_workload(w.scaled(dims=tuple(dims) + (7, 5)))
+    assert lsam.lsam_workspace_bytes(cfg) == 0 and "n_layers" in lsam.last_error()
+
+
 def test_residual_configurations_that_cannot_run_are_rejected():
     for over, msg in ((dict(skip_mask=0b010), "two convolutions below"),
                       (dict(bn_mask=0b011), "must be batch-normalised"),
@@ -1099,6 +1187,7 @@ def test_residual_configurations_that_cannot_run_are_rejected():
                       (dict(stride_mask=0b110), "does not fit"),
                       (dict(dims=(3, 16, 8, 8, 5)), "does not fit"),
                       (dict(stride_mask=0b1000), "no convolution"),
+                      (dict(proj_mask=0b010), "closes no residual block"),
                       (dict(img_h=6, img_w=6, stride_mask=0b011), "even image sides")):
         cfg, keep = lsam.config_from_workload(RES_SMALL.scaled(**over))
         assert lsam.lsam_workspace_bytes(cfg) == 0, over

@@ -13,7 +13,7 @@ def oracle_from(w, init, **over):
               algorithm=w.algorithm, noise_scale=w.noise_scale, noise_seed=w.noise_seed,
               n_conv=w.n_conv, img_h=w.img_h, img_w=w.img_w, pool_mask=w.pool_mask,
               bn_mask=w.bn_mask, bn_eps=w.bn_eps, stride_mask=w.stride_mask,
-              skip_mask=w.skip_mask, global_avg_pool=w.global_avg_pool)
+              skip_mask=w.skip_mask, global_avg_pool=w.global_avg_pool, proj_mask=w.proj_mask)
     kw.update(over)
     return LsamOracle(**kw)
 

@@ -59,6 +59,8 @@ class Workload:
     stride_mask: int = 0                    # bit l: convolution l has stride 2
     skip_mask: int = 0                      # bit l: the input of convolution l-1 is added to the
                                             # output of convolution l before its ReLU (basic block)
+    proj_mask: int = 0                      # bit l (with skip_mask): that shortcut is a 1x1 convolution
+                                            # with batch normalisation (projection), C_{l-1} -> C_{l+1}
     global_avg_pool: int = 0                # 1: the dense layers read the per-channel mean of the last image
     steps: int = 20
     data_seed: int = 0
@@ -93,7 +95,8 @@ class Workload:
     def d(self) -> int:
         if not self.dims:
             return self.d_raw
-        return sum(fi * fo + fo + (2 * fo if (self.bn_mask >> l) & 1 and l < self.n_conv else 0)
+        return sum(fi * fo + fo + (2 * fo if (self.bn_mask >> l) & 1 and l < self.n_conv else 0) +
+                   (fo * self.dims[l - 1] + 3 * fo if (self.proj_mask >> l) & 1 else 0)
                    for l, (fi, fo) in enumerate(self.layer_shapes))
 
     def scaled(self, **kw) -> "Workload":
@@ -157,6 +160,36 @@ WORKLOADS["resnet20"] = Workload(
     img_h=32, img_w=32, bn_mask=(1 << 19) - 1, stride_mask=(1 << 7) | (1 << 13),
     skip_mask=sum(1 << l for l in range(2, 19, 2)), global_avg_pool=1, rho=0.1, lr=0.2,
     tau=(16, 16, 16, 16), steps=20, data_seed=10, n_classes=10, batch_pool=2)
+
+
+def _basic_block_net(name, blocks, widths, classes, **kw):
+    """A 3x3 stem of widths[0] channels, then stage s of blocks[s] basic blocks at widths[s]
+    channels; the first block of every stage but the first halves the image and changes the
+    channel count through a projection shortcut.  Every convolution batch-normalised, global
+    average pooling, one dense layer."""
+    dims, stride, skip, proj = [3, widths[0]], 0, 0, 0
+    l = 1
+    for s, (n, c) in enumerate(zip(blocks, widths)):
+        for b in range(n):
+            if s > 0 and b == 0:
+                stride |= 1 << l
+                proj |= 1 << (l + 1)
+            skip |= 1 << (l + 1)
+            dims += [c, c]
+            l += 2
+    return Workload(name, K=4, dims=tuple(dims) + (classes,), batch=128, n_conv=l, img_h=32, img_w=32,
+                    bn_mask=(1 << l) - 1, stride_mask=stride, skip_mask=skip, proj_mask=proj,
+                    global_avg_pool=1, rho=0.1, lr=0.1, tau=(16, 16, 16, 16), steps=20, n_classes=classes,
+                    batch_pool=2, **kw)
+
+
+# ResNet-18 (Experiments: SVHN) and ResNet-34 (CIFAR-100) of He et al., four stages of 64, 128,
+# 256 and 512 channels with (2, 2, 2, 2) resp. (3, 4, 6, 3) basic blocks and projection
+# shortcuts where a stage begins; on 32x32 images the stem is one 3x3 convolution without the
+# ImageNet models' 7x7 stride-2 convolution and max-pool (the usual form for images of this
+# size; the paper does not say which it uses).  4 workers, batch 128, communication interval 16.
+WORKLOADS["resnet18"] = _basic_block_net("resnet18", (2, 2, 2, 2), (64, 128, 256, 512), 10, data_seed=12)
+WORKLOADS["resnet34"] = _basic_block_net("resnet34", (3, 4, 6, 3), (64, 128, 256, 512), 100, data_seed=13)
 # the same model with bf16 matrix products (tensors stay fp32; see the boundary's gemm_dtype)
 WORKLOADS["vgg16bf"] = replace(WORKLOADS["vgg16"], name="vgg16bf", gemm_dtype=1)
 
@@ -168,7 +201,8 @@ def _rng(seed: int, stream: int) -> np.random.Generator:
 def init_params(w: Workload, seed: Optional[int] = None) -> np.ndarray:
     """One flat fp32 parameter vector [d]: per layer W [out,in] row-major then b [out],
     each drawn U(-1/sqrt(in), 1/sqrt(in)), then gamma ~ U(0.9, 1.1) and beta ~ U(-0.1, 0.1) for a
-    batch-normalised layer; raw mode: N(0,1)."""
+    batch-normalised layer, then W_p, b_p, gamma_p, beta_p of a projection shortcut drawn the
+    same way (fan-in C_{l-1}); raw mode: N(0,1)."""
     rng = _rng(w.data_seed if seed is None else seed, 1)
     if not w.dims:
         return rng.standard_normal(w.d_raw, dtype=np.float32)
@@ -179,6 +213,13 @@ def init_params(w: Workload, seed: Optional[int] = None) -> np.ndarray:
         parts.append((rng.random(out, dtype=np.float32) * 2 - 1) * bound)
         if l < w.n_conv and (w.bn_mask >> l) & 1:
             # gamma around 1, beta around 0 (not exactly, so that tests see both)
+            parts.append(1 + (rng.random(out, dtype=np.float32) - np.float32(0.5)) * np.float32(0.2))
+            parts.append((rng.random(out, dtype=np.float32) - np.float32(0.5)) * np.float32(0.2))
+        if (w.proj_mask >> l) & 1:
+            cs = w.dims[l - 1]
+            bound = np.float32(1.0 / np.sqrt(cs))
+            parts.append((rng.random(out * cs, dtype=np.float32) * 2 - 1) * bound)
+            parts.append((rng.random(out, dtype=np.float32) * 2 - 1) * bound)
             parts.append(1 + (rng.random(out, dtype=np.float32) - np.float32(0.5)) * np.float32(0.2))
             parts.append((rng.random(out, dtype=np.float32) - np.float32(0.5)) * np.float32(0.2))
     return np.concatenate(parts).astype(np.float32)
@@ -206,6 +247,8 @@ def init_params_margin(w: Workload, seed: Optional[int] = None, ratio: float = 8
         off += out * fan_in + out
         if l < w.n_conv and (w.bn_mask >> l) & 1:
             off += 2 * out
+        if (w.proj_mask >> l) & 1:
+            off += out * w.dims[l - 1] + 3 * out
     return p
 
 

@@ -92,16 +92,17 @@ def gemm_flops(w, layers):
     from paper_2509_03110_amd import lsam
     K = w.K
     per = [float(rows) * fi * fo if kind not in (lsam.LAYER_HEAD, lsam.LAYER_CONV_FIRST) else 0.0
-           for kind, _, _, rows, fi, fo in layers]
-    first = sum(float(rows) * fi * fo for kind, _, _, rows, fi, fo in layers if kind == lsam.LAYER_CONV_FIRST)
-    sw, sw_dx = sum(per), sum(per[1:])
+           for kind, _, _, rows, fi, fo, _, _ in layers]
+    first = sum(float(rows) * fi * fo for kind, _, _, rows, fi, fo, _, _ in layers if kind == lsam.LAYER_CONV_FIRST)
+    proj = sum(float(rows) * pc * fo for _, _, _, rows, _, fo, pc, _ in layers)    # 1x1 projections
+    sw, sw_dx = sum(per) + proj, sum(per[1:]) + proj
     out = {"gemm_fwd": 2 * 2.0 * sw * K, "gemm_dx": 2 * 2.0 * sw_dx * K}
     if first:
         out["conv_first"] = 2 * 2 * 2.0 * first * K      # forward and weight gradient
-    if any(route for _, _, route, _, _, _ in layers):
+    if any(r[2] for r in layers):
         out["gemm_dw_ascend"] = out["gemm_dw_step"] = 2.0 * sw * K
         out["gemm_dw_norm"] = K * sum(2.0 * rows * rows * (fi + fo) if route == 2 else 2.0 * rows * fi * fo
-                                      for _, _, route, rows, fi, fo in layers)
+                                      for _, _, route, rows, fi, fo, _, _ in layers)
     else:
         out["gemm_dw"] = 2 * 2.0 * sw * K
     return out
@@ -116,14 +117,23 @@ def conv_bytes(w, layers):
     from paper_2509_03110_amd import lsam
     unfold = pool = bn = 0.0
     for l in range(w.n_conv):
-        kind, dx_stored, _, rows, _, _ = layers[l]
+        kind, dx_stored, _, rows, _, _, proj_c, proj_step = layers[l]
         cin, cout = w.dims[l], w.dims[l + 1]
         st2 = 4 if (w.stride_mask >> l) & 1 else 1    # pixels of the image read per output pixel
         if kind == lsam.LAYER_CONV_STORED:
             unfold += rows * (st2 * cin + 9 * cin) * 4.0
         if dx_stored:
             unfold += rows * (9 * cin + st2 * cin) * 4.0
-        if (w.skip_mask >> l) & 1:
+        if proj_c:
+            # projection: its normalisation costs what the layer's own does (below), and its
+            # output is read once more where the two branches meet; the gather for a strided
+            # one reads and writes the pixels it keeps; backward, the gradient of those pixels
+            # is added to the block input's gradient under that input's mask (3 reads, 1 write)
+            bn += rows * cout * 4.0 * (1 + 1 + 2 + 3)
+            if proj_step == 2:
+                unfold += rows * proj_c * 4.0 * 2
+            pool += rows * proj_c * 4.0 * 4
+        elif (w.skip_mask >> l) & 1:
             # shortcut: read with the normalisation (forward); backward reads dY, the mask and the
             # block input's gradient and writes the latter
             pool += rows * w.dims[l - 1] * 4.0 * (1 + 4)
@@ -289,7 +299,7 @@ def run_workload(w, steps, warmup, kernel_timing=True):
         stats = eng.lsam_timing_read()
         eng.lsam_timing_enable(False)
         layers = layer_table(eng, w) if w.dims else []
-        fused_step = any(route for _, _, route, _, _, _ in layers)
+        fused_step = any(r[2] for r in layers)
         flops = gemm_flops(w, layers) if w.dims else {}
         nbytes = stream_bytes(w, fused_step)
         nbytes.update(conv_bytes(w, layers))

@@ -236,7 +236,7 @@ int lsam_set_fused_step(lsam_ctx* ctx, int32_t on);
 
 /* Which kernels serve layer `layer` (0-based) of this context, for reports that attribute time
  * and work to kernel classes without restating the library's choices.  `info` [host] gets
- * LSAM_LAYER_INFO_FIELDS (6) values, `n` its capacity:
+ * LSAM_LAYER_INFO_FIELDS (8) values, `n` its capacity:
  *   [0] LSAM_LAYER_DENSE (GEMM kernels), LSAM_LAYER_HEAD (the two fused kernels of a narrow fp32
  *       classifier head), LSAM_LAYER_CONV_FIRST (first-layer convolution kernels),
  *       LSAM_LAYER_CONV_DIRECT (GEMM that unfolds the image on the fly), LSAM_LAYER_CONV_STORED
@@ -245,8 +245,11 @@ int lsam_set_fused_step(lsam_ctx* ctx, int32_t on);
  *   [2] 0: both weight gradients are stored; 1: fused path, norm from a weight-gradient product
  *       whose result is only summed; 2: fused path, norm from the Gram matrices of its factors
  *   [3] rows of its matrix products (B, or B H W of the layer's output for a convolution)
- *   [4], [5] columns of its weight matrix (fan-in) and its outputs */
-#define LSAM_LAYER_INFO_FIELDS 6
+ *   [4], [5] columns of its weight matrix (fan-in) and its outputs
+ *   [6] channels its projection shortcut reads (0: the layer closes no block with a projection;
+ *       then three more products of [3] rows, [6] columns and [5] outputs belong to the layer)
+ *   [7] pixel step of that projection (2: it reads every second pixel, through a gather) */
+#define LSAM_LAYER_INFO_FIELDS 8
 #define LSAM_LAYER_DENSE 0
 #define LSAM_LAYER_HEAD 1
 #define LSAM_LAYER_CONV_FIRST 2

@@ -1727,6 +1727,8 @@ int lsam_layer_info(lsam_ctx* c, int32_t layer, int32_t* info, int32_t n) {
   info[3] = (int32_t)rows;
   info[4] = ly.in;
   info[5] = ly.out;
+  info[6] = ly.proj ? ly.proj_in : 0;
+  info[7] = ly.proj ? lo.conv[layer].skip_step : 0;
   return LSAM_OK;
 }
 

@@ -294,8 +294,9 @@ class Lsam:
         return tau.tolist(), cnt.tolist(), ty.value
 
     def lsam_layer_info(self, layer):
-        """(kind, dx_stored, norm_route, rows, fan_in, out) of layer `layer`; see include/lsam.h."""
-        out = np.zeros(6, dtype=np.int32)
+        """(kind, dx_stored, norm_route, rows, fan_in, out, projection channels, projection step)
+        of layer `layer`; see include/lsam.h."""
+        out = np.zeros(8, dtype=np.int32)
         _check(lib().lsam_layer_info(self._h, layer, out.ctypes.data, out.size))
         return tuple(int(v) for v in out)
 

@@ -256,6 +256,10 @@ def _bn_away_from_zero(w, init):
     for l, (b0, b1, b2) in model.bn_offsets.items():
         init[b0:b1] = 0.25
         init[b1:b2] = np.where(np.arange(b1 - b0) % 2 == 0, 1.5, -1.5)
+    # a projection shortcut adds its own normalised values: same sign per channel as the main branch
+    for l, (p0, p1, p2, p3, p4) in model.proj_offsets.items():
+        init[p2:p3] = 0.25
+        init[p3:p4] = np.where(np.arange(p4 - p3) % 2 == 0, 1.5, -1.5)
     return init
 
 
@@ -302,5 +306,43 @@ def test_resnet20_full_size_one_step_against_the_oracle(natural):
             close_enough(g2[o1:o2], ora.last_g2[0][o1:o2], tol_g, "db%d" % (l + 1))
     ex = close_enough(eng.lsam_get_params(i), ora.get_params(0), tol_x, "x after one step")
     print("resnet20 full size, natural=%s: worst weight-gradient error %.2e, parameters %.2e" % (natural, worst, ex))
+    assert eng.lsam_sync() == 0
+    eng.close()
+
+
+@pytest.mark.parametrize("name,batch", [("resnet18", 16), ("resnet34", 8)])
+def test_resnet18_and_34_full_model_one_step_against_the_oracle(name, batch):
+    # ResNet-18 / ResNet-34 with every layer at its real shape (32x32x3 images, stages of 64 to
+    # 512 channels, projection shortcuts where a stage begins, 4 workers) at a batch the oracle
+    # finishes in half a minute for one replica (it needs 1.7 s per sample and pass here).  The
+    # GPU steps all four replicas, the oracle follows the last one.  Normalisation parameters
+    # that keep ReLU decisions away from zero, as in the ResNet-20 test above, so that gradients
+    # can be held to 2e-3 group by group, the projection's own included.
+    w = workloads.WORKLOADS[name].scaled(batch=batch)
+    init = _bn_away_from_zero(w, workloads.init_params(w))
+    cfg, keep = lsam.config_from_workload(w)
+    eng = lsam.Lsam(cfg, init, device=DEV, keep=keep)
+    loss = torch.zeros(w.K, dtype=torch.float32, device=DEV)
+    X, lab = workloads.batch(w, 0)
+    eng.lsam_step(torch.from_numpy(X).to(DEV), torch.from_numpy(lab).to(DEV), loss)
+    gl, norms = loss.cpu().numpy(), eng.lsam_get_norms()
+    i = w.K - 1
+    ora = oracle_from(w.scaled(K=1, tau=(w.tau[i],)), init)
+    ol = ora.step(X[i:i + 1], lab[i:i + 1])
+    assert abs(gl[i] - ol[0]) <= 1e-5 * abs(ol[0])
+    assert abs(norms[i] - ora.last_norm[0]) <= 1e-3 * ora.last_norm[0]
+    g2 = eng.lsam_get_buffer(lsam.BUF_GRAD, i)
+    worst = 0.0
+    for l, (o0, o1, o2) in enumerate(ora.model.offsets):
+        worst = max(worst, close_enough(g2[o0:o1], ora.last_g2[0][o0:o1], 2e-3, "dW%d" % (l + 1)))
+        if l in ora.model.bn_offsets:
+            b0, b1, b2 = ora.model.bn_offsets[l]
+            close_enough(g2[b0:b2], ora.last_g2[0][b0:b2], 2e-3, "dgamma, dbeta %d" % (l + 1))
+        if l in ora.model.proj_offsets:
+            p0, p1, p2, p3, p4 = ora.model.proj_offsets[l]
+            worst = max(worst, close_enough(g2[p0:p1], ora.last_g2[0][p0:p1], 2e-3, "dW_p %d" % (l + 1)))
+            close_enough(g2[p2:p4], ora.last_g2[0][p2:p4], 2e-3, "dgamma_p, dbeta_p %d" % (l + 1))
+    ex = close_enough(eng.lsam_get_params(i), ora.get_params(0), 1e-5, "x after one step")
+    print("%s, batch %d: worst weight-gradient error %.2e, parameters %.2e" % (name, batch, worst, ex))
     assert eng.lsam_sync() == 0
     eng.close()

@@ -1206,7 +1206,7 @@ def test_layer_info_reports_which_kernels_serve_a_layer():
     # fp32 MLP with a narrow head: GEMM layers, then the fused head kernels; gradients stored
     t = table(workloads.WORKLOADS["cfg1"])
     assert [r[0] for r in t] == [lsam.LAYER_DENSE, lsam.LAYER_HEAD] and all(r[2] == 0 for r in t)
-    assert t[0][3:] == (32, 784, 128)
+    assert t[0][3:] == (32, 784, 128, 0, 0)
     # bf16 MLP: fused path; the Gram route only where 2 B (out + in) <= out in
     w = workloads.WORKLOADS["cfg3"].scaled(K=2, dims=(384, 256, 256, 40), batch=32, tau=(2, 3), n_classes=40)
     assert [r[2] for r in table(w)] == [2, 2, 1] and [r[2] for r in table(w.scaled(rho=0.0))] == [0, 0, 0]

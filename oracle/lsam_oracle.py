@@ -237,12 +237,26 @@ class Cnn:
     convolution l in the flat vector.  global_avg_pool: the dense layers read the
     mean of the last image over its positions, one value per channel.
 
+    preact = 1 gives the pre-activation blocks of wide residual networks (Zagoruyko and
+    Komodakis, "Wide Residual Networks"; the Experiments section trains WRN-16/28/40 x 10): the
+    sum of a block is taken on the convolutions' outputs before any normalisation, and the
+    normalisation and ReLU of convolution l act on that sum, u_l = conv_l(a_{l-1}) + b_l
+    [+ shortcut], a_l = relu(bn_l(u_l)).  The shortcut of a block closed by convolution l is
+    u_{l-2}, the sum two convolutions below (shapes must agree), or, with bit l of proj_mask, a
+    1x1 convolution (block stride, bias, no normalisation) of a_{l-2}, the normalised and
+    rectified block input, as that paper's networks use where a block changes shape; its
+    parameters are W_p [C_{l+1}, C_{l-1}] and b_p only.  Read this way the network's first
+    normalisation is the stem's, each block's two normalisations are those of the convolution
+    below its first and of its first convolution, and the last convolution's is the one in
+    front of the pooling.
+
       Z[b,i,j,o] = b[o] + sum_{u,v,c} Xpad[b,s i+u,s j+v,c] W[o,u,v,c]     (Xpad: X with a zero rim, s: stride)
       P[b,i,j,c] = max_{u,v in {0,1}} A[b,2i+u,2j+v,c]
     The pool's gradient goes to the first maximal element of each window in (u, v) order."""
 
     def __init__(self, dims, n_conv, img_h, img_w, pool_mask, bn_mask=0, bn_eps=1e-5, gemm_dtype=0,
-                 stride_mask=0, skip_mask=0, global_avg_pool=0, proj_mask=0):
+                 stride_mask=0, skip_mask=0, global_avg_pool=0, proj_mask=0, preact=0):
+        self.preact = int(preact)
         self.bn_mask, self.bn_eps = int(bn_mask), float(bn_eps)
         self.stride_mask, self.skip_mask = int(stride_mask), int(skip_mask)
         self.proj_mask = int(proj_mask)
@@ -275,9 +289,10 @@ class Cnn:
                 off += 2 * fo
             if l < self.n_conv and (self.proj_mask >> l) & 1:
                 cs = self.dims[l - 1]
-                self.proj_offsets[l] = (off, off + fo * cs, off + fo * cs + fo, off + fo * cs + 2 * fo,
-                                        off + fo * cs + 3 * fo)
-                off += fo * cs + 3 * fo
+                nb = 0 if self.preact else fo        # a pre-activation projection has no normalisation
+                self.proj_offsets[l] = (off, off + fo * cs, off + fo * cs + fo, off + fo * cs + fo + nb,
+                                        off + fo * cs + fo + 2 * nb)
+                off += fo * cs + fo + 2 * nb
         self.d = off
         self.last_margin = np.inf
 
@@ -315,7 +330,7 @@ class Cnn:
         B = X.shape[0]
         self.last_margin = np.inf
         # ---- forward ----
-        conv_in, conv_act, pooled_from, conv_src = [], [], [], []
+        conv_in, conv_act, pooled_from, conv_src, raw = [], [], [], [], []
         A = X
         for l in range(self.n_conv):
             o0, o1, o2 = self.offsets[l]
@@ -331,6 +346,19 @@ class Cnn:
             for u in range(3):
                 for v in range(3):
                     Z += Apq[:, u:u + st * h:st, v:v + st * w:st, :] @ Wq[:, u, v, :].T
+            if self.preact and (self.skip_mask >> l) & 1:
+                if l in self.proj_offsets:
+                    p0, p1, p2, _, _ = self.proj_offsets[l]
+                    S = conv_src[l - 1]
+                    if S.shape[1] != h:
+                        S = S[:, ::2, ::2, :]
+                    proj_saved[l] = (S,)
+                    Z = Z + q(S) @ q(x[p0:p1].reshape(cout, S.shape[3])).T + x[p1:p2]
+                else:
+                    if raw[l - 2].shape != Z.shape:
+                        raise ValueError("shortcut and block output do not fit")
+                    Z = Z + raw[l - 2]
+            raw.append(Z)
             if l in self.bn_offsets:
                 g0, g1, g2 = self.bn_offsets[l]
                 mu = Z.mean(axis=(0, 1, 2))
@@ -339,7 +367,9 @@ class Cnn:
                 Xh = (Z - mu) * inv
                 bn_saved[l] = (Xh, inv)
                 Z = x[g0:g1] * Xh + x[g1:g2]
-            if l in self.proj_offsets:
+            if self.preact:
+                pass
+            elif l in self.proj_offsets:
                 p0, p1, p2, p3, p4 = self.proj_offsets[l]
                 S = conv_src[l - 1]
                 if S.shape[1] != h:
@@ -404,6 +434,7 @@ class Cnn:
             bh, bw = final_image.shape[1], final_image.shape[2]
             dA = np.broadcast_to(dA[:, None, None, :] / (bh * bw), final_image.shape)
         skip_grad = {}       # layer whose input receives it -> gradient of the shortcut
+        raw_grad = {}        # pre-activation blocks: layer whose sum u_l receives it -> gradient
         for l in range(self.n_conv - 1, -1, -1):
             o0, o1, o2 = self.offsets[l]
             cin, cout = self.dims[l], self.dims[l + 1]
@@ -419,7 +450,9 @@ class Cnn:
             else:
                 dR = dA.reshape(B, h, w, cout)
             dZc = dR * (R > 0.0)
-            if l in self.proj_offsets:
+            if self.preact:
+                pass
+            elif l in self.proj_offsets:
                 # through the projection's normalisation and 1x1 convolution, back to the block input
                 p0, p1, p2, p3, p4 = self.proj_offsets[l]
                 S, Xhp, invp = proj_saved[l]
@@ -451,6 +484,26 @@ class Cnn:
                 grad[g0:g1] = dgamma
                 grad[g1:g2] = dbeta
                 dZc = x[g0:g1] * inv * (dZc - dbeta / n - Xh * dgamma / n)
+            if self.preact:
+                # dZc is the gradient of the sum u_l: add what the block above sent down its
+                # identity shortcut, then hand this block's own shortcut its share
+                if l in raw_grad:
+                    dZc = dZc + raw_grad.pop(l)
+                if l in self.proj_offsets:
+                    p0, p1, p2, _, _ = self.proj_offsets[l]
+                    (S,) = proj_saved[l]
+                    du = dZc.reshape(-1, cout)
+                    grad[p0:p1] = (q(du).T @ q(S.reshape(-1, S.shape[3]))).ravel()
+                    grad[p1:p2] = du.sum(axis=0)
+                    dSu = q(dZc) @ q(x[p0:p1].reshape(cout, S.shape[3]))
+                    spread = np.zeros(conv_src[l - 1].shape)
+                    if spread.shape[1] != h:
+                        spread[:, ::2, ::2, :] = dSu
+                    else:
+                        spread[...] = dSu
+                    skip_grad[l - 1] = ("full", spread)
+                elif (self.skip_mask >> l) & 1:
+                    raw_grad[l - 2] = dZc
             Wl = x[o0:o1].reshape(cout, 3, 3, cin)
             Ap = conv_in[l]
             hin, win = Ap.shape[1] - 2, Ap.shape[2] - 2
@@ -517,7 +570,7 @@ def normals_from_counters(counter, key):
     return out
 
 
-def langevin_noise(dims, d_raw, replica, step, seed, shapes=None, bn_mask=0, proj_mask=0):
+def langevin_noise(dims, d_raw, replica, step, seed, shapes=None, bn_mask=0, proj_mask=0, preact=0):
     """xi for one replica and step, in the flat parameter layout.  `shapes`: (fan_in, out) per
     layer when they are not the consecutive pairs of `dims` (convolutional layers: a filter
     bank [out, 3, 3, C] is the matrix [out, 9 C]).  The pieces of layer l carry the codes
@@ -537,7 +590,9 @@ def langevin_noise(dims, d_raw, replica, step, seed, shapes=None, bn_mask=0, pro
         if (bn_mask >> l) & 1:
             pieces += [(8 * l + 2, 1, fo), (8 * l + 3, 1, fo)]
         if (proj_mask >> l) & 1:
-            pieces += [(8 * l + 4, fo, dims[l - 1]), (8 * l + 5, 1, fo), (8 * l + 6, 1, fo), (8 * l + 7, 1, fo)]
+            pieces += [(8 * l + 4, fo, dims[l - 1]), (8 * l + 5, 1, fo)]
+            if not preact:
+                pieces += [(8 * l + 6, 1, fo), (8 * l + 7, 1, fo)]
         for which, rows, cols in pieces:
             cg = np.arange((cols + 3) // 4, dtype=np.uint64)[None, :]
             rr = np.arange(rows, dtype=np.uint64)[:, None]
@@ -564,7 +619,7 @@ class LsamOracle:
                  lambda0=0.5, lambda_abs=-1.0, nesterov=1, tau=None, tau_min=1, tau_max=1,
                  sched_seed=0, sched_mode=SCHED_FIXED, algorithm=ALG_LSAM, noise_scale=0.0,
                  noise_seed=0, n_conv=0, img_h=0, img_w=0, pool_mask=0, bn_mask=0, bn_eps=1e-5,
-                 stride_mask=0, skip_mask=0, global_avg_pool=0, proj_mask=0):
+                 stride_mask=0, skip_mask=0, global_avg_pool=0, proj_mask=0, preact=0):
         self.K = int(K)
         self.algorithm = int(algorithm)
         self.noise_scale, self.noise_seed = float(noise_scale), int(noise_seed)
@@ -572,12 +627,13 @@ class LsamOracle:
         self.t = 0                      # sampler steps taken so far
         if n_conv:
             self.model = Cnn(dims, n_conv, img_h, img_w, pool_mask, bn_mask, bn_eps, gemm_dtype,
-                             stride_mask, skip_mask, global_avg_pool, proj_mask)
+                             stride_mask, skip_mask, global_avg_pool, proj_mask, preact)
         else:
             self.model = Mlp(dims, gemm_dtype) if len(dims) else None
         self.shapes = self.model.shapes if n_conv else None
         self.bn_mask = int(bn_mask) if n_conv else 0
         self.proj_mask = int(proj_mask) if n_conv else 0
+        self.preact = int(preact) if n_conv else 0
         self.d = self.model.d if self.model else int(d_raw)
         self.batch = int(batch)
         self.rho, self.gamma = float(rho), float(gamma)
@@ -635,7 +691,7 @@ class LsamOracle:
             self.x[i] = self.x[i] - self.lr * self.v[i]
         if self.noise_scale != 0.0:
             xi = langevin_noise(self.dims, self.d, i, self.t, self.noise_seed, self.shapes, self.bn_mask,
-                                self.proj_mask)
+                                self.proj_mask, self.preact)
             self.x[i] = self.x[i] + self.noise_scale * np.sqrt(2.0 * self.lr) * xi
         self.S[i] += self.x[i]
 

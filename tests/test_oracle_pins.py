@@ -1218,6 +1218,171 @@ def test_torch_witness_catches_a_mistake_in_the_projection(case, monkeypatch):
             (3, 8, 6, 4, 4, 4, 8, 8, 5), 7, 8, 4, 0b0100000, 0b1010100, 0b1000100, 2)
 
 
+# ---- pre-activation blocks (wide residual networks) ------------------------------------------------
+def _torch_wrn_loss(xt, X, lab, stem, blocks, classes, bn_eps=1e-5, prod=None):
+    """A wide residual network written block by block the way Zagoruyko and Komodakis describe
+    it, with torch's routines: stem convolution; per block  o = relu(bn1(x)),
+    y = conv2(relu(bn2(conv1(o)))), result = y + (x if the shapes agree else conv1x1(o));
+    after the last block relu(bn(x)), mean over the pixels, dense layer.  `blocks` lists
+    (channels, stride) per block.  Parameters are read from xt in the order of the flat layout:
+    a block's bn1 belongs to the convolution below its first (stem or the previous block's
+    second), bn2 to its first convolution, the 1x1 convolution follows the second convolution
+    and that one's normalisation (the bn1 of the next block, or the final one).
+    prod: the product routine for the bf16 variant (convolutions by F.unfold), None = float64."""
+    import torch.nn.functional as F
+    B = X.shape[0]
+    pos = [0]
+
+    def take(n):
+        v = xt[pos[0]:pos[0] + n]
+        pos[0] += n
+        return v
+
+    def conv3(a, cin, cout, stride):
+        Wt = take(cout * 9 * cin).reshape(cout, 3, 3, cin)
+        b = take(cout)
+        if prod is None:
+            return F.conv2d(a, Wt.permute(0, 3, 1, 2), b, padding=1, stride=stride)
+        h, w = a.shape[2] // stride, a.shape[3] // stride
+        cols = F.unfold(a, 3, padding=1, stride=stride).transpose(1, 2).reshape(B * h * w, 9 * cin)
+        z = prod(cols, Wt.permute(0, 3, 1, 2).reshape(cout, 9 * cin)) + b
+        return z.reshape(B, h, w, cout).permute(0, 3, 1, 2)
+
+    def bn_relu(z, c):
+        g, be = take(c), take(c)
+        return F.relu(F.batch_norm(z, None, None, g, be, training=True, eps=bn_eps))
+
+    x = conv3(torch.tensor(X).permute(0, 3, 1, 2), X.shape[3], stem, 1)
+    cin = stem
+    o = bn_relu(x, cin)                                  # bn1 of the first block
+    for c, stride in blocks:
+        y = conv3(o, cin, c, stride)
+        y = bn_relu(y, c)                                # bn2
+        y = conv3(y, c, c, 1)
+        # the flat layout has the second convolution's normalisation before the 1x1 convolution
+        g_next, b_next = take(c), take(c)
+        if cin != c or stride != 1:
+            Wp, bp = take(c * cin).reshape(c, cin), take(c)
+            src = o[:, :, ::stride, ::stride]
+            if prod is None:
+                sc = F.conv2d(o, Wp.reshape(c, cin, 1, 1), bp, stride=stride)
+            else:
+                hh, ww = src.shape[2], src.shape[3]
+                sc = (prod(src.permute(0, 2, 3, 1).reshape(B * hh * ww, cin), Wp) + bp)
+                sc = sc.reshape(B, hh, ww, c).permute(0, 3, 1, 2)
+        else:
+            sc = x
+        x = y + sc
+        o = F.relu(F.batch_norm(x, None, None, g_next, b_next, training=True, eps=bn_eps))
+        cin = c
+    a = o.mean(dim=(2, 3))
+    Wd, bd = take(classes * cin).reshape(classes, cin), take(classes)
+    logits = (a @ Wd.T if prod is None else prod(a, Wd)) + bd
+    assert pos[0] == xt.numel()
+    return F.cross_entropy(logits, torch.tensor(lab))
+
+
+def _wrn_masks(stem, blocks):
+    """dims and masks of the layered description for the same network."""
+    dims, stride, skip, proj = [stem], 0, 0, 0
+    cin, l = stem, 1
+    for c, st in blocks:
+        if st == 2:
+            stride |= 1 << l
+        skip |= 1 << (l + 1)
+        if cin != c or st != 1:
+            proj |= 1 << (l + 1)
+        dims += [c, c]
+        cin = c
+        l += 2
+    return dims, l, stride, skip, proj
+
+
+_WRN_CASES = [
+    # widening without stride, identity, widening with stride, identity (a small WRN-10-like net)
+    (4, [(8, 1), (8, 1), (16, 2), (16, 1)], 8, 4, 2, 5),
+    # one identity block only
+    (4, [(4, 1)], 4, 4, 3, 3),
+    # two strided blocks in a row on a wide image
+    (2, [(4, 2), (6, 2)], 8, 12, 2, 4),
+]
+
+
+@pytest.mark.parametrize("stem,blocks,H,W,B,classes", _WRN_CASES)
+@pytest.mark.parametrize("bf16", [0, 1])
+def test_preactivation_network_matches_torch(stem, blocks, H, W, B, classes, bf16):
+    from oracle.lsam_oracle import Cnn
+    dims, n_conv, stride, skip, proj = _wrn_masks(stem, blocks)
+    dims = (3,) + tuple(dims) + (classes,)
+    m = Cnn(dims, n_conv, H, W, 0, (1 << n_conv) - 1, 1e-5, bf16, stride, skip, 1, proj, preact=1)
+    rng = np.random.default_rng(17)
+    x = (rng.standard_normal(m.d) * 0.3).astype(np.float32).astype(np.float64)
+    for l, (g0, g1, g2) in m.bn_offsets.items():
+        x[g0:g1] = (1.0 + 0.3 * rng.standard_normal(g1 - g0)).astype(np.float32)
+    X = rng.standard_normal((B, H, W, 3)).astype(np.float32).astype(np.float64)
+    lab = rng.integers(0, classes, B)
+    loss, g = m.loss_and_grad(x, X, lab)
+    xt = torch.tensor(x, requires_grad=True)
+    L = _torch_wrn_loss(xt, X, lab, stem, blocks, classes, prod=_torch_rounded_product() if bf16 else None)
+    L.backward()
+    assert abs(loss - L.item()) < 1e-12
+    assert np.max(np.abs(g - xt.grad.numpy())) / np.max(np.abs(g)) < 1e-10
+    # a pre-activation projection has a weight and a bias only, and every convolution bias, the
+    # projection's included, is cancelled by a normalisation further up
+    for l, (p0, p1, p2, p3, p4) in m.proj_offsets.items():
+        assert p2 == p3 == p4 and np.max(np.abs(g[p0:p1])) > 1e-6
+        assert np.max(np.abs(g[p1:p2])) < 1e-12
+    for l in range(n_conv):
+        o0, o1, o2 = m.offsets[l]
+        assert np.max(np.abs(g[o1:o2])) < 1e-12
+
+
+def test_preactivation_network_gradient_matches_finite_differences():
+    from oracle.lsam_oracle import Cnn
+    stem, blocks, H, W, B, classes = _WRN_CASES[0]
+    dims, n_conv, stride, skip, proj = _wrn_masks(stem, blocks)
+    m = Cnn((3,) + tuple(dims) + (classes,), n_conv, H, W, 0, (1 << n_conv) - 1, 1e-5, 0, stride, skip, 1, proj,
+            preact=1)
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal(m.d) * 0.4
+    X = rng.standard_normal((B, H, W, 3))
+    lab = rng.integers(0, classes, B)
+    _, g = m.loss_and_grad(x, X, lab)
+    h = 1e-6
+    for j in rng.choice(m.d, 60, replace=False):
+        e = np.zeros(m.d)
+        e[j] = h
+        fd = (m.loss_and_grad(x + e, X, lab)[0] - m.loss_and_grad(x - e, X, lab)[0]) / (2 * h)
+        assert abs(fd - g[j]) < 1e-6 * max(1.0, np.max(np.abs(g))), j
+
+
+_PREACT_MISTAKES = [
+    ("Z = Z + q(S) @ q(x[p0:p1].reshape(cout, S.shape[3])).T + x[p1:p2]",
+     "Z = Z + S @ q(x[p0:p1].reshape(cout, S.shape[3])).T + x[p1:p2]"),
+    ("Z = Z + raw[l - 2]", "Z = Z + conv_src[l - 1]"),                 # the activated input instead of the sum
+    ("                    dZc = dZc + raw_grad.pop(l)", "                    raw_grad.pop(l)"),
+    ("raw_grad[l - 2] = dZc", "raw_grad[l - 2] = dR * (R > 0.0)"),     # the gradient in front of the normalisation
+    ("grad[p0:p1] = (q(du).T @ q(S.reshape(-1, S.shape[3]))).ravel()",
+     "grad[p0:p1] = (du.T @ q(S.reshape(-1, S.shape[3]))).ravel()"),
+    ("dSu = q(dZc) @ q(x[p0:p1].reshape(cout, S.shape[3]))", "dSu = q(dZc) @ x[p0:p1].reshape(cout, S.shape[3])"),
+    ("spread[:, ::2, ::2, :] = dSu", "spread[:, 1::2, 1::2, :] = dSu"),
+]
+
+
+@pytest.mark.parametrize("case", range(len(_PREACT_MISTAKES)))
+def test_torch_witness_catches_a_mistake_in_the_preactivation_blocks(case, monkeypatch):
+    import types
+    import oracle.lsam_oracle as real
+    old, new = _PREACT_MISTAKES[case]
+    src = open(real.__file__).read()
+    assert src.count(old) == 1, "the oracle no longer contains: " + old
+    planted = types.ModuleType("planted_oracle")
+    exec(compile(src.replace(old, new, 1), "planted_oracle", "exec"), planted.__dict__)
+    monkeypatch.setattr(real, "Cnn", planted.Cnn)
+    with pytest.raises((AssertionError, ValueError)):
+        test_preactivation_network_matches_torch(*_WRN_CASES[0], 1)
+
+
 def test_residual_model_gradient_matches_finite_differences():
     from oracle.lsam_oracle import Cnn
     m = Cnn((2, 4, 8, 8, 3), 3, 4, 4, 0, 0b111, 1e-5, 0, 0b010, 0b100, 1)

@@ -65,6 +65,14 @@
  * b_p, gamma_p, beta_p [C_{l+1}] follow those of the closing convolution l in the flat layout;
  * b_p, like b_l, cannot influence the loss and its gradient is reported as exactly zero.  Any
  * channel counts (multiples of 8) are allowed on both sides of a projection.
+ * preact = 1 reads the same layer list as the pre-activation blocks of wide residual networks
+ * (Zagoruyko and Komodakis, "Wide Residual Networks"; Section "Experiments" trains WRN-16x10,
+ * WRN-28x10 and WRN-40x10): a block's sum is taken on convolution outputs before any
+ * normalisation, u_l = conv_l(a_{l-1}) + b_l [+ shortcut], a_l = relu(bn_l(u_l)); the shortcut of
+ * the block closed by convolution l is u_{l-2} (same shape required) or, with bit l of proj_mask,
+ * a 1x1 convolution (block stride, bias, no normalisation) of a_{l-2}, whose parameters are W_p
+ * and b_p only.  Every convolution must be batch-normalised; then no convolution bias, b_p
+ * included, influences the loss, and their gradients are reported as exactly zero.
  */
 #ifndef LSAM_H
 #define LSAM_H
@@ -150,6 +158,8 @@ typedef struct {
                              1x1 convolution with batch normalisation; see below            */
   int32_t global_avg_pool; /* 1: the dense layers read the mean of the last image over its
                              positions (one value per channel) instead of the flattened image */
+  int32_t preact;         /* 1: residual blocks are pre-activation blocks (wide residual
+                             networks); see below                                      */
 } lsam_config;
 
 /* Which per-replica buffer `lsam_get_buffer` copies out. */

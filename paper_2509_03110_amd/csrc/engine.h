@@ -256,6 +256,8 @@ struct ShortcutDesc {
 // stats[k] = (mean, 1/sqrt(var + eps)) per channel of Z [K][rows][C]; scratch as for launch_bn_forward.
 int launch_bn_stats(const float* Z, float* scratch, float* stats, int K, int64_t rows, int C, float eps,
                     hipStream_t s);
+// dst[i] += src[i] for i < n (n % 4 == 0; both 16-byte aligned, not overlapping).
+int launch_add_into(float* dst, const float* src, int64_t n, hipStream_t s);
 // dst[img][i][j][c] = src[img][2 i][2 j][c] for `images` images [2H][2W][C] (C % 4 == 0).
 int launch_subsample2(const float* src, float* dst, int64_t images, int H, int W, int C, hipStream_t s);
 int bn_chunks(int64_t rows, int C, int K);

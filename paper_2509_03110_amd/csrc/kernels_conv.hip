@@ -654,6 +654,14 @@ __global__ __launch_bounds__(kThreads) void subsample2_kernel(const float* __res
   *reinterpret_cast<f32x4*>(dst + idx * 4) = *reinterpret_cast<const f32x4*>(src + at);
 }
 
+// dst += src, element by element (n a multiple of 4, both 16-byte aligned).
+__global__ __launch_bounds__(kThreads) void add_into_kernel(float* __restrict__ dst,
+                                                            const float* __restrict__ src, long long words) {
+  const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= words) return;
+  *reinterpret_cast<f32x4*>(dst + idx * 4) += *reinterpret_cast<const f32x4*>(src + idx * 4);
+}
+
 // Global average pooling: P[k][b][c] = mean over the H W positions of A[k][b][.][.][c] (summed
 // in position order), P rows of pitch ldp; and its backward pass fused with the ReLU the image
 // came from: dA[k][b][i][j][c] = dP[k][b][c] / (H W) where A > 0 (mask null: everywhere).
@@ -829,6 +837,12 @@ int launch_bn_stats(const float* Z, float* scratch, float* stats, int K, int64_t
       Z, pmean, pm2, rows, C, chunks, pl.chunk_rows);
   bn_stats_finish_kernel<<<dim3((unsigned)((C + 63) / 64), (unsigned)K), 64 * kBnChains, 0, s>>>(
       pmean, pm2, stats, rows, C, chunks, pl.chunk_rows, eps);
+  return 0;
+}
+
+int launch_add_into(float* dst, const float* src, int64_t n, hipStream_t s) {
+  if (n < 4 || n % 4) return -1;
+  add_into_kernel<<<blocks_for(n / 4), kThreads, 0, s>>>(dst, src, n / 4);
   return 0;
 }
 

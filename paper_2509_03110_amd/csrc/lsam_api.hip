@@ -158,6 +158,7 @@ struct ConvLayer {
 struct Layout {
   int K = 0, L = 0, B = 0;
   int n_conv = 0;              // layers 0..n_conv-1 are convolutions
+  bool preact = false;         // residual blocks sum un-normalised convolution outputs (wide residual networks)
   std::vector<ConvLayer> conv;
   size_t dcol = 0;             // gradient of an unfolded image (largest layer that needs one)
   size_t gram1 = 0, gram2 = 0; // bf16 dense model: Gram matrices [K][B][ldg] of a layer's dZ and of its input
@@ -210,8 +211,8 @@ int check_config(const lsam_config* c) {
       return fail(LSAM_EINVAL, "n_conv=%d must leave at least one dense layer of %d", c->n_conv,
                   c->n_layers);
     if (c->n_conv == 0 && c->bn_mask) return fail(LSAM_EINVAL, "bn_mask needs convolution layers");
-    if (c->n_conv == 0 && (c->stride_mask || c->skip_mask || c->proj_mask || c->global_avg_pool))
-      return fail(LSAM_EINVAL, "stride_mask, skip_mask, proj_mask and global_avg_pool need convolution layers");
+    if (c->n_conv == 0 && (c->stride_mask || c->skip_mask || c->proj_mask || c->global_avg_pool || c->preact))
+      return fail(LSAM_EINVAL, "stride_mask, skip_mask, proj_mask, global_avg_pool and preact need convolution layers");
     if (c->n_conv > 0) {
       if (c->img_h < 1 || c->img_w < 1) return fail(LSAM_EINVAL, "img_h, img_w must be >= 1");
       if (c->bn_mask >> c->n_conv) return fail(LSAM_EINVAL, "bn_mask names a layer that is no convolution");
@@ -222,6 +223,9 @@ int check_config(const lsam_config* c) {
         return fail(LSAM_EINVAL, "proj_mask names a layer that closes no residual block");
       if (c->global_avg_pool != 0 && c->global_avg_pool != 1)
         return fail(LSAM_EINVAL, "global_avg_pool must be 0 or 1");
+      if (c->preact != 0 && c->preact != 1) return fail(LSAM_EINVAL, "preact must be 0 or 1");
+      if (c->preact && c->bn_mask != ((1ull << c->n_conv) - 1))
+        return fail(LSAM_EINVAL, "pre-activation blocks need every convolution batch-normalised");
       int64_t h = c->img_h, w = c->img_w;
       int64_t in_h[LSAM_MAX_LAYERS + 1], in_w[LSAM_MAX_LAYERS + 1];   // image each convolution reads
       for (int l = 0; l < c->n_conv; ++l) {
@@ -244,8 +248,10 @@ int check_config(const lsam_config* c) {
             return fail(LSAM_EINVAL, "convolution %d: no pool may sit inside a residual block or in front of it", l);
           const int64_t sh = in_h[l - 1], sw = in_w[l - 1];
           const bool proj = ((c->proj_mask >> l) & 1u) != 0;
+          // (a pre-activation block without projection adds two sums of the same shape)
           if (!((sh == h && sw == w) || (sh == 2 * h && sw == 2 * w)) ||
-              (!proj && c->dims[l - 1] > c->dims[l + 1]) || c->dims[l - 1] % (proj ? 8 : 4))
+              (!proj && c->dims[l - 1] > c->dims[l + 1]) || c->dims[l - 1] % (proj ? 8 : 4) ||
+              (c->preact && !proj && (sh != h || sw != w || c->dims[l - 1] != c->dims[l + 1])))
             return fail(LSAM_EINVAL, "convolution %d: the block input (%lldx%lldx%d) does not fit the block output (%lldx%lldx%d)",
                         l, (long long)sh, (long long)sw, c->dims[l - 1], (long long)h, (long long)w, c->dims[l + 1]);
         }
@@ -308,6 +314,7 @@ void build_layout(const lsam_config& c, Layout& lo) {
     lo.d_pad = round_up(c.d_raw, 64);
   } else {
     lo.n_conv = c.n_conv;
+    lo.preact = c.n_conv > 0 && c.preact != 0;
     // width[l]: columns of the matrix layer l reads (l < L), of the logits (l = L)
     std::vector<int> width(lo.L + 1);
     {
@@ -379,7 +386,7 @@ void build_layout(const lsam_config& c, Layout& lo) {
         int64_t* slot[3] = {&s.pb_off, &s.pgam_off, &s.pbet_off};
         lo.pieces.push_back(Piece{s.pw_off, flat, s.out, s.proj_in, s.proj_in, 8 * l + 4});
         flat += (int64_t)s.out * s.proj_in;
-        for (int q = 0; q < 3; ++q) {
+        for (int q = 0; q < (lo.preact ? 1 : 3); ++q) {
           *slot[q] = off;
           lo.pieces.push_back(Piece{off, flat, 1, s.out, (int)round_up(s.out, 4), 8 * l + 5 + q});
           off = round_up(off + s.out, 64);
@@ -470,7 +477,7 @@ void build_layout(const lsam_config& c, Layout& lo) {
       if (cv.proj) {
         cv.psub = take(cur, (size_t)lo.K * cv.rows * cv.skip_C * 4);
         cv.pz = take(cur, full);
-        cv.pstats = take(cur, (size_t)lo.K * 2 * cv.Cout * 4);
+        if (!lo.preact) cv.pstats = take(cur, (size_t)lo.K * 2 * cv.Cout * 4);
       }
       if (l > 0 && !cv.direct_dx) dcol_bytes = std::max(dcol_bytes, (size_t)lo.K * cv.rows * cv.ldc * 4);
     }
@@ -720,18 +727,32 @@ int conv_forward(lsam_ctx* c, const float* X, const float* params) {
         LaunchTimer t(c, KC_GEMM_FWD);
         if (launch_gemm(d, s) != 0) return fail(LSAM_EINVAL, "projection of convolution %d rejected", l);
       }
-      LaunchTimer t(c, KC_BATCHNORM);
-      if (launch_bn_stats(c->at<float>(cv.pz), c->at<float>(lo.colsum), c->at<float>(cv.pstats), lo.K,
-                          cv.rows, cv.Cout, c->cfg.bn_eps, s) != 0)
-        return fail(LSAM_EINVAL, "projection of convolution %d: statistics rejected", l);
+      if (lo.preact) {
+        // the bare projection joins the convolution's output in front of the normalisation
+        LaunchTimer t(c, KC_POOL);
+        if (launch_add_into(c->at<float>(cv.z), c->at<float>(cv.pz), (int64_t)lo.K * cv.rows * cv.Cout, s) != 0)
+          return fail(LSAM_EINVAL, "projection of convolution %d: sum rejected", l);
+      } else {
+        LaunchTimer t(c, KC_BATCHNORM);
+        if (launch_bn_stats(c->at<float>(cv.pz), c->at<float>(lo.colsum), c->at<float>(cv.pstats), lo.K,
+                            cv.rows, cv.Cout, c->cfg.bn_eps, s) != 0)
+          return fail(LSAM_EINVAL, "projection of convolution %d: statistics rejected", l);
+      }
+    } else if (cv.skip && lo.preact) {
+      // identity shortcut of a pre-activation block: the sum two convolutions below
+      LaunchTimer t(c, KC_POOL);
+      if (launch_add_into(c->at<float>(cv.z), c->at<float>(lo.conv[l - 2].z), (int64_t)lo.K * cv.rows * cv.Cout,
+                          s) != 0)
+        return fail(LSAM_EINVAL, "shortcut of convolution %d: sum rejected", l);
     }
     if (cv.bn) {
       LaunchTimer t(c, KC_BATCHNORM);
       ShortcutDesc sc{};
-      if (cv.proj) {
+      const bool post_sum = cv.skip && !lo.preact;     // the shortcut joins behind the normalisation
+      if (post_sum && cv.proj) {
         sc.pz = c->at<float>(cv.pz); sc.pstats = c->at<float>(cv.pstats);
         sc.pgam_off = ly.pgam_off; sc.pbet_off = ly.pbet_off;
-      } else if (cv.skip) {
+      } else if (post_sum) {
         // the block input: what convolution l-1 read, i.e. the ReLU output of convolution l-2
         sc.src = c->at<float>(lo.conv[l - 2].out);
         sc.stride = lo.conv[l - 2].rows * cv.skip_C;
@@ -739,7 +760,7 @@ int conv_forward(lsam_ctx* c, const float* X, const float* params) {
       }
       if (launch_bn_forward(c->at<float>(cv.z), c->at<float>(lo.colsum), c->at<float>(cv.stats), params,
                             lo.d_pad, ly.gam_off, ly.bet_off, c->at<float>(cv.out), lo.K, cv.rows,
-                            cv.Cout, c->cfg.bn_eps, cv.skip ? &sc : nullptr, s) != 0)
+                            cv.Cout, c->cfg.bn_eps, post_sum ? &sc : nullptr, s) != 0)
         return fail(LSAM_EINVAL, "batch normalisation of convolution %d rejected", l);
     }
     in = c->at<float>(cv.out);
@@ -815,10 +836,10 @@ int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq,
       }
       // A block's closing convolution keeps dY: it is also the gradient of the shortcut, added
       // to the block input's gradient further down.  Its dZ goes where Z was (Z is not needed again).
-      float* dz = cv.skip ? c->at<float>(cv.z) : dout;
+      float* dz = (cv.skip && !lo.preact) ? c->at<float>(cv.z) : dout;
       launch_bn_backward_apply(c->at<float>(cv.z), dout, dz, c->at<float>(cv.stats), params, g, lo.d_pad,
                                ly.gam_off, ly.bet_off, lo.K, cv.rows, cv.Cout, s);
-      if (cv.proj) {
+      if (cv.proj && !lo.preact) {
         // the same gradient dY enters the projection's normalisation: dgamma_p, dbeta_p, then
         // the gradient of the 1x1 convolution's output, which takes that output's place
         float* pz = c->at<float>(cv.pz);
@@ -836,10 +857,18 @@ int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq,
       }
       dout = dz;
     }
+    if (lo.preact && l + 2 < lo.n_conv && lo.conv[l + 2].skip && !lo.conv[l + 2].proj) {
+      // this convolution's sum is the identity shortcut of the block above: that block's sum
+      // hands its gradient (complete since its own backward pass) down unchanged
+      LaunchTimer t(c, KC_POOL);
+      if (launch_add_into(dout, c->at<float>(lo.conv[l + 2].dout), (int64_t)lo.K * cv.rows * cv.Cout, s) != 0)
+        return fail(LSAM_EINVAL, "shortcut into convolution %d: sum rejected", l);
+    }
     if (cv.proj) {
       // dW_p = dZ_p^T S and dS = dZ_p W_p; dS replaces the gathered pixels and reaches the block
-      // input's gradient once the block's opening convolution has written that gradient
-      const float* dzp = c->at<float>(cv.pz);
+      // input's gradient once the block's opening convolution has written that gradient.  In a
+      // pre-activation block the projection's output gradient is the sum's own.
+      const float* dzp = lo.preact ? dout : c->at<float>(cv.pz);
       float* psub = c->at<float>(cv.psub);
       {
         GemmDesc d{};
@@ -958,7 +987,7 @@ int conv_backward(lsam_ctx* c, const float* X, const float* params, double* ssq,
                          cv.stride, s) != 0)
         return fail(LSAM_EINVAL, "fold of convolution %d rejected", l);
     }
-    if (l + 1 < lo.n_conv && lo.conv[l + 1].skip) {
+    if (l + 1 < lo.n_conv && lo.conv[l + 1].skip && (lo.conv[l + 1].proj || !lo.preact)) {
       // this convolution opened a residual block: the gradient of the block output (kept by the
       // closing convolution) also reaches the block input through the shortcut
       const ConvLayer& top = lo.conv[l + 1];

@@ -45,7 +45,7 @@ class lsam_config(C.Structure):
         ("n_conv", C.c_int32), ("img_h", C.c_int32), ("img_w", C.c_int32),
         ("bn_eps", C.c_float), ("pool_mask", C.c_uint64), ("bn_mask", C.c_uint64),
         ("stride_mask", C.c_uint64), ("skip_mask", C.c_uint64), ("proj_mask", C.c_uint64),
-        ("global_avg_pool", C.c_int32),
+        ("global_avg_pool", C.c_int32), ("preact", C.c_int32),
     ]
 
 
@@ -143,7 +143,7 @@ def make_config(K, dims=(), d_raw=0, batch=0, gemm_dtype=GEMM_FP32, rho=0.05, ga
                 nesterov=1, tau=None, tau_min=1, tau_max=1, sched_seed=0,
                 sched_mode=SCHED_FIXED, algorithm=ALG_LSAM, noise_scale=0.0, noise_seed=0,
                 n_conv=0, img_h=0, img_w=0, pool_mask=0, bn_mask=0, bn_eps=1e-5, stride_mask=0,
-                skip_mask=0, global_avg_pool=0, proj_mask=0):
+                skip_mask=0, global_avg_pool=0, proj_mask=0, preact=0):
     """Fills an lsam_config; returns (config, keepalive) -- keep `keepalive` referenced while
     the config is in use (it owns the dims / tau arrays the struct points to)."""
     cfg = lsam_config()
@@ -171,7 +171,7 @@ def make_config(K, dims=(), d_raw=0, batch=0, gemm_dtype=GEMM_FP32, rho=0.05, ga
     cfg.n_conv, cfg.img_h, cfg.img_w, cfg.pool_mask = n_conv, img_h, img_w, pool_mask
     cfg.bn_mask, cfg.bn_eps = bn_mask, bn_eps
     cfg.stride_mask, cfg.skip_mask, cfg.global_avg_pool = stride_mask, skip_mask, global_avg_pool
-    cfg.proj_mask = proj_mask
+    cfg.proj_mask, cfg.preact = proj_mask, preact
     return cfg, keep
 
 
@@ -184,7 +184,7 @@ def config_from_workload(w, **over):
               noise_seed=w.noise_seed, n_conv=w.n_conv, img_h=w.img_h, img_w=w.img_w,
               pool_mask=w.pool_mask, bn_mask=w.bn_mask, bn_eps=w.bn_eps,
               stride_mask=w.stride_mask, skip_mask=w.skip_mask, global_avg_pool=w.global_avg_pool,
-              proj_mask=w.proj_mask)
+              proj_mask=w.proj_mask, preact=w.preact)
     kw.update(over)
     return make_config(**kw)
 

@@ -18,7 +18,7 @@ import torch
 
 import workloads
 from paper_2509_03110_amd import lsam
-from util import close_enough, oracle_from, rel_max
+from util import bn_away_from_zero, close_enough, oracle_from, rel_max
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -245,22 +245,7 @@ def test_vgg16_reduced_batch_against_oracle_and_full_batch_properties(name, tol)
     eng.close()
 
 
-def _bn_away_from_zero(w, init):
-    """Every normalised layer gets gamma = 0.25 and beta = +1.5 (even channels) or -1.5 (odd
-    channels): normalised values lie within about four standard deviations, so a channel is
-    either positive everywhere (its ReLU passes everything; shortcuts only add non-negative
-    values to it) or negative everywhere (dead, and the shortcut into it comes from a dead
-    channel as well), and almost no ReLU decision is taken near zero."""
-    init = init.copy()
-    model = oracle_from(w.scaled(K=1, tau=(1,)), init).model
-    for l, (b0, b1, b2) in model.bn_offsets.items():
-        init[b0:b1] = 0.25
-        init[b1:b2] = np.where(np.arange(b1 - b0) % 2 == 0, 1.5, -1.5)
-    # a projection shortcut adds its own normalised values: same sign per channel as the main branch
-    for l, (p0, p1, p2, p3, p4) in model.proj_offsets.items():
-        init[p2:p3] = 0.25
-        init[p3:p4] = np.where(np.arange(p4 - p3) % 2 == 0, 1.5, -1.5)
-    return init
+_bn_away_from_zero = bn_away_from_zero
 
 
 @pytest.mark.parametrize("natural", [False, True])

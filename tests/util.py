@@ -13,7 +13,7 @@ def oracle_from(w, init, **over):
               algorithm=w.algorithm, noise_scale=w.noise_scale, noise_seed=w.noise_seed,
               n_conv=w.n_conv, img_h=w.img_h, img_w=w.img_w, pool_mask=w.pool_mask,
               bn_mask=w.bn_mask, bn_eps=w.bn_eps, stride_mask=w.stride_mask,
-              skip_mask=w.skip_mask, global_avg_pool=w.global_avg_pool, proj_mask=w.proj_mask)
+              skip_mask=w.skip_mask, global_avg_pool=w.global_avg_pool, proj_mask=w.proj_mask, preact=w.preact)
     kw.update(over)
     return LsamOracle(**kw)
 
@@ -51,3 +51,21 @@ def close_enough(a, b, tol, what):
     assert fr <= 2e-3, "%s: %.2e of the elements are off by more than %.1e (max %.3e)" % (what, fr, tol, mx)
     assert mx <= 100 * tol, "%s: worst element off by %.3e" % (what, mx)
     return max(l2, mx if fr == 0.0 else l2)
+
+
+def bn_away_from_zero(w, init):
+    """Every normalised layer gets gamma = 0.25 and beta = +1.5 (even channels) or -1.5 (odd
+    channels): normalised values lie within about four standard deviations, so a channel is
+    either positive everywhere (its ReLU passes everything; shortcuts only add non-negative
+    values to it) or negative everywhere (dead, and the shortcut into it comes from a dead
+    channel as well), and almost no ReLU decision is taken near zero."""
+    init = init.copy()
+    model = oracle_from(w.scaled(K=1, tau=(1,)), init).model
+    for l, (b0, b1, b2) in model.bn_offsets.items():
+        init[b0:b1] = 0.25
+        init[b1:b2] = np.where(np.arange(b1 - b0) % 2 == 0, 1.5, -1.5)
+    # a normalised projection shortcut adds its own values: same sign per channel as the main branch
+    for l, (p0, p1, p2, p3, p4) in model.proj_offsets.items():
+        init[p2:p3] = 0.25
+        init[p3:p4] = np.where(np.arange(p4 - p3) % 2 == 0, 1.5, -1.5)
+    return init

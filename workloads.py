@@ -61,6 +61,8 @@ class Workload:
                                             # output of convolution l before its ReLU (basic block)
     proj_mask: int = 0                      # bit l (with skip_mask): that shortcut is a 1x1 convolution
                                             # with batch normalisation (projection), C_{l-1} -> C_{l+1}
+    preact: int = 0                         # 1: pre-activation blocks (sums before the normalisations;
+                                            # a projection is a bare 1x1 convolution of the rectified input)
     global_avg_pool: int = 0                # 1: the dense layers read the per-channel mean of the last image
     steps: int = 20
     data_seed: int = 0
@@ -96,7 +98,7 @@ class Workload:
         if not self.dims:
             return self.d_raw
         return sum(fi * fo + fo + (2 * fo if (self.bn_mask >> l) & 1 and l < self.n_conv else 0) +
-                   (fo * self.dims[l - 1] + 3 * fo if (self.proj_mask >> l) & 1 else 0)
+                   (fo * self.dims[l - 1] + (1 if self.preact else 3) * fo if (self.proj_mask >> l) & 1 else 0)
                    for l, (fi, fo) in enumerate(self.layer_shapes))
 
     def scaled(self, **kw) -> "Workload":
@@ -190,6 +192,37 @@ def _basic_block_net(name, blocks, widths, classes, **kw):
 # size; the paper does not say which it uses).  4 workers, batch 128, communication interval 16.
 WORKLOADS["resnet18"] = _basic_block_net("resnet18", (2, 2, 2, 2), (64, 128, 256, 512), 10, data_seed=12)
 WORKLOADS["resnet34"] = _basic_block_net("resnet34", (3, 4, 6, 3), (64, 128, 256, 512), 100, data_seed=13)
+
+
+def _wide_resnet(name, depth, k, classes, **kw):
+    """WRN-depth x k of Zagoruyko and Komodakis: a 3x3 stem of 16 channels, three stages of
+    (depth - 4) / 6 pre-activation basic blocks with 16 k, 32 k and 64 k channels, stages two and
+    three starting with stride 2; a 1x1 convolution as the shortcut where a block changes
+    shape (the first block of every stage); normalisation, ReLU, global average pooling and
+    one dense layer at the end.  No dropout."""
+    n = (depth - 4) // 6
+    dims, stride, skip, proj = [3, 16], 0, 0, 0
+    l = 1
+    for s, c in enumerate((16 * k, 32 * k, 64 * k)):
+        for b in range(n):
+            if b == 0:
+                proj |= 1 << (l + 1)
+                if s > 0:
+                    stride |= 1 << l
+            skip |= 1 << (l + 1)
+            dims += [c, c]
+            l += 2
+    return Workload(name, K=4, dims=tuple(dims) + (classes,), batch=128, n_conv=l, img_h=32, img_w=32,
+                    bn_mask=(1 << l) - 1, stride_mask=stride, skip_mask=skip, proj_mask=proj, preact=1,
+                    global_avg_pool=1, rho=0.1, lr=0.1, tau=(16, 16, 16, 16), steps=20, n_classes=classes,
+                    batch_pool=2, **kw)
+
+
+# The wide residual networks of the Experiments section: WRN-16x10 (CIFAR-10), WRN-28x10 and
+# WRN-40x10 (CIFAR-100); 4 workers, batch 128, communication interval 16.
+WORKLOADS["wrn16x10"] = _wide_resnet("wrn16x10", 16, 10, 10, data_seed=14)
+WORKLOADS["wrn28x10"] = _wide_resnet("wrn28x10", 28, 10, 100, data_seed=15)
+WORKLOADS["wrn40x10"] = _wide_resnet("wrn40x10", 40, 10, 100, data_seed=16)
 # the same model with bf16 matrix products (tensors stay fp32; see the boundary's gemm_dtype)
 WORKLOADS["vgg16bf"] = replace(WORKLOADS["vgg16"], name="vgg16bf", gemm_dtype=1)
 
@@ -220,8 +253,9 @@ def init_params(w: Workload, seed: Optional[int] = None) -> np.ndarray:
             bound = np.float32(1.0 / np.sqrt(cs))
             parts.append((rng.random(out * cs, dtype=np.float32) * 2 - 1) * bound)
             parts.append((rng.random(out, dtype=np.float32) * 2 - 1) * bound)
-            parts.append(1 + (rng.random(out, dtype=np.float32) - np.float32(0.5)) * np.float32(0.2))
-            parts.append((rng.random(out, dtype=np.float32) - np.float32(0.5)) * np.float32(0.2))
+            if not w.preact:
+                parts.append(1 + (rng.random(out, dtype=np.float32) - np.float32(0.5)) * np.float32(0.2))
+                parts.append((rng.random(out, dtype=np.float32) - np.float32(0.5)) * np.float32(0.2))
     return np.concatenate(parts).astype(np.float32)
 
 
@@ -248,7 +282,7 @@ def init_params_margin(w: Workload, seed: Optional[int] = None, ratio: float = 8
         if l < w.n_conv and (w.bn_mask >> l) & 1:
             off += 2 * out
         if (w.proj_mask >> l) & 1:
-            off += out * w.dims[l - 1] + 3 * out
+            off += out * w.dims[l - 1] + (1 if w.preact else 3) * out
     return p
 
 

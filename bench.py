@@ -129,10 +129,19 @@ def conv_bytes(w, layers):
             # output is read once more where the two branches meet; the gather for a strided
             # one reads and writes the pixels it keeps; backward, the gradient of those pixels
             # is added to the block input's gradient under that input's mask (3 reads, 1 write)
-            bn += rows * cout * 4.0 * (1 + 1 + 2 + 3)
+            # (a pre-activation block's bare projection is added to the convolution's output
+            # instead: two reads and a write)
+            if w.preact:
+                pool += rows * cout * 4.0 * 3
+            else:
+                bn += rows * cout * 4.0 * (1 + 1 + 2 + 3)
             if proj_step == 2:
                 unfold += rows * proj_c * 4.0 * 2
             pool += rows * proj_c * 4.0 * 4
+        elif (w.skip_mask >> l) & 1 and w.preact:
+            # identity shortcut of a pre-activation block: the sum two convolutions below is added
+            # to this one's (forward), this one's gradient to that one's (backward)
+            pool += rows * cout * 4.0 * (3 + 3)
         elif (w.skip_mask >> l) & 1:
             # shortcut: read with the normalisation (forward); backward reads dY, the mask and the
             # block input's gradient and writes the latter

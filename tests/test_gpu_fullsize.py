@@ -295,7 +295,7 @@ def test_resnet20_full_size_one_step_against_the_oracle(natural):
     eng.close()
 
 
-@pytest.mark.parametrize("name,batch", [("resnet18", 16), ("resnet34", 8)])
+@pytest.mark.parametrize("name,batch", [("resnet18", 16), ("resnet34", 8), ("wrn16x10", 4), ("wrn40x10", 2)])
 def test_resnet18_and_34_full_model_one_step_against_the_oracle(name, batch):
     # ResNet-18 / ResNet-34 with every layer at its real shape (32x32x3 images, stages of 64 to
     # 512 channels, projection shortcuts where a stage begins, 4 workers) at a batch the oracle
@@ -303,6 +303,9 @@ def test_resnet18_and_34_full_model_one_step_against_the_oracle(name, batch):
     # GPU steps all four replicas, the oracle follows the last one.  Normalisation parameters
     # that keep ReLU decisions away from zero, as in the ResNet-20 test above, so that gradients
     # can be held to 2e-3 group by group, the projection's own included.
+    # The wide residual networks WRN-16x10 and WRN-40x10 (pre-activation blocks, 160 to 640
+    # channels, 14 resp. 38 weight layers) the same way at batch 4 resp. 2: 10 s per sample and
+    # pass in the oracle.  (WRN-28x10 lies between the two and has no shape of its own.)
     w = workloads.WORKLOADS[name].scaled(batch=batch)
     init = _bn_away_from_zero(w, workloads.init_params(w))
     cfg, keep = lsam.config_from_workload(w)
@@ -326,7 +329,8 @@ def test_resnet18_and_34_full_model_one_step_against_the_oracle(name, batch):
         if l in ora.model.proj_offsets:
             p0, p1, p2, p3, p4 = ora.model.proj_offsets[l]
             worst = max(worst, close_enough(g2[p0:p1], ora.last_g2[0][p0:p1], 2e-3, "dW_p %d" % (l + 1)))
-            close_enough(g2[p2:p4], ora.last_g2[0][p2:p4], 2e-3, "dgamma_p, dbeta_p %d" % (l + 1))
+            if p4 > p2:      # (a pre-activation projection has no normalisation)
+                close_enough(g2[p2:p4], ora.last_g2[0][p2:p4], 2e-3, "dgamma_p, dbeta_p %d" % (l + 1))
     ex = close_enough(eng.lsam_get_params(i), ora.get_params(0), 1e-5, "x after one step")
     print("%s, batch %d: worst weight-gradient error %.2e, parameters %.2e" % (name, batch, worst, ex))
     assert eng.lsam_sync() == 0

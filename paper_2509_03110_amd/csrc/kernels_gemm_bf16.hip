@@ -189,6 +189,7 @@ template <> struct Out<__bf16> {
 //   EPI_ASCEND  weight gradient of the first pass, recomputed once the norm is known: write
 //               the operand copy of the perturbed weights, bf16(x + scale * g)
 enum { EPI_STORE = 0, EPI_STEP = 1, EPI_SUMSQ = 2, EPI_ASCEND = 3 };
+constexpr int kStepGroup = 4;      // EPI_STEP: side of the tile groups an XCD takes through all replicas
 
 template <typename TC, int BM, int BN, int NSTAGE, bool A_KMAJOR, bool B_KMAJOR, int OCC, int MODE = EPI_STORE>
 __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams p) {
@@ -205,17 +206,37 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
   __shared__ __attribute__((aligned(1024))) unsigned char st3[NSTAGE == 4 ? STAGE_BYTES : 1024];
 
   const int w = blockIdx.x;
-  const int logical = (w % 8) * p.chunks + w / 8;    // contiguous tile range per XCD
-  if (logical >= p.total) return;
-  constexpr int GROUP_M = 8;
-  const int per_rep = p.tilesM * p.tilesN;
-  const int bat = logical / per_rep;
-  const int t_in = logical - bat * per_rep;
-  const int band = t_in / (GROUP_M * p.tilesN);
-  const int first_m = band * GROUP_M;
-  const int gsize = p.tilesM - first_m < GROUP_M ? p.tilesM - first_m : GROUP_M;
-  const int tin = t_in - band * GROUP_M * p.tilesN;
-  const int m0 = (first_m + tin % gsize) * BM, n0 = (tin / gsize) * BN;
+  int bat, m0, n0, t_in = 0;
+  if constexpr (MODE == EPI_STEP) {
+    // The step reads the centre y, which all replicas share: an XCD takes whole groups of
+    // kStepGroup x kStepGroup tiles and works through the replicas of one group before it
+    // moves to the next, so that the group's piece of y comes from memory once per XCD and
+    // from that XCD's L2 for the other replicas (replica-major order fetched it once per
+    // replica).  chunks = workgroups per XCD = groups per XCD * batch * tiles per group; tiles
+    // of a ragged group that fall outside the matrix leave at once.
+    constexpr int G = kStepGroup;
+    const int idx = w / 8;
+    const int t = idx % (G * G);
+    const int rest = idx / (G * G);
+    bat = rest % p.batch;
+    const int group = (rest / p.batch) * 8 + (w % 8);
+    const int groupsN = (p.tilesN + G - 1) / G;
+    const int tm = (group / groupsN) * G + t % G, tn = (group % groupsN) * G + t / G;
+    if (tm >= p.tilesM || tn >= p.tilesN) return;
+    m0 = tm * BM; n0 = tn * BN;
+  } else {
+    const int logical = (w % 8) * p.chunks + w / 8;    // contiguous tile range per XCD
+    if (logical >= p.total) return;
+    constexpr int GROUP_M = 8;
+    const int per_rep = p.tilesM * p.tilesN;
+    bat = logical / per_rep;
+    t_in = logical - bat * per_rep;
+    const int band = t_in / (GROUP_M * p.tilesN);
+    const int first_m = band * GROUP_M;
+    const int gsize = p.tilesM - first_m < GROUP_M ? p.tilesM - first_m : GROUP_M;
+    const int tin = t_in - band * GROUP_M * p.tilesN;
+    m0 = (first_m + tin % gsize) * BM; n0 = (tin / gsize) * BN;
+  }
 
   const __bf16* A = reinterpret_cast<const __bf16*>(p.A) + (long long)bat * p.strideA;
   const __bf16* B = reinterpret_cast<const __bf16*>(p.B) + (long long)bat * p.strideB;
@@ -568,6 +589,11 @@ int launch_one(const Bf16GemmParams& p0, hipStream_t s, int* slots) {
   if constexpr (sizeof(TC) == 4 && !AK && !BK_) {
     // the fused epilogues exist for weight-gradient launches (both operands m-major) only
     if (p.mode == EPI_STEP) {
+      const long long groups = (long long)((p.tilesM + kStepGroup - 1) / kStepGroup) *
+                               ((p.tilesN + kStepGroup - 1) / kStepGroup);
+      const long long per_xcd = (groups + 7) / 8 * p.batch * kStepGroup * kStepGroup;
+      if (per_xcd * 8 >= (1ll << 31)) return -1;
+      p.chunks = (int)per_xcd;
       gemm_bf16_kernel<TC, BM, BN, NSTAGE, AK, BK_, OCC, EPI_STEP><<<p.chunks * 8, kThreads, 0, s>>>(p);
       if (slots) *slots = 0;
       return 0;

@@ -32,33 +32,49 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "dc6fe7f589e4d611"
+TRAFFIC_SOURCES = "37fdf659f11305b1"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 2151595, "center": 100986368, "descent": 538490880, "gemm_dw": 43604829,
-             "gemm_dx": 42146133, "gemm_fwd": 62123008, "perturb": 201945771},
-    "cfg3": {"bias_grad": 13682027, "center": 1773570816, "descent": 883866, "gemm_dw_ascend":
-             667498257, "gemm_dw_norm": 30883556, "gemm_dw_step": 3165084860, "gemm_dx":
-             250126400, "gemm_fwd": 233870669, "softmax_ce": 1428821},
-    "cfg4": {"center": 3200044672, "descent": 25600046037, "perturb": 9600050859,
-             "sumsq_partials": 3416298229},
-    "cfg5": {"bias_grad": 118025778, "descent": 3481527, "gemm_dw_ascend": 7042551333,
-             "gemm_dw_norm": 1333559570, "gemm_dw_step": 28891494345, "gemm_dx": 2333172907,
-             "gemm_fwd": 2034185839, "softmax_ce": 95815579},
-    "cnn5": {"bias_grad": 17357404, "conv_first": 80448981, "descent": 79476736, "gemm_dw":
-             67379730, "gemm_dx": 34806101, "gemm_fwd": 38356749, "perturb": 29813760, "pool":
-             68582500},
-    "cnn5bn": {"batchnorm": 157832220, "bias_grad": 565845, "conv_first": 80450528, "descent":
-             79542272, "gemm_dw": 67383520, "gemm_dx": 34806101, "gemm_fwd": 38355482, "perturb":
-             29838336, "pool": 68582265},
-    "resnet20": {"batchnorm": 86672327, "descent": 34871296, "gemm_dw": 212855069, "gemm_dx":
-             269489085, "gemm_fwd": 100370211, "perturb": 13086720, "pool": 64190801,
-             "unfold_fold": 328636392},
-    "vgg16": {"batchnorm": 175735471, "bias_grad": 1094784, "conv_first": 155184192, "descent":
-             1952546048, "gemm_dw": 140515626, "gemm_dx": 16980139, "gemm_fwd": 137906665,
-             "perturb": 732214869, "pool": 89623913},
-    "vgg16bf": {"batchnorm": 175702069, "bias_grad": 1014282, "conv_first": 155193632, "descent":
-             1952546005, "gemm_dw": 129611248, "gemm_dx": 12106752, "gemm_fwd": 135410792,
-             "perturb": 732214784, "pool": 89623930, "softmax_ce": 114005},
+    "cfg2": {"bias_grad": 2151595, "center": 100978176, "descent": 538490880, "gemm_dw": 43594029,
+             "gemm_dx": 42146133, "gemm_fwd": 62123072, "perturb": 201945472},
+    "cfg3": {"bias_grad": 13682005, "center": 1773558016, "descent": 884002, "gemm_dw_ascend":
+             667733333, "gemm_dw_norm": 17540907, "gemm_dw_step": 3027554347, "gemm_dx":
+             250134747, "gemm_fwd": 138154321, "softmax_ce": 1428971},
+    "cfg4": {"center": 3200036352, "descent": 25600039125, "perturb": 9600050944,
+             "sumsq_partials": 3417305024},
+    "cfg5": {"bias_grad": 117996999, "descent": 3479838, "gemm_dw_ascend": 7032758437,
+             "gemm_dw_norm": 152154795, "gemm_dw_step": 28458556294, "gemm_dx": 2333230020,
+             "gemm_fwd": 1161966463, "softmax_ce": 95782464},
+    "cnn5": {"bias_grad": 17357404, "conv_first": 80461280, "descent": 79476736, "gemm_dw":
+             67384807, "gemm_dx": 34806101, "gemm_fwd": 38358093, "perturb": 29813760, "pool":
+             68586084},
+    "cnn5bn": {"batchnorm": 157827634, "bias_grad": 565845, "conv_first": 80450987, "descent":
+             79542272, "gemm_dw": 67411118, "gemm_dx": 34806101, "gemm_fwd": 38355716, "perturb":
+             29838336, "pool": 68585842},
+    "resnet18": {"batchnorm": 259999014, "conv_first": 155253739, "descent": 1430962389,
+             "gemm_dw": 308412332, "gemm_dx": 178723324, "gemm_fwd": 231058508, "perturb":
+             536623659, "pool": 183890656, "unfold_fold": 218021625},
+    "resnet20": {"batchnorm": 86667721, "descent": 34871296, "gemm_dw": 212796341, "gemm_dx":
+             269461656, "gemm_fwd": 100363162, "perturb": 13086720, "pool": 64194118,
+             "unfold_fold": 328684334},
+    "resnet34": {"batchnorm": 244146758, "bias_grad": 352128, "conv_first": 155197611, "descent":
+             2731188480, "gemm_dw": 264957997, "gemm_dx": 153663454, "gemm_fwd": 215831534,
+             "perturb": 1024209365, "pool": 195406034, "softmax_ce": 474709, "unfold_fold":
+             218021549},
+    "vgg16": {"batchnorm": 175730851, "bias_grad": 1094784, "conv_first": 155198411, "descent":
+             1952538965, "gemm_dw": 140538518, "gemm_dx": 16980139, "gemm_fwd": 137951731,
+             "perturb": 732214741, "pool": 89627475},
+    "vgg16bf": {"batchnorm": 175697435, "bias_grad": 1014282, "conv_first": 155199637, "descent":
+             1952538965, "gemm_dw": 129603442, "gemm_dx": 12106752, "gemm_fwd": 135424216,
+             "perturb": 732214741, "pool": 89627503, "softmax_ce": 114027},
+    "wrn16x10": {"batchnorm": 736317762, "descent": 2191769685, "gemm_dw": 1860330520, "gemm_dx":
+             549296461, "gemm_fwd": 1309050691, "perturb": 821926912, "pool": 441879848,
+             "unfold_fold": 629743096},
+    "wrn28x10": {"batchnorm": 760369421, "bias_grad": 350293, "descent": 4678181376, "gemm_dw":
+             1946464138, "gemm_dx": 458426105, "gemm_fwd": 1426855670, "perturb": 1754332800,
+             "pool": 508961017, "softmax_ce": 474453, "unfold_fold": 629743061},
+    "wrn40x10": {"batchnorm": 768820178, "bias_grad": 350293, "descent": 7157212885, "gemm_dw":
+             2025269276, "gemm_dx": 458408199, "gemm_fwd": 1485178121, "perturb": 2683971072,
+             "pool": 533675093, "softmax_ce": 474795, "unfold_fold": 629743005},
 }
 
 

@@ -19,6 +19,7 @@
 // The MFMA is issued with the roles swapped (rows <- B operand, columns <- A operand), so
 // that a lane ends up with 4 consecutive n of one row m: 16-byte stores in the epilogue.
 #include <atomic>
+#include <type_traits>
 
 #include "engine.h"
 
@@ -89,6 +90,14 @@ constexpr unsigned kOob = 0x7FFFFFF0u;   // byte offset past any operand: load r
 // conflicts; now none.)
 template <int UE>
 __device__ __forceinline__ int swz(int r) { return r ^ ((r / (2 * UE)) & (UE - 1)); }
+// The same for tiles of 8-byte units (fp32 operands rounded to bfloat16 on their way into LDS).
+// A 64-bit LDS access is served 16 lanes at a time.  The MFMA reads put 16 lanes on 16
+// consecutive rows: 128 contiguous bytes under any permutation inside groups of four.  The
+// transposing writes put lane i on row 4 i + e, 32 bytes apart, so lanes four apart meet on the
+// same banks unless their permutations differ: bits of r / 16.  The k-major writes put 8 lanes
+// on the 8 k-units of a row and the next 8 on the next row; with a k-unit pitch of R + 2 units
+// (2 mod 16) the first 8 take the even 8-byte slots and the second 8 the odd ones.
+__device__ __forceinline__ int swz_half(int r) { return r ^ ((r / 16) & 3); }
 
 // Loads one operand tile (R rows x BKU units of 16 bytes: 16*BKU bytes of k per k-step) from
 // global memory into registers and writes it to LDS laid out as units [BKU][R + 1].
@@ -286,6 +295,46 @@ struct TileLoader {
       }
     }
   }
+
+  // The same tile (fp32 in registers) written as bfloat16: units of 8 bytes, four k each, at the
+  // same unit positions.  For the arithmetic mode that rounds fp32 operands on their way into
+  // the matrix unit: rounding here instead of after the LDS read halves the LDS traffic.
+  __device__ __forceinline__ void store(u32x2* __restrict__ lds, int tid) const {
+    static_assert(UE == 4, "fp32 operands");
+    if constexpr (KMAJOR) {
+#pragma unroll
+      for (int j = 0; j < NUNITS; ++j) {
+        const int u = tid + kThreads * j;
+        lds[(u % BKU) * (R + 2) + swz_half(u / BKU)] = round4(__builtin_bit_cast(f32x4, reg[j]));
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < NBLK; ++j) {
+        const int b = tid + kThreads * j;
+        if (NBLK_TOTAL % kThreads == 0 || b < NBLK_TOTAL) {
+          const int mg = b % (R / UE), kb = b / (R / UE);
+          // round each loaded row (one k, four m), then transpose the 4x4 block of halfwords
+          u32x2 c[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) c[q] = round4(__builtin_bit_cast(f32x4, reg[j * 4 + q]));
+#pragma unroll
+          for (int e = 0; e < UE; ++e) {
+            const unsigned sel = (e & 1) ? 0x07060302u : 0x05040100u;   // odd / even halfwords of {hi, lo}
+            u32x2 unit;
+            unit[0] = __builtin_amdgcn_perm(c[1][e / 2], c[0][e / 2], sel);
+            unit[1] = __builtin_amdgcn_perm(c[3][e / 2], c[2][e / 2], sel);
+            lds[kb * (R + 2) + swz_half(mg * UE + e)] = unit;
+          }
+        }
+      }
+    }
+  }
+  static __device__ __forceinline__ u32x2 round4(const f32x4& v) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 lo = {static_cast<__bf16>(v[0]), static_cast<__bf16>(v[1])};
+    const bf16x2 hi = {static_cast<__bf16>(v[2]), static_cast<__bf16>(v[3])};
+    return u32x2{__builtin_bit_cast(unsigned, lo), __builtin_bit_cast(unsigned, hi)};
+  }
 };
 
 template <typename T> struct Pack;
@@ -348,10 +397,11 @@ __device__ __forceinline__ float widen(float v) { return v; }
 __device__ __forceinline__ float widen(__bf16 v) { return static_cast<float>(v); }
 
 // CONV: 0 = both operands stored; 1 = A is an unfolded image (k-major); 2 = B is one (m-major).
-// BF16MATH (fp32 operands only): the operands stay fp32 in memory and in LDS, but each pair of
-// k-chunks is rounded to bfloat16 in registers (round to nearest even) and fed to one
-// v_mfma_f32_32x32x16_bf16 instead of eight v_mfma_f32_32x32x2_f32 -- the rounding rule of the
-// bf16 configurations (only what enters the matrix unit is rounded) at fp32 memory traffic.
+// BF16MATH (fp32 operands only): the operands stay fp32 in memory; they are rounded to bfloat16
+// (round to nearest even) as the loaded tile is written to LDS, in units of 8 instead of 16
+// bytes, and each pair of k-chunks feeds one v_mfma_f32_32x32x16_bf16 instead of eight
+// v_mfma_f32_32x32x2_f32 -- the rounding rule of the bf16 configurations (only what enters the
+// matrix unit is rounded) at fp32 memory traffic and half the LDS traffic.
 // Which k a lane's eight values stand for does not matter as long as both operands agree: a
 // lane takes the four of its unit in the even chunk and the four of its unit in the odd one.
 template <typename T, typename TC, int BM, int BN, int BKU, bool A_KMAJOR, bool B_KMAJOR, int OCC,
@@ -361,10 +411,12 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
   static_assert(CONV == 0 || (CONV == 1 && A_KMAJOR) || (CONV == 2 && !B_KMAJOR), "operand layout");
   constexpr int UE = Op<T>::UE;
   constexpr int TM = BM / 64, TN = BN / 64;
-  constexpr int A_UNITS = BKU * (BM + 1), B_UNITS = BKU * (BN + 1);
+  constexpr int PAD = BF16MATH ? 2 : 1;          // k-unit pitch of a tile is its rows + PAD units
+  constexpr int A_UNITS = BKU * (BM + PAD), B_UNITS = BKU * (BN + PAD);
   constexpr int STAGE_UNITS = A_UNITS + B_UNITS;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  u32x4* lds = reinterpret_cast<u32x4*>(smem);
+  typedef typename std::conditional<BF16MATH, u32x2, u32x4>::type unit_t;   // one LDS unit: 4 k of a row
+  unit_t* lds = reinterpret_cast<unit_t*>(smem);
 
   // Workgroup -> tile.  Hardware deals consecutive workgroup ids round-robin over the 8
   // XCDs; remap so that each XCD walks a contiguous range of tiles (tiles that share a
@@ -445,16 +497,18 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
   // LDS read positions of this lane (k-unit `h` of each k-chunk is added per chunk)
   int posA[TM], posB[TN];
 #pragma unroll
-  for (int i = 0; i < TM; ++i) posA[i] = h * (BM + 1) + swz<UE>(wm0 + i * 32 + l32);
+  for (int i = 0; i < TM; ++i)
+    posA[i] = h * (BM + PAD) + (BF16MATH ? swz_half(wm0 + i * 32 + l32) : swz<UE>(wm0 + i * 32 + l32));
 #pragma unroll
-  for (int j = 0; j < TN; ++j) posB[j] = A_UNITS + h * (BN + 1) + swz<UE>(wn0 + j * 32 + l32);
+  for (int j = 0; j < TN; ++j)
+    posB[j] = A_UNITS + h * (BN + PAD) + (BF16MATH ? swz_half(wn0 + j * 32 + l32) : swz<UE>(wn0 + j * 32 + l32));
 
-  u32x4 fa[2][TM], fb[2][TN];
-  auto read_frags = [&](const u32x4* stage, int kc, int buf) {
+  unit_t fa[2][TM], fb[2][TN];
+  auto read_frags = [&](const unit_t* stage, int kc, int buf) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i) fa[buf][i] = stage[posA[i] + kc * 2 * (BM + 1)];
+    for (int i = 0; i < TM; ++i) fa[buf][i] = stage[posA[i] + kc * 2 * (BM + PAD)];
 #pragma unroll
-    for (int j = 0; j < TN; ++j) fb[buf][j] = stage[posB[j] + kc * 2 * (BN + 1)];
+    for (int j = 0; j < TN; ++j) fb[buf][j] = stage[posB[j] + kc * 2 * (BN + PAD)];
   };
   u32x2 ha[TM], hb[TN];     // BF16MATH: the even chunk's operands, rounded, waiting for the odd one
   auto mfma_chunk = [&](int buf) {
@@ -462,21 +516,15 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
       // chunk parity equals the fragment buffer index (an even number of chunks per k-step)
       if (buf == 0) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) ha[i] = Pack<__bf16>::from(__builtin_bit_cast(f32x4, fa[0][i]));
+        for (int i = 0; i < TM; ++i) ha[i] = fa[0][i];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) hb[j] = Pack<__bf16>::from(__builtin_bit_cast(f32x4, fb[0][j]));
+        for (int j = 0; j < TN; ++j) hb[j] = fb[0][j];
       } else {
         u32x4 qa[TM], qb[TN];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          const u32x2 hi = Pack<__bf16>::from(__builtin_bit_cast(f32x4, fa[1][i]));
-          qa[i] = u32x4{ha[i][0], ha[i][1], hi[0], hi[1]};
-        }
+        for (int i = 0; i < TM; ++i) qa[i] = u32x4{ha[i][0], ha[i][1], fa[1][i][0], fa[1][i][1]};
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const u32x2 hi = Pack<__bf16>::from(__builtin_bit_cast(f32x4, fb[1][j]));
-          qb[j] = u32x4{hb[j][0], hb[j][1], hi[0], hi[1]};
-        }
+        for (int j = 0; j < TN; ++j) qb[j] = u32x4{hb[j][0], hb[j][1], fb[1][j][0], fb[1][j][1]};
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -485,24 +533,24 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
                                                                 __builtin_bit_cast(bf16x8, qa[i]),
                                                                 acc[i][j], 0, 0, 0);
       }
-      return;
-    }
+    } else {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        if constexpr (UE == 4) {
-          const f32x4 a = __builtin_bit_cast(f32x4, fa[buf][i]);
-          const f32x4 b = __builtin_bit_cast(f32x4, fb[buf][j]);
+        for (int j = 0; j < TN; ++j) {
+          if constexpr (UE == 4) {
+            const f32x4 a = __builtin_bit_cast(f32x4, fa[buf][i]);
+            const f32x4 b = __builtin_bit_cast(f32x4, fb[buf][j]);
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[e], a[e], acc[i][j], 0, 0, 0);
-        } else {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              __builtin_bit_cast(bf16x8, fb[buf][j]), __builtin_bit_cast(bf16x8, fa[buf][i]),
-              acc[i][j], 0, 0, 0);
+            for (int e = 0; e < 4; ++e)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[e], a[e], acc[i][j], 0, 0, 0);
+          } else {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                __builtin_bit_cast(bf16x8, fb[buf][j]), __builtin_bit_cast(bf16x8, fa[buf][i]),
+                acc[i][j], 0, 0, 0);
+          }
         }
-      }
+    }
   };
 
   // Software pipeline.  At the top of k-step ks: LDS buffer ks&1 holds tile ks, the registers
@@ -524,8 +572,8 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
   read_frags(lds, 0, 0);
 
   for (int ks = 0; ks + 1 < ksteps; ++ks) {
-    const u32x4* cur = lds + (ks & 1) * STAGE_UNITS;
-    u32x4* nxt = lds + ((ks + 1) & 1) * STAGE_UNITS;
+    const unit_t* cur = lds + (ks & 1) * STAGE_UNITS;
+    unit_t* nxt = lds + ((ks + 1) & 1) * STAGE_UNITS;
 #pragma unroll
     for (int kc = 0; kc + 1 < NKC; ++kc) {
       read_frags(cur, kc + 1, (kc + 1) & 1);
@@ -546,7 +594,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmParams p) {
     if constexpr (!BF16MATH) Pipeline<ND, NV, 0x020, NM>::run();
   }
   {
-    const u32x4* cur = lds + ((ksteps - 1) & 1) * STAGE_UNITS;
+    const unit_t* cur = lds + ((ksteps - 1) & 1) * STAGE_UNITS;
 #pragma unroll
     for (int kc = 0; kc < NKC; ++kc) {
       if (kc + 1 < NKC) read_frags(cur, kc + 1, (kc + 1) & 1);
@@ -784,7 +832,8 @@ int launch_one(const GemmParams& p0, hipStream_t s, int* sumsq_slots) {
   p.tilesN = (p.N + BN - 1) / BN;
   p.total = p.tilesM * p.tilesN * p.batch * p.splits;
   p.chunks = (p.total + 7) / 8;
-  const size_t loop_smem = (size_t)2 * BKU * ((BM + 1) + (BN + 1)) * 16;
+  const size_t loop_smem = BF16MATH ? (size_t)2 * BKU * ((BM + 2) + (BN + 2)) * 8
+                                    : (size_t)2 * BKU * ((BM + 1) + (BN + 1)) * 16;
   const size_t epi_smem = (size_t)64 * (BN + 4) * 4;
   const size_t smem = loop_smem > epi_smem ? loop_smem : epi_smem;
   auto kern = gemm_kernel<T, TC, BM, BN, BKU, AK, BK_, OCC, CONV, BF16MATH>;

@@ -32,49 +32,56 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "37fdf659f11305b1"
+TRAFFIC_SOURCES = "5a0ee00049ae417d"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 2151595, "center": 100978176, "descent": 538490880, "gemm_dw": 43594029,
-             "gemm_dx": 42146133, "gemm_fwd": 62123072, "perturb": 201945472},
-    "cfg3": {"bias_grad": 13682005, "center": 1773558016, "descent": 884002, "gemm_dw_ascend":
-             667733333, "gemm_dw_norm": 17540907, "gemm_dw_step": 3027554347, "gemm_dx":
-             250134747, "gemm_fwd": 138154321, "softmax_ce": 1428971},
-    "cfg4": {"center": 3200036352, "descent": 25600039125, "perturb": 9600050944,
-             "sumsq_partials": 3417305024},
-    "cfg5": {"bias_grad": 117996999, "descent": 3479838, "gemm_dw_ascend": 7032758437,
-             "gemm_dw_norm": 152154795, "gemm_dw_step": 28458556294, "gemm_dx": 2333230020,
-             "gemm_fwd": 1161966463, "softmax_ce": 95782464},
-    "cnn5": {"bias_grad": 17357404, "conv_first": 80461280, "descent": 79476736, "gemm_dw":
-             67384807, "gemm_dx": 34806101, "gemm_fwd": 38358093, "perturb": 29813760, "pool":
-             68586084},
-    "cnn5bn": {"batchnorm": 157827634, "bias_grad": 565845, "conv_first": 80450987, "descent":
-             79542272, "gemm_dw": 67411118, "gemm_dx": 34806101, "gemm_fwd": 38355716, "perturb":
-             29838336, "pool": 68585842},
-    "resnet18": {"batchnorm": 259999014, "conv_first": 155253739, "descent": 1430962389,
-             "gemm_dw": 308412332, "gemm_dx": 178723324, "gemm_fwd": 231058508, "perturb":
-             536623659, "pool": 183890656, "unfold_fold": 218021625},
-    "resnet20": {"batchnorm": 86667721, "descent": 34871296, "gemm_dw": 212796341, "gemm_dx":
-             269461656, "gemm_fwd": 100363162, "perturb": 13086720, "pool": 64194118,
-             "unfold_fold": 328684334},
-    "resnet34": {"batchnorm": 244146758, "bias_grad": 352128, "conv_first": 155197611, "descent":
-             2731188480, "gemm_dw": 264957997, "gemm_dx": 153663454, "gemm_fwd": 215831534,
-             "perturb": 1024209365, "pool": 195406034, "softmax_ce": 474709, "unfold_fold":
-             218021549},
-    "vgg16": {"batchnorm": 175730851, "bias_grad": 1094784, "conv_first": 155198411, "descent":
-             1952538965, "gemm_dw": 140538518, "gemm_dx": 16980139, "gemm_fwd": 137951731,
-             "perturb": 732214741, "pool": 89627475},
-    "vgg16bf": {"batchnorm": 175697435, "bias_grad": 1014282, "conv_first": 155199637, "descent":
-             1952538965, "gemm_dw": 129603442, "gemm_dx": 12106752, "gemm_fwd": 135424216,
-             "perturb": 732214741, "pool": 89627503, "softmax_ce": 114027},
-    "wrn16x10": {"batchnorm": 736317762, "descent": 2191769685, "gemm_dw": 1860330520, "gemm_dx":
-             549296461, "gemm_fwd": 1309050691, "perturb": 821926912, "pool": 441879848,
-             "unfold_fold": 629743096},
-    "wrn28x10": {"batchnorm": 760369421, "bias_grad": 350293, "descent": 4678181376, "gemm_dw":
-             1946464138, "gemm_dx": 458426105, "gemm_fwd": 1426855670, "perturb": 1754332800,
-             "pool": 508961017, "softmax_ce": 474453, "unfold_fold": 629743061},
-    "wrn40x10": {"batchnorm": 768820178, "bias_grad": 350293, "descent": 7157212885, "gemm_dw":
-             2025269276, "gemm_dx": 458408199, "gemm_fwd": 1485178121, "perturb": 2683971072,
-             "pool": 533675093, "softmax_ce": 474795, "unfold_fold": 629743005},
+    "cfg2": {"bias_grad": 2151595, "center": 100978176, "descent": 538490923, "gemm_dw": 43623400,
+             "gemm_dx": 42127701, "gemm_fwd": 62107637, "perturb": 201945515},
+    "cfg3": {"bias_grad": 13682022, "center": 1773558080, "descent": 884002, "gemm_dw_ascend":
+             667643273, "gemm_dw_norm": 17540907, "gemm_dw_step": 3028864623, "gemm_dx":
+             250134720, "gemm_fwd": 138149319, "softmax_ce": 1428971},
+    "cfg4": {"center": 3200036736, "descent": 25600038741, "perturb": 9600049835,
+             "sumsq_partials": 3416029749},
+    "cfg5": {"bias_grad": 117998798, "descent": 3479936, "gemm_dw_ascend": 7047667700,
+             "gemm_dw_norm": 152180053, "gemm_dw_step": 28464209597, "gemm_dx": 2333069760,
+             "gemm_fwd": 1161927755, "softmax_ce": 95763413},
+    "cnn5": {"bias_grad": 17357404, "conv_first": 80452843, "descent": 79476736, "gemm_dw":
+             67366176, "gemm_dx": 34787669, "gemm_fwd": 38345583, "perturb": 29813760, "pool":
+             68586126},
+    "cnn5bn": {"batchnorm": 157829081, "bias_grad": 565845, "conv_first": 80449141, "descent":
+             79542272, "gemm_dw": 67378329, "gemm_dx": 34787669, "gemm_fwd": 38345698, "perturb":
+             29838336, "pool": 68585856},
+    "resnet18": {"batchnorm": 259999012, "conv_first": 155235744, "descent": 1430962091,
+             "gemm_dw": 308322700, "gemm_dx": 178780284, "gemm_fwd": 230701943, "perturb":
+             536623573, "pool": 183890656, "unfold_fold": 218021608},
+    "resnet18bf": {"batchnorm": 260000119, "bias_grad": 52992, "conv_first": 155238155, "descent":
+             1430962475, "gemm_dw": 268542490, "gemm_dx": 145318686, "gemm_fwd": 274835484,
+             "perturb": 536623659, "pool": 183890633, "softmax_ce": 114347, "unfold_fold":
+             218021608},
+    "resnet20": {"batchnorm": 86667719, "descent": 34871296, "gemm_dw": 212796629, "gemm_dx":
+             269488405, "gemm_fwd": 100366866, "perturb": 13086720, "pool": 64194124,
+             "unfold_fold": 328703022},
+    "resnet34": {"batchnorm": 244146745, "bias_grad": 352128, "conv_first": 155196011, "descent":
+             2731188480, "gemm_dw": 264905817, "gemm_dx": 153704680, "gemm_fwd": 215090053,
+             "perturb": 1024209451, "pool": 195406040, "softmax_ce": 474709, "unfold_fold":
+             218021537},
+    "vgg16": {"batchnorm": 175730853, "bias_grad": 1094766, "conv_first": 155206229, "descent":
+             1952538880, "gemm_dw": 140499656, "gemm_dx": 16961707, "gemm_fwd": 137685186,
+             "perturb": 732214784, "pool": 89627473},
+    "vgg16bf": {"batchnorm": 175697476, "bias_grad": 1014282, "conv_first": 155208608, "descent":
+             1952539136, "gemm_dw": 113798809, "gemm_dx": 12092075, "gemm_fwd": 169057665,
+             "perturb": 732214784, "pool": 89627490, "softmax_ce": 114048},
+    "wrn16x10": {"batchnorm": 736317830, "descent": 2191769771, "gemm_dw": 1858586075, "gemm_dx":
+             549476006, "gemm_fwd": 1310928629, "perturb": 821926827, "pool": 441879860,
+             "unfold_fold": 629743067},
+    "wrn16x10bf": {"batchnorm": 736317769, "bias_grad": 51755, "descent": 2191769856, "gemm_dw":
+             1112432612, "gemm_dx": 496534581, "gemm_fwd": 1404442842, "perturb": 821926699,
+             "pool": 441880549, "softmax_ce": 114005, "unfold_fold": 629743040},
+    "wrn28x10": {"batchnorm": 760369556, "bias_grad": 350293, "descent": 4678181120, "gemm_dw":
+             1947900525, "gemm_dx": 458594460, "gemm_fwd": 1425731356, "perturb": 1754332715,
+             "pool": 508961013, "softmax_ce": 474453, "unfold_fold": 629743016},
+    "wrn40x10": {"batchnorm": 768820488, "bias_grad": 350293, "descent": 7157213056, "gemm_dw":
+             2026163132, "gemm_dx": 458543684, "gemm_fwd": 1482353449, "perturb": 2683971115,
+             "pool": 533675085, "softmax_ce": 474453, "unfold_fold": 629742939},
 }
 
 

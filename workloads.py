@@ -225,6 +225,8 @@ WORKLOADS["wrn28x10"] = _wide_resnet("wrn28x10", 28, 10, 100, data_seed=15)
 WORKLOADS["wrn40x10"] = _wide_resnet("wrn40x10", 40, 10, 100, data_seed=16)
 # the same model with bf16 matrix products (tensors stay fp32; see the boundary's gemm_dtype)
 WORKLOADS["vgg16bf"] = replace(WORKLOADS["vgg16"], name="vgg16bf", gemm_dtype=1)
+WORKLOADS["resnet18bf"] = replace(WORKLOADS["resnet18"], name="resnet18bf", gemm_dtype=1)
+WORKLOADS["wrn16x10bf"] = replace(WORKLOADS["wrn16x10"], name="wrn16x10bf", gemm_dtype=1)
 
 
 def _rng(seed: int, stream: int) -> np.random.Generator:

@@ -181,7 +181,7 @@ def _basic_block_net(name, blocks, widths, classes, **kw):
             l += 2
     return Workload(name, K=4, dims=tuple(dims) + (classes,), batch=128, n_conv=l, img_h=32, img_w=32,
                     bn_mask=(1 << l) - 1, stride_mask=stride, skip_mask=skip, proj_mask=proj,
-                    global_avg_pool=1, rho=0.1, lr=0.1, tau=(16, 16, 16, 16), steps=20, n_classes=classes,
+                    global_avg_pool=1, rho=0.1, lr=0.2, tau=(16, 16, 16, 16), steps=20, n_classes=classes,
                     batch_pool=2, **kw)
 
 
@@ -189,7 +189,8 @@ def _basic_block_net(name, blocks, widths, classes, **kw):
 # 256 and 512 channels with (2, 2, 2, 2) resp. (3, 4, 6, 3) basic blocks and projection
 # shortcuts where a stage begins; on 32x32 images the stem is one 3x3 convolution without the
 # ImageNet models' 7x7 stride-2 convolution and max-pool (the usual form for images of this
-# size; the paper does not say which it uses).  4 workers, batch 128, communication interval 16.
+# size; the paper does not say which it uses).  4 workers, batch 128, communication interval 16,
+# learning rate 0.2 and rho 0.1 (Appendix "Hyperparameter Selection").
 WORKLOADS["resnet18"] = _basic_block_net("resnet18", (2, 2, 2, 2), (64, 128, 256, 512), 10, data_seed=12)
 WORKLOADS["resnet34"] = _basic_block_net("resnet34", (3, 4, 6, 3), (64, 128, 256, 512), 100, data_seed=13)
 
@@ -214,12 +215,12 @@ def _wide_resnet(name, depth, k, classes, **kw):
             l += 2
     return Workload(name, K=4, dims=tuple(dims) + (classes,), batch=128, n_conv=l, img_h=32, img_w=32,
                     bn_mask=(1 << l) - 1, stride_mask=stride, skip_mask=skip, proj_mask=proj, preact=1,
-                    global_avg_pool=1, rho=0.1, lr=0.1, tau=(16, 16, 16, 16), steps=20, n_classes=classes,
+                    global_avg_pool=1, rho=0.1, lr=0.2, tau=(16, 16, 16, 16), steps=20, n_classes=classes,
                     batch_pool=2, **kw)
 
 
 # The wide residual networks of the Experiments section: WRN-16x10 (CIFAR-10), WRN-28x10 and
-# WRN-40x10 (CIFAR-100); 4 workers, batch 128, communication interval 16.
+# WRN-40x10 (CIFAR-100); 4 workers, batch 128, communication interval 16, learning rate 0.2, rho 0.1.
 WORKLOADS["wrn16x10"] = _wide_resnet("wrn16x10", 16, 10, 10, data_seed=14)
 WORKLOADS["wrn28x10"] = _wide_resnet("wrn28x10", 28, 10, 100, data_seed=15)
 WORKLOADS["wrn40x10"] = _wide_resnet("wrn40x10", 40, 10, 100, data_seed=16)

@@ -32,56 +32,56 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "5a0ee00049ae417d"
+TRAFFIC_SOURCES = "674fd5393e8e8725"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 2151595, "center": 100978176, "descent": 538490923, "gemm_dw": 43623400,
-             "gemm_dx": 42127701, "gemm_fwd": 62107637, "perturb": 201945515},
-    "cfg3": {"bias_grad": 13682022, "center": 1773558080, "descent": 884002, "gemm_dw_ascend":
-             667643273, "gemm_dw_norm": 17540907, "gemm_dw_step": 3028864623, "gemm_dx":
-             250134720, "gemm_fwd": 138149319, "softmax_ce": 1428971},
-    "cfg4": {"center": 3200036736, "descent": 25600038741, "perturb": 9600049835,
-             "sumsq_partials": 3416029749},
-    "cfg5": {"bias_grad": 117998798, "descent": 3479936, "gemm_dw_ascend": 7047667700,
-             "gemm_dw_norm": 152180053, "gemm_dw_step": 28464209597, "gemm_dx": 2333069760,
-             "gemm_fwd": 1161927755, "softmax_ce": 95763413},
-    "cnn5": {"bias_grad": 17357404, "conv_first": 80452843, "descent": 79476736, "gemm_dw":
-             67366176, "gemm_dx": 34787669, "gemm_fwd": 38345583, "perturb": 29813760, "pool":
-             68586126},
-    "cnn5bn": {"batchnorm": 157829081, "bias_grad": 565845, "conv_first": 80449141, "descent":
-             79542272, "gemm_dw": 67378329, "gemm_dx": 34787669, "gemm_fwd": 38345698, "perturb":
-             29838336, "pool": 68585856},
-    "resnet18": {"batchnorm": 259999012, "conv_first": 155235744, "descent": 1430962091,
-             "gemm_dw": 308322700, "gemm_dx": 178780284, "gemm_fwd": 230701943, "perturb":
-             536623573, "pool": 183890656, "unfold_fold": 218021608},
-    "resnet18bf": {"batchnorm": 260000119, "bias_grad": 52992, "conv_first": 155238155, "descent":
-             1430962475, "gemm_dw": 268542490, "gemm_dx": 145318686, "gemm_fwd": 274835484,
-             "perturb": 536623659, "pool": 183890633, "softmax_ce": 114347, "unfold_fold":
-             218021608},
-    "resnet20": {"batchnorm": 86667719, "descent": 34871296, "gemm_dw": 212796629, "gemm_dx":
-             269488405, "gemm_fwd": 100366866, "perturb": 13086720, "pool": 64194124,
-             "unfold_fold": 328703022},
-    "resnet34": {"batchnorm": 244146745, "bias_grad": 352128, "conv_first": 155196011, "descent":
-             2731188480, "gemm_dw": 264905817, "gemm_dx": 153704680, "gemm_fwd": 215090053,
-             "perturb": 1024209451, "pool": 195406040, "softmax_ce": 474709, "unfold_fold":
-             218021537},
-    "vgg16": {"batchnorm": 175730853, "bias_grad": 1094766, "conv_first": 155206229, "descent":
-             1952538880, "gemm_dw": 140499656, "gemm_dx": 16961707, "gemm_fwd": 137685186,
-             "perturb": 732214784, "pool": 89627473},
-    "vgg16bf": {"batchnorm": 175697476, "bias_grad": 1014282, "conv_first": 155208608, "descent":
-             1952539136, "gemm_dw": 113798809, "gemm_dx": 12092075, "gemm_fwd": 169057665,
-             "perturb": 732214784, "pool": 89627490, "softmax_ce": 114048},
-    "wrn16x10": {"batchnorm": 736317830, "descent": 2191769771, "gemm_dw": 1858586075, "gemm_dx":
-             549476006, "gemm_fwd": 1310928629, "perturb": 821926827, "pool": 441879860,
-             "unfold_fold": 629743067},
-    "wrn16x10bf": {"batchnorm": 736317769, "bias_grad": 51755, "descent": 2191769856, "gemm_dw":
-             1112432612, "gemm_dx": 496534581, "gemm_fwd": 1404442842, "perturb": 821926699,
-             "pool": 441880549, "softmax_ce": 114005, "unfold_fold": 629743040},
-    "wrn28x10": {"batchnorm": 760369556, "bias_grad": 350293, "descent": 4678181120, "gemm_dw":
-             1947900525, "gemm_dx": 458594460, "gemm_fwd": 1425731356, "perturb": 1754332715,
-             "pool": 508961013, "softmax_ce": 474453, "unfold_fold": 629743016},
-    "wrn40x10": {"batchnorm": 768820488, "bias_grad": 350293, "descent": 7157213056, "gemm_dw":
-             2026163132, "gemm_dx": 458543684, "gemm_fwd": 1482353449, "perturb": 2683971115,
-             "pool": 533675085, "softmax_ce": 474453, "unfold_fold": 629742939},
+    "cfg2": {"bias_grad": 2151595, "center": 100978176, "descent": 538490880, "gemm_dw": 43624136,
+             "gemm_dx": 42127701, "gemm_fwd": 62107669, "perturb": 201945259},
+    "cfg3": {"bias_grad": 13682010, "center": 1773558144, "descent": 883900, "gemm_dw_ascend":
+             652331759, "gemm_dw_norm": 17540907, "gemm_dw_step": 2976832614, "gemm_dx":
+             250134725, "gemm_fwd": 137771625, "softmax_ce": 1428821},
+    "cfg4": {"center": 3200036480, "descent": 25600039125, "perturb": 9600051157,
+             "sumsq_partials": 3416933696},
+    "cfg5": {"bias_grad": 118027720, "descent": 3479918, "gemm_dw_ascend": 6885937713,
+             "gemm_dw_norm": 152178517, "gemm_dw_step": 27793770130, "gemm_dx": 2333143428,
+             "gemm_fwd": 1161890471, "softmax_ce": 95761877},
+    "cnn5": {"bias_grad": 17357404, "conv_first": 80457131, "descent": 79476736, "gemm_dw":
+             67366958, "gemm_dx": 34787669, "gemm_fwd": 38346125, "perturb": 29813760, "pool":
+             68586069},
+    "cnn5bn": {"batchnorm": 157827630, "bias_grad": 565845, "conv_first": 80453771, "descent":
+             79542272, "gemm_dw": 67393269, "gemm_dx": 34787669, "gemm_fwd": 38345775, "perturb":
+             29838336, "pool": 68585845},
+    "resnet18": {"batchnorm": 259998974, "conv_first": 155243413, "descent": 1430962176,
+             "gemm_dw": 308575109, "gemm_dx": 178786667, "gemm_fwd": 230555389, "perturb":
+             536623701, "pool": 183890643, "unfold_fold": 218021623},
+    "resnet18bf": {"batchnorm": 260000111, "bias_grad": 52992, "conv_first": 155242421, "descent":
+             1430962176, "gemm_dw": 268557264, "gemm_dx": 145297859, "gemm_fwd": 274912162,
+             "perturb": 536623616, "pool": 183890643, "softmax_ce": 114005, "unfold_fold":
+             218021637},
+    "resnet20": {"batchnorm": 86667718, "descent": 34871296, "gemm_dw": 212833460, "gemm_dx":
+             269463476, "gemm_fwd": 100363989, "perturb": 13086720, "pool": 64194095,
+             "unfold_fold": 328684782},
+    "resnet34": {"batchnorm": 244146749, "bias_grad": 352128, "conv_first": 155203840, "descent":
+             2731188437, "gemm_dw": 264936119, "gemm_dx": 153706615, "gemm_fwd": 215014925,
+             "perturb": 1024209579, "pool": 195406039, "softmax_ce": 474731, "unfold_fold":
+             218021540},
+    "vgg16": {"batchnorm": 175730836, "bias_grad": 1094729, "conv_first": 155191477, "descent":
+             1952539051, "gemm_dw": 140501020, "gemm_dx": 16961707, "gemm_fwd": 137707245,
+             "perturb": 732214784, "pool": 89627439},
+    "vgg16bf": {"batchnorm": 175697427, "bias_grad": 1014282, "conv_first": 155205429, "descent":
+             1952539136, "gemm_dw": 113779056, "gemm_dx": 12092075, "gemm_fwd": 169154679,
+             "perturb": 732214741, "pool": 89627507, "softmax_ce": 114005},
+    "wrn16x10": {"batchnorm": 736317413, "descent": 2191770069, "gemm_dw": 1862060855, "gemm_dx":
+             549486413, "gemm_fwd": 1311007357, "perturb": 821926827, "pool": 441879845,
+             "unfold_fold": 629743069},
+    "wrn16x10bf": {"batchnorm": 736317218, "bias_grad": 51755, "descent": 2191769899, "gemm_dw":
+             1114521028, "gemm_dx": 496613308, "gemm_fwd": 1392134398, "perturb": 821927083,
+             "pool": 441879843, "softmax_ce": 114005, "unfold_fold": 629743067},
+    "wrn28x10": {"batchnorm": 760369324, "bias_grad": 350293, "descent": 4678181291, "gemm_dw":
+             1944654377, "gemm_dx": 458592971, "gemm_fwd": 1424983324, "perturb": 1754333099,
+             "pool": 508961026, "softmax_ce": 474453, "unfold_fold": 629743029},
+    "wrn40x10": {"batchnorm": 768819941, "bias_grad": 350293, "descent": 7157212629, "gemm_dw":
+             2025833206, "gemm_dx": 458564366, "gemm_fwd": 1481807296, "perturb": 2683970859,
+             "pool": 533675101, "softmax_ce": 474795, "unfold_fold": 629742955},
 }
 
 

@@ -644,7 +644,7 @@ def test_peak_probe_reports_plausible_ceilings():
         lsam.lsam_probe_peaks(scratch[:16])          # too small
 
 
-@pytest.mark.parametrize("name", ["cfg1", "bf16", "cnn"])
+@pytest.mark.parametrize("name", ["cfg1", "bf16", "cnn", "residual"])
 def test_step_can_be_captured_and_replayed_as_a_hip_graph(name):
     """`lsam_step` allocates nothing and never synchronises, so a caller may capture it.  Four
     replays of the captured step, with eager work and synchronisations between them, must
@@ -659,6 +659,13 @@ def test_step_can_be_captured_and_replayed_as_a_hip_graph(name):
         w = workloads.Workload("cnn_graph", K=2, dims=(3, 32, 32, 24, 40, 10), batch=8, n_conv=4,
                                img_h=8, img_w=8, pool_mask=0b0110, rho=0.05, lr=0.05,
                                tau=(100, 100), n_classes=10, data_seed=41)
+    elif name == "residual":
+        # batch normalisation, a strided projection block, then a pre-activation variant of the
+        # same layers is not needed: the two differ in kernels' arguments only
+        w = workloads.Workload("res_graph", K=2, dims=(3, 8, 16, 16, 16, 16, 5), batch=6, n_conv=5, img_h=8,
+                               img_w=8, bn_mask=0b11111, stride_mask=0b00010, skip_mask=0b10100,
+                               proj_mask=0b00100, global_avg_pool=1, rho=0.05, lr=0.05, tau=(100, 100),
+                               n_classes=5, data_seed=51)
     else:
         full = workloads.WORKLOADS["cfg3"]
         dims = (full.dims[0] // 8,) + (256,) * (len(full.dims) - 2) + (full.dims[-1],)

@@ -32,56 +32,56 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "674fd5393e8e8725"
+TRAFFIC_SOURCES = "2e14ad28a4ee25ac"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 2151595, "center": 100978176, "descent": 538490880, "gemm_dw": 43624136,
-             "gemm_dx": 42127701, "gemm_fwd": 62107669, "perturb": 201945259},
-    "cfg3": {"bias_grad": 13682010, "center": 1773558144, "descent": 883900, "gemm_dw_ascend":
-             652331759, "gemm_dw_norm": 17540907, "gemm_dw_step": 2976832614, "gemm_dx":
-             250134725, "gemm_fwd": 137771625, "softmax_ce": 1428821},
-    "cfg4": {"center": 3200036480, "descent": 25600039125, "perturb": 9600051157,
-             "sumsq_partials": 3416933696},
-    "cfg5": {"bias_grad": 118027720, "descent": 3479918, "gemm_dw_ascend": 6885937713,
-             "gemm_dw_norm": 152178517, "gemm_dw_step": 27793770130, "gemm_dx": 2333143428,
-             "gemm_fwd": 1161890471, "softmax_ce": 95761877},
-    "cnn5": {"bias_grad": 17357404, "conv_first": 80457131, "descent": 79476736, "gemm_dw":
-             67366958, "gemm_dx": 34787669, "gemm_fwd": 38346125, "perturb": 29813760, "pool":
-             68586069},
-    "cnn5bn": {"batchnorm": 157827630, "bias_grad": 565845, "conv_first": 80453771, "descent":
-             79542272, "gemm_dw": 67393269, "gemm_dx": 34787669, "gemm_fwd": 38345775, "perturb":
-             29838336, "pool": 68585845},
-    "resnet18": {"batchnorm": 259998974, "conv_first": 155243413, "descent": 1430962176,
-             "gemm_dw": 308575109, "gemm_dx": 178786667, "gemm_fwd": 230555389, "perturb":
-             536623701, "pool": 183890643, "unfold_fold": 218021623},
-    "resnet18bf": {"batchnorm": 260000111, "bias_grad": 52992, "conv_first": 155242421, "descent":
-             1430962176, "gemm_dw": 268557264, "gemm_dx": 145297859, "gemm_fwd": 274912162,
-             "perturb": 536623616, "pool": 183890643, "softmax_ce": 114005, "unfold_fold":
-             218021637},
-    "resnet20": {"batchnorm": 86667718, "descent": 34871296, "gemm_dw": 212833460, "gemm_dx":
-             269463476, "gemm_fwd": 100363989, "perturb": 13086720, "pool": 64194095,
-             "unfold_fold": 328684782},
-    "resnet34": {"batchnorm": 244146749, "bias_grad": 352128, "conv_first": 155203840, "descent":
-             2731188437, "gemm_dw": 264936119, "gemm_dx": 153706615, "gemm_fwd": 215014925,
-             "perturb": 1024209579, "pool": 195406039, "softmax_ce": 474731, "unfold_fold":
-             218021540},
-    "vgg16": {"batchnorm": 175730836, "bias_grad": 1094729, "conv_first": 155191477, "descent":
-             1952539051, "gemm_dw": 140501020, "gemm_dx": 16961707, "gemm_fwd": 137707245,
-             "perturb": 732214784, "pool": 89627439},
-    "vgg16bf": {"batchnorm": 175697427, "bias_grad": 1014282, "conv_first": 155205429, "descent":
-             1952539136, "gemm_dw": 113779056, "gemm_dx": 12092075, "gemm_fwd": 169154679,
-             "perturb": 732214741, "pool": 89627507, "softmax_ce": 114005},
-    "wrn16x10": {"batchnorm": 736317413, "descent": 2191770069, "gemm_dw": 1862060855, "gemm_dx":
-             549486413, "gemm_fwd": 1311007357, "perturb": 821926827, "pool": 441879845,
-             "unfold_fold": 629743069},
-    "wrn16x10bf": {"batchnorm": 736317218, "bias_grad": 51755, "descent": 2191769899, "gemm_dw":
-             1114521028, "gemm_dx": 496613308, "gemm_fwd": 1392134398, "perturb": 821927083,
-             "pool": 441879843, "softmax_ce": 114005, "unfold_fold": 629743067},
-    "wrn28x10": {"batchnorm": 760369324, "bias_grad": 350293, "descent": 4678181291, "gemm_dw":
-             1944654377, "gemm_dx": 458592971, "gemm_fwd": 1424983324, "perturb": 1754333099,
-             "pool": 508961026, "softmax_ce": 474453, "unfold_fold": 629743029},
-    "wrn40x10": {"batchnorm": 768819941, "bias_grad": 350293, "descent": 7157212629, "gemm_dw":
-             2025833206, "gemm_dx": 458564366, "gemm_fwd": 1481807296, "perturb": 2683970859,
-             "pool": 533675101, "softmax_ce": 474795, "unfold_fold": 629742955},
+    "cfg2": {"bias_grad": 2151595, "center": 100978176, "descent": 538490880, "gemm_dw": 43618995,
+             "gemm_dx": 42127701, "gemm_fwd": 62107659, "perturb": 201945387},
+    "cfg3": {"bias_grad": 13682095, "center": 1773558016, "descent": 884019, "gemm_dw_ascend":
+             652402048, "gemm_dw_norm": 17540907, "gemm_dw_step": 2975853286, "gemm_dx":
+             250134725, "gemm_fwd": 137769527, "softmax_ce": 1428971},
+    "cfg4": {"center": 3200035968, "descent": 25600038784, "perturb": 9600051371,
+             "sumsq_partials": 3417465365},
+    "cfg5": {"bias_grad": 118030318, "descent": 3479948, "gemm_dw_ascend": 6889944472,
+             "gemm_dw_norm": 152156459, "gemm_dw_step": 27800478470, "gemm_dx": 2333165099,
+             "gemm_fwd": 1161909084, "softmax_ce": 95634597},
+    "cnn5": {"bias_grad": 17357404, "conv_first": 80457003, "descent": 79476736, "gemm_dw":
+             67348057, "gemm_dx": 34787669, "gemm_fwd": 38345408, "perturb": 29813760, "pool":
+             68586066},
+    "cnn5bn": {"batchnorm": 157827620, "bias_grad": 565845, "conv_first": 80453120, "descent":
+             79542272, "gemm_dw": 67400672, "gemm_dx": 34787669, "gemm_fwd": 38346159, "perturb":
+             29838336, "pool": 68585874},
+    "resnet18": {"batchnorm": 259998977, "conv_first": 155248821, "descent": 1430963413,
+             "gemm_dw": 308345566, "gemm_dx": 178787161, "gemm_fwd": 230520647, "perturb":
+             536623573, "pool": 183890650, "unfold_fold": 218021623},
+    "resnet18bf": {"batchnorm": 260000035, "bias_grad": 52992, "conv_first": 155252907, "descent":
+             1430962347, "gemm_dw": 268621174, "gemm_dx": 145320570, "gemm_fwd": 274960013,
+             "perturb": 536623701, "pool": 183890643, "softmax_ce": 114005, "unfold_fold":
+             218021634},
+    "resnet20": {"batchnorm": 86667721, "descent": 34871808, "gemm_dw": 212819164, "gemm_dx":
+             269456205, "gemm_fwd": 100366592, "perturb": 13086720, "pool": 64194174,
+             "unfold_fold": 328681592},
+    "resnet34": {"batchnorm": 244146769, "bias_grad": 352128, "conv_first": 155213099, "descent":
+             2731189717, "gemm_dw": 264842958, "gemm_dx": 153712646, "gemm_fwd": 215074202,
+             "perturb": 1024209195, "pool": 195406040, "softmax_ce": 474773, "unfold_fold":
+             218021544},
+    "vgg16": {"batchnorm": 175730847, "bias_grad": 1094784, "conv_first": 155201493, "descent":
+             1952538837, "gemm_dw": 140513625, "gemm_dx": 16961707, "gemm_fwd": 137687724,
+             "perturb": 732214741, "pool": 89627435},
+    "vgg16bf": {"batchnorm": 175697425, "bias_grad": 1014282, "conv_first": 155206347, "descent":
+             1952538965, "gemm_dw": 113766246, "gemm_dx": 12092075, "gemm_fwd": 169039550,
+             "perturb": 732214656, "pool": 89627522, "softmax_ce": 114091},
+    "wrn16x10": {"batchnorm": 736317434, "descent": 2191769685, "gemm_dw": 1859069338, "gemm_dx":
+             549485184, "gemm_fwd": 1181466498, "perturb": 821926997, "pool": 441879829,
+             "unfold_fold": 629743093},
+    "wrn16x10bf": {"batchnorm": 736318086, "bias_grad": 51755, "descent": 2191769941, "gemm_dw":
+             1111989331, "gemm_dx": 496572619, "gemm_fwd": 1397520108, "perturb": 821927040,
+             "pool": 441879832, "softmax_ce": 114347, "unfold_fold": 629743061},
+    "wrn28x10": {"batchnorm": 760369764, "bias_grad": 350293, "descent": 4678182656, "gemm_dw":
+             1944912402, "gemm_dx": 458588210, "gemm_fwd": 1271410985, "perturb": 1754332373,
+             "pool": 508961015, "softmax_ce": 474453, "unfold_fold": 629743037},
+    "wrn40x10": {"batchnorm": 768820409, "bias_grad": 350293, "descent": 7157214037, "gemm_dw":
+             2023560197, "gemm_dx": 458559580, "gemm_fwd": 1320496224, "perturb": 2683971413,
+             "pool": 533675097, "softmax_ce": 474795, "unfold_fold": 629742992},
 }
 
 

@@ -1302,3 +1302,67 @@ def test_layer_info_reports_which_kernels_serve_a_layer():
     assert [r[0] for r in t] == [lsam.LAYER_CONV_FIRST, lsam.LAYER_CONV_DIRECT, lsam.LAYER_CONV_DIRECT,
                                  lsam.LAYER_CONV_STORED, lsam.LAYER_HEAD]
     assert [r[1] for r in t[:4]] == [0, 0, 1, 1] and [r[3] for r in t] == [512, 512, 128, 32, 8]
+
+
+# ---- randomly drawn residual configurations -----------------------------------------------------------
+def _random_residual_workload(rng):
+    """A valid configuration drawn at random: a stem, then blocks that keep, halve or change
+    the shape, closed by a parameter-free shortcut where that fits and by a projection where it
+    does not (or by choice), plain convolutions and pools in between; post- or pre-activation."""
+    preact = int(rng.integers(0, 2))
+    chans = [8, 16, 24, 32]
+    H0, W0 = int(rng.choice([8, 12, 16])), int(rng.choice([8, 16]))
+    h, w = H0, W0
+    dims = [int(rng.choice([2, 3, 4])), int(rng.choice(chans[:2]))]
+    stride = skip = proj = pool = 0
+    l = 1                                       # index of the next convolution
+    for _ in range(int(rng.integers(1, 4))):
+        cin, st = dims[-1], 1
+        kind = rng.choice(["same", "widen", "halve", "narrow"])
+        cout = cin
+        if kind == "widen":
+            cout = int(rng.choice([c for c in chans if c >= cin]))
+        elif kind == "narrow":
+            cout = int(rng.choice([c for c in chans if c <= cin]))
+        elif kind == "halve" and h % 2 == 0 and w % 2 == 0 and min(h, w) >= 4:
+            st, cout = 2, int(rng.choice([c for c in chans if c >= cin]))
+            h, w = h // 2, w // 2
+        if st == 2:
+            stride |= 1 << l
+        dims += [cout, cout]
+        skip |= 1 << (l + 1)
+        fits_plain = (cout == cin and st == 1) if preact else cout >= cin
+        if not fits_plain or rng.integers(0, 3) == 0:
+            proj |= 1 << (l + 1)
+        l += 2
+        if not preact and rng.integers(0, 4) == 0:
+            # a plain convolution between two blocks, with a pool when the image allows; a block's
+            # input has to be a convolution's ReLU output, so a pool is followed by one more
+            dims.append(int(rng.choice(chans)))
+            l += 1
+            if h % 2 == 0 and w % 2 == 0 and min(h, w) >= 4 and rng.integers(0, 2) == 0:
+                pool |= 1 << (l - 1)
+                h, w = h // 2, w // 2
+                dims.append(int(rng.choice(chans)))
+                l += 1
+    gap = int(rng.integers(0, 2)) if h * w * dims[-1] <= 512 else 1
+    classes = int(rng.choice([3, 5, 10]))
+    dense = [classes] if rng.integers(0, 2) else [int(rng.choice([12, 20])), classes]
+    K = int(rng.integers(1, 4))
+    return workloads.Workload(
+        "rand_res", K=K, dims=tuple(dims + dense), batch=int(rng.choice([3, 4, 6])), n_conv=l, img_h=H0, img_w=W0,
+        bn_mask=(1 << l) - 1, stride_mask=stride, skip_mask=skip, proj_mask=proj, pool_mask=pool, preact=preact,
+        global_avg_pool=gap, rho=0.05, lr=0.05, tau=tuple(int(t) for t in rng.integers(1, 4, K)),
+        n_classes=classes, data_seed=int(rng.integers(1, 1000)))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_randomly_drawn_residual_configurations_match_oracle(seed):
+    w = _random_residual_workload(np.random.default_rng(1000 + seed))
+    cfg, keep = lsam.config_from_workload(w)
+    assert lsam.lsam_workspace_bytes(cfg) > 0, (w, lsam.last_error())
+    # decisions away from zero: the step has to agree to 1e-5 whatever the structure
+    worst = run_mlp(w, 4, 1e-5, 1e-5, anchor_after=2, init_fn=bn_away_from_zero)
+    print("seed %d: %d convolutions, preact=%d, skip=%s, proj=%s, stride=%s, pool=%s, gap=%d, K=%d: %.2e"
+          % (seed, w.n_conv, w.preact, bin(w.skip_mask), bin(w.proj_mask), bin(w.stride_mask), bin(w.pool_mask),
+             w.global_avg_pool, w.K, worst))

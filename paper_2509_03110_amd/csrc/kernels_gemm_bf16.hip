@@ -660,6 +660,12 @@ int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s, int* s
   else if (tile_override == 4) tile = 128;
   else if (d.M >= 256 && d.N >= 256 && tiles(256, 256) >= 512 && (d.Kd >= 1024 || d.a_kmajor)) tile = 256;
   else if (d.M >= 256 && d.N >= 128 && tiles(256, 128) >= 256) tile = 2;
+  // The step epilogue streams seven arrays per tile; there the 128x128 tile (one workgroup per
+  // compute unit with its four-stage ring) measured best: 27.0-27.8 ms per step of the largest
+  // configuration against 28.7-29.9 for 256x128 tiles, two workgroups per unit (and 30.3 for
+  // 256x256); the ascent epilogue, one array in and one out, keeps the choice above (9.1 against
+  // 9.6 ms with 128x128).
+  if (d.fuse != nullptr && tile_override == 0) tile = 128;
   const int kpad = (d.Kd + 31) / 32 * 32;
   // stored shapes: k-major [rows][k], m-major [k][rows]
   const long long blocksA = d.a_kmajor ? (long long)b32s_blocks(d.M) * d.cbA : (long long)b32s_blocks(kpad) * d.cbA;

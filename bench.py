@@ -32,56 +32,56 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "2e14ad28a4ee25ac"
+TRAFFIC_SOURCES = "ed0d986662dedc07"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 2151595, "center": 100978176, "descent": 538490880, "gemm_dw": 43618995,
-             "gemm_dx": 42127701, "gemm_fwd": 62107659, "perturb": 201945387},
-    "cfg3": {"bias_grad": 13682095, "center": 1773558016, "descent": 884019, "gemm_dw_ascend":
-             652402048, "gemm_dw_norm": 17540907, "gemm_dw_step": 2975853286, "gemm_dx":
-             250134725, "gemm_fwd": 137769527, "softmax_ce": 1428971},
-    "cfg4": {"center": 3200035968, "descent": 25600038784, "perturb": 9600051371,
-             "sumsq_partials": 3417465365},
-    "cfg5": {"bias_grad": 118030318, "descent": 3479948, "gemm_dw_ascend": 6889944472,
-             "gemm_dw_norm": 152156459, "gemm_dw_step": 27800478470, "gemm_dx": 2333165099,
-             "gemm_fwd": 1161909084, "softmax_ce": 95634597},
-    "cnn5": {"bias_grad": 17357404, "conv_first": 80457003, "descent": 79476736, "gemm_dw":
-             67348057, "gemm_dx": 34787669, "gemm_fwd": 38345408, "perturb": 29813760, "pool":
+    "cfg2": {"bias_grad": 2151595, "center": 100978176, "descent": 538490880, "gemm_dw": 43620536,
+             "gemm_dx": 42127701, "gemm_fwd": 62107733, "perturb": 201945557},
+    "cfg3": {"bias_grad": 13682074, "center": 1773558336, "descent": 884011, "gemm_dw_ascend":
+             652352486, "gemm_dw_norm": 17540907, "gemm_dw_step": 2937892318, "gemm_dx":
+             250134752, "gemm_fwd": 137771163, "softmax_ce": 1428971},
+    "cfg4": {"center": 3200035968, "descent": 25600038827, "perturb": 9600050837,
+             "sumsq_partials": 3416622859},
+    "cfg5": {"bias_grad": 118016034, "descent": 3479906, "gemm_dw_ascend": 6889510260,
+             "gemm_dw_norm": 152197333, "gemm_dw_step": 26923607528, "gemm_dx": 2333160036,
+             "gemm_fwd": 1161912823, "softmax_ce": 95773387},
+    "cnn5": {"bias_grad": 17357404, "conv_first": 80459488, "descent": 79476736, "gemm_dw":
+             67361611, "gemm_dx": 34787669, "gemm_fwd": 38345331, "perturb": 29813760, "pool":
              68586066},
-    "cnn5bn": {"batchnorm": 157827620, "bias_grad": 565845, "conv_first": 80453120, "descent":
-             79542272, "gemm_dw": 67400672, "gemm_dx": 34787669, "gemm_fwd": 38346159, "perturb":
-             29838336, "pool": 68585874},
-    "resnet18": {"batchnorm": 259998977, "conv_first": 155248821, "descent": 1430963413,
-             "gemm_dw": 308345566, "gemm_dx": 178787161, "gemm_fwd": 230520647, "perturb":
-             536623573, "pool": 183890650, "unfold_fold": 218021623},
-    "resnet18bf": {"batchnorm": 260000035, "bias_grad": 52992, "conv_first": 155252907, "descent":
-             1430962347, "gemm_dw": 268621174, "gemm_dx": 145320570, "gemm_fwd": 274960013,
-             "perturb": 536623701, "pool": 183890643, "softmax_ce": 114005, "unfold_fold":
-             218021634},
-    "resnet20": {"batchnorm": 86667721, "descent": 34871808, "gemm_dw": 212819164, "gemm_dx":
-             269456205, "gemm_fwd": 100366592, "perturb": 13086720, "pool": 64194174,
-             "unfold_fold": 328681592},
-    "resnet34": {"batchnorm": 244146769, "bias_grad": 352128, "conv_first": 155213099, "descent":
-             2731189717, "gemm_dw": 264842958, "gemm_dx": 153712646, "gemm_fwd": 215074202,
-             "perturb": 1024209195, "pool": 195406040, "softmax_ce": 474773, "unfold_fold":
-             218021544},
-    "vgg16": {"batchnorm": 175730847, "bias_grad": 1094784, "conv_first": 155201493, "descent":
-             1952538837, "gemm_dw": 140513625, "gemm_dx": 16961707, "gemm_fwd": 137687724,
-             "perturb": 732214741, "pool": 89627435},
-    "vgg16bf": {"batchnorm": 175697425, "bias_grad": 1014282, "conv_first": 155206347, "descent":
-             1952538965, "gemm_dw": 113766246, "gemm_dx": 12092075, "gemm_fwd": 169039550,
-             "perturb": 732214656, "pool": 89627522, "softmax_ce": 114091},
-    "wrn16x10": {"batchnorm": 736317434, "descent": 2191769685, "gemm_dw": 1859069338, "gemm_dx":
-             549485184, "gemm_fwd": 1181466498, "perturb": 821926997, "pool": 441879829,
-             "unfold_fold": 629743093},
-    "wrn16x10bf": {"batchnorm": 736318086, "bias_grad": 51755, "descent": 2191769941, "gemm_dw":
-             1111989331, "gemm_dx": 496572619, "gemm_fwd": 1397520108, "perturb": 821927040,
-             "pool": 441879832, "softmax_ce": 114347, "unfold_fold": 629743061},
-    "wrn28x10": {"batchnorm": 760369764, "bias_grad": 350293, "descent": 4678182656, "gemm_dw":
-             1944912402, "gemm_dx": 458588210, "gemm_fwd": 1271410985, "perturb": 1754332373,
-             "pool": 508961015, "softmax_ce": 474453, "unfold_fold": 629743037},
-    "wrn40x10": {"batchnorm": 768820409, "bias_grad": 350293, "descent": 7157214037, "gemm_dw":
-             2023560197, "gemm_dx": 458559580, "gemm_fwd": 1320496224, "perturb": 2683971413,
-             "pool": 533675097, "softmax_ce": 474795, "unfold_fold": 629742992},
+    "cnn5bn": {"batchnorm": 157827648, "bias_grad": 565845, "conv_first": 80450965, "descent":
+             79542272, "gemm_dw": 67393099, "gemm_dx": 34787669, "gemm_fwd": 38345216, "perturb":
+             29838336, "pool": 68585845},
+    "resnet18": {"batchnorm": 259999041, "conv_first": 155247861, "descent": 1430962901,
+             "gemm_dw": 308418342, "gemm_dx": 178792277, "gemm_fwd": 230628764, "perturb":
+             536623659, "pool": 183890647, "unfold_fold": 218021625},
+    "resnet18bf": {"batchnorm": 260000099, "bias_grad": 52992, "conv_first": 155243765, "descent":
+             1430962560, "gemm_dw": 268431217, "gemm_dx": 145316230, "gemm_fwd": 274887920,
+             "perturb": 536623872, "pool": 183890635, "softmax_ce": 115285, "unfold_fold":
+             218021625},
+    "resnet20": {"batchnorm": 86667722, "descent": 34871296, "gemm_dw": 212816369, "gemm_dx":
+             269483409, "gemm_fwd": 100365532, "perturb": 13086720, "pool": 64194207,
+             "unfold_fold": 328681063},
+    "resnet34": {"batchnorm": 244146788, "bias_grad": 352128, "conv_first": 155202304, "descent":
+             2731188992, "gemm_dw": 264985859, "gemm_dx": 153705271, "gemm_fwd": 215013963,
+             "perturb": 1024209408, "pool": 195406042, "softmax_ce": 474731, "unfold_fold":
+             218021551},
+    "vgg16": {"batchnorm": 175730841, "bias_grad": 1094766, "conv_first": 155204757, "descent":
+             1952538880, "gemm_dw": 140517383, "gemm_dx": 16961707, "gemm_fwd": 137589342,
+             "perturb": 732214912, "pool": 89627445},
+    "vgg16bf": {"batchnorm": 175697431, "bias_grad": 1014282, "conv_first": 155213013, "descent":
+             1952539264, "gemm_dw": 113803295, "gemm_dx": 12092075, "gemm_fwd": 169127720,
+             "perturb": 732214741, "pool": 89627531, "softmax_ce": 114005},
+    "wrn16x10": {"batchnorm": 736317695, "descent": 2191770325, "gemm_dw": 1858848765, "gemm_dx":
+             549473574, "gemm_fwd": 1183988385, "perturb": 821926827, "pool": 441879826,
+             "unfold_fold": 629743029},
+    "wrn16x10bf": {"batchnorm": 736317160, "bias_grad": 51755, "descent": 2191770368, "gemm_dw":
+             1111678728, "gemm_dx": 496431079, "gemm_fwd": 1397641037, "perturb": 821926741,
+             "pool": 441879835, "softmax_ce": 114005, "unfold_fold": 629743077},
+    "wrn28x10": {"batchnorm": 760369899, "bias_grad": 350293, "descent": 4678181888, "gemm_dw":
+             1945349506, "gemm_dx": 458588284, "gemm_fwd": 1271395588, "perturb": 1754333056,
+             "pool": 508961026, "softmax_ce": 474453, "unfold_fold": 629743027},
+    "wrn40x10": {"batchnorm": 768820215, "bias_grad": 350293, "descent": 7157212971, "gemm_dw":
+             2021309750, "gemm_dx": 458558596, "gemm_fwd": 1319692893, "perturb": 2683970987,
+             "pool": 533675102, "softmax_ce": 474453, "unfold_fold": 629742989},
 }
 
 

@@ -661,7 +661,11 @@ int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s, int* s
   if (tile_override == 1) tile = 256;
   else if (tile_override == 2) tile = 2;
   else if (tile_override == 4) tile = 128;
-  else if (d.M >= 256 && d.N >= 256 && tiles(256, 256) >= 512 && (d.Kd >= 1024 || d.a_kmajor)) tile = 256;
+  // (the input gradient, whose weights are read through transposing LDS reads, also prefers
+  // 256x128: 9.3 against 9.8 ms per step of the largest configuration; the forward pass
+  // 256x256: 9.5 against 9.9)
+  else if (d.M >= 256 && d.N >= 256 && tiles(256, 256) >= 512 &&
+           (d.Kd >= 1024 ? (d.b_kmajor || !d.a_kmajor) : d.a_kmajor && d.b_kmajor)) tile = 256;
   else if (d.M >= 256 && d.N >= 128 && tiles(256, 128) >= 256) tile = 2;
   // The step epilogue streams seven arrays per tile; there the 128x128 tile (one workgroup per
   // compute unit with its four-stage ring) measured best: 27.0-27.8 ms per step of the largest

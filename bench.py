@@ -32,56 +32,56 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "ed0d986662dedc07"
+TRAFFIC_SOURCES = "84cfd54fed468500"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 2151595, "center": 100978176, "descent": 538490880, "gemm_dw": 43620536,
-             "gemm_dx": 42127701, "gemm_fwd": 62107733, "perturb": 201945557},
-    "cfg3": {"bias_grad": 13682074, "center": 1773558336, "descent": 884011, "gemm_dw_ascend":
-             652352486, "gemm_dw_norm": 17540907, "gemm_dw_step": 2937892318, "gemm_dx":
-             250134752, "gemm_fwd": 137771163, "softmax_ce": 1428971},
-    "cfg4": {"center": 3200035968, "descent": 25600038827, "perturb": 9600050837,
-             "sumsq_partials": 3416622859},
-    "cfg5": {"bias_grad": 118016034, "descent": 3479906, "gemm_dw_ascend": 6889510260,
-             "gemm_dw_norm": 152197333, "gemm_dw_step": 26923607528, "gemm_dx": 2333160036,
-             "gemm_fwd": 1161912823, "softmax_ce": 95773387},
-    "cnn5": {"bias_grad": 17357404, "conv_first": 80459488, "descent": 79476736, "gemm_dw":
-             67361611, "gemm_dx": 34787669, "gemm_fwd": 38345331, "perturb": 29813760, "pool":
-             68586066},
-    "cnn5bn": {"batchnorm": 157827648, "bias_grad": 565845, "conv_first": 80450965, "descent":
-             79542272, "gemm_dw": 67393099, "gemm_dx": 34787669, "gemm_fwd": 38345216, "perturb":
-             29838336, "pool": 68585845},
-    "resnet18": {"batchnorm": 259999041, "conv_first": 155247861, "descent": 1430962901,
-             "gemm_dw": 308418342, "gemm_dx": 178792277, "gemm_fwd": 230628764, "perturb":
-             536623659, "pool": 183890647, "unfold_fold": 218021625},
-    "resnet18bf": {"batchnorm": 260000099, "bias_grad": 52992, "conv_first": 155243765, "descent":
-             1430962560, "gemm_dw": 268431217, "gemm_dx": 145316230, "gemm_fwd": 274887920,
-             "perturb": 536623872, "pool": 183890635, "softmax_ce": 115285, "unfold_fold":
-             218021625},
-    "resnet20": {"batchnorm": 86667722, "descent": 34871296, "gemm_dw": 212816369, "gemm_dx":
-             269483409, "gemm_fwd": 100365532, "perturb": 13086720, "pool": 64194207,
-             "unfold_fold": 328681063},
-    "resnet34": {"batchnorm": 244146788, "bias_grad": 352128, "conv_first": 155202304, "descent":
-             2731188992, "gemm_dw": 264985859, "gemm_dx": 153705271, "gemm_fwd": 215013963,
-             "perturb": 1024209408, "pool": 195406042, "softmax_ce": 474731, "unfold_fold":
-             218021551},
-    "vgg16": {"batchnorm": 175730841, "bias_grad": 1094766, "conv_first": 155204757, "descent":
-             1952538880, "gemm_dw": 140517383, "gemm_dx": 16961707, "gemm_fwd": 137589342,
-             "perturb": 732214912, "pool": 89627445},
-    "vgg16bf": {"batchnorm": 175697431, "bias_grad": 1014282, "conv_first": 155213013, "descent":
-             1952539264, "gemm_dw": 113803295, "gemm_dx": 12092075, "gemm_fwd": 169127720,
-             "perturb": 732214741, "pool": 89627531, "softmax_ce": 114005},
-    "wrn16x10": {"batchnorm": 736317695, "descent": 2191770325, "gemm_dw": 1858848765, "gemm_dx":
-             549473574, "gemm_fwd": 1183988385, "perturb": 821926827, "pool": 441879826,
-             "unfold_fold": 629743029},
-    "wrn16x10bf": {"batchnorm": 736317160, "bias_grad": 51755, "descent": 2191770368, "gemm_dw":
-             1111678728, "gemm_dx": 496431079, "gemm_fwd": 1397641037, "perturb": 821926741,
-             "pool": 441879835, "softmax_ce": 114005, "unfold_fold": 629743077},
-    "wrn28x10": {"batchnorm": 760369899, "bias_grad": 350293, "descent": 4678181888, "gemm_dw":
-             1945349506, "gemm_dx": 458588284, "gemm_fwd": 1271395588, "perturb": 1754333056,
-             "pool": 508961026, "softmax_ce": 474453, "unfold_fold": 629743027},
-    "wrn40x10": {"batchnorm": 768820215, "bias_grad": 350293, "descent": 7157212971, "gemm_dw":
-             2021309750, "gemm_dx": 458558596, "gemm_fwd": 1319692893, "perturb": 2683970987,
-             "pool": 533675102, "softmax_ce": 474453, "unfold_fold": 629742989},
+    "cfg2": {"bias_grad": 2151595, "center": 100978176, "descent": 538490880, "gemm_dw": 43619275,
+             "gemm_dx": 42127701, "gemm_fwd": 62107701, "perturb": 201945344},
+    "cfg3": {"bias_grad": 13682048, "center": 1773557952, "descent": 884002, "gemm_dw_ascend":
+             652353570, "gemm_dw_norm": 17540907, "gemm_dw_step": 2938611439, "gemm_dx":
+             250134736, "gemm_fwd": 137770602, "softmax_ce": 1428821},
+    "cfg4": {"center": 3200037248, "descent": 25600039125, "perturb": 9600050773,
+             "sumsq_partials": 3417773120},
+    "cfg5": {"bias_grad": 118017722, "descent": 3479899, "gemm_dw_ascend": 6878671372,
+             "gemm_dw_norm": 152155947, "gemm_dw_step": 26949085038, "gemm_dx": 2576656928,
+             "gemm_fwd": 1161952470, "softmax_ce": 95744576},
+    "cnn5": {"bias_grad": 17357404, "conv_first": 80460597, "descent": 79476736, "gemm_dw":
+             67362876, "gemm_dx": 34787669, "gemm_fwd": 38345199, "perturb": 29813760, "pool":
+             68586073},
+    "cnn5bn": {"batchnorm": 157827644, "bias_grad": 565845, "conv_first": 80451317, "descent":
+             79542272, "gemm_dw": 67390347, "gemm_dx": 34787669, "gemm_fwd": 38345318, "perturb":
+             29838336, "pool": 68585842},
+    "resnet18": {"batchnorm": 259999049, "conv_first": 155236235, "descent": 1430962475,
+             "gemm_dw": 308801215, "gemm_dx": 178773945, "gemm_fwd": 230761705, "perturb":
+             536623531, "pool": 183890645, "unfold_fold": 218021630},
+    "resnet18bf": {"batchnorm": 260000088, "bias_grad": 52992, "conv_first": 155232075, "descent":
+             1430962304, "gemm_dw": 268496781, "gemm_dx": 145290828, "gemm_fwd": 275122021,
+             "perturb": 536623573, "pool": 183890630, "softmax_ce": 114005, "unfold_fold":
+             218021641},
+    "resnet20": {"batchnorm": 86667720, "descent": 34871808, "gemm_dw": 212890181, "gemm_dx":
+             269451780, "gemm_fwd": 100352742, "perturb": 13086720, "pool": 64194170,
+             "unfold_fold": 328668063},
+    "resnet34": {"batchnorm": 244146766, "bias_grad": 352128, "conv_first": 155200256, "descent":
+             2731188352, "gemm_dw": 265157874, "gemm_dx": 153685147, "gemm_fwd": 215050183,
+             "perturb": 1024209195, "pool": 195406044, "softmax_ce": 474731, "unfold_fold":
+             218021566},
+    "vgg16": {"batchnorm": 175730844, "bias_grad": 1094747, "conv_first": 155195211, "descent":
+             1952538667, "gemm_dw": 140475123, "gemm_dx": 16961707, "gemm_fwd": 137741163,
+             "perturb": 732214699, "pool": 89627447},
+    "vgg16bf": {"batchnorm": 175697446, "bias_grad": 1014282, "conv_first": 155200917, "descent":
+             1952539179, "gemm_dw": 113810026, "gemm_dx": 12092075, "gemm_fwd": 169170298,
+             "perturb": 732214699, "pool": 89627526, "softmax_ce": 114005},
+    "wrn16x10": {"batchnorm": 736317636, "descent": 2191769941, "gemm_dw": 1861227297, "gemm_dx":
+             549469773, "gemm_fwd": 1183651478, "perturb": 821927040, "pool": 441880681,
+             "unfold_fold": 629743101},
+    "wrn16x10bf": {"batchnorm": 736317722, "bias_grad": 51755, "descent": 2191770240, "gemm_dw":
+             1114158360, "gemm_dx": 496396715, "gemm_fwd": 1401399618, "perturb": 821926699,
+             "pool": 441879826, "softmax_ce": 114005, "unfold_fold": 629743088},
+    "wrn28x10": {"batchnorm": 760369300, "bias_grad": 350293, "descent": 4678181973, "gemm_dw":
+             1945638541, "gemm_dx": 458583637, "gemm_fwd": 1274137707, "perturb": 1754332715,
+             "pool": 508961026, "softmax_ce": 474453, "unfold_fold": 629743051},
+    "wrn40x10": {"batchnorm": 768819891, "bias_grad": 350293, "descent": 7157212672, "gemm_dw":
+             2022599027, "gemm_dx": 458556889, "gemm_fwd": 1320964114, "perturb": 2683970773,
+             "pool": 533675095, "softmax_ce": 474795, "unfold_fold": 629742976},
 }
 
 

@@ -54,8 +54,9 @@ void launch_sumsq_partials(const float* g, int64_t g_stride, int64_t n, int K, d
                            int nblk, hipStream_t s);
 // Inner product of K pairs of matrices G1, G2 (each `n` floats, replica stride `stride`, both
 // multiples of 4, 16-byte aligned): partials[k * pstride + j] for j < the returned count (<= 64).
-int launch_gram_dot(const float* G1, const float* G2, int64_t stride, int64_t n, int K, double* partials,
-                    int64_t pstride, hipStream_t s);
+// G1 (G2) is the sum of pieces1 (pieces2) >= 1 partial matrices lying piece_stride elements apart.
+int launch_gram_dot(const float* G1, const float* G2, int64_t stride, int64_t n, int K, int pieces1,
+                    int pieces2, int64_t piece_stride, double* partials, int64_t pstride, hipStream_t s);
 // Pass 2: norms[k] = sqrt(sum_{b<nblk} partials[k * partials_stride + b]); scale[k] = rho / (norm + gamma).
 // If loss_rows != nullptr also reduces loss_rows [K,B] to loss_out[k] = mean (both passes of
 // the tree are fixed-order, so the result is run-to-run deterministic).
@@ -149,6 +150,11 @@ struct GemmDesc {
   const struct AscentFusion* ascend;
   // If set (same kind of launch, `sumsq` given): only the sums of squares are written.
   int sumsq_only;
+  // bf16 operands in the blocked layout, plain fp32 result, none of the options above: with
+  // ksplit > 1 the contraction is cut into ksplit pieces of whole 32-deep steps, each taken by
+  // workgroups of its own, and piece j writes its partial result at C + j * split_stride
+  // (elements, beside the replica stride); the caller adds the pieces up in a fixed order.
+  int ksplit; int64_t split_stride;
 };
 struct AscentFusion {
   const float* x; const float* scale;

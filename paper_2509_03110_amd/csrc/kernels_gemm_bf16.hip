@@ -54,6 +54,10 @@ struct Bf16GemmParams {
   // and the operand copy that receives bf16(x + scale g) (fshadow, strideShadow, cbShadow above)
   const float* ax; const float* ascale;
   int mode;                               // EPI_* the launch asks for
+  // EPI_STORE with a plain fp32 result only: the contraction is cut into ksplit pieces, each
+  // taken by a workgroup of its own; piece j of replica k writes its partial result at
+  // C + k * strideC + j * strideSplit (elements)
+  int ksplit; long long strideSplit;
 };
 
 // s_waitcnt immediate: vmcnt = vm (0..63), lgkmcnt = lgkm (0..15), expcnt untouched.
@@ -118,6 +122,12 @@ struct Operand {
         }
       }
     }
+  }
+
+  // Moves the tile's first k-step `first` steps into the contraction.
+  __device__ __forceinline__ void skip(int first) {
+#pragma unroll
+    for (int j = 0; j < NLOAD; ++j) goff[j] += (unsigned)first * kstep;
   }
 
   // Requests k-step `ks` of the tile into `tile`.  A step at or past `ksteps` is sent out of
@@ -206,7 +216,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
   __shared__ __attribute__((aligned(1024))) unsigned char st3[NSTAGE == 4 ? STAGE_BYTES : 1024];
 
   const int w = blockIdx.x;
-  int bat, m0, n0, t_in = 0;
+  int bat, m0, n0, t_in = 0, piece = 0;
   if constexpr (MODE == EPI_STEP) {
     // The step reads the centre y, which all replicas share: an XCD takes whole groups of
     // kStepGroup x kStepGroup tiles and works through the replicas of one group before it
@@ -231,6 +241,10 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
     const int per_rep = p.tilesM * p.tilesN;
     bat = logical / per_rep;
     t_in = logical - bat * per_rep;
+    if (p.ksplit > 1) {                                // (replica, piece of the contraction)
+      piece = bat % p.ksplit;
+      bat /= p.ksplit;
+    }
     const int band = t_in / (GROUP_M * p.tilesN);
     const int first_m = band * GROUP_M;
     const int gsize = p.tilesM - first_m < GROUP_M ? p.tilesM - first_m : GROUP_M;
@@ -275,7 +289,16 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
             acc[i][j], 0, 0, 0);
   };
 
-  const int ksteps = (p.Kd + BK - 1) / BK;     // the stored operands are zero-padded to 32
+  int ksteps = (p.Kd + BK - 1) / BK;           // the stored operands are zero-padded to 32
+  if (p.ksplit > 1) {
+    // this workgroup's piece of the contraction: k-steps [first, first + ksteps), possibly none
+    const int per = (ksteps + p.ksplit - 1) / p.ksplit;
+    const int first = piece * per;
+    ksteps = ksteps - first < per ? ksteps - first : per;
+    if (ksteps < 0) ksteps = 0;
+    oa.skip(first);
+    ob.skip(first);
+  }
   lds_byte* s0 = (lds_byte*)st0;
   lds_byte* s1 = (lds_byte*)st1;
   lds_byte* s2 = (lds_byte*)st2;
@@ -341,7 +364,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
   // barrier: LDS operations of one wavefront complete in order) and writes them out as row
   // segments, consecutive lanes on consecutive 16 bytes; bias and the ReLU mask are read the
   // same way.
-  TC* C = reinterpret_cast<TC*>(p.C) + (long long)bat * p.strideC;
+  TC* C = reinterpret_cast<TC*>(p.C) + (long long)bat * p.strideC + (long long)piece * p.strideSplit;
   const float* bias = p.bias ? p.bias + (long long)bat * p.strideBias : nullptr;
   const float* bias_dir = p.bias_dir ? p.bias_dir + (long long)bat * p.strideBias : nullptr;
   const float bias_sc = p.bias_dir ? p.bias_scale[bat] : 0.f;
@@ -595,7 +618,7 @@ int launch_one(const Bf16GemmParams& p0, hipStream_t s, int* slots) {
   Bf16GemmParams p = p0;
   p.tilesM = (p.M + BM - 1) / BM;
   p.tilesN = (p.N + BN - 1) / BN;
-  p.total = p.tilesM * p.tilesN * p.batch;
+  p.total = p.tilesM * p.tilesN * p.batch * p.ksplit;
   p.chunks = (p.total + 7) / 8;
   if constexpr (sizeof(TC) == 4 && !AK && !BK_) {
     // the fused epilogues exist for weight-gradient launches (both operands m-major) only
@@ -704,6 +727,14 @@ int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s, int* s
   p.fx = nullptr;
   p.mode = EPI_STORE;
   const bool plain_f32 = !d.out_bf16 && d.epilogue == EPI_PLAIN && (d.ldC % 4) == 0 && (d.strideC % 4) == 0;
+  p.ksplit = 1; p.strideSplit = 0;
+  if (d.ksplit > 1) {
+    // partial results of a split contraction: plain fp32 stores and nothing else
+    if (!plain_f32 || d.sumsq != nullptr || d.fuse != nullptr || d.ascend != nullptr || d.sumsq_only ||
+        d.ksplit > 64 || (d.split_stride % 4) != 0 || tiles(128, 128) * d.ksplit >= (1ll << 28))
+      return -1;
+    p.ksplit = d.ksplit; p.strideSplit = d.split_stride;
+  }
   // 32-bit byte offsets inside one replica's W_l, rows of a ragged last tile included
   const bool offsets_fit = ((long long)d.M + 256) * d.ldC * 4 < 0x7FFFFFF0LL;
   if (d.fuse != nullptr) {

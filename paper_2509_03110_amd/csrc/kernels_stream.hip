@@ -124,10 +124,22 @@ __global__ __launch_bounds__(kThreads) void sumsq_partials_kernel(
 // ||dZ^T A||_F^2 = sum_{b,b'} (dZ dZ^T)[b,b'] (A A^T)[b,b']: the squared norm of the weight
 // gradient dW = dZ^T A [out x in] of a layer with batch B is the inner product of the two B x B
 // Gram matrices of its factors, which take 2 B^2 (out + in) flops instead of 2 B out in.  This
-// kernel is the inner product: partial sums in the fixed order of sumsq_partials_kernel.
+// kernel is the inner product: partial sums in the fixed order of sumsq_partials_kernel.  Each
+// Gram matrix may arrive as several partial matrices (its contraction split over workgroups),
+// `piece_stride` elements apart, which are added up first, in order.
+__device__ __forceinline__ f32x4 gram_word(const float* p, int64_t i, int pieces, int64_t piece_stride) {
+  f32x4 u = ldc<4>(p + i * 4);
+  for (int j = 1; j < pieces; ++j) {
+    const f32x4 t = ldc<4>(p + (int64_t)j * piece_stride + i * 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) u[e] += t[e];
+  }
+  return u;
+}
+
 __global__ __launch_bounds__(kThreads) void gram_dot_partials_kernel(
-    const float* __restrict__ G1, const float* __restrict__ G2, int64_t stride, int64_t nv,
-    double* __restrict__ partials, int64_t pstride, int nblk) {
+    const float* __restrict__ G1, const float* __restrict__ G2, int64_t stride, int64_t nv, int pieces1,
+    int pieces2, int64_t piece_stride, double* __restrict__ partials, int64_t pstride, int nblk) {
   const int k = blockIdx.y;
   const int64_t chunk = (nv + nblk - 1) / nblk;
   const int64_t beg = (int64_t)blockIdx.x * chunk;
@@ -137,8 +149,9 @@ __global__ __launch_bounds__(kThreads) void gram_dot_partials_kernel(
   float a0 = 0.f, a1 = 0.f;
   int64_t i = beg + threadIdx.x;
   for (; i + kThreads < end; i += 2 * kThreads) {
-    const auto u0 = ldc<4>(a + i * 4), w0 = ldc<4>(b + i * 4);
-    const auto u1 = ldc<4>(a + (i + kThreads) * 4), w1 = ldc<4>(b + (i + kThreads) * 4);
+    const auto u0 = gram_word(a, i, pieces1, piece_stride), w0 = gram_word(b, i, pieces2, piece_stride);
+    const auto u1 = gram_word(a, i + kThreads, pieces1, piece_stride);
+    const auto w1 = gram_word(b, i + kThreads, pieces2, piece_stride);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       a0 += u0[e] * w0[e];
@@ -146,7 +159,7 @@ __global__ __launch_bounds__(kThreads) void gram_dot_partials_kernel(
     }
   }
   for (; i < end; i += kThreads) {
-    const auto u0 = ldc<4>(a + i * 4), w0 = ldc<4>(b + i * 4);
+    const auto u0 = gram_word(a, i, pieces1, piece_stride), w0 = gram_word(b, i, pieces2, piece_stride);
 #pragma unroll
     for (int e = 0; e < 4; ++e) a0 += u0[e] * w0[e];
   }
@@ -421,13 +434,14 @@ void launch_sumsq_partials(const float* g, int64_t g_stride, int64_t n, int K, d
   }
 }
 
-int launch_gram_dot(const float* G1, const float* G2, int64_t stride, int64_t n, int K, double* partials,
-                    int64_t pstride, hipStream_t s) {
-  // n and stride are multiples of 4 (rows padded to 8 floats), the matrices 16-byte aligned
+int launch_gram_dot(const float* G1, const float* G2, int64_t stride, int64_t n, int K, int pieces1,
+                    int pieces2, int64_t piece_stride, double* partials, int64_t pstride, hipStream_t s) {
+  // n and the strides are multiples of 4 (rows padded to 8 floats), the matrices 16-byte aligned
   const int64_t nv = n / 4;
   int64_t nb = (nv + 4 * kThreads - 1) / (4 * kThreads);
   const int nblk = (int)(nb < 1 ? 1 : (nb > 64 ? 64 : nb));
-  gram_dot_partials_kernel<<<dim3(nblk, K), kThreads, 0, s>>>(G1, G2, stride, nv, partials, pstride, nblk);
+  gram_dot_partials_kernel<<<dim3(nblk, K), kThreads, 0, s>>>(G1, G2, stride, nv, pieces1, pieces2, piece_stride,
+                                                              partials, pstride, nblk);
   return nblk;
 }
 

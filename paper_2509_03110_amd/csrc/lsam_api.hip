@@ -301,6 +301,17 @@ size_t take(size_t& cursor, size_t bytes) {
   return at;
 }
 
+// Into how many pieces the contraction (length kd) of a layer's B x B Gram product is cut: on
+// its own it has only K (B/128)^2 tiles of work for 256 compute units and a long k-loop each.
+// Aims at one workgroup per compute unit (with the chip full already, two and four pieces
+// measured no faster and slower), keeps at least 16 steps of 32 per piece, at most 8 pieces.
+int gram_pieces(int K, int B, int kd) {
+  const int64_t tiles = (int64_t)K * ((B + 127) / 128) * ((B + 127) / 128);
+  const int64_t want = (256 + tiles - 1) / tiles;
+  const int64_t deep = ((kd + 31) / 32) / 16;
+  return (int)std::max<int64_t>(1, std::min<int64_t>({want, deep, 8}));
+}
+
 void build_layout(const lsam_config& c, Layout& lo) {
   lo.K = c.K;
   lo.L = c.n_layers;
@@ -542,9 +553,13 @@ void build_layout(const lsam_config& c, Layout& lo) {
     lo.splitk_bytes = need;
     if (need) lo.splitk = take(cur, need);
     if (lo.bf16) {
+      // room for the most pieces any layer's Gram products are cut into
       lo.ldg = (int)round_up(lo.B, 8);
-      lo.gram1 = take(cur, (size_t)lo.K * lo.B * lo.ldg * 4);
-      lo.gram2 = take(cur, (size_t)lo.K * lo.B * lo.ldg * 4);
+      int pieces = 1;
+      for (int l = lo.n_conv; l < lo.L; ++l)
+        pieces = std::max({pieces, gram_pieces(lo.K, lo.B, lo.layers[l].out), gram_pieces(lo.K, lo.B, lo.layers[l].in)});
+      lo.gram1 = take(cur, (size_t)pieces * lo.K * lo.B * lo.ldg * 4);
+      lo.gram2 = take(cur, (size_t)pieces * lo.K * lo.B * lo.ldg * 4);
     }
     if (c.noise_scale > 0.f) lo.noise_segs = take(cur, lo.pieces.size() * sizeof(NoiseSeg));
   }
@@ -1140,10 +1155,12 @@ int forward_backward(lsam_ctx* c, const void* X, const int32_t* labels, const vo
           q.strideC = (int64_t)B * lo.ldg; q.ldC = lo.ldg;
           q.M = q.N = B; q.Kd = which == 0 ? ly.out : ly.in; q.batch = K;
           q.in_bf16 = 1; q.out_bf16 = 0; q.epilogue = EPI_PLAIN;
+          q.ksplit = gram_pieces(K, B, q.Kd); q.split_stride = (int64_t)K * B * lo.ldg;
           if (launch_gemm(q, s) != 0) return fail(LSAM_EINVAL, "Gram GEMM of layer %d rejected", l);
         }
         slots += launch_gram_dot(c->at<float>(lo.gram1), c->at<float>(lo.gram2), (int64_t)B * lo.ldg,
-                                 (int64_t)B * lo.ldg, K, ssq + slots, lo.nblk, s);
+                                 (int64_t)B * lo.ldg, K, gram_pieces(K, B, ly.out), gram_pieces(K, B, ly.in),
+                                 (int64_t)K * B * lo.ldg, ssq + slots, lo.nblk, s);
         return LSAM_OK;
       }
       SamplerFusion f;

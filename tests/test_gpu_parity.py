@@ -363,7 +363,8 @@ def test_bf16_reduced_shapes_free_running_twenty_steps(name, width, B):
     ((384, 256, 256, 256, 100), 32, 3, (2, 3, 4), 1),
     ((40, 72, 100, 9), 20, 2, (1, 2), 0),              # widths that are no multiples of 4, 8 or 32
     ((352, 288, 288, 160), 160, 2, (2, 3), 1),         # ragged 128x128 tiles
-    ((512, 512, 520, 24), 256, 2, (2, 2), 1)])         # 256x128 tiles with a ragged last column tile
+    ((512, 512, 520, 24), 256, 2, (2, 2), 1),          # 256x128 tiles with a ragged last column tile
+    ((1040, 1536, 2048, 24), 32, 2, (2, 3), 1)])       # Gram products cut into 2, 3 and 4 pieces (33 k-steps: ragged)
 def test_fused_sampler_step_equals_the_separate_kernel(dims, B, K, tau, nesterov):
     """The fused path (norm of the first-pass weight gradients from Gram matrices or from a
     norm-only product, ascent in the epilogue of the recomputed products, sampler step in the
@@ -406,6 +407,15 @@ def test_bf16_ragged_shapes():
                                            tau=(2, 3), n_classes=9, steps=6, batch_pool=0)
     run_mlp(w, w.steps, 2e-2, 2e-2, margin=True)
     run_mlp(w, w.steps, 2e-2, 2e-2, margin=False, tol_flip=1e-1, anchor_after=2)
+
+
+def test_bf16_wide_layers_whose_gram_products_are_cut_into_pieces():
+    # contractions of 1040, 1536 and 2048 (33, 48, 64 steps of 32): the B x B Gram products behind
+    # the norm are cut into 2, 3 and 4 pieces, the first of them raggedly
+    w = workloads.WORKLOADS["cfg3"].scaled(name="wide16", K=2, dims=(1040, 1536, 2048, 24), batch=32,
+                                           tau=(2, 3), n_classes=24, steps=4, batch_pool=0)
+    # (64 k pre-activations per layer leave no initialisation with a margin: natural one, anchored)
+    run_mlp(w, w.steps, 2e-2, 2e-2, margin=False, tol_flip=1e-1, anchor_after=1)
 
 
 def test_bf16_ring_kernel_ragged_tiles_and_short_contractions():

@@ -200,6 +200,7 @@ template <> struct Out<__bf16> {
 //               the operand copy of the perturbed weights, bf16(x + scale * g)
 enum { EPI_STORE = 0, EPI_STEP = 1, EPI_SUMSQ = 2, EPI_ASCEND = 3 };
 constexpr int kStepGroup = 4;      // EPI_STEP: side of the tile groups an XCD takes through all replicas
+constexpr int kAscendBand = 2;    // EPI_ASCEND: tile rows of the band all XCDs share
 
 template <typename TC, int BM, int BN, int NSTAGE, bool A_KMAJOR, bool B_KMAJOR, int OCC, int MODE = EPI_STORE>
 __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams p) {
@@ -234,6 +235,26 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
     const int tm = (group / groupsN) * G + t % G, tn = (group % groupsN) * G + t / G;
     if (tm >= p.tilesM || tn >= p.tilesN) return;
     m0 = tm * BM; n0 = tn * BN;
+  } else if constexpr (MODE == EPI_ASCEND) {
+    // All XCDs work in the same replica and band of kAscendBand tile rows, XCD x on the column
+    // tiles n = 8 n' + x: the row panels of the first operand are then wanted by all eight at
+    // about the same time instead of by one XCD per replica (8.9-9.0 against 9.2-9.3 ms per
+    // step of the largest configuration; bands of 1 to 4 tile rows alike, 8 and 16 slower).
+    // chunks = workgroups per XCD = batch * tilesM * ceil(tilesN / 8).
+    constexpr int GROUP_M = kAscendBand;
+    const int x = w % 8, idx = w / 8;
+    const int tn8 = (p.tilesN + 7) / 8;
+    const int per_rep = p.tilesM * tn8;
+    bat = idx / per_rep;
+    if (bat >= p.batch) return;
+    t_in = idx - bat * per_rep;
+    const int band = t_in / (GROUP_M * tn8);
+    const int first_m = band * GROUP_M;
+    const int gsize = p.tilesM - first_m < GROUP_M ? p.tilesM - first_m : GROUP_M;
+    const int tin = t_in - band * GROUP_M * tn8;
+    const int tn = (tin / gsize) * 8 + x;
+    if (tn >= p.tilesN) return;
+    m0 = (first_m + tin % gsize) * BM; n0 = tn * BN;
   } else {
     const int logical = (w % 8) * p.chunks + w / 8;    // contiguous tile range per XCD
     if (logical >= p.total) return;
@@ -633,6 +654,9 @@ int launch_one(const Bf16GemmParams& p0, hipStream_t s, int* slots) {
       return 0;
     }
     if (p.mode == EPI_ASCEND) {
+      const long long per_xcd = (long long)p.batch * p.tilesM * ((p.tilesN + 7) / 8);
+      if (per_xcd * 8 >= (1ll << 31)) return -1;
+      p.chunks = (int)per_xcd;
       gemm_bf16_kernel<TC, BM, BN, NSTAGE, AK, BK_, OCC, EPI_ASCEND><<<p.chunks * 8, kThreads, 0, s>>>(p);
       if (slots) *slots = 0;
       return 0;
@@ -690,8 +714,8 @@ int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s, int* s
   else if (d.M >= 256 && d.N >= 256 && tiles(256, 256) >= 512 &&
            (d.Kd >= 1024 ? (d.b_kmajor || !d.a_kmajor) : d.a_kmajor && d.b_kmajor)) tile = 256;
   else if (d.M >= 256 && d.N >= 128 && tiles(256, 128) >= 256) tile = 2;
-  // The step epilogue streams seven arrays per tile; there the 128x128 tile (one workgroup per
-  // compute unit with its four-stage ring) measured best: 27.0-27.8 ms per step of the largest
+  // The step epilogue streams seven arrays per tile; there the 128x128 tile (two workgroups per
+  // compute unit, four-stage ring) measured best: 27.0-27.8 ms per step of the largest
   // configuration against 28.7-29.9 for 256x128 tiles, two workgroups per unit (and 30.3 for
   // 256x256); the ascent epilogue, one array in and one out, keeps the choice above (9.1 against
   // 9.6 ms with 128x128).

@@ -123,6 +123,63 @@ __global__ __launch_bounds__(kThreads) void bias_grad_kernel(const TD* __restric
   }
 }
 
+// The same for dz in the blocked bf16 layout, read the way it is stored: a workgroup owns two
+// adjacent column blocks (64 columns) of one replica, and per block row its 256 threads take the
+// 4 KiB the two blocks occupy as one 16-byte unit each -- a thread keeps its position inside the
+// block, so its 8 elements are the same 8 columns of the same row in every block row.  The 32
+// threads that share 8 columns are then combined in row order through LDS.
+__global__ __launch_bounds__(kThreads) void bias_grad_blocked_kernel(
+    const __bf16* __restrict__ dz, long long stride, float* __restrict__ db, long long strideDb, int B,
+    int N, double* __restrict__ sumsq, long long strideSumsq) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  __shared__ float part[kThreads][9];            // pitch 9: the combining reads hit distinct banks
+  const int k = blockIdx.y, t = threadIdx.x;
+  const int cb = b32s_blocks(N), rbs = b32s_blocks(B);
+  const int blk = blockIdx.x * 2 + (t >> 7);     // this thread's column block
+  const int row = (t & 127) >> 2;                // its row inside a block
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (blk < cb) {
+    const __bf16* p = dz + (long long)k * stride + (long long)blk * 1024 + (t & 127) * 8;
+    const long long step = (long long)cb * 1024;
+    auto add = [&](const u32x4& u) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc[2 * e] += __builtin_bit_cast(float, u[e] << 16);
+        acc[2 * e + 1] += __builtin_bit_cast(float, u[e] & 0xFFFF0000u);
+      }
+    };
+    int rb = 0;
+    for (; rb + 3 < rbs && (rb + 3) * 32 + row < B; rb += 4) {
+      const u32x4 u0 = *reinterpret_cast<const u32x4*>(p + rb * step);
+      const u32x4 u1 = *reinterpret_cast<const u32x4*>(p + (rb + 1) * step);
+      const u32x4 u2 = *reinterpret_cast<const u32x4*>(p + (rb + 2) * step);
+      const u32x4 u3 = *reinterpret_cast<const u32x4*>(p + (rb + 3) * step);
+      add(u0); add(u1); add(u2); add(u3);
+    }
+    for (; rb < rbs && rb * 32 + row < B; ++rb) add(*reinterpret_cast<const u32x4*>(p + rb * step));
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) part[t][e] = acc[e];
+  __syncthreads();
+  if (t < 64) {
+    // column c of this workgroup: block c / 32, unit q = (c % 32) / 8, element c % 8; in row r the
+    // unit sits at position q ^ ((r / 4) % 4)
+    const int n = blockIdx.x * 64 + t;
+    const int q = (t & 31) >> 3, e = t & 7, base = (t >> 5) * 128;
+    float r = 0.f;
+    if (n < N) {
+      for (int rr = 0; rr < 32; ++rr) r += part[base + rr * 4 + (q ^ ((rr >> 2) & 3))][e];
+      db[(long long)k * strideDb + n] = r;
+    }
+    if (sumsq != nullptr) {        // sum of the squares of this workgroup's 64 results
+      double sq = (double)r * (double)r;
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) sq += __shfl_xor(sq, off, 64);
+      if (t == 0) sumsq[(long long)k * strideSumsq + blockIdx.x] = sq;
+    }
+  }
+}
+
 // ---- narrow classifier head (fp32, at most 16 classes, at most 1024 inputs) ---------------------
 // With C <= 16 outputs the last layer is three matrix products far too thin for MFMA tiles
 // (forward [B x in] x [in x C], dX [B x C] x [C x in], dW [C x B] x [B x in]); as GEMMs each is
@@ -357,7 +414,7 @@ int launch_bias_grad(const void* dz, int64_t ld, int dz_bf16, float* db, int64_t
                      int B, int N, double* sumsq, int64_t sumsq_stride, hipStream_t s) {
   dim3 grid((N + 63) / 64, K);
   if (dz_bf16)
-    bias_grad_kernel<__bf16><<<grid, kThreads, 0, s>>>((const __bf16*)dz, ld, db, strideDb, B, N,
+    bias_grad_blocked_kernel<<<grid, kThreads, 0, s>>>((const __bf16*)dz, ld, db, strideDb, B, N,
                                                        sumsq, sumsq_stride);
   else
     bias_grad_kernel<float><<<grid, kThreads, 0, s>>>((const float*)dz, ld, db, strideDb, B, N,

@@ -32,56 +32,56 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "84cfd54fed468500"
+TRAFFIC_SOURCES = "e5913c3692896b67"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 2151595, "center": 100978176, "descent": 538490880, "gemm_dw": 43619275,
-             "gemm_dx": 42127701, "gemm_fwd": 62107701, "perturb": 201945344},
-    "cfg3": {"bias_grad": 13682048, "center": 1773557952, "descent": 884002, "gemm_dw_ascend":
-             652353570, "gemm_dw_norm": 17540907, "gemm_dw_step": 2938611439, "gemm_dx":
-             250134736, "gemm_fwd": 137770602, "softmax_ce": 1428821},
-    "cfg4": {"center": 3200037248, "descent": 25600039125, "perturb": 9600050773,
-             "sumsq_partials": 3417773120},
-    "cfg5": {"bias_grad": 118017722, "descent": 3479899, "gemm_dw_ascend": 6878671372,
-             "gemm_dw_norm": 152155947, "gemm_dw_step": 26949085038, "gemm_dx": 2576656928,
-             "gemm_fwd": 1161952470, "softmax_ce": 95744576},
-    "cnn5": {"bias_grad": 17357404, "conv_first": 80460597, "descent": 79476736, "gemm_dw":
-             67362876, "gemm_dx": 34787669, "gemm_fwd": 38345199, "perturb": 29813760, "pool":
-             68586073},
-    "cnn5bn": {"batchnorm": 157827644, "bias_grad": 565845, "conv_first": 80451317, "descent":
-             79542272, "gemm_dw": 67390347, "gemm_dx": 34787669, "gemm_fwd": 38345318, "perturb":
-             29838336, "pool": 68585842},
-    "resnet18": {"batchnorm": 259999049, "conv_first": 155236235, "descent": 1430962475,
-             "gemm_dw": 308801215, "gemm_dx": 178773945, "gemm_fwd": 230761705, "perturb":
-             536623531, "pool": 183890645, "unfold_fold": 218021630},
-    "resnet18bf": {"batchnorm": 260000088, "bias_grad": 52992, "conv_first": 155232075, "descent":
-             1430962304, "gemm_dw": 268496781, "gemm_dx": 145290828, "gemm_fwd": 275122021,
-             "perturb": 536623573, "pool": 183890630, "softmax_ce": 114005, "unfold_fold":
-             218021641},
-    "resnet20": {"batchnorm": 86667720, "descent": 34871808, "gemm_dw": 212890181, "gemm_dx":
-             269451780, "gemm_fwd": 100352742, "perturb": 13086720, "pool": 64194170,
-             "unfold_fold": 328668063},
-    "resnet34": {"batchnorm": 244146766, "bias_grad": 352128, "conv_first": 155200256, "descent":
-             2731188352, "gemm_dw": 265157874, "gemm_dx": 153685147, "gemm_fwd": 215050183,
-             "perturb": 1024209195, "pool": 195406044, "softmax_ce": 474731, "unfold_fold":
-             218021566},
-    "vgg16": {"batchnorm": 175730844, "bias_grad": 1094747, "conv_first": 155195211, "descent":
-             1952538667, "gemm_dw": 140475123, "gemm_dx": 16961707, "gemm_fwd": 137741163,
-             "perturb": 732214699, "pool": 89627447},
-    "vgg16bf": {"batchnorm": 175697446, "bias_grad": 1014282, "conv_first": 155200917, "descent":
-             1952539179, "gemm_dw": 113810026, "gemm_dx": 12092075, "gemm_fwd": 169170298,
-             "perturb": 732214699, "pool": 89627526, "softmax_ce": 114005},
-    "wrn16x10": {"batchnorm": 736317636, "descent": 2191769941, "gemm_dw": 1861227297, "gemm_dx":
-             549469773, "gemm_fwd": 1183651478, "perturb": 821927040, "pool": 441880681,
-             "unfold_fold": 629743101},
-    "wrn16x10bf": {"batchnorm": 736317722, "bias_grad": 51755, "descent": 2191770240, "gemm_dw":
-             1114158360, "gemm_dx": 496396715, "gemm_fwd": 1401399618, "perturb": 821926699,
-             "pool": 441879826, "softmax_ce": 114005, "unfold_fold": 629743088},
-    "wrn28x10": {"batchnorm": 760369300, "bias_grad": 350293, "descent": 4678181973, "gemm_dw":
-             1945638541, "gemm_dx": 458583637, "gemm_fwd": 1274137707, "perturb": 1754332715,
-             "pool": 508961026, "softmax_ce": 474453, "unfold_fold": 629743051},
-    "wrn40x10": {"batchnorm": 768819891, "bias_grad": 350293, "descent": 7157212672, "gemm_dw":
-             2022599027, "gemm_dx": 458556889, "gemm_fwd": 1320964114, "perturb": 2683970773,
-             "pool": 533675095, "softmax_ce": 474795, "unfold_fold": 629742976},
+    "cfg2": {"bias_grad": 2148523, "center": 100986368, "descent": 538490880, "gemm_dw": 43636981,
+             "gemm_dx": 42127701, "gemm_fwd": 62107637, "perturb": 201945557},
+    "cfg3": {"bias_grad": 13690142, "center": 1773566720, "descent": 884028, "gemm_dw_ascend":
+             732966315, "gemm_dw_norm": 17549099, "gemm_dw_step": 2937680128, "gemm_dx":
+             250149973, "gemm_fwd": 144075071, "softmax_ce": 1429717},
+    "cfg4": {"center": 3200045440, "descent": 25600046251, "perturb": 9600050859,
+             "sumsq_partials": 3415341419},
+    "cfg5": {"bias_grad": 117981758, "descent": 3479802, "gemm_dw_ascend": 6220240713,
+             "gemm_dw_norm": 152151723, "gemm_dw_step": 26945262366, "gemm_dx": 2583557764,
+             "gemm_fwd": 1162260679, "softmax_ce": 95693296},
+    "cnn5": {"bias_grad": 17354844, "conv_first": 80456629, "descent": 79476736, "gemm_dw":
+             67364711, "gemm_dx": 34787669, "gemm_fwd": 38345421, "perturb": 29813760, "pool":
+             68586126},
+    "cnn5bn": {"batchnorm": 157826087, "bias_grad": 562773, "conv_first": 80454059, "descent":
+             79542272, "gemm_dw": 67388732, "gemm_dx": 34787669, "gemm_fwd": 38345694, "perturb":
+             29838336, "pool": 68585845},
+    "resnet18": {"batchnorm": 259997251, "conv_first": 155244779, "descent": 1430969472,
+             "gemm_dw": 308422632, "gemm_dx": 178728007, "gemm_fwd": 230415962, "perturb":
+             536623829, "pool": 183890637, "unfold_fold": 218021620},
+    "resnet18bf": {"batchnorm": 259998338, "bias_grad": 50432, "conv_first": 155240341, "descent":
+             1430969557, "gemm_dw": 268605351, "gemm_dx": 145305429, "gemm_fwd": 274909122,
+             "perturb": 536623659, "pool": 183890635, "softmax_ce": 125184, "unfold_fold":
+             218021613},
+    "resnet20": {"batchnorm": 86666182, "descent": 34871808, "gemm_dw": 212817163, "gemm_dx":
+             269454653, "gemm_fwd": 100364212, "perturb": 13086720, "pool": 64194128,
+             "unfold_fold": 328691049},
+    "resnet34": {"batchnorm": 244145058, "bias_grad": 347008, "conv_first": 155202571, "descent":
+             2731195776, "gemm_dw": 264873867, "gemm_dx": 153677400, "gemm_fwd": 215068571,
+             "perturb": 1024209237, "pool": 195406035, "softmax_ce": 485653, "unfold_fold":
+             218021511},
+    "vgg16": {"batchnorm": 175729170, "bias_grad": 1091657, "conv_first": 155184309, "descent":
+             1952545877, "gemm_dw": 140485944, "gemm_dx": 16961707, "gemm_fwd": 137660600,
+             "perturb": 732214784, "pool": 89627452},
+    "vgg16bf": {"batchnorm": 175695848, "bias_grad": 1011180, "conv_first": 155198037, "descent":
+             1952546005, "gemm_dw": 113753909, "gemm_dx": 12092075, "gemm_fwd": 169089462,
+             "perturb": 732214827, "pool": 89627543, "softmax_ce": 124587},
+    "wrn16x10": {"batchnorm": 736315332, "descent": 2191777280, "gemm_dw": 1858459622, "gemm_dx":
+             549486153, "gemm_fwd": 1181831377, "perturb": 821926784, "pool": 441879834,
+             "unfold_fold": 629743093},
+    "wrn16x10bf": {"batchnorm": 736315362, "bias_grad": 50048, "descent": 2191776981, "gemm_dw":
+             1111452339, "gemm_dx": 496394855, "gemm_fwd": 1406746803, "perturb": 821926997,
+             "pool": 441879838, "softmax_ce": 124587, "unfold_fold": 629743085},
+    "wrn28x10": {"batchnorm": 760367276, "bias_grad": 346880, "descent": 4678188459, "gemm_dw":
+             1944948603, "gemm_dx": 458575257, "gemm_fwd": 1273365848, "perturb": 1754332331,
+             "pool": 508961029, "softmax_ce": 485035, "unfold_fold": 629743029},
+    "wrn40x10": {"batchnorm": 768817737, "bias_grad": 346880, "descent": 7157220139, "gemm_dw":
+             2022935155, "gemm_dx": 458560736, "gemm_fwd": 1319765114, "perturb": 2683970944,
+             "pool": 533675093, "softmax_ce": 485376, "unfold_fold": 629742944},
 }
 
 

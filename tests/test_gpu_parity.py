@@ -377,20 +377,28 @@ def test_fused_sampler_step_equals_the_separate_kernel(dims, B, K, tau, nesterov
     several steps and center updates."""
     w = workloads.WORKLOADS["cfg3"].scaled(name="fuse", K=K, dims=dims, batch=B, tau=tau,
                                            nesterov=nesterov, n_classes=dims[-1], batch_pool=0)
+    _fused_equals_separate(w, 5)
+
+
+def _fused_equals_separate(w, steps):
+    """One context with the fused path, one with every gradient stored and the streaming kernels
+    run on it, same inputs: norms, parameters, velocities, iterate sums, center to 2e-6; the operand
+    copy of x~ equal but for elements on a rounding boundary."""
+    K = w.K
     init = workloads.init_params(w)
     cfg, keep = lsam.config_from_workload(w)
     a = lsam.Lsam(cfg, init, device=DEV, keep=keep)
     b = lsam.Lsam(cfg, init, device=DEV, keep=keep)
     assert a.lsam_set_fused_step(True) == 1 and b.lsam_set_fused_step(False) == 0
-    for t in range(5):
+    for t in range(steps):
         X, lab = workloads.batch(w, t)
         Xd, ld = to_dev(X, lab, w)
         a.lsam_step(Xd, ld, None)
         b.lsam_step(Xd, ld, None)
-        assert np.allclose(a.lsam_get_norms(), b.lsam_get_norms(), rtol=2e-6, atol=0)
+        assert np.allclose(a.lsam_get_norms(), b.lsam_get_norms(), rtol=2e-6, atol=0), (t, w.dims)
         assert a.lsam_sync() == b.lsam_sync()
         for i in list(range(K)) + [-1]:
-            assert rel_max(a.lsam_get_params(i), b.lsam_get_params(i)) < 2e-6, (t, i)
+            assert rel_max(a.lsam_get_params(i), b.lsam_get_params(i)) < 2e-6, (t, i, w.dims)
         for i in range(K):
             for which in (lsam.BUF_VELOCITY, lsam.BUF_ITER_SUM):
                 assert rel_max(a.lsam_get_buffer(which, i), b.lsam_get_buffer(which, i)) < 2e-6, (t, i, which)
@@ -400,6 +408,38 @@ def test_fused_sampler_step_equals_the_separate_kernel(dims, B, K, tau, nesterov
             assert np.all(np.abs(pa - pb)[differ] <= 2.0 ** -7 * np.abs(pb)[differ]), (t, i)
     a.close()
     b.close()
+
+
+def _random_bf16_mlp(rng):
+    """A bf16 dense model drawn at random: 2 to 4 layers with widths that are and are not
+    multiples of 4, 8, 32 and of the tile sides, some long enough for the Gram products behind
+    the norm to be cut into pieces, a batch that is or is not a multiple of 32, 1 to 5 replicas."""
+    widths = [40, 72, 100, 128, 160, 288, 352, 520, 1040, 1536]
+    L = int(rng.integers(2, 5))
+    dims = [int(rng.choice([40, 352, 384, 1040]))]
+    budget = 2.5e6                                  # weights per replica, so the oracle stays quick
+    for _ in range(L - 1):
+        fits = [v for v in widths if dims[-1] * v <= budget]
+        dims.append(int(rng.choice(fits)))
+        budget -= dims[-2] * dims[-1]
+    classes = int(rng.choice([9, 24, 100, 160]))
+    dims.append(classes)
+    K = int(rng.integers(1, 6))
+    B = int(rng.choice([20, 32, 64, 160, 256]))
+    tau = tuple(int(v) for v in rng.integers(1, 5, size=K))
+    return workloads.WORKLOADS["cfg3"].scaled(name="rand16", K=K, dims=tuple(dims), batch=B, tau=tau,
+                                               nesterov=int(rng.integers(0, 2)), n_classes=classes,
+                                               steps=4, batch_pool=0, data_seed=int(rng.integers(1, 1000)))
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_randomly_drawn_bf16_dense_models(seed):
+    w = _random_bf16_mlp(np.random.default_rng(2000 + seed))
+    print("seed %d: dims %s, B=%d, K=%d, tau=%s, nesterov=%d" % (seed, w.dims, w.batch, w.K, w.tau, w.nesterov))
+    _fused_equals_separate(w, 4)
+    # and the fused path against the oracle, from the oracle's state at every step past the first
+    # (natural initialisation: a ReLU decided the other way moves single rows, which tol_flip covers)
+    run_mlp(w, 3, 2e-2, 2e-2, margin=False, tol_flip=1e-1, anchor_after=1)
 
 
 def test_bf16_ragged_shapes():

@@ -442,6 +442,26 @@ def test_randomly_drawn_bf16_dense_models(seed):
     run_mlp(w, 3, 2e-2, 2e-2, margin=False, tol_flip=1e-1, anchor_after=1)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_randomly_drawn_fp32_dense_models(seed):
+    """fp32 dense models drawn at random (1 to 3 hidden layers; widths, batches and class counts
+    on both sides of every kernel's limits: the narrow-head kernels up to 16 classes, contractions
+    split over workgroups, ragged tiles) against the oracle: parameters to 1e-4 at every step."""
+    rng = np.random.default_rng(3000 + seed)
+    dims = [int(rng.choice([20, 100, 784, 1030]))]
+    for _ in range(int(rng.integers(1, 4))):
+        dims.append(int(rng.choice([10, 24, 37, 64, 128, 200, 264, 1024])))
+    classes = int(rng.choice([3, 10, 16, 17, 40]))
+    dims.append(classes)
+    K = int(rng.integers(1, 5))
+    w = workloads.WORKLOADS["cfg1"].scaled(name="rand32", K=K, dims=tuple(dims), batch=int(rng.choice([8, 20, 32, 128])),
+                                           tau=tuple(int(v) for v in rng.integers(1, 5, size=K)),
+                                           nesterov=int(rng.integers(0, 2)), n_classes=classes, steps=4,
+                                           data_seed=int(rng.integers(1, 1000)))
+    print("seed %d: dims %s, B=%d, K=%d, tau=%s, nesterov=%d" % (seed, w.dims, w.batch, w.K, w.tau, w.nesterov))
+    run_mlp(w, 4, 1e-4, 1e-3, margin=False, anchor_after=1)
+
+
 def test_bf16_ragged_shapes():
     w = workloads.WORKLOADS["cfg3"].scaled(name="ragged16", K=2, dims=(40, 72, 100, 9), batch=20,
                                            tau=(2, 3), n_classes=9, steps=6, batch_pool=0)

@@ -1436,3 +1436,15 @@ def test_randomly_drawn_residual_configurations_match_oracle(seed):
     print("seed %d: %d convolutions, preact=%d, skip=%s, proj=%s, stride=%s, pool=%s, gap=%d, K=%d: %.2e"
           % (seed, w.n_conv, w.preact, bin(w.skip_mask), bin(w.proj_mask), bin(w.stride_mask), bin(w.pool_mask),
              w.global_avg_pool, w.K, worst))
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_randomly_drawn_residual_configurations_with_bf16_products(seed):
+    """The same draw with both operands of every matrix product rounded to bf16 on their way into
+    the matrix unit: 2e-2 on the parameters, step by step from the oracle's state.  (The bf16
+    gradient of a normalised network moves by percent when an operand moves by its last bit, see
+    the oracle's pin of that, hence the looser bound on gradients and velocities.)"""
+    w = _random_residual_workload(np.random.default_rng(1000 + seed)).scaled(gemm_dtype=1)
+    worst = run_mlp(w, 4, 2e-2, 2e-2, anchor_after=1, tol_flip=3e-1, init_fn=bn_away_from_zero)
+    print("seed %d, bf16 products: %d convolutions, preact=%d, K=%d: %.2e" % (seed, w.n_conv, w.preact, w.K, worst))
+

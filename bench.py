@@ -32,56 +32,56 @@ PEAK_TFLOPS = {0: 157.3, 1: 2500.0}   # dense MFMA: fp32, bf16
 # 1 GiB device copy: x2.0 and x1.0), summed over the dispatches of a class and divided by its
 # launches (a split-K GEMM and its reduce count as one launch).  The figures belong to the
 # kernel sources whose digest is TRAFFIC_SOURCES; with any other sources `traffic` is null.
-TRAFFIC_SOURCES = "e5913c3692896b67"
+TRAFFIC_SOURCES = "184631bf3fbaf3a4"
 TRAFFIC = {
-    "cfg2": {"bias_grad": 2148523, "center": 100986368, "descent": 538490880, "gemm_dw": 43636981,
-             "gemm_dx": 42127701, "gemm_fwd": 62107637, "perturb": 201945557},
-    "cfg3": {"bias_grad": 13690142, "center": 1773566720, "descent": 884028, "gemm_dw_ascend":
-             732966315, "gemm_dw_norm": 17549099, "gemm_dw_step": 2937680128, "gemm_dx":
-             250149973, "gemm_fwd": 144075071, "softmax_ce": 1429717},
-    "cfg4": {"center": 3200045440, "descent": 25600046251, "perturb": 9600050859,
-             "sumsq_partials": 3415341419},
-    "cfg5": {"bias_grad": 117981758, "descent": 3479802, "gemm_dw_ascend": 6220240713,
-             "gemm_dw_norm": 152151723, "gemm_dw_step": 26945262366, "gemm_dx": 2583557764,
-             "gemm_fwd": 1162260679, "softmax_ce": 95693296},
-    "cnn5": {"bias_grad": 17354844, "conv_first": 80456629, "descent": 79476736, "gemm_dw":
-             67364711, "gemm_dx": 34787669, "gemm_fwd": 38345421, "perturb": 29813760, "pool":
-             68586126},
-    "cnn5bn": {"batchnorm": 157826087, "bias_grad": 562773, "conv_first": 80454059, "descent":
-             79542272, "gemm_dw": 67388732, "gemm_dx": 34787669, "gemm_fwd": 38345694, "perturb":
-             29838336, "pool": 68585845},
-    "resnet18": {"batchnorm": 259997251, "conv_first": 155244779, "descent": 1430969472,
-             "gemm_dw": 308422632, "gemm_dx": 178728007, "gemm_fwd": 230415962, "perturb":
-             536623829, "pool": 183890637, "unfold_fold": 218021620},
-    "resnet18bf": {"batchnorm": 259998338, "bias_grad": 50432, "conv_first": 155240341, "descent":
-             1430969557, "gemm_dw": 268605351, "gemm_dx": 145305429, "gemm_fwd": 274909122,
-             "perturb": 536623659, "pool": 183890635, "softmax_ce": 125184, "unfold_fold":
-             218021613},
-    "resnet20": {"batchnorm": 86666182, "descent": 34871808, "gemm_dw": 212817163, "gemm_dx":
-             269454653, "gemm_fwd": 100364212, "perturb": 13086720, "pool": 64194128,
-             "unfold_fold": 328691049},
-    "resnet34": {"batchnorm": 244145058, "bias_grad": 347008, "conv_first": 155202571, "descent":
-             2731195776, "gemm_dw": 264873867, "gemm_dx": 153677400, "gemm_fwd": 215068571,
-             "perturb": 1024209237, "pool": 195406035, "softmax_ce": 485653, "unfold_fold":
-             218021511},
-    "vgg16": {"batchnorm": 175729170, "bias_grad": 1091657, "conv_first": 155184309, "descent":
-             1952545877, "gemm_dw": 140485944, "gemm_dx": 16961707, "gemm_fwd": 137660600,
-             "perturb": 732214784, "pool": 89627452},
-    "vgg16bf": {"batchnorm": 175695848, "bias_grad": 1011180, "conv_first": 155198037, "descent":
-             1952546005, "gemm_dw": 113753909, "gemm_dx": 12092075, "gemm_fwd": 169089462,
-             "perturb": 732214827, "pool": 89627543, "softmax_ce": 124587},
-    "wrn16x10": {"batchnorm": 736315332, "descent": 2191777280, "gemm_dw": 1858459622, "gemm_dx":
-             549486153, "gemm_fwd": 1181831377, "perturb": 821926784, "pool": 441879834,
-             "unfold_fold": 629743093},
-    "wrn16x10bf": {"batchnorm": 736315362, "bias_grad": 50048, "descent": 2191776981, "gemm_dw":
-             1111452339, "gemm_dx": 496394855, "gemm_fwd": 1406746803, "perturb": 821926997,
-             "pool": 441879838, "softmax_ce": 124587, "unfold_fold": 629743085},
-    "wrn28x10": {"batchnorm": 760367276, "bias_grad": 346880, "descent": 4678188459, "gemm_dw":
-             1944948603, "gemm_dx": 458575257, "gemm_fwd": 1273365848, "perturb": 1754332331,
-             "pool": 508961029, "softmax_ce": 485035, "unfold_fold": 629743029},
-    "wrn40x10": {"batchnorm": 768817737, "bias_grad": 346880, "descent": 7157220139, "gemm_dw":
-             2022935155, "gemm_dx": 458560736, "gemm_fwd": 1319765114, "perturb": 2683970944,
-             "pool": 533675093, "softmax_ce": 485376, "unfold_fold": 629742944},
+    "cfg2": {"bias_grad": 2148523, "center": 84162976, "descent": 538499328, "gemm_dw": 43632755,
+             "gemm_dx": 42127701, "gemm_fwd": 62107669, "perturb": 201932160},
+    "cfg3": {"bias_grad": 13690112, "center": 1393525408, "descent": 877295, "gemm_dw_ascend":
+             732954300, "gemm_dw_norm": 17543979, "gemm_dw_step": 2905857877, "gemm_dx":
+             250149963, "gemm_fwd": 144075458, "softmax_ce": 1429696},
+    "cfg4": {"center": 2400049184, "descent": 25600058581, "perturb": 9600045269,
+             "sumsq_partials": 3416877589},
+    "cfg5": {"bias_grad": 117981832, "descent": 3481941, "gemm_dw_ascend": 6219425829,
+             "gemm_dw_norm": 152019669, "gemm_dw_step": 27294712777, "gemm_dx": 2581714869,
+             "gemm_fwd": 1161916226, "softmax_ce": 96450869},
+    "cnn5": {"bias_grad": 17354844, "conv_first": 80453440, "descent": 79486763, "gemm_dw":
+             67376004, "gemm_dx": 34787669, "gemm_fwd": 38345732, "perturb": 29800448, "pool":
+             68586073},
+    "cnn5bn": {"batchnorm": 157826080, "bias_grad": 562773, "conv_first": 80449835, "descent":
+             79552597, "gemm_dw": 67362485, "gemm_dx": 34787669, "gemm_fwd": 38344209, "perturb":
+             29825024, "pool": 68585845},
+    "resnet18": {"batchnorm": 259997189, "conv_first": 155183819, "descent": 1431000491,
+             "gemm_dw": 308601196, "gemm_dx": 178777639, "gemm_fwd": 230439253, "perturb":
+             536618624, "pool": 183890665, "unfold_fold": 218021649},
+    "resnet18bf": {"batchnorm": 259998289, "bias_grad": 50432, "conv_first": 155182635, "descent":
+             1431003904, "gemm_dw": 268401223, "gemm_dx": 145274408, "gemm_fwd": 274711036,
+             "perturb": 536618453, "pool": 183890643, "softmax_ce": 124587, "unfold_fold":
+             218021620},
+    "resnet20": {"batchnorm": 86666182, "descent": 34874283, "gemm_dw": 212806394, "gemm_dx":
+             269469124, "gemm_fwd": 100369632, "perturb": 13073408, "pool": 64194118,
+             "unfold_fold": 328611381},
+    "resnet34": {"batchnorm": 244145097, "bias_grad": 347008, "conv_first": 155250368, "descent":
+             2731215403, "gemm_dw": 264940556, "gemm_dx": 153711067, "gemm_fwd": 215734746,
+             "perturb": 1024204416, "pool": 195406042, "softmax_ce": 485291, "unfold_fold":
+             218021544},
+    "vgg16": {"batchnorm": 175729217, "bias_grad": 1091675, "conv_first": 155189792, "descent":
+             1952575829, "gemm_dw": 140527392, "gemm_dx": 16961707, "gemm_fwd": 137751684,
+             "perturb": 732209579, "pool": 89627452},
+    "vgg16bf": {"batchnorm": 175695851, "bias_grad": 1011170, "conv_first": 155195029, "descent":
+             1952580053, "gemm_dw": 113747526, "gemm_dx": 12092075, "gemm_fwd": 169044908,
+             "perturb": 732209749, "pool": 89627526, "softmax_ce": 124587},
+    "wrn16x10": {"batchnorm": 736315405, "descent": 2191812864, "gemm_dw": 1854432135, "gemm_dx":
+             549450901, "gemm_fwd": 1184345296, "perturb": 821921621, "pool": 441879842,
+             "unfold_fold": 629743101},
+    "wrn16x10bf": {"batchnorm": 736315944, "bias_grad": 50048, "descent": 2191814955, "gemm_dw":
+             1114631144, "gemm_dx": 496001376, "gemm_fwd": 1400264620, "perturb": 821921707,
+             "pool": 441879842, "softmax_ce": 124587, "unfold_fold": 629743085},
+    "wrn28x10": {"batchnorm": 760367501, "bias_grad": 346880, "descent": 4678217856, "gemm_dw":
+             1943620653, "gemm_dx": 458547460, "gemm_fwd": 1271969861, "perturb": 1754327680,
+             "pool": 508961023, "softmax_ce": 485035, "unfold_fold": 629743043},
+    "wrn40x10": {"batchnorm": 768818096, "bias_grad": 346880, "descent": 7157244245, "gemm_dw":
+             2026127685, "gemm_dx": 458552949, "gemm_fwd": 1321328546, "perturb": 2683965739,
+             "pool": 533675103, "softmax_ce": 485376, "unfold_fold": 629742957},
 }
 
 
@@ -185,16 +185,18 @@ def conv_bytes(w, layers):
     return out
 
 
-def stream_bytes(w, fused_step=False):
+def stream_bytes(w, fused_step=False, restarts=0.0):
     """Algorithmic bytes per all-replica step of the update-path kernels (reads + writes
     the method itself requires; y is shared by the K replicas): descent reads x, g2, v, S
     (16 B per parameter) and writes x, v, S (12 B), plus the bf16 operand copy (2 B) in bf16
-    mode, plus y once for all replicas."""
+    mode, plus y once for all replicas.  `restarts`: replicas per step, on average, whose sum
+    of iterates starts again from zero (served by the center update one tick before): their S
+    is written but not read."""
     n = float(w.K) * w.d
     bf = w.gemm_dtype == 1 and not w.n_conv
     out = {"sumsq_partials": 4 * n,
            "perturb": (10 if bf else 12) * n,
-           "descent": (30 if bf else 28) * n + 4.0 * w.d}
+           "descent": (30 if bf else 28) * n + 4.0 * w.d - 4.0 * restarts * w.d}
     if fused_step:
         # the weight matrices take their step where the second-pass gradient is produced: that
         # kernel reads x, v, S (12 B per parameter) and y once, writes x, v, S (12 B) and the
@@ -202,8 +204,8 @@ def stream_bytes(w, fused_step=False):
         # with the bias vectors
         nw = sum(a * b for a, b in w.layer_shapes)
         nb = w.d - nw
-        out["gemm_dw_step"] = 26.0 * w.K * nw + 4.0 * nw
-        out["descent"] = 28.0 * w.K * nb + 4.0 * nb
+        out["gemm_dw_step"] = 26.0 * w.K * nw + 4.0 * nw - 4.0 * restarts * nw
+        out["descent"] = 28.0 * w.K * nb + 4.0 * nb - 4.0 * restarts * nb
         # the ascent GEMMs read x and write the bf16 copy of x~; no perturbation kernel runs
         out["gemm_dw_ascend"] = 6.0 * w.K * nw
         del out["perturb"]
@@ -333,14 +335,16 @@ def run_workload(w, steps, warmup, kernel_timing=True):
         layers = layer_table(eng, w) if w.dims else []
         fused_step = any(r[2] for r in layers)
         flops = gemm_flops(w, layers) if w.dims else {}
-        nbytes = stream_bytes(w, fused_step)
-        nbytes.update(conv_bytes(w, layers))
-        # center update: 8 B/param per due replica (S read, S cleared) + 16 B/param (y and
-        # g'_prev read and written), summed over the ticks of this run that had a sync
+        # center update: 4 B/param per due replica (S read; starting it again from zero costs
+        # no write, the next step simply does not read it) + 16 B/param (y and g'_prev read and
+        # written), summed over the ticks of this run that had a sync
         first = warmup + steps
         due, _ = lsam.lsam_schedule_replay(cfg, first + steps)
         nd = due[first:].sum(axis=1)
-        nbytes["center"] = float(np.sum((8.0 * nd + 16.0) * (nd > 0))) * w.d / steps
+        restarts = float(due[first - 1:-1].sum()) / steps     # served one tick earlier
+        nbytes = stream_bytes(w, fused_step, restarts)
+        nbytes.update(conv_bytes(w, layers))
+        nbytes["center"] = float(np.sum((4.0 * nd + 16.0) * (nd > 0))) * w.d / steps
         traffic = TRAFFIC.get(w.name, {}) if kernel_sources_digest() == TRAFFIC_SOURCES else {}
         for name, (cnt, tot) in stats.items():
             if cnt == 0:

@@ -165,7 +165,8 @@ typedef struct {
 /* Which per-replica buffer `lsam_get_buffer` copies out. */
 #define LSAM_BUF_PARAMS     0  /* x_i (replica -1: center y)                          */
 #define LSAM_BUF_VELOCITY   1  /* v_i                                                  */
-#define LSAM_BUF_ITER_SUM   2  /* S_i = sum of x_i's iterates since its last sync     */
+#define LSAM_BUF_ITER_SUM   2  /* S_i = sum of x_i's iterates since its last sync (zero
+                                  right after the sync that served replica i)         */
 #define LSAM_BUF_GRAD       3  /* gradient buffer (g2 after a step, but see
                                   lsam_set_fused_step; MLP mode only)                 */
 #define LSAM_BUF_PERTURBED  4  /* fp32 mode: x~_i of the last step.  bf16 mode: the bf16

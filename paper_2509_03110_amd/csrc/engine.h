@@ -60,9 +60,11 @@ int launch_gram_dot(const float* G1, const float* G2, int64_t stride, int64_t n,
 // Pass 2: norms[k] = sqrt(sum_{b<nblk} partials[k * partials_stride + b]); scale[k] = rho / (norm + gamma).
 // If loss_rows != nullptr also reduces loss_rows [K,B] to loss_out[k] = mean (both passes of
 // the tree are fixed-order, so the result is run-to-run deterministic).
+// `restart` (may be null): the per-replica marks described at launch_center; this kernel, which
+// runs once per step before anything touches the iterate sums, counts every mark down by one.
 void launch_norm_finish(const double* partials, int nblk, int64_t partials_stride, int K, float rho, float gamma,
                         float* norms, float* scale, const float* loss_rows, int B,
-                        float* loss_out, hipStream_t s);
+                        float* loss_out, hipStream_t s, int32_t* restart = nullptr);
 // x~ = x + scale[k] * g.  Writes fp32 (xt_f32), or, if xt_bf16 is non-null, the bf16 operand
 // copy of the weight matrices in the blocked layout described by `map` (replica stride
 // `shadow_stride` elements).
@@ -72,20 +74,28 @@ void launch_perturb(const float* x, const float* g, int64_t g_stride, const floa
 // Descent + coupling for all K replicas, y read once per index:
 //   G = g + lam[k] (x - y); v = mu v + G; x -= lr (G + mu v) [nesterov] | lr v; S += x.
 // Also refreshes the bf16 operand copy of the weight matrices if `shadow` is non-null, and adds
-// the Langevin noise described by `noise` (null: none) to the new x.
+// the Langevin noise described by `noise` (null: none) to the new x.  A replica whose mark in
+// `restart` (may be null) is 1 starts its sum afresh: S = x, without reading S.
 void launch_descent(float* x, const float* g, int64_t g_stride, float* v, float* S,
                     const float* y, uint16_t* shadow, const ShadowMap* map, int64_t shadow_stride,
                     int64_t stride, int64_t n, int K, const ReplicaScalars& lam, float lr, float mu,
-                    int nesterov, const NoiseMap* noise, hipStream_t s);
+                    int nesterov, const NoiseMap* noise, hipStream_t s, const int32_t* restart = nullptr);
 // dst[c * dst_stride + i] = (1/K) sum_k src[k * src_stride + i] for c < copies, i < n; the K
 // terms are added in replica order.  dst may be src (each index is read in full before it is
 // written).
 void launch_grad_mean(const float* src, int64_t src_stride, float* dst, int64_t dst_stride,
                       int64_t n, int K, int copies, hipStream_t s);
-// Center update over the due replicas (Algorithm 2, synchronous optimization step).
+// Center update over the due replicas (Algorithm 2, synchronous optimization step).  The sums of
+// the due replicas start again from zero afterwards.  Without `restart` the kernel writes the
+// zeros.  With it (K words of device memory, zero at first) it writes none: it sets the mark of
+// every due replica to 2, which means "this sum reads as zero, its memory is stale"; the next
+// step's launch_norm_finish makes that a 1, which tells that step's sampler kernels to start the
+// sum from x alone instead of reading it, and the step after makes it 0 again.  All of it is
+// data on the device, so a captured step replays correctly.  Saves writing and reading back
+// 4 bytes per parameter of every replica served.
 void launch_center(float* S, float* y, float* gprev, int64_t stride, int64_t n,
                    const DueList& due, float inv_m, float beta, float lr_center, int has_prev,
-                   hipStream_t s);
+                   hipStream_t s, int32_t* restart = nullptr);
 // dst[k, :] = src[:] for k < K (fp32).
 void launch_broadcast(const float* src, float* dst, int64_t stride, int64_t n, int K, hipStream_t s);
 // Rebuilds the bf16 operand copy of K replicas from their fp32 parameters.
@@ -166,6 +176,7 @@ struct SamplerFusion {
   ReplicaScalars lam;
   float lr, mu;
   int nesterov;
+  const int32_t* restart;     // marks of launch_center (may be null)
 };
 // 0 ok, <0 unsupported shape; *sumsq_slots (if non-null) = slots written per replica
 int launch_gemm(const GemmDesc& d, hipStream_t s, int* sumsq_slots = nullptr);

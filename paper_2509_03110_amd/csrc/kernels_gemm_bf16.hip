@@ -50,6 +50,7 @@ struct Bf16GemmParams {
   unsigned short* fshadow; long long strideShadow; int cbShadow;
   float lr, mu; int nesterov;
   ReplicaScalars lam;
+  const int* frestart;                    // per-replica marks: 1 = the sum S starts afresh (may be null)
   // EPI_ASCEND kernels: x (same addressing as the result), the per-replica scale rho/(||g||+gamma),
   // and the operand copy that receives bf16(x + scale g) (fshadow, strideShadow, cbShadow above)
   const float* ax; const float* ascale;
@@ -441,6 +442,9 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
     const bool col_ok = n < p.N;
     const unsigned rowbytes = (unsigned)p.ldC * 4u;
     const unsigned off0 = (unsigned)(m0 + wm0 + rsub) * rowbytes + (unsigned)n * 4u;
+    // a replica served by the last center update starts its sum afresh: S is not read (its
+    // loads go out of range and return zeros)
+    const bool fresh = p.frestart != nullptr && p.frestart[bat] == 1;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -460,7 +464,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_bf16_kernel(Bf16GemmParams
           const unsigned off = col_ok ? off0 + (unsigned)(i * 32 + (pb + u) * ROWS_PER_PASS) * rowbytes : kOut;
           xv[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, NT);
           vv[u] = __builtin_amdgcn_raw_buffer_load_b128(rv, off, 0, NT);
-          sv[u] = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, NT);
+          sv[u] = __builtin_amdgcn_raw_buffer_load_b128(rs, fresh ? kOut : off, 0, NT);
           yv[u] = __builtin_amdgcn_raw_buffer_load_b128(ry, off, 0, 0);
         }
 #pragma unroll
@@ -748,7 +752,7 @@ int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s, int* s
   p.bytesB = (unsigned)(blocksB * 2048);
   p.sumsq = d.out_bf16 ? nullptr : d.sumsq;
   p.strideSumsq = d.sumsq_stride;
-  p.fx = nullptr;
+  p.fx = nullptr; p.frestart = nullptr;
   p.mode = EPI_STORE;
   const bool plain_f32 = !d.out_bf16 && d.epilogue == EPI_PLAIN && (d.ldC % 4) == 0 && (d.strideC % 4) == 0;
   p.ksplit = 1; p.strideSplit = 0;
@@ -772,6 +776,7 @@ int launch_gemm_bf16(const GemmDesc& d, int tile_override, hipStream_t s, int* s
     p.fshadow = f.shadow; p.strideShadow = f.shadow_stride; p.cbShadow = f.cbShadow;
     p.lr = f.lr; p.mu = f.mu; p.nesterov = f.nesterov;
     p.lam = f.lam;
+    p.frestart = f.restart;
     p.sumsq = nullptr;
     p.mode = EPI_STEP;
   } else if (d.ascend != nullptr) {

@@ -171,8 +171,12 @@ __global__ __launch_bounds__(kThreads) void gram_dot_partials_kernel(
 __global__ __launch_bounds__(kThreads) void norm_finish_kernel(
     const double* __restrict__ partials, int nblk, int64_t pstride, float rho, float gamma,
     float* __restrict__ norms, float* __restrict__ scale, const float* __restrict__ loss_rows,
-    int B, float* __restrict__ loss_out) {
+    int B, float* __restrict__ loss_out, int32_t* __restrict__ restart) {
   const int k = blockIdx.x;
+  if (restart != nullptr && threadIdx.x == 0) {     // 2 (sum just served) -> 1 (restart it in this step) -> 0
+    const int32_t m = restart[k];
+    if (m > 0) restart[k] = m - 1;
+  }
   double s = 0.0;
   for (int i = threadIdx.x; i < nblk; i += kThreads) s += partials[(int64_t)k * pstride + i];
   s = block_sum(s);
@@ -266,7 +270,7 @@ __global__ __launch_bounds__(kThreads) void descent_kernel(
     float* __restrict__ x, const float* __restrict__ g, int64_t g_stride, float* __restrict__ v,
     float* __restrict__ S, const float* __restrict__ y, uint16_t* __restrict__ shadow,
     ShadowMap map, int64_t shadow_stride, int64_t stride, int64_t nv, int K, ReplicaScalars lam,
-    float lr, float mu, int nesterov, NOISE noise) {
+    float lr, float mu, int nesterov, NOISE noise, const int32_t* __restrict__ restart) {
   const int64_t b = blockIdx.x;
   const int k = (int)(b % K);
   const int64_t i = (b / K) * kThreads + threadIdx.x;
@@ -276,7 +280,13 @@ __global__ __launch_bounds__(kThreads) void descent_kernel(
   auto xv = ldv<VEC>(x + o);
   auto gv = ldv<VEC>(g + (int64_t)k * g_stride + i * VEC);
   auto vv = ldv<VEC>(v + o);
-  auto sv = ldv<VEC>(S + o);
+  typename Vec<VEC>::type sv;
+  if (restart != nullptr && restart[k] == 1) {       // the sum starts afresh: its memory is stale
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) set_elem(sv, e, 0.f);
+  } else {
+    sv = ldv<VEC>(S + o);
+  }
   const float lk = lam.v[k];
   float xi[4] = {0.f, 0.f, 0.f, 0.f};      // sigma sqrt(2 eta) xi of the Langevin sampler
   if constexpr (!std::is_same<NOISE, NoNoise>::value) {
@@ -328,7 +338,11 @@ __global__ __launch_bounds__(kThreads) void grad_mean_kernel(
 template <int VEC>
 __global__ __launch_bounds__(kThreads) void center_kernel(
     float* __restrict__ S, float* __restrict__ y, float* __restrict__ gprev, int64_t stride,
-    int64_t nv, DueList due, float inv_m, float beta, float lr_center, int has_prev) {
+    int64_t nv, DueList due, float inv_m, float beta, float lr_center, int has_prev,
+    int32_t* __restrict__ restart) {
+  // (no thread of this kernel reads a mark: a replica that is due has taken a step since it
+  // was last served, and that step's norm kernel had counted its mark down to at most 1)
+  if (restart != nullptr && blockIdx.x == 0 && (int)threadIdx.x < due.n) restart[due.idx[threadIdx.x]] = 2;
   const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (i >= nv) return;
   typename Vec<VEC>::type tot, zero;
@@ -339,7 +353,7 @@ __global__ __launch_bounds__(kThreads) void center_kernel(
     auto sv = ldv<VEC>(p);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) set_elem(tot, e, elem(tot, e) + elem(sv, e));
-    stv<VEC>(p, zero);
+    if (restart == nullptr) stv<VEC>(p, zero);
   }
   auto yv = ldc<VEC>(y + i * VEC);
   auto pv = ldc<VEC>(gprev + i * VEC);
@@ -447,9 +461,9 @@ int launch_gram_dot(const float* G1, const float* G2, int64_t stride, int64_t n,
 
 void launch_norm_finish(const double* partials, int nblk, int64_t partials_stride, int K, float rho,
                         float gamma, float* norms, float* scale, const float* loss_rows, int B,
-                        float* loss_out, hipStream_t s) {
+                        float* loss_out, hipStream_t s, int32_t* restart) {
   norm_finish_kernel<<<K, kThreads, 0, s>>>(partials, nblk, partials_stride, rho, gamma, norms,
-                                            scale, loss_rows, B, loss_out);
+                                            scale, loss_rows, B, loss_out, restart);
 }
 
 void launch_perturb(const float* x, const float* g, int64_t g_stride, const float* scale,
@@ -492,39 +506,41 @@ void launch_descent_with(float* x, const float* g, int64_t g_stride, float* v, f
                          const float* y, uint16_t* shadow, const ShadowMap* map,
                          int64_t shadow_stride, int64_t stride, int64_t n, int K,
                          const ReplicaScalars& lam, float lr, float mu, int nesterov,
-                         const NOISE& noise, hipStream_t s) {
+                         const NOISE& noise, hipStream_t s, const int32_t* restart) {
   const bool vec = n % 4 == 0 && g_stride % 4 == 0 && stride % 4 == 0 && aligned16(g);
   ShadowMap none{};
   if (shadow) {
     const unsigned grid = blocks_for(n / 4) * (unsigned)K;
     descent_kernel<4, true, true, NOISE><<<grid, kThreads, 0, s>>>(
         x, g, g_stride, v, S, y, shadow, *map, shadow_stride, stride, n / 4, K, lam, lr, mu,
-        nesterov, noise);
+        nesterov, noise, restart);
   } else if (vec) {
     const unsigned grid = blocks_for(n / 4) * (unsigned)K;
     if ((int64_t)K * n * 4 > kCacheResidentBytes)
       descent_kernel<4, false, true, NOISE><<<grid, kThreads, 0, s>>>(
-          x, g, g_stride, v, S, y, nullptr, none, 0, stride, n / 4, K, lam, lr, mu, nesterov, noise);
+          x, g, g_stride, v, S, y, nullptr, none, 0, stride, n / 4, K, lam, lr, mu, nesterov, noise,
+          restart);
     else
       descent_kernel<4, false, false, NOISE><<<grid, kThreads, 0, s>>>(
-          x, g, g_stride, v, S, y, nullptr, none, 0, stride, n / 4, K, lam, lr, mu, nesterov, noise);
+          x, g, g_stride, v, S, y, nullptr, none, 0, stride, n / 4, K, lam, lr, mu, nesterov, noise,
+          restart);
   } else {
     const unsigned grid = blocks_for(n) * (unsigned)K;
     descent_kernel<1, false, true, NOISE><<<grid, kThreads, 0, s>>>(
-        x, g, g_stride, v, S, y, nullptr, none, 0, stride, n, K, lam, lr, mu, nesterov, noise);
+        x, g, g_stride, v, S, y, nullptr, none, 0, stride, n, K, lam, lr, mu, nesterov, noise, restart);
   }
 }
 
 void launch_descent(float* x, const float* g, int64_t g_stride, float* v, float* S,
                     const float* y, uint16_t* shadow, const ShadowMap* map, int64_t shadow_stride,
                     int64_t stride, int64_t n, int K, const ReplicaScalars& lam, float lr, float mu,
-                    int nesterov, const NoiseMap* noise, hipStream_t s) {
+                    int nesterov, const NoiseMap* noise, hipStream_t s, const int32_t* restart) {
   if (noise)
     launch_descent_with<NoiseMap>(x, g, g_stride, v, S, y, shadow, map, shadow_stride, stride, n, K,
-                                  lam, lr, mu, nesterov, *noise, s);
+                                  lam, lr, mu, nesterov, *noise, s, restart);
   else
     launch_descent_with<NoNoise>(x, g, g_stride, v, S, y, shadow, map, shadow_stride, stride, n, K,
-                                 lam, lr, mu, nesterov, NoNoise{}, s);
+                                 lam, lr, mu, nesterov, NoNoise{}, s, restart);
 }
 
 void launch_grad_mean(const float* src, int64_t src_stride, float* dst, int64_t dst_stride,
@@ -539,13 +555,13 @@ void launch_grad_mean(const float* src, int64_t src_stride, float* dst, int64_t 
 
 void launch_center(float* S, float* y, float* gprev, int64_t stride, int64_t n,
                    const DueList& due, float inv_m, float beta, float lr_center, int has_prev,
-                   hipStream_t s) {
+                   hipStream_t s, int32_t* restart) {
   if (n % 4 == 0 && stride % 4 == 0) {
     center_kernel<4><<<blocks_for(n / 4), kThreads, 0, s>>>(S, y, gprev, stride, n / 4, due, inv_m,
-                                                            beta, lr_center, has_prev);
+                                                            beta, lr_center, has_prev, restart);
   } else {
     center_kernel<1><<<blocks_for(n), kThreads, 0, s>>>(S, y, gprev, stride, n, due, inv_m, beta,
-                                                        lr_center, has_prev);
+                                                        lr_center, has_prev, restart);
   }
 }
 

@@ -162,6 +162,7 @@ struct Layout {
   std::vector<ConvLayer> conv;
   size_t dcol = 0;             // gradient of an unfolded image (largest layer that needs one)
   size_t gram1 = 0, gram2 = 0; // bf16 dense model: Gram matrices [K][B][ldg] of a layer's dZ and of its input
+  size_t restart = 0;         // K marks: which iterate sums read as zero / start afresh (launch_center)
   int ldg = 0;
   int gap_hw = 0;              // > 0: global average pooling over that many positions feeds the dense layers
   size_t gap_out = 0, gap_grad = 0;   // [K][B][ld] pooled vector and its gradient
@@ -451,6 +452,7 @@ void build_layout(const lsam_config& c, Layout& lo) {
   lo.gprev = take(cur, (size_t)lo.d_pad * 4);
   if (lo.raw && c.algorithm == LSAM_ALG_DATA_PARALLEL) lo.gmean = take(cur, (size_t)lo.d_pad * 4);
   lo.partials = take(cur, (size_t)lo.K * lo.nblk * 8);
+  lo.restart = take(cur, (size_t)lo.K * 4);
   lo.norms = take(cur, (size_t)lo.K * 4);
   lo.scale = take(cur, (size_t)lo.K * 4);
   lo.loss = take(cur, (size_t)lo.K * 4);
@@ -1192,7 +1194,8 @@ int forward_backward(lsam_ctx* c, const void* X, const int32_t* labels, const vo
         LaunchTimer t(c, KC_DESCENT);
         launch_descent(fuse->x + ly.b_off, g + ly.b_off, lo.d_pad, fuse->v + ly.b_off,
                        fuse->S + ly.b_off, fuse->y + ly.b_off, nullptr, nullptr, 0, lo.d_pad,
-                       round_up(ly.out, 4), K, fuse->lam, fuse->lr, fuse->mu, fuse->nesterov, nullptr, s);
+                       round_up(ly.out, 4), K, fuse->lam, fuse->lr, fuse->mu, fuse->nesterov, nullptr, s,
+                       fuse->restart);
       }
     };
     auto input_grad = [&]() -> int {
@@ -1283,7 +1286,8 @@ int update_tail_first(lsam_ctx* c, const float* g1, int64_t g_stride, int64_t n,
                        c->rho, c->cfg.gamma,
                        c->at<float>(lo.norms), c->at<float>(lo.scale),
                        lo.raw ? nullptr : c->at<float>(lo.loss_rows), lo.B,
-                       lo.raw ? nullptr : (loss ? loss : c->at<float>(lo.loss)), s);
+                       lo.raw ? nullptr : (loss ? loss : c->at<float>(lo.loss)), s,
+                       c->at<int32_t>(lo.restart));
   }
   if (c->rho != 0.f && perturb) {
     LaunchTimer t(c, KC_PERTURB);
@@ -1322,7 +1326,7 @@ int update_tail_second(lsam_ctx* c, const float* g2, int64_t g_stride, int64_t n
     launch_descent(c->at<float>(lo.x), g2, g_stride, c->at<float>(lo.v), c->at<float>(lo.S),
                    c->at<float>(lo.y), lo.bf16 ? c->at<uint16_t>(lo.xt) : nullptr, &lo.map,
                    lo.shadow_stride, lo.d_pad, n, lo.K, lam, c->lr, c->cfg.momentum, c->cfg.nesterov,
-                   noise, c->stream);
+                   noise, c->stream, c->at<int32_t>(lo.restart));
   }
   ++c->t_step;
   c->sched.tick();
@@ -1591,6 +1595,7 @@ int lsam_step(lsam_ctx* c, const void* X, const int32_t* labels, float* loss) {
     SamplerFusion f;
     if (fused) {
       f.x = c->at<float>(lo.x); f.v = c->at<float>(lo.v); f.S = c->at<float>(lo.S);
+      f.restart = c->at<int32_t>(lo.restart);
       f.y = c->at<float>(lo.y);
       f.shadow = c->at<uint16_t>(lo.xt); f.shadow_stride = lo.shadow_stride; f.cbShadow = 0;
       for (int i = 0; i < lo.K; ++i) f.lam.v[i] = coupling(c, i);
@@ -1641,7 +1646,7 @@ int lsam_sync(lsam_ctx* c) {
     LaunchTimer t(c, KC_CENTER);
     launch_center(c->at<float>(lo.S), c->at<float>(lo.y), c->at<float>(lo.gprev), lo.d_pad,
                   lo.raw ? lo.d : lo.d_pad, due, (float)(1.0 / (double)m), c->cfg.beta,
-                  c->cfg.lr_center, c->sched.t_y() > 0 ? 1 : 0, c->stream);
+                  c->cfg.lr_center, c->sched.t_y() > 0 ? 1 : 0, c->stream, c->at<int32_t>(lo.restart));
   }
   int rc = check_launch("center update");
   if (rc != LSAM_OK) return rc;
@@ -1666,7 +1671,17 @@ int lsam_get_buffer(lsam_ctx* c, int32_t which, int32_t replica, float* dst, int
   if (replica < 0) return fail(LSAM_EINVAL, "replica -1 is valid for the parameters only");
   switch (which) {
     case LSAM_BUF_VELOCITY: return copy_out(c, c->at<float>(lo.v) + roff, dst);
-    case LSAM_BUF_ITER_SUM: return copy_out(c, c->at<float>(lo.S) + roff, dst);
+    case LSAM_BUF_ITER_SUM: {
+      // a sum the last center update served reads as zero; its memory is rewritten by the next step
+      int32_t mark = 0;
+      int rc = to_host(c, &mark, c->at<int32_t>(lo.restart) + replica, 4);
+      if (rc != LSAM_OK) return rc;
+      if (mark == 2) {
+        memset(dst, 0, (size_t)n * 4);
+        return LSAM_OK;
+      }
+      return copy_out(c, c->at<float>(lo.S) + roff, dst);
+    }
     case LSAM_BUF_GRAD:
       if (lo.raw) return fail(LSAM_ESTATE, "raw-vector mode keeps no gradient buffer");
       return copy_out(c, c->at<float>(lo.g) + roff, dst);
@@ -1716,6 +1731,11 @@ int lsam_set_buffer(lsam_ctx* c, int32_t which, int32_t replica, const float* sr
   if (!dst) return fail(LSAM_EINVAL, "replica -1 is valid for the parameters only");
   int rc = copy_in(c, src, dst);
   if (rc != LSAM_OK) return rc;
+  if (which == LSAM_BUF_ITER_SUM) {
+    // the sum is what the caller wrote from now on, not "zero since the last center update"
+    const int32_t none = 0;
+    if ((rc = to_device(c, c->at<int32_t>(lo.restart) + replica, &none, 4)) != LSAM_OK) return rc;
+  }
   if (which == LSAM_BUF_PARAMS && replica >= 0 && lo.bf16) {
     launch_shadow_refresh(dst, c->at<uint16_t>(lo.xt) + (int64_t)replica * lo.shadow_stride, lo.map,
                           lo.d_pad, lo.shadow_stride, lo.d_pad, 1, c->stream);

@@ -1448,3 +1448,62 @@ def test_randomly_drawn_residual_configurations_with_bf16_products(seed):
     worst = run_mlp(w, 4, 2e-2, 2e-2, anchor_after=1, tol_flip=3e-1, init_fn=bn_away_from_zero)
     print("seed %d, bf16 products: %d convolutions, preact=%d, K=%d: %.2e" % (seed, w.n_conv, w.preact, w.K, worst))
 
+
+# ---- iterate sums restart after a center update without being zeroed in memory ----------------------
+def _restart_case(kind):
+    if kind == "raw":
+        w = workloads.WORKLOADS["cfg4"].scaled(name="restart_raw", K=3, d_raw=4099, tau=(1, 2, 3))
+        g, o = make_pair(w)
+        rng = np.random.default_rng(5)
+        def step(t):
+            g1 = (rng.standard_normal((w.K, w.d_raw)) * 1e-2).astype(np.float32)
+            g2 = (rng.standard_normal((w.K, w.d_raw)) * 1e-2).astype(np.float32)
+            g.lsam_step_grads(torch.from_numpy(g1).to(DEV), torch.from_numpy(g2).to(DEV))
+            o.step_grads(g1.astype(np.float64), g2.astype(np.float64))
+        return w, g, o, step
+    dt = {"fp32": 0, "bf16": 1}[kind]
+    w = workloads.WORKLOADS["cfg3"].scaled(name="restart_" + kind, K=3, dims=(40, 72, 100, 9), batch=20, tau=(1, 2, 3),
+                                           n_classes=9, batch_pool=0, gemm_dtype=dt)
+    g, o = make_pair(w)
+    def step(t):
+        X, lab = workloads.batch(w, t)
+        Xd, ld = to_dev(X, lab, w)
+        g.lsam_step(Xd, ld, None)
+        o.step(X, lab)
+    return w, g, o, step
+
+
+@pytest.mark.parametrize("kind", ["raw", "fp32", "bf16"])
+def test_iterate_sums_restart_after_a_center_update(kind):
+    """A replica the center update has just served reads back an iterate sum of exact zeros, the
+    others keep theirs; one step later its sum is exactly its new parameters (0 + x); a replica
+    served at every tick (period 1) goes through that at every step; a sum written through the
+    boundary right after a center update counts from what was written."""
+    w, g, o, step = _restart_case(kind)
+    for t in range(7):
+        step(t)
+        before = [g.lsam_get_buffer(lsam.BUF_ITER_SUM, i) for i in range(w.K)]
+        count = g.lsam_get_schedule()[1]
+        due = [i for i in range(w.K) if count[i] >= w.tau[i]]
+        assert g.lsam_sync() == o.sync() == len(due)
+        for i in range(w.K):
+            S = g.lsam_get_buffer(lsam.BUF_ITER_SUM, i)
+            if i in due:
+                assert not np.any(S), (t, i)
+            else:
+                assert np.array_equal(S, before[i]) and np.any(S), (t, i)
+            assert not np.any(o.S[i]) or rel_max(S, o.S[i]) < (2e-2 if kind == "bf16" else 1e-4), (t, i)
+        if t == 3:
+            # replica 1 was served at this tick (period 2): give it a sum of its own choosing
+            assert 1 in due
+            z = np.linspace(-1.0, 1.0, g.lsam_get_params(1).size).astype(np.float32)
+            g.lsam_set_buffer(lsam.BUF_ITER_SUM, 1, z)
+            o.S[1] = z.astype(np.float64)
+            assert np.array_equal(g.lsam_get_buffer(lsam.BUF_ITER_SUM, 1), z)
+    step(7)
+    # replica 0 (period 1) was served at tick 6: its sum is its parameters, bit for bit
+    assert np.array_equal(g.lsam_get_buffer(lsam.BUF_ITER_SUM, 0), g.lsam_get_params(0))
+    for i in range(w.K):
+        assert rel_max(g.lsam_get_buffer(lsam.BUF_ITER_SUM, i), o.S[i]) < (2e-2 if kind == "bf16" else 1e-4), i
+    g.close()
+
